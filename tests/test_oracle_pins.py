@@ -1,0 +1,633 @@
+"""Pins of the CPU oracle against things other than itself.
+
+The paper prints no worked example, bitstream or per-kernel number for this
+path, so the pins are what the paper's text and the mathematics fix: the
+pointwise error bound (Sec. II-B), lossless entropy stage (Sec. IV-B), optimal
+prefix codes (Sec. II-B), width-trimmed fixed-length packing (Sec. V-B), the
+argmin selector with RAW fallback (Eq. 2, Algorithm 1), independently decodable
+validated frames (Sec. IV-D, Algorithm 2) and exact integer reduction
+(Sec. III, IV-A).  Each check uses brute force, a closed form, or an
+independent implementation written here in numpy / pure Python.
+"""
+import heapq
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2605_12396_amd import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ----------------------------------------------------------------------------
+# quantizer
+# ----------------------------------------------------------------------------
+
+def test_quantizer_worked_values():
+    """Hand-checkable case (tests/golden/quantizer_worked.txt): eb=0.5 -> step = 0.984375 exactly."""
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "quantizer_worked.txt")) if l.strip() and l[0] != "#"]
+    eb = 0.5
+    step, inv = oracle.step_constants(eb)
+    assert float(step) == 0.984375
+    x = np.array([float(r[0]) for r in rows], np.float32)
+    q, ok = oracle.quantize(x, eb)
+    assert ok.all()
+    assert q.tolist() == [int(r[1]) for r in rows]
+    xh = oracle.dequantize(q, eb)
+    assert xh.tolist() == [float(r[2]) for r in rows]
+
+
+@pytest.mark.parametrize("eb,scale", [(1e-4, 1.0), (1e-5, 1e-3), (2.7e-4, 0.3), (3.0, 5e4), (1e-30, 1e-26),
+                                      (0.5, 16000.0), (1e-4, 3.2)])
+def test_error_bound_float64(eb, scale):
+    """|x - xhat| <= eb for every quantizable element, checked in float64 (Sec. II-B strict error control)."""
+    rng = np.random.default_rng(123)
+    x = np.concatenate([rng.uniform(-scale, scale, 400000), rng.laplace(0, scale / 8, 400000)]).astype(np.float32)
+    eb32 = float(np.float32(eb))
+    q, ok = oracle.quantize(x, eb32)
+    step, _ = oracle.step_constants(eb32)
+    xh = (q.astype(np.float32) * step).astype(np.float32)
+    err = np.abs(x.astype(np.float64) - xh.astype(np.float64))
+    assert (err[ok] <= eb32).all()
+    # nearest-bin property: q is the integer nearest to x/step (up to fp32 rounding slack of u)
+    u = x.astype(np.float64) / float(step)
+    assert (np.abs(q[ok] - u[ok]) <= 0.5 + 32768 * 2.0 ** -22).all()
+    # everything with |x/step| comfortably below QMAX is quantizable, everything far above is not
+    assert ok[np.abs(u) <= 32766.0].all()
+    assert not ok[np.abs(u) >= 32768.5].any()
+
+
+def test_error_bound_at_largest_codes():
+    """The bound is tightest near |q| = QMAX; sweep a dense neighbourhood there."""
+    for eb in (1e-4, 0.37, 7.3e-3):
+        eb32 = float(np.float32(eb))
+        step, _ = oracle.step_constants(eb32)
+        base = np.float32(32760.0) * step
+        x = (base + np.arange(0, 200000, dtype=np.float64) * float(step) / 20000.0).astype(np.float32)
+        x = np.concatenate([x, -x])
+        q, ok = oracle.quantize(x, eb32)
+        xh = (q.astype(np.float32) * step).astype(np.float32)
+        err = np.abs(x.astype(np.float64) - xh.astype(np.float64))
+        assert (err[ok] <= eb32).all()
+        assert ok.sum() > 0.5 * ok.size
+        assert np.abs(q).max() == 32767
+
+
+def test_quantizer_invariants():
+    rng = np.random.default_rng(7)
+    eb = float(np.float32(1e-3))
+    x = np.sort(rng.uniform(-20.0, 20.0, 200000).astype(np.float32))
+    q, ok = oracle.quantize(x, eb)
+    assert ok.all()
+    assert (np.diff(q) >= 0).all()                              # monotone
+    qn, _ = oracle.quantize(-x, eb)
+    assert (qn == -q).all()                                     # odd symmetry
+    step, _ = oracle.step_constants(eb)
+    allq = np.arange(-32767, 32768, dtype=np.int32)
+    back, ok2 = oracle.quantize((allq.astype(np.float32) * step).astype(np.float32), eb)
+    assert ok2.all() and (back == allq).all()                    # quant(dequant(q)) == q
+    assert oracle.quantize(np.zeros(3, np.float32), eb)[0].tolist() == [0, 0, 0]
+
+
+def test_unquantizable_values_make_raw_frames_and_pass_through():
+    eb = 1e-3
+    x = W.gradient_like(3000, seed=5)
+    special = np.array([np.nan, np.inf, -np.inf, 1e30, -3e38], np.float32)
+    for v in special:
+        y = x.copy()
+        y[1234] = v
+        q, ok = oracle.quantize(y, eb)
+        assert not ok[1234] and ok.sum() == y.size - 1
+        opts = oracle.make_opts(chunk_elems=1000)
+        s, res, rc = oracle.compress(y, eb, opts)
+        assert rc == 0 and (res.n_raw, res.n_frames) == (1, 3)
+        out, _, rc = oracle.decompress(s, y.size, eb)
+        assert rc == 0
+        assert out[1000:2000].view(np.uint32).tolist() == y[1000:2000].view(np.uint32).tolist()   # bit-exact
+        assert (np.abs(out[:1000].astype(np.float64) - y[:1000]) <= np.float32(eb)).all()
+
+
+def test_invalid_arguments():
+    x = np.ones(10, np.float32)
+    for eb in (0.0, -1.0, float("nan"), float("inf"), 1e-35, 1e35):
+        _, res, rc = oracle.compress(x, eb)
+        assert rc == oracle.ERR_INVALID and res.status == oracle.ERR_INVALID
+    for bad in (dict(chunk_elems=(1 << 20) + 1), dict(seg_syms=31), dict(seg_syms=1025), dict(alphabet=3),
+                dict(alphabet=2048), dict(alphabet=1), dict(force_codec=3), dict(min_gain_permil=1001)):
+        _, res, rc = oracle.compress(x, 1e-3, oracle.make_opts(**bad))
+        assert rc == oracle.ERR_INVALID, bad
+
+
+# ----------------------------------------------------------------------------
+# zigzag + FIXEDLEN
+# ----------------------------------------------------------------------------
+
+def test_zigzag_textbook():
+    assert [oracle.zigzag(v) for v in (0, -1, 1, -2, 2, 2147483647, -2147483648)] == \
+        [0, 1, 2, 3, 4, 4294967294, 4294967295]
+    for z in (0, 1, 2, 3, 4, 77, 4294967295, 4294967294):
+        assert oracle.zigzag(oracle.unzigzag(z)) == z
+
+
+def _np_zigzag(q):
+    q = q.astype(np.int64)
+    return np.where(q >= 0, 2 * q, -2 * q - 1).astype(np.uint64)
+
+
+def _unpack_fixed(payload, n, w):
+    """Independent unpacker: little-endian bit order, w bits per value, bit 0 first."""
+    if w == 0:
+        return np.zeros(n, np.uint64)
+    bits = np.unpackbits(payload, bitorder="little")[: n * w].reshape(n, w).astype(np.uint64)
+    return (bits << np.arange(w, dtype=np.uint64)).sum(axis=1)
+
+
+@pytest.mark.parametrize("w", list(range(0, 33)))
+def test_fixedlen_every_width(w):
+    rng = np.random.default_rng(w)
+    n = 1000 + w
+    if w == 0:
+        q = np.zeros(n, np.int32)
+    else:
+        z = rng.integers(0, 1 << w, n, dtype=np.uint64)
+        z[n // 2] = (1 << w) - 1                      # make the width exact
+        q = np.where(z & 1, -((z + 1) >> 1).astype(np.int64), (z >> 1).astype(np.int64)).astype(np.int32)
+    fr = oracle.frame_encode(q, oracle.FIXEDLEN, oracle.make_opts(chunk_elems=n), step_bits=0x3f800000)
+    hdr = fr[:32].view(np.uint32)
+    assert hdr[1] == oracle.FIXEDLEN and hdr[2] == 4 * n and hdr[4] == w
+    assert hdr[3] == 4 * ((n * w + 31) // 32)                 # payload bits = n*w rounded up to words
+    assert fr.size == (32 + hdr[3] + 15) // 16 * 16
+    got = _unpack_fixed(fr[32:32 + hdr[3]], n, w)
+    assert (got == _np_zigzag(q)).all()
+    assert not fr[32 + (n * w + 7) // 8:].any()              # padding is zero
+
+
+# ----------------------------------------------------------------------------
+# Huffman code lengths
+# ----------------------------------------------------------------------------
+
+def _bruteforce_cost(freqs):
+    """Minimum of sum f*len over all length vectors with Kraft sum <= 1 (m <= 8 symbols)."""
+    m = len(freqs)
+    if m == 1:
+        return freqs[0]
+    best = None
+    order = sorted(freqs, reverse=True)          # optimal lengths are monotone in frequency: search sorted
+    for lens in itertools.combinations_with_replacement(range(1, m), m):   # non-decreasing lengths
+        if sum(2.0 ** -l for l in lens) <= 1.0 + 1e-12:
+            c = sum(f * l for f, l in zip(order, lens))
+            if best is None or c < best:
+                best = c
+    return best
+
+
+def _heap_cost(freqs):
+    """Independent Huffman cost: sum of all internal node weights, by a binary heap."""
+    h = [f for f in freqs if f > 0]
+    if len(h) == 1:
+        return h[0]
+    heapq.heapify(h)
+    cost = 0
+    while len(h) > 1:
+        a, b = heapq.heappop(h), heapq.heappop(h)
+        cost += a + b
+        heapq.heappush(h, a + b)
+    return cost
+
+
+def test_huffman_lengths_bruteforce_optimal():
+    rng = np.random.default_rng(11)
+    for trial in range(300):
+        m = int(rng.integers(1, 9))
+        hi = int(rng.choice([2, 4, 20, 1000]))            # small ranges force many ties
+        f = rng.integers(1, hi + 1, m)
+        K = 16
+        freq = np.zeros(K, np.uint32)
+        pos = rng.choice(K, m, replace=False)
+        freq[pos] = f
+        ln = oracle.huffman_lengths(freq)
+        assert (ln[freq == 0] == 0).all() and (ln[freq > 0] >= 1).all()
+        cost = int((freq.astype(np.int64) * ln).sum())
+        assert cost == _bruteforce_cost([int(v) for v in f]), (f, ln)
+        if m >= 2:
+            assert sum(2.0 ** -int(l) for l in ln if l) == 1.0       # Kraft equality
+
+
+def test_huffman_cost_matches_heap_and_shannon():
+    rng = np.random.default_rng(12)
+    for trial in range(40):
+        K = int(rng.choice([2, 16, 256, 1024]))
+        kind = trial % 4
+        if kind == 0:
+            f = rng.integers(0, 50, K)
+        elif kind == 1:
+            f = np.floor(1e5 * np.exp(-np.arange(K) / rng.uniform(1, 50))).astype(np.int64)
+        elif kind == 2:
+            f = rng.integers(0, 3, K) * rng.integers(1, 100000, K)
+        else:
+            f = np.ones(K, np.int64) * int(rng.integers(1, 5))
+        if f.sum() == 0:
+            f[0] = 1
+        freq = f.astype(np.uint32)
+        ln = oracle.huffman_lengths(freq).astype(np.int64)
+        n = int(freq.sum())
+        cost = int((freq.astype(np.int64) * ln).sum())
+        assert cost == _heap_cost([int(v) for v in freq])
+        p = freq[freq > 0] / n
+        H = float(-(p * np.log2(p)).sum())
+        if (freq > 0).sum() >= 2:
+            assert H - 1e-9 <= cost / n < H + 1.0
+            assert abs(sum(2.0 ** -int(l) for l in ln if l) - 1.0) < 1e-12
+
+
+def test_huffman_closed_forms():
+    for k in range(1, 11):                                          # uniform over 2^k symbols -> all len = k
+        ln = oracle.huffman_lengths(np.full(1 << k, 7, np.uint32))
+        assert (ln == k).all()
+    f = np.zeros(16, np.uint32)                                      # dyadic: p = 1/2,1/4,...,2^-9,2^-9
+    f[[3, 5, 6, 7, 9, 10, 11, 12, 14, 15]] = [512, 256, 128, 64, 32, 16, 8, 4, 2, 2]
+    ln = oracle.huffman_lengths(f)
+    assert ln[[3, 5, 6, 7, 9, 10, 11, 12, 14, 15]].tolist() == [1, 2, 3, 4, 5, 6, 7, 8, 9, 10][:9] + [9]
+    fib = [1, 1]                                                     # Fibonacci weights: a maximally deep tree
+    while len(fib) < 28:
+        fib.append(fib[-1] + fib[-2])
+    assert sum(fib) <= (1 << 20)                                     # fits the largest frame (2^20 symbols)
+    f = np.zeros(64, np.uint32)
+    f[:28] = fib
+    ln = oracle.huffman_lengths(f)                                   # chain: depth m-1 = 27 (<= 28, the decoder's cap)
+    assert sorted(ln[:28].tolist(), reverse=True) == [27] + list(range(27, 0, -1))
+    one = np.zeros(8, np.uint32)
+    one[5] = 9
+    assert oracle.huffman_lengths(one).tolist() == [0, 0, 0, 0, 0, 1, 0, 0]
+    assert oracle.huffman_lengths(np.zeros(8, np.uint32)).tolist() == [0] * 8
+
+
+def test_huffman_tie_rule_is_deterministic_leaf_first():
+    """Format rule: leaves sorted by (f, symbol); on equal weight a leaf is merged before an internal node.
+    Frequencies 1,1,2,2: leaf-first gives lengths {2,2,2,2}; node-first would give {3,3,2,1}."""
+    assert oracle.huffman_lengths(np.array([1, 1, 2, 2], np.uint32)).tolist() == [2, 2, 2, 2]
+    # three equal weights: the two lowest symbols merge first, so the highest symbol gets the short code
+    assert oracle.huffman_lengths(np.array([5, 5, 5], np.uint32)).tolist() == [2, 2, 1]
+
+
+def test_canonical_codes_prefix_free_and_ordered():
+    rng = np.random.default_rng(13)
+    for trial in range(30):
+        K = int(rng.choice([4, 32, 256]))
+        freq = (rng.integers(0, 4, K) * rng.integers(1, 1000, K)).astype(np.uint32)
+        if (freq > 0).sum() < 2:
+            freq[:2] = [3, 4]
+        ln = oracle.huffman_lengths(freq)
+        code = oracle.canonical_codes(ln)
+        used = [(int(ln[s]), s, int(code[s])) for s in range(K) if ln[s]]
+        strs = {s: format(c, "0%db" % l) for l, s, c in used}
+        for (a, sa), (b, sb) in itertools.permutations(strs.items(), 2):
+            assert not sb.startswith(sa), "code of %d is a prefix of code of %d" % (a, b)
+        used.sort()                                                 # by (len, sym)
+        vals = [c << (32 - l) for l, s, c in used]                  # left-aligned codes strictly increase
+        assert all(x < y for x, y in zip(vals, vals[1:]))
+        assert used[0][2] == 0                                      # first code of the shortest length is 0
+        assert used[-1][2] == (1 << used[-1][0]) - 1                # complete code: last code is all ones
+
+
+# ----------------------------------------------------------------------------
+# HUFFMAN frame layout, decoded by an independent pure-Python reader
+# ----------------------------------------------------------------------------
+
+def _py_huffman_decode(frame, n, K, seg):
+    """Independent reader of a HUFFMAN frame: dictionary of bit strings, one segment at a time."""
+    hdr = frame[:32].view(np.uint32)
+    assert hdr[0] == 0x31465A4E and hdr[1] == oracle.HUFFMAN
+    nsym, p1 = int(hdr[4]), int(hdr[5])
+    assert p1 == (seg | (K << 16))
+    pay = frame[32:32 + int(hdr[3])]
+    lens = pay[:nsym]
+    nseg = (n + seg - 1) // seg
+    o1 = (nsym + 3) // 4 * 4
+    o2 = o1 + (2 * nseg + 3) // 4 * 4
+    segt = pay[o1:o1 + 2 * nseg].view(np.uint16).astype(np.int64)
+    bits = np.unpackbits(pay[o2:], bitorder="little")
+    code = oracle.canonical_codes(lens)          # checked separately by the canonical-code pins
+    table = {format(int(code[s]), "0%db" % int(lens[s])): s for s in range(nsym) if lens[s]}
+    z = np.zeros(n, np.uint64)
+    pos = 0
+    for g in range(nseg):
+        p = pos
+        for i in range(g * seg, min(n, (g + 1) * seg)):
+            cur = ""
+            while cur not in table:
+                cur += str(int(bits[p]))
+                p += 1
+                assert len(cur) <= 28
+            s = table[cur]
+            if s == 0:
+                v = 0
+                for b in range(32):
+                    v |= int(bits[p + b]) << b
+                p += 32
+                z[i] = v
+            else:
+                z[i] = s - 1
+        assert p - pos == segt[g], "segment %d bit length" % g
+        pos += int(segt[g])
+    assert not bits[pos:].any()
+    return z, pos
+
+
+@pytest.mark.parametrize("K,seg,n", [(1024, 256, 5000), (16, 32, 777), (256, 100, 2500), (2, 64, 300)])
+def test_huffman_frame_layout(K, seg, n):
+    rng = np.random.default_rng(K + n)
+    q = np.rint(rng.laplace(0, 6.0, n)).astype(np.int32)
+    q[rng.integers(0, n, 5)] = rng.integers(-30000, 30000, 5)          # a few ESC symbols
+    opts = oracle.make_opts(chunk_elems=n, seg_syms=seg, alphabet=K)
+    plan = oracle.frame_plan(q, opts)
+    fr = oracle.frame_encode(q, oracle.HUFFMAN, opts, step_bits=123)
+    z, nbits = _py_huffman_decode(fr, n, K, seg)
+    assert (z == _np_zigzag(q)).all()
+    assert nbits == plan["huff_bits"]
+    assert fr.size == plan["totals"][oracle.HUFFMAN]
+
+
+# ----------------------------------------------------------------------------
+# selector
+# ----------------------------------------------------------------------------
+
+def _frames_for_selector():
+    rng = np.random.default_rng(21)
+    n = 4096
+    yield "laplace_narrow", np.rint(rng.laplace(0, 2.0, n)).astype(np.int32)
+    yield "uniform_8bit", rng.integers(-128, 128, n).astype(np.int32)
+    yield "uniform_16bit", rng.integers(-32767, 32768, n).astype(np.int32)
+    yield "all_zero", np.zeros(n, np.int32)
+    yield "constant", np.full(n, 37, np.int32)
+    yield "one_outlier", np.where(np.arange(n) == 99, 30000, 0).astype(np.int32)
+    yield "huge_codes", rng.integers(-(1 << 30), 1 << 30, n).astype(np.int32)
+    yield "tiny", np.array([3], np.int32)
+    yield "two_values", rng.integers(0, 2, n).astype(np.int32)
+
+
+def test_selector_equals_exhaustive_minimum():
+    """Eq. 2: encode every frame all three ways; the choice is the smallest realized frame, ties to the
+    lower codec id; predicted sizes equal realized sizes."""
+    for name, q in _frames_for_selector():
+        for K in (1024, 16):
+            opts = oracle.make_opts(chunk_elems=max(q.size, 1), alphabet=K)
+            plan = oracle.frame_plan(q, opts)
+            realized = [oracle.frame_encode(q, c, opts).size for c in (0, 1, 2)]
+            assert realized == plan["totals"].tolist(), name
+            best = min(range(3), key=lambda c: (realized[c], c))
+            assert plan["codec"] == best, (name, realized)
+
+
+def test_selector_gates():
+    rng = np.random.default_rng(22)
+    q = np.rint(rng.laplace(0, 2.0, 4096)).astype(np.int32)
+    base = oracle.frame_plan(q, oracle.make_opts(chunk_elems=4096))
+    assert base["codec"] == oracle.HUFFMAN
+    raw, fx, hf = [int(v) for v in base["payloads"]]
+    # Huffman size threshold: rawBytes < T_huff disables Huffman
+    assert oracle.frame_plan(q, oracle.make_opts(chunk_elems=4096, huff_min_bytes=4 * 4096))["codec"] == oracle.HUFFMAN
+    assert oracle.frame_plan(q, oracle.make_opts(chunk_elems=4096, huff_min_bytes=4 * 4096 + 1))["codec"] == oracle.FIXEDLEN
+    # minimum gain in permil of the raw size
+    g_h = (raw - hf) * 1000 // raw
+    g_f = (raw - fx) * 1000 // raw
+    assert g_h > g_f > 0
+    assert oracle.frame_plan(q, oracle.make_opts(chunk_elems=4096, min_gain_permil=g_h))["codec"] == oracle.HUFFMAN
+    assert oracle.frame_plan(q, oracle.make_opts(chunk_elems=4096, min_gain_permil=g_h + 1))["codec"] == oracle.RAW \
+        if g_f < g_h + 1 else True
+    assert oracle.frame_plan(q, oracle.make_opts(chunk_elems=4096, min_gain_permil=1000))["codec"] == oracle.RAW
+    # pinned codec, and an unquantizable frame is always RAW
+    for c in (0, 1, 2):
+        assert oracle.frame_plan(q, oracle.make_opts(chunk_elems=4096, force_codec=c))["codec"] == c
+        assert oracle.frame_plan(q, oracle.make_opts(chunk_elems=4096, force_codec=c), quantizable=False)["codec"] == 0
+
+
+def test_capacity_guard():
+    """Algorithm 1 guards: nothing is published when the output does not fit."""
+    x = W.gradient_like(5000, seed=3)
+    s, res, rc = oracle.compress(x, 1e-4, oracle.make_opts(chunk_elems=1024))
+    assert rc == 0
+    for cap in (res.bytes - 1, 100, 0):
+        s2, res2, rc2 = oracle.compress(x, 1e-4, oracle.make_opts(chunk_elems=1024), cap=cap)
+        assert rc2 == oracle.ERR_CAPACITY and res2.bytes == 0 and res2.status == oracle.ERR_CAPACITY
+    s3, res3, rc3 = oracle.compress(x, 1e-4, oracle.make_opts(chunk_elems=1024), cap=int(res.bytes))
+    assert rc3 == 0 and (s3 == s).all()
+    assert oracle.compress(np.zeros(0, np.float32), 1e-4)[2] == oracle.ERR_INVALID
+
+
+# ----------------------------------------------------------------------------
+# streams
+# ----------------------------------------------------------------------------
+
+def _configs_small():
+    yield "c1_like", W.smooth_field((32, 16, 16), seed=1), 1e-4, oracle.make_opts(chunk_elems=2048)
+    x = W.gradient_like(50000, seed=2)
+    yield "c2_like", x, W.abs_bound_from_rel(x, 1e-4), oracle.make_opts(chunk_elems=16384)
+    yield "uniform", W.sweep_payload("uniform", 10000, 50), 1e-4, oracle.make_opts(chunk_elems=4096)
+    yield "ragged", W.sweep_payload("laplace", 4097, 51), 1e-4, oracle.make_opts(chunk_elems=4096)
+    yield "n1", np.array([0.25], np.float32), 1e-4, None
+
+
+def test_stream_roundtrip_and_layout():
+    for name, x, eb, opts in _configs_small():
+        s, res, rc = oracle.compress(x, eb, opts)
+        assert rc == 0, name
+        assert s.size == res.bytes <= oracle.compress_bound(x.size, opts)
+        assert res.n_raw + res.n_fixed + res.n_huff == res.n_frames
+        out, res2, rc2 = oracle.decompress(s, x.size, eb)
+        assert rc2 == 0
+        assert (np.abs(out.astype(np.float64) - x.astype(np.float64)) <= np.float32(eb)).all(), name
+        # lossless entropy stage: decoded integer codes == the quantizer's codes, whatever codec was chosen
+        q, ok = oracle.quantize(x, eb)
+        assert ok.all()
+        qd, rbits, kinds, _, rc3 = oracle.decode_codes(s, x.size, eb)
+        assert rc3 == 0
+        chunk = opts.chunk_elems if opts is not None else 262144
+        for k, kind in enumerate(kinds):
+            sl = slice(k * chunk, min(x.size, (k + 1) * chunk))
+            if kind == 0:
+                assert (qd[sl] == q[sl]).all()
+            else:                           # a RAW frame (chosen on a size tie) carries the fp32 bits
+                assert kind == 1 and (rbits[sl] == x[sl].view(np.uint32)).all()
+        # same reconstruction for every pinned codec (Sec. V-D: codecs differ in ratio and cost only)
+        for c in (1, 2):
+            o2 = oracle.make_opts(**{**{k: getattr(opts, k) for k, _ in oracle.Opts._fields_}, "force_codec": c}) \
+                if opts is not None else oracle.make_opts(force_codec=c)
+            s_c, _, _ = oracle.compress(x, eb, o2)
+            out_c, _, rc_c = oracle.decompress(s_c, x.size, eb)
+            coded = np.repeat(kinds == 0, chunk)[:x.size]       # frames the selector did not leave RAW
+            assert rc_c == 0 and (out_c.view(np.uint32)[coded] == out.view(np.uint32)[coded]).all()
+            assert (np.abs(out_c.astype(np.float64) - x.astype(np.float64)) <= np.float32(eb)).all()
+        # stream layout: header fields, offsets 16-byte aligned, frames tile the stream exactly
+        h = s[:64]
+        assert h[:4].tobytes() == b"NZS1" and int(h[8:16].view(np.uint64)[0]) == x.size
+        nfr = int(h[20:24].view(np.uint32)[0])
+        assert int(h[40:48].view(np.uint64)[0]) == s.size
+        offs = s[64:64 + 8 * nfr].view(np.uint64).astype(np.int64)
+        assert offs[0] == 64 + (8 * nfr + 15) // 16 * 16 and (offs % 16 == 0).all()
+        ends = list(offs[1:]) + [s.size]
+        for k in range(nfr):
+            fh = s[offs[k]:offs[k] + 32].view(np.uint32)
+            assert fh[0] == 0x31465A4E
+            assert ends[k] - offs[k] == (32 + int(fh[3]) + 15) // 16 * 16
+            chk = 0x5A5A5A5A
+            for v in fh[:7]:
+                chk ^= int(v)
+            assert int(fh[7]) == chk
+
+
+def test_header_mutations_are_rejected_or_harmless():
+    """Receiver side of Algorithm 2: every one-byte change of a frame header either fails validation or
+    decodes to the identical output; the other frames are unaffected."""
+    x = W.gradient_like(6000, seed=9)
+    eb = 1e-4
+    for force in (-1, 1, 0):
+        opts = oracle.make_opts(chunk_elems=2048, force_codec=force)
+        s, res, rc = oracle.compress(x, eb, opts)
+        ref, _, _ = oracle.decompress(s, x.size, eb)
+        off = int(s[64 + 8:64 + 16].view(np.uint64)[0])          # frame 1
+        for i in range(32):
+            for flip in (0x01, 0x80, 0xFF):
+                t = s.copy()
+                t[off + i] ^= flip
+                out, r2, rc2 = oracle.decompress(t, x.size, eb)
+                assert rc2 in (oracle.OK, oracle.ERR_CORRUPT, oracle.ERR_MISMATCH)
+                if rc2 == oracle.OK:
+                    assert (out.view(np.uint32) == ref.view(np.uint32)).all()
+                else:
+                    assert not out[2048:4096].any()                       # rejected frame is zero-filled
+                    assert (out[:2048].view(np.uint32) == ref[:2048].view(np.uint32)).all()
+                    assert (out[4096:].view(np.uint32) == ref[4096:].view(np.uint32)).all()
+
+
+def test_stream_level_rejections():
+    x = W.gradient_like(3000, seed=10)
+    eb = 1e-4
+    s, res, rc = oracle.compress(x, eb, oracle.make_opts(chunk_elems=1024))
+    assert oracle.decompress(s, x.size + 1, eb)[2] == oracle.ERR_MISMATCH
+    assert oracle.decompress(s, x.size, 2e-4)[2] == oracle.ERR_MISMATCH
+    assert oracle.decompress(s[:63], x.size, eb)[2] == oracle.ERR_CORRUPT
+    assert oracle.decompress(s[:-16], x.size, eb)[2] == oracle.ERR_CORRUPT       # shorter than total_bytes
+    t = s.copy(); t[0] ^= 1
+    assert oracle.decompress(t, x.size, eb)[2] == oracle.ERR_CORRUPT
+    t = s.copy(); t[64] ^= 16                                                   # frame 0 offset moved
+    assert oracle.decompress(t, x.size, eb)[2] == oracle.ERR_CORRUPT
+    # garbage in a Huffman payload: never crashes, either decodes to something or is rejected
+    rng = np.random.default_rng(5)
+    off = int(s[64:72].view(np.uint64)[0])
+    for _ in range(200):
+        t = s.copy()
+        i = int(rng.integers(off + 32, s.size))
+        t[i] ^= int(rng.integers(1, 256))
+        out, r2, rc2 = oracle.decompress(t, x.size, eb)
+        assert rc2 in (oracle.OK, oracle.ERR_CORRUPT)
+
+
+# ----------------------------------------------------------------------------
+# reduce
+# ----------------------------------------------------------------------------
+
+def test_reduce_is_exact_integer_sum_and_order_free():
+    n, eb = 20000, 1e-5
+    opts = oracle.make_opts(chunk_elems=4096)
+    msgs = W.peer_messages(n, peers=4, seed0=40)
+    streams = [oracle.compress(m, eb, opts)[0] for m in msgs]
+    qs = [oracle.quantize(m, eb)[0] for m in msgs]
+    ab, res, rc = oracle.reduce_frames(streams[0], streams[1], n, eb, opts)
+    assert rc == 0
+    ba, _, _ = oracle.reduce_frames(streams[1], streams[0], n, eb, opts)
+    assert (ab == ba).all()                                                     # commutative bytes
+    qd, _, kinds, _, _ = oracle.decode_codes(ab, n, eb)
+    assert (kinds == 0).all() and (qd == qs[0] + qs[1]).all()                    # exact integer sum
+    # any association order of the peers gives identical final bytes
+    def red(a, b):
+        return oracle.reduce_frames(a, b, n, eb, opts)[0]
+    left = red(red(red(streams[0], streams[1]), streams[2]), streams[3])
+    tree = red(red(streams[0], streams[1]), red(streams[2], streams[3]))
+    other = red(streams[3], red(streams[1], red(streams[2], streams[0])))
+    assert (left == tree).all() and (left == other).all()
+    # the reduced stream's frames are exactly the frames of the summed codes under the selector
+    Q = qs[0] + qs[1] + qs[2] + qs[3]
+    step_bits = int(np.float32(oracle.step_constants(eb)[0]).view(np.uint32))
+    offs = left[64:64 + 8 * 5].view(np.uint64).astype(np.int64)
+    for k in range(5):
+        qf = Q[k * 4096:(k + 1) * 4096]
+        o1 = oracle.make_opts(chunk_elems=4096)
+        plan = oracle.frame_plan(qf, o1)
+        fr = oracle.frame_encode(qf, plan["codec"], o1, step_bits=step_bits)
+        assert (left[offs[k]:offs[k] + fr.size] == fr).all()
+    # error of the reduced reconstruction against the true sum: <= P * eb (float64)
+    out, _, _ = oracle.decompress(left, n, eb)
+    true = sum(m.astype(np.float64) for m in msgs)
+    assert (np.abs(out.astype(np.float64) - true) <= 4 * float(np.float32(eb))).all()
+
+
+def test_reduce_raw_and_overflow_paths():
+    n, eb = 3000, 1e-3
+    opts = oracle.make_opts(chunk_elems=1000)
+    a = W.gradient_like(n, seed=70)
+    b = W.gradient_like(n, seed=71)
+    a[1500] = np.nan
+    b[2500] = np.inf
+    sa = oracle.compress(a, eb, opts)[0]
+    sb = oracle.compress(b, eb, opts)[0]
+    r, res, rc = oracle.reduce_frames(sa, sb, n, eb, opts)
+    assert rc == 0 and res.n_raw == 2
+    out, _, _ = oracle.decompress(r, n, eb)
+    da, _, _ = oracle.decompress(sa, n, eb)
+    db, _, _ = oracle.decompress(sb, n, eb)
+    with np.errstate(invalid="ignore"):
+        expect = (da + db).astype(np.float32)
+    expect_bits = expect.view(np.uint32).copy()
+    expect_bits[np.isnan(expect)] = 0x7FC00000                                   # canonical NaN
+    assert (out[1000:].view(np.uint32) == expect_bits[1000:]).all()              # RAW frames: fp32 sum
+    qa = oracle.quantize(a[:1000], eb)[0]; qb = oracle.quantize(b[:1000], eb)[0]
+    qd, _, kinds, _, _ = oracle.decode_codes(r, n, eb)
+    assert kinds.tolist() == [0, 1, 1] and (qd[:1000] == qa + qb).all()
+    # overflow: doubling a stream 16 times pushes |Q| past 2^30 -> RAW frame with the fp32 sum
+    x = np.zeros(1000, np.float32)
+    step, _ = oracle.step_constants(eb)
+    x[7] = np.float32(32767.0) * step
+    s = oracle.compress(x, eb, opts)[0]
+    for i in range(15):
+        s2, res, rc = oracle.reduce_frames(s, s, 1000, eb, opts)
+        assert rc == 0 and res.n_raw == 0
+        s = s2
+    qd = oracle.decode_codes(s, 1000, eb)[0]
+    assert qd[7] == 32767 << 15
+    s2, res, rc = oracle.reduce_frames(s, s, 1000, eb, opts)
+    assert rc == 0 and res.n_raw == 1
+    out = oracle.decompress(s2, 1000, eb)[0]
+    v = np.float32(np.float32(32767 << 15) * step)
+    assert out[7] == np.float32(v + v) and not out[:7].any()
+    # mismatching operands
+    sc = oracle.compress(a, 2e-3, opts)[0]
+    assert oracle.reduce_frames(sa, sc, n, eb, opts)[2] == oracle.ERR_MISMATCH
+    sd = oracle.compress(a, eb, oracle.make_opts(chunk_elems=500))[0]
+    assert oracle.reduce_frames(sa, sd, n, eb, opts)[2] == oracle.ERR_MISMATCH
+
+
+# ----------------------------------------------------------------------------
+# compression-ratio sanity against the discrete-Laplace entropy (closed form)
+# ----------------------------------------------------------------------------
+
+def test_laplace_bits_per_symbol_within_entropy_bounds():
+    b, eb = 1e-3, 1e-4
+    n = 1 << 18
+    x = W.gradient_like(n, seed=33, outlier_frac=0.0)
+    step = float(oracle.step_constants(eb)[0])
+    r = step / b
+    ks = np.arange(1, 4000)
+    p0 = 1.0 - math.exp(-r / 2.0)
+    pk = math.sinh(r / 2.0) * np.exp(-ks * r)
+    probs = np.concatenate([[p0], pk, pk])
+    probs = probs[probs > 0]
+    H = float(-(probs * np.log2(probs)).sum())
+    s, res, rc = oracle.compress(x, eb, oracle.make_opts(chunk_elems=n, force_codec=2))
+    plan = oracle.frame_plan(oracle.quantize(x, eb)[0], oracle.make_opts(chunk_elems=n))
+    bps = plan["huff_bits"] / n
+    assert H - 0.05 <= bps < H + 1.0
