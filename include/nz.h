@@ -1,0 +1,130 @@
+/*
+ * nz.h -- C ABI of the MI355X (gfx950) per-rank compression path.
+ *
+ * The path is the per-rank pipeline that sits in front of and behind a
+ * collective's transport: interface quantizer (Sec. IV-A/IV-B of the paper),
+ * device-side runtime entropy arbitration among RAW / FIXEDLEN / HUFFMAN
+ * (Sec. IV-C, Eq. 1-2, Algorithm 1), self-describing frames (Sec. IV-D "Batch
+ * Framing"), receiver-side validate + decode (Algorithm 2, receiver side) and
+ * the compute part of the fused receive-decode-reduce-encode-send step
+ * (Sec. IV-D "In-Primitive Overlap").
+ *
+ * Conventions for every entry point
+ *   - Pointers named d_* are DEVICE pointers (hipMalloc'd or PyTorch-owned),
+ *     16-byte aligned; `opts` is a HOST pointer (may be NULL = defaults).
+ *   - The caller owns every buffer.  The library allocates nothing, keeps no
+ *     state between calls, enqueues its kernels on `stream` (a hipStream_t
+ *     passed as void*) and never synchronises it.  Two calls may run
+ *     concurrently only if they use different workspaces and outputs.
+ *   - The return value reports what the host can check before launching
+ *     (NZ_ERR_INVALID arguments, a workspace or output too small to hold even
+ *     the stream header, a failed launch = NZ_ERR_HIP).  Everything detected
+ *     on the device is written to d_res->status once the stream has run; when
+ *     several conditions hold the numerically largest code is reported.
+ *   - No kernel reads or writes outside [d_out, d_out+out_cap), the given
+ *     input lengths, or the workspace, whatever the input bytes are.
+ *   - `eb` is an ABSOLUTE error bound: finite, 2^-100 <= eb <= 2^100.  A
+ *     range-relative bound (the paper's REL, Sec. V-B) is converted by the
+ *     caller: eb = REL * (max - min).
+ */
+#ifndef NZ_H
+#define NZ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    NZ_OK           = 0,
+    NZ_ERR_INVALID  = 1,   /* bad argument (n = 0, eb out of range, misaligned pointer, bad opts)        */
+    NZ_ERR_CAPACITY = 2,   /* output does not fit out_cap: nothing is published (Algorithm 1 returns 0) */
+    NZ_ERR_RANGE    = 3,   /* nz_reduce_frames: an integer sum exceeded 2^30 in magnitude               */
+    NZ_ERR_CORRUPT  = 4,   /* a stream or frame failed validation (Algorithm 2, ValidateHeader)         */
+    NZ_ERR_MISMATCH = 5,   /* n, frame size, alphabet or quantization step differ from the stream's     */
+    NZ_ERR_HIP      = 6    /* a HIP launch failed (host return value only)                              */
+} nz_status;
+
+typedef enum { NZ_CODEC_RAW = 0, NZ_CODEC_FIXEDLEN = 1, NZ_CODEC_HUFFMAN = 2 } nz_codec;
+
+/* Options; zero in a size field selects the default. */
+typedef struct {
+    uint32_t chunk_elems;      /* fp32 elements per frame, 1..2^20 (the paper's frame is one 4 MiB channel
+                                  buffer, Sec. IV-D "8-slot batching"); default 262144 (1 MiB)              */
+    uint32_t seg_syms;         /* symbols per independently decodable Huffman segment; this build
+                                  supports 256 only (0 or 256)                                              */
+    uint32_t alphabet;         /* Huffman alphabet K (escape + K-1 symbols), power of two 2..1024;
+                                  default 256 (the paper's selector profiles a 256-bin histogram, Sec. IV-C) */
+    int32_t  force_codec;      /* -1 = arbitrate; 0/1/2 pin RAW/FIXEDLEN/HUFFMAN as the paper does for its
+                                  ratio study (Sec. V-B)                                                    */
+    uint32_t min_gain_permil;  /* minimum-gain threshold of Algorithm 1 (minGainPermil), 0..1000            */
+    uint32_t huff_min_bytes;   /* Huffman size threshold T_huff of Algorithm 1 on the frame's raw bytes     */
+} nz_opts;
+
+/* Result record, lives in DEVICE memory, valid once the stream has executed the call. */
+typedef struct {
+    uint64_t bytes;            /* compress/reduce: stream bytes written (0 on any error);
+                                  decompress: total_bytes field of the stream header                        */
+    uint32_t status;           /* nz_status                                                                 */
+    uint32_t n_frames;
+    uint32_t n_raw, n_fixed, n_huff;   /* frames per chosen (compress/reduce) or found (decompress) codec   */
+    uint32_t reserved;
+} nz_result;
+
+/* Host, pure.  Worst-case stream bytes for n elements: every frame RAW (a pinned HUFFMAN can exceed that
+ * and is bounded at 60 bits per symbol instead).  0 when n = 0 or opts are invalid. */
+size_t nz_compress_bound(size_t n, const nz_opts* opts);
+
+/* Host, pure.  Workspace bytes nz_compress / nz_decompress need for n elements (0 on invalid opts). */
+size_t nz_workspace_bytes(size_t n, const nz_opts* opts);
+
+/* Host, pure.  Workspace bytes nz_reduce_frames needs (it also stages the n summed codes). */
+size_t nz_reduce_workspace_bytes(size_t n, const nz_opts* opts);
+
+/*
+ * Quantize d_in[0..n) with bin width fl32(eb*63/32) and write an NZ stream:
+ * per frame of chunk_elems elements the exact sizes of the three codecs are
+ * computed from the frame's full statistics and the smallest admissible one is
+ * materialised (Eq. 2 with transmitted size as the cost; Algorithm 1's gates
+ * are min_gain_permil, huff_min_bytes, force_codec and out_cap).  A frame with
+ * a value that cannot be quantized within eb (NaN, Inf, |x| > 32767 bins) is
+ * RAW and carries the fp32 input unchanged.
+ *   d_out/out_cap  device output and its capacity in bytes; a stream larger
+ *                  than out_cap sets NZ_ERR_CAPACITY and bytes = 0.
+ *   d_ws/ws_bytes  device scratch of at least nz_workspace_bytes(n, opts).
+ */
+nz_status nz_compress(const float* d_in, size_t n, float eb, void* d_out, size_t out_cap, nz_result* d_res,
+                      const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream);
+
+/*
+ * Validate and decode an NZ stream into d_out[0..n): xhat = fl32(float(q) *
+ * step); RAW frames are copied through.  n, eb and opts (chunk_elems,
+ * alphabet) must be the ones the stream was produced with, otherwise
+ * NZ_ERR_MISMATCH; a stream header or frame that fails validation sets
+ * NZ_ERR_CORRUPT, the other frames are still decoded and the output range of a
+ * rejected frame is unspecified (but written only inside its own range).
+ */
+nz_status nz_decompress(const void* d_stream, size_t stream_bytes, float* d_out, size_t n, float eb,
+                        nz_result* d_res, const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream);
+
+/*
+ * Fused decode(A), decode(B), integer add, re-arbitrate, re-encode, frame by
+ * frame: the output decodes to qa+qb exactly, so no lossy step is repeated
+ * (Sec. III "Error propagation").  A and B must have been produced with the
+ * same n, eb and opts.  If either input frame is RAW the output frame is RAW
+ * and holds the fp32 sum (NaN sums stored as 0x7FC00000).  A sum beyond 2^30
+ * in magnitude sets NZ_ERR_RANGE and publishes nothing.
+ */
+nz_status nz_reduce_frames(const void* d_a, size_t a_bytes, const void* d_b, size_t b_bytes, void* d_out,
+                           size_t out_cap, size_t n, float eb, nz_result* d_res, const nz_opts* opts,
+                           void* d_ws, size_t ws_bytes, void* stream);
+
+/* Library version (format version in the high 16 bits, build in the low 16). */
+uint32_t nz_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NZ_H */

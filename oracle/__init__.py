@@ -11,7 +11,7 @@ import numpy as np
 
 from . import build as _build
 
-OK, ERR_INVALID, ERR_CAPACITY, ERR_CORRUPT, ERR_MISMATCH = 0, 1, 2, 3, 4
+OK, ERR_INVALID, ERR_CAPACITY, ERR_RANGE, ERR_CORRUPT, ERR_MISMATCH = 0, 1, 2, 3, 4, 5
 RAW, FIXEDLEN, HUFFMAN = 0, 1, 2
 HDR_BYTES = 32
 STREAM_HDR = 64
@@ -170,7 +170,7 @@ def reduce_frames(a, b, n, eb, opts=None, cap=None):
 def frame_plan(q, opts=None, quantizable=True):
     """Plan one frame of integer codes.  Returns dict with the selector's choice and exact sizes."""
     q = np.ascontiguousarray(q, dtype=np.int32)
-    K = (opts.alphabet if opts is not None and opts.alphabet else 1024)
+    K = (opts.alphabet if opts is not None and opts.alphabet else 256)
     totals = np.zeros(3, np.uint64)
     pay = np.zeros(3, np.uint64)
     w = np.zeros(1, np.uint32)

@@ -47,15 +47,16 @@
 /* public types                                                         */
 /* ------------------------------------------------------------------ */
 
-enum { NZO_OK = 0, NZO_ERR_INVALID = 1, NZO_ERR_CAPACITY = 2, NZO_ERR_CORRUPT = 3,
-       NZO_ERR_MISMATCH = 4 };
+/* Status codes are ordered by precedence: when several conditions hold the largest code is reported. */
+enum { NZO_OK = 0, NZO_ERR_INVALID = 1, NZO_ERR_CAPACITY = 2, NZO_ERR_RANGE = 3, NZO_ERR_CORRUPT = 4,
+       NZO_ERR_MISMATCH = 5 };
 
 enum { NZO_RAW = 0, NZO_FIXEDLEN = 1, NZO_HUFFMAN = 2 };
 
 typedef struct {
     uint32_t chunk_elems;     /* fp32 elements per frame, 1..2^20; 0 -> 262144        */
     uint32_t seg_syms;        /* symbols per Huffman segment, 32..1024; 0 -> 256      */
-    uint32_t alphabet;        /* K, power of two in 2..1024; 0 -> 1024                */
+    uint32_t alphabet;        /* K, power of two in 2..1024; 0 -> 256                 */
     int32_t  force_codec;     /* -1 auto, 0/1/2 pin a codec (Sec. V-B pins codecs)    */
     uint32_t min_gain_permil; /* minimum-gain threshold of Algorithm 1, default 0     */
     uint32_t huff_min_bytes;  /* Huffman size threshold T_huff of Algorithm 1         */
@@ -109,7 +110,7 @@ static int resolve_opts(const nzo_opts* in, nzo_opts* o) {
     if (in) d = *in;
     if (d.chunk_elems == 0) d.chunk_elems = 262144u;
     if (d.seg_syms == 0) d.seg_syms = 256u;
-    if (d.alphabet == 0) d.alphabet = 1024u;
+    if (d.alphabet == 0) d.alphabet = 256u;    /* the paper profiles a 256-bin histogram (Sec. IV-C) */
     if (d.chunk_elems > NZO_MAX_CHUNK) return NZO_ERR_INVALID;
     if (d.seg_syms < 32u || d.seg_syms > 1024u) return NZO_ERR_INVALID;
     if (d.alphabet < 2u || d.alphabet > NZO_MAX_K || !is_pow2(d.alphabet)) return NZO_ERR_INVALID;
@@ -716,7 +717,7 @@ int nzo_decompress(const uint8_t* s, size_t bytes, float* out, size_t n, float e
 
 typedef struct {
     const int32_t* qa; const int32_t* qb; const uint32_t* ra; const uint32_t* rb;
-    const uint8_t* fa; const uint8_t* fb; float step;
+    const uint8_t* fa; const uint8_t* fb; float step; int overflow;
 } reduce_ctx;
 
 static uint32_t canon_sum_bits(float a, float b) {
@@ -727,31 +728,28 @@ static uint32_t canon_sum_bits(float a, float b) {
 }
 
 /*
- * Frame k of the output: both inputs coded -> Q = qa + qb exactly; when every
- * |Q| <= 2^30 the frame is re-planned and re-selected on Q, otherwise it is
- * RAW holding fl32(fl32(qa*step) + fl32(qb*step)).  Either input RAW -> RAW
- * holding the fp32 sum of the two (dequantized or raw) values.
+ * Frame k of the output: both inputs coded -> Q = qa + qb exactly (64-bit), re-planned and re-selected on
+ * Q; a sum with |Q| > 2^30 cannot be carried further and makes the whole call fail with NZO_ERR_RANGE.
+ * Either input RAW -> RAW frame holding the fp32 sum of the two (dequantized or raw) values.
  */
 static int reduce_src(void* vctx, uint32_t k, uint64_t i0, uint32_t nf, int32_t* q, uint32_t* rbits) {
     reduce_ctx* c = (reduce_ctx*)vctx;
     const int a_raw = c->fa[k] == 1, b_raw = c->fb[k] == 1;
-    int coded = !a_raw && !b_raw;
-    if (coded) {
+    if (!a_raw && !b_raw) {
         for (uint32_t i = 0; i < nf; i++) {
             int64_t Q = (int64_t)c->qa[i0 + i] + (int64_t)c->qb[i0 + i];
-            if (Q > NZO_QSUM_MAX || Q < -(int64_t)NZO_QSUM_MAX) coded = 0;
-            q[i] = (int32_t)(coded ? Q : 0);
+            if (Q > NZO_QSUM_MAX || Q < -(int64_t)NZO_QSUM_MAX) { c->overflow = 1; Q = 0; }
+            q[i] = (int32_t)Q;
         }
+        return 1;
     }
-    if (!coded) {
-        for (uint32_t i = 0; i < nf; i++) {
-            float va = a_raw ? bits_f32(c->ra[i0 + i]) : nzo_dequantize_one(c->qa[i0 + i], c->step);
-            float vb = b_raw ? bits_f32(c->rb[i0 + i]) : nzo_dequantize_one(c->qb[i0 + i], c->step);
-            rbits[i] = canon_sum_bits(va, vb);
-            q[i] = 0;
-        }
+    for (uint32_t i = 0; i < nf; i++) {
+        float va = a_raw ? bits_f32(c->ra[i0 + i]) : nzo_dequantize_one(c->qa[i0 + i], c->step);
+        float vb = b_raw ? bits_f32(c->rb[i0 + i]) : nzo_dequantize_one(c->qb[i0 + i], c->step);
+        rbits[i] = canon_sum_bits(va, vb);
+        q[i] = 0;
     }
-    return coded;
+    return 0;
 }
 
 int nzo_reduce_frames(const uint8_t* a, size_t a_bytes, const uint8_t* b, size_t b_bytes, uint8_t* out, size_t cap,
@@ -775,8 +773,14 @@ int nzo_reduce_frames(const uint8_t* a, size_t a_bytes, const uint8_t* b, size_t
     if (!rc) rc = nzo_decode_codes(a, a_bytes, n, eb, qa, ra, fa, NULL);
     if (!rc) rc = nzo_decode_codes(b, b_bytes, n, eb, qb, rb, fb, NULL);
     if (!rc) {
-        reduce_ctx c = { qa, qb, ra, rb, fa, fb, step };
+        reduce_ctx c = { qa, qb, ra, rb, fa, fb, step, 0 };
         rc = emit_stream(reduce_src, &c, n, &o, f32_bits(step), out, cap, res);
+        if (c.overflow) {                       /* RANGE outranks CAPACITY; nothing is published */
+            rc = NZO_ERR_RANGE;
+            uint32_t nfr = res->n_frames;
+            memset(res, 0, sizeof *res);
+            res->n_frames = nfr; res->status = NZO_ERR_RANGE;
+        }
     } else {
         res->status = (uint32_t)rc;
     }

@@ -1,0 +1,139 @@
+"""Thin ctypes binding of libnz.so (include/nz.h).  Argument marshalling only.
+
+PyTorch is used for device memory and streams: tensors are handed over as raw
+device pointers, the current HIP stream as a void*.  There is no CPU fallback:
+if the library has not been built (python -m paper_2605_12396_amd.build or
+__graft_entry__.build()) loading raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+OK, ERR_INVALID, ERR_CAPACITY, ERR_RANGE, ERR_CORRUPT, ERR_MISMATCH, ERR_HIP = range(7)
+RAW, FIXEDLEN, HUFFMAN = 0, 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libnz.so")
+
+
+class Opts(C.Structure):
+    _fields_ = [("chunk_elems", C.c_uint32), ("seg_syms", C.c_uint32), ("alphabet", C.c_uint32),
+                ("force_codec", C.c_int32), ("min_gain_permil", C.c_uint32), ("huff_min_bytes", C.c_uint32)]
+
+
+def make_opts(chunk_elems=0, seg_syms=0, alphabet=0, force_codec=-1, min_gain_permil=0, huff_min_bytes=0):
+    return Opts(chunk_elems, seg_syms, alphabet, force_codec, min_gain_permil, huff_min_bytes)
+
+
+RESULT_BYTES = 32   # sizeof(nz_result)
+_lib = None
+
+
+def lib():
+    """Load libnz.so (once).  Raises if it is missing: the product path has no fallback."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libnz.so is not built: run __graft_entry__.build() (hipcc --offload-arch=gfx950)")
+        L = C.CDLL(LIB_PATH)
+        vp, sz, f32, po = C.c_void_p, C.c_size_t, C.c_float, C.POINTER(Opts)
+        L.nz_version.restype = C.c_uint32
+        L.nz_compress_bound.argtypes = [sz, po]
+        L.nz_compress_bound.restype = sz
+        L.nz_workspace_bytes.argtypes = [sz, po]
+        L.nz_workspace_bytes.restype = sz
+        L.nz_reduce_workspace_bytes.argtypes = [sz, po]
+        L.nz_reduce_workspace_bytes.restype = sz
+        L.nz_compress.argtypes = [vp, sz, f32, vp, sz, vp, po, vp, sz, vp]
+        L.nz_compress.restype = C.c_int
+        L.nz_decompress.argtypes = [vp, sz, vp, sz, f32, vp, po, vp, sz, vp]
+        L.nz_decompress.restype = C.c_int
+        L.nz_reduce_frames.argtypes = [vp, sz, vp, sz, vp, sz, sz, f32, vp, po, vp, sz, vp]
+        L.nz_reduce_frames.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _po(opts):
+    return C.byref(opts) if opts is not None else None
+
+
+def _stream(stream=None):
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return C.c_void_p(s.cuda_stream)
+
+
+def nz_compress_bound(n, opts=None):
+    return int(lib().nz_compress_bound(n, _po(opts)))
+
+
+def nz_workspace_bytes(n, opts=None):
+    return int(lib().nz_workspace_bytes(n, _po(opts)))
+
+
+def nz_reduce_workspace_bytes(n, opts=None):
+    return int(lib().nz_reduce_workspace_bytes(n, _po(opts)))
+
+
+def nz_compress(d_in, n, eb, d_out, out_cap, d_res, opts, d_ws, ws_bytes, stream=None):
+    """d_in: float32 cuda tensor; d_out, d_ws: uint8 cuda tensors; d_res: uint8 cuda tensor of RESULT_BYTES."""
+    return int(lib().nz_compress(d_in.data_ptr(), n, C.c_float(eb), d_out.data_ptr(), out_cap, d_res.data_ptr(),
+                                 _po(opts), d_ws.data_ptr(), ws_bytes, _stream(stream)))
+
+
+def nz_decompress(d_stream, stream_bytes, d_out, n, eb, d_res, opts, d_ws=None, ws_bytes=0, stream=None):
+    return int(lib().nz_decompress(d_stream.data_ptr(), stream_bytes, d_out.data_ptr(), n, C.c_float(eb),
+                                   d_res.data_ptr(), _po(opts), d_ws.data_ptr() if d_ws is not None else None,
+                                   ws_bytes, _stream(stream)))
+
+
+def nz_reduce_frames(d_a, a_bytes, d_b, b_bytes, d_out, out_cap, n, eb, d_res, opts, d_ws, ws_bytes, stream=None):
+    return int(lib().nz_reduce_frames(d_a.data_ptr(), a_bytes, d_b.data_ptr(), b_bytes, d_out.data_ptr(), out_cap, n,
+                                      C.c_float(eb), d_res.data_ptr(), _po(opts), d_ws.data_ptr(), ws_bytes,
+                                      _stream(stream)))
+
+
+def read_result(d_res):
+    """Copy the device result record to the host (synchronises) and unpack it."""
+    import struct
+    raw = bytes(d_res.cpu().numpy().tobytes()[:RESULT_BYTES])
+    b, st, nfr, nraw, nfix, nhuf, _ = struct.unpack("<QIIIIII", raw)
+    return dict(bytes=b, status=st, n_frames=nfr, n_raw=nraw, n_fixed=nfix, n_huff=nhuf)
+
+
+class Session:
+    """Caller-owned buffers for repeated calls on messages of up to n elements (a convenience for tests and
+    the benchmark; the library itself keeps no state)."""
+
+    def __init__(self, n, opts=None, device="cuda:0", reduce=False):
+        self.n, self.opts, self.device = n, opts, torch.device(device)
+        self.cap = nz_compress_bound(n, opts)
+        self.ws_bytes = nz_reduce_workspace_bytes(n, opts) if reduce else nz_workspace_bytes(n, opts)
+        if self.cap == 0 or self.ws_bytes == 0:
+            raise ValueError("invalid n/opts")
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=self.device)
+        self.res = torch.zeros(RESULT_BYTES, dtype=torch.uint8, device=self.device)
+
+    def new_stream_buffer(self):
+        return torch.empty(self.cap, dtype=torch.uint8, device=self.device)
+
+    def compress(self, x, eb, out=None, cap=None):
+        out = out if out is not None else self.new_stream_buffer()
+        rc = nz_compress(x, x.numel(), eb, out, self.cap if cap is None else cap, self.res, self.opts, self.ws,
+                         self.ws_bytes)
+        return rc, out
+
+    def decompress(self, stream, nbytes, n, eb, out=None):
+        out = out if out is not None else torch.empty(n, dtype=torch.float32, device=self.device)
+        rc = nz_decompress(stream, nbytes, out, n, eb, self.res, self.opts, self.ws, self.ws_bytes)
+        return rc, out
+
+    def reduce(self, a, a_bytes, b, b_bytes, n, eb, out=None, cap=None):
+        out = out if out is not None else self.new_stream_buffer()
+        rc = nz_reduce_frames(a, a_bytes, b, b_bytes, out, self.cap if cap is None else cap, n, eb, self.res,
+                              self.opts, self.ws, self.ws_bytes)
+        return rc, out
+
+    def result(self):
+        return read_result(self.res)

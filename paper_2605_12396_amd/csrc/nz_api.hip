@@ -1,0 +1,171 @@
+// nz_api.hip -- extern "C" boundary: argument checks, workspace carve-up and kernel launches.
+// Host code only validates and launches; every step of the path runs in the kernels.
+#include "../../include/nz.h"
+#include "nz_common.hpp"
+
+using namespace nz;
+
+namespace {
+
+struct Opts { uint32_t chunk, seg, K; int32_t force; uint32_t gain, huff_min; };
+
+bool resolve(const nz_opts* in, Opts& o) {
+    o.chunk = 262144u; o.seg = kSeg; o.K = 256u; o.force = -1; o.gain = 0; o.huff_min = 0;
+    if (in) {
+        if (in->chunk_elems) o.chunk = in->chunk_elems;
+        if (in->seg_syms) o.seg = in->seg_syms;
+        if (in->alphabet) o.K = in->alphabet;
+        o.force = in->force_codec; o.gain = in->min_gain_permil; o.huff_min = in->huff_min_bytes;
+    }
+    if (o.chunk > kMaxChunk) return false;
+    if (o.seg != kSeg) return false;                                   // the kernels decode 256-symbol segments
+    if (o.K < 2u || o.K > kMaxK || (o.K & (o.K - 1u))) return false;
+    if (o.force < -1 || o.force > 2) return false;
+    if (o.gain > 1000u) return false;
+    return true;
+}
+
+// step = fl32(eb * 63/32), inv_step = fl32(1/step); each operation rounded once to fp32.
+bool step_constants(float eb, float& step, float& inv) {
+    if (!(eb >= 0x1p-100f && eb <= 0x1p100f)) return false;
+    volatile float s = eb * 1.96875f;
+    volatile float r = 1.0f / s;
+    step = s; inv = r;
+    return true;
+}
+
+uint32_t bits_of(float f) { uint32_t u; __builtin_memcpy(&u, &f, 4); return u; }
+uint64_t pad16h(uint64_t v) { return (v + 15u) & ~(uint64_t)15u; }
+uint64_t pad4h(uint64_t v) { return (v + 3u) & ~(uint64_t)3u; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+uint64_t frame_bound(uint64_t nf, const Opts& o) {
+    uint64_t pay = 4ull * nf;
+    if (o.force == NZ_CODEC_HUFFMAN) {
+        const uint64_t nseg = (nf + o.seg - 1) / o.seg;
+        const uint64_t h = pad4h(o.K) + pad4h(2ull * nseg) + 4ull * ((nf * 60ull + 31u) / 32u);
+        if (h > pay) pay = h;
+    }
+    return pad16h(kHdrBytes + pay);
+}
+
+constexpr uint64_t kMaxElems = 1ull << 38;      // keeps every grid below 2^31 workgroups for frames >= 8192 elements
+
+bool geometry_ok(size_t n, const Opts& o) {
+    if (n == 0 || n > kMaxElems) return false;
+    const uint64_t nfr = (n + o.chunk - 1) / o.chunk;
+    const uint64_t ebpf = (o.chunk + kEncBlock - 1) / kEncBlock;
+    return nfr * ebpf < (1ull << 31) && nfr < (1ull << 31);
+}
+
+}  // namespace
+
+extern "C" {
+
+uint32_t nz_version(void) { return (1u << 16) | 1u; }
+
+size_t nz_compress_bound(size_t n, const nz_opts* opts) {
+    Opts o;
+    if (!resolve(opts, o) || !geometry_ok(n, o)) return 0;
+    const uint64_t nfr = (n + o.chunk - 1) / o.chunk;
+    const uint64_t last = n - (nfr - 1) * o.chunk;
+    return (size_t)(kStreamHdr + pad16h(8ull * nfr) + (nfr - 1) * frame_bound(o.chunk, o) + frame_bound(last, o));
+}
+
+size_t nz_workspace_bytes(size_t n, const nz_opts* opts) {
+    Opts o;
+    if (!resolve(opts, o) || !geometry_ok(n, o)) return 0;
+    return ws_layout(n, o.chunk, kStatBlock, false).total;
+}
+
+size_t nz_reduce_workspace_bytes(size_t n, const nz_opts* opts) {
+    Opts o;
+    if (!resolve(opts, o) || !geometry_ok(n, o)) return 0;
+    return ws_layout(n, o.chunk, kDecBlock, true).total;
+}
+
+nz_status nz_compress(const float* d_in, size_t n, float eb, void* d_out, size_t out_cap, nz_result* d_res,
+                      const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream) {
+    Opts o; float step, inv;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (!d_in || !d_out || !d_res || !d_ws || !resolve(opts, o) || !geometry_ok(n, o) || !step_constants(eb, step, inv))
+        return NZ_ERR_INVALID;
+    if (!aligned16(d_in) || !aligned16(d_out) || !aligned16(d_ws) || !aligned16(d_res)) return NZ_ERR_INVALID;
+    const WsLayout L = ws_layout(n, o.chunk, kStatBlock, false);
+    if (ws_bytes < L.total) return NZ_ERR_INVALID;
+    const uint32_t nfr = (uint32_t)((n + o.chunk - 1) / o.chunk);
+    uint8_t* ws = reinterpret_cast<uint8_t*>(d_ws);
+    if (out_cap < kStreamHdr + pad16h(8ull * nfr)) {        // not even the frame table fits: publish nothing
+        if (launch_init(ws, 0, d_res, nfr, NZ_ERR_CAPACITY, st) != hipSuccess) return NZ_ERR_HIP;
+        return NZ_ERR_CAPACITY;
+    }
+    CompressArgs A;
+    A.in = d_in; A.n = n; A.chunk = o.chunk; A.n_frames = nfr; A.K = o.K;
+    A.stat_block = kStatBlock; A.sbpf = (o.chunk + kStatBlock - 1) / kStatBlock;
+    A.force_codec = o.force; A.min_gain_permil = o.gain; A.huff_min_bytes = o.huff_min;
+    A.eb = eb; A.step = step; A.inv_step = inv; A.step_bits = bits_of(step);
+    A.out = reinterpret_cast<uint8_t*>(d_out); A.out_cap = out_cap; A.ws = ws; A.L = L; A.res = d_res;
+    if (launch_init(ws + L.ctrl, L.zero_end - L.ctrl, d_res, nfr, NZ_OK, st) != hipSuccess) return NZ_ERR_HIP;
+    if (launch_stats(A, st) != hipSuccess) return NZ_ERR_HIP;
+    if (launch_codebook(A, st) != hipSuccess) return NZ_ERR_HIP;
+    if (launch_encode(A, false, st) != hipSuccess) return NZ_ERR_HIP;
+    return NZ_OK;
+}
+
+nz_status nz_decompress(const void* d_stream, size_t stream_bytes, float* d_out, size_t n, float eb,
+                        nz_result* d_res, const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream) {
+    Opts o; float step, inv;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    (void)d_ws; (void)ws_bytes;                                 // decoding needs no scratch
+    if (!d_stream || !d_out || !d_res || !resolve(opts, o) || !geometry_ok(n, o) || !step_constants(eb, step, inv))
+        return NZ_ERR_INVALID;
+    if (!aligned16(d_stream) || !aligned16(d_out) || !aligned16(d_res)) return NZ_ERR_INVALID;
+    const uint32_t nfr = (uint32_t)((n + o.chunk - 1) / o.chunk);
+    DecodeArgs A;
+    A.a = reinterpret_cast<const uint8_t*>(d_stream); A.a_bytes = stream_bytes; A.b = nullptr; A.b_bytes = 0;
+    A.out = d_out; A.n = n; A.chunk = o.chunk; A.n_frames = nfr; A.K = o.K;
+    A.dbpf = (o.chunk + kDecBlock - 1) / kDecBlock;
+    A.step = step; A.step_bits = bits_of(step); A.ws = nullptr; A.L = WsLayout(); A.res = d_res;
+    if (launch_init(nullptr, 0, d_res, nfr, NZ_OK, st) != hipSuccess) return NZ_ERR_HIP;
+    if (launch_decode(A, false, st) != hipSuccess) return NZ_ERR_HIP;
+    return NZ_OK;
+}
+
+nz_status nz_reduce_frames(const void* d_a, size_t a_bytes, const void* d_b, size_t b_bytes, void* d_out,
+                           size_t out_cap, size_t n, float eb, nz_result* d_res, const nz_opts* opts,
+                           void* d_ws, size_t ws_bytes, void* stream) {
+    Opts o; float step, inv;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (!d_a || !d_b || !d_out || !d_res || !d_ws || !resolve(opts, o) || !geometry_ok(n, o) ||
+        !step_constants(eb, step, inv))
+        return NZ_ERR_INVALID;
+    if (!aligned16(d_a) || !aligned16(d_b) || !aligned16(d_out) || !aligned16(d_ws) || !aligned16(d_res))
+        return NZ_ERR_INVALID;
+    const WsLayout L = ws_layout(n, o.chunk, kDecBlock, true);
+    if (ws_bytes < L.total) return NZ_ERR_INVALID;
+    const uint32_t nfr = (uint32_t)((n + o.chunk - 1) / o.chunk);
+    uint8_t* ws = reinterpret_cast<uint8_t*>(d_ws);
+    if (out_cap < kStreamHdr + pad16h(8ull * nfr)) {
+        if (launch_init(ws, 0, d_res, nfr, NZ_ERR_CAPACITY, st) != hipSuccess) return NZ_ERR_HIP;
+        return NZ_ERR_CAPACITY;
+    }
+    DecodeArgs D;
+    D.a = reinterpret_cast<const uint8_t*>(d_a); D.a_bytes = a_bytes;
+    D.b = reinterpret_cast<const uint8_t*>(d_b); D.b_bytes = b_bytes;
+    D.out = nullptr; D.n = n; D.chunk = o.chunk; D.n_frames = nfr; D.K = o.K;
+    D.dbpf = (o.chunk + kDecBlock - 1) / kDecBlock;
+    D.step = step; D.step_bits = bits_of(step); D.ws = ws; D.L = L; D.res = d_res;
+    CompressArgs A;
+    A.in = nullptr; A.n = n; A.chunk = o.chunk; A.n_frames = nfr; A.K = o.K;
+    A.stat_block = kDecBlock; A.sbpf = D.dbpf;
+    A.force_codec = o.force; A.min_gain_permil = o.gain; A.huff_min_bytes = o.huff_min;
+    A.eb = eb; A.step = step; A.inv_step = inv; A.step_bits = bits_of(step);
+    A.out = reinterpret_cast<uint8_t*>(d_out); A.out_cap = out_cap; A.ws = ws; A.L = L; A.res = d_res;
+    if (launch_init(ws + L.ctrl, L.zero_end - L.ctrl, d_res, nfr, NZ_OK, st) != hipSuccess) return NZ_ERR_HIP;
+    if (launch_decode(D, true, st) != hipSuccess) return NZ_ERR_HIP;
+    if (launch_codebook(A, st) != hipSuccess) return NZ_ERR_HIP;
+    if (launch_encode(A, true, st) != hipSuccess) return NZ_ERR_HIP;
+    return NZ_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,190 @@
+// nz_common.hpp -- constants, workspace layout and wave/LDS helpers shared by the gfx950 kernels.
+// (Device-side only; the CPU oracle has its own, separate definitions.)
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace nz {
+
+// ---- stream format v1 constants (the paper leaves header layout open, Sec. IV-D "Batch Framing") ----
+constexpr uint32_t kHdrBytes      = 32;          // frame header: 8 little-endian u32
+constexpr uint32_t kStreamHdr     = 64;          // stream header bytes
+constexpr uint32_t kMagicFrame    = 0x31465A4Eu; // 'N','Z','F','1'
+constexpr uint32_t kMagicStream   = 0x31535A4Eu; // 'N','Z','S','1'
+constexpr uint32_t kCheckXor      = 0x5A5A5A5Au;
+constexpr uint32_t kCanonNaN      = 0x7FC00000u;
+constexpr int      kQMax          = 32767;       // largest quantization code magnitude
+constexpr int      kQSumMax       = 1 << 30;     // largest magnitude a reduced code may take
+constexpr uint32_t kMaxChunk      = 1u << 20;
+constexpr uint32_t kMaxK          = 1024;
+constexpr uint32_t kSeg           = 256;         // symbols per Huffman segment (one wave pass of 4 symbols/lane)
+constexpr uint32_t kMaxLen        = 28;          // deepest optimal code for <= 2^20 symbols (Fibonacci bound)
+
+enum : uint32_t { ST_OK = 0, ST_INVALID = 1, ST_CAPACITY = 2, ST_RANGE = 3, ST_CORRUPT = 4, ST_MISMATCH = 5 };
+enum : uint32_t { CODEC_RAW = 0, CODEC_FIXED = 1, CODEC_HUFF = 2 };
+
+// ---- launch geometry ----
+constexpr uint32_t kStatThreads   = 512;
+constexpr uint32_t kStatBlock     = 32768;       // symbols per statistics workgroup (compress)
+constexpr uint32_t kEncThreads    = 256;
+constexpr uint32_t kEncBlock      = 8192;        // symbols per encode workgroup = 32 segments
+constexpr uint32_t kEncIters      = kEncBlock / (kEncThreads * 4);   // 8 passes of 1024 symbols
+constexpr uint32_t kDecThreads    = 256;
+constexpr uint32_t kDecBlock      = kDecThreads * kSeg;              // 65536 symbols per decode workgroup
+constexpr uint32_t kBookThreads   = 1024;
+
+// ---- per-frame record written by the codebook/selector kernel, read by the encoder ----
+struct FrameMeta {
+    uint64_t offset;      // byte offset of the frame in the stream
+    uint32_t total;       // padded frame bytes
+    uint32_t payload;     // payload bytes
+    uint32_t codec;
+    uint32_t w;           // FIXEDLEN width
+    uint32_t nsym;        // HUFFMAN: 1 + largest used symbol
+    uint32_t fits;        // 1 when offset+total <= out_cap (the encoder writes nothing otherwise)
+    uint32_t segt_off;    // byte offset of the segment table inside the frame
+    uint32_t bits_off;    // byte offset of the bitstream inside the frame
+    uint32_t bits_words;  // bitstream length in 32-bit words
+    uint32_t pad_;
+    uint64_t huff_bits;
+    uint64_t pad2_;
+};
+static_assert(sizeof(FrameMeta) == 64, "FrameMeta is 64 bytes");
+
+// ---- control block at the start of the workspace (zeroed at the start of every call) ----
+struct Ctrl {
+    uint32_t ticket_book;   // dynamic workgroup ids: look-back only ever waits on smaller tickets
+    uint32_t ticket_enc;
+    uint32_t frames_done;
+    uint32_t pad[13];
+};
+static_assert(sizeof(Ctrl) == 64, "Ctrl is 64 bytes");
+
+// Workspace carve-up; computed identically on host for sizing and launch.
+struct WsLayout {
+    size_t ctrl, frame_desc, blk_desc, blk_tail, zero_end;   // [ctrl, zero_end) is cleared per call
+    size_t meta, book_code, book_len, phist, pmeta, codes, total;
+};
+
+__host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+__host__ inline WsLayout ws_layout(size_t n, uint32_t chunk, uint32_t stat_block, bool with_codes) {
+    WsLayout L;
+    const size_t n_frames = (n + chunk - 1) / chunk;
+    const size_t ebpf = (chunk + kEncBlock - 1) / kEncBlock;        // encode blocks per frame
+    const size_t sbpf = (chunk + stat_block - 1) / stat_block;      // statistics blocks per frame
+    size_t o = 0;
+    L.ctrl = o;        o += sizeof(Ctrl);
+    L.frame_desc = o;  o += align_up(8 * n_frames, 256);
+    L.blk_desc = o;    o += align_up(8 * n_frames * ebpf, 256);
+    L.blk_tail = o;    o += align_up(4 * n_frames * ebpf, 256);
+    L.zero_end = o;
+    L.meta = o;        o += align_up(sizeof(FrameMeta) * n_frames, 256);
+    L.book_code = o;   o += align_up(4 * (size_t)kMaxK * n_frames, 256);
+    L.book_len = o;    o += align_up((size_t)kMaxK * n_frames, 256);
+    L.phist = o;       o += align_up(4 * (size_t)kMaxK * n_frames * sbpf, 256);
+    L.pmeta = o;       o += align_up(8 * n_frames * sbpf, 256);
+    L.codes = o;       if (with_codes) o += align_up(4 * n, 256);
+    L.total = o;
+    return L;
+}
+
+// ---- agent-scope relaxed atomics: the only inter-workgroup traffic inside a kernel ----
+__device__ inline uint64_t ld_agent(const uint64_t* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void st_agent(uint64_t* p, uint64_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline uint32_t ld_agent(const uint32_t* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void st_agent(uint32_t* p, uint32_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// ---- wave64 helpers ----
+__device__ inline uint32_t lane_id() { return __lane_id(); }
+
+__device__ inline uint32_t wave_incl_scan(uint32_t v) {
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint32_t t = __shfl_up(v, d, 64);
+        if ((int)lane_id() >= d) v += t;
+    }
+    return v;
+}
+__device__ inline uint32_t wave_sum(uint32_t v) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+__device__ inline uint64_t wave_sum64(uint64_t v) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+    return v;
+}
+__device__ inline uint32_t wave_max(uint32_t v) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) { uint32_t t = __shfl_xor(v, d, 64); v = t > v ? t : v; }
+    return v;
+}
+
+__device__ inline uint32_t zigzag(int32_t q) { return ((uint32_t)q << 1) ^ (uint32_t)(q >> 31); }
+__device__ inline int32_t unzigzag(uint32_t z) { return (int32_t)(z >> 1) ^ -(int32_t)(z & 1u); }
+__device__ inline uint32_t sym_of(uint32_t z, uint32_t K) { return z <= K - 2u ? z + 1u : 0u; }
+
+// Quantize one value (interface quantizer, Sec. IV-B): u = fl(x*inv_step), q = rne(u), accepted when
+// |u| <= 32767 and fl(|x - fl(q*step)|) <= eb.  Every product and difference is rounded on its own.
+__device__ inline bool quantize1(float x, float eb, float step, float inv_step, int32_t& q) {
+#pragma clang fp contract(off)
+    float u = x * inv_step;
+    bool ok = fabsf(u) <= 32767.0f;            // false for NaN
+    float r = __builtin_rintf(u);              // ties to even
+    int32_t qi = ok ? (int32_t)r : 0;
+    float xh = (float)qi * step;
+    float d = x - xh;
+    ok = ok && (fabsf(d) <= eb);
+    q = ok ? qi : 0;
+    return ok;
+}
+__device__ inline float dequantize1(int32_t q, float step) {
+#pragma clang fp contract(off)
+    return (float)q * step;
+}
+
+// Launchers (one per translation unit).
+struct CompressArgs {
+    const float* in;          // fp32 input (compress) or nullptr (reduce: symbols come from ws codes)
+    uint64_t n;
+    uint32_t chunk, n_frames, K, sbpf, stat_block;
+    int32_t force_codec;
+    uint32_t min_gain_permil, huff_min_bytes;
+    float eb, step, inv_step;
+    uint32_t step_bits;
+    uint8_t* out; uint64_t out_cap;
+    uint8_t* ws; WsLayout L;
+    void* res;                // nz_result* (device)
+};
+
+// Result record as laid out by nz_result in the public header.
+struct ResultRec { uint64_t bytes; uint32_t status, n_frames, n_raw, n_fixed, n_huff, reserved; };
+
+struct DecodeArgs {
+    const uint8_t* a; uint64_t a_bytes;
+    const uint8_t* b; uint64_t b_bytes;       // second operand (reduce only)
+    float* out;                               // decompress only
+    uint64_t n;
+    uint32_t chunk, n_frames, K, dbpf;
+    float step; uint32_t step_bits;
+    uint8_t* ws; WsLayout L;                  // reduce only: staged codes, partial histograms
+    void* res;
+};
+
+hipError_t launch_init(void* zero_base, size_t zero_bytes, void* res, uint32_t n_frames, uint32_t status, hipStream_t st);
+hipError_t launch_stats(const CompressArgs& A, hipStream_t st);
+hipError_t launch_codebook(const CompressArgs& A, hipStream_t st);
+hipError_t launch_encode(const CompressArgs& A, bool from_codes, hipStream_t st);
+hipError_t launch_decode(const DecodeArgs& A, bool reduce, hipStream_t st);
+
+}  // namespace nz

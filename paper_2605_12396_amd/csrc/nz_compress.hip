@@ -1,0 +1,556 @@
+// nz_compress.hip -- gfx950 kernels of the sender side: frame statistics (quantize + zmax + histogram),
+// per-frame codebook + exact-size selector + frame-offset look-back, and the bit-packing encoder.
+//
+// Paper mapping: interface quantizer (Sec. IV-B), runtime entropy arbitration with transmitted size as
+// the cost (Sec. IV-C, Eq. 1-2, Algorithm 1), frame = header + payload (Sec. IV-D "Batch Framing").
+// Unlike the paper's sampled estimate by one control thread, the statistics here cover the whole frame,
+// so predicted and realized sizes coincide and Algorithm 1's post-validation never fires.
+#include "nz_common.hpp"
+#include "nz_scan.hpp"
+
+namespace nz {
+
+// ------------------------------------------------------------------------------------------------
+// K0: clear the control block / look-back descriptors and initialise the result record
+// ------------------------------------------------------------------------------------------------
+__global__ void k_init(uint32_t* zero_base, size_t zero_words, ResultRec* res, uint32_t n_frames, uint32_t status) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < zero_words) zero_base[i] = 0;
+    if (i == 0 && res) {
+        res->bytes = 0; res->status = status; res->n_frames = n_frames;
+        res->n_raw = 0; res->n_fixed = 0; res->n_huff = 0; res->reserved = 0;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// K1: frame statistics.  One workgroup per kStatBlock symbols of one frame: coalesced 16-byte loads,
+// quantize, zigzag, lane-replicated LDS histogram, zmax and the "cannot be quantized" flag.
+// The partial histogram goes to the workspace with plain stores; the codebook kernel adds the partials.
+// ------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kStatThreads) void k_stats(CompressArgs A) {
+    __shared__ uint32_t s_h[8192];
+    __shared__ uint32_t s_zmax, s_unq;
+    const uint32_t tid = threadIdx.x, lane = lane_id();
+    const uint32_t frame = blockIdx.x / A.sbpf, sb = blockIdx.x % A.sbpf;
+    const uint64_t f0 = (uint64_t)frame * A.chunk;
+    const uint32_t nf = (uint32_t)((A.n - f0 < A.chunk) ? (A.n - f0) : A.chunk);
+    const uint32_t b0 = sb * kStatBlock;
+    if (b0 >= nf) return;
+    const uint32_t cnt = (nf - b0 < kStatBlock) ? (nf - b0) : kStatBlock;
+    const uint32_t K = A.K;
+    // replicate the histogram over lanes: 8192/K copies (at most 32) so hot bins do not serialise
+    uint32_t ncs = 0;
+    while ((K << (ncs + 1)) <= 8192u && ncs < 5) ncs++;
+    const uint32_t copy = lane & ((1u << ncs) - 1u);
+    for (uint32_t i = tid; i < (K << ncs); i += kStatThreads) s_h[i] = 0;
+    if (tid == 0) { s_zmax = 0; s_unq = 0; }
+    __syncthreads();
+
+    const float* src = A.in + f0 + b0;
+    const bool vec_ok = (((f0 + b0) & 3u) == 0);
+    uint32_t zmax = 0, unq = 0;
+    for (uint32_t i = tid * 4; i < cnt; i += kStatThreads * 4) {
+        float v[4];
+        const uint32_t m = (cnt - i < 4) ? (cnt - i) : 4;
+        if (vec_ok && m == 4) {
+            const float4 t = *reinterpret_cast<const float4*>(src + i);
+            v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+        } else {
+            for (uint32_t j = 0; j < 4; j++) v[j] = (j < m) ? src[i + j] : 0.0f;
+        }
+#pragma unroll
+        for (uint32_t j = 0; j < 4; j++) {
+            if (j < m) {
+                int32_t q;
+                if (!quantize1(v[j], A.eb, A.step, A.inv_step, q)) unq = 1;
+                const uint32_t z = zigzag(q);
+                zmax = z > zmax ? z : zmax;
+                atomicAdd(&s_h[(sym_of(z, K) << ncs) + copy], 1u);
+            }
+        }
+    }
+    zmax = wave_max(zmax);
+    unq = wave_max(unq);
+    if (lane == 0) { atomicMax(&s_zmax, zmax); atomicMax(&s_unq, unq); }
+    __syncthreads();
+    uint32_t* ph = reinterpret_cast<uint32_t*>(A.ws + A.L.phist) + (size_t)blockIdx.x * kMaxK;
+    for (uint32_t s = tid; s < K; s += kStatThreads) {
+        uint32_t t = 0;
+        for (uint32_t c = 0; c < (1u << ncs); c++) t += s_h[(s << ncs) + c];
+        ph[s] = t;
+    }
+    if (tid == 0) {
+        uint2* pm = reinterpret_cast<uint2*>(A.ws + A.L.pmeta) + blockIdx.x;
+        *pm = make_uint2(s_zmax, s_unq);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// K2: one workgroup per frame.  Sum the partial histograms, build optimal prefix-code lengths with the
+// two-queue construction (leaves sorted by (count, symbol), a leaf wins a weight tie against an internal
+// node), assign canonical codes, compute the exact size of each codec, arbitrate, place the frame with a
+// decoupled look-back over frame sizes, and write header, code-length table and the encoder's codebook.
+// ------------------------------------------------------------------------------------------------
+__device__ inline uint64_t pad4u(uint64_t v) { return (v + 3u) & ~(uint64_t)3u; }
+__device__ inline uint64_t pad16u(uint64_t v) { return (v + 15u) & ~(uint64_t)15u; }
+
+__global__ __launch_bounds__(kBookThreads) void k_codebook(CompressArgs A) {
+    __shared__ uint32_t s_f[kMaxK];
+    __shared__ __align__(16) uint32_t s_key[kMaxK];
+    __shared__ uint32_t s_sorted[kMaxK];
+    __shared__ uint32_t s_w[2 * kMaxK];
+    __shared__ uint16_t s_par[2 * kMaxK];
+    __shared__ __align__(4) uint8_t s_len[kMaxK];
+    __shared__ uint16_t s_rank[kMaxK];
+    __shared__ uint32_t s_wcnt[16 * 32], s_cnt[32], s_first[32], s_idx0[32];
+    __shared__ uint64_t s_part[16];
+    __shared__ uint32_t s_fid, s_m, s_nsym, s_zmax, s_unq, s_codec, s_payload, s_total, s_w_fixed;
+    __shared__ uint64_t s_bits, s_off;
+
+    const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const uint32_t K = A.K;
+    Ctrl* ctrl = reinterpret_cast<Ctrl*>(A.ws + A.L.ctrl);
+    if (tid == 0) { s_fid = atomicAdd(&ctrl->ticket_book, 1u); s_m = 0; s_nsym = 0; s_zmax = 0; s_unq = 0; }
+    __syncthreads();
+    const uint32_t fid = s_fid;
+    const uint64_t f0 = (uint64_t)fid * A.chunk;
+    const uint32_t nf = (uint32_t)((A.n - f0 < A.chunk) ? (A.n - f0) : A.chunk);
+    const uint32_t sbc = (nf + A.stat_block - 1) / A.stat_block;
+
+    // (1) frame histogram, zmax, quantizable flag
+    uint32_t f = 0;
+    if (tid < K) {
+        const uint32_t* ph = reinterpret_cast<const uint32_t*>(A.ws + A.L.phist) + (size_t)fid * A.sbpf * kMaxK + tid;
+        for (uint32_t b = 0; b < sbc; b++) f += ph[(size_t)b * kMaxK];
+    }
+    s_f[tid] = f;
+    s_len[tid] = 0;
+    if (tid < sbc) {
+        const uint2 pm = reinterpret_cast<const uint2*>(A.ws + A.L.pmeta)[(size_t)fid * A.sbpf + tid];
+        atomicMax(&s_zmax, pm.x);
+        atomicMax(&s_unq, pm.y);
+    }
+    const bool used = f > 0;
+    {
+        const uint64_t um = __ballot(used);
+        if (lane == 0 && um) { atomicAdd(&s_m, (uint32_t)__popcll(um)); atomicMax(&s_nsym, wave * 64 + 64 - (uint32_t)__clzll(um)); }
+    }
+    // (2) sort used symbols ascending by (count, symbol): rank = number of smaller keys
+    const uint32_t key = used ? ((f << 10) | tid) : 0xFFFFFFFFu;
+    s_key[tid] = key;
+    __syncthreads();
+    const uint32_t m = s_m, nsym = s_nsym;
+    if (used) {
+        uint32_t rank = 0;
+        const uint4* k4 = reinterpret_cast<const uint4*>(s_key);
+        for (uint32_t j = 0; j < K / 4 || j < 1; j++) {
+            const uint4 t = k4[j];
+            rank += (t.x < key) + (t.y < key) + (t.z < key) + (t.w < key);
+        }
+        s_sorted[rank] = key;
+    }
+    __syncthreads();
+    if (tid < m) s_w[tid] = s_sorted[tid] >> 10;
+    __syncthreads();
+
+    // (3) two-queue merge, one lane; queue heads cached in registers
+    if (tid == 0 && m >= 2) {
+        const uint32_t INF = 0xFFFFFFFFu;
+        uint32_t ia = 0, ib = m, nb = m;
+        uint32_t a0 = s_w[0], a1 = (m > 1) ? s_w[1] : INF, b0 = INF, b1 = INF;
+        for (uint32_t step = 0; step + 1 < m; step++) {
+            uint32_t p0, p1, w;
+            if (a0 <= b0) {                       // first pick: leaf (a leaf wins ties)
+                if (a1 <= b0) {                   // second pick: leaf
+                    p0 = ia; p1 = ia + 1; w = a0 + a1; ia += 2;
+                    a0 = (ia < m) ? s_w[ia] : INF; a1 = (ia + 1 < m) ? s_w[ia + 1] : INF;
+                } else {                          // second pick: internal node
+                    p0 = ia; p1 = ib; w = a0 + b0; ia += 1; ib += 1;
+                    a0 = a1; a1 = (ia + 1 < m) ? s_w[ia + 1] : INF;
+                    b0 = b1; b1 = (ib + 1 < nb) ? s_w[ib + 1] : INF;
+                }
+            } else {                              // first pick: internal node
+                if (a0 <= b1) {                   // second pick: leaf
+                    p0 = ib; p1 = ia; w = b0 + a0; ia += 1; ib += 1;
+                    a0 = a1; a1 = (ia + 1 < m) ? s_w[ia + 1] : INF;
+                    b0 = b1; b1 = (ib + 1 < nb) ? s_w[ib + 1] : INF;
+                } else {                          // second pick: internal node
+                    p0 = ib; p1 = ib + 1; w = b0 + b1; ib += 2;
+                    b0 = (ib < nb) ? s_w[ib] : INF; b1 = (ib + 1 < nb) ? s_w[ib + 1] : INF;
+                }
+            }
+            s_w[nb] = w; s_par[p0] = (uint16_t)nb; s_par[p1] = (uint16_t)nb;
+            if (ib == nb) b0 = w; else if (ib + 1 == nb) b1 = w;   // the new node may be a queue head
+            nb++;
+        }
+    }
+    __syncthreads();
+    // (4) code length = depth of the leaf
+    if (tid < m) {
+        uint32_t d = 1;
+        if (m >= 2) {
+            const uint32_t root = 2 * m - 2;
+            d = 0;
+            for (uint32_t x = tid; x != root; x = s_par[x]) d++;
+        }
+        s_len[s_sorted[tid] & 1023u] = (uint8_t)d;
+    }
+    __syncthreads();
+    // (5) canonical codes
+    canonical_tables<kBookThreads>(s_len, K, s_wcnt, s_cnt, s_first, s_idx0, s_rank);
+    const uint32_t L = s_len[tid];
+    const uint32_t code = L ? (s_first[L] + s_rank[tid]) : 0u;
+    // (6) exact Huffman bitstream length: sum f*len, an escape carries 32 more bits
+    {
+        uint64_t b = (uint64_t)f * L + (tid == 0 ? 32ull * f : 0ull);
+        b = wave_sum64(b);
+        if (lane == 0) s_part[wave] = b;
+    }
+    __syncthreads();
+    // (7) sizes and arbitration (Eq. 2: argmin of frame bytes over RAW + admissible codecs, ties to the lower id)
+    if (tid == 0) {
+        uint64_t bits = 0;
+        for (int i = 0; i < 16; i++) bits += s_part[i];
+        const uint32_t zmax = s_zmax;
+        const uint32_t w = zmax ? (32u - (uint32_t)__clz(zmax)) : 0u;
+        const uint32_t nseg = (nf + kSeg - 1) / kSeg;
+        uint64_t pay[3], tot[3];
+        pay[CODEC_RAW] = 4ull * nf;
+        pay[CODEC_FIXED] = 4ull * (((uint64_t)nf * w + 31u) / 32u);
+        pay[CODEC_HUFF] = pad4u(nsym) + pad4u(2ull * nseg) + 4ull * ((bits + 31u) / 32u);
+        for (int c = 0; c < 3; c++) tot[c] = pad16u(kHdrBytes + pay[c]);
+        uint32_t best = CODEC_RAW;
+        if (!s_unq) {
+            if (A.force_codec >= 0) best = (uint32_t)A.force_codec;
+            else {
+                for (uint32_t c = CODEC_FIXED; c <= CODEC_HUFF; c++) {
+                    if (c == CODEC_HUFF && pay[CODEC_RAW] < A.huff_min_bytes) continue;
+                    if (pay[c] > pay[CODEC_RAW]) continue;
+                    if ((pay[CODEC_RAW] - pay[c]) * 1000ull < (uint64_t)A.min_gain_permil * pay[CODEC_RAW]) continue;
+                    if (tot[c] < tot[best]) best = c;
+                }
+            }
+        }
+        s_codec = best; s_payload = (uint32_t)pay[best]; s_total = (uint32_t)tot[best];
+        s_w_fixed = w; s_bits = bits;
+    }
+    __syncthreads();
+    // (8) place the frame: decoupled look-back over padded frame sizes
+    uint64_t* fdesc = reinterpret_cast<uint64_t*>(A.ws + A.L.frame_desc);
+    if (wave == 0) {
+        const uint64_t mine = s_total;
+        if (lane == 0) st_agent(fdesc + fid, kDescA | mine);
+        const uint64_t base = kStreamHdr + pad16u(8ull * A.n_frames);
+        const uint64_t excl = lookback_exclusive(fdesc, 0, (int64_t)fid, base);
+        if (lane == 0) { st_agent(fdesc + fid, kDescP | (excl + mine)); s_off = excl; }
+    }
+    __syncthreads();
+    // (9) publish: offsets table, header, code-length table, encoder codebook, counters
+    const uint64_t off = s_off;
+    const uint32_t codec = s_codec, payload = s_payload, total = s_total;
+    const bool fits = off + total <= A.out_cap;
+    const uint32_t nseg = (nf + kSeg - 1) / kSeg;
+    uint8_t* fr = A.out + off;
+    if (tid == 0) {
+        *reinterpret_cast<uint64_t*>(A.out + kStreamHdr + 8ull * fid) = off;
+        if (fid == A.n_frames - 1 && (A.n_frames & 1u))
+            *reinterpret_cast<uint64_t*>(A.out + kStreamHdr + 8ull * A.n_frames) = 0;      // pad16 of the table
+        FrameMeta M;
+        M.offset = off; M.total = total; M.payload = payload; M.codec = codec; M.w = s_w_fixed; M.nsym = nsym;
+        M.fits = fits ? 1u : 0u;
+        M.segt_off = kHdrBytes + (uint32_t)pad4u(nsym);
+        M.bits_off = (codec == CODEC_HUFF) ? (M.segt_off + (uint32_t)pad4u(2ull * nseg)) : kHdrBytes;
+        M.bits_words = (codec == CODEC_HUFF) ? (uint32_t)((s_bits + 31u) / 32u)
+                                             : (uint32_t)(((uint64_t)nf * s_w_fixed + 31u) / 32u);
+        M.pad_ = 0; M.huff_bits = s_bits; M.pad2_ = 0;
+        reinterpret_cast<FrameMeta*>(A.ws + A.L.meta)[fid] = M;
+        if (fits) {
+            uint32_t h[8];
+            h[0] = kMagicFrame; h[1] = codec; h[2] = 4u * nf; h[3] = payload;
+            h[4] = (codec == CODEC_FIXED) ? s_w_fixed : (codec == CODEC_HUFF ? nsym : 0u);
+            h[5] = (codec == CODEC_HUFF) ? (kSeg | (K << 16)) : 0u;
+            h[6] = A.step_bits;
+            uint32_t x = kCheckXor;
+            for (int i = 0; i < 7; i++) x ^= h[i];
+            h[7] = x;
+            uint4* dst = reinterpret_cast<uint4*>(fr);
+            dst[0] = make_uint4(h[0], h[1], h[2], h[3]);
+            dst[1] = make_uint4(h[4], h[5], h[6], h[7]);
+        }
+        ResultRec* res = reinterpret_cast<ResultRec*>(A.res);
+        atomicAdd(codec == CODEC_RAW ? &res->n_raw : (codec == CODEC_FIXED ? &res->n_fixed : &res->n_huff), 1u);
+        if (fid == A.n_frames - 1) {
+            const uint64_t stream_total = off + total;
+            if (stream_total > A.out_cap) atomicMax(&res->status, (uint32_t)ST_CAPACITY);
+            uint32_t* sh = reinterpret_cast<uint32_t*>(A.out);
+            sh[0] = kMagicStream; sh[1] = 1u;
+            sh[2] = (uint32_t)A.n; sh[3] = (uint32_t)(A.n >> 32);
+            sh[4] = A.chunk; sh[5] = A.n_frames; sh[6] = A.step_bits; sh[7] = kSeg; sh[8] = K; sh[9] = 0;
+            sh[10] = (uint32_t)stream_total; sh[11] = (uint32_t)(stream_total >> 32);
+            sh[12] = 0; sh[13] = 0; sh[14] = 0; sh[15] = 0;
+            const uint32_t st = atomicMax(&res->status, 0u);
+            res->bytes = (st == ST_OK && stream_total <= A.out_cap) ? stream_total : 0ull;
+        }
+    }
+    if (codec == CODEC_HUFF) {
+        if (fits) {   // code lengths, one byte per symbol, zero padded to 4
+            const uint32_t words = (uint32_t)(pad4u(nsym) / 4);
+            if (tid < words) reinterpret_cast<uint32_t*>(fr + kHdrBytes)[tid] = reinterpret_cast<const uint32_t*>(s_len)[tid];
+        }
+        // encoder codebook: code bits reversed so that emitting them LSB-first sends the code MSB-first
+        if (tid < K) {
+            reinterpret_cast<uint32_t*>(A.ws + A.L.book_code)[(size_t)fid * kMaxK + tid] = L ? (__brev(code) >> (32u - L)) : 0u;
+            (A.ws + A.L.book_len)[(size_t)fid * kMaxK + tid] = (uint8_t)L;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// K4: encoder.  One workgroup per kEncBlock symbols of one frame.
+//   RAW      copy the words.
+//   FIXEDLEN w bits per zigzag code, positions in closed form (a block starts on a word boundary).
+//   HUFFMAN  phase 1: code lengths -> per-segment bit counts (written to the segment table) and the
+//            block's bit count, published for the in-frame decoupled look-back; phase 2: pack the codes
+//            of 1024 symbols at a time into an LDS stage with ds_or and flush whole words coalesced.
+//            Blocks are not word aligned: the word a block shares with its predecessor is written by the
+//            later block, which fetches the predecessor's last 31 stream bits from its tail descriptor.
+// SRC = 0: symbols are quantized from the fp32 input; SRC = 1: symbols are the int32 codes staged in the
+// workspace by the reduce front end (RAW frames hold fp32 bit patterns there).
+// ------------------------------------------------------------------------------------------------
+template <int SRC>
+__global__ __launch_bounds__(kEncThreads) void k_encode(CompressArgs A) {
+    __shared__ uint32_t s_code[kMaxK];
+    __shared__ uint8_t s_len[kMaxK];
+    __shared__ uint32_t s_stage[2048];
+    __shared__ uint32_t s_wtot[4], s_seglen[32];
+    __shared__ uint32_t s_bid, s_first_word, s_first_taken, s_lastw;
+    __shared__ uint64_t s_excl;
+
+    const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    Ctrl* ctrl = reinterpret_cast<Ctrl*>(A.ws + A.L.ctrl);
+    if (tid == 0) { s_bid = atomicAdd(&ctrl->ticket_enc, 1u); s_first_taken = 0; s_first_word = 0; s_lastw = 0; }
+    __syncthreads();
+    const uint32_t bid = s_bid;
+    const uint32_t ebpf = (A.chunk + kEncBlock - 1) / kEncBlock;
+    const uint32_t frame = bid / ebpf, bif = bid % ebpf;
+    const uint64_t f0 = (uint64_t)frame * A.chunk;
+    const uint32_t nf = (uint32_t)((A.n - f0 < A.chunk) ? (A.n - f0) : A.chunk);
+    const uint32_t blk0 = bif * kEncBlock;
+    if (blk0 >= nf) return;
+    const FrameMeta M = reinterpret_cast<const FrameMeta*>(A.ws + A.L.meta)[frame];
+    if (!M.fits) return;
+    const uint32_t cnt = (nf - blk0 < kEncBlock) ? (nf - blk0) : kEncBlock;
+    const bool last_blk = (blk0 + cnt == nf);
+    uint8_t* fr = A.out + M.offset;
+    const uint32_t K = A.K;
+    const uint32_t* codes_ws = reinterpret_cast<const uint32_t*>(A.ws + A.L.codes);
+
+    // ---- RAW: copy this block's words, the last block zero-fills the frame padding ----
+    if (M.codec == CODEC_RAW) {
+        uint32_t* dst = reinterpret_cast<uint32_t*>(fr + kHdrBytes) + blk0;
+        const uint32_t* src = (SRC == 0) ? reinterpret_cast<const uint32_t*>(A.in) + f0 + blk0 : codes_ws + f0 + blk0;
+        for (uint32_t i = tid; i < cnt; i += kEncThreads) dst[i] = src[i];
+        if (last_blk) {
+            const uint32_t w0 = (kHdrBytes + 4u * nf) / 4, w1 = M.total / 4;
+            if (tid < w1 - w0) reinterpret_cast<uint32_t*>(fr)[w0 + tid] = 0;
+        }
+        return;
+    }
+
+    // ---- load this thread's 32 symbols: pass `it` covers symbols it*1024 + tid*4 .. +3 of the block ----
+    int32_t q[kEncIters][4];
+    {
+        const bool vec_ok = (((f0 + blk0) & 3u) == 0);
+#pragma unroll
+        for (uint32_t it = 0; it < kEncIters; it++) {
+            const uint32_t i = it * 1024 + tid * 4;
+            const uint32_t mvalid = (i < cnt) ? ((cnt - i < 4) ? (cnt - i) : 4u) : 0u;
+            if (SRC == 0) {
+                const float* src = A.in + f0 + blk0;
+                float v[4] = { 0.f, 0.f, 0.f, 0.f };
+                if (vec_ok && mvalid == 4) {
+                    const float4 t = *reinterpret_cast<const float4*>(src + i);
+                    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+                } else {
+                    for (uint32_t j = 0; j < 4; j++) if (j < mvalid) v[j] = src[i + j];
+                }
+#pragma unroll
+                for (uint32_t j = 0; j < 4; j++) { int32_t t; quantize1(v[j], A.eb, A.step, A.inv_step, t); q[it][j] = t; }
+            } else {
+                const uint32_t* src = codes_ws + f0 + blk0;
+                if (vec_ok && mvalid == 4) {
+                    const uint4 t = *reinterpret_cast<const uint4*>(src + i);
+                    q[it][0] = (int32_t)t.x; q[it][1] = (int32_t)t.y; q[it][2] = (int32_t)t.z; q[it][3] = (int32_t)t.w;
+                } else {
+#pragma unroll
+                    for (uint32_t j = 0; j < 4; j++) q[it][j] = (j < mvalid) ? (int32_t)src[i + j] : 0;
+                }
+            }
+        }
+    }
+
+    const bool huff = (M.codec == CODEC_HUFF);
+    uint32_t start_bit = 0;                       // first bit of this block inside the frame's bitstream
+    if (huff) {
+        for (uint32_t s = tid; s < K; s += kEncThreads) {
+            s_code[s] = reinterpret_cast<const uint32_t*>(A.ws + A.L.book_code)[(size_t)frame * kMaxK + s];
+            s_len[s] = (A.ws + A.L.book_len)[(size_t)frame * kMaxK + s];
+        }
+        __syncthreads();
+        // phase 1: bit count of every segment (= one wave pass) and of the block
+        uint16_t* segt = reinterpret_cast<uint16_t*>(fr + M.segt_off);
+        const uint32_t nseg = (nf + kSeg - 1) / kSeg;
+#pragma unroll
+        for (uint32_t it = 0; it < kEncIters; it++) {
+            const uint32_t i = it * 1024 + tid * 4;
+            uint32_t tl = 0;
+#pragma unroll
+            for (uint32_t j = 0; j < 4; j++) {
+                if (i + j < cnt) {
+                    const uint32_t sy = sym_of(zigzag(q[it][j]), K);
+                    tl += s_len[sy] + (sy == 0 ? 32u : 0u);
+                }
+            }
+            tl = wave_sum(tl);
+            if (lane == 0) {
+                const uint32_t g = it * 4 + wave;                       // segment index inside the block
+                s_seglen[g] = tl;
+                const uint32_t gseg = blk0 / kSeg + g;
+                if (gseg < nseg) segt[gseg] = (uint16_t)tl;
+                if (last_blk && gseg == nseg - 1 && (nseg & 1u)) segt[nseg] = 0;   // pad4 of the table
+            }
+        }
+        __syncthreads();
+        uint64_t* bdesc = reinterpret_cast<uint64_t*>(A.ws + A.L.blk_desc) + (size_t)frame * ebpf;
+        if (wave == 0) {
+            uint32_t t = (lane < 32) ? s_seglen[lane] : 0u;
+            t = wave_sum(t);
+            if (lane == 0) st_agent(bdesc + bif, kDescA | (uint64_t)t);
+            const uint64_t excl = lookback_exclusive(bdesc, 0, (int64_t)bif, 0);
+            if (lane == 0) { st_agent(bdesc + bif, kDescP | (excl + t)); s_excl = excl; }
+        }
+        __syncthreads();
+        start_bit = (uint32_t)s_excl;
+    } else {
+        start_bit = blk0 * M.w;                   // multiple of 32: blk0 is a multiple of 8192
+    }
+
+    // phase 2: pack
+    for (uint32_t i = tid; i < 2048; i += kEncThreads) s_stage[i] = 0;
+    __syncthreads();
+    uint32_t* bits = reinterpret_cast<uint32_t*>(fr + M.bits_off);
+    const uint32_t c0 = start_bit & 31u;          // bits of the first word owned by the predecessor
+    const uint32_t w_first = start_bit >> 5;
+    uint32_t carry = c0, wpos = w_first;
+    const uint32_t wfix = M.w;
+#pragma unroll
+    for (uint32_t it = 0; it < kEncIters; it++) {
+        if (it * 1024 >= cnt) continue;            // uniform over the workgroup; q[it] stays a static index
+        const uint32_t i = it * 1024 + tid * 4;
+        uint32_t val[4], len[4], esc[4], tl = 0;
+#pragma unroll
+        for (uint32_t j = 0; j < 4; j++) {
+            val[j] = 0; len[j] = 0; esc[j] = 0;
+            if (i + j < cnt) {
+                const uint32_t z = zigzag(q[it][j]);
+                if (huff) {
+                    const uint32_t sy = sym_of(z, K);
+                    val[j] = s_code[sy]; len[j] = s_len[sy];
+                    if (sy == 0) { esc[j] = 1; }
+                } else { val[j] = z; len[j] = wfix; }
+                tl += len[j] + (esc[j] ? 32u : 0u);
+            }
+        }
+        const uint32_t incl = wave_incl_scan(tl);
+        if (lane == 63) s_wtot[wave] = incl;
+        __syncthreads();
+        uint32_t pos = carry + incl - tl;
+        uint32_t total_it = 0;
+#pragma unroll
+        for (uint32_t w = 0; w < 4; w++) { if (w < wave) pos += s_wtot[w]; total_it += s_wtot[w]; }
+#pragma unroll
+        for (uint32_t j = 0; j < 4; j++) {
+            if (len[j]) {
+                const uint32_t sh = pos & 31u, wi = pos >> 5;
+                atomicOr(&s_stage[wi], val[j] << sh);
+                if (sh + len[j] > 32u) atomicOr(&s_stage[wi + 1], val[j] >> (32u - sh));
+                pos += len[j];
+            }
+            if (esc[j]) {
+                const uint32_t z = zigzag(q[it][j]);
+                const uint32_t sh = pos & 31u, wi = pos >> 5;
+                atomicOr(&s_stage[wi], z << sh);
+                if (sh) atomicOr(&s_stage[wi + 1], z >> (32u - sh));
+                pos += 32u;
+            }
+        }
+        __syncthreads();
+        const uint32_t nbits = carry + total_it;
+        const uint32_t nw = nbits >> 5;
+        for (uint32_t k = tid; k < nw; k += kEncThreads) {
+            const uint32_t wv = s_stage[k];
+            if (c0 && wpos + k == w_first) { s_first_word = wv; s_first_taken = 1; }   // deferred: shared word
+            else bits[wpos + k] = wv;
+        }
+        const uint32_t partial = s_stage[nw];
+        if (tid == 0 && nw) s_lastw = s_stage[nw - 1];
+        __syncthreads();
+        for (uint32_t k = tid; k <= nw; k += kEncThreads) s_stage[k] = (k == 0) ? partial : 0u;
+        carry = nbits & 31u;
+        wpos += nw;
+        __syncthreads();
+    }
+    // tail: the word shared with the successor is the successor's to write; publish our last 31 bits
+    const uint32_t partial = s_stage[0];
+    uint32_t* btail = reinterpret_cast<uint32_t*>(A.ws + A.L.blk_tail) + (size_t)frame * ebpf;
+    if (tid == 0) {
+        if (!last_blk) {
+            const uint64_t X = (uint64_t)s_lastw | ((uint64_t)partial << 32);
+            st_agent(btail + bif, 0x80000000u | (uint32_t)((X >> (1u + carry)) & 0x7FFFFFFFu));
+        } else if (carry) {
+            if (c0 && wpos == w_first && !s_first_taken) { s_first_word = partial; s_first_taken = 1; }
+            else bits[wpos] = partial;
+        }
+        if (c0) {
+            // the first word: predecessor's last c0 bits (low) + our own bits (high)
+            uint32_t t;
+            while (((t = ld_agent(btail + bif - 1)) & 0x80000000u) == 0) __builtin_amdgcn_s_sleep(2);
+            bits[w_first] = s_first_word | ((t & 0x7FFFFFFFu) >> (31u - c0));
+        }
+    }
+    if (last_blk) {   // zero the padding after the last bitstream word
+        const uint32_t w0 = M.bits_off / 4 + M.bits_words, w1 = M.total / 4;
+        if (tid < w1 - w0) reinterpret_cast<uint32_t*>(fr)[w0 + tid] = 0;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------
+// host launchers
+// ------------------------------------------------------------------------------------------------
+hipError_t launch_init(void* zero_base, size_t zero_bytes, void* res, uint32_t n_frames, uint32_t status,
+                       hipStream_t st) {
+    const size_t words = zero_bytes / 4;
+    const uint32_t blocks = (uint32_t)((words + 255) / 256);
+    hipLaunchKernelGGL(k_init, dim3(blocks ? blocks : 1), dim3(256), 0, st, reinterpret_cast<uint32_t*>(zero_base), words,
+                       reinterpret_cast<ResultRec*>(res), n_frames, status);
+    return hipGetLastError();
+}
+
+hipError_t launch_stats(const CompressArgs& A, hipStream_t st) {
+    hipLaunchKernelGGL(k_stats, dim3(A.n_frames * A.sbpf), dim3(kStatThreads), 0, st, A);
+    return hipGetLastError();
+}
+
+hipError_t launch_codebook(const CompressArgs& A, hipStream_t st) {
+    hipLaunchKernelGGL(k_codebook, dim3(A.n_frames), dim3(kBookThreads), 0, st, A);
+    return hipGetLastError();
+}
+
+hipError_t launch_encode(const CompressArgs& A, bool from_codes, hipStream_t st) {
+    const uint32_t ebpf = (A.chunk + kEncBlock - 1) / kEncBlock;
+    if (from_codes) hipLaunchKernelGGL(k_encode<1>, dim3(A.n_frames * ebpf), dim3(kEncThreads), 0, st, A);
+    else hipLaunchKernelGGL(k_encode<0>, dim3(A.n_frames * ebpf), dim3(kEncThreads), 0, st, A);
+    return hipGetLastError();
+}
+
+}  // namespace nz

@@ -1,0 +1,366 @@
+// nz_decode.hip -- gfx950 kernels of the receiver side: validate stream and frame headers, rebuild the
+// canonical decode table from the code lengths carried in the frame, decode one 256-symbol segment per
+// thread from its recorded bit offset, then either dequantize (decompress) or add the codes of two
+// streams and gather the statistics of the sum (front end of the fused reduce).
+//
+// Paper mapping: receiver side of Algorithm 2 (ParseHeader, ValidateHeader, DecodeOrMemcpy) and the
+// decode + reduce part of the fused receive-decode-reduce-encode-send step (Sec. IV-D).
+#include "nz_common.hpp"
+#include "nz_scan.hpp"
+
+namespace nz {
+
+constexpr uint32_t kPrimaryBits = 11;         // first-level decode table: 2048 entries of sym | len<<10
+enum : uint32_t { KIND_RAW = 0, KIND_FIXED = 1, KIND_HUFF = 2, KIND_ZERO = 3 };
+
+__device__ inline uint64_t pad4d(uint64_t v) { return (v + 3u) & ~(uint64_t)3u; }
+__device__ inline uint64_t pad16d(uint64_t v) { return (v + 15u) & ~(uint64_t)15u; }
+
+// Stream header checks (format violations first, then disagreement with the caller's n / step / options).
+__device__ inline uint32_t check_stream(const uint8_t* s, uint64_t bytes, const DecodeArgs& A, uint64_t& total) {
+    total = 0;
+    if (bytes < kStreamHdr) return ST_CORRUPT;
+    const uint32_t* h = reinterpret_cast<const uint32_t*>(s);
+    if (h[0] != kMagicStream || h[1] != 1u) return ST_CORRUPT;
+    const uint64_t n = (uint64_t)h[2] | ((uint64_t)h[3] << 32);
+    const uint32_t chunk = h[4], nfr = h[5], stepb = h[6], seg = h[7], K = h[8];
+    total = (uint64_t)h[10] | ((uint64_t)h[11] << 32);
+    if (n == 0 || chunk == 0 || chunk > kMaxChunk) return ST_CORRUPT;
+    if (seg < 32u || seg > 1024u) return ST_CORRUPT;
+    if (K < 2u || K > kMaxK || (K & (K - 1u))) return ST_CORRUPT;
+    if ((n + chunk - 1) / chunk != (uint64_t)nfr) return ST_CORRUPT;
+    if (total > bytes || total < kStreamHdr + pad16d(8ull * nfr)) return ST_CORRUPT;
+    if (n != A.n || stepb != A.step_bits) return ST_MISMATCH;
+    if (chunk != A.chunk || K != A.K || seg != kSeg) return ST_MISMATCH;
+    return ST_OK;
+}
+
+// Shared memory of one operand's decoder.
+struct DecTables {
+    uint16_t tab[1u << kPrimaryBits];
+    uint16_t sorted[kMaxK];
+    uint32_t cnt[32], first[32], idx0[32];
+};
+
+struct FrameView {
+    uint32_t status;          // ST_OK or the reason the frame was rejected
+    uint32_t kind;            // KIND_*
+    uint32_t w;               // FIXEDLEN width
+    const uint32_t* words;    // RAW: payload words; FIXEDLEN/HUFFMAN: bitstream words
+    uint32_t nwords;
+    const uint16_t* segt;
+    uint64_t seg_prefix;      // bits before this workgroup's first segment
+};
+
+// Build-time scratch shared by both operands.
+struct BuildScratch {
+    __align__(4) uint8_t len[kMaxK];
+    uint16_t rank[kMaxK];
+    uint32_t wcnt[16 * 32];
+    uint64_t red[4];
+    uint32_t flag;
+};
+
+template <int NT>
+__device__ inline uint64_t block_sum64(uint64_t v, uint64_t* s_red) {
+    v = wave_sum64(v);
+    __syncthreads();
+    if (lane_id() == 0) s_red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    uint64_t t = 0;
+    for (int i = 0; i < NT / 64; i++) t += s_red[i];
+    return t;
+}
+
+// Validate one frame and prepare its decoder (all threads of the workgroup call this together).
+template <int NT>
+__device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t frame, uint32_t nf, uint32_t first_seg,
+                                  const DecodeArgs& A, DecTables* T, BuildScratch* B, FrameView& V) {
+    const uint32_t tid = threadIdx.x;
+    V.status = ST_CORRUPT; V.kind = KIND_ZERO; V.w = 0; V.words = nullptr; V.nwords = 0; V.segt = nullptr; V.seg_prefix = 0;
+    const uint64_t off = *reinterpret_cast<const uint64_t*>(s + kStreamHdr + 8ull * frame);
+    if ((off & 15u) || off < kStreamHdr + pad16d(8ull * A.n_frames) || off + kHdrBytes > total) return;
+    const uint8_t* fr = s + off;
+    const uint4 h0 = reinterpret_cast<const uint4*>(fr)[0], h1 = reinterpret_cast<const uint4*>(fr)[1];
+    const uint32_t x = kCheckXor ^ h0.x ^ h0.y ^ h0.z ^ h0.w ^ h1.x ^ h1.y ^ h1.z;
+    if (h0.x != kMagicFrame || h1.w != x) return;
+    const uint32_t codec = h0.y, raw_bytes = h0.z, payload = h0.w, p0 = h1.x, p1 = h1.y;
+    if (codec > 2u || raw_bytes != 4u * nf) return;
+    if (off + kHdrBytes + (uint64_t)payload > total) return;
+    if (h1.z != A.step_bits) { V.status = ST_MISMATCH; return; }
+    const uint8_t* pay = fr + kHdrBytes;
+    if (codec == CODEC_RAW) {
+        if (payload != 4u * nf || p0 || p1) return;
+        V.status = ST_OK; V.kind = KIND_RAW; V.words = reinterpret_cast<const uint32_t*>(pay); V.nwords = nf;
+        return;
+    }
+    if (codec == CODEC_FIXED) {
+        if (p0 > 32u || p1) return;
+        const uint64_t need = 4ull * (((uint64_t)nf * p0 + 31u) / 32u);
+        if (payload != need) return;
+        V.status = ST_OK; V.kind = KIND_FIXED; V.w = p0;
+        V.words = reinterpret_cast<const uint32_t*>(pay); V.nwords = payload / 4;
+        return;
+    }
+    // HUFFMAN
+    const uint32_t nsym = p0, seg = p1 & 0xFFFFu, K = p1 >> 16;
+    if (seg != kSeg || K != A.K || nsym == 0 || nsym > K) return;
+    const uint32_t nseg = (nf + kSeg - 1) / kSeg;
+    const uint64_t tables = pad4d(nsym) + pad4d(2ull * nseg);
+    if (payload < tables || (payload & 3u)) return;
+    const uint8_t* lens = pay;
+    const uint16_t* segt = reinterpret_cast<const uint16_t*>(pay + pad4d(nsym));
+    // code lengths: <= 28, padding zero, at least one used, Kraft sum <= 1
+    uint32_t bad = 0;
+    uint64_t kraft = 0;
+    for (uint32_t t = tid; t < kMaxK; t += NT) {
+        uint32_t L = 0;
+        if (t < (uint32_t)pad4d(nsym)) L = lens[t];
+        if (L > kMaxLen || (t >= nsym && L)) bad = 1;
+        if (L && L <= kMaxLen && t < nsym) kraft += 1ull << (kMaxLen - L);
+        B->len[t] = (t < nsym && L <= kMaxLen) ? (uint8_t)L : 0;
+    }
+    // segment table: bits before this workgroup's first segment, and in the whole frame
+    uint64_t pre = 0, all = 0;
+    for (uint32_t g = tid; g < nseg; g += NT) { const uint32_t v = segt[g]; all += v; if (g < first_seg) pre += v; }
+    if ((nseg & 1u) && tid == 0 && segt[nseg] != 0) bad = 1;
+    kraft = block_sum64<NT>(kraft, B->red);
+    pre = block_sum64<NT>(pre, B->red);
+    all = block_sum64<NT>(all, B->red);
+    const uint64_t badsum = block_sum64<NT>(bad, B->red);
+    if (badsum || kraft == 0 || kraft > (1ull << kMaxLen)) return;
+    const uint64_t avail = 8ull * (payload - tables);
+    if (all > avail || 4ull * ((all + 31u) / 32u) != payload - tables) return;
+    // canonical tables and the first-level lookup
+    uint32_t* s_cnt = T->cnt; uint32_t* s_first = T->first; uint32_t* s_idx0 = T->idx0;
+    canonical_tables<NT>(B->len, K, B->wcnt, s_cnt, s_first, s_idx0, B->rank);
+    for (uint32_t sy = tid; sy < K; sy += NT) {
+        const uint32_t L = B->len[sy];
+        if (L) T->sorted[s_idx0[L] + B->rank[sy]] = (uint16_t)sy;
+    }
+    __syncthreads();
+    for (uint32_t i = tid; i < (1u << kPrimaryBits); i += NT) {
+        uint32_t code = 0, e = 0;
+        for (uint32_t L = 1; L <= kPrimaryBits; L++) {
+            code = (code << 1) | ((i >> (L - 1)) & 1u);            // stream order: first bit is the code's MSB
+            const uint32_t d = code - s_first[L];
+            if (d < s_cnt[L]) { e = T->sorted[s_idx0[L] + d] | (L << 10); break; }
+        }
+        T->tab[i] = (uint16_t)e;
+    }
+    __syncthreads();
+    V.status = ST_OK; V.kind = KIND_HUFF; V.segt = segt; V.seg_prefix = pre;
+    V.words = reinterpret_cast<const uint32_t*>(pay + tables); V.nwords = (uint32_t)((payload - tables) / 4);
+}
+
+// Per-thread sequential reader of one segment.
+struct Reader {
+    uint32_t kind, w;
+    const uint32_t* words; uint32_t nwords, widx;
+    uint64_t buf; uint32_t navail, consumed, bad;
+    const DecTables* T;
+
+    __device__ inline uint32_t ldw(uint32_t i) const { return i < nwords ? words[i] : 0u; }
+    __device__ inline void init(const FrameView& V, const DecTables* tables, uint64_t bitpos, uint32_t elem0) {
+        kind = V.kind; w = V.w; words = V.words; nwords = V.nwords; T = tables; consumed = 0; bad = 0;
+        buf = 0; navail = 0; widx = 0;
+        if (kind == KIND_RAW) { widx = elem0; return; }
+        if (kind == KIND_ZERO) return;
+        widx = (uint32_t)(bitpos >> 5);
+        const uint32_t sh = (uint32_t)(bitpos & 31u);
+        buf = ((uint64_t)ldw(widx) | ((uint64_t)ldw(widx + 1) << 32)) >> sh;
+        navail = 64u - sh;
+        widx += 2;
+    }
+    __device__ inline void refill() {
+        if (navail <= 32u) { buf |= (uint64_t)ldw(widx++) << navail; navail += 32u; }
+    }
+    __device__ inline uint32_t take(uint32_t nb) {
+        const uint32_t v = (uint32_t)(buf & ((1ull << nb) - 1ull));
+        buf >>= nb; navail -= nb; consumed += nb;
+        return v;
+    }
+    // Next element: returns the zigzag code (coded frames) or the fp32 bit pattern (RAW frames).
+    __device__ inline uint32_t next() {
+        if (kind == KIND_HUFF) {
+            refill();
+            uint32_t e = T->tab[(uint32_t)buf & ((1u << kPrimaryBits) - 1u)];
+            uint32_t L = e >> 10, sy = e & 1023u;
+            if (L == 0) {                                     // long or unassigned code: canonical search
+                uint32_t code = 0;
+                for (uint32_t l = 1; l <= kMaxLen; l++) {
+                    code = (code << 1) | ((uint32_t)(buf >> (l - 1)) & 1u);
+                    const uint32_t d = code - T->first[l];
+                    if (d < T->cnt[l]) { sy = T->sorted[T->idx0[l] + d]; L = l; break; }
+                }
+                if (L == 0) { bad = 1; L = 1; sy = 1; }
+            }
+            take(L);
+            if (sy == 0) { refill(); return take(32); }
+            return sy - 1u;
+        }
+        if (kind == KIND_FIXED) { refill(); return take(w); }
+        if (kind == KIND_RAW) return words[widx++];
+        return 0u;
+    }
+};
+
+// MODE 0: decompress A into fp32.  MODE 1: reduce front end, Q = qa + qb into the workspace + statistics.
+template <int MODE>
+__global__ __launch_bounds__(kDecThreads) void k_decode(DecodeArgs A) {
+    __shared__ DecTables s_ta;
+    __shared__ DecTables s_tb[1];             // second operand (reduce)
+    __shared__ BuildScratch s_build;
+    __shared__ uint32_t s_h[MODE == 1 ? 4096 : 1];
+    __shared__ uint32_t s_zmax;
+
+    const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const uint32_t frame = blockIdx.x / A.dbpf, db = blockIdx.x % A.dbpf;
+    const uint64_t f0 = (uint64_t)frame * A.chunk;
+    const uint32_t nf = (uint32_t)((A.n - f0 < A.chunk) ? (A.n - f0) : A.chunk);
+    const uint32_t blk0 = db * kDecBlock;
+    if (blk0 >= nf) return;
+    ResultRec* res = reinterpret_cast<ResultRec*>(A.res);
+    const uint32_t first_seg = db * kDecThreads;
+    const uint32_t nseg = (nf + kSeg - 1) / kSeg;
+    const uint32_t gseg = first_seg + tid;
+    const bool seg_valid = gseg < nseg;
+    const uint32_t e0 = gseg * kSeg;                                    // first element of my segment in the frame
+    const uint32_t cntseg = seg_valid ? ((nf - e0 < kSeg) ? (nf - e0) : kSeg) : 0u;
+
+    uint64_t total_a = 0, total_b = 0;
+    const uint32_t st_a = check_stream(A.a, A.a_bytes, A, total_a);
+    uint32_t st_b = ST_OK;
+    if (MODE == 1) st_b = check_stream(A.b, A.b_bytes, A, total_b);
+    if (blockIdx.x == 0 && tid == 0) {
+        if (st_a) atomicMax(&res->status, st_a);
+        if (st_b) atomicMax(&res->status, st_b);
+        if (MODE == 0 && st_a == ST_OK) res->bytes = total_a;
+    }
+    if (MODE == 0 && st_a) return;                                      // nothing is written on a stream-level error
+
+    FrameView va, vb;
+    va.status = ST_OK; va.kind = KIND_ZERO; va.w = 0; va.words = nullptr; va.nwords = 0; va.segt = nullptr; va.seg_prefix = 0;
+    vb = va;
+    if (st_a == ST_OK && (MODE == 0 || st_b == ST_OK)) {
+        open_frame<kDecThreads>(A.a, total_a, frame, nf, first_seg, A, &s_ta, &s_build, va);
+        if (MODE == 1) open_frame<kDecThreads>(A.b, total_b, frame, nf, first_seg, A, &s_tb[0], &s_build, vb);
+        if (tid == 0) {
+            if (va.status) atomicMax(&res->status, va.status);
+            if (MODE == 1 && vb.status) atomicMax(&res->status, vb.status);
+            if (MODE == 0 && db == 0 && va.status == ST_OK)
+                atomicAdd(va.kind == KIND_RAW ? &res->n_raw : (va.kind == KIND_FIXED ? &res->n_fixed : &res->n_huff), 1u);
+        }
+        if (MODE == 1 && (va.status || vb.status)) { va.kind = KIND_ZERO; vb.kind = KIND_ZERO; }
+    }
+    if (MODE == 0 && va.status) return;                                 // rejected frame: its output range is left alone
+
+    // bit offset of my segment: prefix of the segment table (HUFFMAN) or closed form (FIXEDLEN)
+    uint64_t bit_a = 0, bit_b = 0;
+    uint32_t seglen_a = 0, seglen_b = 0;
+    {
+        uint32_t la = (va.kind == KIND_HUFF && seg_valid) ? va.segt[gseg] : 0u;
+        uint32_t lb = (MODE == 1 && vb.kind == KIND_HUFF && seg_valid) ? vb.segt[gseg] : 0u;
+        seglen_a = la; seglen_b = lb;
+        // both lengths are < 2^16: scan them packed in one 64-bit lane value (sums stay below 2^32 each)
+        uint64_t v = (uint64_t)la | ((uint64_t)lb << 32);
+        uint64_t incl = v;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) { uint64_t t = __shfl_up(incl, d, 64); if ((int)lane >= d) incl += t; }
+        __shared__ uint64_t s_wsum[4];
+        if (lane == 63) s_wsum[wave] = incl;
+        __syncthreads();
+        uint64_t excl = incl - v;
+        for (uint32_t w = 0; w < wave; w++) excl += s_wsum[w];
+        bit_a = va.seg_prefix + (excl & 0xFFFFFFFFull);
+        bit_b = vb.seg_prefix + (excl >> 32);
+        if (va.kind == KIND_FIXED) bit_a = (uint64_t)e0 * va.w;
+        if (MODE == 1 && vb.kind == KIND_FIXED) bit_b = (uint64_t)e0 * vb.w;
+    }
+
+    Reader ra, rb;
+    ra.init(va, &s_ta, bit_a, e0);
+    if (MODE == 1) rb.init(vb, &s_tb[0], bit_b, e0);
+
+    if (MODE == 0) {
+        float* dst = A.out + f0 + e0;
+        const bool vec_ok = ((f0 & 3u) == 0);
+        for (uint32_t i = 0; i < cntseg; i += 4) {
+            float v[4];
+            const uint32_t m = (cntseg - i < 4) ? (cntseg - i) : 4u;
+            for (uint32_t j = 0; j < 4; j++) {
+                v[j] = 0.f;
+                if (j < m) {
+                    const uint32_t t = ra.next();
+                    v[j] = (ra.kind == KIND_RAW) ? __uint_as_float(t) : dequantize1(unzigzag(t), A.step);
+                }
+            }
+            if (vec_ok && m == 4) *reinterpret_cast<float4*>(dst + i) = make_float4(v[0], v[1], v[2], v[3]);
+            else for (uint32_t j = 0; j < m; j++) dst[i + j] = v[j];
+        }
+        if (seg_valid && ra.kind == KIND_HUFF && (ra.bad || ra.consumed != seglen_a)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
+        return;
+    }
+
+    // ---- MODE 1: sum of codes, statistics of the sum ----
+    const uint32_t K = A.K;
+    uint32_t ncs = 0;
+    while ((K << (ncs + 1)) <= 4096u && ncs < 5) ncs++;
+    const uint32_t copy = lane & ((1u << ncs) - 1u);
+    for (uint32_t i = tid; i < (K << ncs); i += kDecThreads) s_h[i] = 0;
+    if (tid == 0) s_zmax = 0;
+    __syncthreads();
+    const bool out_raw = (ra.kind == KIND_RAW) || (rb.kind == KIND_RAW);      // uniform over the frame
+    uint32_t* dstq = reinterpret_cast<uint32_t*>(A.ws + A.L.codes) + f0 + e0;
+    const bool vec_ok = ((f0 & 3u) == 0);
+    uint32_t zmax = 0, overflow = 0;
+    for (uint32_t i = 0; i < cntseg; i += 4) {
+        uint32_t o[4] = { 0, 0, 0, 0 };
+        const uint32_t m = (cntseg - i < 4) ? (cntseg - i) : 4u;
+        for (uint32_t j = 0; j < 4; j++) {
+            if (j < m) {
+                const uint32_t ta = ra.next(), tb = rb.next();
+                if (out_raw) {
+#pragma clang fp contract(off)
+                    const float fa = (ra.kind == KIND_RAW) ? __uint_as_float(ta) : dequantize1(unzigzag(ta), A.step);
+                    const float fb = (rb.kind == KIND_RAW) ? __uint_as_float(tb) : dequantize1(unzigzag(tb), A.step);
+                    const float sum = fa + fb;
+                    o[j] = (sum != sum) ? kCanonNaN : __float_as_uint(sum);
+                } else {
+                    const int64_t Q = (int64_t)unzigzag(ta) + (int64_t)unzigzag(tb);
+                    if (Q > (int64_t)kQSumMax || Q < -(int64_t)kQSumMax) overflow = 1;
+                    const int32_t qs = (int32_t)Q;
+                    const uint32_t z = zigzag(qs);
+                    zmax = z > zmax ? z : zmax;
+                    atomicAdd(&s_h[(sym_of(z, K) << ncs) + copy], 1u);
+                    o[j] = (uint32_t)qs;
+                }
+            }
+        }
+        if (vec_ok && m == 4) *reinterpret_cast<uint4*>(dstq + i) = make_uint4(o[0], o[1], o[2], o[3]);
+        else for (uint32_t j = 0; j < m; j++) dstq[i + j] = o[j];
+    }
+    if (seg_valid) {
+        if (ra.kind == KIND_HUFF && (ra.bad || ra.consumed != seglen_a)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
+        if (rb.kind == KIND_HUFF && (rb.bad || rb.consumed != seglen_b)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
+        if (overflow) atomicMax(&res->status, (uint32_t)ST_RANGE);
+    }
+    zmax = wave_max(zmax);
+    if (lane == 0) atomicMax(&s_zmax, zmax);
+    __syncthreads();
+    uint32_t* ph = reinterpret_cast<uint32_t*>(A.ws + A.L.phist) + (size_t)blockIdx.x * kMaxK;
+    for (uint32_t sy = tid; sy < K; sy += kDecThreads) {
+        uint32_t t = 0;
+        for (uint32_t c = 0; c < (1u << ncs); c++) t += s_h[(sy << ncs) + c];
+        ph[sy] = t;
+    }
+    if (tid == 0) reinterpret_cast<uint2*>(A.ws + A.L.pmeta)[blockIdx.x] = make_uint2(s_zmax, out_raw ? 1u : 0u);
+}
+
+hipError_t launch_decode(const DecodeArgs& A, bool reduce, hipStream_t st) {
+    if (reduce) hipLaunchKernelGGL(k_decode<1>, dim3(A.n_frames * A.dbpf), dim3(kDecThreads), 0, st, A);
+    else hipLaunchKernelGGL(k_decode<0>, dim3(A.n_frames * A.dbpf), dim3(kDecThreads), 0, st, A);
+    return hipGetLastError();
+}
+
+}  // namespace nz

@@ -1,0 +1,75 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol include/nz.h declares, and its pure
+host functions (bounds, workspace sizes, argument checks that need no GPU) behave.  No compute call is made."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def nz():
+    from paper_2605_12396_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2605_12396_amd import build
+        build.build()
+    binding.lib()
+    return binding
+
+
+def test_exports_every_declared_symbol(nz):
+    hdr = open(os.path.join(ROOT, "include", "nz.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    names = set(re.findall(r"\b(nz_[a-z_]+)\s*\(", hdr))
+    assert {"nz_compress", "nz_decompress", "nz_reduce_frames", "nz_compress_bound", "nz_workspace_bytes",
+            "nz_reduce_workspace_bytes", "nz_version"} <= names
+    L = nz.lib()
+    for n in names:
+        assert hasattr(L, n), n
+    assert L.nz_version() >> 16 == 1
+
+
+def test_struct_layouts_match_header(nz):
+    assert C.sizeof(nz.Opts) == 24 and nz.RESULT_BYTES == 32 == C.sizeof(oracle.Result)
+
+
+def test_compress_bound_equals_oracle_bound(nz):
+    for n in (1, 37, 16384, 100000, (1 << 20) + 1, 1 << 26):
+        for kw in (dict(), dict(chunk_elems=16384), dict(chunk_elems=1000, force_codec=2), dict(chunk_elems=1 << 20),
+                   dict(alphabet=1024, force_codec=2)):
+            assert nz.nz_compress_bound(n, nz.make_opts(**kw)) == oracle.compress_bound(n, oracle.make_opts(**kw))
+    assert nz.nz_compress_bound(0) == 0
+    assert nz.nz_compress_bound(100, nz.make_opts(alphabet=3)) == 0
+    assert nz.nz_compress_bound(100, nz.make_opts(seg_syms=64)) == 0       # the HIP build decodes 256-symbol segments
+    assert nz.nz_compress_bound(100, nz.make_opts(chunk_elems=(1 << 20) + 1)) == 0
+
+
+def test_workspace_sizes(nz):
+    n = 1 << 26
+    w = nz.nz_workspace_bytes(n)
+    wr = nz.nz_reduce_workspace_bytes(n)
+    assert 0 < w < 32 << 20                      # per-frame tables and partial histograms only
+    assert wr >= 4 * n and wr < 4 * n + (32 << 20)
+    assert nz.nz_workspace_bytes(0) == 0
+
+
+def test_missing_library_fails_loudly(nz, monkeypatch, tmp_path):
+    from paper_2605_12396_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError):
+        binding.lib()
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2605_12396_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".hpp", ".h")):
+                src = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in src and "from oracle" not in src and "nz_oracle" not in src, f

@@ -1,0 +1,275 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bars: compressed / reduced streams bit-identical (bytes, selector decisions, sizes); decompressed fp32 values
+bit-identical (both sides compute fl32(float(q)*step), so the 1-ulp allowance is not needed); |x - xhat| <= eb
+checked in float64 as a hard invariant.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2605_12396_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def nz(gpu_device):
+    from paper_2605_12396_amd import binding
+    binding.lib()
+    return binding
+
+
+def _opts_pair(nz, **kw):
+    return nz.make_opts(**kw), oracle.make_opts(**kw)
+
+
+def _to_dev(nz, x):
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(x)).to("cuda:0")
+
+
+def gpu_compress(nz, x, eb, g_opts, cap=None):
+    sess = nz.Session(x.size, g_opts, "cuda:0")
+    rc, out = sess.compress(_to_dev(nz, x), eb, cap=cap)
+    r = sess.result()
+    return rc, r, out[:r["bytes"]].cpu().numpy()
+
+
+def gpu_decompress(nz, stream, n, eb, g_opts):
+    import torch
+    sess = nz.Session(n, g_opts, "cuda:0")
+    pad = (-stream.size) % 16
+    d = _to_dev(nz, np.concatenate([stream, np.zeros(pad, np.uint8)]))
+    out = torch.full((n,), 7.0, dtype=torch.float32, device="cuda:0")
+    rc, out = sess.decompress(d, stream.size, n, eb, out=out)
+    r = sess.result()
+    return rc, r, out.cpu().numpy()
+
+
+def gpu_reduce(nz, a, b, n, eb, g_opts, cap=None):
+    sess = nz.Session(n, g_opts, "cuda:0", reduce=True)
+    da = _to_dev(nz, np.concatenate([a, np.zeros((-a.size) % 16, np.uint8)]))
+    db = _to_dev(nz, np.concatenate([b, np.zeros((-b.size) % 16, np.uint8)]))
+    rc, out = sess.reduce(da, a.size, db, b.size, n, eb, cap=cap)
+    r = sess.result()
+    return rc, r, out[:r["bytes"]].cpu().numpy()
+
+
+def _first_diff(a, b):
+    m = min(a.size, b.size)
+    d = np.nonzero(a[:m] != b[:m])[0]
+    return int(d[0]) if d.size else (m if a.size != b.size else -1)
+
+
+def check_compress(nz, x, eb, **kw):
+    g, o = _opts_pair(nz, **kw)
+    ref, ores, orc = oracle.compress(x, eb, o)
+    rc, r, got = gpu_compress(nz, x, eb, g)
+    assert rc == 0 and orc == 0 and r["status"] == 0, (rc, orc, r)
+    assert (r["n_raw"], r["n_fixed"], r["n_huff"], r["n_frames"]) == (ores.n_raw, ores.n_fixed, ores.n_huff, ores.n_frames)
+    assert r["bytes"] == ores.bytes, (r, ores.as_dict())
+    assert _first_diff(got, ref) == -1, "first differing byte at %d" % _first_diff(got, ref)
+    return ref, ores
+
+
+def check_decompress(nz, stream, x, eb, **kw):
+    g, o = _opts_pair(nz, **kw)
+    ref, ores, orc = oracle.decompress(stream, x.size, eb)
+    rc, r, got = gpu_decompress(nz, stream, x.size, eb, g)
+    assert rc == 0 and orc == 0 and r["status"] == 0, (rc, orc, r)
+    assert r["bytes"] == stream.size
+    assert (r["n_raw"], r["n_fixed"], r["n_huff"]) == (ores.n_raw, ores.n_fixed, ores.n_huff)
+    assert (got.view(np.uint32) == ref.view(np.uint32)).all()
+    finite = np.isfinite(x)
+    err = np.abs(got[finite].astype(np.float64) - x[finite].astype(np.float64))
+    assert (err <= np.float32(eb)).all()                     # hard invariant (RAW frames reproduce x exactly)
+
+
+# ------------------------------------------------------------------------------------------------
+# compress + decompress
+# ------------------------------------------------------------------------------------------------
+
+def _cases():
+    rng = np.random.default_rng(99)
+    yield "c1_smooth_64KBframes", W.smooth_field((256, 64, 64), seed=1), 1e-4, dict(chunk_elems=16384)
+    x = W.gradient_like(1 << 20, seed=2)
+    yield "c2_like_1MBframes", x, W.abs_bound_from_rel(x, 1e-4), dict(chunk_elems=262144)
+    yield "c2_like_K1024", x[:300000], W.abs_bound_from_rel(x, 1e-4), dict(chunk_elems=100000, alphabet=1024)
+    yield "ragged_tail", W.gradient_like(70001, seed=4), 1e-4, dict(chunk_elems=20000)
+    yield "chunk_not_multiple_of_4", W.gradient_like(30011, seed=5), 1e-4, dict(chunk_elems=10003)
+    yield "n1", np.array([0.123], np.float32), 1e-3, dict()
+    yield "n_tiny", W.gradient_like(37, seed=6), 1e-4, dict(chunk_elems=16)
+    yield "max_chunk", W.gradient_like((1 << 20) + 5000, seed=7), 3e-4, dict(chunk_elems=1 << 20)
+    yield "uniform_fixedlen", W.sweep_payload("uniform", 200000, 50), 1e-4, dict(chunk_elems=65536)
+    yield "sinusoid", W.sweep_payload("sinusoid", 200000, 51), 1e-4, dict(chunk_elems=16384)
+    yield "all_zero", np.zeros(50000, np.float32), 1e-4, dict(chunk_elems=16384)
+    yield "constant", np.full(50000, 0.777, np.float32), 1e-4, dict(chunk_elems=16384)
+    yield "escape_heavy_K16", (rng.laplace(0, 3e-3, 100000)).astype(np.float32), 1e-4, dict(chunk_elems=32768, alphabet=16)
+    yield "K2", (rng.laplace(0, 1e-4, 60000)).astype(np.float32), 1e-4, dict(chunk_elems=32768, alphabet=2)
+    y = W.gradient_like(100000, seed=8)
+    y[[5, 40000, 99999]] = [np.nan, np.inf, -1e30]
+    yield "nan_inf_frames_raw", y, 1e-4, dict(chunk_elems=16384)
+    z = (rng.uniform(-1, 1, 80000) * 32767 * 1.96875e-3).astype(np.float32)
+    yield "codes_up_to_qmax", z, 1e-3, dict(chunk_elems=16384)
+    yield "denormals_and_tiny_eb", (rng.standard_normal(40000) * 1e-38).astype(np.float32), 1e-30, dict(chunk_elems=8192)
+
+
+@pytest.mark.parametrize("name,x,eb,kw", list(_cases()), ids=[c[0] for c in _cases()])
+def test_compress_bytes_and_decompress_values_match_oracle(nz, name, x, eb, kw):
+    ref, _ = check_compress(nz, x, eb, **kw)
+    check_decompress(nz, ref, x, eb, **kw)
+
+
+@pytest.mark.parametrize("codec", [0, 1, 2])
+@pytest.mark.parametrize("kind", ["laplace", "uniform", "sinusoid"])
+def test_pinned_codecs(nz, codec, kind):
+    x = W.sweep_payload(kind, 150000, 60)
+    kw = dict(chunk_elems=40000, force_codec=codec)
+    ref, _ = check_compress(nz, x, 1e-4, **kw)
+    check_decompress(nz, ref, x, 1e-4, **kw)
+
+
+def test_selector_gates(nz):
+    x = W.gradient_like(200000, seed=12)
+    for kw in (dict(chunk_elems=50000, huff_min_bytes=200001), dict(chunk_elems=50000, min_gain_permil=700),
+               dict(chunk_elems=50000, min_gain_permil=1000), dict(chunk_elems=50000, huff_min_bytes=4 * 50000)):
+        check_compress(nz, x, 1e-4, **kw)
+
+
+def test_repeatable(nz):
+    x = W.gradient_like(500000, seed=13)
+    g, _ = _opts_pair(nz, chunk_elems=65536)
+    first = gpu_compress(nz, x, 1e-4, g)[2]
+    for _ in range(3):
+        assert (gpu_compress(nz, x, 1e-4, g)[2] == first).all()
+
+
+def test_capacity_and_argument_errors(nz):
+    import torch
+    x = W.gradient_like(100000, seed=14)
+    g, o = _opts_pair(nz, chunk_elems=16384)
+    ref, ores, _ = oracle.compress(x, 1e-4, o)
+    for cap in (int(ores.bytes) - 16, 4096, 64):
+        rc, r, _ = gpu_compress(nz, x, 1e-4, g, cap=cap)
+        assert r["status"] == nz.ERR_CAPACITY and r["bytes"] == 0
+    rc, r, got = gpu_compress(nz, x, 1e-4, g, cap=int(ores.bytes))
+    assert rc == 0 and r["status"] == 0 and (got == ref).all()
+    sess = nz.Session(x.size, g, "cuda:0")
+    dx = _to_dev(nz, x)
+    out = sess.new_stream_buffer()
+    for eb in (0.0, -1.0, float("nan"), float("inf"), 1e-35):
+        assert nz.nz_compress(dx, x.size, eb, out, sess.cap, sess.res, g, sess.ws, sess.ws_bytes) == nz.ERR_INVALID
+    assert nz.nz_compress(dx, 0, 1e-4, out, sess.cap, sess.res, g, sess.ws, sess.ws_bytes) == nz.ERR_INVALID
+    assert nz.nz_compress(dx, x.size, 1e-4, out, sess.cap, sess.res, g, sess.ws, 16) == nz.ERR_INVALID
+    assert nz.nz_compress(dx[1:], x.size - 1, 1e-4, out, sess.cap, sess.res, g, sess.ws, sess.ws_bytes) == nz.ERR_INVALID
+    bad = nz.make_opts(chunk_elems=16384, seg_syms=128)
+    assert nz.nz_compress(dx, x.size, 1e-4, out, sess.cap, sess.res, bad, sess.ws, sess.ws_bytes) == nz.ERR_INVALID
+    torch.cuda.synchronize()
+
+
+def test_decompress_rejections(nz):
+    x = W.gradient_like(60000, seed=15)
+    eb = 1e-4
+    g, o = _opts_pair(nz, chunk_elems=16384)
+    s, _, _ = oracle.compress(x, eb, o)
+    ref, _, _ = oracle.decompress(s, x.size, eb)
+    # stream-level
+    assert gpu_decompress(nz, s, x.size, 2e-4, g)[1]["status"] == nz.ERR_MISMATCH
+    g2 = nz.make_opts(chunk_elems=8192)
+    assert gpu_decompress(nz, s, x.size, eb, g2)[1]["status"] == nz.ERR_MISMATCH
+    t = s.copy(); t[0] ^= 1
+    assert gpu_decompress(nz, t, x.size, eb, g)[1]["status"] == nz.ERR_CORRUPT
+    assert gpu_decompress(nz, s[:-16], x.size, eb, g)[1]["status"] == nz.ERR_CORRUPT
+    # frame headers: same verdict as the oracle; accepted mutations decode identically; other frames unaffected
+    off = int(s[64 + 8:64 + 16].view(np.uint64)[0])
+    for i in range(32):
+        t = s.copy(); t[off + i] ^= 0x41
+        oref, ores, orc = oracle.decompress(t, x.size, eb)
+        rc, r, got = gpu_decompress(nz, t, x.size, eb, g)
+        assert r["status"] == orc, (i, r, orc)
+        keep = np.ones(x.size, bool)
+        if orc:
+            keep[16384:32768] = False
+        assert (got.view(np.uint32)[keep] == ref.view(np.uint32)[keep]).all()
+    # garbage inside payloads: never faults; status is OK or CORRUPT like the oracle's
+    rng = np.random.default_rng(3)
+    for _ in range(40):
+        t = s.copy()
+        i = int(rng.integers(off + 32, s.size))
+        t[i] ^= int(rng.integers(1, 256))
+        orc = oracle.decompress(t, x.size, eb)[2]
+        r = gpu_decompress(nz, t, x.size, eb, g)[1]
+        assert r["status"] in (nz.OK, nz.ERR_CORRUPT)
+        if orc == 0:
+            assert r["status"] == 0
+
+
+# ------------------------------------------------------------------------------------------------
+# fused reduce
+# ------------------------------------------------------------------------------------------------
+
+def test_reduce_matches_oracle_and_chains(nz):
+    n, eb = 300000, 1e-5
+    kw = dict(chunk_elems=65536)
+    g, o = _opts_pair(nz, **kw)
+    msgs = W.peer_messages(n, peers=4, seed0=40)
+    streams = [oracle.compress(m, eb, o)[0] for m in msgs]
+    acc_o = streams[0]
+    acc_g = streams[0]
+    for p in range(1, 4):
+        acc_o, ores, orc = oracle.reduce_frames(acc_o, streams[p], n, eb, o)
+        rc, r, acc_g = gpu_reduce(nz, acc_g, streams[p], n, eb, g)
+        assert rc == 0 and orc == 0 and r["status"] == 0
+        assert r["bytes"] == ores.bytes and _first_diff(acc_g, acc_o) == -1
+        assert (r["n_raw"], r["n_fixed"], r["n_huff"]) == (ores.n_raw, ores.n_fixed, ores.n_huff)
+    rc, r, got = gpu_decompress(nz, acc_g, n, eb, g)
+    true = sum(m.astype(np.float64) for m in msgs)
+    assert (np.abs(got.astype(np.float64) - true) <= 4 * float(np.float32(eb))).all()
+
+
+@pytest.mark.parametrize("ca,cb", [(0, 0), (0, 1), (0, 2), (1, 1), (1, 2), (2, 1), (2, 2), (2, 0)])
+def test_reduce_all_codec_pairs(nz, ca, cb):
+    n, eb = 70001, 1e-4
+    a = W.gradient_like(n, seed=80)
+    b = W.sweep_payload("uniform", n, 81)
+    sa = oracle.compress(a, eb, oracle.make_opts(chunk_elems=20000, force_codec=ca))[0]
+    sb = oracle.compress(b, eb, oracle.make_opts(chunk_elems=20000, force_codec=cb))[0]
+    g, o = _opts_pair(nz, chunk_elems=20000)
+    ref, ores, orc = oracle.reduce_frames(sa, sb, n, eb, o)
+    rc, r, got = gpu_reduce(nz, sa, sb, n, eb, g)
+    assert rc == 0 and orc == 0 and r["status"] == 0
+    assert r["bytes"] == ores.bytes and _first_diff(got, ref) == -1
+
+
+def test_reduce_raw_nan_range_and_mismatch(nz):
+    n, eb = 3000, 1e-3
+    g, o = _opts_pair(nz, chunk_elems=1000)
+    a = W.gradient_like(n, seed=70); b = W.gradient_like(n, seed=71)
+    a[1500] = np.nan; b[2500] = np.inf; a[2501] = -np.inf
+    sa = oracle.compress(a, eb, o)[0]; sb = oracle.compress(b, eb, o)[0]
+    ref, ores, orc = oracle.reduce_frames(sa, sb, n, eb, o)
+    rc, r, got = gpu_reduce(nz, sa, sb, n, eb, g)
+    assert orc == 0 and r["status"] == 0 and r["bytes"] == ores.bytes and _first_diff(got, ref) == -1
+    # range: double a stream until the sum passes 2^30
+    x = np.zeros(1000, np.float32)
+    x[7] = np.float32(32767.0) * oracle.step_constants(eb)[0]
+    s = oracle.compress(x, eb, o)[0]
+    for i in range(15):
+        s_o = oracle.reduce_frames(s, s, 1000, eb, o)[0]
+        rc, r, s_g = gpu_reduce(nz, s, s, 1000, eb, g)
+        assert r["status"] == 0 and _first_diff(s_g, s_o) == -1
+        s = s_o
+    assert oracle.reduce_frames(s, s, 1000, eb, o)[2] == oracle.ERR_RANGE
+    rc, r, _ = gpu_reduce(nz, s, s, 1000, eb, g)
+    assert r["status"] == nz.ERR_RANGE and r["bytes"] == 0
+    # operands that disagree
+    sc = oracle.compress(a, 2e-3, o)[0]
+    assert gpu_reduce(nz, sa, sc, n, eb, g)[1]["status"] == nz.ERR_MISMATCH
+    sd = oracle.compress(a, eb, oracle.make_opts(chunk_elems=500))[0]
+    assert gpu_reduce(nz, sa, sd, n, eb, g)[1]["status"] == nz.ERR_MISMATCH
+    t = sa.copy(); t[int(t[64:72].view(np.uint64)[0]) + 4] ^= 7          # frame 0 codec id
+    assert gpu_reduce(nz, t, sb, n, eb, g)[1]["status"] == nz.ERR_CORRUPT
+    # capacity
+    rc, r, _ = gpu_reduce(nz, sa, sb, n, eb, g, cap=int(ores.bytes) - 16)
+    assert r["status"] == nz.ERR_CAPACITY and r["bytes"] == 0

@@ -588,7 +588,7 @@ def test_reduce_raw_and_overflow_paths():
     qa = oracle.quantize(a[:1000], eb)[0]; qb = oracle.quantize(b[:1000], eb)[0]
     qd, _, kinds, _, _ = oracle.decode_codes(r, n, eb)
     assert kinds.tolist() == [0, 1, 1] and (qd[:1000] == qa + qb).all()
-    # overflow: doubling a stream 16 times pushes |Q| past 2^30 -> RAW frame with the fp32 sum
+    # overflow: doubling a stream 15 times reaches 32767 * 2^15 < 2^30; once more exceeds 2^30 -> RANGE error
     x = np.zeros(1000, np.float32)
     step, _ = oracle.step_constants(eb)
     x[7] = np.float32(32767.0) * step
@@ -599,11 +599,10 @@ def test_reduce_raw_and_overflow_paths():
         s = s2
     qd = oracle.decode_codes(s, 1000, eb)[0]
     assert qd[7] == 32767 << 15
+    out = oracle.decompress(s, 1000, eb)[0]
+    assert out[7] == np.float32(np.float32(32767 << 15) * step) and not out[:7].any()
     s2, res, rc = oracle.reduce_frames(s, s, 1000, eb, opts)
-    assert rc == 0 and res.n_raw == 1
-    out = oracle.decompress(s2, 1000, eb)[0]
-    v = np.float32(np.float32(32767 << 15) * step)
-    assert out[7] == np.float32(v + v) and not out[:7].any()
+    assert rc == oracle.ERR_RANGE and res.bytes == 0 and res.status == oracle.ERR_RANGE
     # mismatching operands
     sc = oracle.compress(a, 2e-3, opts)[0]
     assert oracle.reduce_frames(sa, sc, n, eb, opts)[2] == oracle.ERR_MISMATCH
