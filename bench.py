@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the per-rank compression path on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch of synthetic input already resident in HBM:
+nz_compress(message) -> nz_decompress(stream) -> nz_reduce_frames(stream, peer stream), on the headline
+workload (64 Mi fp32 gradient-like values, eb = 1e-4 x range, 1 MiB frames).  `value` is the fp32 input bytes
+the three stages handle per step (3 x 4n) divided by the step time.  Per-stage GB/s, the compression ratio,
+the roofline record of the dominant kernel (HIP events recorded by the library between its kernels) and the
+CPU oracle timed on this host's cores are reported in the same JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def make_workload(name):
+    import numpy as np
+    from paper_2605_12396_amd import workloads as W
+    if name == "c2":
+        n = 1 << 26
+        x = W.gradient_like(n, seed=2)
+        peer = W.gradient_like(n, seed=102)
+        eb = W.abs_bound_from_rel(x, 1e-4)
+        desc = "config2: 64Mi fp32 Laplace(0,1e-3)+1% Laplace(0,1e-1) outliers, eb=1e-4*range, 1MiB frames"
+        chunk = 262144
+    elif name == "c1":
+        x = W.smooth_field((256, 64, 64), seed=1)
+        peer = W.smooth_field((256, 64, 64), seed=11)
+        n, eb, chunk = x.size, 1e-4, 16384
+        desc = "config1: smooth 256x64x64 fp32 field, eb=1e-4, 64KiB frames"
+    elif name == "c4":
+        n = 1 << 25
+        x = W.gradient_like(n, seed=40, outlier_frac=0.0)
+        peer = W.gradient_like(n, seed=41, outlier_frac=0.0)
+        eb, chunk = 1e-5, 262144
+        desc = "config4 (one ring step): 32Mi fp32 Laplace(0,1e-3) per peer, eb=1e-5, 1MiB frames"
+    else:
+        raise SystemExit("unknown workload %r" % name)
+    return dict(name=name, desc=desc, n=n, x=x, peer=peer, eb=float(np.float32(eb)), chunk=chunk)
+
+
+def cpu_baseline(wl):
+    """The oracle as it stands, single thread, on the whole headline message (about 10-15 s of CPU work)."""
+    import oracle
+    n = wl["n"]
+    o = oracle.make_opts(chunk_elems=wl["chunk"])
+    t0 = time.perf_counter()
+    s, res, rc = oracle.compress(wl["x"], wl["eb"], o)
+    t1 = time.perf_counter()
+    y, _, rc2 = oracle.decompress(s, n, wl["eb"])
+    t2 = time.perf_counter()
+    sp, _, _ = oracle.compress(wl["peer"], wl["eb"], o)
+    t3 = time.perf_counter()
+    r, _, rc3 = oracle.reduce_frames(s, sp, n, wl["eb"], o)
+    t4 = time.perf_counter()
+    assert rc == 0 and rc2 == 0 and rc3 == 0
+    step = (t1 - t0) + (t2 - t1) + (t4 - t3)
+    gb = 4.0 * n / 1e9
+    return dict(value=3 * gb / step, unit="GB/s", cores=1, kind="oracle",
+                sample="whole %s message (%d elements): compress %.2fs, decompress %.2fs, reduce %.2fs" %
+                       (wl["name"], n, t1 - t0, t2 - t1, t4 - t3),
+                compress_GBps=gb / (t1 - t0), decompress_GBps=gb / (t2 - t1), reduce_GBps=gb / (t4 - t3)), s
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rotate", type=int, default=3, help="number of distinct input copies cycled through")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py measures the one-GPU hot path only: run with --gpus 1 "
+                         "(no collectives or second GPU are part of this build)")
+
+    import numpy as np
+    import torch
+    from paper_2605_12396_amd import binding as nz
+
+    nz.lib()
+    dev = torch.device("cuda:0")
+    wl = make_workload(args.workload)
+    n, eb = wl["n"], wl["eb"]
+    opts = nz.make_opts(chunk_elems=wl["chunk"])
+    sess = nz.Session(n, opts, dev, reduce=True)
+
+    xs = [torch.from_numpy(wl["x"]).to(dev) for _ in range(max(1, args.rotate))]
+    xpeer = torch.from_numpy(wl["peer"]).to(dev)
+    outs = [sess.new_stream_buffer() for _ in range(len(xs))]
+    peer_stream = sess.new_stream_buffer()
+    red_out = sess.new_stream_buffer()
+    y = torch.empty(n, dtype=torch.float32, device=dev)
+
+    rc, _ = sess.compress(xpeer, eb, out=peer_stream)
+    r = sess.result()
+    assert rc == 0 and r["status"] == 0
+    peer_bytes = r["bytes"]
+    rc, _ = sess.compress(xs[0], eb, out=outs[0])
+    r0 = sess.result()
+    assert rc == 0 and r0["status"] == 0
+    stream_bytes = r0["bytes"]
+
+    def step(i):
+        k = i % len(xs)
+        a = sess.compress(xs[k], eb, out=outs[k])[0]
+        b = sess.decompress(outs[k], stream_bytes, n, eb, out=y)[0]
+        c = sess.reduce(outs[k], stream_bytes, peer_stream, peer_bytes, n, eb, out=red_out)[0]
+        return a | b | c
+
+    for i in range(args.warmup):
+        assert step(i) == 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    rr = sess.result()
+    assert rr["status"] == 0
+    reduce_bytes = rr["bytes"]
+
+    # per-stage and per-kernel times from HIP events the library records on its stream
+    names = {"compress": ["init", "stats", "codebook", "encode"], "decompress": ["init", "decode"],
+             "reduce": ["init", "decode_add", "codebook", "encode"]}
+    acc = {k: [0.0] * len(v) for k, v in names.items()}
+    reps = max(5, min(args.steps, 20))
+    with nz.KernelTrace(8) as tr:
+        for i in range(reps):
+            k = i % len(xs)
+            sess.compress(xs[k], eb, out=outs[k])
+            for j, t in enumerate(tr.kernel_ms()):
+                acc["compress"][j] += t
+            sess.decompress(outs[k], stream_bytes, n, eb, out=y)
+            for j, t in enumerate(tr.kernel_ms()):
+                acc["decompress"][j] += t
+            sess.reduce(outs[k], stream_bytes, peer_stream, peer_bytes, n, eb, out=red_out)
+            for j, t in enumerate(tr.kernel_ms()):
+                acc["reduce"][j] += t
+    kern = {st: {nm: acc[st][j] / reps for j, nm in enumerate(names[st])} for st in names}
+    stage_ms = {st: sum(kern[st].values()) for st in names}
+    gb = 4.0 * n / 1e9
+    cr = 4.0 * n / stream_bytes
+    # algorithmic bytes each kernel must move per launch (bytes per element x n): see the design doc
+    alg = {("compress", "stats"): 4.0 * n, ("compress", "encode"): 4.0 * n + stream_bytes,
+           ("decompress", "decode"): 4.0 * n + stream_bytes,
+           ("reduce", "decode_add"): stream_bytes + peer_bytes + 4.0 * n,
+           ("reduce", "encode"): 4.0 * n + reduce_bytes}
+    dom = max(alg, key=lambda k: kern[k[0]][k[1]])
+    dom_ms = kern[dom[0]][dom[1]]
+    achieved = alg[dom] / (dom_ms * 1e-3) / 1e9
+    roofline = dict(bound="hbm", kernel="%s/%s" % dom, achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s",
+                    frac=achieved / HBM_PEAK_GBPS, traffic=None, kernel_ms=dom_ms,
+                    algorithmic_bytes=alg[dom])
+
+    out = dict(metric="compress+decompress+fused-reduce throughput on fp32 input bytes", value=3 * gb / (ms_per_step * 1e-3),
+               unit="GB/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step,
+               higher_is_better=True, scaling="weak", vs_baseline=None, dtype="f32+i32", data="synthetic",
+               config=dict(workload=wl["desc"], n_elems=n, chunk_elems=wl["chunk"], alphabet=256, eb=eb),
+               stages=dict(compress_GBps=gb / (stage_ms["compress"] * 1e-3),
+                           decompress_GBps=gb / (stage_ms["decompress"] * 1e-3),
+                           reduce_GBps=gb / (stage_ms["reduce"] * 1e-3),
+                           compress_frac_hbm=gb / (stage_ms["compress"] * 1e-3) / HBM_PEAK_GBPS,
+                           decompress_frac_hbm=gb / (stage_ms["decompress"] * 1e-3) / HBM_PEAK_GBPS,
+                           reduce_frac_hbm=gb / (stage_ms["reduce"] * 1e-3) / HBM_PEAK_GBPS,
+                           compression_ratio=cr, stream_bytes=stream_bytes, reduce_stream_bytes=reduce_bytes,
+                           frames=dict(raw=r0["n_raw"], fixed=r0["n_fixed"], huffman=r0["n_huff"]),
+                           kernel_ms=kern),
+               roofline=roofline)
+    if not args.no_cpu_baseline:
+        base, ref_stream = cpu_baseline(wl)
+        out["cpu_baseline"] = base
+        got = outs[0][:stream_bytes].cpu().numpy()
+        out["bytes_match_oracle"] = bool(got.size == ref_stream.size and (got == ref_stream).all())
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

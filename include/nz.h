@@ -121,6 +121,17 @@ nz_status nz_reduce_frames(const void* d_a, size_t a_bytes, const void* d_b, siz
                            size_t out_cap, size_t n, float eb, nz_result* d_res, const nz_opts* opts,
                            void* d_ws, size_t ws_bytes, void* stream);
 
+/*
+ * Profiling aid for benchmarks (not part of the paper's path).  While armed for the calling thread, every
+ * entry point above records events[0] on its stream before its first kernel and events[i] after its i-th
+ * kernel, up to `count` events (hipEvent_t handles created by the caller, host array).  nz_trace_recorded()
+ * returns how many events the last call recorded.  nz_trace_events(NULL, 0) disarms.  Kernel order:
+ * compress = init, stats, codebook, encode; decompress = init, decode; reduce = init, decode+add, codebook,
+ * encode.
+ */
+void   nz_trace_events(void** events, size_t count);
+size_t nz_trace_recorded(void);
+
 /* Library version (format version in the high 16 bits, build in the low 16). */
 uint32_t nz_version(void);
 

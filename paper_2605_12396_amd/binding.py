@@ -51,6 +51,9 @@ def lib():
         L.nz_decompress.restype = C.c_int
         L.nz_reduce_frames.argtypes = [vp, sz, vp, sz, vp, sz, sz, f32, vp, po, vp, sz, vp]
         L.nz_reduce_frames.restype = C.c_int
+        L.nz_trace_events.argtypes = [C.POINTER(C.c_void_p), sz]
+        L.nz_trace_events.restype = None
+        L.nz_trace_recorded.restype = sz
         _lib = L
     return _lib
 
@@ -137,3 +140,27 @@ class Session:
 
     def result(self):
         return read_result(self.res)
+
+
+class KernelTrace:
+    """Per-kernel timing of nz_* calls with HIP events recorded by the library on the call's stream."""
+
+    def __init__(self, max_events=8):
+        self.events = [torch.cuda.Event(enable_timing=True) for _ in range(max_events)]
+        for e in self.events:
+            e.record()                      # torch creates the hipEvent_t lazily at the first record
+        torch.cuda.synchronize()
+        self.handles = (C.c_void_p * max_events)(*[C.c_void_p(e.cuda_event) for e in self.events])
+
+    def __enter__(self):
+        lib().nz_trace_events(self.handles, len(self.events))
+        return self
+
+    def __exit__(self, *exc):
+        lib().nz_trace_events(None, 0)
+
+    def kernel_ms(self):
+        """Durations between consecutive recorded events of the last call (synchronises)."""
+        k = int(lib().nz_trace_recorded())
+        torch.cuda.synchronize()
+        return [self.events[i].elapsed_time(self.events[i + 1]) for i in range(k - 1)]

@@ -49,6 +49,18 @@ uint64_t frame_bound(uint64_t nf, const Opts& o) {
     return pad16h(kHdrBytes + pay);
 }
 
+// Optional per-kernel event trace (benchmark aid), per host thread.
+thread_local void** t_events = nullptr;
+thread_local size_t t_event_cap = 0, t_event_n = 0;
+
+inline void trace_reset() { t_event_n = 0; }
+inline void trace_mark(hipStream_t st) {
+    if (t_events && t_event_n < t_event_cap) {
+        (void)hipEventRecord(reinterpret_cast<hipEvent_t>(t_events[t_event_n]), st);
+        t_event_n++;
+    }
+}
+
 constexpr uint64_t kMaxElems = 1ull << 38;      // keeps every grid below 2^31 workgroups for frames >= 8192 elements
 
 bool geometry_ok(size_t n, const Opts& o) {
@@ -63,6 +75,9 @@ bool geometry_ok(size_t n, const Opts& o) {
 extern "C" {
 
 uint32_t nz_version(void) { return (1u << 16) | 1u; }
+
+void nz_trace_events(void** events, size_t count) { t_events = events; t_event_cap = events ? count : 0; t_event_n = 0; }
+size_t nz_trace_recorded(void) { return t_event_n; }
 
 size_t nz_compress_bound(size_t n, const nz_opts* opts) {
     Opts o;
@@ -105,10 +120,15 @@ nz_status nz_compress(const float* d_in, size_t n, float eb, void* d_out, size_t
     A.force_codec = o.force; A.min_gain_permil = o.gain; A.huff_min_bytes = o.huff_min;
     A.eb = eb; A.step = step; A.inv_step = inv; A.step_bits = bits_of(step);
     A.out = reinterpret_cast<uint8_t*>(d_out); A.out_cap = out_cap; A.ws = ws; A.L = L; A.res = d_res;
+    trace_reset(); trace_mark(st);
     if (launch_init(ws + L.ctrl, L.zero_end - L.ctrl, d_res, nfr, NZ_OK, st) != hipSuccess) return NZ_ERR_HIP;
+    trace_mark(st);
     if (launch_stats(A, st) != hipSuccess) return NZ_ERR_HIP;
+    trace_mark(st);
     if (launch_codebook(A, st) != hipSuccess) return NZ_ERR_HIP;
+    trace_mark(st);
     if (launch_encode(A, false, st) != hipSuccess) return NZ_ERR_HIP;
+    trace_mark(st);
     return NZ_OK;
 }
 
@@ -126,8 +146,11 @@ nz_status nz_decompress(const void* d_stream, size_t stream_bytes, float* d_out,
     A.out = d_out; A.n = n; A.chunk = o.chunk; A.n_frames = nfr; A.K = o.K;
     A.dbpf = (o.chunk + kDecBlock - 1) / kDecBlock;
     A.step = step; A.step_bits = bits_of(step); A.ws = nullptr; A.L = WsLayout(); A.res = d_res;
+    trace_reset(); trace_mark(st);
     if (launch_init(nullptr, 0, d_res, nfr, NZ_OK, st) != hipSuccess) return NZ_ERR_HIP;
+    trace_mark(st);
     if (launch_decode(A, false, st) != hipSuccess) return NZ_ERR_HIP;
+    trace_mark(st);
     return NZ_OK;
 }
 
@@ -161,10 +184,15 @@ nz_status nz_reduce_frames(const void* d_a, size_t a_bytes, const void* d_b, siz
     A.force_codec = o.force; A.min_gain_permil = o.gain; A.huff_min_bytes = o.huff_min;
     A.eb = eb; A.step = step; A.inv_step = inv; A.step_bits = bits_of(step);
     A.out = reinterpret_cast<uint8_t*>(d_out); A.out_cap = out_cap; A.ws = ws; A.L = L; A.res = d_res;
+    trace_reset(); trace_mark(st);
     if (launch_init(ws + L.ctrl, L.zero_end - L.ctrl, d_res, nfr, NZ_OK, st) != hipSuccess) return NZ_ERR_HIP;
+    trace_mark(st);
     if (launch_decode(D, true, st) != hipSuccess) return NZ_ERR_HIP;
+    trace_mark(st);
     if (launch_codebook(A, st) != hipSuccess) return NZ_ERR_HIP;
+    trace_mark(st);
     if (launch_encode(A, true, st) != hipSuccess) return NZ_ERR_HIP;
+    trace_mark(st);
     return NZ_OK;
 }
 
