@@ -78,6 +78,7 @@ def main():
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rotate", type=int, default=3, help="number of distinct input copies cycled through")
+    ap.add_argument("--only", default="", help="profiling aid: time only this stage (compress|decompress|reduce)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures the one-GPU hot path only: run with --gpus 1 "
@@ -110,11 +111,18 @@ def main():
     assert rc == 0 and r0["status"] == 0
     stream_bytes = r0["bytes"]
 
+    for k in range(1, len(xs)):
+        sess.compress(xs[k], eb, out=outs[k])
+
     def step(i):
         k = i % len(xs)
-        a = sess.compress(xs[k], eb, out=outs[k])[0]
-        b = sess.decompress(outs[k], stream_bytes, n, eb, out=y)[0]
-        c = sess.reduce(outs[k], stream_bytes, peer_stream, peer_bytes, n, eb, out=red_out)[0]
+        a = b = c = 0
+        if args.only in ("", "compress"):
+            a = sess.compress(xs[k], eb, out=outs[k])[0]
+        if args.only in ("", "decompress"):
+            b = sess.decompress(outs[k], stream_bytes, n, eb, out=y)[0]
+        if args.only in ("", "reduce"):
+            c = sess.reduce(outs[k], stream_bytes, peer_stream, peer_bytes, n, eb, out=red_out)[0]
         return a | b | c
 
     for i in range(args.warmup):
@@ -126,6 +134,9 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    if args.only:
+        print(json.dumps(dict(only=args.only, ms_per_step=ms_per_step, GBps=4.0 * n / 1e9 / (ms_per_step * 1e-3))))
+        return
     rr = sess.result()
     assert rr["status"] == 0
     reduce_bytes = rr["bytes"]

@@ -153,66 +153,167 @@ __device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t fra
     V.words = reinterpret_cast<const uint32_t*>(pay + tables); V.nwords = (uint32_t)((payload - tables) / 4);
 }
 
-// Per-thread sequential reader of one segment.
+// Per-thread sequential LSB-first bit reader over 32-bit words, with the next word prefetched one refill
+// ahead so that the global-load latency is off the symbol-to-symbol dependency chain.
 struct Reader {
-    uint32_t kind, w;
     const uint32_t* words; uint32_t nwords, widx;
-    uint64_t buf; uint32_t navail, consumed, bad;
+    uint64_t buf; uint32_t navail, pre, consumed, bad, w;
     const DecTables* T;
 
     __device__ inline uint32_t ldw(uint32_t i) const { return i < nwords ? words[i] : 0u; }
     __device__ inline void init(const FrameView& V, const DecTables* tables, uint64_t bitpos, uint32_t elem0) {
-        kind = V.kind; w = V.w; words = V.words; nwords = V.nwords; T = tables; consumed = 0; bad = 0;
-        buf = 0; navail = 0; widx = 0;
-        if (kind == KIND_RAW) { widx = elem0; return; }
-        if (kind == KIND_ZERO) return;
+        words = V.words; nwords = V.nwords; T = tables; consumed = 0; bad = 0; w = V.w;
+        buf = 0; navail = 0; widx = 0; pre = 0;
+        if (V.kind == KIND_RAW) { widx = elem0; return; }
+        if (V.kind == KIND_ZERO) { nwords = 0; w = 0; }
         widx = (uint32_t)(bitpos >> 5);
         const uint32_t sh = (uint32_t)(bitpos & 31u);
         buf = ((uint64_t)ldw(widx) | ((uint64_t)ldw(widx + 1) << 32)) >> sh;
         navail = 64u - sh;
-        widx += 2;
+        pre = ldw(widx + 2);
+        widx += 3;
     }
     __device__ inline void refill() {
-        if (navail <= 32u) { buf |= (uint64_t)ldw(widx++) << navail; navail += 32u; }
+        if (navail <= 32u) { buf |= (uint64_t)pre << navail; navail += 32u; pre = ldw(widx); widx++; }
     }
     __device__ inline uint32_t take(uint32_t nb) {
-        const uint32_t v = (uint32_t)(buf & ((1ull << nb) - 1ull));
+        const uint32_t v = (uint32_t)buf & (uint32_t)((1ull << nb) - 1ull);
         buf >>= nb; navail -= nb; consumed += nb;
         return v;
     }
-    // Next element: returns the zigzag code (coded frames) or the fp32 bit pattern (RAW frames).
-    __device__ inline uint32_t next() {
-        if (kind == KIND_HUFF) {
-            refill();
-            uint32_t e = T->tab[(uint32_t)buf & ((1u << kPrimaryBits) - 1u)];
-            uint32_t L = e >> 10, sy = e & 1023u;
-            if (L == 0) {                                     // long or unassigned code: canonical search
-                uint32_t code = 0;
-                for (uint32_t l = 1; l <= kMaxLen; l++) {
-                    code = (code << 1) | ((uint32_t)(buf >> (l - 1)) & 1u);
-                    const uint32_t d = code - T->first[l];
-                    if (d < T->cnt[l]) { sy = T->sorted[T->idx0[l] + d]; L = l; break; }
-                }
-                if (L == 0) { bad = 1; L = 1; sy = 1; }
+    __device__ inline uint32_t next_huff() {
+        refill();
+        const uint32_t e = T->tab[(uint32_t)buf & ((1u << kPrimaryBits) - 1u)];
+        uint32_t L = e >> 10, sy = e & 1023u;
+        if (__builtin_expect(L == 0, 0)) {                    // long or unassigned code: canonical search
+            uint32_t code = 0;
+            for (uint32_t l = 1; l <= kMaxLen; l++) {
+                code = (code << 1) | ((uint32_t)(buf >> (l - 1)) & 1u);
+                const uint32_t d = code - T->first[l];
+                if (d < T->cnt[l]) { sy = T->sorted[T->idx0[l] + d]; L = l; break; }
             }
-            take(L);
-            if (sy == 0) { refill(); return take(32); }
-            return sy - 1u;
+            if (L == 0) { bad = 1; L = 1; sy = 1; }
         }
-        if (kind == KIND_FIXED) { refill(); return take(w); }
-        if (kind == KIND_RAW) return words[widx++];
-        return 0u;
+        buf >>= L; navail -= L; consumed += L;
+        if (__builtin_expect(sy == 0, 0)) { refill(); return take(32); }
+        return sy - 1u;
     }
+    __device__ inline uint32_t next_fixed() { refill(); return take(w); }
+    __device__ inline uint32_t next_raw() { return words[widx++]; }
 };
+
+template <int KIND>
+__device__ inline uint32_t rd_next(Reader& r) {
+    if (KIND == KIND_HUFF) return r.next_huff();
+    if (KIND == KIND_FIXED) return r.next_fixed();
+    return r.next_raw();
+}
+
+constexpr uint32_t kTileR = 16;                      // symbols per thread between two coalesced output phases
+constexpr uint32_t kTileStride = kTileR + 1;         // odd row stride: conflict-free column writes
+
+struct DecShared {
+    union { uint32_t tile[kDecThreads * kTileStride]; BuildScratch build; } u;
+    uint64_t wsum[4];
+    uint32_t zmax, flags;
+};
+
+struct SegCtx {
+    uint32_t tid, lane, first_seg, nf, cntseg;
+    uint64_t f0;
+    bool vec_ok;
+};
+
+// One 256-symbol segment per thread, kTileR symbols at a time into an LDS tile, then the workgroup writes the
+// tile out with 16-byte stores (kTileR/4 lanes cover one thread's run, so every store instruction fills whole
+// 64-byte runs).  MODE 0: dequantize to fp32.  MODE 1: Q = qa + qb, histogram + zmax of Q, stage Q.
+template <int MODE, int KA, int KB>
+__device__ inline void run_segments(const DecodeArgs& A, const SegCtx& C, Reader& ra, Reader& rb, DecShared* S,
+                                    uint32_t* s_h, uint32_t ncs, bool out_raw, uint32_t& overflow) {
+    const uint32_t tid = C.tid;
+    const uint32_t K = A.K;
+    const uint32_t copy = C.lane & ((1u << ncs) - 1u);
+    uint32_t* tile = S->u.tile;
+    uint32_t zmax = 0;
+    constexpr uint32_t LPR = kTileR / 4;             // lanes per row in the output phase
+    for (uint32_t r0 = 0; r0 < kSeg; r0 += kTileR) {
+        if (r0 < C.cntseg) {
+            const uint32_t nr = (C.cntseg - r0 < kTileR) ? (C.cntseg - r0) : kTileR;
+            uint32_t* row = tile + tid * kTileStride;
+            for (uint32_t r = 0; r < nr; r++) {
+                uint32_t v;
+                if (MODE == 0) {
+                    v = rd_next<KA>(ra);
+                } else {
+                    const uint32_t ta = rd_next<KA>(ra), tb = rd_next<KB>(rb);
+                    if (KA == KIND_RAW || KB == KIND_RAW) {
+#pragma clang fp contract(off)
+                        const float fa = (KA == KIND_RAW) ? __uint_as_float(ta) : dequantize1(unzigzag(ta), A.step);
+                        const float fb = (KB == KIND_RAW) ? __uint_as_float(tb) : dequantize1(unzigzag(tb), A.step);
+                        const float sum = fa + fb;
+                        v = (sum != sum) ? kCanonNaN : __float_as_uint(sum);
+                    } else {
+                        const int32_t qa = unzigzag(ta), qb = unzigzag(tb);
+                        v = (uint32_t)qa + (uint32_t)qb;
+                        if (__builtin_expect(((ta | tb) >> 30) != 0, 0)) {       // only then can |qa+qb| pass 2^30
+                            const int64_t Q = (int64_t)qa + (int64_t)qb;
+                            if (Q > (int64_t)kQSumMax || Q < -(int64_t)kQSumMax) overflow = 1;
+                        }
+                    }
+                }
+                row[r] = v;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (uint32_t k = 0; k < LPR; k++) {
+            const uint32_t g = tid + kDecThreads * k;
+            const uint32_t rw = g / LPR, c = (g % LPR) * 4;
+            const uint32_t e = (C.first_seg + rw) * kSeg + r0 + c;              // element index in the frame
+            if (e < C.nf) {
+                const uint32_t m = (C.nf - e < 4) ? (C.nf - e) : 4u;
+                uint32_t t[4];
+#pragma unroll
+                for (uint32_t j = 0; j < 4; j++) t[j] = tile[rw * kTileStride + c + j];
+                if (MODE == 0) {
+                    float v[4];
+#pragma unroll
+                    for (uint32_t j = 0; j < 4; j++)
+                        v[j] = (KA == KIND_RAW) ? __uint_as_float(t[j]) : dequantize1(unzigzag(t[j]), A.step);
+                    float* dst = A.out + C.f0 + e;
+                    if (C.vec_ok && m == 4) *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+                    else for (uint32_t j = 0; j < m; j++) dst[j] = v[j];
+                } else {
+                    if (!out_raw) {
+#pragma unroll
+                        for (uint32_t j = 0; j < 4; j++) {
+                            if (j < m) {
+                                const uint32_t z = zigzag((int32_t)t[j]);
+                                zmax = z > zmax ? z : zmax;
+                                atomicAdd(&s_h[(sym_of(z, K) << ncs) + copy], 1u);
+                            }
+                        }
+                    }
+                    uint32_t* dst = reinterpret_cast<uint32_t*>(A.ws + A.L.codes) + C.f0 + e;
+                    if (C.vec_ok && m == 4) *reinterpret_cast<uint4*>(dst) = make_uint4(t[0], t[1], t[2], t[3]);
+                    else for (uint32_t j = 0; j < m; j++) dst[j] = t[j];
+                }
+            }
+        }
+        __syncthreads();
+    }
+    if (MODE == 1) {
+        zmax = wave_max(zmax);
+        if (C.lane == 0) atomicMax(&S->zmax, zmax);
+    }
+}
 
 // MODE 0: decompress A into fp32.  MODE 1: reduce front end, Q = qa + qb into the workspace + statistics.
 template <int MODE>
 __global__ __launch_bounds__(kDecThreads) void k_decode(DecodeArgs A) {
-    __shared__ DecTables s_ta;
-    __shared__ DecTables s_tb[1];             // second operand (reduce)
-    __shared__ BuildScratch s_build;
-    __shared__ uint32_t s_h[MODE == 1 ? 4096 : 1];
-    __shared__ uint32_t s_zmax;
+    __shared__ DecTables s_t[MODE == 1 ? 2 : 1];
+    __shared__ DecShared S;
+    __shared__ uint32_t s_h[MODE == 1 ? 2048 : 1];
 
     const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const uint32_t frame = blockIdx.x / A.dbpf, db = blockIdx.x % A.dbpf;
@@ -243,8 +344,8 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(DecodeArgs A) {
     va.status = ST_OK; va.kind = KIND_ZERO; va.w = 0; va.words = nullptr; va.nwords = 0; va.segt = nullptr; va.seg_prefix = 0;
     vb = va;
     if (st_a == ST_OK && (MODE == 0 || st_b == ST_OK)) {
-        open_frame<kDecThreads>(A.a, total_a, frame, nf, first_seg, A, &s_ta, &s_build, va);
-        if (MODE == 1) open_frame<kDecThreads>(A.b, total_b, frame, nf, first_seg, A, &s_tb[0], &s_build, vb);
+        open_frame<kDecThreads>(A.a, total_a, frame, nf, first_seg, A, &s_t[0], &S.u.build, va);
+        if (MODE == 1) open_frame<kDecThreads>(A.b, total_b, frame, nf, first_seg, A, &s_t[MODE == 1 ? 1 : 0], &S.u.build, vb);
         if (tid == 0) {
             if (va.status) atomicMax(&res->status, va.status);
             if (MODE == 1 && vb.status) atomicMax(&res->status, vb.status);
@@ -254,6 +355,33 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(DecodeArgs A) {
         if (MODE == 1 && (va.status || vb.status)) { va.kind = KIND_ZERO; vb.kind = KIND_ZERO; }
     }
     if (MODE == 0 && va.status) return;                                 // rejected frame: its output range is left alone
+    const bool vec_ok = ((f0 & 3u) == 0);
+
+    // ---- MODE 0, RAW / FIXEDLEN frames: element-parallel, coalesced on both sides ----
+    if (MODE == 0 && va.kind != KIND_HUFF) {
+        const uint32_t cnt = (nf - blk0 < kDecBlock) ? (nf - blk0) : kDecBlock;
+        const uint32_t w = va.w;
+        const uint32_t mask = (w >= 32u) ? 0xFFFFFFFFu : ((1u << w) - 1u);
+        for (uint32_t i = tid * 4; i < cnt; i += kDecThreads * 4) {
+            const uint32_t e = blk0 + i;
+            const uint32_t m = (cnt - i < 4) ? (cnt - i) : 4u;
+            float v[4] = { 0.f, 0.f, 0.f, 0.f };
+            for (uint32_t j = 0; j < m; j++) {
+                if (va.kind == KIND_RAW) v[j] = __uint_as_float(va.words[e + j]);
+                else {
+                    const uint64_t bp = (uint64_t)(e + j) * w;
+                    const uint32_t wi = (uint32_t)(bp >> 5), sh = (uint32_t)(bp & 31u);
+                    const uint32_t lo = wi < va.nwords ? va.words[wi] : 0u, hi = (wi + 1 < va.nwords) ? va.words[wi + 1] : 0u;
+                    const uint32_t z = (uint32_t)((((uint64_t)hi << 32) | lo) >> sh) & mask;
+                    v[j] = dequantize1(unzigzag(z), A.step);
+                }
+            }
+            float* dst = A.out + f0 + e;
+            if (vec_ok && m == 4) *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+            else for (uint32_t j = 0; j < m; j++) dst[j] = v[j];
+        }
+        return;
+    }
 
     // bit offset of my segment: prefix of the segment table (HUFFMAN) or closed form (FIXEDLEN)
     uint64_t bit_a = 0, bit_b = 0;
@@ -267,11 +395,11 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(DecodeArgs A) {
         uint64_t incl = v;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) { uint64_t t = __shfl_up(incl, d, 64); if ((int)lane >= d) incl += t; }
-        __shared__ uint64_t s_wsum[4];
-        if (lane == 63) s_wsum[wave] = incl;
+        if (lane == 63) S.wsum[wave] = incl;
+        if (tid == 0) { S.zmax = 0; S.flags = 0; }
         __syncthreads();
         uint64_t excl = incl - v;
-        for (uint32_t w = 0; w < wave; w++) excl += s_wsum[w];
+        for (uint32_t w = 0; w < wave; w++) excl += S.wsum[w];
         bit_a = va.seg_prefix + (excl & 0xFFFFFFFFull);
         bit_b = vb.seg_prefix + (excl >> 32);
         if (va.kind == KIND_FIXED) bit_a = (uint64_t)e0 * va.w;
@@ -279,74 +407,43 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(DecodeArgs A) {
     }
 
     Reader ra, rb;
-    ra.init(va, &s_ta, bit_a, e0);
-    if (MODE == 1) rb.init(vb, &s_tb[0], bit_b, e0);
+    ra.init(va, &s_t[0], bit_a, e0);
+    rb.init(vb, &s_t[MODE == 1 ? 1 : 0], bit_b, e0);
+    SegCtx C;
+    C.tid = tid; C.lane = lane; C.first_seg = first_seg; C.nf = nf; C.cntseg = cntseg; C.f0 = f0; C.vec_ok = vec_ok;
+    uint32_t overflow = 0;
 
     if (MODE == 0) {
-        float* dst = A.out + f0 + e0;
-        const bool vec_ok = ((f0 & 3u) == 0);
-        for (uint32_t i = 0; i < cntseg; i += 4) {
-            float v[4];
-            const uint32_t m = (cntseg - i < 4) ? (cntseg - i) : 4u;
-            for (uint32_t j = 0; j < 4; j++) {
-                v[j] = 0.f;
-                if (j < m) {
-                    const uint32_t t = ra.next();
-                    v[j] = (ra.kind == KIND_RAW) ? __uint_as_float(t) : dequantize1(unzigzag(t), A.step);
-                }
-            }
-            if (vec_ok && m == 4) *reinterpret_cast<float4*>(dst + i) = make_float4(v[0], v[1], v[2], v[3]);
-            else for (uint32_t j = 0; j < m; j++) dst[i + j] = v[j];
-        }
-        if (seg_valid && ra.kind == KIND_HUFF && (ra.bad || ra.consumed != seglen_a)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
+        run_segments<0, KIND_HUFF, KIND_FIXED>(A, C, ra, rb, &S, s_h, 0, false, overflow);
+        if (seg_valid && (ra.bad || ra.consumed != seglen_a)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
         return;
     }
 
     // ---- MODE 1: sum of codes, statistics of the sum ----
     const uint32_t K = A.K;
     uint32_t ncs = 0;
-    while ((K << (ncs + 1)) <= 4096u && ncs < 5) ncs++;
-    const uint32_t copy = lane & ((1u << ncs) - 1u);
+    while ((K << (ncs + 1)) <= 2048u && ncs < 5) ncs++;
     for (uint32_t i = tid; i < (K << ncs); i += kDecThreads) s_h[i] = 0;
-    if (tid == 0) s_zmax = 0;
     __syncthreads();
-    const bool out_raw = (ra.kind == KIND_RAW) || (rb.kind == KIND_RAW);      // uniform over the frame
-    uint32_t* dstq = reinterpret_cast<uint32_t*>(A.ws + A.L.codes) + f0 + e0;
-    const bool vec_ok = ((f0 & 3u) == 0);
-    uint32_t zmax = 0, overflow = 0;
-    for (uint32_t i = 0; i < cntseg; i += 4) {
-        uint32_t o[4] = { 0, 0, 0, 0 };
-        const uint32_t m = (cntseg - i < 4) ? (cntseg - i) : 4u;
-        for (uint32_t j = 0; j < 4; j++) {
-            if (j < m) {
-                const uint32_t ta = ra.next(), tb = rb.next();
-                if (out_raw) {
-#pragma clang fp contract(off)
-                    const float fa = (ra.kind == KIND_RAW) ? __uint_as_float(ta) : dequantize1(unzigzag(ta), A.step);
-                    const float fb = (rb.kind == KIND_RAW) ? __uint_as_float(tb) : dequantize1(unzigzag(tb), A.step);
-                    const float sum = fa + fb;
-                    o[j] = (sum != sum) ? kCanonNaN : __float_as_uint(sum);
-                } else {
-                    const int64_t Q = (int64_t)unzigzag(ta) + (int64_t)unzigzag(tb);
-                    if (Q > (int64_t)kQSumMax || Q < -(int64_t)kQSumMax) overflow = 1;
-                    const int32_t qs = (int32_t)Q;
-                    const uint32_t z = zigzag(qs);
-                    zmax = z > zmax ? z : zmax;
-                    atomicAdd(&s_h[(sym_of(z, K) << ncs) + copy], 1u);
-                    o[j] = (uint32_t)qs;
-                }
-            }
-        }
-        if (vec_ok && m == 4) *reinterpret_cast<uint4*>(dstq + i) = make_uint4(o[0], o[1], o[2], o[3]);
-        else for (uint32_t j = 0; j < m; j++) dstq[i + j] = o[j];
+    const bool out_raw = (va.kind == KIND_RAW) || (vb.kind == KIND_RAW);      // uniform over the frame
+    const uint32_t ka = (va.kind == KIND_ZERO) ? (uint32_t)KIND_FIXED : va.kind;
+    const uint32_t kb = (vb.kind == KIND_ZERO) ? (uint32_t)KIND_FIXED : vb.kind;
+    switch (ka * 3 + kb) {
+        case KIND_RAW * 3 + KIND_RAW:     run_segments<1, KIND_RAW, KIND_RAW>(A, C, ra, rb, &S, s_h, ncs, out_raw, overflow); break;
+        case KIND_RAW * 3 + KIND_FIXED:   run_segments<1, KIND_RAW, KIND_FIXED>(A, C, ra, rb, &S, s_h, ncs, out_raw, overflow); break;
+        case KIND_RAW * 3 + KIND_HUFF:    run_segments<1, KIND_RAW, KIND_HUFF>(A, C, ra, rb, &S, s_h, ncs, out_raw, overflow); break;
+        case KIND_FIXED * 3 + KIND_RAW:   run_segments<1, KIND_FIXED, KIND_RAW>(A, C, ra, rb, &S, s_h, ncs, out_raw, overflow); break;
+        case KIND_FIXED * 3 + KIND_FIXED: run_segments<1, KIND_FIXED, KIND_FIXED>(A, C, ra, rb, &S, s_h, ncs, out_raw, overflow); break;
+        case KIND_FIXED * 3 + KIND_HUFF:  run_segments<1, KIND_FIXED, KIND_HUFF>(A, C, ra, rb, &S, s_h, ncs, out_raw, overflow); break;
+        case KIND_HUFF * 3 + KIND_RAW:    run_segments<1, KIND_HUFF, KIND_RAW>(A, C, ra, rb, &S, s_h, ncs, out_raw, overflow); break;
+        case KIND_HUFF * 3 + KIND_FIXED:  run_segments<1, KIND_HUFF, KIND_FIXED>(A, C, ra, rb, &S, s_h, ncs, out_raw, overflow); break;
+        default:                          run_segments<1, KIND_HUFF, KIND_HUFF>(A, C, ra, rb, &S, s_h, ncs, out_raw, overflow); break;
     }
     if (seg_valid) {
-        if (ra.kind == KIND_HUFF && (ra.bad || ra.consumed != seglen_a)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
-        if (rb.kind == KIND_HUFF && (rb.bad || rb.consumed != seglen_b)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
+        if (va.kind == KIND_HUFF && (ra.bad || ra.consumed != seglen_a)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
+        if (vb.kind == KIND_HUFF && (rb.bad || rb.consumed != seglen_b)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
         if (overflow) atomicMax(&res->status, (uint32_t)ST_RANGE);
     }
-    zmax = wave_max(zmax);
-    if (lane == 0) atomicMax(&s_zmax, zmax);
     __syncthreads();
     uint32_t* ph = reinterpret_cast<uint32_t*>(A.ws + A.L.phist) + (size_t)blockIdx.x * kMaxK;
     for (uint32_t sy = tid; sy < K; sy += kDecThreads) {
@@ -354,7 +451,7 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(DecodeArgs A) {
         for (uint32_t c = 0; c < (1u << ncs); c++) t += s_h[(sy << ncs) + c];
         ph[sy] = t;
     }
-    if (tid == 0) reinterpret_cast<uint2*>(A.ws + A.L.pmeta)[blockIdx.x] = make_uint2(s_zmax, out_raw ? 1u : 0u);
+    if (tid == 0) reinterpret_cast<uint2*>(A.ws + A.L.pmeta)[blockIdx.x] = make_uint2(S.zmax, out_raw ? 1u : 0u);
 }
 
 hipError_t launch_decode(const DecodeArgs& A, bool reduce, hipStream_t st) {
