@@ -10,7 +10,7 @@
 
 namespace nz {
 
-constexpr uint32_t kPrimaryBits = 11;         // first-level decode table: 2048 entries of sym | len<<10
+constexpr uint32_t kPrimaryBits = 11;         // first-level decode table: 2048 entries of zigzag code | len<<10 (+flags)
 enum : uint32_t { KIND_RAW = 0, KIND_FIXED = 1, KIND_HUFF = 2, KIND_ZERO = 3 };
 
 __device__ inline uint64_t pad4d(uint64_t v) { return (v + 3u) & ~(uint64_t)3u; }
@@ -36,10 +36,16 @@ __device__ inline uint32_t check_stream(const uint8_t* s, uint64_t bytes, const 
 }
 
 // Shared memory of one operand's decoder.
+constexpr uint32_t kSubBits = 6;               // second-level tables resolve codes of 12..17 bits
+constexpr uint32_t kMaxSub = 32;               // at most this many second-level tables (the rest: canonical search)
+
 struct DecTables {
     uint16_t tab[1u << kPrimaryBits];
+    uint16_t tab2[kMaxSub << kSubBits];
     uint16_t sorted[kMaxK];
+    uint16_t sub_prefix[kMaxSub];
     uint32_t cnt[32], first[32], idx0[32];
+    uint32_t nsub;
 };
 
 struct FrameView {
@@ -113,6 +119,7 @@ __device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t fra
     // code lengths: <= 28, padding zero, at least one used, Kraft sum <= 1
     uint32_t bad = 0;
     uint64_t kraft = 0;
+#pragma unroll 1
     for (uint32_t t = tid; t < kMaxK; t += NT) {
         uint32_t L = 0;
         if (t < (uint32_t)pad4d(nsym)) L = lens[t];
@@ -139,77 +146,166 @@ __device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t fra
         if (L) T->sorted[s_idx0[L] + B->rank[sy]] = (uint16_t)sy;
     }
     __syncthreads();
+    // Entry formats (16 bits).  First level, indexed by the next 11 stream bits:
+    //   z | L<<10            symbol with zigzag code z and an L <= 11 bit code
+    //   0x8000 | L<<10       escape symbol with an L-bit code (32 raw bits follow)
+    //   0xC000 | id          no code of <= 11 bits starts here; id < kMaxSub: second-level table, else search
+    // Second level, indexed by stream bits 11..16: same with L-11 in place of L; 0xC000 = longer still.
+    if (tid == 0) T->nsub = 0;
+    __syncthreads();
+#pragma unroll 1
     for (uint32_t i = tid; i < (1u << kPrimaryBits); i += NT) {
-        uint32_t code = 0, e = 0;
+        uint32_t code = 0, e = 0xC000u;
         for (uint32_t L = 1; L <= kPrimaryBits; L++) {
             code = (code << 1) | ((i >> (L - 1)) & 1u);            // stream order: first bit is the code's MSB
             const uint32_t d = code - s_first[L];
-            if (d < s_cnt[L]) { e = T->sorted[s_idx0[L] + d] | (L << 10); break; }
+            if (d < s_cnt[L]) {
+                const uint32_t sy = T->sorted[s_idx0[L] + d];
+                e = sy ? ((sy - 1u) | (L << 10)) : (0x8000u | (L << 10));
+                break;
+            }
+        }
+        if (e == 0xC000u) {
+            const uint32_t id = atomicAdd(&T->nsub, 1u);
+            if (id < kMaxSub) { e |= id; T->sub_prefix[id] = (uint16_t)i; } else e |= 0x3FFu;
         }
         T->tab[i] = (uint16_t)e;
+    }
+    __syncthreads();
+    const uint32_t nsub = T->nsub < kMaxSub ? T->nsub : kMaxSub;
+#pragma unroll 1
+    for (uint32_t idx = tid; idx < (nsub << kSubBits); idx += NT) {
+        const uint32_t bits = (uint32_t)T->sub_prefix[idx >> kSubBits] | ((idx & ((1u << kSubBits) - 1u)) << kPrimaryBits);
+        uint32_t code = 0, e = 0xC000u;
+        for (uint32_t L = 1; L <= kPrimaryBits + kSubBits; L++) {
+            code = (code << 1) | ((bits >> (L - 1)) & 1u);
+            if (L > kPrimaryBits) {
+                const uint32_t d = code - s_first[L];
+                if (d < s_cnt[L]) {
+                    const uint32_t sy = T->sorted[s_idx0[L] + d];
+                    e = sy ? ((sy - 1u) | ((L - kPrimaryBits) << 10)) : (0x8000u | ((L - kPrimaryBits) << 10));
+                    break;
+                }
+            }
+        }
+        T->tab2[idx] = (uint16_t)e;
     }
     __syncthreads();
     V.status = ST_OK; V.kind = KIND_HUFF; V.segt = segt; V.seg_prefix = pre;
     V.words = reinterpret_cast<const uint32_t*>(pay + tables); V.nwords = (uint32_t)((payload - tables) / 4);
 }
 
-// Per-thread sequential LSB-first bit reader over 32-bit words, with the next word prefetched one refill
-// ahead so that the global-load latency is off the symbol-to-symbol dependency chain.
-struct Reader {
-    const uint32_t* words; uint32_t nwords, widx;
-    uint64_t buf; uint32_t navail, pre, consumed, bad, w;
+// Per-thread sequential reader of one HUFFMAN segment.  Every lane owns a 12-word window in LDS that is
+// refilled from global memory (three aligned 16-byte loads) at points that are uniform over the wave: the
+// start of every run of 8 symbols.  A symbol reads the two window words at its bit position (ds_read2) and
+// funnel-shifts them, so fast symbols, long codes and escapes all advance by plain position arithmetic and
+// nothing is loaded from global memory inside divergent code, except when a run with several escapes or long
+// codes uses up its window (then that lane reloads at once).  Budget: a window starts at most 127 bits before
+// the position; 8 first-level symbols use at most 88 bits; after any other symbol the lane reloads if it is
+// 224 or more bits into the window; so every two-word read stays inside the 384 bits.
+// Chunk addresses are clamped to the last 16-byte chunk that holds a bitstream word, so any input stays in
+// bounds (a valid stream never consumes a clamped chunk).
+constexpr uint32_t kWinWords = 12;
+
+struct HuffReader {
+    uint64_t bits_addr, last_chunk;      // byte address of bitstream word 0; of the last aligned chunk
+    uint32_t* win;                       // this lane's window in LDS
+    int32_t win_bit0;                    // bit index (relative to bitstream bit 0) of window word 0
+    uint32_t pos;                        // current position, in bits from the window start
+    uint32_t start_bit, bad;
     const DecTables* T;
 
-    __device__ inline uint32_t ldw(uint32_t i) const { return i < nwords ? words[i] : 0u; }
-    __device__ inline void init(const FrameView& V, const DecTables* tables, uint64_t bitpos, uint32_t elem0) {
-        words = V.words; nwords = V.nwords; T = tables; consumed = 0; bad = 0; w = V.w;
-        buf = 0; navail = 0; widx = 0; pre = 0;
-        if (V.kind == KIND_RAW) { widx = elem0; return; }
-        if (V.kind == KIND_ZERO) { nwords = 0; w = 0; }
-        widx = (uint32_t)(bitpos >> 5);
-        const uint32_t sh = (uint32_t)(bitpos & 31u);
-        buf = ((uint64_t)ldw(widx) | ((uint64_t)ldw(widx + 1) << 32)) >> sh;
-        navail = 64u - sh;
-        pre = ldw(widx + 2);
-        widx += 3;
-    }
-    __device__ inline void refill() {
-        if (navail <= 32u) { buf |= (uint64_t)pre << navail; navail += 32u; pre = ldw(widx); widx++; }
-    }
-    __device__ inline uint32_t take(uint32_t nb) {
-        const uint32_t v = (uint32_t)buf & (uint32_t)((1ull << nb) - 1ull);
-        buf >>= nb; navail -= nb; consumed += nb;
-        return v;
-    }
-    __device__ inline uint32_t next_huff() {
-        refill();
-        const uint32_t e = T->tab[(uint32_t)buf & ((1u << kPrimaryBits) - 1u)];
-        uint32_t L = e >> 10, sy = e & 1023u;
-        if (__builtin_expect(L == 0, 0)) {                    // long or unassigned code: canonical search
-            uint32_t code = 0;
-            for (uint32_t l = 1; l <= kMaxLen; l++) {
-                code = (code << 1) | ((uint32_t)(buf >> (l - 1)) & 1u);
-                const uint32_t d = code - T->first[l];
-                if (d < T->cnt[l]) { sy = T->sorted[T->idx0[l] + d]; L = l; break; }
-            }
-            if (L == 0) { bad = 1; L = 1; sy = 1; }
+    __device__ inline void init(const FrameView& V, const DecTables* tables, uint32_t bitpos, const void* safe16,
+                                uint32_t* lane_window) {
+        T = tables; bad = 0; win = lane_window; start_bit = bitpos;
+        if (V.nwords == 0 || V.kind != KIND_HUFF) {                      // nothing to read: point at valid memory
+            bits_addr = reinterpret_cast<uint64_t>(safe16); last_chunk = bits_addr;
+        } else {
+            bits_addr = reinterpret_cast<uint64_t>(V.words);
+            last_chunk = (bits_addr + 4ull * (V.nwords - 1)) & ~15ull;
         }
-        buf >>= L; navail -= L; consumed += L;
-        if (__builtin_expect(sy == 0, 0)) { refill(); return take(32); }
-        return sy - 1u;
+        win_bit0 = (int32_t)bitpos; pos = 0;
     }
-    __device__ inline uint32_t next_fixed() { refill(); return take(w); }
-    __device__ inline uint32_t next_raw() { return words[widx++]; }
+    __device__ inline void reload() {
+        const uint32_t cur = (uint32_t)(win_bit0 + (int32_t)pos);
+        const uint64_t a = bits_addr + 4ull * (cur >> 5);
+        uint64_t al = a & ~15ull;
+        const uint32_t back = (uint32_t)(a - al);                        // bytes between the chunk start and the word
+        al = al < last_chunk ? al : last_chunk;
+        const uint64_t c1 = al + 16 < last_chunk ? al + 16 : last_chunk;
+        const uint64_t c2 = al + 32 < last_chunk ? al + 32 : last_chunk;
+        const uint4 x0 = *reinterpret_cast<const uint4*>(al);
+        const uint4 x1 = *reinterpret_cast<const uint4*>(c1);
+        const uint4 x2 = *reinterpret_cast<const uint4*>(c2);
+        uint4* w = reinterpret_cast<uint4*>(win);
+        w[0] = x0; w[1] = x1; w[2] = x2;
+        win_bit0 = (int32_t)(cur & ~31u) - (int32_t)(8u * back);
+        pos = cur - (uint32_t)win_bit0;
+    }
+    __device__ inline uint32_t peek() const {                            // the next 32 stream bits
+        const uint32_t k = pos >> 5;
+        return __builtin_amdgcn_alignbit(win[k + 1], win[k], pos);
+    }
+    __device__ inline uint32_t consumed() const { return (uint32_t)(win_bit0 + (int32_t)pos) - start_bit; }
+    __device__ inline uint32_t next() {
+        const uint32_t w32 = peek();
+        const uint32_t e = T->tab[w32 & ((1u << kPrimaryBits) - 1u)];
+        if (__builtin_expect(e < 0x8000u, 1)) { pos += e >> 10; return e & 1023u; }
+        return next_slow(e, w32);
+    }
+    __device__ inline uint32_t next_slow(uint32_t e, uint32_t w32) {
+        uint32_t L = (e >> 10) & 15u, z = 0, esc = (e < 0xC000u);
+        if (e >= 0xC000u) {
+            uint32_t e2 = 0xC000u;
+            const uint32_t id = e & 0x3FFu;
+            if (id < kMaxSub) e2 = T->tab2[(id << kSubBits) + ((w32 >> kPrimaryBits) & ((1u << kSubBits) - 1u))];
+            if (e2 < 0xC000u) {
+                L = kPrimaryBits + ((e2 >> 10) & 7u); z = e2 & 1023u; esc = (e2 >= 0x8000u);
+            } else {                                                     // longer than 17 bits or unassigned: search
+                const volatile uint32_t* vfirst = T->first; const volatile uint32_t* vcnt = T->cnt;
+                const volatile uint32_t* vidx0 = T->idx0;
+                uint32_t code = 0, sy = 1;
+                L = 0;
+#pragma unroll 1
+                for (uint32_t l = 1; l <= kMaxLen; l++) {
+                    code = (code << 1) | ((w32 >> (l - 1)) & 1u);
+                    const uint32_t d = code - vfirst[l];
+                    if (d < vcnt[l]) { sy = T->sorted[vidx0[l] + d]; L = l; break; }
+                }
+                if (L == 0) { bad = 1; L = 1; sy = 1; }
+                z = sy - 1u; esc = (sy == 0);
+            }
+        }
+        pos += L;
+        if (esc) { z = peek(); pos += 32u; }                             // escape: the 32 raw bits of z follow
+        if (pos >= 224u) reload();
+        return z;
+    }
 };
 
-template <int KIND>
-__device__ inline uint32_t rd_next(Reader& r) {
-    if (KIND == KIND_HUFF) return r.next_huff();
-    if (KIND == KIND_FIXED) return r.next_fixed();
-    return r.next_raw();
-}
+// Position-addressed fetch of element e of a RAW / FIXEDLEN (or rejected = all-zero) frame.
+struct DirectFetch {
+    const uint32_t* words; uint32_t last, w, mask, kind;
+    __device__ inline void init(const FrameView& V, const uint32_t* safe_word) {
+        words = V.words; kind = V.kind; w = V.w;
+        uint32_t nwords = V.nwords;
+        if (kind == KIND_ZERO) { nwords = 0; w = 0; kind = KIND_FIXED; }
+        if (nwords == 0) { words = safe_word; nwords = 1; }
+        last = nwords - 1;
+        mask = (w >= 32u) ? 0xFFFFFFFFu : ((1u << w) - 1u);
+    }
+    // zigzag code (FIXEDLEN) or fp32 bit pattern (RAW)
+    __device__ inline uint32_t get(uint32_t e) const {
+        if (kind == KIND_RAW) return words[e < last ? e : last];
+        const uint64_t bp = (uint64_t)e * w;
+        const uint32_t i = (uint32_t)(bp >> 5), sh = (uint32_t)(bp & 31u);
+        const uint32_t lo = words[i < last ? i : last], hi = words[i + 1 < last ? i + 1 : last];
+        return __builtin_amdgcn_alignbit(hi, lo, sh) & mask;
+    }
+};
 
 constexpr uint32_t kTileR = 16;                      // symbols per thread between two coalesced output phases
+constexpr uint32_t kRun = 8;                         // symbols between two window reloads
 constexpr uint32_t kTileStride = kTileR + 1;         // odd row stride: conflict-free column writes
 
 struct DecShared {
@@ -218,50 +314,103 @@ struct DecShared {
     uint32_t zmax, flags;
 };
 
+template <int NOPS>
+struct __align__(16) DecWindows { uint32_t w[NOPS][kDecThreads * kWinWords]; };
+
 struct SegCtx {
-    uint32_t tid, lane, first_seg, nf, cntseg;
+    uint32_t tid, lane, first_seg, nf, cntseg, e0;
     uint64_t f0;
     bool vec_ok;
 };
 
+// Combine one element of A and one of B (reduce): raw operands give the canonical fp32 sum, coded operands
+// the exact integer sum (wrapped to 32 bits; a sum beyond 2^30 raises the overflow flag).
+template <bool ANY_RAW>
+__device__ inline uint32_t combine(uint32_t ta, bool a_raw, uint32_t tb, bool b_raw, float step, uint32_t& overflow) {
+    if (ANY_RAW) {
+#pragma clang fp contract(off)
+        const float fa = a_raw ? __uint_as_float(ta) : dequantize1(unzigzag(ta), step);
+        const float fb = b_raw ? __uint_as_float(tb) : dequantize1(unzigzag(tb), step);
+        const float sum = fa + fb;
+        return (sum != sum) ? kCanonNaN : __float_as_uint(sum);
+    }
+    const int32_t qa = unzigzag(ta), qb = unzigzag(tb);
+    if (__builtin_expect(((ta | tb) >> 30) != 0, 0)) {                   // only then can |qa+qb| pass 2^30
+        const int64_t Q = (int64_t)qa + (int64_t)qb;
+        if (Q > (int64_t)kQSumMax || Q < -(int64_t)kQSumMax) overflow = 1;
+    }
+    return (uint32_t)qa + (uint32_t)qb;
+}
+
+// Coalesced consumer of 4 consecutive elements starting at frame element e (m of them valid).
+// MODE 0: dequantize (or pass RAW bits through) and store fp32.  MODE 1: histogram + zmax of the sums
+// (coded output) and stage the 32-bit values.
+template <int MODE>
+__device__ inline void emit4(const DecodeArgs& A, const SegCtx& C, uint32_t e, uint32_t m, const uint32_t t[4], bool raw_vals,
+                             uint32_t* s_h, uint32_t ncs, uint32_t copy, uint32_t& zmax) {
+    if (MODE == 0) {
+        float v[4];
+#pragma unroll
+        for (uint32_t j = 0; j < 4; j++) v[j] = raw_vals ? __uint_as_float(t[j]) : dequantize1(unzigzag(t[j]), A.step);
+        float* dst = A.out + C.f0 + e;
+        if (C.vec_ok && m == 4) *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+        else for (uint32_t j = 0; j < m; j++) dst[j] = v[j];
+    } else {
+        if (!raw_vals) {
+#pragma unroll
+            for (uint32_t j = 0; j < 4; j++) {
+                if (j < m) {
+                    const uint32_t z = zigzag((int32_t)t[j]);
+                    zmax = z > zmax ? z : zmax;
+                    atomicAdd(&s_h[(sym_of(z, A.K) << ncs) + copy], 1u);
+                }
+            }
+        }
+        uint32_t* dst = reinterpret_cast<uint32_t*>(A.ws + A.L.codes) + C.f0 + e;
+        if (C.vec_ok && m == 4) *reinterpret_cast<uint4*>(dst) = make_uint4(t[0], t[1], t[2], t[3]);
+        else for (uint32_t j = 0; j < m; j++) dst[j] = t[j];
+    }
+}
+
 // One 256-symbol segment per thread, kTileR symbols at a time into an LDS tile, then the workgroup writes the
 // tile out with 16-byte stores (kTileR/4 lanes cover one thread's run, so every store instruction fills whole
-// 64-byte runs).  MODE 0: dequantize to fp32.  MODE 1: Q = qa + qb, histogram + zmax of Q, stage Q.
+// 64-byte runs).  KA / KB say which operands are HUFFMAN (sequential reader) and which are addressed directly.
 template <int MODE, int KA, int KB>
-__device__ inline void run_segments(const DecodeArgs& A, const SegCtx& C, Reader& ra, Reader& rb, DecShared* S,
-                                    uint32_t* s_h, uint32_t ncs, bool out_raw, uint32_t& overflow) {
+__device__ inline void run_segments(const DecodeArgs& A, const SegCtx& C, HuffReader& ra, HuffReader& rb,
+                                    const DirectFetch& da, const DirectFetch& db, DecShared* S,
+                                    uint32_t* s_h, uint32_t ncs, uint32_t& overflow) {
     const uint32_t tid = C.tid;
-    const uint32_t K = A.K;
     const uint32_t copy = C.lane & ((1u << ncs) - 1u);
     uint32_t* tile = S->u.tile;
     uint32_t zmax = 0;
     constexpr uint32_t LPR = kTileR / 4;             // lanes per row in the output phase
+    constexpr bool ANY_RAW = (MODE == 1) && (KA == KIND_RAW || KB == KIND_RAW);
+    uint32_t e = C.e0;                               // next element of my segment (frame index)
+    auto produce = [&]() -> uint32_t {
+        const uint32_t ta = (KA == KIND_HUFF) ? ra.next() : da.get(e);
+        if (MODE == 0) { e++; return ta; }
+        const uint32_t tb = (KB == KIND_HUFF) ? rb.next() : db.get(e);
+        e++;
+        return combine<ANY_RAW>(ta, KA == KIND_RAW, tb, KB == KIND_RAW, A.step, overflow);
+    };
     for (uint32_t r0 = 0; r0 < kSeg; r0 += kTileR) {
-        if (r0 < C.cntseg) {
-            const uint32_t nr = (C.cntseg - r0 < kTileR) ? (C.cntseg - r0) : kTileR;
-            uint32_t* row = tile + tid * kTileStride;
+        uint32_t* row = tile + tid * kTileStride;
+        if (r0 + kTileR <= C.cntseg) {                                   // full run: static tile offsets
+#pragma unroll
+            for (uint32_t h = 0; h < kTileR; h += kRun) {
+                if (KA == KIND_HUFF) ra.reload();
+                if (MODE == 1 && KB == KIND_HUFF) rb.reload();
+#pragma unroll
+                for (uint32_t r = 0; r < kRun; r++) row[h + r] = produce();
+            }
+        } else if (r0 < C.cntseg) {
+            const uint32_t nr = C.cntseg - r0;
             for (uint32_t r = 0; r < nr; r++) {
-                uint32_t v;
-                if (MODE == 0) {
-                    v = rd_next<KA>(ra);
-                } else {
-                    const uint32_t ta = rd_next<KA>(ra), tb = rd_next<KB>(rb);
-                    if (KA == KIND_RAW || KB == KIND_RAW) {
-#pragma clang fp contract(off)
-                        const float fa = (KA == KIND_RAW) ? __uint_as_float(ta) : dequantize1(unzigzag(ta), A.step);
-                        const float fb = (KB == KIND_RAW) ? __uint_as_float(tb) : dequantize1(unzigzag(tb), A.step);
-                        const float sum = fa + fb;
-                        v = (sum != sum) ? kCanonNaN : __float_as_uint(sum);
-                    } else {
-                        const int32_t qa = unzigzag(ta), qb = unzigzag(tb);
-                        v = (uint32_t)qa + (uint32_t)qb;
-                        if (__builtin_expect(((ta | tb) >> 30) != 0, 0)) {       // only then can |qa+qb| pass 2^30
-                            const int64_t Q = (int64_t)qa + (int64_t)qb;
-                            if (Q > (int64_t)kQSumMax || Q < -(int64_t)kQSumMax) overflow = 1;
-                        }
-                    }
+                if ((r % kRun) == 0) {
+                    if (KA == KIND_HUFF) ra.reload();
+                    if (MODE == 1 && KB == KIND_HUFF) rb.reload();
                 }
-                row[r] = v;
+                row[r] = produce();
             }
         }
         __syncthreads();
@@ -269,38 +418,45 @@ __device__ inline void run_segments(const DecodeArgs& A, const SegCtx& C, Reader
         for (uint32_t k = 0; k < LPR; k++) {
             const uint32_t g = tid + kDecThreads * k;
             const uint32_t rw = g / LPR, c = (g % LPR) * 4;
-            const uint32_t e = (C.first_seg + rw) * kSeg + r0 + c;              // element index in the frame
-            if (e < C.nf) {
-                const uint32_t m = (C.nf - e < 4) ? (C.nf - e) : 4u;
+            const uint32_t eo = (C.first_seg + rw) * kSeg + r0 + c;             // element index in the frame
+            if (eo < C.nf) {
+                const uint32_t m = (C.nf - eo < 4) ? (C.nf - eo) : 4u;
                 uint32_t t[4];
 #pragma unroll
                 for (uint32_t j = 0; j < 4; j++) t[j] = tile[rw * kTileStride + c + j];
-                if (MODE == 0) {
-                    float v[4];
-#pragma unroll
-                    for (uint32_t j = 0; j < 4; j++)
-                        v[j] = (KA == KIND_RAW) ? __uint_as_float(t[j]) : dequantize1(unzigzag(t[j]), A.step);
-                    float* dst = A.out + C.f0 + e;
-                    if (C.vec_ok && m == 4) *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-                    else for (uint32_t j = 0; j < m; j++) dst[j] = v[j];
-                } else {
-                    if (!out_raw) {
-#pragma unroll
-                        for (uint32_t j = 0; j < 4; j++) {
-                            if (j < m) {
-                                const uint32_t z = zigzag((int32_t)t[j]);
-                                zmax = z > zmax ? z : zmax;
-                                atomicAdd(&s_h[(sym_of(z, K) << ncs) + copy], 1u);
-                            }
-                        }
-                    }
-                    uint32_t* dst = reinterpret_cast<uint32_t*>(A.ws + A.L.codes) + C.f0 + e;
-                    if (C.vec_ok && m == 4) *reinterpret_cast<uint4*>(dst) = make_uint4(t[0], t[1], t[2], t[3]);
-                    else for (uint32_t j = 0; j < m; j++) dst[j] = t[j];
-                }
+                emit4<MODE>(A, C, eo, m, t, MODE == 0 ? false : ANY_RAW, s_h, ncs, copy, zmax);
             }
         }
         __syncthreads();
+    }
+    if (MODE == 1) {
+        zmax = wave_max(zmax);
+        if (C.lane == 0) atomicMax(&S->zmax, zmax);
+    }
+}
+
+// Frames without a HUFFMAN operand: element-parallel and coalesced on both sides.
+template <int MODE>
+__device__ inline void run_elementwise(const DecodeArgs& A, const SegCtx& C, uint32_t blk0, const DirectFetch& da,
+                                       const DirectFetch& db, DecShared* S, uint32_t* s_h, uint32_t ncs, uint32_t& overflow) {
+    const uint32_t cnt = (C.nf - blk0 < kDecBlock) ? (C.nf - blk0) : kDecBlock;
+    const uint32_t copy = C.lane & ((1u << ncs) - 1u);
+    const bool a_raw = da.kind == KIND_RAW, b_raw = (MODE == 1) && db.kind == KIND_RAW;
+    uint32_t zmax = 0;
+    for (uint32_t i = C.tid * 4; i < cnt; i += kDecThreads * 4) {
+        const uint32_t e = blk0 + i;
+        const uint32_t m = (cnt - i < 4) ? (cnt - i) : 4u;
+        uint32_t t[4] = { 0, 0, 0, 0 };
+        for (uint32_t j = 0; j < m; j++) {
+            const uint32_t ta = da.get(e + j);
+            if (MODE == 0) t[j] = ta;
+            else {
+                const uint32_t tb = db.get(e + j);
+                t[j] = (a_raw || b_raw) ? combine<true>(ta, a_raw, tb, b_raw, A.step, overflow)
+                                        : combine<false>(ta, false, tb, false, A.step, overflow);
+            }
+        }
+        emit4<MODE>(A, C, e, m, t, MODE == 0 ? a_raw : (a_raw || b_raw), s_h, ncs, copy, zmax);
     }
     if (MODE == 1) {
         zmax = wave_max(zmax);
@@ -313,6 +469,7 @@ template <int MODE>
 __global__ __launch_bounds__(kDecThreads) void k_decode(DecodeArgs A) {
     __shared__ DecTables s_t[MODE == 1 ? 2 : 1];
     __shared__ DecShared S;
+    __shared__ DecWindows<(MODE == 1 ? 2 : 1)> s_win;
     __shared__ uint32_t s_h[MODE == 1 ? 2048 : 1];
 
     const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
@@ -355,43 +512,15 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(DecodeArgs A) {
         if (MODE == 1 && (va.status || vb.status)) { va.kind = KIND_ZERO; vb.kind = KIND_ZERO; }
     }
     if (MODE == 0 && va.status) return;                                 // rejected frame: its output range is left alone
-    const bool vec_ok = ((f0 & 3u) == 0);
 
-    // ---- MODE 0, RAW / FIXEDLEN frames: element-parallel, coalesced on both sides ----
-    if (MODE == 0 && va.kind != KIND_HUFF) {
-        const uint32_t cnt = (nf - blk0 < kDecBlock) ? (nf - blk0) : kDecBlock;
-        const uint32_t w = va.w;
-        const uint32_t mask = (w >= 32u) ? 0xFFFFFFFFu : ((1u << w) - 1u);
-        for (uint32_t i = tid * 4; i < cnt; i += kDecThreads * 4) {
-            const uint32_t e = blk0 + i;
-            const uint32_t m = (cnt - i < 4) ? (cnt - i) : 4u;
-            float v[4] = { 0.f, 0.f, 0.f, 0.f };
-            for (uint32_t j = 0; j < m; j++) {
-                if (va.kind == KIND_RAW) v[j] = __uint_as_float(va.words[e + j]);
-                else {
-                    const uint64_t bp = (uint64_t)(e + j) * w;
-                    const uint32_t wi = (uint32_t)(bp >> 5), sh = (uint32_t)(bp & 31u);
-                    const uint32_t lo = wi < va.nwords ? va.words[wi] : 0u, hi = (wi + 1 < va.nwords) ? va.words[wi + 1] : 0u;
-                    const uint32_t z = (uint32_t)((((uint64_t)hi << 32) | lo) >> sh) & mask;
-                    v[j] = dequantize1(unzigzag(z), A.step);
-                }
-            }
-            float* dst = A.out + f0 + e;
-            if (vec_ok && m == 4) *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-            else for (uint32_t j = 0; j < m; j++) dst[j] = v[j];
-        }
-        return;
-    }
-
-    // bit offset of my segment: prefix of the segment table (HUFFMAN) or closed form (FIXEDLEN)
-    uint64_t bit_a = 0, bit_b = 0;
-    uint32_t seglen_a = 0, seglen_b = 0;
+    // bit offset of my segment inside a HUFFMAN bitstream: prefix of the segment table
+    uint32_t bit_a = 0, bit_b = 0, seglen_a = 0, seglen_b = 0;
     {
-        uint32_t la = (va.kind == KIND_HUFF && seg_valid) ? va.segt[gseg] : 0u;
-        uint32_t lb = (MODE == 1 && vb.kind == KIND_HUFF && seg_valid) ? vb.segt[gseg] : 0u;
+        const uint32_t la = (va.kind == KIND_HUFF && seg_valid) ? va.segt[gseg] : 0u;
+        const uint32_t lb = (MODE == 1 && vb.kind == KIND_HUFF && seg_valid) ? vb.segt[gseg] : 0u;
         seglen_a = la; seglen_b = lb;
         // both lengths are < 2^16: scan them packed in one 64-bit lane value (sums stay below 2^32 each)
-        uint64_t v = (uint64_t)la | ((uint64_t)lb << 32);
+        const uint64_t v = (uint64_t)la | ((uint64_t)lb << 32);
         uint64_t incl = v;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) { uint64_t t = __shfl_up(incl, d, 64); if ((int)lane >= d) incl += t; }
@@ -400,22 +529,28 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(DecodeArgs A) {
         __syncthreads();
         uint64_t excl = incl - v;
         for (uint32_t w = 0; w < wave; w++) excl += S.wsum[w];
-        bit_a = va.seg_prefix + (excl & 0xFFFFFFFFull);
-        bit_b = vb.seg_prefix + (excl >> 32);
-        if (va.kind == KIND_FIXED) bit_a = (uint64_t)e0 * va.w;
-        if (MODE == 1 && vb.kind == KIND_FIXED) bit_b = (uint64_t)e0 * vb.w;
+        bit_a = (uint32_t)va.seg_prefix + (uint32_t)(excl & 0xFFFFFFFFull);
+        bit_b = (uint32_t)vb.seg_prefix + (uint32_t)(excl >> 32);
     }
-
-    Reader ra, rb;
-    ra.init(va, &s_t[0], bit_a, e0);
-    rb.init(vb, &s_t[MODE == 1 ? 1 : 0], bit_b, e0);
+    const uint32_t* safe = reinterpret_cast<const uint32_t*>(A.res);
+    HuffReader ra, rb;
+    DirectFetch da, dbf;
+    ra.init(va, &s_t[0], bit_a, safe, &s_win.w[0][tid * kWinWords]);
+    rb.init(vb, &s_t[MODE == 1 ? 1 : 0], bit_b, safe, &s_win.w[MODE == 1 ? 1 : 0][tid * kWinWords]);
+    da.init(va, safe);
+    dbf.init(vb, safe);
     SegCtx C;
-    C.tid = tid; C.lane = lane; C.first_seg = first_seg; C.nf = nf; C.cntseg = cntseg; C.f0 = f0; C.vec_ok = vec_ok;
+    C.tid = tid; C.lane = lane; C.first_seg = first_seg; C.nf = nf; C.cntseg = cntseg; C.e0 = e0; C.f0 = f0;
+    C.vec_ok = ((f0 & 3u) == 0);
     uint32_t overflow = 0;
 
     if (MODE == 0) {
-        run_segments<0, KIND_HUFF, KIND_FIXED>(A, C, ra, rb, &S, s_h, 0, false, overflow);
-        if (seg_valid && (ra.bad || ra.consumed != seglen_a)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
+        if (va.kind == KIND_HUFF) {
+            run_segments<0, KIND_HUFF, KIND_FIXED>(A, C, ra, rb, da, dbf, &S, s_h, 0, overflow);
+            if (seg_valid && (ra.bad || ra.consumed() != seglen_a)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
+        } else {
+            run_elementwise<0>(A, C, blk0, da, dbf, &S, s_h, 0, overflow);
+        }
         return;
     }
 
@@ -426,24 +561,18 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(DecodeArgs A) {
     for (uint32_t i = tid; i < (K << ncs); i += kDecThreads) s_h[i] = 0;
     __syncthreads();
     const bool out_raw = (va.kind == KIND_RAW) || (vb.kind == KIND_RAW);      // uniform over the frame
-    const uint32_t ka = (va.kind == KIND_ZERO) ? (uint32_t)KIND_FIXED : va.kind;
-    const uint32_t kb = (vb.kind == KIND_ZERO) ? (uint32_t)KIND_FIXED : vb.kind;
-    switch (ka * 3 + kb) {
-        case KIND_RAW * 3 + KIND_RAW:     run_segments<1, KIND_RAW, KIND_RAW>(A, C, ra, rb, &S, s_h, ncs, out_raw, overflow); break;
-        case KIND_RAW * 3 + KIND_FIXED:   run_segments<1, KIND_RAW, KIND_FIXED>(A, C, ra, rb, &S, s_h, ncs, out_raw, overflow); break;
-        case KIND_RAW * 3 + KIND_HUFF:    run_segments<1, KIND_RAW, KIND_HUFF>(A, C, ra, rb, &S, s_h, ncs, out_raw, overflow); break;
-        case KIND_FIXED * 3 + KIND_RAW:   run_segments<1, KIND_FIXED, KIND_RAW>(A, C, ra, rb, &S, s_h, ncs, out_raw, overflow); break;
-        case KIND_FIXED * 3 + KIND_FIXED: run_segments<1, KIND_FIXED, KIND_FIXED>(A, C, ra, rb, &S, s_h, ncs, out_raw, overflow); break;
-        case KIND_FIXED * 3 + KIND_HUFF:  run_segments<1, KIND_FIXED, KIND_HUFF>(A, C, ra, rb, &S, s_h, ncs, out_raw, overflow); break;
-        case KIND_HUFF * 3 + KIND_RAW:    run_segments<1, KIND_HUFF, KIND_RAW>(A, C, ra, rb, &S, s_h, ncs, out_raw, overflow); break;
-        case KIND_HUFF * 3 + KIND_FIXED:  run_segments<1, KIND_HUFF, KIND_FIXED>(A, C, ra, rb, &S, s_h, ncs, out_raw, overflow); break;
-        default:                          run_segments<1, KIND_HUFF, KIND_HUFF>(A, C, ra, rb, &S, s_h, ncs, out_raw, overflow); break;
-    }
+    const bool ha = va.kind == KIND_HUFF, hb = vb.kind == KIND_HUFF;
+    if (!ha && !hb) run_elementwise<1>(A, C, blk0, da, dbf, &S, s_h, ncs, overflow);
+    else if (ha && hb) run_segments<1, KIND_HUFF, KIND_HUFF>(A, C, ra, rb, da, dbf, &S, s_h, ncs, overflow);
+    else if (ha && vb.kind == KIND_RAW) run_segments<1, KIND_HUFF, KIND_RAW>(A, C, ra, rb, da, dbf, &S, s_h, ncs, overflow);
+    else if (ha) run_segments<1, KIND_HUFF, KIND_FIXED>(A, C, ra, rb, da, dbf, &S, s_h, ncs, overflow);
+    else if (va.kind == KIND_RAW) run_segments<1, KIND_RAW, KIND_HUFF>(A, C, ra, rb, da, dbf, &S, s_h, ncs, overflow);
+    else run_segments<1, KIND_FIXED, KIND_HUFF>(A, C, ra, rb, da, dbf, &S, s_h, ncs, overflow);
     if (seg_valid) {
-        if (va.kind == KIND_HUFF && (ra.bad || ra.consumed != seglen_a)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
-        if (vb.kind == KIND_HUFF && (rb.bad || rb.consumed != seglen_b)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
-        if (overflow) atomicMax(&res->status, (uint32_t)ST_RANGE);
+        if (ha && (ra.bad || ra.consumed() != seglen_a)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
+        if (hb && (rb.bad || rb.consumed() != seglen_b)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
     }
+    if (overflow) atomicMax(&res->status, (uint32_t)ST_RANGE);
     __syncthreads();
     uint32_t* ph = reinterpret_cast<uint32_t*>(A.ws + A.L.phist) + (size_t)blockIdx.x * kMaxK;
     for (uint32_t sy = tid; sy < K; sy += kDecThreads) {
