@@ -36,6 +36,8 @@ __device__ inline uint32_t check_stream(const uint8_t* s, uint64_t bytes, const 
 }
 
 // Shared memory of one operand's decoder.
+constexpr uint32_t kRun = 8;                   // symbols per run: window reloads happen at run starts only
+constexpr uint32_t kWinFreshBits = 193;        // bits a freshly loaded window offers before a lane must reload
 constexpr uint32_t kSubBits = 6;               // second-level tables resolve codes of 12..17 bits
 constexpr uint32_t kMaxSub = 32;               // at most this many second-level tables (the rest: canonical search)
 
@@ -56,6 +58,7 @@ struct FrameView {
     uint32_t nwords;
     const uint16_t* segt;
     uint64_t seg_prefix;      // bits before this workgroup's first segment
+    uint32_t cadence;         // HUFFMAN: runs of 8 symbols between two scheduled window reloads
 };
 
 // Build-time scratch shared by both operands.
@@ -84,6 +87,7 @@ __device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t fra
                                   const DecodeArgs& A, DecTables* T, BuildScratch* B, FrameView& V) {
     const uint32_t tid = threadIdx.x;
     V.status = ST_CORRUPT; V.kind = KIND_ZERO; V.w = 0; V.words = nullptr; V.nwords = 0; V.segt = nullptr; V.seg_prefix = 0;
+    V.cadence = 1;
     const uint64_t off = *reinterpret_cast<const uint64_t*>(s + kStreamHdr + 8ull * frame);
     if ((off & 15u) || off < kStreamHdr + pad16d(8ull * A.n_frames) || off + kHdrBytes > total) return;
     const uint8_t* fr = s + off;
@@ -191,24 +195,38 @@ __device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t fra
         T->tab2[idx] = (uint16_t)e;
     }
     __syncthreads();
+    {   // schedule reloads so that an average lane (with a 25 % margin) never needs one of its own
+        const uint32_t run_bits = (uint32_t)((all * kRun) / nf) + 1u;
+        const uint32_t c = kWinFreshBits / (run_bits + run_bits / 4u);
+        V.cadence = c < 1u ? 1u : (c > 16u ? 16u : c);
+    }
     V.status = ST_OK; V.kind = KIND_HUFF; V.segt = segt; V.seg_prefix = pre;
     V.words = reinterpret_cast<const uint32_t*>(pay + tables); V.nwords = (uint32_t)((payload - tables) / 4);
 }
 
-// Per-thread sequential reader of one HUFFMAN segment.  Every lane owns a 12-word window in LDS that is
-// refilled from global memory (three aligned 16-byte loads) at points that are uniform over the wave: the
-// start of every run of 8 symbols.  A symbol reads the two window words at its bit position (ds_read2) and
-// funnel-shifts them, so fast symbols, long codes and escapes all advance by plain position arithmetic and
-// nothing is loaded from global memory inside divergent code, except when a run with several escapes or long
-// codes uses up its window (then that lane reloads at once).  Budget: a window starts at most 127 bits before
-// the position; 8 first-level symbols use at most 88 bits; after any other symbol the lane reloads if it is
-// 224 or more bits into the window; so every two-word read stays inside the 384 bits.
-// Chunk addresses are clamped to the last 16-byte chunk that holds a bitstream word, so any input stays in
-// bounds (a valid stream never consumes a clamped chunk).
+// Per-thread sequential reader of one HUFFMAN segment.  Every lane owns a small window (kWinWords words) in LDS, filled from
+// global memory with dword-aligned 16-byte loads starting at the word the lane is in.  Reloads happen at
+// the start of a run of 8 symbols, a point that is uniform over the wave: on a schedule derived from the
+// frame's average code length (so that the global-load stall is paid once for all lanes and few fetched bytes
+// go unused), and for a single lane when it is kWinRunLimit or more bits into its window.  A symbol reads the two
+// window words at its bit position (ds_read2) and funnel-shifts them, so first-level symbols, long codes and
+// escapes all advance by plain position arithmetic; a lane also reloads at once when a long code or an escape
+// leaves it kWinSlowLimit or more bits into the window.  Budget: 8 first-level symbols use at most 88 bits, a
+// long code 28, an escape 60, so every two-word read stays inside the window.  Near the end of the bitstream words are
+// fetched one by one with the index clamped to the last word, so any input stays in bounds (a valid stream
+// never consumes a clamped word).
 constexpr uint32_t kWinWords = 12;
+constexpr uint32_t kWinBits = 32 * kWinWords;
+// A two-word read at position p needs p < kWinBits - 32.  After a long code or an escape a lane reloads unless
+// p < kWinSlowLimit; up to 7 first-level symbols (77 bits) and the code of an escape (28 bits) may follow
+// before the next check, and the escape's raw word is read there: kWinSlowLimit + 77 + 28 < kWinBits - 32.
+constexpr uint32_t kWinSlowLimit = kWinBits - 32 - 77 - 28 - 7;      // 240 for 12 words
+constexpr uint32_t kWinRunLimit = kWinSlowLimit - 16;                // reload at a run start when this far in
+static_assert(kWinRunLimit - 31 == kWinFreshBits, "cadence constant out of step with the window size");
 
 struct HuffReader {
-    uint64_t bits_addr, last_chunk;      // byte address of bitstream word 0; of the last aligned chunk
+    uint64_t bits_addr;                  // byte address of bitstream word 0
+    uint32_t nwords;                     // words in the bitstream (at least 1)
     uint32_t* win;                       // this lane's window in LDS
     int32_t win_bit0;                    // bit index (relative to bitstream bit 0) of window word 0
     uint32_t pos;                        // current position, in bits from the window start
@@ -219,39 +237,66 @@ struct HuffReader {
                                 uint32_t* lane_window) {
         T = tables; bad = 0; win = lane_window; start_bit = bitpos;
         if (V.nwords == 0 || V.kind != KIND_HUFF) {                      // nothing to read: point at valid memory
-            bits_addr = reinterpret_cast<uint64_t>(safe16); last_chunk = bits_addr;
+            bits_addr = reinterpret_cast<uint64_t>(safe16); nwords = 1;
         } else {
-            bits_addr = reinterpret_cast<uint64_t>(V.words);
-            last_chunk = (bits_addr + 4ull * (V.nwords - 1)) & ~15ull;
+            bits_addr = reinterpret_cast<uint64_t>(V.words); nwords = V.nwords;
         }
         win_bit0 = (int32_t)bitpos; pos = 0;
     }
     __device__ inline void reload() {
+#ifdef NZ_EXP_NO_RELOAD
+        if (pos < 0x7fffffffu) { win_bit0 += (int32_t)(pos & ~31u); pos &= 31u; return; }
+#endif
         const uint32_t cur = (uint32_t)(win_bit0 + (int32_t)pos);
-        const uint64_t a = bits_addr + 4ull * (cur >> 5);
-        uint64_t al = a & ~15ull;
-        const uint32_t back = (uint32_t)(a - al);                        // bytes between the chunk start and the word
-        al = al < last_chunk ? al : last_chunk;
-        const uint64_t c1 = al + 16 < last_chunk ? al + 16 : last_chunk;
-        const uint64_t c2 = al + 32 < last_chunk ? al + 32 : last_chunk;
-        const uint4 x0 = *reinterpret_cast<const uint4*>(al);
-        const uint4 x1 = *reinterpret_cast<const uint4*>(c1);
-        const uint4 x2 = *reinterpret_cast<const uint4*>(c2);
-        uint4* w = reinterpret_cast<uint4*>(win);
-        w[0] = x0; w[1] = x1; w[2] = x2;
-        win_bit0 = (int32_t)(cur & ~31u) - (int32_t)(8u * back);
-        pos = cur - (uint32_t)win_bit0;
+        const uint32_t wi = cur >> 5;
+        // the window is stored word-major (word k of every lane side by side): conflict-free for equal k
+        if (__builtin_expect(wi + kWinWords <= nwords, 1)) {
+            // four dword-aligned 16-byte loads straight from the lane's position (no alignment waste)
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+            typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
+            typedef const u32x4_a4 __attribute__((address_space(1))) * gptr;  // plain global loads, not flat ones
+            gptr p = reinterpret_cast<gptr>(bits_addr + 4ull * wi);
+            u32x4 x[kWinWords / 4];
+#pragma unroll
+            for (uint32_t c = 0; c < kWinWords / 4; c++) x[c] = p[c];
+#pragma unroll
+            for (uint32_t c = 0; c < kWinWords / 4; c++) {
+                win[(4 * c + 0) * kDecThreads] = x[c].x; win[(4 * c + 1) * kDecThreads] = x[c].y;
+                win[(4 * c + 2) * kDecThreads] = x[c].z; win[(4 * c + 3) * kDecThreads] = x[c].w;
+            }
+        } else {
+            // near the end of the bitstream: word by word, indices clamped to the last word
+            typedef const uint32_t __attribute__((address_space(1))) * wptr;
+            wptr w = reinterpret_cast<wptr>(bits_addr);
+            const uint32_t last = nwords - 1u;
+#pragma unroll 1
+            for (uint32_t j = 0; j < kWinWords; j++) win[j * kDecThreads] = w[wi + j < last ? wi + j : last];
+        }
+        win_bit0 = (int32_t)(cur & ~31u);
+        pos = cur & 31u;
     }
     __device__ inline uint32_t peek() const {                            // the next 32 stream bits
         const uint32_t k = pos >> 5;
-        return __builtin_amdgcn_alignbit(win[k + 1], win[k], pos);
+        return __builtin_amdgcn_alignbit(win[(k + 1) * kDecThreads], win[k * kDecThreads], pos);
     }
     __device__ inline uint32_t consumed() const { return (uint32_t)(win_bit0 + (int32_t)pos) - start_bit; }
     __device__ inline uint32_t next() {
+#ifdef NZ_EXP_NO_WINDOW
+        const uint32_t w32 = pos * 2654435761u;
+#else
         const uint32_t w32 = peek();
+#endif
+#ifdef NZ_EXP_NO_TABLE
+        const uint32_t e = (w32 & 7u) | (3u << 10);
+#else
         const uint32_t e = T->tab[w32 & ((1u << kPrimaryBits) - 1u)];
+#endif
+#ifdef NZ_EXP_NO_SLOW
+        pos += (e >> 10) & 15u; return e & 1023u;
+#else
         if (__builtin_expect(e < 0x8000u, 1)) { pos += e >> 10; return e & 1023u; }
         return next_slow(e, w32);
+#endif
     }
     __device__ inline uint32_t next_slow(uint32_t e, uint32_t w32) {
         uint32_t L = (e >> 10) & 15u, z = 0, esc = (e < 0xC000u);
@@ -262,15 +307,15 @@ struct HuffReader {
             if (e2 < 0xC000u) {
                 L = kPrimaryBits + ((e2 >> 10) & 7u); z = e2 & 1023u; esc = (e2 >= 0x8000u);
             } else {                                                     // longer than 17 bits or unassigned: search
-                const volatile uint32_t* vfirst = T->first; const volatile uint32_t* vcnt = T->cnt;
-                const volatile uint32_t* vidx0 = T->idx0;
                 uint32_t code = 0, sy = 1;
                 L = 0;
 #pragma unroll 1
                 for (uint32_t l = 1; l <= kMaxLen; l++) {
+                    uint32_t li = l;
+                    asm volatile("" : "+v"(li));                         // keeps the table reads inside this rare loop
                     code = (code << 1) | ((w32 >> (l - 1)) & 1u);
-                    const uint32_t d = code - vfirst[l];
-                    if (d < vcnt[l]) { sy = T->sorted[vidx0[l] + d]; L = l; break; }
+                    const uint32_t d = code - T->first[li];
+                    if (d < T->cnt[li]) { sy = T->sorted[T->idx0[li] + d]; L = l; break; }
                 }
                 if (L == 0) { bad = 1; L = 1; sy = 1; }
                 z = sy - 1u; esc = (sy == 0);
@@ -278,7 +323,7 @@ struct HuffReader {
         }
         pos += L;
         if (esc) { z = peek(); pos += 32u; }                             // escape: the 32 raw bits of z follow
-        if (pos >= 224u) reload();
+        if (pos >= kWinSlowLimit) reload();
         return z;
     }
 };
@@ -305,7 +350,6 @@ struct DirectFetch {
 };
 
 constexpr uint32_t kTileR = 16;                      // symbols per thread between two coalesced output phases
-constexpr uint32_t kRun = 8;                         // symbols between two window reloads
 constexpr uint32_t kTileStride = kTileR + 1;         // odd row stride: conflict-free column writes
 
 struct DecShared {
@@ -378,7 +422,7 @@ __device__ inline void emit4(const DecodeArgs& A, const SegCtx& C, uint32_t e, u
 template <int MODE, int KA, int KB>
 __device__ inline void run_segments(const DecodeArgs& A, const SegCtx& C, HuffReader& ra, HuffReader& rb,
                                     const DirectFetch& da, const DirectFetch& db, DecShared* S,
-                                    uint32_t* s_h, uint32_t ncs, uint32_t& overflow) {
+                                    uint32_t* s_h, uint32_t ncs, uint32_t ca, uint32_t cb, uint32_t& overflow) {
     const uint32_t tid = C.tid;
     const uint32_t copy = C.lane & ((1u << ncs) - 1u);
     uint32_t* tile = S->u.tile;
@@ -393,27 +437,37 @@ __device__ inline void run_segments(const DecodeArgs& A, const SegCtx& C, HuffRe
         e++;
         return combine<ANY_RAW>(ta, KA == KIND_RAW, tb, KB == KIND_RAW, A.step, overflow);
     };
+    uint32_t due_a = 1, due_b = 1;                                       // runs left until the next scheduled reload
+    auto start_run = [&]() {
+        if (KA == KIND_HUFF) {
+            const bool sched = (--due_a == 0);                           // uniform over the workgroup
+            if (sched) due_a = ca;
+            if (sched || ra.pos >= kWinRunLimit) ra.reload();
+        }
+        if (MODE == 1 && KB == KIND_HUFF) {
+            const bool sched = (--due_b == 0);
+            if (sched) due_b = cb;
+            if (sched || rb.pos >= kWinRunLimit) rb.reload();
+        }
+    };
     for (uint32_t r0 = 0; r0 < kSeg; r0 += kTileR) {
         uint32_t* row = tile + tid * kTileStride;
         if (r0 + kTileR <= C.cntseg) {                                   // full run: static tile offsets
 #pragma unroll
             for (uint32_t h = 0; h < kTileR; h += kRun) {
-                if (KA == KIND_HUFF) ra.reload();
-                if (MODE == 1 && KB == KIND_HUFF) rb.reload();
+                start_run();
 #pragma unroll
                 for (uint32_t r = 0; r < kRun; r++) row[h + r] = produce();
             }
         } else if (r0 < C.cntseg) {
             const uint32_t nr = C.cntseg - r0;
             for (uint32_t r = 0; r < nr; r++) {
-                if ((r % kRun) == 0) {
-                    if (KA == KIND_HUFF) ra.reload();
-                    if (MODE == 1 && KB == KIND_HUFF) rb.reload();
-                }
+                if ((r % kRun) == 0) start_run();
                 row[r] = produce();
             }
         }
         __syncthreads();
+#ifndef NZ_EXP_NO_OUTPUT
 #pragma unroll
         for (uint32_t k = 0; k < LPR; k++) {
             const uint32_t g = tid + kDecThreads * k;
@@ -427,11 +481,82 @@ __device__ inline void run_segments(const DecodeArgs& A, const SegCtx& C, HuffRe
                 emit4<MODE>(A, C, eo, m, t, MODE == 0 ? false : ANY_RAW, s_h, ncs, copy, zmax);
             }
         }
+#endif
         __syncthreads();
     }
     if (MODE == 1) {
         zmax = wave_max(zmax);
         if (C.lane == 0) atomicMax(&S->zmax, zmax);
+    }
+}
+
+// Decompress of a HUFFMAN frame.  Same scheme as run_segments, but the tile holds 16-bit zigzag codes, 32 per
+// thread between two output phases, so that eight lanes write one thread's run as a full 128-byte line.  A
+// code that does not fit 16 bits (an escape with a large value) is stored straight to global memory by the
+// decoding lane and leaves the marker 0xFFFF in the tile; the output phase writes around it.
+constexpr uint32_t kTile16R = 32;
+constexpr uint32_t kTile16Stride = kTile16R + 2;     // halfwords per row: 17 words, an odd word stride
+
+__device__ inline void run_decompress_huff(const DecodeArgs& A, const SegCtx& C, HuffReader& ra, DecShared* S, uint32_t ca) {
+    static_assert(kDecThreads * kTile16Stride * 2 <= sizeof(S->u.tile), "16-bit tile must fit the tile storage");
+    const uint32_t tid = C.tid;
+    uint16_t* tile = reinterpret_cast<uint16_t*>(S->u.tile);
+    uint32_t* row32 = reinterpret_cast<uint32_t*>(tile + tid * kTile16Stride);
+    float* seg_out = A.out + C.f0 + C.e0;
+    uint32_t e = 0;                                   // symbols of my segment decoded so far
+    uint32_t due = 1;
+    auto start_run = [&]() {
+        const bool sched = (--due == 0);              // uniform over the workgroup
+        if (sched) due = ca;
+        if (sched || ra.pos >= kWinRunLimit) ra.reload();
+    };
+    auto next16 = [&]() -> uint32_t {
+        uint32_t z = ra.next();
+        if (__builtin_expect(z >= 0xFFFFu, 0)) { seg_out[e] = dequantize1(unzigzag(z), A.step); z = 0xFFFFu; }
+        e++;
+        return z;
+    };
+    constexpr uint32_t LPR = kTile16R / 4;            // 8 lanes write one row
+    for (uint32_t r0 = 0; r0 < kSeg; r0 += kTile16R) {
+        if (r0 + kTile16R <= C.cntseg) {
+#pragma unroll
+            for (uint32_t h = 0; h < kTile16R; h += kRun) {
+                start_run();
+#pragma unroll
+                for (uint32_t r = 0; r < kRun; r += 2) {
+                    const uint32_t z0 = next16(), z1 = next16();
+                    row32[(h + r) / 2] = z0 | (z1 << 16);
+                }
+            }
+        } else if (r0 < C.cntseg) {
+            const uint32_t nr = C.cntseg - r0;
+            uint16_t* row = tile + tid * kTile16Stride;
+            for (uint32_t r = 0; r < nr; r++) {
+                if ((r % kRun) == 0) start_run();
+                row[r] = (uint16_t)next16();
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (uint32_t k = 0; k < LPR; k++) {
+            const uint32_t g = tid + kDecThreads * k;
+            const uint32_t rw = g / LPR, c = (g % LPR) * 4;
+            const uint32_t eo = (C.first_seg + rw) * kSeg + r0 + c;              // element index in the frame
+            if (eo < C.nf) {
+                const uint32_t m = (C.nf - eo < 4) ? (C.nf - eo) : 4u;
+                const uint32_t* src = reinterpret_cast<const uint32_t*>(tile + rw * kTile16Stride + c);
+                const uint32_t p0 = src[0], p1 = src[1];
+                const uint32_t z[4] = { p0 & 0xFFFFu, p0 >> 16, p1 & 0xFFFFu, p1 >> 16 };
+                float v[4];
+#pragma unroll
+                for (uint32_t j = 0; j < 4; j++) v[j] = dequantize1(unzigzag(z[j]), A.step);
+                float* dst = A.out + C.f0 + eo;
+                const bool marked = (z[0] == 0xFFFFu) | (z[1] == 0xFFFFu) | (z[2] == 0xFFFFu) | (z[3] == 0xFFFFu);
+                if (C.vec_ok && m == 4 && !marked) *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+                else for (uint32_t j = 0; j < m; j++) if (z[j] != 0xFFFFu) dst[j] = v[j];
+            }
+        }
+        __syncthreads();
     }
 }
 
@@ -499,6 +624,7 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(DecodeArgs A) {
 
     FrameView va, vb;
     va.status = ST_OK; va.kind = KIND_ZERO; va.w = 0; va.words = nullptr; va.nwords = 0; va.segt = nullptr; va.seg_prefix = 0;
+    va.cadence = 1;
     vb = va;
     if (st_a == ST_OK && (MODE == 0 || st_b == ST_OK)) {
         open_frame<kDecThreads>(A.a, total_a, frame, nf, first_seg, A, &s_t[0], &S.u.build, va);
@@ -535,8 +661,8 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(DecodeArgs A) {
     const uint32_t* safe = reinterpret_cast<const uint32_t*>(A.res);
     HuffReader ra, rb;
     DirectFetch da, dbf;
-    ra.init(va, &s_t[0], bit_a, safe, &s_win.w[0][tid * kWinWords]);
-    rb.init(vb, &s_t[MODE == 1 ? 1 : 0], bit_b, safe, &s_win.w[MODE == 1 ? 1 : 0][tid * kWinWords]);
+    ra.init(va, &s_t[0], bit_a, safe, &s_win.w[0][tid]);
+    rb.init(vb, &s_t[MODE == 1 ? 1 : 0], bit_b, safe, &s_win.w[MODE == 1 ? 1 : 0][tid]);
     da.init(va, safe);
     dbf.init(vb, safe);
     SegCtx C;
@@ -544,9 +670,13 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(DecodeArgs A) {
     C.vec_ok = ((f0 & 3u) == 0);
     uint32_t overflow = 0;
 
+#ifdef NZ_EXP_NO_DECODE
+    if (tid == 0 && va.cadence == 77) res->reserved = bit_a + bit_b;
+    return;
+#endif
     if (MODE == 0) {
         if (va.kind == KIND_HUFF) {
-            run_segments<0, KIND_HUFF, KIND_FIXED>(A, C, ra, rb, da, dbf, &S, s_h, 0, overflow);
+            run_decompress_huff(A, C, ra, &S, va.cadence);
             if (seg_valid && (ra.bad || ra.consumed() != seglen_a)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
         } else {
             run_elementwise<0>(A, C, blk0, da, dbf, &S, s_h, 0, overflow);
@@ -563,11 +693,11 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(DecodeArgs A) {
     const bool out_raw = (va.kind == KIND_RAW) || (vb.kind == KIND_RAW);      // uniform over the frame
     const bool ha = va.kind == KIND_HUFF, hb = vb.kind == KIND_HUFF;
     if (!ha && !hb) run_elementwise<1>(A, C, blk0, da, dbf, &S, s_h, ncs, overflow);
-    else if (ha && hb) run_segments<1, KIND_HUFF, KIND_HUFF>(A, C, ra, rb, da, dbf, &S, s_h, ncs, overflow);
-    else if (ha && vb.kind == KIND_RAW) run_segments<1, KIND_HUFF, KIND_RAW>(A, C, ra, rb, da, dbf, &S, s_h, ncs, overflow);
-    else if (ha) run_segments<1, KIND_HUFF, KIND_FIXED>(A, C, ra, rb, da, dbf, &S, s_h, ncs, overflow);
-    else if (va.kind == KIND_RAW) run_segments<1, KIND_RAW, KIND_HUFF>(A, C, ra, rb, da, dbf, &S, s_h, ncs, overflow);
-    else run_segments<1, KIND_FIXED, KIND_HUFF>(A, C, ra, rb, da, dbf, &S, s_h, ncs, overflow);
+    else if (ha && hb) run_segments<1, KIND_HUFF, KIND_HUFF>(A, C, ra, rb, da, dbf, &S, s_h, ncs, va.cadence, vb.cadence, overflow);
+    else if (ha && vb.kind == KIND_RAW) run_segments<1, KIND_HUFF, KIND_RAW>(A, C, ra, rb, da, dbf, &S, s_h, ncs, va.cadence, vb.cadence, overflow);
+    else if (ha) run_segments<1, KIND_HUFF, KIND_FIXED>(A, C, ra, rb, da, dbf, &S, s_h, ncs, va.cadence, vb.cadence, overflow);
+    else if (va.kind == KIND_RAW) run_segments<1, KIND_RAW, KIND_HUFF>(A, C, ra, rb, da, dbf, &S, s_h, ncs, va.cadence, vb.cadence, overflow);
+    else run_segments<1, KIND_FIXED, KIND_HUFF>(A, C, ra, rb, da, dbf, &S, s_h, ncs, va.cadence, vb.cadence, overflow);
     if (seg_valid) {
         if (ha && (ra.bad || ra.consumed() != seglen_a)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
         if (hb && (rb.bad || rb.consumed() != seglen_b)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
