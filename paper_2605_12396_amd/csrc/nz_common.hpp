@@ -27,8 +27,9 @@ enum : uint32_t { CODEC_RAW = 0, CODEC_FIXED = 1, CODEC_HUFF = 2 };
 constexpr uint32_t kStatThreads   = 512;
 constexpr uint32_t kStatBlock     = 32768;       // symbols per statistics workgroup (compress)
 constexpr uint32_t kEncThreads    = 256;
-constexpr uint32_t kEncBlock      = 8192;        // symbols per encode workgroup = 32 segments
-constexpr uint32_t kEncIters      = kEncBlock / (kEncThreads * 4);   // 8 passes of 1024 symbols
+constexpr uint32_t kEncBlock      = 4096;        // symbols per encode workgroup = 16 segments
+constexpr uint32_t kEncIters      = kEncBlock / (kEncThreads * 4);   // passes of 1024 symbols
+constexpr uint32_t kEncSegs       = kEncBlock / kSeg;                // segments per encode workgroup
 constexpr uint32_t kDecThreads    = 256;
 constexpr uint32_t kDecBlock      = kDecThreads * kSeg;              // 65536 symbols per decode workgroup
 constexpr uint32_t kBookThreads   = 1024;
@@ -54,7 +55,7 @@ static_assert(sizeof(FrameMeta) == 64, "FrameMeta is 64 bytes");
 // ---- control block at the start of the workspace (zeroed at the start of every call) ----
 struct Ctrl {
     uint32_t ticket_book;   // dynamic workgroup ids: look-back only ever waits on smaller tickets
-    uint32_t ticket_enc;
+    uint32_t unused_;
     uint32_t frames_done;
     uint32_t pad[13];
 };
@@ -62,7 +63,7 @@ static_assert(sizeof(Ctrl) == 64, "Ctrl is 64 bytes");
 
 // Workspace carve-up; computed identically on host for sizing and launch.
 struct WsLayout {
-    size_t ctrl, frame_desc, blk_desc, blk_tail, zero_end;   // [ctrl, zero_end) is cleared per call
+    size_t ctrl, frame_desc, frame_ticket, blk_desc, blk_tail, zero_end;   // [ctrl, zero_end) is cleared per call
     size_t meta, book_code, book_len, phist, pmeta, codes, total;
 };
 
@@ -76,6 +77,7 @@ __host__ inline WsLayout ws_layout(size_t n, uint32_t chunk, uint32_t stat_block
     size_t o = 0;
     L.ctrl = o;        o += sizeof(Ctrl);
     L.frame_desc = o;  o += align_up(8 * n_frames, 256);
+    L.frame_ticket = o; o += align_up(4 * n_frames, 256);
     L.blk_desc = o;    o += align_up(8 * n_frames * ebpf, 256);
     L.blk_tail = o;    o += align_up(4 * n_frames * ebpf, 256);
     L.zero_end = o;
@@ -112,6 +114,17 @@ __device__ inline uint32_t wave_incl_scan(uint32_t v) {
         uint32_t t = __shfl_up(v, d, 64);
         if ((int)lane_id() >= d) v += t;
     }
+    return v;
+}
+// Inclusive wave scan on the DPP network (no LDS traffic): Kogge-Stone inside each row of 16 lanes, then the
+// last lane of row 0 / 2 is added to row 1 / 3 and the last lane of the lower half to the upper half.
+__device__ inline uint32_t wave_incl_scan_dpp(uint32_t v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, true);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, true);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, true);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, true);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false);  // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);  // row_bcast:31 into rows 2 and 3
     return v;
 }
 __device__ inline uint32_t wave_sum(uint32_t v) {

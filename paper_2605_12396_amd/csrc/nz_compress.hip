@@ -319,37 +319,73 @@ __global__ __launch_bounds__(kBookThreads) void k_codebook(CompressArgs A) {
 // ------------------------------------------------------------------------------------------------
 template <int SRC>
 __global__ __launch_bounds__(kEncThreads) void k_encode(CompressArgs A) {
-    __shared__ uint32_t s_code[kMaxK];
-    __shared__ uint8_t s_len[kMaxK];
-    __shared__ uint32_t s_stage[2048];
-    __shared__ uint32_t s_wtot[4], s_seglen[32];
+    constexpr uint32_t kStageWords = 2048;
+    __shared__ uint64_t s_book[kMaxK];            // reversed code | length << 32
+    __shared__ uint32_t s_stage[kStageWords];
+    __shared__ uint32_t s_wtot[kEncSegs];         // bit count of each of the block's segments
+    __shared__ uint32_t s_pbase[kEncIters + 1];   // bit offset of every pass inside the block
     __shared__ uint32_t s_bid, s_first_word, s_first_taken, s_lastw;
     __shared__ uint64_t s_excl;
 
     const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
-    Ctrl* ctrl = reinterpret_cast<Ctrl*>(A.ws + A.L.ctrl);
-    if (tid == 0) { s_bid = atomicAdd(&ctrl->ticket_enc, 1u); s_first_taken = 0; s_first_word = 0; s_lastw = 0; }
-    __syncthreads();
-    const uint32_t bid = s_bid;
+    // The frame is fixed by the launch index; the position inside the frame is a ticket from the frame's own
+    // counter, so the in-frame look-back only ever waits on workgroups that already run, and the tickets of
+    // different frames do not serialise on one address.
     const uint32_t ebpf = (A.chunk + kEncBlock - 1) / kEncBlock;
-    const uint32_t frame = bid / ebpf, bif = bid % ebpf;
+    const uint32_t frame = blockIdx.x / ebpf;
+    if (tid == 0) {
+#ifdef NZ_EXP_ENC_NO_TICKET
+        s_bid = blockIdx.x % ebpf;
+#else
+        s_bid = atomicAdd(reinterpret_cast<uint32_t*>(A.ws + A.L.frame_ticket) + frame, 1u);
+#endif
+        s_first_taken = 0; s_first_word = 0; s_lastw = 0;
+    }
+    __syncthreads();
+    const uint32_t bif = s_bid;
     const uint64_t f0 = (uint64_t)frame * A.chunk;
     const uint32_t nf = (uint32_t)((A.n - f0 < A.chunk) ? (A.n - f0) : A.chunk);
     const uint32_t blk0 = bif * kEncBlock;
     if (blk0 >= nf) return;
-    const FrameMeta M = reinterpret_cast<const FrameMeta*>(A.ws + A.L.meta)[frame];
-    if (!M.fits) return;
     const uint32_t cnt = (nf - blk0 < kEncBlock) ? (nf - blk0) : kEncBlock;
     const bool last_blk = (blk0 + cnt == nf);
-    uint8_t* fr = A.out + M.offset;
     const uint32_t K = A.K;
-    const uint32_t* codes_ws = reinterpret_cast<const uint32_t*>(A.ws + A.L.codes);
+    // source words of this block: fp32 input (SRC 0) or the staged codes / fp32 sums of the reduce (SRC 1)
+    const uint32_t* src = (SRC == 0 ? reinterpret_cast<const uint32_t*>(A.in) : reinterpret_cast<const uint32_t*>(A.ws + A.L.codes)) + f0 + blk0;
+    const bool vec_ok = (((f0 + blk0) & 3u) == 0);
+
+    // ---- issue all loads of the block first: pass `it` covers symbols it*1024 + tid*4 .. +3 ----
+    uint32_t raw[kEncIters][4];
+#pragma unroll
+    for (uint32_t it = 0; it < kEncIters; it++) {
+        const uint32_t i = it * 1024 + tid * 4;
+        const uint32_t mvalid = (i < cnt) ? ((cnt - i < 4) ? (cnt - i) : 4u) : 0u;
+        if (vec_ok && mvalid == 4) {
+            const uint4 t = *reinterpret_cast<const uint4*>(src + i);
+            raw[it][0] = t.x; raw[it][1] = t.y; raw[it][2] = t.z; raw[it][3] = t.w;
+        } else {
+#pragma unroll
+            for (uint32_t j = 0; j < 4; j++) raw[it][j] = (j < mvalid) ? src[i + j] : 0u;
+        }
+    }
+    const FrameMeta M = reinterpret_cast<const FrameMeta*>(A.ws + A.L.meta)[frame];
+    if (!M.fits) return;
+    uint8_t* fr = A.out + M.offset;
+    // zigzag code of a source word
+    auto zz = [&](uint32_t w) -> uint32_t {
+        if (SRC == 0) { int32_t t; quantize1(__uint_as_float(w), A.eb, A.step, A.inv_step, t); return zigzag(t); }
+        return zigzag((int32_t)w);
+    };
 
     // ---- RAW: copy this block's words, the last block zero-fills the frame padding ----
     if (M.codec == CODEC_RAW) {
         uint32_t* dst = reinterpret_cast<uint32_t*>(fr + kHdrBytes) + blk0;
-        const uint32_t* src = (SRC == 0) ? reinterpret_cast<const uint32_t*>(A.in) + f0 + blk0 : codes_ws + f0 + blk0;
-        for (uint32_t i = tid; i < cnt; i += kEncThreads) dst[i] = src[i];
+#pragma unroll
+        for (uint32_t it = 0; it < kEncIters; it++) {
+            const uint32_t i = it * 1024 + tid * 4;
+            if (vec_ok && i + 4 <= cnt) *reinterpret_cast<uint4*>(dst + i) = make_uint4(raw[it][0], raw[it][1], raw[it][2], raw[it][3]);
+            else for (uint32_t j = 0; j < 4; j++) if (i + j < cnt) dst[i + j] = raw[it][j];
+        }
         if (last_blk) {
             const uint32_t w0 = (kHdrBytes + 4u * nf) / 4, w1 = M.total / 4;
             if (tid < w1 - w0) reinterpret_cast<uint32_t*>(fr)[w0 + tid] = 0;
@@ -357,136 +393,180 @@ __global__ __launch_bounds__(kEncThreads) void k_encode(CompressArgs A) {
         return;
     }
 
-    // ---- load this thread's 32 symbols: pass `it` covers symbols it*1024 + tid*4 .. +3 of the block ----
-    int32_t q[kEncIters][4];
-    {
-        const bool vec_ok = (((f0 + blk0) & 3u) == 0);
+    uint32_t* bits = reinterpret_cast<uint32_t*>(fr + M.bits_off);
+
+    // ---- FIXEDLEN: w bits per code at closed-form positions; a pass of 1024 codes is 32*w whole words ----
+    if (M.codec == CODEC_FIXED) {
+        const uint32_t w = M.w;
+        const uint32_t wblk = (blk0 / 32u) * w;                          // first bitstream word of this block
 #pragma unroll
         for (uint32_t it = 0; it < kEncIters; it++) {
-            const uint32_t i = it * 1024 + tid * 4;
-            const uint32_t mvalid = (i < cnt) ? ((cnt - i < 4) ? (cnt - i) : 4u) : 0u;
-            if (SRC == 0) {
-                const float* src = A.in + f0 + blk0;
-                float v[4] = { 0.f, 0.f, 0.f, 0.f };
-                if (vec_ok && mvalid == 4) {
-                    const float4 t = *reinterpret_cast<const float4*>(src + i);
-                    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
-                } else {
-                    for (uint32_t j = 0; j < 4; j++) if (j < mvalid) v[j] = src[i + j];
-                }
+            if (it * 1024 < cnt) {
+                const uint32_t i = it * 1024 + tid * 4;
+                const uint32_t pass_syms = (cnt - it * 1024 < 1024u) ? (cnt - it * 1024) : 1024u;
+                const uint32_t pass_words = (pass_syms * w + 31u) / 32u;
+                for (uint32_t k = tid; k < pass_words; k += kEncThreads) s_stage[k] = 0;
+                __syncthreads();
+                uint32_t pos = tid * 4 * w;
 #pragma unroll
-                for (uint32_t j = 0; j < 4; j++) { int32_t t; quantize1(v[j], A.eb, A.step, A.inv_step, t); q[it][j] = t; }
-            } else {
-                const uint32_t* src = codes_ws + f0 + blk0;
-                if (vec_ok && mvalid == 4) {
-                    const uint4 t = *reinterpret_cast<const uint4*>(src + i);
-                    q[it][0] = (int32_t)t.x; q[it][1] = (int32_t)t.y; q[it][2] = (int32_t)t.z; q[it][3] = (int32_t)t.w;
-                } else {
-#pragma unroll
-                    for (uint32_t j = 0; j < 4; j++) q[it][j] = (j < mvalid) ? (int32_t)src[i + j] : 0;
+                for (uint32_t j = 0; j < 4; j++) {
+                    if (i + j < cnt && w) {
+                        const uint32_t z = zz(raw[it][j]);
+                        const uint32_t sh = pos & 31u, wi = pos >> 5;
+                        atomicOr(&s_stage[wi], z << sh);
+                        if (sh + w > 32u) atomicOr(&s_stage[wi + 1], z >> (32u - sh));
+                        pos += w;
+                    }
                 }
+                __syncthreads();
+                uint32_t* dst = bits + wblk + it * 32u * w;
+                for (uint32_t k = tid; k < pass_words; k += kEncThreads) dst[k] = s_stage[k];
+                __syncthreads();
             }
         }
+        if (last_blk) {
+            const uint32_t w0 = M.bits_off / 4 + M.bits_words, w1 = M.total / 4;
+            if (tid < w1 - w0) reinterpret_cast<uint32_t*>(fr)[w0 + tid] = 0;
+        }
+        return;
     }
 
-    const bool huff = (M.codec == CODEC_HUFF);
+    // ---- HUFFMAN ----
+    uint64_t pk[kEncIters];                       // the thread's 4 symbols of a pass packed LSB-first
+    uint32_t ln[kEncIters];                       // exclusive bit offset of the thread inside its pass
+    uint32_t wide = 0;                            // pass mask: the 4 symbols need more than 64 bits
     uint32_t start_bit = 0;                       // first bit of this block inside the frame's bitstream
-    if (huff) {
+
+    {
         for (uint32_t s = tid; s < K; s += kEncThreads) {
-            s_code[s] = reinterpret_cast<const uint32_t*>(A.ws + A.L.book_code)[(size_t)frame * kMaxK + s];
-            s_len[s] = (A.ws + A.L.book_len)[(size_t)frame * kMaxK + s];
+            const uint32_t c = reinterpret_cast<const uint32_t*>(A.ws + A.L.book_code)[(size_t)frame * kMaxK + s];
+            const uint32_t l = (A.ws + A.L.book_len)[(size_t)frame * kMaxK + s];
+            s_book[s] = (uint64_t)c | ((uint64_t)l << 32);
         }
         __syncthreads();
-        // phase 1: bit count of every segment (= one wave pass) and of the block
-        uint16_t* segt = reinterpret_cast<uint16_t*>(fr + M.segt_off);
-        const uint32_t nseg = (nf + kSeg - 1) / kSeg;
+        // phase 1: look every symbol up once; pack the 4 symbols of a pass (code, and the 32 raw bits of an
+        // escape) into 64 bits; scan the bit counts
 #pragma unroll
         for (uint32_t it = 0; it < kEncIters; it++) {
             const uint32_t i = it * 1024 + tid * 4;
+            uint64_t acc = 0;
             uint32_t tl = 0;
 #pragma unroll
             for (uint32_t j = 0; j < 4; j++) {
                 if (i + j < cnt) {
-                    const uint32_t sy = sym_of(zigzag(q[it][j]), K);
-                    tl += s_len[sy] + (sy == 0 ? 32u : 0u);
+#ifdef NZ_EXP_ENC_NO_PHASE1
+                    const uint32_t z = raw[it][j] & 7u, sy = 1;
+                    const uint64_t b = (uint64_t)z | (3ull << 32);
+#else
+                    const uint32_t z = zz(raw[it][j]);
+                    const uint32_t sy = sym_of(z, K);
+                    const uint64_t b = s_book[sy];
+#endif
+                    if (tl < 64u) acc |= (uint64_t)(uint32_t)b << tl;
+                    tl += (uint32_t)(b >> 32);
+                    if (sy == 0) { if (tl < 64u) acc |= (uint64_t)z << tl; tl += 32u; }
                 }
             }
-            tl = wave_sum(tl);
-            if (lane == 0) {
-                const uint32_t g = it * 4 + wave;                       // segment index inside the block
-                s_seglen[g] = tl;
-                const uint32_t gseg = blk0 / kSeg + g;
-                if (gseg < nseg) segt[gseg] = (uint16_t)tl;
-                if (last_blk && gseg == nseg - 1 && (nseg & 1u)) segt[nseg] = 0;   // pad4 of the table
-            }
+            pk[it] = acc;
+            wide |= (tl > 64u ? 1u : 0u) << it;
+            const uint32_t incl = wave_incl_scan_dpp(tl);
+            ln[it] = incl - tl;                                       // exclusive inside the wave's segment
+            if (lane == 63) s_wtot[it * 4 + wave] = incl;             // bits of segment it*4 + wave
         }
         __syncthreads();
+        uint32_t block_bits = 0;
+#pragma unroll
+        for (uint32_t it = 0; it < kEncIters; it++) {
+            if (tid == 0) s_pbase[it] = block_bits;
+#pragma unroll
+            for (uint32_t w = 0; w < 4; w++) {
+                const uint32_t t = s_wtot[it * 4 + w];
+                if (w < wave) ln[it] += t;                                // now exclusive inside the pass
+                block_bits += t;
+            }
+        }
+        if (tid == 0) s_pbase[kEncIters] = block_bits;
+        uint16_t* segt = reinterpret_cast<uint16_t*>(fr + M.segt_off);
+        const uint32_t nseg = (nf + kSeg - 1) / kSeg;
+        if (tid < kEncSegs) {
+            const uint32_t gseg = blk0 / kSeg + tid;
+            if (gseg < nseg) segt[gseg] = (uint16_t)s_wtot[tid];
+            if (last_blk && gseg == nseg - 1 && (nseg & 1u)) segt[nseg] = 0;   // pad4 of the table
+        }
         uint64_t* bdesc = reinterpret_cast<uint64_t*>(A.ws + A.L.blk_desc) + (size_t)frame * ebpf;
+#ifdef NZ_EXP_ENC_NO_LOOKBACK
+        if (tid == 0) s_excl = (uint64_t)bif * 32u * 600u;
+        (void)bdesc;
+#else
         if (wave == 0) {
-            uint32_t t = (lane < 32) ? s_seglen[lane] : 0u;
-            t = wave_sum(t);
+            const uint32_t t = block_bits;
             if (lane == 0) st_agent(bdesc + bif, kDescA | (uint64_t)t);
             const uint64_t excl = lookback_exclusive(bdesc, 0, (int64_t)bif, 0);
             if (lane == 0) { st_agent(bdesc + bif, kDescP | (excl + t)); s_excl = excl; }
         }
+#endif
+        for (uint32_t i = tid; i < kStageWords; i += kEncThreads) s_stage[i] = 0;
         __syncthreads();
         start_bit = (uint32_t)s_excl;
-    } else {
-        start_bit = blk0 * M.w;                   // multiple of 32: blk0 is a multiple of 8192
     }
 
-    // phase 2: pack
-    for (uint32_t i = tid; i < 2048; i += kEncThreads) s_stage[i] = 0;
-    __syncthreads();
-    uint32_t* bits = reinterpret_cast<uint32_t*>(fr + M.bits_off);
+    // phase 2: OR the passes into the LDS stage at their final bit positions (stage word 0 is stream word
+    // w_first of the bitstream), as many passes at a time as fit, then flush whole words coalesced
     const uint32_t c0 = start_bit & 31u;          // bits of the first word owned by the predecessor
     const uint32_t w_first = start_bit >> 5;
-    uint32_t carry = c0, wpos = w_first;
-    const uint32_t wfix = M.w;
+    uint32_t flushed = 0;                         // words of the stage origin already written out
+    uint32_t it0 = 0;
+#ifdef NZ_EXP_ENC_NO_PHASE2
+    it0 = kEncIters;
+#endif
+    while (it0 < kEncIters && it0 * 1024 < cnt) {
+        // passes [it0, it1) fit the stage
+        uint32_t it1 = it0 + 1;
+        while (it1 < kEncIters && c0 + s_pbase[it1 + 1] - 32u * flushed <= 32u * (kStageWords - 2)) it1++;
 #pragma unroll
-    for (uint32_t it = 0; it < kEncIters; it++) {
-        if (it * 1024 >= cnt) continue;            // uniform over the workgroup; q[it] stays a static index
-        const uint32_t i = it * 1024 + tid * 4;
-        uint32_t val[4], len[4], esc[4], tl = 0;
+        for (uint32_t it = 0; it < kEncIters; it++) {
+            if (it >= it0 && it < it1) {
+                const uint32_t i = it * 1024 + tid * 4;
+                uint32_t pos = c0 + s_pbase[it] + ln[it] - 32u * flushed;
+                if (!((wide >> it) & 1u)) {
+                    const uint64_t a = pk[it];
+                    if (a) {
+                        const uint32_t sh = pos & 31u, wi = pos >> 5;
+                        const uint64_t t = a << sh;
+                        atomicOr(&s_stage[wi], (uint32_t)t);
+                        if ((uint32_t)(t >> 32)) atomicOr(&s_stage[wi + 1], (uint32_t)(t >> 32));
+                        if (sh) { const uint32_t hi = (uint32_t)(a >> (64u - sh)); if (hi) atomicOr(&s_stage[wi + 2], hi); }
+                    }
+                } else {
+                    // the pass needs more than 64 bits (rare): reload its 4 source words, emit symbol by symbol
 #pragma unroll
-        for (uint32_t j = 0; j < 4; j++) {
-            val[j] = 0; len[j] = 0; esc[j] = 0;
-            if (i + j < cnt) {
-                const uint32_t z = zigzag(q[it][j]);
-                if (huff) {
-                    const uint32_t sy = sym_of(z, K);
-                    val[j] = s_code[sy]; len[j] = s_len[sy];
-                    if (sy == 0) { esc[j] = 1; }
-                } else { val[j] = z; len[j] = wfix; }
-                tl += len[j] + (esc[j] ? 32u : 0u);
+                    for (uint32_t j = 0; j < 4; j++) {
+                        if (i + j < cnt) {
+                            const uint32_t z = zz(src[i + j]);
+                            const uint32_t sy = sym_of(z, K);
+                            const uint64_t b = s_book[sy];
+                            const uint32_t val = (uint32_t)b, len = (uint32_t)(b >> 32);
+                            if (len) {
+                                const uint32_t sh = pos & 31u, wi = pos >> 5;
+                                atomicOr(&s_stage[wi], val << sh);
+                                if (sh + len > 32u) atomicOr(&s_stage[wi + 1], val >> (32u - sh));
+                                pos += len;
+                            }
+                            if (sy == 0) {
+                                const uint32_t sh = pos & 31u, wi = pos >> 5;
+                                atomicOr(&s_stage[wi], z << sh);
+                                if (sh) atomicOr(&s_stage[wi + 1], z >> (32u - sh));
+                                pos += 32u;
+                            }
+                        }
+                    }
+                }
             }
         }
-        const uint32_t incl = wave_incl_scan(tl);
-        if (lane == 63) s_wtot[wave] = incl;
         __syncthreads();
-        uint32_t pos = carry + incl - tl;
-        uint32_t total_it = 0;
-#pragma unroll
-        for (uint32_t w = 0; w < 4; w++) { if (w < wave) pos += s_wtot[w]; total_it += s_wtot[w]; }
-#pragma unroll
-        for (uint32_t j = 0; j < 4; j++) {
-            if (len[j]) {
-                const uint32_t sh = pos & 31u, wi = pos >> 5;
-                atomicOr(&s_stage[wi], val[j] << sh);
-                if (sh + len[j] > 32u) atomicOr(&s_stage[wi + 1], val[j] >> (32u - sh));
-                pos += len[j];
-            }
-            if (esc[j]) {
-                const uint32_t z = zigzag(q[it][j]);
-                const uint32_t sh = pos & 31u, wi = pos >> 5;
-                atomicOr(&s_stage[wi], z << sh);
-                if (sh) atomicOr(&s_stage[wi + 1], z >> (32u - sh));
-                pos += 32u;
-            }
-        }
-        __syncthreads();
-        const uint32_t nbits = carry + total_it;
+        const uint32_t nbits = c0 + s_pbase[it1] - 32u * flushed;       // bits now in the stage
         const uint32_t nw = nbits >> 5;
+        const uint32_t wpos = w_first + flushed;
         for (uint32_t k = tid; k < nw; k += kEncThreads) {
             const uint32_t wv = s_stage[k];
             if (c0 && wpos + k == w_first) { s_first_word = wv; s_first_taken = 1; }   // deferred: shared word
@@ -495,12 +575,15 @@ __global__ __launch_bounds__(kEncThreads) void k_encode(CompressArgs A) {
         const uint32_t partial = s_stage[nw];
         if (tid == 0 && nw) s_lastw = s_stage[nw - 1];
         __syncthreads();
-        for (uint32_t k = tid; k <= nw; k += kEncThreads) s_stage[k] = (k == 0) ? partial : 0u;
-        carry = nbits & 31u;
-        wpos += nw;
+        for (uint32_t k = tid; k <= nw + 2 && k < kStageWords; k += kEncThreads) s_stage[k] = (k == 0) ? partial : 0u;
+        flushed += nw;
+        it0 = it1;
         __syncthreads();
     }
     // tail: the word shared with the successor is the successor's to write; publish our last 31 bits
+    const uint32_t end_bit = c0 + s_pbase[kEncIters];                   // relative to stage origin (word w_first)
+    const uint32_t carry = end_bit & 31u;
+    const uint32_t wpos = w_first + flushed;
     const uint32_t partial = s_stage[0];
     uint32_t* btail = reinterpret_cast<uint32_t*>(A.ws + A.L.blk_tail) + (size_t)frame * ebpf;
     if (tid == 0) {
