@@ -63,8 +63,8 @@ static_assert(sizeof(Ctrl) == 64, "Ctrl is 64 bytes");
 
 // Workspace carve-up; computed identically on host for sizing and launch.
 struct WsLayout {
-    size_t ctrl, frame_desc, frame_ticket, blk_desc, blk_tail, zero_end;   // [ctrl, zero_end) is cleared per call
-    size_t meta, book_code, book_len, phist, pmeta, codes, total;
+    size_t ctrl, frame_desc, zero_end;      // [ctrl, zero_end) is cleared per call
+    size_t meta, book_code, book_len, phist, pmeta, grp_start, codes, total;
 };
 
 __host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -72,20 +72,17 @@ __host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a -
 __host__ inline WsLayout ws_layout(size_t n, uint32_t chunk, uint32_t stat_block, bool with_codes) {
     WsLayout L;
     const size_t n_frames = (n + chunk - 1) / chunk;
-    const size_t ebpf = (chunk + kEncBlock - 1) / kEncBlock;        // encode blocks per frame
     const size_t sbpf = (chunk + stat_block - 1) / stat_block;      // statistics blocks per frame
     size_t o = 0;
     L.ctrl = o;        o += sizeof(Ctrl);
     L.frame_desc = o;  o += align_up(8 * n_frames, 256);
-    L.frame_ticket = o; o += align_up(4 * n_frames, 256);
-    L.blk_desc = o;    o += align_up(8 * n_frames * ebpf, 256);
-    L.blk_tail = o;    o += align_up(4 * n_frames * ebpf, 256);
     L.zero_end = o;
     L.meta = o;        o += align_up(sizeof(FrameMeta) * n_frames, 256);
     L.book_code = o;   o += align_up(4 * (size_t)kMaxK * n_frames, 256);
     L.book_len = o;    o += align_up((size_t)kMaxK * n_frames, 256);
     L.phist = o;       o += align_up(4 * (size_t)kMaxK * n_frames * sbpf, 256);
     L.pmeta = o;       o += align_up(8 * n_frames * sbpf, 256);
+    L.grp_start = o;   o += align_up(4 * n_frames * sbpf, 256);
     L.codes = o;       if (with_codes) o += align_up(4 * n, 256);
     L.total = o;
     return L;

@@ -293,6 +293,32 @@ __global__ __launch_bounds__(kBookThreads) void k_codebook(CompressArgs A) {
         }
     }
     if (codec == CODEC_HUFF) {
+        // Exact bitstream position of every statistics block (= one encoder workgroup): its bit count is
+        // sum over symbols of (block count) x (code length), an escape carrying 32 more bits.  The encoder
+        // therefore needs no scan of its own.  The word in which two blocks meet is written by both with an
+        // atomic OR, so it is cleared here.
+        const uint32_t* ph = reinterpret_cast<const uint32_t*>(A.ws + A.L.phist) + (size_t)fid * A.sbpf * kMaxK;
+        for (uint32_t b = wave; b < sbc; b += kBookThreads / 64) {
+            uint64_t t = 0;
+            for (uint32_t sy = lane; sy < K; sy += 64) {
+                const uint32_t c = ph[(size_t)b * kMaxK + sy];
+                t += (uint64_t)c * (s_len[sy] + (sy == 0 ? 32u : 0u));
+            }
+            t = wave_sum64(t);
+            if (lane == 0) s_w[b] = (uint32_t)t;                          // s_w is free again: block bit counts
+        }
+        __syncthreads();
+        if (tid == 0) {
+            uint32_t* gs = reinterpret_cast<uint32_t*>(A.ws + A.L.grp_start) + (size_t)fid * A.sbpf;
+            uint32_t run = 0;
+            const uint32_t segt_off = kHdrBytes + (uint32_t)pad4u(nsym);
+            uint32_t* bitsw = reinterpret_cast<uint32_t*>(fr + segt_off + (uint32_t)pad4u(2ull * nseg));
+            for (uint32_t b = 0; b < sbc; b++) {
+                gs[b] = run;
+                if (fits && b > 0) bitsw[run >> 5] = 0;
+                run += s_w[b];
+            }
+        }
         if (fits) {   // code lengths, one byte per symbol, zero padded to 4
             const uint32_t words = (uint32_t)(pad4u(nsym) / 4);
             if (tid < words) reinterpret_cast<uint32_t*>(fr + kHdrBytes)[tid] = reinterpret_cast<const uint32_t*>(s_len)[tid];
@@ -306,14 +332,18 @@ __global__ __launch_bounds__(kBookThreads) void k_codebook(CompressArgs A) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// K4: encoder.  One workgroup per kEncBlock symbols of one frame.
+// K4: encoder.  One workgroup per statistics block of one frame (32768 symbols for compress, 65536 for
+// the reduce), worked through in sub-blocks of kEncBlock symbols; the next sub-block's source words are
+// loaded while the current one is packed.
 //   RAW      copy the words.
-//   FIXEDLEN w bits per zigzag code, positions in closed form (a block starts on a word boundary).
-//   HUFFMAN  phase 1: code lengths -> per-segment bit counts (written to the segment table) and the
-//            block's bit count, published for the in-frame decoupled look-back; phase 2: pack the codes
-//            of 1024 symbols at a time into an LDS stage with ds_or and flush whole words coalesced.
-//            Blocks are not word aligned: the word a block shares with its predecessor is written by the
-//            later block, which fetches the predecessor's last 31 stream bits from its tail descriptor.
+//   FIXEDLEN w bits per zigzag code at closed-form positions (a pass of 1024 codes is 32*w whole words).
+//   HUFFMAN  the workgroup's first bit in the frame's bitstream comes from the codebook kernel, so there is
+//            no scan and no waiting between workgroups.  Per sub-block: phase 1 looks every symbol up once,
+//            packs the 4 symbols of a thread (codes, and the 32 raw bits of an escape) into 64 bits and scans
+//            the bit counts on the DPP network (segment table entries fall out of the scan); phase 2 ORs the
+//            packed strings into an LDS stage at their final bit positions and flushes whole words
+//            coalesced.  The word in which two workgroups meet was cleared by the codebook kernel and
+//            receives both parts by atomic OR; every other word has a single writer.
 // SRC = 0: symbols are quantized from the fp32 input; SRC = 1: symbols are the int32 codes staged in the
 // workspace by the reduce front end (RAW frames hold fp32 bit patterns there).
 // ------------------------------------------------------------------------------------------------
@@ -322,52 +352,42 @@ __global__ __launch_bounds__(kEncThreads) void k_encode(CompressArgs A) {
     constexpr uint32_t kStageWords = 2048;
     __shared__ uint64_t s_book[kMaxK];            // reversed code | length << 32
     __shared__ uint32_t s_stage[kStageWords];
-    __shared__ uint32_t s_wtot[kEncSegs];         // bit count of each of the block's segments
-    __shared__ uint32_t s_pbase[kEncIters + 1];   // bit offset of every pass inside the block
-    __shared__ uint32_t s_bid, s_first_word, s_first_taken, s_lastw;
-    __shared__ uint64_t s_excl;
+    __shared__ uint32_t s_wtot[kEncSegs];         // bit count of each of the sub-block's segments
+    __shared__ uint32_t s_pbase[kEncIters + 1];   // bit offset of every pass inside the sub-block
 
     const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
-    // The frame is fixed by the launch index; the position inside the frame is a ticket from the frame's own
-    // counter, so the in-frame look-back only ever waits on workgroups that already run, and the tickets of
-    // different frames do not serialise on one address.
-    const uint32_t ebpf = (A.chunk + kEncBlock - 1) / kEncBlock;
-    const uint32_t frame = blockIdx.x / ebpf;
-    if (tid == 0) {
-#ifdef NZ_EXP_ENC_NO_TICKET
-        s_bid = blockIdx.x % ebpf;
-#else
-        s_bid = atomicAdd(reinterpret_cast<uint32_t*>(A.ws + A.L.frame_ticket) + frame, 1u);
-#endif
-        s_first_taken = 0; s_first_word = 0; s_lastw = 0;
-    }
-    __syncthreads();
-    const uint32_t bif = s_bid;
+    const uint32_t frame = blockIdx.x / A.sbpf, gb = blockIdx.x % A.sbpf;
     const uint64_t f0 = (uint64_t)frame * A.chunk;
     const uint32_t nf = (uint32_t)((A.n - f0 < A.chunk) ? (A.n - f0) : A.chunk);
-    const uint32_t blk0 = bif * kEncBlock;
-    if (blk0 >= nf) return;
-    const uint32_t cnt = (nf - blk0 < kEncBlock) ? (nf - blk0) : kEncBlock;
-    const bool last_blk = (blk0 + cnt == nf);
+    const uint32_t g0 = gb * A.stat_block;                               // first symbol of this workgroup in the frame
+    if (g0 >= nf) return;
+    const uint32_t gcnt = (nf - g0 < A.stat_block) ? (nf - g0) : A.stat_block;
+    const bool last_grp = (g0 + gcnt == nf);
+    const uint32_t nsub = (gcnt + kEncBlock - 1) / kEncBlock;
     const uint32_t K = A.K;
-    // source words of this block: fp32 input (SRC 0) or the staged codes / fp32 sums of the reduce (SRC 1)
-    const uint32_t* src = (SRC == 0 ? reinterpret_cast<const uint32_t*>(A.in) : reinterpret_cast<const uint32_t*>(A.ws + A.L.codes)) + f0 + blk0;
-    const bool vec_ok = (((f0 + blk0) & 3u) == 0);
+    // source words: fp32 input (SRC 0) or the staged codes / fp32 sums of the reduce (SRC 1)
+    const uint32_t* gsrc = (SRC == 0 ? reinterpret_cast<const uint32_t*>(A.in) : reinterpret_cast<const uint32_t*>(A.ws + A.L.codes)) + f0 + g0;
+    const bool vec_ok = (((f0 + g0) & 3u) == 0);                         // kEncBlock is a multiple of 4
 
-    // ---- issue all loads of the block first: pass `it` covers symbols it*1024 + tid*4 .. +3 ----
-    uint32_t raw[kEncIters][4];
+    // loads of one sub-block: pass `it` covers its symbols it*1024 + tid*4 .. +3
+    auto load_sub = [&](uint32_t sb, uint32_t (&raw)[kEncIters][4]) {
+        const uint32_t* src = gsrc + sb * kEncBlock;
+        const uint32_t cnt = (sb < nsub) ? ((gcnt - sb * kEncBlock < kEncBlock) ? (gcnt - sb * kEncBlock) : kEncBlock) : 0u;
 #pragma unroll
-    for (uint32_t it = 0; it < kEncIters; it++) {
-        const uint32_t i = it * 1024 + tid * 4;
-        const uint32_t mvalid = (i < cnt) ? ((cnt - i < 4) ? (cnt - i) : 4u) : 0u;
-        if (vec_ok && mvalid == 4) {
-            const uint4 t = *reinterpret_cast<const uint4*>(src + i);
-            raw[it][0] = t.x; raw[it][1] = t.y; raw[it][2] = t.z; raw[it][3] = t.w;
-        } else {
+        for (uint32_t it = 0; it < kEncIters; it++) {
+            const uint32_t i = it * 1024 + tid * 4;
+            const uint32_t mvalid = (i < cnt) ? ((cnt - i < 4) ? (cnt - i) : 4u) : 0u;
+            if (vec_ok && mvalid == 4) {
+                const uint4 t = *reinterpret_cast<const uint4*>(src + i);
+                raw[it][0] = t.x; raw[it][1] = t.y; raw[it][2] = t.z; raw[it][3] = t.w;
+            } else {
 #pragma unroll
-            for (uint32_t j = 0; j < 4; j++) raw[it][j] = (j < mvalid) ? src[i + j] : 0u;
+                for (uint32_t j = 0; j < 4; j++) raw[it][j] = (j < mvalid) ? src[i + j] : 0u;
+            }
         }
-    }
+    };
+    uint32_t raw[kEncIters][4], nxt[kEncIters][4];
+    load_sub(0, raw);
     const FrameMeta M = reinterpret_cast<const FrameMeta*>(A.ws + A.L.meta)[frame];
     if (!M.fits) return;
     uint8_t* fr = A.out + M.offset;
@@ -376,76 +396,89 @@ __global__ __launch_bounds__(kEncThreads) void k_encode(CompressArgs A) {
         if (SRC == 0) { int32_t t; quantize1(__uint_as_float(w), A.eb, A.step, A.inv_step, t); return zigzag(t); }
         return zigzag((int32_t)w);
     };
-
-    // ---- RAW: copy this block's words, the last block zero-fills the frame padding ----
-    if (M.codec == CODEC_RAW) {
-        uint32_t* dst = reinterpret_cast<uint32_t*>(fr + kHdrBytes) + blk0;
-#pragma unroll
-        for (uint32_t it = 0; it < kEncIters; it++) {
-            const uint32_t i = it * 1024 + tid * 4;
-            if (vec_ok && i + 4 <= cnt) *reinterpret_cast<uint4*>(dst + i) = make_uint4(raw[it][0], raw[it][1], raw[it][2], raw[it][3]);
-            else for (uint32_t j = 0; j < 4; j++) if (i + j < cnt) dst[i + j] = raw[it][j];
-        }
-        if (last_blk) {
-            const uint32_t w0 = (kHdrBytes + 4u * nf) / 4, w1 = M.total / 4;
+    auto pad_frame = [&]() {     // the frame's last workgroup zero-fills the padding after the payload
+        if (last_grp) {
+            const uint32_t w0 = (kHdrBytes + M.payload) / 4, w1 = M.total / 4;
             if (tid < w1 - w0) reinterpret_cast<uint32_t*>(fr)[w0 + tid] = 0;
         }
+    };
+
+    // ---- RAW: copy the words ----
+    if (M.codec == CODEC_RAW) {
+        uint32_t* dst = reinterpret_cast<uint32_t*>(fr + kHdrBytes) + g0;
+        for (uint32_t i = tid * 4; i < gcnt; i += kEncThreads * 4) {
+            if (vec_ok && i + 4 <= gcnt) *reinterpret_cast<uint4*>(dst + i) = *reinterpret_cast<const uint4*>(gsrc + i);
+            else for (uint32_t j = 0; j < 4; j++) if (i + j < gcnt) dst[i + j] = gsrc[i + j];
+        }
+        pad_frame();
         return;
     }
-
     uint32_t* bits = reinterpret_cast<uint32_t*>(fr + M.bits_off);
 
-    // ---- FIXEDLEN: w bits per code at closed-form positions; a pass of 1024 codes is 32*w whole words ----
+    // ---- FIXEDLEN ----
     if (M.codec == CODEC_FIXED) {
         const uint32_t w = M.w;
-        const uint32_t wblk = (blk0 / 32u) * w;                          // first bitstream word of this block
+        for (uint32_t sb = 0; sb < nsub; sb++) {
+            const uint32_t cnt = (gcnt - sb * kEncBlock < kEncBlock) ? (gcnt - sb * kEncBlock) : kEncBlock;
+            load_sub(sb + 1, nxt);
+            const uint32_t wblk = ((g0 + sb * kEncBlock) / 32u) * w;     // first bitstream word of this sub-block
 #pragma unroll
-        for (uint32_t it = 0; it < kEncIters; it++) {
-            if (it * 1024 < cnt) {
-                const uint32_t i = it * 1024 + tid * 4;
-                const uint32_t pass_syms = (cnt - it * 1024 < 1024u) ? (cnt - it * 1024) : 1024u;
-                const uint32_t pass_words = (pass_syms * w + 31u) / 32u;
-                for (uint32_t k = tid; k < pass_words; k += kEncThreads) s_stage[k] = 0;
-                __syncthreads();
-                uint32_t pos = tid * 4 * w;
+            for (uint32_t it = 0; it < kEncIters; it++) {
+                if (it * 1024 < cnt) {
+                    const uint32_t i = it * 1024 + tid * 4;
+                    const uint32_t pass_syms = (cnt - it * 1024 < 1024u) ? (cnt - it * 1024) : 1024u;
+                    const uint32_t pass_words = (pass_syms * w + 31u) / 32u;
+                    for (uint32_t k = tid; k < pass_words; k += kEncThreads) s_stage[k] = 0;
+                    __syncthreads();
+                    uint32_t pos = tid * 4 * w;
 #pragma unroll
-                for (uint32_t j = 0; j < 4; j++) {
-                    if (i + j < cnt && w) {
-                        const uint32_t z = zz(raw[it][j]);
-                        const uint32_t sh = pos & 31u, wi = pos >> 5;
-                        atomicOr(&s_stage[wi], z << sh);
-                        if (sh + w > 32u) atomicOr(&s_stage[wi + 1], z >> (32u - sh));
-                        pos += w;
+                    for (uint32_t j = 0; j < 4; j++) {
+                        if (i + j < cnt && w) {
+                            const uint32_t z = zz(raw[it][j]);
+                            const uint32_t sh = pos & 31u, wi = pos >> 5;
+                            atomicOr(&s_stage[wi], z << sh);
+                            if (sh + w > 32u) atomicOr(&s_stage[wi + 1], z >> (32u - sh));
+                            pos += w;
+                        }
                     }
+                    __syncthreads();
+                    uint32_t* dst = bits + wblk + it * 32u * w;
+                    for (uint32_t k = tid; k < pass_words; k += kEncThreads) dst[k] = s_stage[k];
+                    __syncthreads();
                 }
-                __syncthreads();
-                uint32_t* dst = bits + wblk + it * 32u * w;
-                for (uint32_t k = tid; k < pass_words; k += kEncThreads) dst[k] = s_stage[k];
-                __syncthreads();
             }
+#pragma unroll
+            for (uint32_t it = 0; it < kEncIters; it++)
+#pragma unroll
+                for (uint32_t j = 0; j < 4; j++) raw[it][j] = nxt[it][j];
         }
-        if (last_blk) {
-            const uint32_t w0 = M.bits_off / 4 + M.bits_words, w1 = M.total / 4;
-            if (tid < w1 - w0) reinterpret_cast<uint32_t*>(fr)[w0 + tid] = 0;
-        }
+        pad_frame();
         return;
     }
 
     // ---- HUFFMAN ----
-    uint64_t pk[kEncIters];                       // the thread's 4 symbols of a pass packed LSB-first
-    uint32_t ln[kEncIters];                       // exclusive bit offset of the thread inside its pass
-    uint32_t wide = 0;                            // pass mask: the 4 symbols need more than 64 bits
-    uint32_t start_bit = 0;                       // first bit of this block inside the frame's bitstream
+    for (uint32_t s = tid; s < K; s += kEncThreads) {
+        const uint32_t c = reinterpret_cast<const uint32_t*>(A.ws + A.L.book_code)[(size_t)frame * kMaxK + s];
+        const uint32_t l = (A.ws + A.L.book_len)[(size_t)frame * kMaxK + s];
+        s_book[s] = (uint64_t)c | ((uint64_t)l << 32);
+    }
+    for (uint32_t i = tid; i < kStageWords; i += kEncThreads) s_stage[i] = 0;
+    const uint32_t start_bit = reinterpret_cast<const uint32_t*>(A.ws + A.L.grp_start)[blockIdx.x];
+    const uint32_t c0 = start_bit & 31u;          // bits of the first word that belong to the previous workgroup
+    const uint32_t w_first = start_bit >> 5;
+    uint16_t* segt = reinterpret_cast<uint16_t*>(fr + M.segt_off);
+    const uint32_t nseg = (nf + kSeg - 1) / kSeg;
+    uint32_t run_bits = c0;                       // bits in front of the current sub-block, from stage origin
+    uint32_t flushed = 0;                         // stage-origin words already written out
+    __syncthreads();
 
-    {
-        for (uint32_t s = tid; s < K; s += kEncThreads) {
-            const uint32_t c = reinterpret_cast<const uint32_t*>(A.ws + A.L.book_code)[(size_t)frame * kMaxK + s];
-            const uint32_t l = (A.ws + A.L.book_len)[(size_t)frame * kMaxK + s];
-            s_book[s] = (uint64_t)c | ((uint64_t)l << 32);
-        }
-        __syncthreads();
-        // phase 1: look every symbol up once; pack the 4 symbols of a pass (code, and the 32 raw bits of an
-        // escape) into 64 bits; scan the bit counts
+    for (uint32_t sb = 0; sb < nsub; sb++) {
+        const uint32_t cnt = (gcnt - sb * kEncBlock < kEncBlock) ? (gcnt - sb * kEncBlock) : kEncBlock;
+        load_sub(sb + 1, nxt);
+        uint64_t pk[kEncIters];                   // the thread's 4 symbols of a pass packed LSB-first
+        uint32_t ln[kEncIters];                   // exclusive bit offset of the thread inside its pass
+        uint32_t wide = 0;                        // pass mask: the 4 symbols need more than 64 bits
+        // phase 1
 #pragma unroll
         for (uint32_t it = 0; it < kEncIters; it++) {
             const uint32_t i = it * 1024 + tid * 4;
@@ -454,14 +487,9 @@ __global__ __launch_bounds__(kEncThreads) void k_encode(CompressArgs A) {
 #pragma unroll
             for (uint32_t j = 0; j < 4; j++) {
                 if (i + j < cnt) {
-#ifdef NZ_EXP_ENC_NO_PHASE1
-                    const uint32_t z = raw[it][j] & 7u, sy = 1;
-                    const uint64_t b = (uint64_t)z | (3ull << 32);
-#else
                     const uint32_t z = zz(raw[it][j]);
                     const uint32_t sy = sym_of(z, K);
                     const uint64_t b = s_book[sy];
-#endif
                     if (tl < 64u) acc |= (uint64_t)(uint32_t)b << tl;
                     tl += (uint32_t)(b >> 32);
                     if (sy == 0) { if (tl < 64u) acc |= (uint64_t)z << tl; tl += 32u; }
@@ -486,125 +514,88 @@ __global__ __launch_bounds__(kEncThreads) void k_encode(CompressArgs A) {
             }
         }
         if (tid == 0) s_pbase[kEncIters] = block_bits;
-        uint16_t* segt = reinterpret_cast<uint16_t*>(fr + M.segt_off);
-        const uint32_t nseg = (nf + kSeg - 1) / kSeg;
         if (tid < kEncSegs) {
-            const uint32_t gseg = blk0 / kSeg + tid;
+            const uint32_t gseg = (g0 + sb * kEncBlock) / kSeg + tid;
             if (gseg < nseg) segt[gseg] = (uint16_t)s_wtot[tid];
-            if (last_blk && gseg == nseg - 1 && (nseg & 1u)) segt[nseg] = 0;   // pad4 of the table
+            if (gseg == nseg - 1 && (nseg & 1u)) segt[nseg] = 0;          // pad4 of the table
         }
-        uint64_t* bdesc = reinterpret_cast<uint64_t*>(A.ws + A.L.blk_desc) + (size_t)frame * ebpf;
-#ifdef NZ_EXP_ENC_NO_LOOKBACK
-        if (tid == 0) s_excl = (uint64_t)bif * 32u * 600u;
-        (void)bdesc;
-#else
-        if (wave == 0) {
-            const uint32_t t = block_bits;
-            if (lane == 0) st_agent(bdesc + bif, kDescA | (uint64_t)t);
-            const uint64_t excl = lookback_exclusive(bdesc, 0, (int64_t)bif, 0);
-            if (lane == 0) { st_agent(bdesc + bif, kDescP | (excl + t)); s_excl = excl; }
-        }
-#endif
-        for (uint32_t i = tid; i < kStageWords; i += kEncThreads) s_stage[i] = 0;
         __syncthreads();
-        start_bit = (uint32_t)s_excl;
-    }
 
-    // phase 2: OR the passes into the LDS stage at their final bit positions (stage word 0 is stream word
-    // w_first of the bitstream), as many passes at a time as fit, then flush whole words coalesced
-    const uint32_t c0 = start_bit & 31u;          // bits of the first word owned by the predecessor
-    const uint32_t w_first = start_bit >> 5;
-    uint32_t flushed = 0;                         // words of the stage origin already written out
-    uint32_t it0 = 0;
-#ifdef NZ_EXP_ENC_NO_PHASE2
-    it0 = kEncIters;
-#endif
-    while (it0 < kEncIters && it0 * 1024 < cnt) {
-        // passes [it0, it1) fit the stage
-        uint32_t it1 = it0 + 1;
-        while (it1 < kEncIters && c0 + s_pbase[it1 + 1] - 32u * flushed <= 32u * (kStageWords - 2)) it1++;
+        // phase 2: as many passes at a time as fit the stage
+        uint32_t it0 = 0;
+        while (it0 < kEncIters && it0 * 1024 < cnt) {
+            uint32_t it1 = it0 + 1;
+            while (it1 < kEncIters && run_bits + s_pbase[it1 + 1] - 32u * flushed <= 32u * (kStageWords - 2)) it1++;
 #pragma unroll
-        for (uint32_t it = 0; it < kEncIters; it++) {
-            if (it >= it0 && it < it1) {
-                const uint32_t i = it * 1024 + tid * 4;
-                uint32_t pos = c0 + s_pbase[it] + ln[it] - 32u * flushed;
-                if (!((wide >> it) & 1u)) {
-                    const uint64_t a = pk[it];
-                    if (a) {
-                        const uint32_t sh = pos & 31u, wi = pos >> 5;
-                        const uint64_t t = a << sh;
-                        atomicOr(&s_stage[wi], (uint32_t)t);
-                        if ((uint32_t)(t >> 32)) atomicOr(&s_stage[wi + 1], (uint32_t)(t >> 32));
-                        if (sh) { const uint32_t hi = (uint32_t)(a >> (64u - sh)); if (hi) atomicOr(&s_stage[wi + 2], hi); }
-                    }
-                } else {
-                    // the pass needs more than 64 bits (rare): reload its 4 source words, emit symbol by symbol
+            for (uint32_t it = 0; it < kEncIters; it++) {
+                if (it >= it0 && it < it1) {
+                    const uint32_t i = it * 1024 + tid * 4;
+                    uint32_t pos = run_bits + s_pbase[it] + ln[it] - 32u * flushed;
+                    if (!((wide >> it) & 1u)) {
+                        const uint64_t a = pk[it];
+                        if (a) {
+                            const uint32_t sh = pos & 31u, wi = pos >> 5;
+                            const uint64_t t = a << sh;
+                            atomicOr(&s_stage[wi], (uint32_t)t);
+                            if ((uint32_t)(t >> 32)) atomicOr(&s_stage[wi + 1], (uint32_t)(t >> 32));
+                            if (sh) { const uint32_t hi = (uint32_t)(a >> (64u - sh)); if (hi) atomicOr(&s_stage[wi + 2], hi); }
+                        }
+                    } else {
+                        // the pass needs more than 64 bits (rare): emit symbol by symbol
 #pragma unroll
-                    for (uint32_t j = 0; j < 4; j++) {
-                        if (i + j < cnt) {
-                            const uint32_t z = zz(src[i + j]);
-                            const uint32_t sy = sym_of(z, K);
-                            const uint64_t b = s_book[sy];
-                            const uint32_t val = (uint32_t)b, len = (uint32_t)(b >> 32);
-                            if (len) {
-                                const uint32_t sh = pos & 31u, wi = pos >> 5;
-                                atomicOr(&s_stage[wi], val << sh);
-                                if (sh + len > 32u) atomicOr(&s_stage[wi + 1], val >> (32u - sh));
-                                pos += len;
-                            }
-                            if (sy == 0) {
-                                const uint32_t sh = pos & 31u, wi = pos >> 5;
-                                atomicOr(&s_stage[wi], z << sh);
-                                if (sh) atomicOr(&s_stage[wi + 1], z >> (32u - sh));
-                                pos += 32u;
+                        for (uint32_t j = 0; j < 4; j++) {
+                            if (i + j < cnt) {
+                                const uint32_t z = zz(raw[it][j]);
+                                const uint32_t sy = sym_of(z, K);
+                                const uint64_t b = s_book[sy];
+                                const uint32_t val = (uint32_t)b, len = (uint32_t)(b >> 32);
+                                if (len) {
+                                    const uint32_t sh = pos & 31u, wi = pos >> 5;
+                                    atomicOr(&s_stage[wi], val << sh);
+                                    if (sh + len > 32u) atomicOr(&s_stage[wi + 1], val >> (32u - sh));
+                                    pos += len;
+                                }
+                                if (sy == 0) {
+                                    const uint32_t sh = pos & 31u, wi = pos >> 5;
+                                    atomicOr(&s_stage[wi], z << sh);
+                                    if (sh) atomicOr(&s_stage[wi + 1], z >> (32u - sh));
+                                    pos += 32u;
+                                }
                             }
                         }
                     }
                 }
             }
+            __syncthreads();
+            const uint32_t nbits = run_bits + s_pbase[it1] - 32u * flushed;  // bits now in the stage
+            const uint32_t nw = nbits >> 5;
+            const uint32_t wpos = w_first + flushed;
+            for (uint32_t k = tid; k < nw; k += kEncThreads) {
+                const uint32_t wv = s_stage[k];
+                if (gb > 0 && flushed == 0 && k == 0) atomicOr(bits + wpos, wv);   // word shared with the previous workgroup
+                else bits[wpos + k] = wv;
+            }
+            const uint32_t partial = s_stage[nw];
+            __syncthreads();
+            for (uint32_t k = tid; k <= nw + 2 && k < kStageWords; k += kEncThreads) s_stage[k] = (k == 0) ? partial : 0u;
+            flushed += nw;
+            it0 = it1;
+            __syncthreads();
         }
-        __syncthreads();
-        const uint32_t nbits = c0 + s_pbase[it1] - 32u * flushed;       // bits now in the stage
-        const uint32_t nw = nbits >> 5;
+        run_bits += block_bits;
+#pragma unroll
+        for (uint32_t it = 0; it < kEncIters; it++)
+#pragma unroll
+            for (uint32_t j = 0; j < 4; j++) raw[it][j] = nxt[it][j];
+    }
+    // the last, partial word: shared with the next workgroup, or the frame's last bitstream word
+    if (tid == 0 && (run_bits & 31u)) {
+        const uint32_t partial = s_stage[0];
         const uint32_t wpos = w_first + flushed;
-        for (uint32_t k = tid; k < nw; k += kEncThreads) {
-            const uint32_t wv = s_stage[k];
-            if (c0 && wpos + k == w_first) { s_first_word = wv; s_first_taken = 1; }   // deferred: shared word
-            else bits[wpos + k] = wv;
-        }
-        const uint32_t partial = s_stage[nw];
-        if (tid == 0 && nw) s_lastw = s_stage[nw - 1];
-        __syncthreads();
-        for (uint32_t k = tid; k <= nw + 2 && k < kStageWords; k += kEncThreads) s_stage[k] = (k == 0) ? partial : 0u;
-        flushed += nw;
-        it0 = it1;
-        __syncthreads();
+        if (!last_grp || (gb > 0 && flushed == 0)) atomicOr(bits + wpos, partial);
+        else bits[wpos] = partial;
     }
-    // tail: the word shared with the successor is the successor's to write; publish our last 31 bits
-    const uint32_t end_bit = c0 + s_pbase[kEncIters];                   // relative to stage origin (word w_first)
-    const uint32_t carry = end_bit & 31u;
-    const uint32_t wpos = w_first + flushed;
-    const uint32_t partial = s_stage[0];
-    uint32_t* btail = reinterpret_cast<uint32_t*>(A.ws + A.L.blk_tail) + (size_t)frame * ebpf;
-    if (tid == 0) {
-        if (!last_blk) {
-            const uint64_t X = (uint64_t)s_lastw | ((uint64_t)partial << 32);
-            st_agent(btail + bif, 0x80000000u | (uint32_t)((X >> (1u + carry)) & 0x7FFFFFFFu));
-        } else if (carry) {
-            if (c0 && wpos == w_first && !s_first_taken) { s_first_word = partial; s_first_taken = 1; }
-            else bits[wpos] = partial;
-        }
-        if (c0) {
-            // the first word: predecessor's last c0 bits (low) + our own bits (high)
-            uint32_t t;
-            while (((t = ld_agent(btail + bif - 1)) & 0x80000000u) == 0) __builtin_amdgcn_s_sleep(2);
-            bits[w_first] = s_first_word | ((t & 0x7FFFFFFFu) >> (31u - c0));
-        }
-    }
-    if (last_blk) {   // zero the padding after the last bitstream word
-        const uint32_t w0 = M.bits_off / 4 + M.bits_words, w1 = M.total / 4;
-        if (tid < w1 - w0) reinterpret_cast<uint32_t*>(fr)[w0 + tid] = 0;
-    }
+    pad_frame();
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -630,9 +621,8 @@ hipError_t launch_codebook(const CompressArgs& A, hipStream_t st) {
 }
 
 hipError_t launch_encode(const CompressArgs& A, bool from_codes, hipStream_t st) {
-    const uint32_t ebpf = (A.chunk + kEncBlock - 1) / kEncBlock;
-    if (from_codes) hipLaunchKernelGGL(k_encode<1>, dim3(A.n_frames * ebpf), dim3(kEncThreads), 0, st, A);
-    else hipLaunchKernelGGL(k_encode<0>, dim3(A.n_frames * ebpf), dim3(kEncThreads), 0, st, A);
+    if (from_codes) hipLaunchKernelGGL(k_encode<1>, dim3(A.n_frames * A.sbpf), dim3(kEncThreads), 0, st, A);
+    else hipLaunchKernelGGL(k_encode<0>, dim3(A.n_frames * A.sbpf), dim3(kEncThreads), 0, st, A);
     return hipGetLastError();
 }
 
