@@ -66,19 +66,18 @@ struct BuildScratch {
     __align__(4) uint8_t len[kMaxK];
     uint16_t rank[kMaxK];
     uint32_t wcnt[16 * 32];
-    uint64_t red[4];
-    uint32_t flag;
+    uint64_t red[2][kDecThreads / 64];
 };
 
+// Sums of two 64-bit values over the workgroup, one barrier pair for both.
 template <int NT>
-__device__ inline uint64_t block_sum64(uint64_t v, uint64_t* s_red) {
-    v = wave_sum64(v);
+__device__ inline void block_sum64x2(uint64_t& a, uint64_t& b, uint64_t (*s_red)[kDecThreads / 64]) {
+    a = wave_sum64(a); b = wave_sum64(b);
     __syncthreads();
-    if (lane_id() == 0) s_red[threadIdx.x >> 6] = v;
+    if (lane_id() == 0) { s_red[0][threadIdx.x >> 6] = a; s_red[1][threadIdx.x >> 6] = b; }
     __syncthreads();
-    uint64_t t = 0;
-    for (int i = 0; i < NT / 64; i++) t += s_red[i];
-    return t;
+    a = 0; b = 0;
+    for (int i = 0; i < NT / 64; i++) { a += s_red[0][i]; b += s_red[1][i]; }
 }
 
 // Validate one frame and prepare its decoder (all threads of the workgroup call this together).
@@ -120,28 +119,40 @@ __device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t fra
     if (payload < tables || (payload & 3u)) return;
     const uint8_t* lens = pay;
     const uint16_t* segt = reinterpret_cast<const uint16_t*>(pay + pad4d(nsym));
-    // code lengths: <= 28, padding zero, at least one used, Kraft sum <= 1
+    // code lengths (4 per thread): <= 28, padding zero, at least one used, Kraft sum <= 1
+    static_assert(NT * 4 >= kMaxK, "one pass over the code lengths");
     uint32_t bad = 0;
     uint64_t kraft = 0;
-#pragma unroll 1
-    for (uint32_t t = tid; t < kMaxK; t += NT) {
-        uint32_t L = 0;
-        if (t < (uint32_t)pad4d(nsym)) L = lens[t];
-        if (L > kMaxLen || (t >= nsym && L)) bad = 1;
-        if (L && L <= kMaxLen && t < nsym) kraft += 1ull << (kMaxLen - L);
-        B->len[t] = (t < nsym && L <= kMaxLen) ? (uint8_t)L : 0;
+    {
+        const uint32_t lw = (4u * tid < (uint32_t)pad4d(nsym)) ? reinterpret_cast<const uint32_t*>(lens)[tid] : 0u;
+        uint32_t clean = 0;
+#pragma unroll
+        for (uint32_t j = 0; j < 4; j++) {
+            const uint32_t L = (lw >> (8 * j)) & 0xFFu, t = 4u * tid + j;
+            if (L > kMaxLen || (t >= nsym && L)) bad = 1;
+            else if (L) { kraft += 1ull << (kMaxLen - L); clean |= L << (8 * j); }
+        }
+        if (4u * tid < kMaxK) reinterpret_cast<uint32_t*>(B->len)[tid] = clean;
     }
-    // segment table: bits before this workgroup's first segment, and in the whole frame
-    uint64_t pre = 0, all = 0;
-    for (uint32_t g = tid; g < nseg; g += NT) { const uint32_t v = segt[g]; all += v; if (g < first_seg) pre += v; }
-    if ((nseg & 1u) && tid == 0 && segt[nseg] != 0) bad = 1;
-    kraft = block_sum64<NT>(kraft, B->red);
-    pre = block_sum64<NT>(pre, B->red);
-    all = block_sum64<NT>(all, B->red);
-    const uint64_t badsum = block_sum64<NT>(bad, B->red);
-    if (badsum || kraft == 0 || kraft > (1ull << kMaxLen)) return;
+    // segment table (two entries per load): bits before this workgroup's first segment, and in the whole frame
+    uint32_t pre = 0, all = 0;
+    {
+        const uint32_t* segt32 = reinterpret_cast<const uint32_t*>(segt);
+        const uint32_t npairs = (nseg + 1u) / 2u;
+        for (uint32_t p2 = tid; p2 < npairs; p2 += NT) {
+            const uint32_t v = segt32[p2], g = 2u * p2, v0 = v & 0xFFFFu, v1 = v >> 16;
+            all += v0; if (g < first_seg) pre += v0;
+            if (g + 1u < nseg) { all += v1; if (g + 1u < first_seg) pre += v1; }
+            else if (v1) bad = 1;                                      // padding entry of an odd table
+        }
+    }
+    uint64_t r0 = kraft + ((uint64_t)bad << 48), r1 = (uint64_t)pre | ((uint64_t)all << 32);
+    block_sum64x2<NT>(r0, r1, B->red);
+    kraft = r0 & ((1ull << 48) - 1ull);
+    const uint64_t pre_bits = r1 & 0xFFFFFFFFull, all_bits = r1 >> 32;
+    if ((r0 >> 48) || kraft == 0 || kraft > (1ull << kMaxLen)) return;
     const uint64_t avail = 8ull * (payload - tables);
-    if (all > avail || 4ull * ((all + 31u) / 32u) != payload - tables) return;
+    if (all_bits > avail || 4ull * ((all_bits + 31u) / 32u) != payload - tables) return;
     // canonical tables and the first-level lookup
     uint32_t* s_cnt = T->cnt; uint32_t* s_first = T->first; uint32_t* s_idx0 = T->idx0;
     canonical_tables<NT>(B->len, K, B->wcnt, s_cnt, s_first, s_idx0, B->rank);
@@ -149,87 +160,99 @@ __device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t fra
         const uint32_t L = B->len[sy];
         if (L) T->sorted[s_idx0[L] + B->rank[sy]] = (uint16_t)sy;
     }
+    if (tid == 0) T->nsub = 0;
     __syncthreads();
     // Entry formats (16 bits).  First level, indexed by the next 11 stream bits:
     //   z | L<<10            symbol with zigzag code z and an L <= 11 bit code
     //   0x8000 | L<<10       escape symbol with an L-bit code (32 raw bits follow)
     //   0xC000 | id          no code of <= 11 bits starts here; id < kMaxSub: second-level table, else search
     // Second level, indexed by stream bits 11..16: same with L-11 in place of L; 0xC000 = longer still.
-    if (tid == 0) T->nsub = 0;
-    __syncthreads();
-#pragma unroll 1
-    for (uint32_t i = tid; i < (1u << kPrimaryBits); i += NT) {
-        uint32_t code = 0, e = 0xC000u;
-        for (uint32_t L = 1; L <= kPrimaryBits; L++) {
-            code = (code << 1) | ((i >> (L - 1)) & 1u);            // stream order: first bit is the code's MSB
-            const uint32_t d = code - s_first[L];
-            if (d < s_cnt[L]) {
-                const uint32_t sy = T->sorted[s_idx0[L] + d];
+    // Canonical codes left-justified to a common width are ordered by length, so the length of the code that
+    // starts an entry's bits is found by comparing against the end of every length's range (no table walk).
+    {
+        uint32_t lim[kPrimaryBits + 1];                                // end of the codes of length <= l, 11-bit scale
+#pragma unroll
+        for (uint32_t l = 1; l <= kPrimaryBits; l++) lim[l] = (s_first[l] + s_cnt[l]) << (kPrimaryBits - l);
+#pragma unroll
+        for (uint32_t i = tid; i < (1u << kPrimaryBits); i += NT) {
+            const uint32_t v = __brev(i) >> (32 - kPrimaryBits);       // stream order: first bit is the code's MSB
+            uint32_t L = 1;
+#pragma unroll
+            for (uint32_t l = 1; l < kPrimaryBits; l++) L += (v >= lim[l]) ? 1u : 0u;
+            uint32_t e = 0xC000u;
+            if (v < lim[kPrimaryBits]) {
+                const uint32_t sy = T->sorted[s_idx0[L] + (v >> (kPrimaryBits - L)) - s_first[L]];
                 e = sy ? ((sy - 1u) | (L << 10)) : (0x8000u | (L << 10));
-                break;
+            } else {
+                const uint32_t id = atomicAdd(&T->nsub, 1u);
+                if (id < kMaxSub) { e |= id; T->sub_prefix[id] = (uint16_t)i; } else e |= 0x3FFu;
             }
+            T->tab[i] = (uint16_t)e;
         }
-        if (e == 0xC000u) {
-            const uint32_t id = atomicAdd(&T->nsub, 1u);
-            if (id < kMaxSub) { e |= id; T->sub_prefix[id] = (uint16_t)i; } else e |= 0x3FFu;
-        }
-        T->tab[i] = (uint16_t)e;
     }
     __syncthreads();
-    const uint32_t nsub = T->nsub < kMaxSub ? T->nsub : kMaxSub;
+    {
+        constexpr uint32_t W2 = kPrimaryBits + kSubBits;
+        const uint32_t nsub = T->nsub < kMaxSub ? T->nsub : kMaxSub;
+        uint32_t lim[kSubBits + 1];                                    // end of the codes of length <= 11 + l, 17-bit scale
+#pragma unroll
+        for (uint32_t l = 1; l <= kSubBits; l++) lim[l] = (s_first[kPrimaryBits + l] + s_cnt[kPrimaryBits + l]) << (kSubBits - l);
 #pragma unroll 1
-    for (uint32_t idx = tid; idx < (nsub << kSubBits); idx += NT) {
-        const uint32_t bits = (uint32_t)T->sub_prefix[idx >> kSubBits] | ((idx & ((1u << kSubBits) - 1u)) << kPrimaryBits);
-        uint32_t code = 0, e = 0xC000u;
-        for (uint32_t L = 1; L <= kPrimaryBits + kSubBits; L++) {
-            code = (code << 1) | ((bits >> (L - 1)) & 1u);
-            if (L > kPrimaryBits) {
-                const uint32_t d = code - s_first[L];
-                if (d < s_cnt[L]) {
-                    const uint32_t sy = T->sorted[s_idx0[L] + d];
-                    e = sy ? ((sy - 1u) | ((L - kPrimaryBits) << 10)) : (0x8000u | ((L - kPrimaryBits) << 10));
-                    break;
-                }
+        for (uint32_t idx = tid; idx < (nsub << kSubBits); idx += NT) {
+            const uint32_t hi11 = __brev((uint32_t)T->sub_prefix[idx >> kSubBits]) >> (32 - kPrimaryBits);
+            const uint32_t v = (hi11 << kSubBits) | (__brev(idx & ((1u << kSubBits) - 1u)) >> (32 - kSubBits));
+            uint32_t L = kPrimaryBits + 1;
+#pragma unroll
+            for (uint32_t l = 1; l < kSubBits; l++) L += (v >= lim[l]) ? 1u : 0u;
+            uint32_t e = 0xC000u;
+            if (v < lim[kSubBits]) {
+                const uint32_t sy = T->sorted[s_idx0[L] + (v >> (W2 - L)) - s_first[L]];
+                e = sy ? ((sy - 1u) | ((L - kPrimaryBits) << 10)) : (0x8000u | ((L - kPrimaryBits) << 10));
             }
+            T->tab2[idx] = (uint16_t)e;
         }
-        T->tab2[idx] = (uint16_t)e;
     }
     __syncthreads();
     {   // schedule reloads so that an average lane (with a 25 % margin) never needs one of its own
-        const uint32_t run_bits = (uint32_t)((all * kRun) / nf) + 1u;
+        const uint32_t run_bits = (uint32_t)((all_bits * kRun) / nf) + 1u;
         const uint32_t c = kWinFreshBits / (run_bits + run_bits / 4u);
         V.cadence = c < 1u ? 1u : (c > 16u ? 16u : c);
     }
-    V.status = ST_OK; V.kind = KIND_HUFF; V.segt = segt; V.seg_prefix = pre;
+    V.status = ST_OK; V.kind = KIND_HUFF; V.segt = segt; V.seg_prefix = pre_bits;
     V.words = reinterpret_cast<const uint32_t*>(pay + tables); V.nwords = (uint32_t)((payload - tables) / 4);
 }
 
-// Per-thread sequential reader of one HUFFMAN segment.  Every lane owns a small window (kWinWords words) in LDS, filled from
-// global memory with dword-aligned 16-byte loads starting at the word the lane is in.  Reloads happen at
-// the start of a run of 8 symbols, a point that is uniform over the wave: on a schedule derived from the
-// frame's average code length (so that the global-load stall is paid once for all lanes and few fetched bytes
-// go unused), and for a single lane when it is kWinRunLimit or more bits into its window.  A symbol reads the two
-// window words at its bit position (ds_read2) and funnel-shifts them, so first-level symbols, long codes and
-// escapes all advance by plain position arithmetic; a lane also reloads at once when a long code or an escape
-// leaves it kWinSlowLimit or more bits into the window.  Budget: 8 first-level symbols use at most 88 bits, a
-// long code 28, an escape 60, so every two-word read stays inside the window.  Near the end of the bitstream words are
-// fetched one by one with the index clamped to the last word, so any input stays in bounds (a valid stream
-// never consumes a clamped word).
+// Per-thread sequential reader of one HUFFMAN segment.  Every lane owns a small window (kWinWords words) in
+// LDS, filled from global memory with dword-aligned 16-byte loads starting at the word the lane is in.  Reloads
+// happen at the start of a run of 8 symbols, a point that is uniform over the wave: on a schedule derived from
+// the frame's average code length (so that the global-load stall is paid once for all lanes and few fetched
+// bytes go unused), and for a single lane when it is kWinRunLimit or more bits into its window; a lane also
+// reloads at once when a long code or an escape leaves it kWinSlowLimit or more bits into the window.
+// Window words k and k+1 of the current position live in registers (lo, hi), so the next 32 stream bits are a
+// funnel shift away and the only LDS access on a symbol's critical path is the table lookup; words k+2 and k+3
+// are re-read from the window after every symbol and are back long before a later symbol shifts them in.
+// Budget: 8 first-level symbols use at most 88 bits, a long code 28, an escape 60, so lo and hi always come
+// from inside the window (k + 1 < kWinWords); the two prefetched words may lie up to two rows past it, inside
+// the shared-memory block that follows the windows, and are never shifted in before a reload replaces them.
+// Near the end of the bitstream words are fetched one by one with the index clamped to the last word, so any
+// input stays in bounds (a valid stream never consumes a clamped word).
 constexpr uint32_t kWinWords = 12;
 constexpr uint32_t kWinBits = 32 * kWinWords;
-// A two-word read at position p needs p < kWinBits - 32.  After a long code or an escape a lane reloads unless
-// p < kWinSlowLimit; up to 7 first-level symbols (77 bits) and the code of an escape (28 bits) may follow
+// A read of words k, k+1 at position p needs p < kWinBits - 32.  After a long code or an escape a lane reloads
+// unless p < kWinSlowLimit; up to 7 first-level symbols (77 bits) and the code of an escape (28 bits) may follow
 // before the next check, and the escape's raw word is read there: kWinSlowLimit + 77 + 28 < kWinBits - 32.
 constexpr uint32_t kWinSlowLimit = kWinBits - 32 - 77 - 28 - 7;      // 240 for 12 words
 constexpr uint32_t kWinRunLimit = kWinSlowLimit - 16;                // reload at a run start when this far in
 static_assert(kWinRunLimit - 31 == kWinFreshBits, "cadence constant out of step with the window size");
+constexpr uint32_t kWinOverRows = 2;                                 // rows a prefetch may reach past the window
 
 struct HuffReader {
     uint64_t bits_addr;                  // byte address of bitstream word 0
     uint32_t nwords;                     // words in the bitstream (at least 1)
-    uint32_t* win;                       // this lane's window in LDS
+    uint32_t* win;                       // this lane's window in LDS (word j at win[j * kDecThreads])
     int32_t win_bit0;                    // bit index (relative to bitstream bit 0) of window word 0
-    uint32_t pos;                        // current position, in bits from the window start
+    uint32_t k, sh;                      // current position: bit sh (0..31) of window word k
+    uint32_t lo, hi, n1, n2;             // window words k .. k+3
     uint32_t start_bit, bad;
     const DecTables* T;
 
@@ -241,17 +264,15 @@ struct HuffReader {
         } else {
             bits_addr = reinterpret_cast<uint64_t>(V.words); nwords = V.nwords;
         }
-        win_bit0 = (int32_t)bitpos; pos = 0;
+        win_bit0 = (int32_t)bitpos; k = 0; sh = 0; lo = hi = n1 = n2 = 0;
     }
+    __device__ inline uint32_t pos() const { return 32u * k + sh; }
     __device__ inline void reload() {
-#ifdef NZ_EXP_NO_RELOAD
-        if (pos < 0x7fffffffu) { win_bit0 += (int32_t)(pos & ~31u); pos &= 31u; return; }
-#endif
-        const uint32_t cur = (uint32_t)(win_bit0 + (int32_t)pos);
+        const uint32_t cur = (uint32_t)(win_bit0 + (int32_t)pos());
         const uint32_t wi = cur >> 5;
-        // the window is stored word-major (word k of every lane side by side): conflict-free for equal k
+        // the window is stored word-major (word j of every lane side by side): conflict-free for equal j
         if (__builtin_expect(wi + kWinWords <= nwords, 1)) {
-            // four dword-aligned 16-byte loads straight from the lane's position (no alignment waste)
+            // dword-aligned 16-byte loads straight from the lane's position (no alignment waste)
             typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
             typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
             typedef const u32x4_a4 __attribute__((address_space(1))) * gptr;  // plain global loads, not flat ones
@@ -264,6 +285,7 @@ struct HuffReader {
                 win[(4 * c + 0) * kDecThreads] = x[c].x; win[(4 * c + 1) * kDecThreads] = x[c].y;
                 win[(4 * c + 2) * kDecThreads] = x[c].z; win[(4 * c + 3) * kDecThreads] = x[c].w;
             }
+            lo = x[0].x; hi = x[0].y; n1 = x[0].z; n2 = x[0].w;
         } else {
             // near the end of the bitstream: word by word, indices clamped to the last word
             typedef const uint32_t __attribute__((address_space(1))) * wptr;
@@ -271,34 +293,28 @@ struct HuffReader {
             const uint32_t last = nwords - 1u;
 #pragma unroll 1
             for (uint32_t j = 0; j < kWinWords; j++) win[j * kDecThreads] = w[wi + j < last ? wi + j : last];
+            lo = win[0]; hi = win[kDecThreads]; n1 = win[2 * kDecThreads]; n2 = win[3 * kDecThreads];
         }
         win_bit0 = (int32_t)(cur & ~31u);
-        pos = cur & 31u;
+        k = 0; sh = cur & 31u;
     }
-    __device__ inline uint32_t peek() const {                            // the next 32 stream bits
-        const uint32_t k = pos >> 5;
-        return __builtin_amdgcn_alignbit(win[(k + 1) * kDecThreads], win[k * kDecThreads], pos);
-    }
-    __device__ inline uint32_t consumed() const { return (uint32_t)(win_bit0 + (int32_t)pos) - start_bit; }
-    __device__ inline uint32_t next() {
-#ifdef NZ_EXP_NO_WINDOW
-        const uint32_t w32 = pos * 2654435761u;
-#else
-        const uint32_t w32 = peek();
-#endif
-#ifdef NZ_EXP_NO_TABLE
-        const uint32_t e = (w32 & 7u) | (3u << 10);
-#else
+    __device__ inline uint32_t consumed() const { return (uint32_t)(win_bit0 + (int32_t)pos()) - start_bit; }
+    // Decode one symbol; returns its zigzag code.  on_escape(z) is applied to the value of an escaped symbol.
+    template <typename F>
+    __device__ inline uint32_t next(F&& on_escape) {
+        const uint32_t w32 = __builtin_amdgcn_alignbit(hi, lo, sh);      // the next 32 stream bits
         const uint32_t e = T->tab[w32 & ((1u << kPrimaryBits) - 1u)];
-#endif
-#ifdef NZ_EXP_NO_SLOW
-        pos += (e >> 10) & 15u; return e & 1023u;
-#else
-        if (__builtin_expect(e < 0x8000u, 1)) { pos += e >> 10; return e & 1023u; }
-        return next_slow(e, w32);
-#endif
+        uint32_t z;
+        if (__builtin_expect(e < 0x8000u, 1)) { sh += e >> 10; z = e & 1023u; }
+        else z = next_slow(e, w32, on_escape);
+        const bool c = sh >= 32u;                                        // at most one word is used up per symbol here
+        lo = c ? hi : lo; hi = c ? n1 : hi; k += c ? 1u : 0u; sh &= 31u;
+        const uint32_t* p = win + k * kDecThreads;
+        n1 = p[2 * kDecThreads]; n2 = p[3 * kDecThreads];
+        return z;
     }
-    __device__ inline uint32_t next_slow(uint32_t e, uint32_t w32) {
+    template <typename F>
+    __device__ inline uint32_t next_slow(uint32_t e, uint32_t w32, F&& on_escape) {
         uint32_t L = (e >> 10) & 15u, z = 0, esc = (e < 0xC000u);
         if (e >= 0xC000u) {
             uint32_t e2 = 0xC000u;
@@ -321,11 +337,17 @@ struct HuffReader {
                 z = sy - 1u; esc = (sy == 0);
             }
         }
-        pos += L;
-        if (esc) { z = peek(); pos += 32u; }                             // escape: the 32 raw bits of z follow
-        if (pos >= kWinSlowLimit) reload();
+        sh += L;                                                         // < 64
+        if (esc) {                                                       // escape: the 32 raw bits of z follow
+            if (sh >= 32u) { lo = hi; hi = n1; n1 = n2; k++; sh -= 32u; }
+            z = on_escape(__builtin_amdgcn_alignbit(hi, lo, sh));
+            lo = hi; hi = n1; k++;
+        }
+        if (32u * k + sh >= kWinSlowLimit) reload_normalised();
         return z;
     }
+    // reload from a position whose sh may still be >= 32 (the caller's word shift has not happened yet)
+    __device__ inline void reload_normalised() { k += sh >> 5; sh &= 31u; reload(); }
 };
 
 // Position-addressed fetch of element e of a RAW / FIXEDLEN (or rejected = all-zero) frame.
@@ -352,14 +374,17 @@ struct DirectFetch {
 constexpr uint32_t kTileR = 16;                      // symbols per thread between two coalesced output phases
 constexpr uint32_t kTileStride = kTileR + 1;         // odd row stride: conflict-free column writes
 
-struct DecShared {
+// Shared memory of one decode workgroup.  The windows come first and the tile follows them directly: a
+// reader's prefetch may touch up to kWinOverRows rows past its window, which then fall into the next window or
+// the tile (valid shared memory, values never used).
+template <int NOPS>
+struct __align__(16) DecShared {
+    uint32_t win[NOPS][kDecThreads * kWinWords];
     union { uint32_t tile[kDecThreads * kTileStride]; BuildScratch build; } u;
     uint64_t wsum[4];
     uint32_t zmax, flags;
 };
-
-template <int NOPS>
-struct __align__(16) DecWindows { uint32_t w[NOPS][kDecThreads * kWinWords]; };
+static_assert(kDecThreads * kTileStride >= kWinOverRows * kDecThreads, "prefetch rows must stay inside the tile");
 
 struct SegCtx {
     uint32_t tid, lane, first_seg, nf, cntseg, e0;
@@ -419,9 +444,9 @@ __device__ inline void emit4(const DecodeArgs& A, const SegCtx& C, uint32_t e, u
 // One 256-symbol segment per thread, kTileR symbols at a time into an LDS tile, then the workgroup writes the
 // tile out with 16-byte stores (kTileR/4 lanes cover one thread's run, so every store instruction fills whole
 // 64-byte runs).  KA / KB say which operands are HUFFMAN (sequential reader) and which are addressed directly.
-template <int MODE, int KA, int KB>
+template <int MODE, int KA, int KB, typename SH>
 __device__ inline void run_segments(const DecodeArgs& A, const SegCtx& C, HuffReader& ra, HuffReader& rb,
-                                    const DirectFetch& da, const DirectFetch& db, DecShared* S,
+                                    const DirectFetch& da, const DirectFetch& db, SH* S,
                                     uint32_t* s_h, uint32_t ncs, uint32_t ca, uint32_t cb, uint32_t& overflow) {
     const uint32_t tid = C.tid;
     const uint32_t copy = C.lane & ((1u << ncs) - 1u);
@@ -431,9 +456,10 @@ __device__ inline void run_segments(const DecodeArgs& A, const SegCtx& C, HuffRe
     constexpr bool ANY_RAW = (MODE == 1) && (KA == KIND_RAW || KB == KIND_RAW);
     uint32_t e = C.e0;                               // next element of my segment (frame index)
     auto produce = [&]() -> uint32_t {
-        const uint32_t ta = (KA == KIND_HUFF) ? ra.next() : da.get(e);
+        auto same = [](uint32_t z) { return z; };
+        const uint32_t ta = (KA == KIND_HUFF) ? ra.next(same) : da.get(e);
         if (MODE == 0) { e++; return ta; }
-        const uint32_t tb = (KB == KIND_HUFF) ? rb.next() : db.get(e);
+        const uint32_t tb = (KB == KIND_HUFF) ? rb.next(same) : db.get(e);
         e++;
         return combine<ANY_RAW>(ta, KA == KIND_RAW, tb, KB == KIND_RAW, A.step, overflow);
     };
@@ -442,12 +468,12 @@ __device__ inline void run_segments(const DecodeArgs& A, const SegCtx& C, HuffRe
         if (KA == KIND_HUFF) {
             const bool sched = (--due_a == 0);                           // uniform over the workgroup
             if (sched) due_a = ca;
-            if (sched || ra.pos >= kWinRunLimit) ra.reload();
+            if (sched || ra.pos() >= kWinRunLimit) ra.reload();
         }
         if (MODE == 1 && KB == KIND_HUFF) {
             const bool sched = (--due_b == 0);
             if (sched) due_b = cb;
-            if (sched || rb.pos >= kWinRunLimit) rb.reload();
+            if (sched || rb.pos() >= kWinRunLimit) rb.reload();
         }
     };
     for (uint32_t r0 = 0; r0 < kSeg; r0 += kTileR) {
@@ -467,7 +493,6 @@ __device__ inline void run_segments(const DecodeArgs& A, const SegCtx& C, HuffRe
             }
         }
         __syncthreads();
-#ifndef NZ_EXP_NO_OUTPUT
 #pragma unroll
         for (uint32_t k = 0; k < LPR; k++) {
             const uint32_t g = tid + kDecThreads * k;
@@ -481,7 +506,6 @@ __device__ inline void run_segments(const DecodeArgs& A, const SegCtx& C, HuffRe
                 emit4<MODE>(A, C, eo, m, t, MODE == 0 ? false : ANY_RAW, s_h, ncs, copy, zmax);
             }
         }
-#endif
         __syncthreads();
     }
     if (MODE == 1) {
@@ -497,7 +521,8 @@ __device__ inline void run_segments(const DecodeArgs& A, const SegCtx& C, HuffRe
 constexpr uint32_t kTile16R = 32;
 constexpr uint32_t kTile16Stride = kTile16R + 2;     // halfwords per row: 17 words, an odd word stride
 
-__device__ inline void run_decompress_huff(const DecodeArgs& A, const SegCtx& C, HuffReader& ra, DecShared* S, uint32_t ca) {
+template <typename SH>
+__device__ inline void run_decompress_huff(const DecodeArgs& A, const SegCtx& C, HuffReader& ra, SH* S, uint32_t ca) {
     static_assert(kDecThreads * kTile16Stride * 2 <= sizeof(S->u.tile), "16-bit tile must fit the tile storage");
     const uint32_t tid = C.tid;
     uint16_t* tile = reinterpret_cast<uint16_t*>(S->u.tile);
@@ -508,14 +533,13 @@ __device__ inline void run_decompress_huff(const DecodeArgs& A, const SegCtx& C,
     auto start_run = [&]() {
         const bool sched = (--due == 0);              // uniform over the workgroup
         if (sched) due = ca;
-        if (sched || ra.pos >= kWinRunLimit) ra.reload();
+        if (sched || ra.pos() >= kWinRunLimit) ra.reload();
     };
-    auto next16 = [&]() -> uint32_t {
-        uint32_t z = ra.next();
-        if (__builtin_expect(z >= 0xFFFFu, 0)) { seg_out[e] = dequantize1(unzigzag(z), A.step); z = 0xFFFFu; }
-        e++;
+    auto wide = [&](uint32_t z) -> uint32_t {        // only an escape can carry a code of 16 bits or more
+        if (z >= 0xFFFFu) { seg_out[e] = dequantize1(unzigzag(z), A.step); z = 0xFFFFu; }
         return z;
     };
+    auto next16 = [&]() -> uint32_t { const uint32_t z = ra.next(wide); e++; return z; };
     constexpr uint32_t LPR = kTile16R / 4;            // 8 lanes write one row
     for (uint32_t r0 = 0; r0 < kSeg; r0 += kTile16R) {
         if (r0 + kTile16R <= C.cntseg) {
@@ -561,9 +585,9 @@ __device__ inline void run_decompress_huff(const DecodeArgs& A, const SegCtx& C,
 }
 
 // Frames without a HUFFMAN operand: element-parallel and coalesced on both sides.
-template <int MODE>
+template <int MODE, typename SH>
 __device__ inline void run_elementwise(const DecodeArgs& A, const SegCtx& C, uint32_t blk0, const DirectFetch& da,
-                                       const DirectFetch& db, DecShared* S, uint32_t* s_h, uint32_t ncs, uint32_t& overflow) {
+                                       const DirectFetch& db, SH* S, uint32_t* s_h, uint32_t ncs, uint32_t& overflow) {
     const uint32_t cnt = (C.nf - blk0 < kDecBlock) ? (C.nf - blk0) : kDecBlock;
     const uint32_t copy = C.lane & ((1u << ncs) - 1u);
     const bool a_raw = da.kind == KIND_RAW, b_raw = (MODE == 1) && db.kind == KIND_RAW;
@@ -593,8 +617,7 @@ __device__ inline void run_elementwise(const DecodeArgs& A, const SegCtx& C, uin
 template <int MODE>
 __global__ __launch_bounds__(kDecThreads) void k_decode(DecodeArgs A) {
     __shared__ DecTables s_t[MODE == 1 ? 2 : 1];
-    __shared__ DecShared S;
-    __shared__ DecWindows<(MODE == 1 ? 2 : 1)> s_win;
+    __shared__ DecShared<(MODE == 1 ? 2 : 1)> S;
     __shared__ uint32_t s_h[MODE == 1 ? 2048 : 1];
 
     const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
@@ -661,8 +684,8 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(DecodeArgs A) {
     const uint32_t* safe = reinterpret_cast<const uint32_t*>(A.res);
     HuffReader ra, rb;
     DirectFetch da, dbf;
-    ra.init(va, &s_t[0], bit_a, safe, &s_win.w[0][tid]);
-    rb.init(vb, &s_t[MODE == 1 ? 1 : 0], bit_b, safe, &s_win.w[MODE == 1 ? 1 : 0][tid]);
+    ra.init(va, &s_t[0], bit_a, safe, &S.win[0][tid]);
+    rb.init(vb, &s_t[MODE == 1 ? 1 : 0], bit_b, safe, &S.win[MODE == 1 ? 1 : 0][tid]);
     da.init(va, safe);
     dbf.init(vb, safe);
     SegCtx C;
@@ -670,10 +693,6 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(DecodeArgs A) {
     C.vec_ok = ((f0 & 3u) == 0);
     uint32_t overflow = 0;
 
-#ifdef NZ_EXP_NO_DECODE
-    if (tid == 0 && va.cadence == 77) res->reserved = bit_a + bit_b;
-    return;
-#endif
     if (MODE == 0) {
         if (va.kind == KIND_HUFF) {
             run_decompress_huff(A, C, ra, &S, va.cadence);

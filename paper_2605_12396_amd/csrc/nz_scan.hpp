@@ -68,18 +68,28 @@ __device__ inline void canonical_tables(const uint8_t* s_len, uint32_t K, uint32
         if (s < K) s_rank[s] = (uint16_t)rank;
     }
     __syncthreads();
-    // per length: exclusive prefix over the 16 groups, total count
-    if (tid < 32) {
+    // per length (lane = length, wave 0): exclusive prefix over the 16 groups and the total count, then
+    // idx0 = exclusive scan of the counts and first[L] = sum over l < L of cnt[l] << (L - l), taken as an
+    // exclusive scan of the counts left-justified to 28 bits (the Kraft sum is at most 1, so it fits).
+    if (tid < 64) {
         uint32_t run = 0;
-        for (uint32_t g = 0; g < 16; g++) { uint32_t c = s_wcnt[g * 32 + tid]; s_wcnt[g * 32 + tid] = run; run += c; }
-        s_cnt[tid] = tid ? run : 0u;
+        if (tid >= 1 && tid <= kMaxLen) {
+            uint32_t c[16];
+#pragma unroll
+            for (uint32_t g = 0; g < 16; g++) c[g] = s_wcnt[g * 32 + tid];
+#pragma unroll
+            for (uint32_t g = 0; g < 16; g++) { s_wcnt[g * 32 + tid] = run; run += c[g]; }
+        }
+        const uint32_t lj = (tid >= 1 && tid <= kMaxLen) ? (run << (kMaxLen - tid)) : 0u;
+        const uint32_t incl_i = wave_incl_scan_dpp(run);
+        const uint32_t incl_f = wave_incl_scan_dpp(lj);
+        if (tid < 32) {
+            s_cnt[tid] = run;
+            s_idx0[tid] = incl_i - run;
+            s_first[tid] = (tid <= kMaxLen) ? ((incl_f - lj) >> (kMaxLen - tid)) : (incl_f << (tid - kMaxLen));
+        }
     }
     __syncthreads();
-    if (tid == 0) {
-        uint32_t c = 0, idx = 0;
-        s_first[0] = 0; s_idx0[0] = 0;
-        for (uint32_t L = 1; L < 32; L++) { c = (c + s_cnt[L - 1]) << 1; s_first[L] = c; s_idx0[L] = idx; idx += s_cnt[L]; }
-    }
     for (uint32_t base = 0; base < K; base += NT) {
         const uint32_t s = base + tid;
         if (s < K) { const uint32_t L = s_len[s]; if (L) s_rank[s] = (uint16_t)(s_rank[s] + s_wcnt[(s >> 6) * 32 + L]); }
