@@ -27,9 +27,10 @@ enum : uint32_t { CODEC_RAW = 0, CODEC_FIXED = 1, CODEC_HUFF = 2 };
 constexpr uint32_t kStatThreads   = 512;
 constexpr uint32_t kStatBlock     = 32768;       // symbols per statistics workgroup (compress)
 constexpr uint32_t kEncThreads    = 256;
-constexpr uint32_t kEncBlock      = 4096;        // symbols per encode workgroup = 16 segments
+constexpr uint32_t kEncBlock      = 4096;        // symbols per encode sub-block = 16 segments
 constexpr uint32_t kEncIters      = kEncBlock / (kEncThreads * 4);   // passes of 1024 symbols
-constexpr uint32_t kEncSegs       = kEncBlock / kSeg;                // segments per encode workgroup
+constexpr uint32_t kEncSegs       = kEncBlock / kSeg;                // segments per encode sub-block
+constexpr uint32_t kEncGroup      = 65536;       // symbols per encode workgroup: a whole number of statistics blocks
 constexpr uint32_t kDecThreads    = 256;
 constexpr uint32_t kDecBlock      = kDecThreads * kSeg;              // 65536 symbols per decode workgroup
 constexpr uint32_t kBookThreads   = 1024;

@@ -332,270 +332,280 @@ __global__ __launch_bounds__(kBookThreads) void k_codebook(CompressArgs A) {
 }
 
 // ------------------------------------------------------------------------------------------------
-// K4: encoder.  One workgroup per statistics block of one frame (32768 symbols for compress, 65536 for
-// the reduce), worked through in sub-blocks of kEncBlock symbols; the next sub-block's source words are
-// loaded while the current one is packed.
+// K4: encoder.  One workgroup per group of kEncGroup symbols of one frame (a whole number of statistics
+// blocks), worked through in sub-blocks of kEncBlock symbols.
 //   RAW      copy the words.
 //   FIXEDLEN w bits per zigzag code at closed-form positions (a pass of 1024 codes is 32*w whole words).
-//   HUFFMAN  the workgroup's first bit in the frame's bitstream comes from the codebook kernel, so there is
-//            no scan and no waiting between workgroups.  Per sub-block: phase 1 looks every symbol up once,
+//   HUFFMAN  the group's first bit in the frame's bitstream comes from the codebook kernel, so there is no
+//            scan and no waiting between workgroups.  Per sub-block: phase 1 looks every symbol up once,
 //            packs the 4 symbols of a thread (codes, and the 32 raw bits of an escape) into 64 bits and scans
-//            the bit counts on the DPP network (segment table entries fall out of the scan); phase 2 ORs the
-//            packed strings into an LDS stage at their final bit positions and flushes whole words
-//            coalesced.  The word in which two workgroups meet was cleared by the codebook kernel and
-//            receives both parts by atomic OR; every other word has a single writer.
+//            the bit counts on the DPP network (segment table entries fall out of the scan); the source words
+//            of the next sub-block are requested as soon as phase 1 has used the current ones; phase 2 ORs
+//            the packed strings into an LDS stage at their final bit positions; whole words are then flushed
+//            coalesced while the partial last word moves on to the other of two stages, which makes two
+//            barriers per sub-block enough.  The word in which two groups meet was cleared by the codebook
+//            kernel and receives both parts by atomic OR; every other word has a single writer.
 // SRC = 0: symbols are quantized from the fp32 input; SRC = 1: symbols are the int32 codes staged in the
 // workspace by the reduce front end (RAW frames hold fp32 bit patterns there).
 // ------------------------------------------------------------------------------------------------
+constexpr uint32_t kStageWords = 2048;        // one stage holds a sub-block of up to ~16 bits per symbol at once
+
+struct EncShared {
+    uint64_t book[kMaxK];                      // by min(z, K-1): reversed code | length << 32; entry K-1 = escape
+    uint32_t stage[2][kStageWords + 4];
+    __align__(16) uint32_t wtot[kEncSegs];     // bit count of each of the sub-block's segments
+};
+
+// zigzag code of a source word
 template <int SRC>
-__global__ __launch_bounds__(kEncThreads) void k_encode(CompressArgs A) {
-    constexpr uint32_t kStageWords = 2048;
-    __shared__ uint64_t s_book[kMaxK];            // reversed code | length << 32
-    __shared__ uint32_t s_stage[kStageWords];
-    __shared__ uint32_t s_wtot[kEncSegs];         // bit count of each of the sub-block's segments
-    __shared__ uint32_t s_pbase[kEncIters + 1];   // bit offset of every pass inside the sub-block
+__device__ inline uint32_t enc_zz(uint32_t w, const CompressArgs& A) {
+    if (SRC == 0) { int32_t t; quantize1(__uint_as_float(w), A.eb, A.step, A.inv_step, t); return zigzag(t); }
+    return zigzag((int32_t)w);
+}
 
-    const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
-    const uint32_t frame = blockIdx.x / A.sbpf, gb = blockIdx.x % A.sbpf;
-    const uint64_t f0 = (uint64_t)frame * A.chunk;
-    const uint32_t nf = (uint32_t)((A.n - f0 < A.chunk) ? (A.n - f0) : A.chunk);
-    const uint32_t g0 = gb * A.stat_block;                               // first symbol of this workgroup in the frame
-    if (g0 >= nf) return;
-    const uint32_t gcnt = (nf - g0 < A.stat_block) ? (nf - g0) : A.stat_block;
-    const bool last_grp = (g0 + gcnt == nf);
-    const uint32_t nsub = (gcnt + kEncBlock - 1) / kEncBlock;
-    const uint32_t K = A.K;
-    // source words: fp32 input (SRC 0) or the staged codes / fp32 sums of the reduce (SRC 1)
-    const uint32_t* gsrc = (SRC == 0 ? reinterpret_cast<const uint32_t*>(A.in) : reinterpret_cast<const uint32_t*>(A.ws + A.L.codes)) + f0 + g0;
-    const bool vec_ok = (((f0 + g0) & 3u) == 0);                         // kEncBlock is a multiple of 4
+// Geometry of one encode workgroup.
+struct EncGroup {
+    const uint32_t* src;      // first source word of the group
+    uint32_t g0, gcnt, nf, nsub, gb;
+    bool vec_ok, last_grp;
+};
 
-    // loads of one sub-block: pass `it` covers its symbols it*1024 + tid*4 .. +3
-    auto load_sub = [&](uint32_t sb, uint32_t (&raw)[kEncIters][4]) {
-        const uint32_t* src = gsrc + sb * kEncBlock;
-        const uint32_t cnt = (sb < nsub) ? ((gcnt - sb * kEncBlock < kEncBlock) ? (gcnt - sb * kEncBlock) : kEncBlock) : 0u;
+// Source words of sub-block sb: pass `it` covers its symbols it*1024 + tid*4 .. +3 (zero past the end).
+__device__ inline void enc_load(const EncGroup& G, uint32_t sb, uint32_t (&raw)[kEncIters][4]) {
+    const uint32_t tid = threadIdx.x;
+    const uint32_t* src = G.src + sb * kEncBlock;
+    const uint32_t cnt = (sb < G.nsub) ? ((G.gcnt - sb * kEncBlock < kEncBlock) ? (G.gcnt - sb * kEncBlock) : kEncBlock) : 0u;
+    if (G.vec_ok && cnt == kEncBlock) {                                  // uniform: the common, branch-free case
 #pragma unroll
         for (uint32_t it = 0; it < kEncIters; it++) {
+            const uint4 t = *reinterpret_cast<const uint4*>(src + it * 1024 + tid * 4);
+            raw[it][0] = t.x; raw[it][1] = t.y; raw[it][2] = t.z; raw[it][3] = t.w;
+        }
+    } else {
+#pragma unroll 1
+        for (uint32_t it = 0; it < kEncIters; it++) {
             const uint32_t i = it * 1024 + tid * 4;
-            const uint32_t mvalid = (i < cnt) ? ((cnt - i < 4) ? (cnt - i) : 4u) : 0u;
-            if (vec_ok && mvalid == 4) {
-                const uint4 t = *reinterpret_cast<const uint4*>(src + i);
-                raw[it][0] = t.x; raw[it][1] = t.y; raw[it][2] = t.z; raw[it][3] = t.w;
-            } else {
+            uint32_t t[4];
 #pragma unroll
-                for (uint32_t j = 0; j < 4; j++) raw[it][j] = (j < mvalid) ? src[i + j] : 0u;
+            for (uint32_t j = 0; j < 4; j++) t[j] = (i + j < cnt) ? src[i + j] : 0u;
+#pragma unroll
+            for (uint32_t q = 0; q < kEncIters; q++)
+                if (q == it) { raw[q][0] = t[0]; raw[q][1] = t[1]; raw[q][2] = t[2]; raw[q][3] = t[3]; }
+        }
+    }
+}
+
+template <int SRC>
+__device__ inline void enc_raw_fixed(const CompressArgs& A, const EncGroup& G, const FrameMeta& M, uint8_t* fr, uint32_t* stage) {
+    const uint32_t tid = threadIdx.x;
+    if (M.codec == CODEC_RAW) {
+        uint32_t* dst = reinterpret_cast<uint32_t*>(fr + kHdrBytes) + G.g0;
+        for (uint32_t i = tid * 4; i < G.gcnt; i += kEncThreads * 4) {
+            if (G.vec_ok && i + 4 <= G.gcnt) *reinterpret_cast<uint4*>(dst + i) = *reinterpret_cast<const uint4*>(G.src + i);
+            else for (uint32_t j = 0; j < 4; j++) if (i + j < G.gcnt) dst[i + j] = G.src[i + j];
+        }
+        return;
+    }
+    // FIXEDLEN: passes of 1024 codes = 32*w whole words, staged in LDS and written coalesced
+    const uint32_t w = M.w;
+    uint32_t* bits = reinterpret_cast<uint32_t*>(fr + M.bits_off) + (G.g0 / 32u) * w;
+    for (uint32_t p0 = 0; p0 < G.gcnt; p0 += 1024) {
+        const uint32_t pass_syms = (G.gcnt - p0 < 1024u) ? (G.gcnt - p0) : 1024u;
+        const uint32_t pass_words = (pass_syms * w + 31u) / 32u;
+        uint32_t z[4];
+#pragma unroll
+        for (uint32_t j = 0; j < 4; j++) z[j] = (tid * 4 + j < pass_syms) ? enc_zz<SRC>(G.src[p0 + tid * 4 + j], A) : 0u;
+        for (uint32_t k = tid; k < pass_words; k += kEncThreads) stage[k] = 0;
+        __syncthreads();
+        uint32_t pos = tid * 4 * w;
+#pragma unroll
+        for (uint32_t j = 0; j < 4; j++) {
+            if (tid * 4 + j < pass_syms && w) {
+                const uint32_t sh = pos & 31u, wi = pos >> 5;
+                atomicOr(&stage[wi], z[j] << sh);
+                if (sh + w > 32u) atomicOr(&stage[wi + 1], z[j] >> (32u - sh));
+                pos += w;
             }
         }
-    };
-    uint32_t raw[kEncIters][4], nxt[kEncIters][4];
-    load_sub(0, raw);
+        __syncthreads();
+        uint32_t* dst = bits + (p0 / 32u) * w;
+        for (uint32_t k = tid; k < pass_words; k += kEncThreads) dst[k] = stage[k];
+        __syncthreads();
+    }
+}
+
+template <int SRC>
+__global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))) void k_encode(CompressArgs A) {
+    __shared__ EncShared S;
+    const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const uint32_t gpf = (A.chunk + kEncGroup - 1) / kEncGroup;
+    const uint32_t frame = blockIdx.x / gpf;
+    EncGroup G;
+    G.gb = blockIdx.x % gpf;
+    const uint64_t f0 = (uint64_t)frame * A.chunk;
+    G.nf = (uint32_t)((A.n - f0 < A.chunk) ? (A.n - f0) : A.chunk);
+    G.g0 = G.gb * kEncGroup;                                             // first symbol of this group in the frame
+    if (G.g0 >= G.nf) return;
+    G.gcnt = (G.nf - G.g0 < kEncGroup) ? (G.nf - G.g0) : kEncGroup;
+    G.last_grp = (G.g0 + G.gcnt == G.nf);
+    G.nsub = (G.gcnt + kEncBlock - 1) / kEncBlock;
+    // source words: fp32 input (SRC 0) or the staged codes / fp32 sums of the reduce (SRC 1)
+    G.src = (SRC == 0 ? reinterpret_cast<const uint32_t*>(A.in) : reinterpret_cast<const uint32_t*>(A.ws + A.L.codes)) + f0 + G.g0;
+    G.vec_ok = (((f0 + G.g0) & 3u) == 0);                                // kEncBlock is a multiple of 4
+    const uint32_t K = A.K, kesc = K - 1u;
+
     const FrameMeta M = reinterpret_cast<const FrameMeta*>(A.ws + A.L.meta)[frame];
     if (!M.fits) return;
     uint8_t* fr = A.out + M.offset;
-    // zigzag code of a source word
-    auto zz = [&](uint32_t w) -> uint32_t {
-        if (SRC == 0) { int32_t t; quantize1(__uint_as_float(w), A.eb, A.step, A.inv_step, t); return zigzag(t); }
-        return zigzag((int32_t)w);
-    };
-    auto pad_frame = [&]() {     // the frame's last workgroup zero-fills the padding after the payload
-        if (last_grp) {
-            const uint32_t w0 = (kHdrBytes + M.payload) / 4, w1 = M.total / 4;
-            if (tid < w1 - w0) reinterpret_cast<uint32_t*>(fr)[w0 + tid] = 0;
+    if (M.codec != CODEC_HUFF) enc_raw_fixed<SRC>(A, G, M, fr, S.stage[0]);
+    else {
+        uint32_t raw[kEncIters][4];
+        enc_load(G, 0, raw);
+        for (uint32_t s = tid; s < K; s += kEncThreads) {
+            const uint32_t sy = (s == kesc) ? 0u : s + 1u;
+            const uint32_t c = reinterpret_cast<const uint32_t*>(A.ws + A.L.book_code)[(size_t)frame * kMaxK + sy];
+            const uint32_t l = (A.ws + A.L.book_len)[(size_t)frame * kMaxK + sy];
+            S.book[s] = (uint64_t)c | ((uint64_t)l << 32);
         }
-    };
-
-    // ---- RAW: copy the words ----
-    if (M.codec == CODEC_RAW) {
-        uint32_t* dst = reinterpret_cast<uint32_t*>(fr + kHdrBytes) + g0;
-        for (uint32_t i = tid * 4; i < gcnt; i += kEncThreads * 4) {
-            if (vec_ok && i + 4 <= gcnt) *reinterpret_cast<uint4*>(dst + i) = *reinterpret_cast<const uint4*>(gsrc + i);
-            else for (uint32_t j = 0; j < 4; j++) if (i + j < gcnt) dst[i + j] = gsrc[i + j];
-        }
-        pad_frame();
-        return;
-    }
-    uint32_t* bits = reinterpret_cast<uint32_t*>(fr + M.bits_off);
-
-    // ---- FIXEDLEN ----
-    if (M.codec == CODEC_FIXED) {
-        const uint32_t w = M.w;
-        for (uint32_t sb = 0; sb < nsub; sb++) {
-            const uint32_t cnt = (gcnt - sb * kEncBlock < kEncBlock) ? (gcnt - sb * kEncBlock) : kEncBlock;
-            load_sub(sb + 1, nxt);
-            const uint32_t wblk = ((g0 + sb * kEncBlock) / 32u) * w;     // first bitstream word of this sub-block
-#pragma unroll
-            for (uint32_t it = 0; it < kEncIters; it++) {
-                if (it * 1024 < cnt) {
-                    const uint32_t i = it * 1024 + tid * 4;
-                    const uint32_t pass_syms = (cnt - it * 1024 < 1024u) ? (cnt - it * 1024) : 1024u;
-                    const uint32_t pass_words = (pass_syms * w + 31u) / 32u;
-                    for (uint32_t k = tid; k < pass_words; k += kEncThreads) s_stage[k] = 0;
-                    __syncthreads();
-                    uint32_t pos = tid * 4 * w;
-#pragma unroll
-                    for (uint32_t j = 0; j < 4; j++) {
-                        if (i + j < cnt && w) {
-                            const uint32_t z = zz(raw[it][j]);
-                            const uint32_t sh = pos & 31u, wi = pos >> 5;
-                            atomicOr(&s_stage[wi], z << sh);
-                            if (sh + w > 32u) atomicOr(&s_stage[wi + 1], z >> (32u - sh));
-                            pos += w;
-                        }
-                    }
-                    __syncthreads();
-                    uint32_t* dst = bits + wblk + it * 32u * w;
-                    for (uint32_t k = tid; k < pass_words; k += kEncThreads) dst[k] = s_stage[k];
-                    __syncthreads();
-                }
-            }
-#pragma unroll
-            for (uint32_t it = 0; it < kEncIters; it++)
-#pragma unroll
-                for (uint32_t j = 0; j < 4; j++) raw[it][j] = nxt[it][j];
-        }
-        pad_frame();
-        return;
-    }
-
-    // ---- HUFFMAN ----
-    for (uint32_t s = tid; s < K; s += kEncThreads) {
-        const uint32_t c = reinterpret_cast<const uint32_t*>(A.ws + A.L.book_code)[(size_t)frame * kMaxK + s];
-        const uint32_t l = (A.ws + A.L.book_len)[(size_t)frame * kMaxK + s];
-        s_book[s] = (uint64_t)c | ((uint64_t)l << 32);
-    }
-    for (uint32_t i = tid; i < kStageWords; i += kEncThreads) s_stage[i] = 0;
-    const uint32_t start_bit = reinterpret_cast<const uint32_t*>(A.ws + A.L.grp_start)[blockIdx.x];
-    const uint32_t c0 = start_bit & 31u;          // bits of the first word that belong to the previous workgroup
-    const uint32_t w_first = start_bit >> 5;
-    uint16_t* segt = reinterpret_cast<uint16_t*>(fr + M.segt_off);
-    const uint32_t nseg = (nf + kSeg - 1) / kSeg;
-    uint32_t run_bits = c0;                       // bits in front of the current sub-block, from stage origin
-    uint32_t flushed = 0;                         // stage-origin words already written out
-    __syncthreads();
-
-    for (uint32_t sb = 0; sb < nsub; sb++) {
-        const uint32_t cnt = (gcnt - sb * kEncBlock < kEncBlock) ? (gcnt - sb * kEncBlock) : kEncBlock;
-        load_sub(sb + 1, nxt);
-        uint64_t pk[kEncIters];                   // the thread's 4 symbols of a pass packed LSB-first
-        uint32_t ln[kEncIters];                   // exclusive bit offset of the thread inside its pass
-        uint32_t wide = 0;                        // pass mask: the 4 symbols need more than 64 bits
-        // phase 1
-#pragma unroll
-        for (uint32_t it = 0; it < kEncIters; it++) {
-            const uint32_t i = it * 1024 + tid * 4;
-            uint64_t acc = 0;
-            uint32_t tl = 0;
-#pragma unroll
-            for (uint32_t j = 0; j < 4; j++) {
-                if (i + j < cnt) {
-                    const uint32_t z = zz(raw[it][j]);
-                    const uint32_t sy = sym_of(z, K);
-                    const uint64_t b = s_book[sy];
-                    if (tl < 64u) acc |= (uint64_t)(uint32_t)b << tl;
-                    tl += (uint32_t)(b >> 32);
-                    if (sy == 0) { if (tl < 64u) acc |= (uint64_t)z << tl; tl += 32u; }
-                }
-            }
-            pk[it] = acc;
-            wide |= (tl > 64u ? 1u : 0u) << it;
-            const uint32_t incl = wave_incl_scan_dpp(tl);
-            ln[it] = incl - tl;                                       // exclusive inside the wave's segment
-            if (lane == 63) s_wtot[it * 4 + wave] = incl;             // bits of segment it*4 + wave
-        }
-        __syncthreads();
-        uint32_t block_bits = 0;
-#pragma unroll
-        for (uint32_t it = 0; it < kEncIters; it++) {
-            if (tid == 0) s_pbase[it] = block_bits;
-#pragma unroll
-            for (uint32_t w = 0; w < 4; w++) {
-                const uint32_t t = s_wtot[it * 4 + w];
-                if (w < wave) ln[it] += t;                                // now exclusive inside the pass
-                block_bits += t;
-            }
-        }
-        if (tid == 0) s_pbase[kEncIters] = block_bits;
-        if (tid < kEncSegs) {
-            const uint32_t gseg = (g0 + sb * kEncBlock) / kSeg + tid;
-            if (gseg < nseg) segt[gseg] = (uint16_t)s_wtot[tid];
-            if (gseg == nseg - 1 && (nseg & 1u)) segt[nseg] = 0;          // pad4 of the table
-        }
+        for (uint32_t i = tid; i < 2 * (kStageWords + 4); i += kEncThreads) (&S.stage[0][0])[i] = 0;
+        const uint32_t start_bit = reinterpret_cast<const uint32_t*>(A.ws + A.L.grp_start)[(size_t)frame * A.sbpf + G.g0 / A.stat_block];
+        uint32_t* bits = reinterpret_cast<uint32_t*>(fr + M.bits_off) + (start_bit >> 5);   // first word this group touches
+        uint16_t* segt = reinterpret_cast<uint16_t*>(fr + M.segt_off);
+        const uint32_t nseg = (G.nf + kSeg - 1) / kSeg;
+        uint32_t rel = start_bit & 31u;           // bits already in the current stage (carried over)
+        uint32_t flushed = 0;                     // words of the group already written out
+        uint32_t cur = 0;                         // stage in use
+        uint32_t carry = 0;                       // thread 0: the partial word carried into the current stage
         __syncthreads();
 
-        // phase 2: as many passes at a time as fit the stage
-        uint32_t it0 = 0;
-        while (it0 < kEncIters && it0 * 1024 < cnt) {
-            uint32_t it1 = it0 + 1;
-            while (it1 < kEncIters && run_bits + s_pbase[it1 + 1] - 32u * flushed <= 32u * (kStageWords - 2)) it1++;
+        // Write the whole words of stage X to the bitstream, clear them, and move the partial word to Y[0].
+        auto flush = [&](uint32_t* X, uint32_t* Y, uint32_t nbits) {
+            const uint32_t nw = nbits >> 5;
+            uint32_t* dst = bits + flushed;
+            for (uint32_t k = tid; k < nw; k += kEncThreads) {
+                const uint32_t wv = X[k];
+                X[k] = 0;
+                if (G.gb > 0 && flushed == 0 && k == 0) atomicOr(dst, wv);   // word shared with the previous group
+                else dst[k] = wv;
+            }
+            if (tid == 0) { carry = X[nw]; X[nw] = 0; Y[0] = carry; }
+            flushed += nw;
+            rel = nbits & 31u;
+        };
+        // One symbol's code (and the raw bits of an escape) ORed into stage X at bit position pos.
+        auto put_symbol = [&](uint32_t* X, uint32_t z, uint32_t& pos) {
+            const uint64_t b = S.book[z < kesc ? z : kesc];
+            const uint32_t val = (uint32_t)b, len = (uint32_t)(b >> 32);
+            if (len) {
+                const uint32_t sh = pos & 31u, wi = pos >> 5;
+                atomicOr(&X[wi], val << sh);
+                if (sh + len > 32u) atomicOr(&X[wi + 1], val >> (32u - sh));
+                pos += len;
+            }
+            if (z >= kesc) {
+                const uint32_t sh = pos & 31u, wi = pos >> 5;
+                atomicOr(&X[wi], z << sh);
+                if (sh) atomicOr(&X[wi + 1], z >> (32u - sh));
+                pos += 32u;
+            }
+        };
+
+        for (uint32_t sb = 0; sb < G.nsub; sb++) {
+            const uint32_t cnt = (G.gcnt - sb * kEncBlock < kEncBlock) ? (G.gcnt - sb * kEncBlock) : kEncBlock;
+            const uint32_t* sub_src = G.src + sb * kEncBlock;
+            uint64_t pk[kEncIters];               // the thread's 4 symbols of a pass packed LSB-first
+            uint32_t ln[kEncIters];               // exclusive bit offset of the thread inside its pass
+            uint32_t wide = 0;                    // pass mask: the 4 symbols need more than 64 bits
+            // phase 1
 #pragma unroll
             for (uint32_t it = 0; it < kEncIters; it++) {
-                if (it >= it0 && it < it1) {
-                    const uint32_t i = it * 1024 + tid * 4;
-                    uint32_t pos = run_bits + s_pbase[it] + ln[it] - 32u * flushed;
-                    if (!((wide >> it) & 1u)) {
+                const uint32_t i = it * 1024 + tid * 4;
+                uint64_t acc = 0;
+                uint32_t tl = 0;
+#pragma unroll
+                for (uint32_t j = 0; j < 4; j++) {
+                    const uint32_t z = enc_zz<SRC>(raw[it][j], A);
+                    const uint64_t b = S.book[z < kesc ? z : kesc];
+                    const bool valid = (cnt == kEncBlock) || i + j < cnt;
+                    const uint32_t len = valid ? (uint32_t)(b >> 32) : 0u, code = valid ? (uint32_t)b : 0u;
+                    acc |= (uint64_t)code << (tl & 63u);                  // garbage once tl > 64: the pass is then redone
+                    tl += len;
+                    if (z >= kesc && valid) { acc |= (uint64_t)z << (tl & 63u); tl += 32u; }
+                }
+                pk[it] = acc;
+                wide |= (tl > 64u ? 1u : 0u) << it;
+                const uint32_t incl = wave_incl_scan_dpp(tl);
+                ln[it] = incl - tl;                                   // exclusive inside the wave's segment
+                if (lane == 63) S.wtot[it * 4 + wave] = incl;         // bits of segment it*4 + wave
+            }
+            enc_load(G, sb + 1, raw);             // the next sub-block's words arrive during phase 2 and the flush
+            __syncthreads();
+            uint32_t pbase[kEncIters + 1];        // bit offset of every pass inside the sub-block
+            pbase[0] = 0;
+#pragma unroll
+            for (uint32_t it = 0; it < kEncIters; it++) {
+                const uint4 t = reinterpret_cast<const uint4*>(S.wtot)[it];
+                ln[it] += (wave > 0 ? t.x : 0u) + (wave > 1 ? t.y : 0u) + (wave > 2 ? t.z : 0u);   // exclusive inside the pass
+                pbase[it + 1] = pbase[it] + t.x + t.y + t.z + t.w;
+            }
+            if (tid < kEncSegs) {
+                const uint32_t gseg = (G.g0 + sb * kEncBlock) / kSeg + tid;
+                if (gseg < nseg) segt[gseg] = (uint16_t)S.wtot[tid];
+                if (gseg == nseg - 1 && (nseg & 1u)) segt[nseg] = 0;      // pad4 of the table
+            }
+            uint32_t* X = S.stage[cur];
+            if (__builtin_expect(rel + pbase[kEncIters] <= 32u * kStageWords, 1)) {
+                // phase 2: the whole sub-block into the stage
+#pragma unroll
+                for (uint32_t it = 0; it < kEncIters; it++) {
+                    uint32_t pos = rel + pbase[it] + ln[it];
+                    if (__builtin_expect(!((wide >> it) & 1u), 1)) {
                         const uint64_t a = pk[it];
                         if (a) {
                             const uint32_t sh = pos & 31u, wi = pos >> 5;
                             const uint64_t t = a << sh;
-                            atomicOr(&s_stage[wi], (uint32_t)t);
-                            if ((uint32_t)(t >> 32)) atomicOr(&s_stage[wi + 1], (uint32_t)(t >> 32));
-                            if (sh) { const uint32_t hi = (uint32_t)(a >> (64u - sh)); if (hi) atomicOr(&s_stage[wi + 2], hi); }
+                            atomicOr(&X[wi], (uint32_t)t);
+                            if ((uint32_t)(t >> 32)) atomicOr(&X[wi + 1], (uint32_t)(t >> 32));
+                            if (sh) { const uint32_t hi = (uint32_t)(a >> (64u - sh)); if (hi) atomicOr(&X[wi + 2], hi); }
                         }
                     } else {
-                        // the pass needs more than 64 bits (rare): emit symbol by symbol
-#pragma unroll
-                        for (uint32_t j = 0; j < 4; j++) {
-                            if (i + j < cnt) {
-                                const uint32_t z = zz(raw[it][j]);
-                                const uint32_t sy = sym_of(z, K);
-                                const uint64_t b = s_book[sy];
-                                const uint32_t val = (uint32_t)b, len = (uint32_t)(b >> 32);
-                                if (len) {
-                                    const uint32_t sh = pos & 31u, wi = pos >> 5;
-                                    atomicOr(&s_stage[wi], val << sh);
-                                    if (sh + len > 32u) atomicOr(&s_stage[wi + 1], val >> (32u - sh));
-                                    pos += len;
-                                }
-                                if (sy == 0) {
-                                    const uint32_t sh = pos & 31u, wi = pos >> 5;
-                                    atomicOr(&s_stage[wi], z << sh);
-                                    if (sh) atomicOr(&s_stage[wi + 1], z >> (32u - sh));
-                                    pos += 32u;
-                                }
-                            }
-                        }
+                        // the thread's 4 symbols need more than 64 bits (rare): symbol by symbol from the source
+                        const uint32_t i = it * 1024 + tid * 4;
+                        for (uint32_t j = 0; j < 4; j++)
+                            if (i + j < cnt) put_symbol(X, enc_zz<SRC>(sub_src[i + j], A), pos);
                     }
                 }
+                __syncthreads();
+                flush(X, S.stage[cur ^ 1u], rel + pbase[kEncIters]);
+                cur ^= 1u;
+            } else {
+                // more bits than the stage holds at once (rare): pass by pass, symbol by symbol from the source
+#pragma unroll 1
+                for (uint32_t it = 0; it < kEncIters; it++) {
+                    const uint32_t i = it * 1024 + tid * 4;
+                    uint32_t lnit = 0, pbits = 0;
+#pragma unroll
+                    for (uint32_t q = 0; q < kEncIters; q++) if (q == it) { lnit = ln[q]; pbits = pbase[q + 1] - pbase[q]; }
+                    uint32_t pos = rel + lnit;
+                    for (uint32_t j = 0; j < 4; j++)
+                        if (i + j < cnt) put_symbol(X, enc_zz<SRC>(sub_src[i + j], A), pos);
+                    __syncthreads();
+                    flush(X, X, rel + pbits);
+                    __syncthreads();
+                }
             }
-            __syncthreads();
-            const uint32_t nbits = run_bits + s_pbase[it1] - 32u * flushed;  // bits now in the stage
-            const uint32_t nw = nbits >> 5;
-            const uint32_t wpos = w_first + flushed;
-            for (uint32_t k = tid; k < nw; k += kEncThreads) {
-                const uint32_t wv = s_stage[k];
-                if (gb > 0 && flushed == 0 && k == 0) atomicOr(bits + wpos, wv);   // word shared with the previous workgroup
-                else bits[wpos + k] = wv;
-            }
-            const uint32_t partial = s_stage[nw];
-            __syncthreads();
-            for (uint32_t k = tid; k <= nw + 2 && k < kStageWords; k += kEncThreads) s_stage[k] = (k == 0) ? partial : 0u;
-            flushed += nw;
-            it0 = it1;
-            __syncthreads();
         }
-        run_bits += block_bits;
-#pragma unroll
-        for (uint32_t it = 0; it < kEncIters; it++)
-#pragma unroll
-            for (uint32_t j = 0; j < 4; j++) raw[it][j] = nxt[it][j];
+        // the last, partial word: shared with the next group, or the frame's last bitstream word
+        if (tid == 0 && rel) {
+            uint32_t* dst = bits + flushed;
+            if (!G.last_grp || (G.gb > 0 && flushed == 0)) atomicOr(dst, carry);
+            else *dst = carry;
+        }
     }
-    // the last, partial word: shared with the next workgroup, or the frame's last bitstream word
-    if (tid == 0 && (run_bits & 31u)) {
-        const uint32_t partial = s_stage[0];
-        const uint32_t wpos = w_first + flushed;
-        if (!last_grp || (gb > 0 && flushed == 0)) atomicOr(bits + wpos, partial);
-        else bits[wpos] = partial;
+    if (G.last_grp) {            // the frame's last group zero-fills the padding after the payload
+        const uint32_t w0 = (kHdrBytes + M.payload) / 4, w1 = M.total / 4;
+        if (tid < w1 - w0) reinterpret_cast<uint32_t*>(fr)[w0 + tid] = 0;
     }
-    pad_frame();
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -621,8 +631,8 @@ hipError_t launch_codebook(const CompressArgs& A, hipStream_t st) {
 }
 
 hipError_t launch_encode(const CompressArgs& A, bool from_codes, hipStream_t st) {
-    if (from_codes) hipLaunchKernelGGL(k_encode<1>, dim3(A.n_frames * A.sbpf), dim3(kEncThreads), 0, st, A);
-    else hipLaunchKernelGGL(k_encode<0>, dim3(A.n_frames * A.sbpf), dim3(kEncThreads), 0, st, A);
+    if (from_codes) hipLaunchKernelGGL(k_encode<1>, dim3(A.n_frames * ((A.chunk + kEncGroup - 1) / kEncGroup)), dim3(kEncThreads), 0, st, A);
+    else hipLaunchKernelGGL(k_encode<0>, dim3(A.n_frames * ((A.chunk + kEncGroup - 1) / kEncGroup)), dim3(kEncThreads), 0, st, A);
     return hipGetLastError();
 }
 
