@@ -70,6 +70,20 @@ def cpu_baseline(wl):
                 compress_GBps=gb / (t1 - t0), decompress_GBps=gb / (t2 - t1), reduce_GBps=gb / (t4 - t3)), s
 
 
+def read_traffic(path, workload, kernel):
+    """HBM bytes per launch of `kernel` (fetch + write, calibrated against a copy kernel) from the committed
+    counter summary: lines of the form `<workload> <stage>/<kernel> fetch_bytes write_bytes`.  None if absent."""
+    try:
+        with open(path) as f:
+            for line in f:
+                t = line.split()
+                if len(t) >= 4 and not line.startswith("#") and t[0] == workload and t[1] == kernel:
+                    return float(t[2]) + float(t[3])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -79,6 +93,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rotate", type=int, default=3, help="number of distinct input copies cycled through")
     ap.add_argument("--only", default="", help="profiling aid: time only this stage (compress|decompress|reduce)")
+    ap.add_argument("--calib-copy", type=int, default=0,
+                    help="profiling aid: also run this many plain 4n-byte copy kernels (counter calibration)")
+    ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "hbm_traffic_c2.txt"),
+                    help="text summary of the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see pmc_summary.py)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures the one-GPU hot path only: run with --gpus 1 "
@@ -125,6 +143,8 @@ def main():
             c = sess.reduce(outs[k], stream_bytes, peer_stream, peer_bytes, n, eb, out=red_out)[0]
         return a | b | c
 
+    for _ in range(args.calib_copy):          # elementwise kernel reading 4n bytes and writing 4n bytes
+        torch.add(xs[0], 0.0, out=y)
     for i in range(args.warmup):
         assert step(i) == 0
     torch.cuda.synchronize()
@@ -171,8 +191,8 @@ def main():
     dom_ms = kern[dom[0]][dom[1]]
     achieved = alg[dom] / (dom_ms * 1e-3) / 1e9
     roofline = dict(bound="hbm", kernel="%s/%s" % dom, achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s",
-                    frac=achieved / HBM_PEAK_GBPS, traffic=None, kernel_ms=dom_ms,
-                    algorithmic_bytes=alg[dom])
+                    frac=achieved / HBM_PEAK_GBPS, traffic=read_traffic(args.traffic_file, wl["name"], "%s/%s" % dom),
+                    kernel_ms=dom_ms, algorithmic_bytes=alg[dom])
 
     out = dict(metric="compress+decompress+fused-reduce throughput on fp32 input bytes", value=3 * gb / (ms_per_step * 1e-3),
                unit="GB/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step,

@@ -188,9 +188,6 @@ nz_status nz_reduce_frames(const void* d_a, size_t a_bytes, const void* d_b, siz
     if (launch_init(ws + L.ctrl, L.zero_end - L.ctrl, d_res, nfr, NZ_OK, st) != hipSuccess) return NZ_ERR_HIP;
     trace_mark(st);
     if (launch_decode(D, true, st) != hipSuccess) return NZ_ERR_HIP;
-#ifdef NZ_EXP_REDUCE_STOP
-    return NZ_OK;
-#endif
     trace_mark(st);
     if (launch_codebook(A, st) != hipSuccess) return NZ_ERR_HIP;
     trace_mark(st);

@@ -49,15 +49,7 @@ __global__ __launch_bounds__(kStatThreads) void k_stats(CompressArgs A) {
     const float* src = A.in + f0 + b0;
     const bool vec_ok = (((f0 + b0) & 3u) == 0);
     uint32_t zmax = 0, unq = 0;
-    for (uint32_t i = tid * 4; i < cnt; i += kStatThreads * 4) {
-        float v[4];
-        const uint32_t m = (cnt - i < 4) ? (cnt - i) : 4;
-        if (vec_ok && m == 4) {
-            const float4 t = *reinterpret_cast<const float4*>(src + i);
-            v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
-        } else {
-            for (uint32_t j = 0; j < 4; j++) v[j] = (j < m) ? src[i + j] : 0.0f;
-        }
+    auto count4 = [&](const float (&v)[4], uint32_t m) {
 #pragma unroll
         for (uint32_t j = 0; j < 4; j++) {
             if (j < m) {
@@ -67,6 +59,30 @@ __global__ __launch_bounds__(kStatThreads) void k_stats(CompressArgs A) {
                 zmax = z > zmax ? z : zmax;
                 atomicAdd(&s_h[(sym_of(z, K) << ncs) + copy], 1u);
             }
+        }
+    };
+    if (vec_ok && cnt == kStatBlock) {
+        // whole block: four 16-byte loads in flight per thread, no bounds checks
+        constexpr uint32_t kIters = kStatBlock / (kStatThreads * 4), kDepth = 4;
+        static_assert(kIters % kDepth == 0, "statistics block must be a whole number of load groups");
+        const float4* src4 = reinterpret_cast<const float4*>(src) + tid;
+#pragma unroll 1
+        for (uint32_t g = 0; g < kIters; g += kDepth) {
+            float4 t[kDepth];
+#pragma unroll
+            for (uint32_t u = 0; u < kDepth; u++) t[u] = src4[(g + u) * kStatThreads];
+#pragma unroll
+            for (uint32_t u = 0; u < kDepth; u++) {
+                const float v[4] = { t[u].x, t[u].y, t[u].z, t[u].w };
+                count4(v, 4);
+            }
+        }
+    } else {
+        for (uint32_t i = tid * 4; i < cnt; i += kStatThreads * 4) {
+            float v[4];
+            const uint32_t m = (cnt - i < 4) ? (cnt - i) : 4;
+            for (uint32_t j = 0; j < 4; j++) v[j] = (j < m) ? src[i + j] : 0.0f;
+            count4(v, m);
         }
     }
     zmax = wave_max(zmax);

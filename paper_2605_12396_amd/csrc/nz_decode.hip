@@ -310,11 +310,7 @@ struct HuffReader {
     template <typename F>
     __device__ inline int32_t finish(uint32_t e, uint32_t w32, F&& on_escape) {
         int32_t q;
-#ifdef NZ_EXP_NO_SLOW
-        if (e < 0xFFFFFFFFu) { sh += (e >> 10) & 15u; q = (int32_t)(e << 22) >> 22; }
-#else
         if (__builtin_expect(e < 0x8000u, 1)) { sh += e >> 10; q = (int32_t)(e << 22) >> 22; }
-#endif
         else q = next_slow(e, w32, on_escape);
         const bool c = sh >= 32u;                                        // at most one word is used up per symbol here
         lo = c ? hi : lo; hi = c ? n1 : hi; k += c ? 1u : 0u; sh &= 31u;
@@ -449,9 +445,7 @@ __device__ inline void emit4(const DecodeArgs& A, const SegCtx& C, uint32_t e, u
                 if (j < m) {
                     const uint32_t z = zigzag((int32_t)t[j]);
                     zmax = z > zmax ? z : zmax;
-#ifndef NZ_EXP_NO_HIST
                     atomicAdd(&s_h[(sym_of(z, A.K) << ncs) + copy], 1u);
-#endif
                 }
             }
         }
@@ -519,9 +513,6 @@ __device__ inline void run_segments(const DecodeArgs& A, const SegCtx& C, HuffRe
             }
         }
         __syncthreads();
-#ifdef NZ_EXP_NO_OUTPUT
-        if (A.n == 77)
-#endif
 #pragma unroll
         for (uint32_t k = 0; k < LPR; k++) {
             const uint32_t g = tid + kDecThreads * k;
@@ -598,9 +589,6 @@ __device__ inline void run_decompress_huff(const DecodeArgs& A, const SegCtx& C,
             }
         }
         __syncthreads();
-#ifdef NZ_EXP_NO_OUTPUT
-        if (A.n == 77)
-#endif
         if (__builtin_expect(whole && S->flags == 0, 1)) {
             float* dst = A.out + C.f0 + eo0 + r0;
 #pragma unroll
@@ -610,7 +598,10 @@ __device__ inline void run_decompress_huff(const DecodeArgs& A, const SegCtx& C,
                 float4 v;
                 v.x = dequantize1((int32_t)(int16_t)(p0 & 0xFFFFu), A.step); v.y = dequantize1((int32_t)p0 >> 16, A.step);
                 v.z = dequantize1((int32_t)(int16_t)(p1 & 0xFFFFu), A.step); v.w = dequantize1((int32_t)p1 >> 16, A.step);
-                *reinterpret_cast<float4*>(dst + (size_t)k * (kDecThreads / LPR) * kSeg) = v;
+                // streaming store: the output is not read again here and should not displace the bitstream in L2
+                typedef float f32x4 __attribute__((ext_vector_type(4)));
+                f32x4 vv; vv.x = v.x; vv.y = v.y; vv.z = v.z; vv.w = v.w;
+                __builtin_nontemporal_store(vv, reinterpret_cast<f32x4*>(dst + (size_t)k * (kDecThreads / LPR) * kSeg));
             }
         } else {
 #pragma unroll 1
@@ -742,16 +733,10 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(DecodeArgs A) {
     C.vec_ok = ((f0 & 3u) == 0);
     uint32_t overflow = 0;
 
-#ifdef NZ_EXP_NO_DECODE
-    if (tid == 0 && va.cadence == 77) res->reserved = bit_a + bit_b;
-    return;
-#endif
     if (MODE == 0) {
         if (va.kind == KIND_HUFF) {
             run_decompress_huff(A, C, ra, &S, va.cadence);
-#ifndef NZ_EXP_ANY
             if (seg_valid && (ra.bad || ra.consumed() != seglen_a)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
-#endif
         } else {
             run_elementwise<0>(A, C, blk0, da, dbf, &S, s_h, 0, overflow);
         }
@@ -772,12 +757,10 @@ __global__ __launch_bounds__(kDecThreads) void k_decode(DecodeArgs A) {
     else if (ha) run_segments<1, KIND_HUFF, KIND_FIXED>(A, C, ra, rb, da, dbf, &S, s_h, ncs, va.cadence, vb.cadence, overflow);
     else if (va.kind == KIND_RAW) run_segments<1, KIND_RAW, KIND_HUFF>(A, C, ra, rb, da, dbf, &S, s_h, ncs, va.cadence, vb.cadence, overflow);
     else run_segments<1, KIND_FIXED, KIND_HUFF>(A, C, ra, rb, da, dbf, &S, s_h, ncs, va.cadence, vb.cadence, overflow);
-#ifndef NZ_EXP_ANY
     if (seg_valid) {
         if (ha && (ra.bad || ra.consumed() != seglen_a)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
         if (hb && (rb.bad || rb.consumed() != seglen_b)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
     }
-#endif
     if (overflow) atomicMax(&res->status, (uint32_t)ST_RANGE);
     __syncthreads();
     uint32_t* ph = reinterpret_cast<uint32_t*>(A.ws + A.L.phist) + (size_t)blockIdx.x * kMaxK;
