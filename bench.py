@@ -163,7 +163,7 @@ def main():
 
     # per-stage and per-kernel times from HIP events the library records on its stream
     names = {"compress": ["init", "stats", "codebook", "encode"], "decompress": ["init", "decode"],
-             "reduce": ["init", "decode_add", "codebook", "encode"]}
+             "reduce": ["init", "stage_a", "add_b", "codebook", "encode"]}
     acc = {k: [0.0] * len(v) for k, v in names.items()}
     reps = max(5, min(args.steps, 20))
     with nz.KernelTrace(8) as tr:
@@ -185,7 +185,8 @@ def main():
     # algorithmic bytes each kernel must move per launch (bytes per element x n): see the design doc
     alg = {("compress", "stats"): 4.0 * n, ("compress", "encode"): 4.0 * n + stream_bytes,
            ("decompress", "decode"): 4.0 * n + stream_bytes,
-           ("reduce", "decode_add"): stream_bytes + peer_bytes + 4.0 * n,
+           ("reduce", "stage_a"): stream_bytes + 2.0 * n,
+           ("reduce", "add_b"): peer_bytes + 2.0 * n + 4.0 * n,
            ("reduce", "encode"): 4.0 * n + reduce_bytes}
     dom = max(alg, key=lambda k: kern[k[0]][k[1]])
     dom_ms = kern[dom[0]][dom[1]]

@@ -149,7 +149,7 @@ nz_status nz_decompress(const void* d_stream, size_t stream_bytes, float* d_out,
     trace_reset(); trace_mark(st);
     if (launch_init(nullptr, 0, d_res, nfr, NZ_OK, st) != hipSuccess) return NZ_ERR_HIP;
     trace_mark(st);
-    if (launch_decode(A, false, st) != hipSuccess) return NZ_ERR_HIP;
+    if (launch_decode(A, 0, st) != hipSuccess) return NZ_ERR_HIP;
     trace_mark(st);
     return NZ_OK;
 }
@@ -187,7 +187,9 @@ nz_status nz_reduce_frames(const void* d_a, size_t a_bytes, const void* d_b, siz
     trace_reset(); trace_mark(st);
     if (launch_init(ws + L.ctrl, L.zero_end - L.ctrl, d_res, nfr, NZ_OK, st) != hipSuccess) return NZ_ERR_HIP;
     trace_mark(st);
-    if (launch_decode(D, true, st) != hipSuccess) return NZ_ERR_HIP;
+    if (launch_decode(D, 1, st) != hipSuccess) return NZ_ERR_HIP;
+    trace_mark(st);
+    if (launch_decode(D, 2, st) != hipSuccess) return NZ_ERR_HIP;
     trace_mark(st);
     if (launch_codebook(A, st) != hipSuccess) return NZ_ERR_HIP;
     trace_mark(st);

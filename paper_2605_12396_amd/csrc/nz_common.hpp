@@ -65,7 +65,7 @@ static_assert(sizeof(Ctrl) == 64, "Ctrl is 64 bytes");
 // Workspace carve-up; computed identically on host for sizing and launch.
 struct WsLayout {
     size_t ctrl, frame_desc, zero_end;      // [ctrl, zero_end) is cleared per call
-    size_t meta, book_code, book_len, phist, pmeta, grp_start, codes, total;
+    size_t meta, book_code, book_len, phist, pmeta, grp_start, codes, a16, a32, akind, awide, total;
 };
 
 __host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -84,7 +84,11 @@ __host__ inline WsLayout ws_layout(size_t n, uint32_t chunk, uint32_t stat_block
     L.phist = o;       o += align_up(4 * (size_t)kMaxK * n_frames * sbpf, 256);
     L.pmeta = o;       o += align_up(8 * n_frames * sbpf, 256);
     L.grp_start = o;   o += align_up(4 * n_frames * sbpf, 256);
-    L.codes = o;       if (with_codes) o += align_up(4 * n, 256);
+    L.codes = o;       if (with_codes) o += align_up(4 * n, 256);      // reduce: the 32-bit sums
+    L.a16 = o;         if (with_codes) o += align_up(2 * n, 256);      // reduce: operand A, 16-bit codes
+    L.a32 = o;         if (with_codes) o += align_up(4 * n, 256);      // reduce: operand A, wide codes and RAW words
+    L.akind = o;       if (with_codes) o += align_up(4 * n_frames, 256);
+    L.awide = o;       if (with_codes) o += align_up(4 * n_frames * sbpf, 256);
     L.total = o;
     return L;
 }
@@ -196,6 +200,6 @@ hipError_t launch_init(void* zero_base, size_t zero_bytes, void* res, uint32_t n
 hipError_t launch_stats(const CompressArgs& A, hipStream_t st);
 hipError_t launch_codebook(const CompressArgs& A, hipStream_t st);
 hipError_t launch_encode(const CompressArgs& A, bool from_codes, hipStream_t st);
-hipError_t launch_decode(const DecodeArgs& A, bool reduce, hipStream_t st);
+hipError_t launch_decode(const DecodeArgs& A, int pass, hipStream_t st);   // 0 decompress, 1 / 2 reduce passes
 
 }  // namespace nz

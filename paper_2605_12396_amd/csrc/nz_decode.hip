@@ -1,7 +1,9 @@
 // nz_decode.hip -- gfx950 kernels of the receiver side: validate stream and frame headers, rebuild the
 // canonical decode table from the code lengths carried in the frame, decode one 256-symbol segment per
-// thread from its recorded bit offset, then either dequantize (decompress) or add the codes of two
-// streams and gather the statistics of the sum (front end of the fused reduce).
+// thread from its recorded bit offset, then dequantize (decompress), or -- front end of the fused reduce --
+// stage the codes of operand A (first pass) and add operand B to them while gathering the statistics of the
+// sum (second pass).  One operand per pass keeps the per-workgroup shared memory small enough for four
+// waves per SIMD in every pass.
 //
 // Paper mapping: receiver side of Algorithm 2 (ParseHeader, ValidateHeader, DecodeOrMemcpy) and the
 // decode + reduce part of the fused receive-decode-reduce-encode-send step (Sec. IV-D).
@@ -66,12 +68,12 @@ struct BuildScratch {
     __align__(4) uint8_t len[kMaxK];
     uint16_t rank[kMaxK];
     uint32_t wcnt[16 * 32];
-    uint64_t red[2][kDecThreads / 64];
+    uint64_t red[2][8];
 };
 
 // Sums of two 64-bit values over the workgroup, one barrier pair for both.
 template <int NT>
-__device__ inline void block_sum64x2(uint64_t& a, uint64_t& b, uint64_t (*s_red)[kDecThreads / 64]) {
+__device__ inline void block_sum64x2(uint64_t& a, uint64_t& b, uint64_t (*s_red)[8]) {
     a = wave_sum64(a); b = wave_sum64(b);
     __syncthreads();
     if (lane_id() == 0) { s_red[0][threadIdx.x >> 6] = a; s_red[1][threadIdx.x >> 6] = b; }
@@ -246,10 +248,11 @@ constexpr uint32_t kWinRunLimit = kWinSlowLimit - 16;                // reload a
 static_assert(kWinRunLimit - 31 == kWinFreshBits, "cadence constant out of step with the window size");
 constexpr uint32_t kWinOverRows = 2;                                 // rows a prefetch may reach past the window
 
+template <int NT>
 struct HuffReader {
     uint64_t bits_addr;                  // byte address of bitstream word 0
     uint32_t nwords;                     // words in the bitstream (at least 1)
-    uint32_t* win;                       // this lane's window in LDS (word j at win[j * kDecThreads])
+    uint32_t* win;                       // this lane's window in LDS (word j at win[j * NT])
     int32_t win_bit0;                    // bit index (relative to bitstream bit 0) of window word 0
     uint32_t k, sh;                      // current position: bit sh (0..31) of window word k
     uint32_t lo, hi, n1, n2;             // window words k .. k+3
@@ -282,8 +285,8 @@ struct HuffReader {
             for (uint32_t c = 0; c < kWinWords / 4; c++) x[c] = p[c];
 #pragma unroll
             for (uint32_t c = 0; c < kWinWords / 4; c++) {
-                win[(4 * c + 0) * kDecThreads] = x[c].x; win[(4 * c + 1) * kDecThreads] = x[c].y;
-                win[(4 * c + 2) * kDecThreads] = x[c].z; win[(4 * c + 3) * kDecThreads] = x[c].w;
+                win[(4 * c + 0) * NT] = x[c].x; win[(4 * c + 1) * NT] = x[c].y;
+                win[(4 * c + 2) * NT] = x[c].z; win[(4 * c + 3) * NT] = x[c].w;
             }
             lo = x[0].x; hi = x[0].y; n1 = x[0].z; n2 = x[0].w;
         } else {
@@ -292,8 +295,8 @@ struct HuffReader {
             wptr w = reinterpret_cast<wptr>(bits_addr);
             const uint32_t last = nwords - 1u;
 #pragma unroll 1
-            for (uint32_t j = 0; j < kWinWords; j++) win[j * kDecThreads] = w[wi + j < last ? wi + j : last];
-            lo = win[0]; hi = win[kDecThreads]; n1 = win[2 * kDecThreads]; n2 = win[3 * kDecThreads];
+            for (uint32_t j = 0; j < kWinWords; j++) win[j * NT] = w[wi + j < last ? wi + j : last];
+            lo = win[0]; hi = win[NT]; n1 = win[2 * NT]; n2 = win[3 * NT];
         }
         win_bit0 = (int32_t)(cur & ~31u);
         k = 0; sh = cur & 31u;
@@ -314,8 +317,8 @@ struct HuffReader {
         else q = next_slow(e, w32, on_escape);
         const bool c = sh >= 32u;                                        // at most one word is used up per symbol here
         lo = c ? hi : lo; hi = c ? n1 : hi; k += c ? 1u : 0u; sh &= 31u;
-        const uint32_t* p = win + k * kDecThreads;
-        n1 = p[2 * kDecThreads]; n2 = p[3 * kDecThreads];
+        const uint32_t* p = win + k * NT;
+        n1 = p[2 * NT]; n2 = p[3 * NT];
         return q;
     }
     template <typename F>
@@ -383,23 +386,28 @@ struct DirectFetch {
     }
 };
 
-constexpr uint32_t kTileR = 16;                      // symbols per thread between two coalesced output phases
-constexpr uint32_t kTileStride = kTileR + 1;         // odd row stride: conflict-free column writes
+// The tile: 16-bit quantization codes, 32 per thread between two output phases, so that eight lanes write
+// one thread's run of 32 consecutive elements together (a full 128-byte line of fp32 or int32 output).
+constexpr uint32_t kTile16R = 32;
+constexpr uint32_t kTile16Stride = kTile16R + 2;     // halfwords per row: 17 words, an odd word stride
+constexpr int32_t kWideMarker = -32768;              // "this code does not fit 16 bits"
+constexpr uint32_t kHalf = 65536;                    // statistics granularity of the reduce (one encoder group)
 
-// Shared memory of one decode workgroup.  The windows come first and the tile follows them directly: a
-// reader's prefetch may touch up to kWinOverRows rows past its window, which then fall into the next window or
-// the tile (valid shared memory, values never used).
-template <int NOPS>
+enum : int { MODE_DECOMPRESS = 0, MODE_STAGE_A = 1, MODE_ADD_B = 2 };
+
+// Shared memory of one decode workgroup.  The window comes first and the tile follows it directly: a reader's
+// prefetch may touch up to kWinOverRows rows past its window, which then fall into the tile (valid shared
+// memory, values never used).
+template <int NT>
 struct __align__(16) DecShared {
-    uint32_t win[NOPS][kDecThreads * kWinWords];
-    union { uint32_t tile[kDecThreads * kTileStride]; BuildScratch build; } u;
-    uint64_t wsum[4];
-    uint32_t zmax, flags;
+    uint32_t win[NT * kWinWords];
+    union { uint16_t tile[NT * kTile16Stride]; BuildScratch build; } u;
+    uint64_t wsum[NT / 64];
+    uint32_t zmax[2], flags;
 };
-static_assert(kDecThreads * kTileStride >= kWinOverRows * kDecThreads, "prefetch rows must stay inside the tile");
 
 struct SegCtx {
-    uint32_t tid, lane, first_seg, nf, cntseg, e0;
+    uint32_t tid, lane, first_seg, nf, cntseg, e0, blk0;
     uint64_t f0;
     bool vec_ok;
 };
@@ -425,131 +433,51 @@ __device__ inline uint32_t combine(uint32_t ta, bool a_raw, uint32_t tb, bool b_
     return (uint32_t)qa + (uint32_t)qb;
 }
 
-// Coalesced consumer of 4 consecutive elements starting at frame element e (m of them valid).
-// MODE 0: dequantize (or pass RAW bits through) and store fp32.  MODE 1: histogram + zmax of the sums
-// (coded output) and stage the 32-bit values.
-template <int MODE>
-__device__ inline void emit4(const DecodeArgs& A, const SegCtx& C, uint32_t e, uint32_t m, const uint32_t t[4], bool raw_vals,
-                             uint32_t* s_h, uint32_t ncs, uint32_t copy, uint32_t& zmax) {
-    if (MODE == 0) {
-        float v[4];
-#pragma unroll
-        for (uint32_t j = 0; j < 4; j++) v[j] = raw_vals ? __uint_as_float(t[j]) : dequantize1(unzigzag(t[j]), A.step);
-        float* dst = A.out + C.f0 + e;
-        if (C.vec_ok && m == 4) *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-        else for (uint32_t j = 0; j < m; j++) dst[j] = v[j];
-    } else {
-        if (!raw_vals) {
-#pragma unroll
-            for (uint32_t j = 0; j < 4; j++) {
-                if (j < m) {
-                    const uint32_t z = zigzag((int32_t)t[j]);
-                    zmax = z > zmax ? z : zmax;
-                    atomicAdd(&s_h[(sym_of(z, A.K) << ncs) + copy], 1u);
-                }
-            }
-        }
-        uint32_t* dst = reinterpret_cast<uint32_t*>(A.ws + A.L.codes) + C.f0 + e;
-        if (C.vec_ok && m == 4) *reinterpret_cast<uint4*>(dst) = make_uint4(t[0], t[1], t[2], t[3]);
-        else for (uint32_t j = 0; j < m; j++) dst[j] = t[j];
+// Staging of operand A between the two reduce passes (workspace): a16 holds one 16-bit code per element,
+// kWideMarker where the code needs 32 bits, which then sits in a32; a RAW frame keeps its fp32 words in a32.
+struct StageA {
+    int16_t* a16; uint32_t* a32;      // both indexed by the element's position in the message
+    __device__ inline void put_code(uint64_t i, int32_t q, uint32_t& wide_seen) const {
+        if (q > 32767 || q <= kWideMarker) { a16[i] = (int16_t)kWideMarker; a32[i] = (uint32_t)q; wide_seen = 1; }
+        else a16[i] = (int16_t)q;
     }
-}
+    __device__ inline uint32_t get(uint64_t i, bool a_raw) const {   // fp32 bits (RAW) or the code
+        if (a_raw) return a32[i];
+        const int32_t q = a16[i];
+        return (q == kWideMarker) ? a32[i] : (uint32_t)q;
+    }
+};
 
-// One 256-symbol segment per thread, kTileR symbols at a time into an LDS tile, then the workgroup writes the
-// tile out with 16-byte stores (kTileR/4 lanes cover one thread's run, so every store instruction fills whole
-// 64-byte runs).  KA / KB say which operands are HUFFMAN (sequential reader) and which are addressed directly.
-template <int MODE, int KA, int KB, typename SH>
-__device__ inline void run_segments(const DecodeArgs& A, const SegCtx& C, HuffReader& ra, HuffReader& rb,
-                                    const DirectFetch& da, const DirectFetch& db, SH* S,
-                                    uint32_t* s_h, uint32_t ncs, uint32_t ca, uint32_t cb, uint32_t& overflow) {
+// Second reduce pass, one element the general way: fetch A, combine, stage the sum, count its symbol.
+struct AddCtx {
+    StageA sa; uint32_t* codes; uint32_t* s_h; uint32_t ncs, copy, K; float step; bool a_raw, b_raw;
+    __device__ inline void finish(const SegCtx& C, uint32_t i, uint32_t tb, uint32_t (&zmax)[2], uint32_t& overflow) const {
+        const uint64_t g = C.f0 + i;
+        const uint32_t ta = sa.get(g, a_raw);
+        if (a_raw || b_raw) { codes[g] = combine<true>(ta, a_raw, tb, b_raw, step, overflow); return; }
+        const uint32_t t = combine<false>(ta, false, tb, false, step, overflow);
+        codes[g] = t;
+        const uint32_t z = zigzag((int32_t)t), h = (i - C.blk0) >> 16;
+        zmax[h] = z > zmax[h] ? z : zmax[h];
+        atomicAdd(&s_h[h * 1024u + (sym_of(z, K) << ncs) + copy], 1u);
+    }
+};
+
+// HUFFMAN frame: every thread decodes its 256-symbol segment 32 symbols at a time into its tile row; after a
+// barrier the workgroup consumes the tile with coalesced accesses (eight lanes per row).
+//   MODE_DECOMPRESS  dequantize and store fp32
+//   MODE_STAGE_A     store the 16-bit codes
+//   MODE_ADD_B       add the staged codes of A (requested before the phase is decoded), store the 32-bit sums,
+//                    count their symbols per half of kHalf elements
+// A code that does not fit 16 bits (an escape with a large value) is finished by the decoding lane itself,
+// which leaves kWideMarker in the tile and raises a workgroup flag; only then does the consumer look for
+// markers.
+template <int MODE, int NT>
+__device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader<NT>& ra, DecShared<NT>* S, uint32_t ca,
+                                const AddCtx& X, bool a_wide, uint32_t (&zmax)[2], uint32_t& overflow) {
     const uint32_t tid = C.tid;
-    const uint32_t copy = C.lane & ((1u << ncs) - 1u);
-    uint32_t* tile = S->u.tile;
-    uint32_t zmax = 0;
-    constexpr uint32_t LPR = kTileR / 4;             // lanes per row in the output phase
-    constexpr bool ANY_RAW = (MODE == 1) && (KA == KIND_RAW || KB == KIND_RAW);
-    uint32_t e = C.e0;                               // next element of my segment (frame index)
-    auto produce = [&]() -> uint32_t {
-        auto code_of = [](uint32_t z) -> int32_t { return unzigzag(z); };
-        // both table lookups are issued before either symbol is finished (two independent dependency chains)
-        uint32_t wa = 0, wb = 0, ea = 0, eb = 0;
-        if (KA == KIND_HUFF) ea = ra.lookup(wa);
-        if (KB == KIND_HUFF) eb = rb.lookup(wb);
-        uint32_t ta, tb;
-        if (KA == KIND_HUFF) ta = (uint32_t)ra.finish(ea, wa, code_of);
-        else { ta = da.get(e); if (KA == KIND_FIXED) ta = (uint32_t)unzigzag(ta); }
-        if (KB == KIND_HUFF) tb = (uint32_t)rb.finish(eb, wb, code_of);
-        else { tb = db.get(e); if (KB == KIND_FIXED) tb = (uint32_t)unzigzag(tb); }
-        e++;
-        return combine<ANY_RAW>(ta, KA == KIND_RAW, tb, KB == KIND_RAW, A.step, overflow);
-    };
-    uint32_t due_a = 1, due_b = 1;                                       // runs left until the next scheduled reload
-    auto start_run = [&]() {
-        if (KA == KIND_HUFF) {
-            const bool sched = (--due_a == 0);                           // uniform over the workgroup
-            if (sched) due_a = ca;
-            if (sched || ra.pos() >= kWinRunLimit) ra.reload();
-        }
-        if (MODE == 1 && KB == KIND_HUFF) {
-            const bool sched = (--due_b == 0);
-            if (sched) due_b = cb;
-            if (sched || rb.pos() >= kWinRunLimit) rb.reload();
-        }
-    };
-    for (uint32_t r0 = 0; r0 < kSeg; r0 += kTileR) {
-        uint32_t* row = tile + tid * kTileStride;
-        if (r0 + kTileR <= C.cntseg) {                                   // full run: static tile offsets
-#pragma unroll
-            for (uint32_t h = 0; h < kTileR; h += kRun) {
-                start_run();
-#pragma unroll
-                for (uint32_t r = 0; r < kRun; r++) row[h + r] = produce();
-            }
-        } else if (r0 < C.cntseg) {
-            const uint32_t nr = C.cntseg - r0;
-            for (uint32_t r = 0; r < nr; r++) {
-                if ((r % kRun) == 0) start_run();
-                row[r] = produce();
-            }
-        }
-        __syncthreads();
-#pragma unroll
-        for (uint32_t k = 0; k < LPR; k++) {
-            const uint32_t g = tid + kDecThreads * k;
-            const uint32_t rw = g / LPR, c = (g % LPR) * 4;
-            const uint32_t eo = (C.first_seg + rw) * kSeg + r0 + c;             // element index in the frame
-            if (eo < C.nf) {
-                const uint32_t m = (C.nf - eo < 4) ? (C.nf - eo) : 4u;
-                uint32_t t[4];
-#pragma unroll
-                for (uint32_t j = 0; j < 4; j++) t[j] = tile[rw * kTileStride + c + j];
-                emit4<MODE>(A, C, eo, m, t, MODE == 0 ? false : ANY_RAW, s_h, ncs, copy, zmax);
-            }
-        }
-        __syncthreads();
-    }
-    if (MODE == 1) {
-        zmax = wave_max(zmax);
-        if (C.lane == 0) atomicMax(&S->zmax, zmax);
-    }
-}
-
-// Decompress of a HUFFMAN frame.  Same scheme as run_segments, but the tile holds 16-bit quantization codes,
-// 32 per thread between two output phases, so that eight lanes write one thread's run as a full 128-byte line.
-// A code that does not fit 16 bits (an escape with a large value) is stored straight to global memory by the
-// decoding lane, which leaves the marker -32768 in the tile and raises a workgroup flag; only then does the
-// output phase look for markers and write around them.
-constexpr uint32_t kTile16R = 32;
-constexpr uint32_t kTile16Stride = kTile16R + 2;     // halfwords per row: 17 words, an odd word stride
-constexpr int32_t kWideMarker = -32768;
-
-template <typename SH>
-__device__ inline void run_decompress_huff(const DecodeArgs& A, const SegCtx& C, HuffReader& ra, SH* S, uint32_t ca) {
-    static_assert(kDecThreads * kTile16Stride * 2 <= sizeof(S->u.tile), "16-bit tile must fit the tile storage");
-    const uint32_t tid = C.tid;
-    uint16_t* tile = reinterpret_cast<uint16_t*>(S->u.tile);
+    uint16_t* tile = S->u.tile;
     uint32_t* row32 = reinterpret_cast<uint32_t*>(tile + tid * kTile16Stride);
-    float* seg_out = A.out + C.f0 + C.e0;
     uint32_t e = 0;                                   // symbols of my segment decoded so far
     uint32_t due = 1;
     auto start_run = [&]() {
@@ -559,17 +487,30 @@ __device__ inline void run_decompress_huff(const DecodeArgs& A, const SegCtx& C,
     };
     auto wide = [&](uint32_t z) -> int32_t {          // only an escape can carry a code of 16 bits or more
         int32_t q = unzigzag(z);
-        if (z >= 0xFFFFu) { seg_out[e] = dequantize1(q, A.step); q = kWideMarker; S->flags = 1u; }
+        if (z >= 0xFFFFu) {
+            if (MODE == MODE_DECOMPRESS) A.out[C.f0 + C.e0 + e] = dequantize1(q, A.step);
+            else if (MODE == MODE_STAGE_A) X.sa.a32[C.f0 + C.e0 + e] = (uint32_t)q;
+            else X.finish(C, C.e0 + e, (uint32_t)q, zmax, overflow);
+            q = kWideMarker; S->flags = 1u;
+        }
         return q;
     };
     auto next16 = [&]() -> uint32_t { const int32_t q = ra.next(wide); e++; return (uint32_t)q; };
-    constexpr uint32_t LPR = kTile16R / 4;            // 8 lanes write one row
-    // output phase: thread (row rw0 + 32 k, columns c .. c+3) for k = 0..7
+    constexpr uint32_t LPR = kTile16R / 4;            // 8 lanes consume one row
+    constexpr uint32_t RPK = NT / LPR;                // rows covered by one step k of the consumer
+    // consumer: thread (row rw0 + RPK k, columns c .. c+3) for k = 0..7
     const uint32_t rw0 = tid / LPR, c = (tid % LPR) * 4;
     const uint32_t* src0 = reinterpret_cast<const uint32_t*>(tile + rw0 * kTile16Stride + c);
     const uint32_t eo0 = (C.first_seg + rw0) * kSeg + c;
-    const bool whole = C.vec_ok && (C.first_seg + kDecThreads) * kSeg <= C.nf;   // every store is a full, aligned float4
+    const bool whole = C.vec_ok && (C.first_seg + NT) * kSeg <= C.nf;   // every access is a full, aligned group of 4
+    const bool fast_add = (MODE == MODE_ADD_B) && whole && !a_wide && !X.a_raw;
     for (uint32_t r0 = 0; r0 < kSeg; r0 += kTile16R) {
+        uint2 pa[LPR];                                // MODE_ADD_B: the staged codes of A this thread will add
+        if (MODE == MODE_ADD_B && fast_add) {
+            const int16_t* ap = X.sa.a16 + C.f0 + eo0 + r0;
+#pragma unroll
+            for (uint32_t k = 0; k < LPR; k++) pa[k] = *reinterpret_cast<const uint2*>(ap + (size_t)k * RPK * kSeg);
+        }
         if (r0 + kTile16R <= C.cntseg) {
 #pragma unroll
             for (uint32_t h = 0; h < kTile16R; h += kRun) {
@@ -589,32 +530,61 @@ __device__ inline void run_decompress_huff(const DecodeArgs& A, const SegCtx& C,
             }
         }
         __syncthreads();
-        if (__builtin_expect(whole && S->flags == 0, 1)) {
+        const bool plain = whole && S->flags == 0;    // no markers in the tile, no bounds to watch
+        if (MODE == MODE_DECOMPRESS && __builtin_expect(plain, 1)) {
             float* dst = A.out + C.f0 + eo0 + r0;
 #pragma unroll
             for (uint32_t k = 0; k < LPR; k++) {
-                const uint32_t* src = src0 + k * (kDecThreads / LPR) * (kTile16Stride / 2);
+                const uint32_t* src = src0 + k * RPK * (kTile16Stride / 2);
                 const uint32_t p0 = src[0], p1 = src[1];
-                float4 v;
-                v.x = dequantize1((int32_t)(int16_t)(p0 & 0xFFFFu), A.step); v.y = dequantize1((int32_t)p0 >> 16, A.step);
-                v.z = dequantize1((int32_t)(int16_t)(p1 & 0xFFFFu), A.step); v.w = dequantize1((int32_t)p1 >> 16, A.step);
                 // streaming store: the output is not read again here and should not displace the bitstream in L2
                 typedef float f32x4 __attribute__((ext_vector_type(4)));
-                f32x4 vv; vv.x = v.x; vv.y = v.y; vv.z = v.z; vv.w = v.w;
-                __builtin_nontemporal_store(vv, reinterpret_cast<f32x4*>(dst + (size_t)k * (kDecThreads / LPR) * kSeg));
+                f32x4 v;
+                v.x = dequantize1((int32_t)(int16_t)(p0 & 0xFFFFu), A.step); v.y = dequantize1((int32_t)p0 >> 16, A.step);
+                v.z = dequantize1((int32_t)(int16_t)(p1 & 0xFFFFu), A.step); v.w = dequantize1((int32_t)p1 >> 16, A.step);
+                __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst + (size_t)k * RPK * kSeg));
+            }
+        } else if (MODE == MODE_STAGE_A && __builtin_expect(whole, 1)) {
+            int16_t* dst = X.sa.a16 + C.f0 + eo0 + r0;      // markers are staged as they are
+#pragma unroll
+            for (uint32_t k = 0; k < LPR; k++) {
+                const uint32_t* src = src0 + k * RPK * (kTile16Stride / 2);
+                *reinterpret_cast<uint2*>(dst + (size_t)k * RPK * kSeg) = make_uint2(src[0], src[1]);
+            }
+        } else if (MODE == MODE_ADD_B && __builtin_expect(fast_add && plain, 1)) {
+            uint32_t* dst = X.codes + C.f0 + eo0 + r0;
+#pragma unroll
+            for (uint32_t k = 0; k < LPR; k++) {
+                const uint32_t* src = src0 + k * RPK * (kTile16Stride / 2);
+                const uint32_t p0 = src[0], p1 = src[1];
+                const uint32_t h = (k * RPK >= kHalf / kSeg) ? 1u : 0u;       // which half of the block this row is in
+                int32_t Q[4];
+                Q[0] = (int32_t)(int16_t)(p0 & 0xFFFFu) + (int32_t)(int16_t)(pa[k].x & 0xFFFFu);
+                Q[1] = ((int32_t)p0 >> 16) + ((int32_t)pa[k].x >> 16);
+                Q[2] = (int32_t)(int16_t)(p1 & 0xFFFFu) + (int32_t)(int16_t)(pa[k].y & 0xFFFFu);
+                Q[3] = ((int32_t)p1 >> 16) + ((int32_t)pa[k].y >> 16);
+#pragma unroll
+                for (uint32_t j = 0; j < 4; j++) {
+                    const uint32_t z = zigzag(Q[j]);
+                    zmax[h] = z > zmax[h] ? z : zmax[h];
+                    atomicAdd(&X.s_h[h * 1024u + (sym_of(z, X.K) << X.ncs) + X.copy], 1u);
+                }
+                *reinterpret_cast<uint4*>(dst + (size_t)k * RPK * kSeg) = make_uint4((uint32_t)Q[0], (uint32_t)Q[1], (uint32_t)Q[2], (uint32_t)Q[3]);
             }
         } else {
+            // ragged block, markers in the tile, wide or raw codes of A: element by element
 #pragma unroll 1
             for (uint32_t k = 0; k < LPR; k++) {
-                const uint32_t eo = eo0 + k * (kDecThreads / LPR) * kSeg + r0;      // element index in the frame
-                if (eo < C.nf) {
-                    const uint32_t m = (C.nf - eo < 4) ? (C.nf - eo) : 4u;
-                    const uint32_t* src = src0 + k * (kDecThreads / LPR) * (kTile16Stride / 2);
-                    const uint32_t p0 = src[0], p1 = src[1];
-                    const int32_t q[4] = { (int32_t)(int16_t)(p0 & 0xFFFFu), (int32_t)p0 >> 16,
-                                           (int32_t)(int16_t)(p1 & 0xFFFFu), (int32_t)p1 >> 16 };
-                    float* dst = A.out + C.f0 + eo;
-                    for (uint32_t j = 0; j < m; j++) if (q[j] != kWideMarker) dst[j] = dequantize1(q[j], A.step);
+                const uint32_t eo = eo0 + k * RPK * kSeg + r0;                    // element index in the frame
+                const uint16_t* src = tile + (rw0 + k * RPK) * kTile16Stride + c;
+                for (uint32_t j = 0; j < 4; j++) {
+                    if (eo + j >= C.nf) break;
+                    const int32_t q = (int16_t)src[j];
+                    if (MODE == MODE_STAGE_A) X.sa.a16[C.f0 + eo + j] = (int16_t)q;
+                    else if (q != kWideMarker) {
+                        if (MODE == MODE_DECOMPRESS) A.out[C.f0 + eo + j] = dequantize1(q, A.step);
+                        else X.finish(C, eo + j, (uint32_t)q, zmax, overflow);
+                    }
                 }
             }
         }
@@ -622,159 +592,170 @@ __device__ inline void run_decompress_huff(const DecodeArgs& A, const SegCtx& C,
     }
 }
 
-// Frames without a HUFFMAN operand: element-parallel and coalesced on both sides.
-template <int MODE, typename SH>
-__device__ inline void run_elementwise(const DecodeArgs& A, const SegCtx& C, uint32_t blk0, const DirectFetch& da,
-                                       const DirectFetch& db, SH* S, uint32_t* s_h, uint32_t ncs, uint32_t& overflow) {
-    const uint32_t cnt = (C.nf - blk0 < kDecBlock) ? (C.nf - blk0) : kDecBlock;
-    const uint32_t copy = C.lane & ((1u << ncs) - 1u);
-    const bool a_raw = da.kind == KIND_RAW, b_raw = (MODE == 1) && db.kind == KIND_RAW;
-    uint32_t zmax = 0;
-    for (uint32_t i = C.tid * 4; i < cnt; i += kDecThreads * 4) {
-        const uint32_t e = blk0 + i;
+// Frames without a HUFFMAN bitstream (RAW, FIXEDLEN, or rejected = all zero): element-parallel.
+template <int MODE, int NT>
+__device__ inline void run_elementwise(const DecodeArgs& A, const SegCtx& C, const DirectFetch& da, DecShared<NT>* S,
+                                       const AddCtx& X, uint32_t (&zmax)[2], uint32_t& overflow) {
+    const uint32_t cnt = (C.nf - C.blk0 < NT * kSeg) ? (C.nf - C.blk0) : NT * kSeg;
+    const bool raw = da.kind == KIND_RAW;
+    uint32_t wide_seen = 0;
+    for (uint32_t i = C.tid * 4; i < cnt; i += NT * 4) {
         const uint32_t m = (cnt - i < 4) ? (cnt - i) : 4u;
-        uint32_t t[4] = { 0, 0, 0, 0 };
         for (uint32_t j = 0; j < m; j++) {
-            uint32_t ta = da.get(e + j);
-            if (MODE == 0) t[j] = ta;
-            else {
-                uint32_t tb = db.get(e + j);
-                if (!a_raw) ta = (uint32_t)unzigzag(ta);
-                if (!b_raw) tb = (uint32_t)unzigzag(tb);
-                t[j] = (a_raw || b_raw) ? combine<true>(ta, a_raw, tb, b_raw, A.step, overflow)
-                                        : combine<false>(ta, false, tb, false, A.step, overflow);
-            }
+            const uint32_t e = C.blk0 + i + j;
+            uint32_t t = da.get(e);                                               // fp32 bits (RAW) or zigzag code
+            if (!raw) t = (uint32_t)unzigzag(t);
+            if (MODE == MODE_DECOMPRESS) A.out[C.f0 + e] = raw ? __uint_as_float(t) : dequantize1((int32_t)t, A.step);
+            else if (MODE == MODE_STAGE_A) { if (raw) X.sa.a32[C.f0 + e] = t; else X.sa.put_code(C.f0 + e, (int32_t)t, wide_seen); }
+            else X.finish(C, e, t, zmax, overflow);
         }
-        emit4<MODE>(A, C, e, m, t, MODE == 0 ? a_raw : (a_raw || b_raw), s_h, ncs, copy, zmax);
     }
-    if (MODE == 1) {
-        zmax = wave_max(zmax);
-        if (C.lane == 0) atomicMax(&S->zmax, zmax);
-    }
+    if (MODE == MODE_STAGE_A && wide_seen) S->flags = 1u;
 }
 
-// MODE 0: decompress A into fp32.  MODE 1: reduce front end, Q = qa + qb into the workspace + statistics.
-template <int MODE>
-__global__ __launch_bounds__(kDecThreads) void k_decode(DecodeArgs A) {
-    __shared__ DecTables s_t[MODE == 1 ? 2 : 1];
-    __shared__ DecShared<(MODE == 1 ? 2 : 1)> S;
-    __shared__ uint32_t s_h[MODE == 1 ? 2048 : 1];
+// One workgroup per NT segments of one frame.
+template <int MODE, int NT>
+__global__ __launch_bounds__(NT) void k_decode(DecodeArgs A) {
+    __shared__ DecTables s_t;
+    __shared__ DecShared<NT> S;
+    __shared__ uint32_t s_h[MODE == MODE_ADD_B ? 2048 : 1];
 
     const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const uint32_t frame = blockIdx.x / A.dbpf, db = blockIdx.x % A.dbpf;
     const uint64_t f0 = (uint64_t)frame * A.chunk;
     const uint32_t nf = (uint32_t)((A.n - f0 < A.chunk) ? (A.n - f0) : A.chunk);
-    const uint32_t blk0 = db * kDecBlock;
+    const uint32_t blk0 = db * NT * kSeg;
     if (blk0 >= nf) return;
     ResultRec* res = reinterpret_cast<ResultRec*>(A.res);
-    const uint32_t first_seg = db * kDecThreads;
+    const uint32_t first_seg = db * NT;
     const uint32_t nseg = (nf + kSeg - 1) / kSeg;
     const uint32_t gseg = first_seg + tid;
     const bool seg_valid = gseg < nseg;
     const uint32_t e0 = gseg * kSeg;                                    // first element of my segment in the frame
     const uint32_t cntseg = seg_valid ? ((nf - e0 < kSeg) ? (nf - e0) : kSeg) : 0u;
+    const uint32_t hpf = (A.chunk + kHalf - 1) / kHalf;                 // halves (statistics blocks) per frame
 
+    // stream headers: the reduce passes look at both operands, so that neither goes on after a stream-level error
     uint64_t total_a = 0, total_b = 0;
     const uint32_t st_a = check_stream(A.a, A.a_bytes, A, total_a);
     uint32_t st_b = ST_OK;
-    if (MODE == 1) st_b = check_stream(A.b, A.b_bytes, A, total_b);
+    if (MODE != MODE_DECOMPRESS) st_b = check_stream(A.b, A.b_bytes, A, total_b);
     if (blockIdx.x == 0 && tid == 0) {
         if (st_a) atomicMax(&res->status, st_a);
         if (st_b) atomicMax(&res->status, st_b);
-        if (MODE == 0 && st_a == ST_OK) res->bytes = total_a;
+        if (MODE == MODE_DECOMPRESS && st_a == ST_OK) res->bytes = total_a;
     }
-    if (MODE == 0 && st_a) return;                                      // nothing is written on a stream-level error
+    if (MODE == MODE_DECOMPRESS && st_a) return;                        // nothing is written on a stream-level error
 
-    FrameView va, vb;
-    va.status = ST_OK; va.kind = KIND_ZERO; va.w = 0; va.words = nullptr; va.nwords = 0; va.segt = nullptr; va.seg_prefix = 0;
-    va.cadence = 1;
-    vb = va;
-    if (st_a == ST_OK && (MODE == 0 || st_b == ST_OK)) {
-        open_frame<kDecThreads>(A.a, total_a, frame, nf, first_seg, A, &s_t[0], &S.u.build, va);
-        if (MODE == 1) open_frame<kDecThreads>(A.b, total_b, frame, nf, first_seg, A, &s_t[MODE == 1 ? 1 : 0], &S.u.build, vb);
+    FrameView V;
+    V.status = ST_OK; V.kind = KIND_ZERO; V.w = 0; V.words = nullptr; V.nwords = 0; V.segt = nullptr; V.seg_prefix = 0;
+    V.cadence = 1;
+    if (st_a == ST_OK && st_b == ST_OK) {
+        open_frame<NT>(MODE == MODE_ADD_B ? A.b : A.a, MODE == MODE_ADD_B ? total_b : total_a, frame, nf, first_seg, A,
+                       &s_t, &S.u.build, V);
         if (tid == 0) {
-            if (va.status) atomicMax(&res->status, va.status);
-            if (MODE == 1 && vb.status) atomicMax(&res->status, vb.status);
-            if (MODE == 0 && db == 0 && va.status == ST_OK)
-                atomicAdd(va.kind == KIND_RAW ? &res->n_raw : (va.kind == KIND_FIXED ? &res->n_fixed : &res->n_huff), 1u);
+            if (V.status) atomicMax(&res->status, V.status);
+            if (MODE == MODE_DECOMPRESS && db == 0 && V.status == ST_OK)
+                atomicAdd(V.kind == KIND_RAW ? &res->n_raw : (V.kind == KIND_FIXED ? &res->n_fixed : &res->n_huff), 1u);
         }
-        if (MODE == 1 && (va.status || vb.status)) { va.kind = KIND_ZERO; vb.kind = KIND_ZERO; }
+        if (V.status) V.kind = KIND_ZERO;                               // reduce: a rejected frame counts as zeros
     }
-    if (MODE == 0 && va.status) return;                                 // rejected frame: its output range is left alone
+    if (MODE == MODE_DECOMPRESS && V.status) return;                    // rejected frame: its output range is left alone
 
     // bit offset of my segment inside a HUFFMAN bitstream: prefix of the segment table
-    uint32_t bit_a = 0, bit_b = 0, seglen_a = 0, seglen_b = 0;
+    uint32_t bit0 = 0, seglen = 0;
     {
-        const uint32_t la = (va.kind == KIND_HUFF && seg_valid) ? va.segt[gseg] : 0u;
-        const uint32_t lb = (MODE == 1 && vb.kind == KIND_HUFF && seg_valid) ? vb.segt[gseg] : 0u;
-        seglen_a = la; seglen_b = lb;
-        // both lengths are < 2^16: scan them packed in one 64-bit lane value (sums stay below 2^32 each)
-        const uint64_t v = (uint64_t)la | ((uint64_t)lb << 32);
-        uint64_t incl = v;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) { uint64_t t = __shfl_up(incl, d, 64); if ((int)lane >= d) incl += t; }
+        seglen = (V.kind == KIND_HUFF && seg_valid) ? V.segt[gseg] : 0u;
+        const uint32_t incl = wave_incl_scan_dpp(seglen);
         if (lane == 63) S.wsum[wave] = incl;
-        if (tid == 0) { S.zmax = 0; S.flags = 0; }
+        if (tid == 0) { S.zmax[0] = 0; S.zmax[1] = 0; S.flags = 0; }
         __syncthreads();
-        uint64_t excl = incl - v;
-        for (uint32_t w = 0; w < wave; w++) excl += S.wsum[w];
-        bit_a = (uint32_t)va.seg_prefix + (uint32_t)(excl & 0xFFFFFFFFull);
-        bit_b = (uint32_t)vb.seg_prefix + (uint32_t)(excl >> 32);
+        uint32_t excl = incl - seglen;
+        for (uint32_t w = 0; w < wave; w++) excl += (uint32_t)S.wsum[w];
+        bit0 = (uint32_t)V.seg_prefix + excl;
     }
     const uint32_t* safe = reinterpret_cast<const uint32_t*>(A.res);
-    HuffReader ra, rb;
-    DirectFetch da, dbf;
-    ra.init(va, &s_t[0], bit_a, safe, &S.win[0][tid]);
-    rb.init(vb, &s_t[MODE == 1 ? 1 : 0], bit_b, safe, &S.win[MODE == 1 ? 1 : 0][tid]);
-    da.init(va, safe);
-    dbf.init(vb, safe);
+    HuffReader<NT> ra;
+    DirectFetch da;
+    ra.init(V, &s_t, bit0, safe, &S.win[tid]);
+    da.init(V, safe);
     SegCtx C;
-    C.tid = tid; C.lane = lane; C.first_seg = first_seg; C.nf = nf; C.cntseg = cntseg; C.e0 = e0; C.f0 = f0;
+    C.tid = tid; C.lane = lane; C.first_seg = first_seg; C.nf = nf; C.cntseg = cntseg; C.e0 = e0; C.f0 = f0; C.blk0 = blk0;
     C.vec_ok = ((f0 & 3u) == 0);
     uint32_t overflow = 0;
+    uint32_t zmax[2] = { 0, 0 };
 
-    if (MODE == 0) {
-        if (va.kind == KIND_HUFF) {
-            run_decompress_huff(A, C, ra, &S, va.cadence);
-            if (seg_valid && (ra.bad || ra.consumed() != seglen_a)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
-        } else {
-            run_elementwise<0>(A, C, blk0, da, dbf, &S, s_h, 0, overflow);
+    AddCtx X;
+    X.sa.a16 = reinterpret_cast<int16_t*>(A.ws + A.L.a16); X.sa.a32 = reinterpret_cast<uint32_t*>(A.ws + A.L.a32);
+    X.codes = reinterpret_cast<uint32_t*>(A.ws + A.L.codes);
+    X.s_h = s_h; X.K = A.K; X.step = A.step; X.ncs = 0; X.copy = 0; X.a_raw = false; X.b_raw = false;
+    uint32_t* akind = reinterpret_cast<uint32_t*>(A.ws + A.L.akind);   // per frame: operand A is RAW
+    uint32_t* awide = reinterpret_cast<uint32_t*>(A.ws + A.L.awide);   // per half: some code of A needs 32 bits
+    bool a_wide = false;
+    if (MODE == MODE_ADD_B) {
+        while ((A.K << (X.ncs + 1)) <= 1024u && X.ncs < 5) X.ncs++;
+        X.copy = lane & ((1u << X.ncs) - 1u);
+        for (uint32_t i = tid; i < 2048u; i += NT) s_h[i] = 0;
+        X.a_raw = akind[frame] != 0;
+        X.b_raw = V.kind == KIND_RAW;
+        for (uint32_t h = 0; h < NT * kSeg / kHalf; h++)
+            if (blk0 + h * kHalf < nf) a_wide = a_wide || (awide[(size_t)frame * hpf + blk0 / kHalf + h] != 0);
+        __syncthreads();
+    }
+
+    if (V.kind == KIND_HUFF) {
+        run_huff<MODE, NT>(A, C, ra, &S, V.cadence, X, a_wide, zmax, overflow);
+        if (seg_valid && (ra.bad || ra.consumed() != seglen)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
+    } else {
+        run_elementwise<MODE, NT>(A, C, da, &S, X, zmax, overflow);
+    }
+    if (MODE == MODE_DECOMPRESS) return;
+
+    if (MODE == MODE_STAGE_A) {
+        static_assert(MODE != MODE_STAGE_A || NT * kSeg == kHalf, "the first reduce pass works in halves");
+        __syncthreads();
+        if (tid == 0) {
+            awide[(size_t)frame * hpf + db] = S.flags;
+            if (db == 0) akind[frame] = (V.kind == KIND_RAW) ? 1u : 0u;
         }
         return;
     }
-
-    // ---- MODE 1: sum of codes, statistics of the sum ----
-    const uint32_t K = A.K;
-    uint32_t ncs = 0;
-    while ((K << (ncs + 1)) <= 2048u && ncs < 5) ncs++;
-    for (uint32_t i = tid; i < (K << ncs); i += kDecThreads) s_h[i] = 0;
-    __syncthreads();
-    const bool out_raw = (va.kind == KIND_RAW) || (vb.kind == KIND_RAW);      // uniform over the frame
-    const bool ha = va.kind == KIND_HUFF, hb = vb.kind == KIND_HUFF;
-    if (!ha && !hb) run_elementwise<1>(A, C, blk0, da, dbf, &S, s_h, ncs, overflow);
-    else if (ha && hb) run_segments<1, KIND_HUFF, KIND_HUFF>(A, C, ra, rb, da, dbf, &S, s_h, ncs, va.cadence, vb.cadence, overflow);
-    else if (ha && vb.kind == KIND_RAW) run_segments<1, KIND_HUFF, KIND_RAW>(A, C, ra, rb, da, dbf, &S, s_h, ncs, va.cadence, vb.cadence, overflow);
-    else if (ha) run_segments<1, KIND_HUFF, KIND_FIXED>(A, C, ra, rb, da, dbf, &S, s_h, ncs, va.cadence, vb.cadence, overflow);
-    else if (va.kind == KIND_RAW) run_segments<1, KIND_RAW, KIND_HUFF>(A, C, ra, rb, da, dbf, &S, s_h, ncs, va.cadence, vb.cadence, overflow);
-    else run_segments<1, KIND_FIXED, KIND_HUFF>(A, C, ra, rb, da, dbf, &S, s_h, ncs, va.cadence, vb.cadence, overflow);
-    if (seg_valid) {
-        if (ha && (ra.bad || ra.consumed() != seglen_a)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
-        if (hb && (rb.bad || rb.consumed() != seglen_b)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
-    }
+    // ---- MODE_ADD_B: statistics of the sum, per half ----
     if (overflow) atomicMax(&res->status, (uint32_t)ST_RANGE);
-    __syncthreads();
-    uint32_t* ph = reinterpret_cast<uint32_t*>(A.ws + A.L.phist) + (size_t)blockIdx.x * kMaxK;
-    for (uint32_t sy = tid; sy < K; sy += kDecThreads) {
-        uint32_t t = 0;
-        for (uint32_t c = 0; c < (1u << ncs); c++) t += s_h[(sy << ncs) + c];
-        ph[sy] = t;
+#pragma unroll
+    for (uint32_t h = 0; h < 2; h++) {
+        const uint32_t zm = wave_max(zmax[h]);
+        if (lane == 0 && zm) atomicMax(&S.zmax[h], zm);
     }
-    if (tid == 0) reinterpret_cast<uint2*>(A.ws + A.L.pmeta)[blockIdx.x] = make_uint2(S.zmax, out_raw ? 1u : 0u);
+    __syncthreads();
+    const bool out_raw = X.a_raw || X.b_raw;                            // uniform over the frame
+    for (uint32_t h = 0; h < NT * kSeg / kHalf; h++) {
+        if (blk0 + h * kHalf >= nf) break;
+        const size_t hb = (size_t)frame * hpf + blk0 / kHalf + h;
+        uint32_t* ph = reinterpret_cast<uint32_t*>(A.ws + A.L.phist) + hb * kMaxK;
+        for (uint32_t sy = tid; sy < A.K; sy += NT) {
+            uint32_t t = 0;
+            for (uint32_t cc = 0; cc < (1u << X.ncs); cc++) t += s_h[h * 1024u + (sy << X.ncs) + cc];
+            ph[sy] = t;
+        }
+        if (tid == 0) reinterpret_cast<uint2*>(A.ws + A.L.pmeta)[hb] = make_uint2(S.zmax[h], out_raw ? 1u : 0u);
+    }
 }
 
-hipError_t launch_decode(const DecodeArgs& A, bool reduce, hipStream_t st) {
-    if (reduce) hipLaunchKernelGGL(k_decode<1>, dim3(A.n_frames * A.dbpf), dim3(kDecThreads), 0, st, A);
-    else hipLaunchKernelGGL(k_decode<0>, dim3(A.n_frames * A.dbpf), dim3(kDecThreads), 0, st, A);
+constexpr int kAddThreads = 512;        // second reduce pass: two halves per workgroup, four waves per SIMD at 2 workgroups per CU
+
+hipError_t launch_decode(const DecodeArgs& A, int pass, hipStream_t st) {
+    DecodeArgs D = A;
+    if (pass == 0) {
+        D.dbpf = (A.chunk + kDecBlock - 1) / kDecBlock;
+        hipLaunchKernelGGL((k_decode<MODE_DECOMPRESS, kDecThreads>), dim3(D.n_frames * D.dbpf), dim3(kDecThreads), 0, st, D);
+    } else if (pass == 1) {
+        D.dbpf = (A.chunk + kDecBlock - 1) / kDecBlock;
+        hipLaunchKernelGGL((k_decode<MODE_STAGE_A, kDecThreads>), dim3(D.n_frames * D.dbpf), dim3(kDecThreads), 0, st, D);
+    } else {
+        D.dbpf = (A.chunk + kAddThreads * kSeg - 1) / (kAddThreads * kSeg);
+        hipLaunchKernelGGL((k_decode<MODE_ADD_B, kAddThreads>), dim3(D.n_frames * D.dbpf), dim3(kAddThreads), 0, st, D);
+    }
     return hipGetLastError();
 }
 

@@ -18,7 +18,8 @@ import os
 import sys
 
 KERNELS = [("k_stats", "compress/stats"), ("k_codebook", "*/codebook"), ("k_encode<0>", "compress/encode"),
-           ("k_encode<1>", "reduce/encode"), ("k_decode<0>", "decompress/decode"), ("k_decode<1>", "reduce/decode_add")]
+           ("k_encode<1>", "reduce/encode"), ("k_decode<0, 256>", "decompress/decode"),
+           ("k_decode<1, 256>", "reduce/stage_a"), ("k_decode<2, 512>", "reduce/add_b")]
 
 
 def per_kernel(d, counter):
