@@ -301,6 +301,35 @@ struct HuffReader {
         win_bit0 = (int32_t)(cur & ~31u);
         k = 0; sh = cur & 31u;
     }
+    // Scheduled refill in two halves, so that the global-load latency passes while the workgroup does something
+    // else (its output phase): request() issues the loads for the window at the current position, install()
+    // makes it the lane's window.  A lane too close to the end of the bitstream for 16-byte loads reads a
+    // harmless 48 bytes in front of the bitstream instead (always inside the stream: header and tables precede
+    // it) and refills the slow way at install time.
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    struct Pending { u32x4 x[kWinWords / 4]; uint32_t cur; bool ok; };
+    __device__ inline void request(Pending& P) const {
+        typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
+        typedef const u32x4_a4 __attribute__((address_space(1))) * gptr;
+        P.cur = (uint32_t)(win_bit0 + (int32_t)pos());
+        const uint32_t wi = P.cur >> 5;
+        P.ok = wi + kWinWords <= nwords;
+        gptr p = reinterpret_cast<gptr>(P.ok ? bits_addr + 4ull * wi : bits_addr - 4ull * kWinWords);
+#pragma unroll
+        for (uint32_t c = 0; c < kWinWords / 4; c++) P.x[c] = p[c];
+    }
+    __device__ inline void install(const Pending& P) {
+        if (__builtin_expect(P.ok, 1)) {
+#pragma unroll
+            for (uint32_t c = 0; c < kWinWords / 4; c++) {
+                win[(4 * c + 0) * NT] = P.x[c].x; win[(4 * c + 1) * NT] = P.x[c].y;
+                win[(4 * c + 2) * NT] = P.x[c].z; win[(4 * c + 3) * NT] = P.x[c].w;
+            }
+            lo = P.x[0].x; hi = P.x[0].y; n1 = P.x[0].z; n2 = P.x[0].w;
+            win_bit0 = (int32_t)(P.cur & ~31u);
+            k = 0; sh = P.cur & 31u;
+        } else reload();
+    }
     __device__ inline uint32_t consumed() const { return (uint32_t)(win_bit0 + (int32_t)pos()) - start_bit; }
     // Decode one symbol in two halves, so that a caller with two readers can issue both table lookups before
     // either result is needed: lookup() returns the table entry for the next stream bits (w32), finish() turns
@@ -435,25 +464,35 @@ __device__ inline uint32_t combine(uint32_t ta, bool a_raw, uint32_t tb, bool b_
 
 // Staging of operand A between the two reduce passes (workspace): a16 holds one 16-bit code per element,
 // kWideMarker where the code needs 32 bits, which then sits in a32; a RAW frame keeps its fp32 words in a32.
+// a32 is indexed by the element's position in the message.  a16 is too, except that inside every full half
+// (kHalf elements = 256 segments) the order is phase-major -- [phase of 32 symbols][segment][32] -- so that
+// what a wave stores or loads in one phase (8 segments x 32 codes) is 512 contiguous bytes, not eight half lines.
 struct StageA {
-    int16_t* a16; uint32_t* a32;      // both indexed by the element's position in the message
-    __device__ inline void put_code(uint64_t i, int32_t q, uint32_t& wide_seen) const {
-        if (q > 32767 || q <= kWideMarker) { a16[i] = (int16_t)kWideMarker; a32[i] = (uint32_t)q; wide_seen = 1; }
-        else a16[i] = (int16_t)q;
+    int16_t* a16; uint32_t* a32;
+    // position in a16 of frame element i (frame starts at message element f0 and has nf elements)
+    __device__ static inline uint64_t at16(uint64_t f0, uint32_t nf, uint32_t i) {
+        const uint32_t base = i & ~(kHalf - 1u), j = i & (kHalf - 1u);
+        const bool full = base + kHalf <= nf;
+        return f0 + base + (full ? ((j & (kSeg - 1u)) >> 5) * (kHalf / 8u) + (j >> 8) * kTile16R + (j & 31u) : j);
     }
-    __device__ inline uint32_t get(uint64_t i, bool a_raw) const {   // fp32 bits (RAW) or the code
-        if (a_raw) return a32[i];
-        const int32_t q = a16[i];
-        return (q == kWideMarker) ? a32[i] : (uint32_t)q;
+    __device__ inline void put_code(uint64_t f0, uint32_t nf, uint32_t i, int32_t q, uint32_t& wide_seen) const {
+        if (q > 32767 || q <= kWideMarker) { a16[at16(f0, nf, i)] = (int16_t)kWideMarker; a32[f0 + i] = (uint32_t)q; wide_seen = 1; }
+        else a16[at16(f0, nf, i)] = (int16_t)q;
+    }
+    __device__ inline uint32_t get(uint64_t f0, uint32_t nf, uint32_t i, bool a_raw) const {   // fp32 bits (RAW) or the code
+        if (a_raw) return a32[f0 + i];
+        const int32_t q = a16[at16(f0, nf, i)];
+        return (q == kWideMarker) ? a32[f0 + i] : (uint32_t)q;
     }
 };
+static_assert(kTile16R == 32 && kSeg == 256, "at16 assumes 8 phases of 32 symbols per segment");
 
 // Second reduce pass, one element the general way: fetch A, combine, stage the sum, count its symbol.
 struct AddCtx {
     StageA sa; uint32_t* codes; uint32_t* s_h; uint32_t ncs, copy, K; float step; bool a_raw, b_raw;
     __device__ inline void finish(const SegCtx& C, uint32_t i, uint32_t tb, uint32_t (&zmax)[2], uint32_t& overflow) const {
         const uint64_t g = C.f0 + i;
-        const uint32_t ta = sa.get(g, a_raw);
+        const uint32_t ta = sa.get(C.f0, C.nf, i, a_raw);
         if (a_raw || b_raw) { codes[g] = combine<true>(ta, a_raw, tb, b_raw, step, overflow); return; }
         const uint32_t t = combine<false>(ta, false, tb, false, step, overflow);
         codes[g] = t;
@@ -479,12 +518,12 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
     uint16_t* tile = S->u.tile;
     uint32_t* row32 = reinterpret_cast<uint32_t*>(tile + tid * kTile16Stride);
     uint32_t e = 0;                                   // symbols of my segment decoded so far
-    uint32_t due = 1;
-    auto start_run = [&]() {
-        const bool sched = (--due == 0);              // uniform over the workgroup
-        if (sched) due = ca;
-        if (sched || ra.pos() >= kWinRunLimit) ra.reload();
-    };
+    // Every phase starts with a fresh window: its loads are requested at the end of the phase before and
+    // installed after the output phase in between, so their latency is not waited for.  Inside a phase a lane
+    // refills on its own at a run start when it is too far into its window.
+    typename HuffReader<NT>::Pending pend;
+    ra.request(pend);
+    auto start_run = [&]() { if (ra.pos() >= kWinRunLimit) ra.reload(); };
     auto wide = [&](uint32_t z) -> int32_t {          // only an escape can carry a code of 16 bits or more
         int32_t q = unzigzag(z);
         if (z >= 0xFFFFu) {
@@ -505,11 +544,19 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
     const bool whole = C.vec_ok && (C.first_seg + NT) * kSeg <= C.nf;   // every access is a full, aligned group of 4
     const bool fast_add = (MODE == MODE_ADD_B) && whole && !a_wide && !X.a_raw;
     for (uint32_t r0 = 0; r0 < kSeg; r0 += kTile16R) {
+        ra.install(pend);
         uint2 pa[LPR];                                // MODE_ADD_B: the staged codes of A this thread will add
         if (MODE == MODE_ADD_B && fast_add) {
-            const int16_t* ap = X.sa.a16 + C.f0 + eo0 + r0;
+            // row rw0 + RPK k of this block, phase r0 / 32 (both halves are full here)
+            const int16_t* ap = X.sa.a16 + C.f0 + C.blk0 + (r0 / kTile16R) * (kHalf / 8u) + c;
 #pragma unroll
-            for (uint32_t k = 0; k < LPR; k++) pa[k] = *reinterpret_cast<const uint2*>(ap + (size_t)k * RPK * kSeg);
+            for (uint32_t k = 0; k < LPR; k++) {
+                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                const uint32_t rw = rw0 + k * RPK;
+                const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(
+                    ap + (size_t)(rw / kSeg) * kHalf + (rw % kSeg) * kTile16R));
+                pa[k] = make_uint2(v.x, v.y);
+            }
         }
         if (r0 + kTile16R <= C.cntseg) {
 #pragma unroll
@@ -529,6 +576,7 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
                 row[r] = (uint16_t)next16();
             }
         }
+        ra.request(pend);                             // (after the last phase: requested and dropped)
         __syncthreads();
         const bool plain = whole && S->flags == 0;    // no markers in the tile, no bounds to watch
         if (MODE == MODE_DECOMPRESS && __builtin_expect(plain, 1)) {
@@ -545,11 +593,13 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
                 __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(dst + (size_t)k * RPK * kSeg));
             }
         } else if (MODE == MODE_STAGE_A && __builtin_expect(whole, 1)) {
-            int16_t* dst = X.sa.a16 + C.f0 + eo0 + r0;      // markers are staged as they are
+            int16_t* dst = X.sa.a16 + C.f0 + C.blk0 + (r0 / kTile16R) * (kHalf / 8u) + rw0 * kTile16R + c;   // markers are staged as they are
 #pragma unroll
             for (uint32_t k = 0; k < LPR; k++) {
                 const uint32_t* src = src0 + k * RPK * (kTile16Stride / 2);
-                *reinterpret_cast<uint2*>(dst + (size_t)k * RPK * kSeg) = make_uint2(src[0], src[1]);
+                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                u32x2 v; v.x = src[0]; v.y = src[1];
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(dst + (size_t)k * RPK * kTile16R));   // streaming, as above
             }
         } else if (MODE == MODE_ADD_B && __builtin_expect(fast_add && plain, 1)) {
             uint32_t* dst = X.codes + C.f0 + eo0 + r0;
@@ -569,7 +619,9 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
                     zmax[h] = z > zmax[h] ? z : zmax[h];
                     atomicAdd(&X.s_h[h * 1024u + (sym_of(z, X.K) << X.ncs) + X.copy], 1u);
                 }
-                *reinterpret_cast<uint4*>(dst + (size_t)k * RPK * kSeg) = make_uint4((uint32_t)Q[0], (uint32_t)Q[1], (uint32_t)Q[2], (uint32_t)Q[3]);
+                typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+                u32x4 v; v.x = (uint32_t)Q[0]; v.y = (uint32_t)Q[1]; v.z = (uint32_t)Q[2]; v.w = (uint32_t)Q[3];
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst + (size_t)k * RPK * kSeg));   // streaming, as above
             }
         } else {
             // ragged block, markers in the tile, wide or raw codes of A: element by element
@@ -580,7 +632,7 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
                 for (uint32_t j = 0; j < 4; j++) {
                     if (eo + j >= C.nf) break;
                     const int32_t q = (int16_t)src[j];
-                    if (MODE == MODE_STAGE_A) X.sa.a16[C.f0 + eo + j] = (int16_t)q;
+                    if (MODE == MODE_STAGE_A) X.sa.a16[StageA::at16(C.f0, C.nf, eo + j)] = (int16_t)q;
                     else if (q != kWideMarker) {
                         if (MODE == MODE_DECOMPRESS) A.out[C.f0 + eo + j] = dequantize1(q, A.step);
                         else X.finish(C, eo + j, (uint32_t)q, zmax, overflow);
@@ -606,7 +658,7 @@ __device__ inline void run_elementwise(const DecodeArgs& A, const SegCtx& C, con
             uint32_t t = da.get(e);                                               // fp32 bits (RAW) or zigzag code
             if (!raw) t = (uint32_t)unzigzag(t);
             if (MODE == MODE_DECOMPRESS) A.out[C.f0 + e] = raw ? __uint_as_float(t) : dequantize1((int32_t)t, A.step);
-            else if (MODE == MODE_STAGE_A) { if (raw) X.sa.a32[C.f0 + e] = t; else X.sa.put_code(C.f0 + e, (int32_t)t, wide_seen); }
+            else if (MODE == MODE_STAGE_A) { if (raw) X.sa.a32[C.f0 + e] = t; else X.sa.put_code(C.f0, C.nf, e, (int32_t)t, wide_seen); }
             else X.finish(C, e, t, zmax, overflow);
         }
     }
