@@ -67,7 +67,14 @@ def cpu_baseline(wl):
     return dict(value=3 * gb / step, unit="GB/s", cores=1, kind="oracle",
                 sample="whole %s message (%d elements): compress %.2fs, decompress %.2fs, reduce %.2fs" %
                        (wl["name"], n, t1 - t0, t2 - t1, t4 - t3),
-                compress_GBps=gb / (t1 - t0), decompress_GBps=gb / (t2 - t1), reduce_GBps=gb / (t4 - t3)), s
+                compress_GBps=gb / (t1 - t0), decompress_GBps=gb / (t2 - t1), reduce_GBps=gb / (t4 - t3)), s, r
+
+
+def oracle_decompress(stream, n, eb):
+    import oracle
+    y, _, rc = oracle.decompress(stream, n, eb)
+    assert rc == 0
+    return y
 
 
 def read_traffic(path, workload, kernel):
@@ -210,10 +217,16 @@ def main():
                            kernel_ms=kern),
                roofline=roofline)
     if not args.no_cpu_baseline:
-        base, ref_stream = cpu_baseline(wl)
+        base, ref_stream, ref_reduced = cpu_baseline(wl)
         out["cpu_baseline"] = base
         got = outs[0][:stream_bytes].cpu().numpy()
         out["bytes_match_oracle"] = bool(got.size == ref_stream.size and (got == ref_stream).all())
+        sess.reduce(outs[0], stream_bytes, peer_stream, peer_bytes, n, eb, out=red_out)
+        got = red_out[:sess.result()["bytes"]].cpu().numpy()
+        out["reduce_bytes_match_oracle"] = bool(got.size == ref_reduced.size and (got == ref_reduced).all())
+        sess.decompress(outs[0], stream_bytes, n, eb, out=y)
+        ref_y = oracle_decompress(ref_stream, n, eb)
+        out["decompress_values_match_oracle"] = bool((y.cpu().numpy().view(np.uint32) == ref_y.view(np.uint32)).all())
     print(json.dumps(out))
 
 

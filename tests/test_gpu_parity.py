@@ -228,6 +228,31 @@ def test_reduce_matches_oracle_and_chains(nz):
     assert (np.abs(got.astype(np.float64) - true) <= 4 * float(np.float32(eb))).all()
 
 
+@pytest.mark.parametrize("wide", [False, True], ids=["plain", "wide_codes"])
+def test_reduce_large_frames(nz, wide):
+    """1 MiB frames: whole 131072-element blocks take the vectorised add path, the ragged last frame the general
+    one; `wide` plants codes that need more than 16 bits after the first reduction (spill array, markers)."""
+    n, eb = 2 * 262144 + 70001, 1e-4
+    g, o = _opts_pair(nz, chunk_elems=262144)
+    msgs = [W.gradient_like(n, seed=90 + p) for p in range(3)]
+    if wide:
+        step = oracle.step_constants(eb)[0]
+        for p, m in enumerate(msgs):
+            m[[11, 65536 + 3, 200000, 262144 + 131072 + 5, n - 2]] = np.float32(30000.0 + p) * step   # sums pass 32767
+            m[[70000, 262144 + 7]] = np.float32(-(29000.0 + p)) * step
+    streams = [oracle.compress(m, eb, o)[0] for m in msgs]
+    acc_o = acc_g = streams[0]
+    for p in (1, 2):
+        acc_o, ores, orc = oracle.reduce_frames(acc_o, streams[p], n, eb, o)
+        rc, r, acc_g = gpu_reduce(nz, acc_g, streams[p], n, eb, g)
+        assert rc == 0 and orc == 0 and r["status"] == 0
+        assert r["bytes"] == ores.bytes and _first_diff(acc_g, acc_o) == -1
+        assert (r["n_raw"], r["n_fixed"], r["n_huff"]) == (ores.n_raw, ores.n_fixed, ores.n_huff)
+    rc, r, got = gpu_decompress(nz, acc_g, n, eb, g)
+    ref = oracle.decompress(acc_o, n, eb)[0]
+    assert r["status"] == 0 and (got.view(np.uint32) == ref.view(np.uint32)).all()
+
+
 @pytest.mark.parametrize("ca,cb", [(0, 0), (0, 1), (0, 2), (1, 1), (1, 2), (2, 1), (2, 2), (2, 0)])
 def test_reduce_all_codec_pairs(nz, ca, cb):
     n, eb = 70001, 1e-4
