@@ -5,6 +5,7 @@
 // the cost (Sec. IV-C, Eq. 1-2, Algorithm 1), frame = header + payload (Sec. IV-D "Batch Framing").
 // Unlike the paper's sampled estimate by one control thread, the statistics here cover the whole frame,
 // so predicted and realized sizes coincide and Algorithm 1's post-validation never fires.
+#include <type_traits>
 #include "nz_common.hpp"
 #include "nz_scan.hpp"
 
@@ -532,28 +533,32 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
             uint64_t pk[kEncIters];               // the thread's 4 symbols of a pass packed LSB-first
             uint32_t ln[kEncIters];               // exclusive bit offset of the thread inside its pass
             uint32_t wide = 0;                    // pass mask: the 4 symbols need more than 64 bits
-            // phase 1
+            // phase 1 (compiled twice: whole sub-blocks carry no bounds logic)
+            auto phase1 = [&](auto whole_tag) {
+                constexpr bool WHOLE = decltype(whole_tag)::value;
 #pragma unroll
-            for (uint32_t it = 0; it < kEncIters; it++) {
-                const uint32_t i = it * 1024 + tid * 4;
-                uint64_t acc = 0;
-                uint32_t tl = 0;
+                for (uint32_t it = 0; it < kEncIters; it++) {
+                    const uint32_t i = it * 1024 + tid * 4;
+                    uint64_t acc = 0;
+                    uint32_t tl = 0;
 #pragma unroll
-                for (uint32_t j = 0; j < 4; j++) {
-                    const uint32_t z = enc_zz<SRC>(raw[it][j], A);
-                    const uint64_t b = S.book[z < kesc ? z : kesc];
-                    const bool valid = (cnt == kEncBlock) || i + j < cnt;
-                    const uint32_t len = valid ? (uint32_t)(b >> 32) : 0u, code = valid ? (uint32_t)b : 0u;
-                    acc |= (uint64_t)code << (tl & 63u);                  // garbage once tl > 64: the pass is then redone
-                    tl += len;
-                    if (z >= kesc && valid) { acc |= (uint64_t)z << (tl & 63u); tl += 32u; }
+                    for (uint32_t j = 0; j < 4; j++) {
+                        const uint32_t z = enc_zz<SRC>(raw[it][j], A);
+                        const uint64_t b = S.book[z < kesc ? z : kesc];
+                        const bool valid = WHOLE || i + j < cnt;
+                        const uint32_t len = valid ? (uint32_t)(b >> 32) : 0u, code = valid ? (uint32_t)b : 0u;
+                        acc |= (uint64_t)code << (tl & 63u);              // garbage once tl > 64: the pass is then redone
+                        tl += len;
+                        if (z >= kesc && valid) { acc |= (uint64_t)z << (tl & 63u); tl += 32u; }
+                    }
+                    pk[it] = acc;
+                    wide |= (tl > 64u ? 1u : 0u) << it;
+                    const uint32_t incl = wave_incl_scan_dpp(tl);
+                    ln[it] = incl - tl;                               // exclusive inside the wave's segment
+                    if (lane == 63) S.wtot[it * 4 + wave] = incl;     // bits of segment it*4 + wave
                 }
-                pk[it] = acc;
-                wide |= (tl > 64u ? 1u : 0u) << it;
-                const uint32_t incl = wave_incl_scan_dpp(tl);
-                ln[it] = incl - tl;                                   // exclusive inside the wave's segment
-                if (lane == 63) S.wtot[it * 4 + wave] = incl;         // bits of segment it*4 + wave
-            }
+            };
+            if (cnt == kEncBlock) phase1(std::true_type{}); else phase1(std::false_type{});
             enc_load(G, sb + 1, raw);             // the next sub-block's words arrive during phase 2 and the flush
             __syncthreads();
             uint32_t pbase[kEncIters + 1];        // bit offset of every pass inside the sub-block
