@@ -373,10 +373,16 @@ struct EncShared {
     __align__(16) uint32_t wtot[kEncSegs];     // bit count of each of the sub-block's segments
 };
 
-// zigzag code of a source word
+// zigzag code of a source word.  Only coded (FIXEDLEN / HUFFMAN) frames come here, and a frame is coded only if
+// the statistics pass found every element quantizable, so the acceptance tests of the quantizer are known to pass
+// and q is simply rne(x * inv_step).
 template <int SRC>
 __device__ inline uint32_t enc_zz(uint32_t w, const CompressArgs& A) {
-    if (SRC == 0) { int32_t t; quantize1(__uint_as_float(w), A.eb, A.step, A.inv_step, t); return zigzag(t); }
+    if (SRC == 0) {
+#pragma clang fp contract(off)
+        const float u = __uint_as_float(w) * A.inv_step;
+        return zigzag((int32_t)__builtin_rintf(u));
+    }
     return zigzag((int32_t)w);
 }
 
