@@ -539,6 +539,7 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
             uint64_t pk[kEncIters];               // the thread's 4 symbols of a pass packed LSB-first
             uint32_t ln[kEncIters];               // exclusive bit offset of the thread inside its pass
             uint32_t wide = 0;                    // pass mask: the 4 symbols need more than 64 bits
+            uint32_t zs[kEncIters][4];            // zigzag codes, kept for the passes that have to be redone
             // phase 1 (compiled twice: whole sub-blocks carry no bounds logic)
             auto phase1 = [&](auto whole_tag) {
                 constexpr bool WHOLE = decltype(whole_tag)::value;
@@ -550,6 +551,7 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
 #pragma unroll
                     for (uint32_t j = 0; j < 4; j++) {
                         const uint32_t z = enc_zz<SRC>(raw[it][j], A);
+                        zs[it][j] = z;
                         const uint64_t b = S.book[z < kesc ? z : kesc];
                         const bool valid = WHOLE || i + j < cnt;
                         const uint32_t len = valid ? (uint32_t)(b >> 32) : 0u, code = valid ? (uint32_t)b : 0u;
@@ -596,10 +598,11 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
                             if (sh) { const uint32_t hi = (uint32_t)(a >> (64u - sh)); if (hi) atomicOr(&X[wi + 2], hi); }
                         }
                     } else {
-                        // the thread's 4 symbols need more than 64 bits (rare): symbol by symbol from the source
+                        // the thread's 4 symbols need more than 64 bits (rare): symbol by symbol
                         const uint32_t i = it * 1024 + tid * 4;
+#pragma unroll
                         for (uint32_t j = 0; j < 4; j++)
-                            if (i + j < cnt) put_symbol(X, enc_zz<SRC>(sub_src[i + j], A), pos);
+                            if (i + j < cnt) put_symbol(X, zs[it][j], pos);
                     }
                 }
                 __syncthreads();
