@@ -298,3 +298,56 @@ def test_reduce_raw_nan_range_and_mismatch(nz):
     # capacity
     rc, r, _ = gpu_reduce(nz, sa, sb, n, eb, g, cap=int(ores.bytes) - 16)
     assert r["status"] == nz.ERR_CAPACITY and r["bytes"] == 0
+
+
+# ------------------------------------------------------------------------------------------------
+# seeded sweep over sizes, frame lengths, alphabets, bounds and value mixtures
+# ------------------------------------------------------------------------------------------------
+
+def _mixture(rng, n):
+    """Values with the structure the method meets: a peaked body, heavy outliers, runs of zeros, smooth stretches."""
+    kind = rng.integers(0, 5)
+    if kind == 0:
+        x = rng.laplace(0, 1e-3, n)
+    elif kind == 1:
+        x = rng.laplace(0, 1e-3, n)
+        m = rng.random(n) < rng.choice([0.001, 0.02, 0.2])
+        x[m] = rng.laplace(0, rng.choice([0.05, 1.0, 30.0]), int(m.sum()))
+    elif kind == 2:
+        x = np.sin(np.arange(n) * rng.uniform(1e-4, 1e-2)) * rng.uniform(1e-3, 1.0) + rng.normal(0, 1e-4, n)
+    elif kind == 3:
+        x = rng.uniform(-1, 1, n) * rng.choice([1e-3, 0.1, 5.0])
+    else:
+        x = rng.laplace(0, 1e-3, n)
+        a = rng.integers(0, n)
+        x[a:a + rng.integers(0, n)] = 0.0
+    return x.astype(np.float32)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_seeded_sweep(nz, seed):
+    rng = np.random.default_rng(1000 + seed)
+    n = int(rng.choice([1, 5, 255, 256, 257, 4097, 65535, 65536, 65537, 131072, 200001, 300007, 600011]))
+    chunk = int(rng.choice([16, 1000, 4096, 16384, 65536, 100003, 131072, 262144, 1 << 20]))
+    K = int(rng.choice([2, 4, 64, 256, 256, 256, 512, 1024]))
+    eb = float(rng.choice([1e-2, 1e-3, 1e-4, 1e-5]))
+    kw = dict(chunk_elems=chunk, alphabet=K)
+    if rng.random() < 0.2:
+        kw["force_codec"] = int(rng.integers(0, 3))
+    a, b = _mixture(rng, n), _mixture(rng, n)
+    if rng.random() < 0.15:
+        a[rng.integers(0, n)] = np.nan
+    ref_a, _ = check_compress(nz, a, eb, **kw)
+    check_decompress(nz, ref_a, a, eb, **kw)
+    g, o = _opts_pair(nz, **kw)
+    ref_b = oracle.compress(b, eb, o)[0]
+    ref, ores, orc = oracle.reduce_frames(ref_a, ref_b, n, eb, o)
+    rc, r, got = gpu_reduce(nz, ref_a, ref_b, n, eb, g)
+    assert rc == 0 and r["status"] == orc
+    if orc == 0:
+        assert r["bytes"] == ores.bytes and _first_diff(got, ref) == -1
+        ref2, ores2, orc2 = oracle.reduce_frames(ref, ref_a, n, eb, o)          # a second level: wider codes
+        rc, r2, got2 = gpu_reduce(nz, got, ref_a, n, eb, g)
+        assert r2["status"] == orc2
+        if orc2 == 0:
+            assert r2["bytes"] == ores2.bytes and _first_diff(got2, ref2) == -1
