@@ -80,8 +80,8 @@ size_t nz_compress_bound(size_t n, const nz_opts* opts);
 /* Host, pure.  Workspace bytes nz_compress / nz_decompress need for n elements (0 on invalid opts). */
 size_t nz_workspace_bytes(size_t n, const nz_opts* opts);
 
-/* Host, pure.  Workspace bytes nz_reduce_frames needs: about 10 bytes per element (the n summed 32-bit
- * codes, and operand A staged between the two decode passes as 16-bit codes with a 32-bit spill array). */
+/* Host, pure.  Workspace bytes nz_reduce_frames needs: about 12 bytes per element (operand A between the two
+ * decode passes, and the sums handed to the encoder, each staged as 16-bit codes with a 32-bit spill array). */
 size_t nz_reduce_workspace_bytes(size_t n, const nz_opts* opts);
 
 /*

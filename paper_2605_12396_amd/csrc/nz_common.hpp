@@ -65,7 +65,7 @@ static_assert(sizeof(Ctrl) == 64, "Ctrl is 64 bytes");
 // Workspace carve-up; computed identically on host for sizing and launch.
 struct WsLayout {
     size_t ctrl, frame_desc, zero_end;      // [ctrl, zero_end) is cleared per call
-    size_t meta, book_code, book_len, phist, pmeta, grp_start, codes, a16, a32, akind, awide, total;
+    size_t meta, book_code, book_len, phist, pmeta, grp_start, codes, c16, cwide, a16, a32, akind, awide, total;
 };
 
 __host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -84,7 +84,9 @@ __host__ inline WsLayout ws_layout(size_t n, uint32_t chunk, uint32_t stat_block
     L.phist = o;       o += align_up(4 * (size_t)kMaxK * n_frames * sbpf, 256);
     L.pmeta = o;       o += align_up(8 * n_frames * sbpf, 256);
     L.grp_start = o;   o += align_up(4 * n_frames * sbpf, 256);
-    L.codes = o;       if (with_codes) o += align_up(4 * n, 256);      // reduce: the 32-bit sums
+    L.codes = o;       if (with_codes) o += align_up(4 * n, 256);      // reduce: sums that need 32 bits, fp32 sums of RAW frames
+    L.c16 = o;         if (with_codes) o += align_up(2 * n, 256);      // reduce: the sums as 16-bit codes
+    L.cwide = o;       if (with_codes) o += align_up(4 * n_frames * sbpf, 256);
     L.a16 = o;         if (with_codes) o += align_up(2 * n, 256);      // reduce: operand A, 16-bit codes
     L.a32 = o;         if (with_codes) o += align_up(4 * n, 256);      // reduce: operand A, wide codes and RAW words
     L.akind = o;       if (with_codes) o += align_up(4 * n_frames, 256);

@@ -388,21 +388,37 @@ __device__ inline uint32_t enc_zz(uint32_t w, const CompressArgs& A) {
 
 // Geometry of one encode workgroup.
 struct EncGroup {
-    const uint32_t* src;      // first source word of the group
+    const uint32_t* src;      // first 32-bit source word of the group (fp32 input; reduce: wide sums, fp32 sums of RAW frames)
+    const int16_t* src16;     // reduce: the group's sums as 16-bit codes, -32768 = "needs 32 bits, look in src"
     uint32_t g0, gcnt, nf, nsub, gb;
-    bool vec_ok, last_grp;
+    bool vec_ok, last_grp, wide16;   // wide16: the group's 16-bit codes contain markers
 };
 
+// Source word i of the group: fp32 bits (SRC 0) or the summed code (SRC 1, coded frames).
+template <int SRC>
+__device__ inline uint32_t enc_word(const EncGroup& G, uint32_t i) {
+    if (SRC == 0) return G.src[i];
+    const int32_t q = G.src16[i];
+    return (q == -32768) ? G.src[i] : (uint32_t)q;
+}
+
 // Source words of sub-block sb: pass `it` covers its symbols it*1024 + tid*4 .. +3 (zero past the end).
+template <int SRC>
 __device__ inline void enc_load(const EncGroup& G, uint32_t sb, uint32_t (&raw)[kEncIters][4]) {
     const uint32_t tid = threadIdx.x;
     const uint32_t* src = G.src + sb * kEncBlock;
     const uint32_t cnt = (sb < G.nsub) ? ((G.gcnt - sb * kEncBlock < kEncBlock) ? (G.gcnt - sb * kEncBlock) : kEncBlock) : 0u;
-    if (G.vec_ok && cnt == kEncBlock) {                                  // uniform: the common, branch-free case
+    if (G.vec_ok && cnt == kEncBlock && (SRC == 0 || !G.wide16)) {       // uniform: the common, branch-free case
 #pragma unroll
         for (uint32_t it = 0; it < kEncIters; it++) {
-            const uint4 t = *reinterpret_cast<const uint4*>(src + it * 1024 + tid * 4);
-            raw[it][0] = t.x; raw[it][1] = t.y; raw[it][2] = t.z; raw[it][3] = t.w;
+            if (SRC == 0) {
+                const uint4 t = *reinterpret_cast<const uint4*>(src + it * 1024 + tid * 4);
+                raw[it][0] = t.x; raw[it][1] = t.y; raw[it][2] = t.z; raw[it][3] = t.w;
+            } else {
+                const uint2 t = *reinterpret_cast<const uint2*>(G.src16 + sb * kEncBlock + it * 1024 + tid * 4);
+                raw[it][0] = (uint32_t)(int32_t)(int16_t)(t.x & 0xFFFFu); raw[it][1] = (uint32_t)((int32_t)t.x >> 16);
+                raw[it][2] = (uint32_t)(int32_t)(int16_t)(t.y & 0xFFFFu); raw[it][3] = (uint32_t)((int32_t)t.y >> 16);
+            }
         }
     } else {
 #pragma unroll 1
@@ -410,7 +426,7 @@ __device__ inline void enc_load(const EncGroup& G, uint32_t sb, uint32_t (&raw)[
             const uint32_t i = it * 1024 + tid * 4;
             uint32_t t[4];
 #pragma unroll
-            for (uint32_t j = 0; j < 4; j++) t[j] = (i + j < cnt) ? src[i + j] : 0u;
+            for (uint32_t j = 0; j < 4; j++) t[j] = (i + j < cnt) ? enc_word<SRC>(G, sb * kEncBlock + i + j) : 0u;
 #pragma unroll
             for (uint32_t q = 0; q < kEncIters; q++)
                 if (q == it) { raw[q][0] = t[0]; raw[q][1] = t[1]; raw[q][2] = t[2]; raw[q][3] = t[3]; }
@@ -437,7 +453,7 @@ __device__ inline void enc_raw_fixed(const CompressArgs& A, const EncGroup& G, c
         const uint32_t pass_words = (pass_syms * w + 31u) / 32u;
         uint32_t z[4];
 #pragma unroll
-        for (uint32_t j = 0; j < 4; j++) z[j] = (tid * 4 + j < pass_syms) ? enc_zz<SRC>(G.src[p0 + tid * 4 + j], A) : 0u;
+        for (uint32_t j = 0; j < 4; j++) z[j] = (tid * 4 + j < pass_syms) ? enc_zz<SRC>(enc_word<SRC>(G, p0 + tid * 4 + j), A) : 0u;
         for (uint32_t k = tid; k < pass_words; k += kEncThreads) stage[k] = 0;
         __syncthreads();
         uint32_t pos = tid * 4 * w;
@@ -475,6 +491,9 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
     // source words: fp32 input (SRC 0) or the staged codes / fp32 sums of the reduce (SRC 1)
     G.src = (SRC == 0 ? reinterpret_cast<const uint32_t*>(A.in) : reinterpret_cast<const uint32_t*>(A.ws + A.L.codes)) + f0 + G.g0;
     G.vec_ok = (((f0 + G.g0) & 3u) == 0);                                // kEncBlock is a multiple of 4
+    G.src16 = reinterpret_cast<const int16_t*>(A.ws + A.L.c16) + f0 + G.g0;
+    G.wide16 = false;
+    if (SRC == 1) G.wide16 = reinterpret_cast<const uint32_t*>(A.ws + A.L.cwide)[(size_t)frame * A.sbpf + G.g0 / A.stat_block] != 0;
     const uint32_t K = A.K, kesc = K - 1u;
 
     const FrameMeta M = reinterpret_cast<const FrameMeta*>(A.ws + A.L.meta)[frame];
@@ -483,7 +502,7 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
     if (M.codec != CODEC_HUFF) enc_raw_fixed<SRC>(A, G, M, fr, S.stage[0]);
     else {
         uint32_t raw[kEncIters][4];
-        enc_load(G, 0, raw);
+        enc_load<SRC>(G, 0, raw);
         for (uint32_t s = tid; s < K; s += kEncThreads) {
             const uint32_t sy = (s == kesc) ? 0u : s + 1u;
             const uint32_t c = reinterpret_cast<const uint32_t*>(A.ws + A.L.book_code)[(size_t)frame * kMaxK + sy];
@@ -535,7 +554,6 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
 
         for (uint32_t sb = 0; sb < G.nsub; sb++) {
             const uint32_t cnt = (G.gcnt - sb * kEncBlock < kEncBlock) ? (G.gcnt - sb * kEncBlock) : kEncBlock;
-            const uint32_t* sub_src = G.src + sb * kEncBlock;
             uint64_t pk[kEncIters];               // the thread's 4 symbols of a pass packed LSB-first
             uint32_t ln[kEncIters];               // exclusive bit offset of the thread inside its pass
             uint32_t wide = 0;                    // pass mask: the 4 symbols need more than 64 bits
@@ -567,7 +585,7 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
                 }
             };
             if (cnt == kEncBlock) phase1(std::true_type{}); else phase1(std::false_type{});
-            enc_load(G, sb + 1, raw);             // the next sub-block's words arrive during phase 2 and the flush
+            enc_load<SRC>(G, sb + 1, raw);             // the next sub-block's words arrive during phase 2 and the flush
             __syncthreads();
             uint32_t pbase[kEncIters + 1];        // bit offset of every pass inside the sub-block
             pbase[0] = 0;
@@ -618,7 +636,7 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
                     for (uint32_t q = 0; q < kEncIters; q++) if (q == it) { lnit = ln[q]; pbits = pbase[q + 1] - pbase[q]; }
                     uint32_t pos = rel + lnit;
                     for (uint32_t j = 0; j < 4; j++)
-                        if (i + j < cnt) put_symbol(X, enc_zz<SRC>(sub_src[i + j], A), pos);
+                        if (i + j < cnt) put_symbol(X, enc_zz<SRC>(enc_word<SRC>(G, sb * kEncBlock + i + j), A), pos);
                     __syncthreads();
                     flush(X, X, rel + pbits);
                     __syncthreads();

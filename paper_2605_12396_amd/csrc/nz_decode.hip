@@ -432,7 +432,7 @@ struct __align__(16) DecShared {
     uint32_t win[NT * kWinWords];
     union { uint16_t tile[NT * kTile16Stride]; BuildScratch build; } u;
     uint64_t wsum[NT / 64];
-    uint32_t zmax[2], flags;
+    uint32_t zmax[2], flags, cwide[2];
 };
 
 struct SegCtx {
@@ -488,15 +488,22 @@ struct StageA {
 static_assert(kTile16R == 32 && kSeg == 256, "at16 assumes 8 phases of 32 symbols per segment");
 
 // Second reduce pass, one element the general way: fetch A, combine, stage the sum, count its symbol.
+// The sums are staged for the encoder as 16-bit codes in c16 (message order), kWideMarker where a sum needs 32
+// bits, which then sits in codes; a frame with a RAW operand keeps its fp32 sums in codes.  wide[h] is raised when
+// half h of the workgroup's block holds a marker.
 struct AddCtx {
-    StageA sa; uint32_t* codes; uint32_t* s_h; uint32_t ncs, copy, K; float step; bool a_raw, b_raw;
+    StageA sa; uint32_t* codes; int16_t* c16; uint32_t* s_h; uint32_t* s_cwide;
+    uint32_t ncs, copy, K; float step; bool a_raw, b_raw;
     __device__ inline void finish(const SegCtx& C, uint32_t i, uint32_t tb, uint32_t (&zmax)[2], uint32_t& overflow) const {
         const uint64_t g = C.f0 + i;
         const uint32_t ta = sa.get(C.f0, C.nf, i, a_raw);
         if (a_raw || b_raw) { codes[g] = combine<true>(ta, a_raw, tb, b_raw, step, overflow); return; }
         const uint32_t t = combine<false>(ta, false, tb, false, step, overflow);
-        codes[g] = t;
-        const uint32_t z = zigzag((int32_t)t), h = (i - C.blk0) >> 16;
+        const uint32_t h = (i - C.blk0) >> 16;
+        const int32_t Q = (int32_t)t;
+        if (Q > 32767 || Q <= kWideMarker) { c16[g] = (int16_t)kWideMarker; codes[g] = t; s_cwide[h] = 1u; }
+        else c16[g] = (int16_t)Q;
+        const uint32_t z = zigzag(Q);
         zmax[h] = z > zmax[h] ? z : zmax[h];
         atomicAdd(&s_h[h * 1024u + (sym_of(z, K) << ncs) + copy], 1u);
     }
@@ -602,7 +609,7 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
                 __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(dst + (size_t)k * RPK * kTile16R));   // streaming, as above
             }
         } else if (MODE == MODE_ADD_B && __builtin_expect(fast_add && plain, 1)) {
-            uint32_t* dst = X.codes + C.f0 + eo0 + r0;
+            int16_t* dst = X.c16 + C.f0 + eo0 + r0;
 #pragma unroll
             for (uint32_t k = 0; k < LPR; k++) {
                 const uint32_t* src = src0 + k * RPK * (kTile16Stride / 2);
@@ -619,9 +626,24 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
                     zmax[h] = z > zmax[h] ? z : zmax[h];
                     atomicAdd(&X.s_h[h * 1024u + (sym_of(z, X.K) << X.ncs) + X.copy], 1u);
                 }
-                typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-                u32x4 v; v.x = (uint32_t)Q[0]; v.y = (uint32_t)Q[1]; v.z = (uint32_t)Q[2]; v.w = (uint32_t)Q[3];
-                __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(dst + (size_t)k * RPK * kSeg));   // streaming, as above
+                // operands of 16 bits: |Q| <= 65534; a sum outside the 16-bit codes is rare and goes to the 32-bit array
+                const int32_t qhi = max(max(Q[0], Q[1]), max(Q[2], Q[3])), qlo = min(min(Q[0], Q[1]), min(Q[2], Q[3]));
+                uint32_t w0 = ((uint32_t)Q[0] & 0xFFFFu) | ((uint32_t)Q[1] << 16), w1 = ((uint32_t)Q[2] & 0xFFFFu) | ((uint32_t)Q[3] << 16);
+                if (__builtin_expect(qhi > 32767 || qlo <= kWideMarker, 0)) {
+                    uint32_t* c32 = X.codes + C.f0 + eo0 + r0 + (size_t)k * RPK * kSeg;
+                    uint32_t hw[4];
+#pragma unroll
+                    for (uint32_t j = 0; j < 4; j++) {
+                        const bool wd = Q[j] > 32767 || Q[j] <= kWideMarker;
+                        if (wd) c32[j] = (uint32_t)Q[j];
+                        hw[j] = wd ? (uint32_t)(uint16_t)kWideMarker : ((uint32_t)Q[j] & 0xFFFFu);
+                    }
+                    w0 = hw[0] | (hw[1] << 16); w1 = hw[2] | (hw[3] << 16);
+                    X.s_cwide[h] = 1u;
+                }
+                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                u32x2 v; v.x = w0; v.y = w1;
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(dst + (size_t)k * RPK * kSeg));   // streaming, as above
             }
         } else {
             // ragged block, markers in the tile, wide or raw codes of A: element by element
@@ -667,7 +689,7 @@ __device__ inline void run_elementwise(const DecodeArgs& A, const SegCtx& C, con
 
 // One workgroup per NT segments of one frame.
 template <int MODE, int NT>
-__global__ __launch_bounds__(NT) void k_decode(DecodeArgs A) {
+__global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_decode(DecodeArgs A) {
     __shared__ DecTables s_t;
     __shared__ DecShared<NT> S;
     __shared__ uint32_t s_h[MODE == MODE_ADD_B ? 2048 : 1];
@@ -720,7 +742,7 @@ __global__ __launch_bounds__(NT) void k_decode(DecodeArgs A) {
         seglen = (V.kind == KIND_HUFF && seg_valid) ? V.segt[gseg] : 0u;
         const uint32_t incl = wave_incl_scan_dpp(seglen);
         if (lane == 63) S.wsum[wave] = incl;
-        if (tid == 0) { S.zmax[0] = 0; S.zmax[1] = 0; S.flags = 0; }
+        if (tid == 0) { S.zmax[0] = 0; S.zmax[1] = 0; S.flags = 0; S.cwide[0] = 0; S.cwide[1] = 0; }
         __syncthreads();
         uint32_t excl = incl - seglen;
         for (uint32_t w = 0; w < wave; w++) excl += (uint32_t)S.wsum[w];
@@ -739,7 +761,8 @@ __global__ __launch_bounds__(NT) void k_decode(DecodeArgs A) {
 
     AddCtx X;
     X.sa.a16 = reinterpret_cast<int16_t*>(A.ws + A.L.a16); X.sa.a32 = reinterpret_cast<uint32_t*>(A.ws + A.L.a32);
-    X.codes = reinterpret_cast<uint32_t*>(A.ws + A.L.codes);
+    X.codes = reinterpret_cast<uint32_t*>(A.ws + A.L.codes); X.c16 = reinterpret_cast<int16_t*>(A.ws + A.L.c16);
+    X.s_cwide = S.cwide;
     X.s_h = s_h; X.K = A.K; X.step = A.step; X.ncs = 0; X.copy = 0; X.a_raw = false; X.b_raw = false;
     uint32_t* akind = reinterpret_cast<uint32_t*>(A.ws + A.L.akind);   // per frame: operand A is RAW
     uint32_t* awide = reinterpret_cast<uint32_t*>(A.ws + A.L.awide);   // per half: some code of A needs 32 bits
@@ -790,7 +813,10 @@ __global__ __launch_bounds__(NT) void k_decode(DecodeArgs A) {
             for (uint32_t cc = 0; cc < (1u << X.ncs); cc++) t += s_h[h * 1024u + (sy << X.ncs) + cc];
             ph[sy] = t;
         }
-        if (tid == 0) reinterpret_cast<uint2*>(A.ws + A.L.pmeta)[hb] = make_uint2(S.zmax[h], out_raw ? 1u : 0u);
+        if (tid == 0) {
+            reinterpret_cast<uint2*>(A.ws + A.L.pmeta)[hb] = make_uint2(S.zmax[h], out_raw ? 1u : 0u);
+            reinterpret_cast<uint32_t*>(A.ws + A.L.cwide)[hb] = S.cwide[h];
+        }
     }
 }
 
