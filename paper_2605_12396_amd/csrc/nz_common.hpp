@@ -25,7 +25,7 @@ enum : uint32_t { CODEC_RAW = 0, CODEC_FIXED = 1, CODEC_HUFF = 2 };
 
 // ---- launch geometry ----
 constexpr uint32_t kStatThreads   = 512;
-constexpr uint32_t kStatBlock     = 32768;       // symbols per statistics workgroup (compress)
+constexpr uint32_t kStatBlock     = 65536;       // symbols per statistics workgroup (compress)
 constexpr uint32_t kEncThreads    = 256;
 constexpr uint32_t kEncBlock      = 4096;        // symbols per encode sub-block = 16 segments
 constexpr uint32_t kEncIters      = kEncBlock / (kEncThreads * 4);   // passes of 1024 symbols
@@ -150,6 +150,10 @@ __device__ inline uint32_t wave_max(uint32_t v) {
 __device__ inline uint32_t zigzag(int32_t q) { return ((uint32_t)q << 1) ^ (uint32_t)(q >> 31); }
 __device__ inline int32_t unzigzag(uint32_t z) { return (int32_t)(z >> 1) ^ -(int32_t)(z & 1u); }
 __device__ inline uint32_t sym_of(uint32_t z, uint32_t K) { return z <= K - 2u ? z + 1u : 0u; }
+// Histogram bin of a zigzag code while counting: one min instead of the compare-and-select above; bin b < K-1
+// counts symbol b + 1 and bin K-1 counts the escape symbol 0 (bin_symbol maps back when the counts are written out).
+__device__ inline uint32_t bin_of(uint32_t z, uint32_t K) { return z < K - 1u ? z : K - 1u; }
+__device__ inline uint32_t bin_symbol(uint32_t b, uint32_t K) { return b == K - 1u ? 0u : b + 1u; }
 
 // Quantize one value (interface quantizer, Sec. IV-B): u = fl(x*inv_step), q = rne(u), accepted when
 // |u| <= 32767 and fl(|x - fl(q*step)|) <= eb.  Every product and difference is rounded on its own.

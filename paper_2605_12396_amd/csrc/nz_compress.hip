@@ -58,13 +58,13 @@ __global__ __launch_bounds__(kStatThreads) void k_stats(CompressArgs A) {
                 if (!quantize1(v[j], A.eb, A.step, A.inv_step, q)) unq = 1;
                 const uint32_t z = zigzag(q);
                 zmax = z > zmax ? z : zmax;
-                atomicAdd(&s_h[(sym_of(z, K) << ncs) + copy], 1u);
+                atomicAdd(&s_h[(bin_of(z, K) << ncs) + copy], 1u);
             }
         }
     };
     if (vec_ok && cnt == kStatBlock) {
-        // whole block: four 16-byte loads in flight per thread, no bounds checks
-        constexpr uint32_t kIters = kStatBlock / (kStatThreads * 4), kDepth = 4;
+        // whole block: eight 16-byte loads in flight per thread, no bounds checks
+        constexpr uint32_t kIters = kStatBlock / (kStatThreads * 4), kDepth = 8;
         static_assert(kIters % kDepth == 0, "statistics block must be a whole number of load groups");
         const float4* src4 = reinterpret_cast<const float4*>(src) + tid;
 #pragma unroll 1
@@ -94,7 +94,7 @@ __global__ __launch_bounds__(kStatThreads) void k_stats(CompressArgs A) {
     for (uint32_t s = tid; s < K; s += kStatThreads) {
         uint32_t t = 0;
         for (uint32_t c = 0; c < (1u << ncs); c++) t += s_h[(s << ncs) + c];
-        ph[s] = t;
+        ph[bin_symbol(s, K)] = t;
     }
     if (tid == 0) {
         uint2* pm = reinterpret_cast<uint2*>(A.ws + A.L.pmeta) + blockIdx.x;

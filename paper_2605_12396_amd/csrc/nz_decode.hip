@@ -505,7 +505,7 @@ struct AddCtx {
         else c16[g] = (int16_t)Q;
         const uint32_t z = zigzag(Q);
         zmax[h] = z > zmax[h] ? z : zmax[h];
-        atomicAdd(&s_h[h * 1024u + (sym_of(z, K) << ncs) + copy], 1u);
+        atomicAdd(&s_h[h * 1024u + (bin_of(z, K) << ncs) + copy], 1u);
     }
 };
 
@@ -624,7 +624,7 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
                 for (uint32_t j = 0; j < 4; j++) {
                     const uint32_t z = zigzag(Q[j]);
                     zmax[h] = z > zmax[h] ? z : zmax[h];
-                    atomicAdd(&X.s_h[h * 1024u + (sym_of(z, X.K) << X.ncs) + X.copy], 1u);
+                    atomicAdd(&X.s_h[h * 1024u + (bin_of(z, X.K) << X.ncs) + X.copy], 1u);
                 }
                 // operands of 16 bits: |Q| <= 65534; a sum outside the 16-bit codes is rare and goes to the 32-bit array
                 const int32_t qhi = max(max(Q[0], Q[1]), max(Q[2], Q[3])), qlo = min(min(Q[0], Q[1]), min(Q[2], Q[3]));
@@ -811,7 +811,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
         for (uint32_t sy = tid; sy < A.K; sy += NT) {
             uint32_t t = 0;
             for (uint32_t cc = 0; cc < (1u << X.ncs); cc++) t += s_h[h * 1024u + (sy << X.ncs) + cc];
-            ph[sy] = t;
+            ph[bin_symbol(sy, A.K)] = t;
         }
         if (tid == 0) {
             reinterpret_cast<uint2*>(A.ws + A.L.pmeta)[hb] = make_uint2(S.zmax[h], out_raw ? 1u : 0u);
