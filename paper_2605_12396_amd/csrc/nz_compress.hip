@@ -115,7 +115,7 @@ __global__ __launch_bounds__(kBookThreads) void k_codebook(CompressArgs A) {
     __shared__ uint32_t s_f[kMaxK];
     __shared__ __align__(16) uint32_t s_key[kMaxK];
     __shared__ uint32_t s_sorted[kMaxK];
-    __shared__ uint32_t s_w[2 * kMaxK];
+    __shared__ uint32_t s_w[2 * kMaxK + 16];      // leaves [0, m) + 8 sentinels; internal nodes from kMaxK + 8, then sentinels
     __shared__ uint16_t s_par[2 * kMaxK];
     __shared__ __align__(4) uint8_t s_len[kMaxK];
     __shared__ uint16_t s_rank[kMaxK];
@@ -167,38 +167,47 @@ __global__ __launch_bounds__(kBookThreads) void k_codebook(CompressArgs A) {
         s_sorted[rank] = key;
     }
     __syncthreads();
+    // leaves in order, followed by sentinels; the internal-node queue starts out all sentinels
+    constexpr uint32_t INF = 0xFFFFFFFFu;
+    uint32_t* s_int = s_w + kMaxK + 8;
     if (tid < m) s_w[tid] = s_sorted[tid] >> 10;
+    if (tid < 8) { s_w[m + tid] = INF; s_int[kMaxK + tid] = INF; }
+    s_int[tid] = INF;
     __syncthreads();
 
-    // (3) two-queue merge, one lane; queue heads cached in registers
+    // (3) two-queue merge, one lane.  A lone wave pays the full latency of every dependent instruction, so the
+    // step is kept on the scalar unit: the two heads of either queue live in scalar registers, every weight that
+    // comes from LDS is moved there with readfirstlane, and the entries behind the heads are requested one step
+    // before they are needed (entries past the end of a queue read as sentinels; a node that would be a head
+    // right after its creation is forwarded from registers).
     if (tid == 0 && m >= 2) {
-        const uint32_t INF = 0xFFFFFFFFu;
-        uint32_t ia = 0, ib = m, nb = m;
-        uint32_t a0 = s_w[0], a1 = (m > 1) ? s_w[1] : INF, b0 = INF, b1 = INF;
+        auto sg = [](uint32_t v) -> uint32_t { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); };
+        uint32_t ia = 0, ib = 0, nint = 0;                    // heads: leaf ia, internal node ib; nodes created
+        uint32_t a0 = sg(s_w[0]), a1 = sg(s_w[1]), b0 = INF, b1 = INF;
+        uint32_t va2 = s_w[2], va3 = s_w[3], vb2 = INF, vb3 = INF;      // entries 2 and 3 behind the heads (vector side)
+#pragma unroll 1
         for (uint32_t step = 0; step + 1 < m; step++) {
-            uint32_t p0, p1, w;
-            if (a0 <= b0) {                       // first pick: leaf (a leaf wins ties)
-                if (a1 <= b0) {                   // second pick: leaf
-                    p0 = ia; p1 = ia + 1; w = a0 + a1; ia += 2;
-                    a0 = (ia < m) ? s_w[ia] : INF; a1 = (ia + 1 < m) ? s_w[ia + 1] : INF;
-                } else {                          // second pick: internal node
-                    p0 = ia; p1 = ib; w = a0 + b0; ia += 1; ib += 1;
-                    a0 = a1; a1 = (ia + 1 < m) ? s_w[ia + 1] : INF;
-                    b0 = b1; b1 = (ib + 1 < nb) ? s_w[ib + 1] : INF;
-                }
-            } else {                              // first pick: internal node
-                if (a0 <= b1) {                   // second pick: leaf
-                    p0 = ib; p1 = ia; w = b0 + a0; ia += 1; ib += 1;
-                    a0 = a1; a1 = (ia + 1 < m) ? s_w[ia + 1] : INF;
-                    b0 = b1; b1 = (ib + 1 < nb) ? s_w[ib + 1] : INF;
-                } else {                          // second pick: internal node
-                    p0 = ib; p1 = ib + 1; w = b0 + b1; ib += 2;
-                    b0 = (ib < nb) ? s_w[ib] : INF; b1 = (ib + 1 < nb) ? s_w[ib + 1] : INF;
-                }
+            const uint16_t node = (uint16_t)(m + nint);
+            uint32_t w;
+            if (a0 <= b0 && a1 <= b0) {                       // two leaves (a leaf wins ties)
+                w = a0 + a1;
+                s_par[ia] = node; s_par[ia + 1] = node; ia += 2;
+                a0 = sg(va2); a1 = sg(va3);
+            } else if (a0 > b0 && a0 > b1) {                  // two internal nodes
+                w = b0 + b1;
+                s_par[m + ib] = node; s_par[m + ib + 1] = node; ib += 2;
+                b0 = sg(vb2); b1 = sg(vb3);
+            } else {                                          // one of each
+                w = a0 + b0;
+                s_par[ia] = node; s_par[m + ib] = node; ia += 1; ib += 1;
+                a0 = a1; a1 = sg(va2);
+                b0 = b1; b1 = sg(vb2);
             }
-            s_w[nb] = w; s_par[p0] = (uint16_t)nb; s_par[p1] = (uint16_t)nb;
-            if (ib == nb) b0 = w; else if (ib + 1 == nb) b1 = w;   // the new node may be a queue head
-            nb++;
+            s_int[nint] = w;
+            if (nint == ib) b0 = w; else if (nint == ib + 1) b1 = w;   // the new node is a queue head already
+            nint++;
+            va2 = s_w[ia + 2]; va3 = s_w[ia + 3];             // requested now, moved to scalars one step from now
+            vb2 = s_int[ib + 2]; vb3 = s_int[ib + 3];
         }
     }
     __syncthreads();
