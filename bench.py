@@ -193,8 +193,8 @@ def main():
     alg = {("compress", "stats"): 4.0 * n, ("compress", "encode"): 4.0 * n + stream_bytes,
            ("decompress", "decode"): 4.0 * n + stream_bytes,
            ("reduce", "stage_a"): stream_bytes + 2.0 * n,
-           ("reduce", "add_b"): peer_bytes + 2.0 * n + 4.0 * n,
-           ("reduce", "encode"): 4.0 * n + reduce_bytes}
+           ("reduce", "add_b"): peer_bytes + 2.0 * n + 2.0 * n,
+           ("reduce", "encode"): 2.0 * n + reduce_bytes}
     dom = max(alg, key=lambda k: kern[k[0]][k[1]])
     dom_ms = kern[dom[0]][dom[1]]
     achieved = alg[dom] / (dom_ms * 1e-3) / 1e9
