@@ -47,11 +47,11 @@ def make_workload(name):
     return dict(name=name, desc=desc, n=n, x=x, peer=peer, eb=float(np.float32(eb)), chunk=chunk)
 
 
-def cpu_baseline(wl):
+def cpu_baseline(wl, alphabet=256):
     """The oracle as it stands, single thread, on the whole headline message (about 10-15 s of CPU work)."""
     import oracle
     n = wl["n"]
-    o = oracle.make_opts(chunk_elems=wl["chunk"])
+    o = oracle.make_opts(chunk_elems=wl["chunk"], alphabet=alphabet)
     t0 = time.perf_counter()
     s, res, rc = oracle.compress(wl["x"], wl["eb"], o)
     t1 = time.perf_counter()
@@ -97,6 +97,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c2")
+    ap.add_argument("--alphabet", type=int, default=256, help="Huffman alphabet K (power of two, 2..1024)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rotate", type=int, default=3, help="number of distinct input copies cycled through")
     ap.add_argument("--only", default="", help="profiling aid: time only this stage (compress|decompress|reduce)")
@@ -117,7 +118,7 @@ def main():
     dev = torch.device("cuda:0")
     wl = make_workload(args.workload)
     n, eb = wl["n"], wl["eb"]
-    opts = nz.make_opts(chunk_elems=wl["chunk"])
+    opts = nz.make_opts(chunk_elems=wl["chunk"], alphabet=args.alphabet)
     sess = nz.Session(n, opts, dev, reduce=True)
 
     xs = [torch.from_numpy(wl["x"]).to(dev) for _ in range(max(1, args.rotate))]
@@ -205,7 +206,7 @@ def main():
     out = dict(metric="compress+decompress+fused-reduce throughput on fp32 input bytes", value=3 * gb / (ms_per_step * 1e-3),
                unit="GB/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step,
                higher_is_better=True, scaling="weak", vs_baseline=None, dtype="f32+i32", data="synthetic",
-               config=dict(workload=wl["desc"], n_elems=n, chunk_elems=wl["chunk"], alphabet=256, eb=eb),
+               config=dict(workload=wl["desc"], n_elems=n, chunk_elems=wl["chunk"], alphabet=args.alphabet, eb=eb),
                stages=dict(compress_GBps=gb / (stage_ms["compress"] * 1e-3),
                            decompress_GBps=gb / (stage_ms["decompress"] * 1e-3),
                            reduce_GBps=gb / (stage_ms["reduce"] * 1e-3),
@@ -217,7 +218,7 @@ def main():
                            kernel_ms=kern),
                roofline=roofline)
     if not args.no_cpu_baseline:
-        base, ref_stream, ref_reduced = cpu_baseline(wl)
+        base, ref_stream, ref_reduced = cpu_baseline(wl, args.alphabet)
         out["cpu_baseline"] = base
         got = outs[0][:stream_bytes].cpu().numpy()
         out["bytes_match_oracle"] = bool(got.size == ref_stream.size and (got == ref_stream).all())
