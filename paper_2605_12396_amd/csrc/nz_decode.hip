@@ -49,6 +49,8 @@ struct DecTables {
     uint16_t sorted[kMaxK];
     uint16_t sub_prefix[kMaxSub];
     uint32_t cnt[32], first[32], idx0[32];
+    __align__(16) uint32_t lim[32];            // lim[l]: end of the codes of length <= l, left-justified to 28 bits
+    int32_t base[32];                          // base[l] = idx0[l] - first[l]: sorted index = (code of length l) + base[l]
     uint32_t nsub;
 };
 
@@ -163,11 +165,15 @@ __device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t fra
         if (L) T->sorted[s_idx0[L] + B->rank[sy]] = (uint16_t)sy;
     }
     if (tid == 0) T->nsub = 0;
+    if (tid < 32) {
+        T->lim[tid] = (tid >= 1 && tid <= kMaxLen) ? ((s_first[tid] + s_cnt[tid]) << (kMaxLen - tid)) : 0u;
+        T->base[tid] = (int32_t)s_idx0[tid] - (int32_t)s_first[tid];
+    }
     __syncthreads();
     // Entry formats (16 bits).  First level, indexed by the next 11 stream bits:
     //   (q & 1023) | L<<10   symbol with quantization code q (10-bit two's complement) and an L <= 11 bit code
     //   0x8000 | L<<10       escape symbol with an L-bit code (32 raw bits follow)
-    //   0xC000 | id          no code of <= 11 bits starts here; id < kMaxSub: second-level table, else search
+    //   0xC000 | id          no code of <= 11 bits starts here; id < kMaxSub: second-level table, else range compare
     // Second level, indexed by stream bits 11..16: same with L-11 in place of L; 0xC000 = longer still.
     // Canonical codes left-justified to a common width are ordered by length, so the length of the code that
     // starts an entry's bits is found by comparing against the end of every length's range (no table walk).
@@ -366,18 +372,22 @@ struct HuffReader {
             if (id < kMaxSub) e2 = T->tab2[(id << kSubBits) + ((w32 >> kPrimaryBits) & ((1u << kSubBits) - 1u))];
             if (e2 < 0xC000u) {
                 L = kPrimaryBits + ((e2 >> 10) & 7u); q = (int32_t)(e2 << 22) >> 22; esc = (e2 >= 0x8000u);
-            } else {                                                     // longer than 17 bits or unassigned: search
-                uint32_t code = 0, sy = 1;
-                L = 0;
-#pragma unroll 1
-                for (uint32_t l = 1; l <= kMaxLen; l++) {
-                    uint32_t li = l;
-                    asm volatile("" : "+v"(li));                         // keeps the table reads inside this rare loop
-                    code = (code << 1) | ((w32 >> (l - 1)) & 1u);
-                    const uint32_t d = code - T->first[li];
-                    if (d < T->cnt[li]) { sy = T->sorted[T->idx0[li] + d]; L = l; break; }
-                }
-                if (L == 0) { bad = 1; L = 1; sy = 1; }
+            } else {
+                // Longer than 17 bits, unassigned, or no second-level table left: v = the next 28 stream bits as a
+                // number, first bit most significant.  Canonical codes left-justified to 28 bits are ordered by
+                // length, so the length is 12 + the number of lengths 12..27 whose range ends at or below v; the
+                // symbol follows from the canonical order.  All limits are read at once (no dependent loop).
+                uint32_t li = 0;
+                asm volatile("" : "+v"(li));                             // keeps the limit reads inside this rare path
+                const uint4* lp = reinterpret_cast<const uint4*>(T->lim + li);
+                const uint4 l3 = lp[3], l4 = lp[4], l5 = lp[5], l6 = lp[6], l7 = lp[7];     // lim[12..31]
+                const uint32_t v = __brev(w32) >> 4;
+                static_assert(kPrimaryBits == 11 && kMaxLen == 28, "limits 12..27 are compared below");
+                L = 12u + (v >= l3.x) + (v >= l3.y) + (v >= l3.z) + (v >= l3.w) + (v >= l4.x) + (v >= l4.y) + (v >= l4.z) + (v >= l4.w) +
+                    (v >= l5.x) + (v >= l5.y) + (v >= l5.z) + (v >= l5.w) + (v >= l6.x) + (v >= l6.y) + (v >= l6.z) + (v >= l6.w);
+                uint32_t sy = 1;
+                if (v >= l7.x) { bad = 1; L = 1; }                       // no code starts with these bits
+                else sy = T->sorted[(uint32_t)((int32_t)(v >> (kMaxLen - L)) + T->base[L])];
                 q = unzigzag(sy - 1u); esc = (sy == 0);
             }
         }
