@@ -61,7 +61,7 @@ def gaussian_random_field(N=512, seed=3, slope=-3.0):
     amp = k ** (slope / 2.0)
     amp[0, 0, 0] = 0.0
     F *= amp
-    f = np.fft.irfftn(F, s=(N, N, N))
+    f = np.fft.irfftn(F, s=(N, N, N), axes=(0, 1, 2))
     del F
     f -= f.mean()
     f /= f.std()

@@ -351,3 +351,80 @@ def test_seeded_sweep(nz, seed):
         assert r2["status"] == orc2
         if orc2 == 0:
             assert r2["bytes"] == ores2.bytes and _first_diff(got2, ref2) == -1
+
+
+# ------------------------------------------------------------------------------------------------
+# the remaining workload shapes (C3, C4, C5) at sizes the oracle finishes in seconds, and C2 at full size
+# ------------------------------------------------------------------------------------------------
+
+@pytest.mark.parametrize("rel", [1e-2, 1e-3, 1e-4])
+def test_c3_random_field_bound_sweep(nz, rel):
+    x = W.gaussian_random_field(N=64, seed=3)                      # 262144 elements, P(k) ~ k^-3, unit variance
+    eb = W.abs_bound_from_rel(x, rel)
+    ref, _ = check_compress(nz, x, eb, chunk_elems=65536)
+    check_decompress(nz, ref, x, eb, chunk_elems=65536)
+
+
+def test_c4_ring_step_chain_and_association_order(nz):
+    n, eb = 200000, 1e-5
+    g, o = _opts_pair(nz, chunk_elems=65536)
+    msgs = W.peer_messages(n, peers=8, seed0=40)
+    streams = [oracle.compress(m, eb, o)[0] for m in msgs]
+
+    def chain(order):
+        acc = streams[order[0]]
+        for p in order[1:]:
+            rc, r, acc = gpu_reduce(nz, acc, streams[p], n, eb, g)
+            assert rc == 0 and r["status"] == 0
+        return acc
+    a = chain(list(range(8)))
+    b = chain([7, 3, 0, 5, 1, 6, 2, 4])
+    acc_o = streams[0]
+    for p in range(1, 8):
+        acc_o = oracle.reduce_frames(acc_o, streams[p], n, eb, o)[0]
+    assert _first_diff(a, acc_o) == -1 and _first_diff(b, acc_o) == -1       # 7 steps, any order: identical bytes
+    rc, r, got = gpu_decompress(nz, a, n, eb, g)
+    true = sum(m.astype(np.float64) for m in msgs)
+    assert (np.abs(got.astype(np.float64) - true) <= 8 * float(np.float32(eb))).all()
+
+
+@pytest.mark.parametrize("kind", ["uniform", "laplace", "sinusoid"])
+@pytest.mark.parametrize("n", [16384, 65536, 262144, 1048576])
+def test_c5_size_sweep(nz, kind, n):
+    x = W.sweep_payload(kind, n, 50)
+    chunk = 16384 if 4 * n <= (4 << 20) else 262144
+    ref, _ = check_compress(nz, x, 1e-4, chunk_elems=chunk)
+    check_decompress(nz, ref, x, 1e-4, chunk_elems=chunk)
+
+
+def test_c2_full_size(nz):
+    """The headline message (64 Mi fp32, 1 MiB frames) in the configuration bench.py times: compressed stream,
+    decompressed values and the reduced stream against the oracle, whole message."""
+    import torch
+    n = 1 << 26
+    x = W.gradient_like(n, seed=2)
+    peer = W.gradient_like(n, seed=102)
+    eb = float(np.float32(W.abs_bound_from_rel(x, 1e-4)))
+    g, o = _opts_pair(nz, chunk_elems=262144)
+    sess = nz.Session(n, g, "cuda:0", reduce=True)
+    rc, out = sess.compress(torch.from_numpy(x).to("cuda:0"), eb)
+    r = sess.result()
+    ref, ores, orc = oracle.compress(x, eb, o)
+    assert rc == 0 and orc == 0 and r["status"] == 0 and r["bytes"] == ores.bytes
+    assert (r["n_raw"], r["n_fixed"], r["n_huff"]) == (ores.n_raw, ores.n_fixed, ores.n_huff)
+    assert _first_diff(out[:r["bytes"]].cpu().numpy(), ref) == -1
+    nbytes = r["bytes"]
+    rc, y = sess.decompress(out, nbytes, n, eb)
+    assert rc == 0 and sess.result()["status"] == 0
+    yo = oracle.decompress(ref, n, eb)[0]
+    y = y.cpu().numpy()
+    assert (y.view(np.uint32) == yo.view(np.uint32)).all()
+    assert float(np.max(np.abs(y.astype(np.float64) - x.astype(np.float64)))) <= float(np.float32(eb))
+    del y, yo
+    rc, pout = nz.Session(n, g, "cuda:0").compress(torch.from_numpy(peer).to("cuda:0"), eb)
+    pref = oracle.compress(peer, eb, o)[0]
+    rc, red = sess.reduce(out, nbytes, pout, pref.size, n, eb)
+    rr = sess.result()
+    ro, rres, rrc = oracle.reduce_frames(ref, pref, n, eb, o)
+    assert rc == 0 and rrc == 0 and rr["status"] == 0 and rr["bytes"] == rres.bytes
+    assert _first_diff(red[:rr["bytes"]].cpu().numpy(), ro) == -1
