@@ -187,6 +187,15 @@ def main():
             for j, t in enumerate(tr.kernel_ms()):
                 acc["reduce"][j] += t
     kern = {st: {nm: acc[st][j] / reps for j, nm in enumerate(names[st])} for st in names}
+    # what a plain streaming kernel reaches on this machine: elementwise copy of the message (4n read + 4n written)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.add(xs[0], 0.0, out=y)
+    ev0.record()
+    for i in range(5):
+        torch.add(xs[i % len(xs)], 0.0, out=y)
+    ev1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 2 * 4.0 * n / 1e9 / (ev0.elapsed_time(ev1) * 1e-3 / 5)
     stage_ms = {st: sum(kern[st].values()) for st in names}
     gb = 4.0 * n / 1e9
     cr = 4.0 * n / stream_bytes
@@ -213,6 +222,7 @@ def main():
                            compress_frac_hbm=gb / (stage_ms["compress"] * 1e-3) / HBM_PEAK_GBPS,
                            decompress_frac_hbm=gb / (stage_ms["decompress"] * 1e-3) / HBM_PEAK_GBPS,
                            reduce_frac_hbm=gb / (stage_ms["reduce"] * 1e-3) / HBM_PEAK_GBPS,
+                           copy_kernel_GBps=copy_gbps,
                            compression_ratio=cr, stream_bytes=stream_bytes, reduce_stream_bytes=reduce_bytes,
                            frames=dict(raw=r0["n_raw"], fixed=r0["n_fixed"], huffman=r0["n_huff"]),
                            kernel_ms=kern),
