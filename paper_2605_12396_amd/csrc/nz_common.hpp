@@ -55,10 +55,8 @@ static_assert(sizeof(FrameMeta) == 64, "FrameMeta is 64 bytes");
 
 // ---- control block at the start of the workspace (zeroed at the start of every call) ----
 struct Ctrl {
-    uint32_t ticket_book;   // dynamic workgroup ids: look-back only ever waits on smaller tickets
-    uint32_t unused_;
-    uint32_t frames_done;
-    uint32_t pad[13];
+    uint32_t ticket_book;   // frame ids handed to codebook workgroups in start order: the frame look-back only waits on smaller ones
+    uint32_t pad[15];
 };
 static_assert(sizeof(Ctrl) == 64, "Ctrl is 64 bytes");
 

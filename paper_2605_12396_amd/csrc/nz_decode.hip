@@ -39,7 +39,6 @@ __device__ inline uint32_t check_stream(const uint8_t* s, uint64_t bytes, const 
 
 // Shared memory of one operand's decoder.
 constexpr uint32_t kRun = 8;                   // symbols per run: window reloads happen at run starts only
-constexpr uint32_t kWinFreshBits = 193;        // bits a freshly loaded window offers before a lane must reload
 constexpr uint32_t kSubBits = 6;               // second-level tables resolve codes of 12..17 bits
 constexpr uint32_t kMaxSub = 32;               // at most this many second-level tables (the rest: canonical search)
 
@@ -62,7 +61,6 @@ struct FrameView {
     uint32_t nwords;
     const uint16_t* segt;
     uint64_t seg_prefix;      // bits before this workgroup's first segment
-    uint32_t cadence;         // HUFFMAN: runs of 8 symbols between two scheduled window reloads
 };
 
 // Build-time scratch shared by both operands.
@@ -90,7 +88,6 @@ __device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t fra
                                   const DecodeArgs& A, DecTables* T, BuildScratch* B, FrameView& V) {
     const uint32_t tid = threadIdx.x;
     V.status = ST_CORRUPT; V.kind = KIND_ZERO; V.w = 0; V.words = nullptr; V.nwords = 0; V.segt = nullptr; V.seg_prefix = 0;
-    V.cadence = 1;
     const uint64_t off = *reinterpret_cast<const uint64_t*>(s + kStreamHdr + 8ull * frame);
     if ((off & 15u) || off < kStreamHdr + pad16d(8ull * A.n_frames) || off + kHdrBytes > total) return;
     const uint8_t* fr = s + off;
@@ -221,21 +218,16 @@ __device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t fra
         }
     }
     __syncthreads();
-    {   // schedule reloads so that an average lane (with a 25 % margin) never needs one of its own
-        const uint32_t run_bits = (uint32_t)((all_bits * kRun) / nf) + 1u;
-        const uint32_t c = kWinFreshBits / (run_bits + run_bits / 4u);
-        V.cadence = c < 1u ? 1u : (c > 16u ? 16u : c);
-    }
     V.status = ST_OK; V.kind = KIND_HUFF; V.segt = segt; V.seg_prefix = pre_bits;
     V.words = reinterpret_cast<const uint32_t*>(pay + tables); V.nwords = (uint32_t)((payload - tables) / 4);
 }
 
 // Per-thread sequential reader of one HUFFMAN segment.  Every lane owns a small window (kWinWords words) in
-// LDS, filled from global memory with dword-aligned 16-byte loads starting at the word the lane is in.  Reloads
-// happen at the start of a run of 8 symbols, a point that is uniform over the wave: on a schedule derived from
-// the frame's average code length (so that the global-load stall is paid once for all lanes and few fetched
-// bytes go unused), and for a single lane when it is kWinRunLimit or more bits into its window; a lane also
-// reloads at once when a long code or an escape leaves it kWinSlowLimit or more bits into the window.
+// LDS, filled from global memory with dword-aligned 16-byte loads starting at the word the lane is in.  The
+// window is renewed at the start of every phase of 32 symbols (requested before the workgroup's output phase,
+// installed after it), and by a single lane at the start of a run of 8 symbols when it is kWinRunLimit or more
+// bits into its window; a lane also reloads at once when a long code or an escape leaves it kWinSlowLimit or
+// more bits into the window.
 // Window words k and k+1 of the current position live in registers (lo, hi), so the next 32 stream bits are a
 // funnel shift away and the only LDS access on a symbol's critical path is the table lookup; words k+2 and k+3
 // are re-read from the window after every symbol and are back long before a later symbol shifts them in.
@@ -251,7 +243,6 @@ constexpr uint32_t kWinBits = 32 * kWinWords;
 // before the next check, and the escape's raw word is read there: kWinSlowLimit + 77 + 28 < kWinBits - 32.
 constexpr uint32_t kWinSlowLimit = kWinBits - 32 - 77 - 28 - 7;      // 240 for 12 words
 constexpr uint32_t kWinRunLimit = kWinSlowLimit - 16;                // reload at a run start when this far in
-static_assert(kWinRunLimit - 31 == kWinFreshBits, "cadence constant out of step with the window size");
 constexpr uint32_t kWinOverRows = 2;                                 // rows a prefetch may reach past the window
 
 template <int NT>
@@ -529,7 +520,7 @@ struct AddCtx {
 // which leaves kWideMarker in the tile and raises a workgroup flag; only then does the consumer look for
 // markers.
 template <int MODE, int NT>
-__device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader<NT>& ra, DecShared<NT>* S, uint32_t ca,
+__device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader<NT>& ra, DecShared<NT>* S,
                                 const AddCtx& X, bool a_wide, uint32_t (&zmax)[2], uint32_t& overflow) {
     const uint32_t tid = C.tid;
     uint16_t* tile = S->u.tile;
@@ -733,7 +724,6 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
 
     FrameView V;
     V.status = ST_OK; V.kind = KIND_ZERO; V.w = 0; V.words = nullptr; V.nwords = 0; V.segt = nullptr; V.seg_prefix = 0;
-    V.cadence = 1;
     if (st_a == ST_OK && st_b == ST_OK) {
         open_frame<NT>(MODE == MODE_ADD_B ? A.b : A.a, MODE == MODE_ADD_B ? total_b : total_a, frame, nf, first_seg, A,
                        &s_t, &S.u.build, V);
@@ -789,7 +779,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
     }
 
     if (V.kind == KIND_HUFF) {
-        run_huff<MODE, NT>(A, C, ra, &S, V.cadence, X, a_wide, zmax, overflow);
+        run_huff<MODE, NT>(A, C, ra, &S, X, a_wide, zmax, overflow);
         if (seg_valid && (ra.bad || ra.consumed() != seglen)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
     } else {
         run_elementwise<MODE, NT>(A, C, da, &S, X, zmax, overflow);
