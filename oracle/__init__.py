@@ -61,6 +61,7 @@ def lib():
         L.nzo_decompress.argtypes = [vp, sz, vp, sz, f32, C.POINTER(Result)]
         L.nzo_decode_codes.argtypes = [vp, sz, sz, f32, vp, vp, vp, C.POINTER(Result)]
         L.nzo_reduce_frames.argtypes = [vp, sz, vp, sz, vp, sz, sz, f32, C.POINTER(Opts), C.POINTER(Result)]
+        L.nzo_reduce_local.argtypes = [vp, sz, vp, vp, sz, sz, f32, C.POINTER(Opts), C.POINTER(Result)]
         L.nzo_frame_plan.argtypes = [vp, C.c_uint32, C.c_int, C.POINTER(Opts), vp, vp, vp, vp, vp, vp, vp]
         L.nzo_frame_encode.argtypes = [vp, vp, C.c_uint32, C.c_int, C.POINTER(Opts), C.c_uint32, vp, sz]
         L.nzo_frame_encode.restype = C.c_int64
@@ -164,6 +165,20 @@ def reduce_frames(a, b, n, eb, opts=None, cap=None):
     res = Result()
     rc = lib().nzo_reduce_frames(_ptr(a), a.size, _ptr(b), b.size, _ptr(out), cap, n, C.c_float(eb),
                                  C.byref(opts) if opts is not None else None, C.byref(res))
+    return out[:res.bytes].copy(), res, rc
+
+
+def reduce_local(a, x, eb, opts=None, cap=None):
+    """Ring-step reduce: incoming stream `a` plus the rank's own fp32 message `x` (quantized, never entropy coded)."""
+    a = np.ascontiguousarray(a, dtype=np.uint8)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    n = x.size
+    if cap is None:
+        cap = compress_bound(n, opts)
+    out = np.zeros(max(cap, 1), np.uint8)
+    res = Result()
+    rc = lib().nzo_reduce_local(_ptr(a), a.size, _ptr(x), _ptr(out), cap, n, C.c_float(eb),
+                                C.byref(opts) if opts is not None else None, C.byref(res))
     return out[:res.bytes].copy(), res, rc
 
 

@@ -28,7 +28,8 @@
  * Pins (tests/test_oracle_pins.py and friends): error bound in float64, worked
  * quantizer values, brute-force optimal prefix-code cost, Kraft equality,
  * closed-form code lengths, independent numpy bit-unpack, exhaustive selector,
- * header-mutation rejection, reduce == encode(qa+qb).
+ * header-mutation rejection, reduce == encode(qa+qb), ring-step reduce ==
+ * encode(q_incoming + quantize(local)) and == reduce with the coded local message.
  * Parity unpinned: the paper prints no bitstream, no worked example and no
  * compression ratio reachable without its datasets, so nothing here is pinned
  * against a number printed in the paper.
@@ -773,6 +774,64 @@ int nzo_reduce_frames(const uint8_t* a, size_t a_bytes, const uint8_t* b, size_t
     if (!rc) rc = nzo_decode_codes(a, a_bytes, n, eb, qa, ra, fa, NULL);
     if (!rc) rc = nzo_decode_codes(b, b_bytes, n, eb, qb, rb, fb, NULL);
     if (!rc) {
+        reduce_ctx c = { qa, qb, ra, rb, fa, fb, step, 0 };
+        rc = emit_stream(reduce_src, &c, n, &o, f32_bits(step), out, cap, res);
+        if (c.overflow) {                       /* RANGE outranks CAPACITY; nothing is published */
+            rc = NZO_ERR_RANGE;
+            uint32_t nfr = res->n_frames;
+            memset(res, 0, sizeof *res);
+            res->n_frames = nfr; res->status = NZO_ERR_RANGE;
+        }
+    } else {
+        res->status = (uint32_t)rc;
+    }
+    free(qa); free(qb); free(ra); free(rb); free(fa); free(fb);
+    return rc;
+}
+
+/* ------------------------------------------------------------------ */
+/* 8b. ring-step reduce: incoming frames + the rank's own fp32 data     */
+/*     (the receive-reduce-send step of Sec. IV-D "In-Primitive         */
+/*     Overlap": the local contribution is quantized at the interface,  */
+/*     Sec. IV-B, and never entropy coded before it is added)           */
+/* ------------------------------------------------------------------ */
+
+/*
+ * out = incoming (+) local.  The local message is quantized frame by frame exactly as nzo_compress would
+ * quantize it (one unquantizable element makes its frame "raw": the original fp32 words stand for it), and
+ * then takes the place of operand B of nzo_reduce_frames: both coded -> exact integer sum of the codes,
+ * re-planned and re-selected; incoming frame RAW or local frame raw -> RAW frame of fp32 sums of the
+ * (dequantized or raw) values.  |Q| > 2^30 in a coded frame -> NZO_ERR_RANGE.
+ */
+int nzo_reduce_local(const uint8_t* in, size_t in_bytes, const float* local, uint8_t* out, size_t cap,
+                     size_t n, float eb, const nzo_opts* opts, nzo_result* res) {
+    nzo_opts o; stream_hdr hi; float step, inv;
+    nzo_result dummy;
+    if (!res) res = &dummy;
+    memset(res, 0, sizeof *res);
+    if (n == 0 || !in || !local || !out) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
+    if (resolve_opts(opts, &o) || nzo_step_constants(eb, &step, &inv)) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
+    int rc = parse_stream(in, in_bytes, &hi);
+    if (rc) { res->status = (uint32_t)rc; return rc; }
+    if (hi.n != n || hi.chunk != o.chunk_elems || hi.step_bits != f32_bits(step)) { res->status = NZO_ERR_MISMATCH; return NZO_ERR_MISMATCH; }
+    int32_t* qa = (int32_t*)malloc(4ull * n); int32_t* qb = (int32_t*)malloc(4ull * n);
+    uint32_t* ra = (uint32_t*)malloc(4ull * n); uint32_t* rb = (uint32_t*)malloc(4ull * n);
+    uint8_t* fa = (uint8_t*)calloc(hi.n_frames, 1); uint8_t* fb = (uint8_t*)calloc(hi.n_frames, 1);
+    if (!qa || !qb || !ra || !rb || !fa || !fb) rc = NZO_ERR_INVALID;
+    if (!rc) rc = nzo_decode_codes(in, in_bytes, n, eb, qa, ra, fa, NULL);
+    if (!rc) {
+        /* the local message, frame by frame: codes, original words, and the per-frame "raw" flag */
+        for (uint32_t k = 0; k < hi.n_frames; k++) {
+            const uint64_t i0 = (uint64_t)k * o.chunk_elems;
+            const uint64_t i1 = (i0 + o.chunk_elems < n) ? i0 + o.chunk_elems : n;
+            int all_ok = 1;
+            for (uint64_t i = i0; i < i1; i++) {
+                int32_t v = 0;
+                if (!nzo_quantize_one(local[i], eb, step, inv, &v)) all_ok = 0;
+                qb[i] = v; rb[i] = f32_bits(local[i]);
+            }
+            fb[k] = all_ok ? 0 : 1;
+        }
         reduce_ctx c = { qa, qb, ra, rb, fa, fb, step, 0 };
         rc = emit_stream(reduce_src, &c, n, &o, f32_bits(step), out, cap, res);
         if (c.overflow) {                       /* RANGE outranks CAPACITY; nothing is published */

@@ -630,3 +630,90 @@ def test_laplace_bits_per_symbol_within_entropy_bounds():
     plan = oracle.frame_plan(oracle.quantize(x, eb)[0], oracle.make_opts(chunk_elems=n))
     bps = plan["huff_bits"] / n
     assert H - 0.05 <= bps < H + 1.0
+
+
+# ------------------------------------------------------------------------------------------------
+# ring-step reduce (incoming frames + the rank's own fp32 data; Sec. IV-D "In-Primitive Overlap")
+# ------------------------------------------------------------------------------------------------
+
+def test_reduce_local_is_exact_integer_sum_with_the_interface_quantizer():
+    n, eb = 20000, 1e-5
+    opts = oracle.make_opts(chunk_elems=4096)
+    msgs = W.peer_messages(n, peers=3, seed0=60)
+    qs = [oracle.quantize(m, eb)[0] for m in msgs]
+    acc = oracle.compress(msgs[0], eb, opts)[0]
+    for p in (1, 2):
+        acc, res, rc = oracle.reduce_local(acc, msgs[p], eb, opts)
+        assert rc == 0 and res.n_raw == 0
+    qd, _, kinds, _, _ = oracle.decode_codes(acc, n, eb)
+    assert (kinds == 0).all() and (qd == qs[0] + qs[1] + qs[2]).all()            # codes add exactly
+    # the frames are the selector's frames of the summed codes (nothing else went into them)
+    Q = qs[0] + qs[1] + qs[2]
+    step_bits = int(np.float32(oracle.step_constants(eb)[0]).view(np.uint32))
+    offs = acc[64:64 + 8 * 5].view(np.uint64).astype(np.int64)
+    for k in range(5):
+        qf = Q[k * 4096:(k + 1) * 4096]
+        plan = oracle.frame_plan(qf, opts)
+        fr = oracle.frame_encode(qf, plan["codec"], opts, step_bits=step_bits)
+        assert (acc[offs[k]:offs[k] + fr.size] == fr).all()
+    out, _, _ = oracle.decompress(acc, n, eb)
+    true = sum(m.astype(np.float64) for m in msgs)
+    assert (np.abs(out.astype(np.float64) - true) <= 3 * float(np.float32(eb))).all()   # P * eb, P = 3
+
+
+def test_reduce_local_equals_reducing_with_the_compressed_local_message():
+    """Entropy coding is lossless, so coding the local message first and reducing two streams must give the same
+    bytes as adding the quantized local data directly -- for coded, raw and mixed frames and for pinned codecs."""
+    rng = np.random.default_rng(5)
+    for case in range(6):
+        n = int(rng.choice([1, 999, 4096, 10001]))
+        eb = float(rng.choice([1e-3, 1e-4]))
+        kw = dict(chunk_elems=int(rng.choice([16, 1000, 4096])), alphabet=int(rng.choice([16, 256])))
+        if case == 4:
+            kw["force_codec"] = 1
+        opts = oracle.make_opts(**kw)
+        a, x = W.gradient_like(n, seed=200 + case), W.gradient_like(n, seed=300 + case)
+        if case in (1, 3):
+            a[rng.integers(0, n)] = np.inf          # incoming frame RAW
+        if case in (2, 3):
+            x[rng.integers(0, n)] = np.nan          # local frame raw
+        sa = oracle.compress(a, eb, opts)[0]
+        direct, r1, rc1 = oracle.reduce_local(sa, x, eb, opts)
+        via, r2, rc2 = oracle.reduce_frames(sa, oracle.compress(x, eb, opts)[0], n, eb, opts)
+        assert rc1 == 0 and rc2 == 0 and direct.size == via.size and (direct == via).all()
+        assert (r1.n_raw, r1.n_fixed, r1.n_huff) == (r2.n_raw, r2.n_fixed, r2.n_huff)
+
+
+def test_reduce_local_raw_values_range_and_mismatch():
+    n, eb = 3000, 1e-3
+    opts = oracle.make_opts(chunk_elems=1000)
+    a, x = W.gradient_like(n, seed=72), W.gradient_like(n, seed=73)
+    a[1500] = np.nan                               # frame 1 of the incoming stream is RAW
+    x[2500] = 3e38                                 # frame 2 of the local message cannot be quantized
+    sa = oracle.compress(a, eb, opts)[0]
+    r, res, rc = oracle.reduce_local(sa, x, eb, opts)
+    assert rc == 0 and res.n_raw == 2
+    out = oracle.decompress(r, n, eb)[0]
+    da = oracle.decompress(sa, n, eb)[0]
+    step, _ = oracle.step_constants(eb)
+    qx = oracle.quantize(x, eb)[0]
+    with np.errstate(invalid="ignore", over="ignore"):
+        e1 = (da[1000:2000] + (qx[1000:2000].astype(np.float32) * np.float32(step))).astype(np.float32)   # raw + dequantized local
+        e2 = (da[2000:] + x[2000:]).astype(np.float32)                                                    # dequantized + raw local
+    for got, exp in ((out[1000:2000], e1), (out[2000:], e2)):
+        eb_ = exp.view(np.uint32).copy(); eb_[np.isnan(exp)] = 0x7FC00000
+        assert (got.view(np.uint32) == eb_).all()
+    # a local message quantized at another bound, or of another length, does not match the stream
+    assert oracle.reduce_local(sa, x, 2e-3, opts)[2] == oracle.ERR_MISMATCH
+    assert oracle.reduce_local(sa, x[:-1], eb, opts)[2] == oracle.ERR_MISMATCH
+    # range: codes near 2^30 plus a local code that passes it
+    z = np.zeros(1000, np.float32); z[7] = np.float32(32767.0) * np.float32(step)
+    o1 = oracle.make_opts(chunk_elems=1000)
+    s = oracle.compress(z, eb, o1)[0]
+    for _ in range(15):
+        s = oracle.reduce_frames(s, s, 1000, eb, o1)[0]
+    s1, _, rc = oracle.reduce_local(s, z, eb, o1)                # 32767 * 2^15 + 32767 = 2^30 - 1: still carried
+    assert rc == 0 and oracle.decode_codes(s1, 1000, eb)[0][7] == (1 << 30) - 1
+    assert oracle.reduce_local(s1, z, eb, o1)[2] == oracle.ERR_RANGE
+    z2 = z.copy(); z2[7] = -z[7]
+    assert oracle.reduce_local(s1, z2, eb, o1)[2] == 0
