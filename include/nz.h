@@ -41,7 +41,7 @@ typedef enum {
     NZ_OK           = 0,
     NZ_ERR_INVALID  = 1,   /* bad argument (n = 0, eb out of range, misaligned pointer, bad opts)        */
     NZ_ERR_CAPACITY = 2,   /* output does not fit out_cap: nothing is published (Algorithm 1 returns 0) */
-    NZ_ERR_RANGE    = 3,   /* nz_reduce_frames: an integer sum exceeded 2^30 in magnitude               */
+    NZ_ERR_RANGE    = 3,   /* reduce: an integer sum exceeded 2^30 in magnitude                         */
     NZ_ERR_CORRUPT  = 4,   /* a stream or frame failed validation (Algorithm 2, ValidateHeader)         */
     NZ_ERR_MISMATCH = 5,   /* n, frame size, alphabet or quantization step differ from the stream's     */
     NZ_ERR_HIP      = 6    /* a HIP launch failed (host return value only)                              */
@@ -121,6 +121,22 @@ nz_status nz_decompress(const void* d_stream, size_t stream_bytes, float* d_out,
 nz_status nz_reduce_frames(const void* d_a, size_t a_bytes, const void* d_b, size_t b_bytes, void* d_out,
                            size_t out_cap, size_t n, float eb, nz_result* d_res, const nz_opts* opts,
                            void* d_ws, size_t ws_bytes, void* stream);
+
+/*
+ * Ring-step reduce (the receive-reduce-send step of Sec. IV-D "In-Primitive
+ * Overlap"): out = incoming stream (+) the rank's own fp32 data d_local[0..n).
+ * The local data is quantized exactly as nz_compress would quantize it (Sec.
+ * IV-B) but is never entropy coded; the result is byte-identical to
+ * nz_reduce_frames(d_in, nz_compress(d_local)).  A local frame holding an
+ * element that cannot be quantized counts as RAW: the output frame is RAW and
+ * holds incoming value + original local value.  d_in is an NZ stream made with
+ * the same n, eb and opts; d_local is device memory, 16-byte aligned; the
+ * workspace is that of nz_reduce_frames (nz_reduce_workspace_bytes).  Errors as
+ * for nz_reduce_frames.
+ */
+nz_status nz_reduce_local(const void* d_in, size_t in_bytes, const float* d_local, void* d_out, size_t out_cap,
+                          size_t n, float eb, nz_result* d_res, const nz_opts* opts, void* d_ws, size_t ws_bytes,
+                          void* stream);
 
 /*
  * Profiling aid for benchmarks (not part of the paper's path).  While armed for the calling thread, every

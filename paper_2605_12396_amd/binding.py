@@ -51,6 +51,8 @@ def lib():
         L.nz_decompress.restype = C.c_int
         L.nz_reduce_frames.argtypes = [vp, sz, vp, sz, vp, sz, sz, f32, vp, po, vp, sz, vp]
         L.nz_reduce_frames.restype = C.c_int
+        L.nz_reduce_local.argtypes = [vp, sz, vp, vp, sz, sz, f32, vp, po, vp, sz, vp]
+        L.nz_reduce_local.restype = C.c_int
         L.nz_trace_events.argtypes = [C.POINTER(C.c_void_p), sz]
         L.nz_trace_events.restype = None
         L.nz_trace_recorded.restype = sz
@@ -97,6 +99,12 @@ def nz_reduce_frames(d_a, a_bytes, d_b, b_bytes, d_out, out_cap, n, eb, d_res, o
                                       _stream(stream)))
 
 
+def nz_reduce_local(d_in, in_bytes, d_local, d_out, out_cap, n, eb, d_res, opts, d_ws, ws_bytes, stream=None):
+    return int(lib().nz_reduce_local(d_in.data_ptr(), in_bytes, d_local.data_ptr(), d_out.data_ptr(), out_cap, n,
+                                     C.c_float(eb), d_res.data_ptr(), _po(opts), d_ws.data_ptr(), ws_bytes,
+                                     _stream(stream)))
+
+
 def read_result(d_res):
     """Copy the device result record to the host (synchronises) and unpack it."""
     import struct
@@ -136,6 +144,12 @@ class Session:
         out = out if out is not None else self.new_stream_buffer()
         rc = nz_reduce_frames(a, a_bytes, b, b_bytes, out, self.cap if cap is None else cap, n, eb, self.res,
                               self.opts, self.ws, self.ws_bytes)
+        return rc, out
+
+    def reduce_local(self, a, a_bytes, x, n, eb, out=None, cap=None):
+        out = out if out is not None else self.new_stream_buffer()
+        rc = nz_reduce_local(a, a_bytes, x, out, self.cap if cap is None else cap, n, eb, self.res,
+                             self.opts, self.ws, self.ws_bytes)
         return rc, out
 
     def result(self):

@@ -143,7 +143,7 @@ nz_status nz_decompress(const void* d_stream, size_t stream_bytes, float* d_out,
     const uint32_t nfr = (uint32_t)((n + o.chunk - 1) / o.chunk);
     DecodeArgs A;
     A.a = reinterpret_cast<const uint8_t*>(d_stream); A.a_bytes = stream_bytes; A.b = nullptr; A.b_bytes = 0;
-    A.out = d_out; A.n = n; A.chunk = o.chunk; A.n_frames = nfr; A.K = o.K;
+    A.out = d_out; A.local = nullptr; A.eb = eb; A.inv_step = 0.0f; A.n = n; A.chunk = o.chunk; A.n_frames = nfr; A.K = o.K;
     A.dbpf = (o.chunk + kDecBlock - 1) / kDecBlock;
     A.step = step; A.step_bits = bits_of(step); A.ws = nullptr; A.L = WsLayout(); A.res = d_res;
     trace_reset(); trace_mark(st);
@@ -154,15 +154,17 @@ nz_status nz_decompress(const void* d_stream, size_t stream_bytes, float* d_out,
     return NZ_OK;
 }
 
-nz_status nz_reduce_frames(const void* d_a, size_t a_bytes, const void* d_b, size_t b_bytes, void* d_out,
-                           size_t out_cap, size_t n, float eb, nz_result* d_res, const nz_opts* opts,
-                           void* d_ws, size_t ws_bytes, void* stream) {
+// The two reduce entry points differ only in the second operand: a stream (d_b) or the rank's own fp32 data (d_local).
+static nz_status reduce_impl(const void* d_a, size_t a_bytes, const void* d_b, size_t b_bytes, const float* d_local,
+                             void* d_out, size_t out_cap, size_t n, float eb, nz_result* d_res, const nz_opts* opts,
+                             void* d_ws, size_t ws_bytes, void* stream) {
     Opts o; float step, inv;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    if (!d_a || !d_b || !d_out || !d_res || !d_ws || !resolve(opts, o) || !geometry_ok(n, o) ||
+    const void* second = d_local ? static_cast<const void*>(d_local) : d_b;
+    if (!d_a || !second || !d_out || !d_res || !d_ws || !resolve(opts, o) || !geometry_ok(n, o) ||
         !step_constants(eb, step, inv))
         return NZ_ERR_INVALID;
-    if (!aligned16(d_a) || !aligned16(d_b) || !aligned16(d_out) || !aligned16(d_ws) || !aligned16(d_res))
+    if (!aligned16(d_a) || !aligned16(second) || !aligned16(d_out) || !aligned16(d_ws) || !aligned16(d_res))
         return NZ_ERR_INVALID;
     const WsLayout L = ws_layout(n, o.chunk, kDecBlock, true);
     if (ws_bytes < L.total) return NZ_ERR_INVALID;
@@ -175,7 +177,8 @@ nz_status nz_reduce_frames(const void* d_a, size_t a_bytes, const void* d_b, siz
     DecodeArgs D;
     D.a = reinterpret_cast<const uint8_t*>(d_a); D.a_bytes = a_bytes;
     D.b = reinterpret_cast<const uint8_t*>(d_b); D.b_bytes = b_bytes;
-    D.out = nullptr; D.n = n; D.chunk = o.chunk; D.n_frames = nfr; D.K = o.K;
+    D.out = nullptr; D.local = d_local; D.eb = eb; D.inv_step = inv;
+    D.n = n; D.chunk = o.chunk; D.n_frames = nfr; D.K = o.K;
     D.dbpf = (o.chunk + kDecBlock - 1) / kDecBlock;
     D.step = step; D.step_bits = bits_of(step); D.ws = ws; D.L = L; D.res = d_res;
     CompressArgs A;
@@ -187,15 +190,35 @@ nz_status nz_reduce_frames(const void* d_a, size_t a_bytes, const void* d_b, siz
     trace_reset(); trace_mark(st);
     if (launch_init(ws + L.ctrl, L.zero_end - L.ctrl, d_res, nfr, NZ_OK, st) != hipSuccess) return NZ_ERR_HIP;
     trace_mark(st);
-    if (launch_decode(D, 1, st) != hipSuccess) return NZ_ERR_HIP;
-    trace_mark(st);
-    if (launch_decode(D, 2, st) != hipSuccess) return NZ_ERR_HIP;
-    trace_mark(st);
+    if (d_local) {
+        if (launch_decode(D, 3, st) != hipSuccess) return NZ_ERR_HIP;       // decode incoming + quantize local + add
+        trace_mark(st);
+        if (launch_fix_local(D, st) != hipSuccess) return NZ_ERR_HIP;       // frames the local data turns RAW; range error
+        trace_mark(st);
+    } else {
+        if (launch_decode(D, 1, st) != hipSuccess) return NZ_ERR_HIP;       // stage operand A
+        trace_mark(st);
+        if (launch_decode(D, 2, st) != hipSuccess) return NZ_ERR_HIP;       // decode operand B + add
+        trace_mark(st);
+    }
     if (launch_codebook(A, st) != hipSuccess) return NZ_ERR_HIP;
     trace_mark(st);
     if (launch_encode(A, true, st) != hipSuccess) return NZ_ERR_HIP;
     trace_mark(st);
     return NZ_OK;
+}
+
+nz_status nz_reduce_frames(const void* d_a, size_t a_bytes, const void* d_b, size_t b_bytes, void* d_out,
+                           size_t out_cap, size_t n, float eb, nz_result* d_res, const nz_opts* opts,
+                           void* d_ws, size_t ws_bytes, void* stream) {
+    return reduce_impl(d_a, a_bytes, d_b, b_bytes, nullptr, d_out, out_cap, n, eb, d_res, opts, d_ws, ws_bytes, stream);
+}
+
+nz_status nz_reduce_local(const void* d_in, size_t in_bytes, const float* d_local, void* d_out, size_t out_cap,
+                          size_t n, float eb, nz_result* d_res, const nz_opts* opts, void* d_ws, size_t ws_bytes,
+                          void* stream) {
+    if (!d_local) return NZ_ERR_INVALID;
+    return reduce_impl(d_in, in_bytes, nullptr, 0, d_local, d_out, out_cap, n, eb, d_res, opts, d_ws, ws_bytes, stream);
 }
 
 }  // extern "C"

@@ -193,6 +193,8 @@ struct DecodeArgs {
     const uint8_t* a; uint64_t a_bytes;
     const uint8_t* b; uint64_t b_bytes;       // second operand (reduce only)
     float* out;                               // decompress only
+    const float* local;                       // ring-step reduce only: the rank's own fp32 message
+    float eb, inv_step;                       // ring-step reduce only: the quantizer's bound and 1/step
     uint64_t n;
     uint32_t chunk, n_frames, K, dbpf;
     float step; uint32_t step_bits;
@@ -204,6 +206,7 @@ hipError_t launch_init(void* zero_base, size_t zero_bytes, void* res, uint32_t n
 hipError_t launch_stats(const CompressArgs& A, hipStream_t st);
 hipError_t launch_codebook(const CompressArgs& A, hipStream_t st);
 hipError_t launch_encode(const CompressArgs& A, bool from_codes, hipStream_t st);
-hipError_t launch_decode(const DecodeArgs& A, int pass, hipStream_t st);   // 0 decompress, 1 / 2 reduce passes
+hipError_t launch_decode(const DecodeArgs& A, int pass, hipStream_t st);   // 0 decompress, 1 / 2 reduce passes, 3 ring-step add
+hipError_t launch_fix_local(const DecodeArgs& A, hipStream_t st);
 
 }  // namespace nz

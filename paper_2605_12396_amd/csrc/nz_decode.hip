@@ -423,7 +423,9 @@ constexpr uint32_t kTile16Stride = kTile16R + 2;     // halfwords per row: 17 wo
 constexpr int32_t kWideMarker = -32768;              // "this code does not fit 16 bits"
 constexpr uint32_t kHalf = 65536;                    // statistics granularity of the reduce (one encoder group)
 
-enum : int { MODE_DECOMPRESS = 0, MODE_STAGE_A = 1, MODE_ADD_B = 2 };
+enum : int { MODE_DECOMPRESS = 0, MODE_STAGE_A = 1, MODE_ADD_B = 2, MODE_ADD_LOCAL = 3 };
+// the two adding passes: ADD_B adds the staged codes of operand A, ADD_LOCAL the rank's own fp32 data, quantized on the fly
+#define NZ_ADDS(M) ((M) == MODE_ADD_B || (M) == MODE_ADD_LOCAL)
 
 // Shared memory of one decode workgroup.  The window comes first and the tile follows it directly: a reader's
 // prefetch may touch up to kWinOverRows rows past its window, which then fall into the tile (valid shared
@@ -433,7 +435,7 @@ struct __align__(16) DecShared {
     uint32_t win[NT * kWinWords];
     union { uint16_t tile[NT * kTile16Stride]; BuildScratch build; } u;
     uint64_t wsum[NT / 64];
-    uint32_t zmax[2], flags, cwide[2];
+    uint32_t zmax[2], flags, cwide[2], lunq[2], ovf;
 };
 
 struct SegCtx {
@@ -492,15 +494,23 @@ static_assert(kTile16R == 32 && kSeg == 256, "at16 assumes 8 phases of 32 symbol
 // The sums are staged for the encoder as 16-bit codes in c16 (message order), kWideMarker where a sum needs 32
 // bits, which then sits in codes; a frame with a RAW operand keeps its fp32 sums in codes.  wide[h] is raised when
 // half h of the workgroup's block holds a marker.
+// In the ring-step pass the other operand is the rank's own fp32 message (`local`), quantized here; an element
+// that cannot be quantized counts as code 0 and raises lunq[h]: its frame becomes RAW and is redone by k_fix_local.
 struct AddCtx {
-    StageA sa; uint32_t* codes; int16_t* c16; uint32_t* s_h; uint32_t* s_cwide;
+    StageA sa; uint32_t* codes; int16_t* c16; uint32_t* s_h; uint32_t* s_cwide; uint32_t* s_lunq;
+    const float* local; float eb, inv;
     uint32_t ncs, copy, K; float step; bool a_raw, b_raw;
     __device__ inline void finish(const SegCtx& C, uint32_t i, uint32_t tb, uint32_t (&zmax)[2], uint32_t& overflow) const {
         const uint64_t g = C.f0 + i;
-        const uint32_t ta = sa.get(C.f0, C.nf, i, a_raw);
+        const uint32_t h = (i - C.blk0) >> 16;
+        uint32_t ta;
+        if (local) {
+            int32_t q;
+            if (!quantize1(local[g], eb, step, inv, q)) s_lunq[h] = 1u;
+            ta = (uint32_t)q;
+        } else ta = sa.get(C.f0, C.nf, i, a_raw);
         if (a_raw || b_raw) { codes[g] = combine<true>(ta, a_raw, tb, b_raw, step, overflow); return; }
         const uint32_t t = combine<false>(ta, false, tb, false, step, overflow);
-        const uint32_t h = (i - C.blk0) >> 16;
         const int32_t Q = (int32_t)t;
         if (Q > 32767 || Q <= kWideMarker) { c16[g] = (int16_t)kWideMarker; codes[g] = t; s_cwide[h] = 1u; }
         else c16[g] = (int16_t)Q;
@@ -550,10 +560,18 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
     const uint32_t* src0 = reinterpret_cast<const uint32_t*>(tile + rw0 * kTile16Stride + c);
     const uint32_t eo0 = (C.first_seg + rw0) * kSeg + c;
     const bool whole = C.vec_ok && (C.first_seg + NT) * kSeg <= C.nf;   // every access is a full, aligned group of 4
-    const bool fast_add = (MODE == MODE_ADD_B) && whole && !a_wide && !X.a_raw;
+    const bool fast_add = NZ_ADDS(MODE) && whole && !a_wide && !X.a_raw;
     for (uint32_t r0 = 0; r0 < kSeg; r0 += kTile16R) {
         ra.install(pend);
         uint2 pa[LPR];                                // MODE_ADD_B: the staged codes of A this thread will add
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        f32x4 pl[MODE == MODE_ADD_LOCAL ? LPR : 1];   // MODE_ADD_LOCAL: the rank's own values this thread will add
+        if (MODE == MODE_ADD_LOCAL && fast_add) {
+            const float* lp = X.local + C.f0 + eo0 + r0;
+#pragma unroll
+            for (uint32_t k = 0; k < LPR; k++)
+                pl[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(lp + (size_t)k * RPK * kSeg));
+        }
         if (MODE == MODE_ADD_B && fast_add) {
             // row rw0 + RPK k of this block, phase r0 / 32 (both halves are full here)
             const int16_t* ap = X.sa.a16 + C.f0 + C.blk0 + (r0 / kTile16R) * (kHalf / 8u) + c;
@@ -609,7 +627,7 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
                 u32x2 v; v.x = src[0]; v.y = src[1];
                 __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(dst + (size_t)k * RPK * kTile16R));   // streaming, as above
             }
-        } else if (MODE == MODE_ADD_B && __builtin_expect(fast_add && plain, 1)) {
+        } else if (NZ_ADDS(MODE) && __builtin_expect(fast_add && plain, 1)) {
             int16_t* dst = X.c16 + C.f0 + eo0 + r0;
 #pragma unroll
             for (uint32_t k = 0; k < LPR; k++) {
@@ -617,17 +635,30 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
                 const uint32_t p0 = src[0], p1 = src[1];
                 const uint32_t h = (k * RPK >= kHalf / kSeg) ? 1u : 0u;       // which half of the block this row is in
                 int32_t Q[4];
+                if (MODE == MODE_ADD_LOCAL) {
+                    // quantize the rank's own values; one that cannot be quantized counts as 0 and flags its half
+                    int32_t ql[4];
+                    const float xl[4] = { pl[k].x, pl[k].y, pl[k].z, pl[k].w };
+                    bool ok = true;
+#pragma unroll
+                    for (uint32_t j = 0; j < 4; j++) ok = quantize1(xl[j], X.eb, X.step, X.inv, ql[j]) && ok;
+                    if (!ok) X.s_lunq[h] = 1u;
+                    Q[0] = (int32_t)(int16_t)(p0 & 0xFFFFu) + ql[0]; Q[1] = ((int32_t)p0 >> 16) + ql[1];
+                    Q[2] = (int32_t)(int16_t)(p1 & 0xFFFFu) + ql[2]; Q[3] = ((int32_t)p1 >> 16) + ql[3];
+                } else {
                 Q[0] = (int32_t)(int16_t)(p0 & 0xFFFFu) + (int32_t)(int16_t)(pa[k].x & 0xFFFFu);
                 Q[1] = ((int32_t)p0 >> 16) + ((int32_t)pa[k].x >> 16);
                 Q[2] = (int32_t)(int16_t)(p1 & 0xFFFFu) + (int32_t)(int16_t)(pa[k].y & 0xFFFFu);
                 Q[3] = ((int32_t)p1 >> 16) + ((int32_t)pa[k].y >> 16);
+                }
 #pragma unroll
                 for (uint32_t j = 0; j < 4; j++) {
                     const uint32_t z = zigzag(Q[j]);
                     zmax[h] = z > zmax[h] ? z : zmax[h];
                     atomicAdd(&X.s_h[h * 1024u + (bin_of(z, X.K) << X.ncs) + X.copy], 1u);
                 }
-                // operands of 16 bits: |Q| <= 65534; a sum outside the 16-bit codes is rare and goes to the 32-bit array
+                // operands of 16 bits (|q| <= 32767 from the quantizer too): |Q| <= 65534; a sum outside the 16-bit codes
+                // is rare and goes to the 32-bit array
                 const int32_t qhi = max(max(Q[0], Q[1]), max(Q[2], Q[3])), qlo = min(min(Q[0], Q[1]), min(Q[2], Q[3]));
                 uint32_t w0 = ((uint32_t)Q[0] & 0xFFFFu) | ((uint32_t)Q[1] << 16), w1 = ((uint32_t)Q[2] & 0xFFFFu) | ((uint32_t)Q[3] << 16);
                 if (__builtin_expect(qhi > 32767 || qlo <= kWideMarker, 0)) {
@@ -693,7 +724,7 @@ template <int MODE, int NT>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_decode(DecodeArgs A) {
     __shared__ DecTables s_t;
     __shared__ DecShared<NT> S;
-    __shared__ uint32_t s_h[MODE == MODE_ADD_B ? 2048 : 1];
+    __shared__ uint32_t s_h[NZ_ADDS(MODE) ? 2048 : 1];
 
     const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const uint32_t frame = blockIdx.x / A.dbpf, db = blockIdx.x % A.dbpf;
@@ -714,7 +745,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
     uint64_t total_a = 0, total_b = 0;
     const uint32_t st_a = check_stream(A.a, A.a_bytes, A, total_a);
     uint32_t st_b = ST_OK;
-    if (MODE != MODE_DECOMPRESS) st_b = check_stream(A.b, A.b_bytes, A, total_b);
+    if (MODE == MODE_STAGE_A || MODE == MODE_ADD_B) st_b = check_stream(A.b, A.b_bytes, A, total_b);
     if (blockIdx.x == 0 && tid == 0) {
         if (st_a) atomicMax(&res->status, st_a);
         if (st_b) atomicMax(&res->status, st_b);
@@ -742,7 +773,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
         seglen = (V.kind == KIND_HUFF && seg_valid) ? V.segt[gseg] : 0u;
         const uint32_t incl = wave_incl_scan_dpp(seglen);
         if (lane == 63) S.wsum[wave] = incl;
-        if (tid == 0) { S.zmax[0] = 0; S.zmax[1] = 0; S.flags = 0; S.cwide[0] = 0; S.cwide[1] = 0; }
+        if (tid == 0) { S.zmax[0] = 0; S.zmax[1] = 0; S.flags = 0; S.cwide[0] = 0; S.cwide[1] = 0; S.lunq[0] = 0; S.lunq[1] = 0; S.ovf = 0; }
         __syncthreads();
         uint32_t excl = incl - seglen;
         for (uint32_t w = 0; w < wave; w++) excl += (uint32_t)S.wsum[w];
@@ -762,19 +793,22 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
     AddCtx X;
     X.sa.a16 = reinterpret_cast<int16_t*>(A.ws + A.L.a16); X.sa.a32 = reinterpret_cast<uint32_t*>(A.ws + A.L.a32);
     X.codes = reinterpret_cast<uint32_t*>(A.ws + A.L.codes); X.c16 = reinterpret_cast<int16_t*>(A.ws + A.L.c16);
-    X.s_cwide = S.cwide;
+    X.s_cwide = S.cwide; X.s_lunq = S.lunq;
+    X.local = (MODE == MODE_ADD_LOCAL) ? A.local : nullptr; X.eb = A.eb; X.inv = A.inv_step;
     X.s_h = s_h; X.K = A.K; X.step = A.step; X.ncs = 0; X.copy = 0; X.a_raw = false; X.b_raw = false;
     uint32_t* akind = reinterpret_cast<uint32_t*>(A.ws + A.L.akind);   // per frame: operand A is RAW
     uint32_t* awide = reinterpret_cast<uint32_t*>(A.ws + A.L.awide);   // per half: some code of A needs 32 bits
     bool a_wide = false;
-    if (MODE == MODE_ADD_B) {
+    if (NZ_ADDS(MODE)) {
         while ((A.K << (X.ncs + 1)) <= 1024u && X.ncs < 5) X.ncs++;
         X.copy = lane & ((1u << X.ncs) - 1u);
         for (uint32_t i = tid; i < 2048u; i += NT) s_h[i] = 0;
-        X.a_raw = akind[frame] != 0;
         X.b_raw = V.kind == KIND_RAW;
-        for (uint32_t h = 0; h < NT * kSeg / kHalf; h++)
-            if (blk0 + h * kHalf < nf) a_wide = a_wide || (awide[(size_t)frame * hpf + blk0 / kHalf + h] != 0);
+        if (MODE == MODE_ADD_B) {
+            X.a_raw = akind[frame] != 0;
+            for (uint32_t h = 0; h < NT * kSeg / kHalf; h++)
+                if (blk0 + h * kHalf < nf) a_wide = a_wide || (awide[(size_t)frame * hpf + blk0 / kHalf + h] != 0);
+        } else if (db == 0 && tid == 0) akind[frame] = X.b_raw ? 1u : 0u;   // ring step: "the incoming frame is RAW", for k_fix_local
         __syncthreads();
     }
 
@@ -795,8 +829,11 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
         }
         return;
     }
-    // ---- MODE_ADD_B: statistics of the sum, per half ----
-    if (overflow) atomicMax(&res->status, (uint32_t)ST_RANGE);
+    // ---- adding passes: statistics of the sum, per half ----
+    // (ring step: whether a sum out of range is an error depends on the whole frame -- a frame made RAW by the
+    // local data has no integer sums -- so the flag is left for k_fix_local)
+    if (MODE == MODE_ADD_B && overflow) atomicMax(&res->status, (uint32_t)ST_RANGE);
+    if (MODE == MODE_ADD_LOCAL && overflow) S.ovf = 1u;
 #pragma unroll
     for (uint32_t h = 0; h < 2; h++) {
         const uint32_t zm = wave_max(zmax[h]);
@@ -814,10 +851,66 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
             ph[bin_symbol(sy, A.K)] = t;
         }
         if (tid == 0) {
-            reinterpret_cast<uint2*>(A.ws + A.L.pmeta)[hb] = make_uint2(S.zmax[h], out_raw ? 1u : 0u);
-            reinterpret_cast<uint32_t*>(A.ws + A.L.cwide)[hb] = S.cwide[h];
+            // flag word: bit 0 = an operand frame is RAW, bit 1 = the local data of this half cannot be quantized
+            reinterpret_cast<uint2*>(A.ws + A.L.pmeta)[hb] = make_uint2(S.zmax[h], (out_raw ? 1u : 0u) | (S.lunq[h] ? 2u : 0u));
+            // bit 0 = the half holds sums that need 32 bits, bit 1 = a sum of this workgroup is out of range
+            reinterpret_cast<uint32_t*>(A.ws + A.L.cwide)[hb] = (S.cwide[h] ? 1u : 0u) | (S.ovf ? 2u : 0u);
         }
     }
+}
+
+// Ring step, after the adding pass: a frame whose local data holds an element that cannot be quantized is RAW
+// (as the interface quantizer would have made it), so its payload is the fp32 sum of the incoming values and
+// the ORIGINAL local values.  Rare; one workgroup per half looks at the frame's flags and returns at once
+// otherwise.  The incoming code is recovered exactly from the staged sum (Q - q_local, q_local = 0 where the
+// element was not quantizable); a RAW incoming frame is read from the stream again.  Also settles the range
+// error: it only exists for frames that keep integer sums.
+__global__ __launch_bounds__(256) void k_fix_local(DecodeArgs A) {
+    const uint32_t tid = threadIdx.x;
+    const uint32_t hpf = (A.chunk + kHalf - 1) / kHalf;
+    const uint32_t frame = blockIdx.x / hpf, h = blockIdx.x % hpf;
+    const uint64_t f0 = (uint64_t)frame * A.chunk;
+    const uint32_t nf = (uint32_t)((A.n - f0 < A.chunk) ? (A.n - f0) : A.chunk);
+    const uint32_t h0 = h * kHalf;
+    if (h0 >= nf) return;
+    const uint32_t cnt = (nf - h0 < kHalf) ? (nf - h0) : kHalf;
+    ResultRec* res = reinterpret_cast<ResultRec*>(A.res);
+    const uint2* pm = reinterpret_cast<const uint2*>(A.ws + A.L.pmeta) + (size_t)frame * hpf;
+    const uint32_t* cw = reinterpret_cast<const uint32_t*>(A.ws + A.L.cwide) + (size_t)frame * hpf;
+    uint32_t lunq = 0, ovf = 0;
+    for (uint32_t j = 0; j < hpf && j * kHalf < nf; j++) { lunq |= pm[j].y & 2u; ovf |= cw[j] & 2u; }
+    const bool in_raw = reinterpret_cast<const uint32_t*>(A.ws + A.L.akind)[frame] != 0;
+    if (!lunq) {
+        if (ovf && !in_raw && h == 0 && tid == 0) atomicMax(&res->status, (uint32_t)ST_RANGE);
+        return;
+    }
+    uint32_t* codes = reinterpret_cast<uint32_t*>(A.ws + A.L.codes) + f0 + h0;
+    const int16_t* c16 = reinterpret_cast<const int16_t*>(A.ws + A.L.c16) + f0 + h0;
+    const float* x = A.local + f0 + h0;
+    const uint32_t* raw_in = nullptr;
+    if (in_raw) {       // header and extent of a RAW incoming frame were validated by the adding pass
+        const uint64_t off = *reinterpret_cast<const uint64_t*>(A.a + kStreamHdr + 8ull * frame);
+        raw_in = reinterpret_cast<const uint32_t*>(A.a + off + kHdrBytes) + h0;
+    }
+    uint32_t dummy = 0;
+    for (uint32_t i = tid; i < cnt; i += 256) {
+        uint32_t ta;
+        if (in_raw) ta = raw_in[i];
+        else {
+            const int32_t s16 = c16[i];
+            const uint32_t Q = (s16 == kWideMarker) ? codes[i] : (uint32_t)s16;
+            int32_t q;
+            quantize1(x[i], A.eb, A.step, A.inv_step, q);
+            ta = Q - (uint32_t)q;
+        }
+        codes[i] = combine<true>(ta, in_raw, __float_as_uint(x[i]), true, A.step, dummy);
+    }
+}
+
+hipError_t launch_fix_local(const DecodeArgs& A, hipStream_t st) {
+    const uint32_t hpf = (A.chunk + kHalf - 1) / kHalf;
+    hipLaunchKernelGGL(k_fix_local, dim3(A.n_frames * hpf), dim3(256), 0, st, A);
+    return hipGetLastError();
 }
 
 constexpr int kAddThreads = 512;        // second reduce pass: two halves per workgroup, four waves per SIMD at 2 workgroups per CU
@@ -830,9 +923,12 @@ hipError_t launch_decode(const DecodeArgs& A, int pass, hipStream_t st) {
     } else if (pass == 1) {
         D.dbpf = (A.chunk + kDecBlock - 1) / kDecBlock;
         hipLaunchKernelGGL((k_decode<MODE_STAGE_A, kDecThreads>), dim3(D.n_frames * D.dbpf), dim3(kDecThreads), 0, st, D);
-    } else {
+    } else if (pass == 2) {
         D.dbpf = (A.chunk + kAddThreads * kSeg - 1) / (kAddThreads * kSeg);
         hipLaunchKernelGGL((k_decode<MODE_ADD_B, kAddThreads>), dim3(D.n_frames * D.dbpf), dim3(kAddThreads), 0, st, D);
+    } else {
+        D.dbpf = (A.chunk + kAddThreads * kSeg - 1) / (kAddThreads * kSeg);
+        hipLaunchKernelGGL((k_decode<MODE_ADD_LOCAL, kAddThreads>), dim3(D.n_frames * D.dbpf), dim3(kAddThreads), 0, st, D);
     }
     return hipGetLastError();
 }

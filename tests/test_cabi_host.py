@@ -26,7 +26,7 @@ def test_exports_every_declared_symbol(nz):
     hdr = open(os.path.join(ROOT, "include", "nz.h")).read()
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b(nz_[a-z_]+)\s*\(", hdr))
-    assert {"nz_compress", "nz_decompress", "nz_reduce_frames", "nz_compress_bound", "nz_workspace_bytes",
+    assert {"nz_compress", "nz_decompress", "nz_reduce_frames", "nz_reduce_local", "nz_compress_bound", "nz_workspace_bytes",
             "nz_reduce_workspace_bytes", "nz_version"} <= names
     L = nz.lib()
     for n in names:

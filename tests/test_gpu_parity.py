@@ -62,6 +62,15 @@ def _first_diff(a, b):
     return int(d[0]) if d.size else (m if a.size != b.size else -1)
 
 
+def gpu_reduce_local(nz, a, x, eb, g_opts, cap=None):
+    n = x.size
+    sess = nz.Session(n, g_opts, "cuda:0", reduce=True)
+    da = _to_dev(nz, np.concatenate([a, np.zeros((-a.size) % 16, np.uint8)]))
+    rc, out = sess.reduce_local(da, a.size, _to_dev(nz, x), n, eb, cap=cap)
+    r = sess.result()
+    return rc, r, out[:r["bytes"]].cpu().numpy()
+
+
 def check_compress(nz, x, eb, **kw):
     g, o = _opts_pair(nz, **kw)
     ref, ores, orc = oracle.compress(x, eb, o)
@@ -428,3 +437,99 @@ def test_c2_full_size(nz):
     ro, rres, rrc = oracle.reduce_frames(ref, pref, n, eb, o)
     assert rc == 0 and rrc == 0 and rr["status"] == 0 and rr["bytes"] == rres.bytes
     assert _first_diff(red[:rr["bytes"]].cpu().numpy(), ro) == -1
+
+
+# ------------------------------------------------------------------------------------------------
+# ring-step reduce: incoming frames + the rank's own fp32 data
+# ------------------------------------------------------------------------------------------------
+
+def _check_reduce_local(nz, a_stream, x, eb, **kw):
+    g, o = _opts_pair(nz, **kw)
+    ref, ores, orc = oracle.reduce_local(a_stream, x, eb, o)
+    rc, r, got = gpu_reduce_local(nz, a_stream, x, eb, g)
+    assert rc == 0 and r["status"] == orc, (r, orc)
+    if orc == 0:
+        assert r["bytes"] == ores.bytes and _first_diff(got, ref) == -1
+        assert (r["n_raw"], r["n_fixed"], r["n_huff"]) == (ores.n_raw, ores.n_fixed, ores.n_huff)
+    else:
+        assert r["bytes"] == 0
+    return ref
+
+
+def test_reduce_local_ring_chain(nz):
+    """A reduce-scatter ring as one rank sees it: every step adds the rank's own fp32 data to the incoming frames."""
+    n, eb = 2 * 262144 + 70001, 1e-5
+    kw = dict(chunk_elems=262144)
+    msgs = W.peer_messages(n, peers=4, seed0=40)
+    acc = oracle.compress(msgs[0], eb, oracle.make_opts(**kw))[0]
+    for p in (1, 2, 3):
+        acc = _check_reduce_local(nz, acc, msgs[p], eb, **kw)
+    g, _ = _opts_pair(nz, **kw)
+    rc, r, got = gpu_decompress(nz, acc, n, eb, g)
+    true = sum(m.astype(np.float64) for m in msgs)
+    assert (np.abs(got.astype(np.float64) - true) <= 4 * float(np.float32(eb))).all()
+
+
+@pytest.mark.parametrize("case", ["local_nan", "incoming_raw", "both", "fixedlen_in", "raw_forced", "wide_sums"])
+def test_reduce_local_frame_kinds(nz, case):
+    n, eb = 2 * 131072 + 9001, 1e-4
+    kw = dict(chunk_elems=131072)
+    a, x = W.gradient_like(n, seed=81), W.gradient_like(n, seed=82)
+    in_kw = dict(kw)
+    if case in ("local_nan", "both"):
+        x[[5, 131072 + 70000]] = [np.nan, 3e38]           # frames 0 and 1 of the local data cannot be quantized
+    if case in ("incoming_raw", "both"):
+        a[[131072 + 1, n - 1]] = [np.inf, -np.inf]        # frames 1 and 2 of the incoming stream are RAW
+    if case == "fixedlen_in":
+        in_kw["force_codec"] = 1
+    if case == "raw_forced":
+        in_kw["force_codec"] = 0
+    if case == "wide_sums":
+        step = oracle.step_constants(eb)[0]
+        a[[3, 70000, 131072 + 5]] = np.float32(30000.0) * step
+        x[[3, 70000, 131072 + 5]] = np.float32(31000.0) * step
+        x[9] = np.float32(-32767.0) * step; a[9] = np.float32(-32767.0) * step
+    sa = oracle.compress(a, eb, oracle.make_opts(**in_kw))[0]
+    _check_reduce_local(nz, sa, x, eb, **kw)
+
+
+def test_reduce_local_range_mismatch_capacity(nz):
+    eb = 1e-3
+    g, o = _opts_pair(nz, chunk_elems=1000)
+    step = oracle.step_constants(eb)[0]
+    z = np.zeros(1000, np.float32); z[7] = np.float32(32767.0) * step
+    s = oracle.compress(z, eb, o)[0]
+    for _ in range(15):
+        s = oracle.reduce_frames(s, s, 1000, eb, o)[0]
+    s1 = _check_reduce_local(nz, s, z, eb, chunk_elems=1000)                      # 2^30 - 1: still carried
+    rc, r, _ = gpu_reduce_local(nz, s1, z, eb, g)
+    assert r["status"] == nz.ERR_RANGE and r["bytes"] == 0
+    zn = z.copy(); zn[500] = np.nan                                              # the frame turns RAW: no range error
+    _check_reduce_local(nz, s1, zn, eb, chunk_elems=1000)
+    a = W.gradient_like(3000, seed=70)
+    sa = oracle.compress(a, eb, o)[0]
+    assert gpu_reduce_local(nz, sa, a, 2e-3, g)[1]["status"] == nz.ERR_MISMATCH
+    g2 = nz.make_opts(chunk_elems=500)
+    assert gpu_reduce_local(nz, sa, a, eb, g2)[1]["status"] == nz.ERR_MISMATCH
+    ref, ores, _ = oracle.reduce_local(sa, a, eb, o)
+    rc, r, _ = gpu_reduce_local(nz, sa, a, eb, g, cap=int(ores.bytes) - 16)
+    assert r["status"] == nz.ERR_CAPACITY and r["bytes"] == 0
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_reduce_local_seeded_sweep(nz, seed):
+    rng = np.random.default_rng(3000 + seed)
+    n = int(rng.choice([1, 257, 4097, 65537, 131072, 200001, 600011]))
+    chunk = int(rng.choice([16, 1000, 16384, 65536, 100003, 131072, 262144]))
+    K = int(rng.choice([2, 64, 256, 256, 1024]))
+    eb = float(rng.choice([1e-3, 1e-4, 1e-5]))
+    kw = dict(chunk_elems=chunk, alphabet=K)
+    a, x = _mixture(rng, n), _mixture(rng, n)
+    if rng.random() < 0.25:
+        x[rng.integers(0, n)] = np.nan
+    if rng.random() < 0.25:
+        a[rng.integers(0, n)] = np.inf
+    sa = oracle.compress(a, eb, oracle.make_opts(**kw))[0]
+    s1 = _check_reduce_local(nz, sa, x, eb, **kw)
+    if s1.size:
+        _check_reduce_local(nz, s1, a, eb, **kw)                                  # second ring step on wider codes
