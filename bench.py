@@ -171,7 +171,8 @@ def main():
 
     # per-stage and per-kernel times from HIP events the library records on its stream
     names = {"compress": ["init", "stats", "codebook", "encode"], "decompress": ["init", "decode"],
-             "reduce": ["init", "stage_a", "add_b", "codebook", "encode"]}
+             "reduce": ["init", "stage_a", "add_b", "codebook", "encode"],
+             "reduce_local": ["init", "add_local", "fix_local", "codebook", "encode"]}
     acc = {k: [0.0] * len(v) for k, v in names.items()}
     reps = max(5, min(args.steps, 20))
     with nz.KernelTrace(8) as tr:
@@ -186,6 +187,10 @@ def main():
             sess.reduce(outs[k], stream_bytes, peer_stream, peer_bytes, n, eb, out=red_out)
             for j, t in enumerate(tr.kernel_ms()):
                 acc["reduce"][j] += t
+            # ring-step variant (not part of `value`): incoming stream + the rank's own fp32 data
+            sess.reduce_local(outs[k], stream_bytes, xpeer, n, eb, out=red_out)
+            for j, t in enumerate(tr.kernel_ms()):
+                acc["reduce_local"][j] += t
     kern = {st: {nm: acc[st][j] / reps for j, nm in enumerate(names[st])} for st in names}
     # what a plain streaming kernel reaches on this machine: elementwise copy of the message (4n read + 4n written)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -204,7 +209,8 @@ def main():
            ("decompress", "decode"): 4.0 * n + stream_bytes,
            ("reduce", "stage_a"): stream_bytes + 2.0 * n,
            ("reduce", "add_b"): peer_bytes + 2.0 * n + 2.0 * n,
-           ("reduce", "encode"): 2.0 * n + reduce_bytes}
+           ("reduce", "encode"): 2.0 * n + reduce_bytes,
+           ("reduce_local", "add_local"): stream_bytes + 4.0 * n + 2.0 * n}
     dom = max(alg, key=lambda k: kern[k[0]][k[1]])
     dom_ms = kern[dom[0]][dom[1]]
     achieved = alg[dom] / (dom_ms * 1e-3) / 1e9
@@ -222,6 +228,7 @@ def main():
                            compress_frac_hbm=gb / (stage_ms["compress"] * 1e-3) / HBM_PEAK_GBPS,
                            decompress_frac_hbm=gb / (stage_ms["decompress"] * 1e-3) / HBM_PEAK_GBPS,
                            reduce_frac_hbm=gb / (stage_ms["reduce"] * 1e-3) / HBM_PEAK_GBPS,
+                           reduce_local_GBps=gb / (stage_ms["reduce_local"] * 1e-3),
                            copy_kernel_GBps=copy_gbps,
                            compression_ratio=cr, stream_bytes=stream_bytes, reduce_stream_bytes=reduce_bytes,
                            frames=dict(raw=r0["n_raw"], fixed=r0["n_fixed"], huffman=r0["n_huff"]),

@@ -524,8 +524,9 @@ struct AddCtx {
 // barrier the workgroup consumes the tile with coalesced accesses (eight lanes per row).
 //   MODE_DECOMPRESS  dequantize and store fp32
 //   MODE_STAGE_A     store the 16-bit codes
-//   MODE_ADD_B       add the staged codes of A (requested before the phase is decoded), store the 32-bit sums,
-//                    count their symbols per half of kHalf elements
+//   MODE_ADD_B       add the staged codes of A, store the sums as 16-bit codes, count their symbols per half of
+//                    kHalf elements
+//   MODE_ADD_LOCAL   the same with the rank's own fp32 data, quantized here, in the place of A
 // A code that does not fit 16 bits (an escape with a large value) is finished by the decoding lane itself,
 // which leaves kWideMarker in the tile and raises a workgroup flag; only then does the consumer look for
 // markers.
@@ -566,24 +567,6 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
         uint2 pa[LPR];                                // MODE_ADD_B: the staged codes of A this thread will add
         typedef float f32x4 __attribute__((ext_vector_type(4)));
         f32x4 pl[MODE == MODE_ADD_LOCAL ? LPR : 1];   // MODE_ADD_LOCAL: the rank's own values this thread will add
-        if (MODE == MODE_ADD_LOCAL && fast_add) {
-            const float* lp = X.local + C.f0 + eo0 + r0;
-#pragma unroll
-            for (uint32_t k = 0; k < LPR; k++)
-                pl[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(lp + (size_t)k * RPK * kSeg));
-        }
-        if (MODE == MODE_ADD_B && fast_add) {
-            // row rw0 + RPK k of this block, phase r0 / 32 (both halves are full here)
-            const int16_t* ap = X.sa.a16 + C.f0 + C.blk0 + (r0 / kTile16R) * (kHalf / 8u) + c;
-#pragma unroll
-            for (uint32_t k = 0; k < LPR; k++) {
-                typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-                const uint32_t rw = rw0 + k * RPK;
-                const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(
-                    ap + (size_t)(rw / kSeg) * kHalf + (rw % kSeg) * kTile16R));
-                pa[k] = make_uint2(v.x, v.y);
-            }
-        }
         if (r0 + kTile16R <= C.cntseg) {
 #pragma unroll
             for (uint32_t h = 0; h < kTile16R; h += kRun) {
@@ -629,6 +612,26 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
             }
         } else if (NZ_ADDS(MODE) && __builtin_expect(fast_add && plain, 1)) {
             int16_t* dst = X.c16 + C.f0 + eo0 + r0;
+            // the other operand is requested here rather than across the decode phase (no registers held, no spills);
+            // the other workgroup of the CU covers the wait
+            if (MODE == MODE_ADD_B) {
+                // row rw0 + RPK k of this block, phase r0 / 32 (both halves are full here)
+                const int16_t* ap = X.sa.a16 + C.f0 + C.blk0 + (r0 / kTile16R) * (kHalf / 8u) + c;
+#pragma unroll
+                for (uint32_t k = 0; k < LPR; k++) {
+                    typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+                    const uint32_t rw = rw0 + k * RPK;
+                    const u32x2 v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(
+                        ap + (size_t)(rw / kSeg) * kHalf + (rw % kSeg) * kTile16R));
+                    pa[k] = make_uint2(v.x, v.y);
+                }
+            }
+            if (MODE == MODE_ADD_LOCAL) {
+                const float* lp = X.local + C.f0 + eo0 + r0;
+#pragma unroll
+                for (uint32_t k = 0; k < LPR; k++)
+                    pl[k] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(lp + (size_t)k * RPK * kSeg));
+            }
 #pragma unroll
             for (uint32_t k = 0; k < LPR; k++) {
                 const uint32_t* src = src0 + k * RPK * (kTile16Stride / 2);

@@ -19,7 +19,8 @@ import sys
 
 KERNELS = [("k_stats", "compress/stats"), ("k_codebook", "*/codebook"), ("k_encode<0>", "compress/encode"),
            ("k_encode<1>", "reduce/encode"), ("k_decode<0, 256>", "decompress/decode"),
-           ("k_decode<1, 256>", "reduce/stage_a"), ("k_decode<2, 512>", "reduce/add_b")]
+           ("k_decode<1, 256>", "reduce/stage_a"), ("k_decode<2, 512>", "reduce/add_b"),
+           ("k_decode<3, 512>", "reduce_local/add_local")]
 
 
 def per_kernel(d, counter):
