@@ -115,7 +115,7 @@ __global__ __launch_bounds__(kBookThreads) void k_codebook(CompressArgs A) {
     __shared__ uint32_t s_f[kMaxK];
     __shared__ __align__(16) uint32_t s_key[kMaxK];
     __shared__ uint32_t s_sorted[kMaxK];
-    __shared__ uint32_t s_w[2 * kMaxK + 16];      // leaves [0, m) + 8 sentinels; internal nodes from kMaxK + 8, then sentinels
+    __shared__ uint32_t s_w[2 * (kMaxK + 128)];   // leaves [0, m) + sentinels; internal nodes from kMaxK + 128, then sentinels
     __shared__ uint16_t s_par[2 * kMaxK];
     __shared__ __align__(4) uint8_t s_len[kMaxK];
     __shared__ uint16_t s_rank[kMaxK];
@@ -169,45 +169,55 @@ __global__ __launch_bounds__(kBookThreads) void k_codebook(CompressArgs A) {
     __syncthreads();
     // leaves in order, followed by sentinels; the internal-node queue starts out all sentinels
     constexpr uint32_t INF = 0xFFFFFFFFu;
-    uint32_t* s_int = s_w + kMaxK + 8;
+    uint32_t* s_int = s_w + kMaxK + 128;
     if (tid < m) s_w[tid] = s_sorted[tid] >> 10;
-    if (tid < 8) { s_w[m + tid] = INF; s_int[kMaxK + tid] = INF; }
+    if (tid < 128) { s_w[m + tid] = INF; s_int[kMaxK + tid] = INF; }
     s_int[tid] = INF;
     __syncthreads();
 
-    // (3) two-queue merge, one lane.  A lone wave pays the full latency of every dependent instruction, so the
-    // step is kept on the scalar unit: the two heads of either queue live in scalar registers, every weight that
-    // comes from LDS is moved there with readfirstlane, and the entries behind the heads are requested one step
-    // before they are needed (entries past the end of a queue read as sentinels; a node that would be a head
-    // right after its creation is forwarded from registers).
-    if (tid == 0 && m >= 2) {
-        auto sg = [](uint32_t v) -> uint32_t { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); };
+    // (3) two-queue merge by wave 0, a run of steps at a time.  The merge alternates between runs of
+    // leaf + leaf steps, runs of node + node steps and single leaf + node steps.  During a leaf + leaf run the
+    // head of the node queue does not change (new nodes join its tail), so the run goes on exactly while the
+    // second leaf of the next pair is <= that head: lane j tests pair j and all pairs that pass are merged at
+    // once.  A node + node run goes on while the second node of the next pair exists and is < the leaf head; only
+    // nodes that existed when the round began are paired, the rest follows in the next round.  The result is the
+    // sequential construction step for step (a leaf wins a tie), in far fewer dependent rounds.
+    if (wave == 0 && m >= 2) {
         uint32_t ia = 0, ib = 0, nint = 0;                    // heads: leaf ia, internal node ib; nodes created
-        uint32_t a0 = sg(s_w[0]), a1 = sg(s_w[1]), b0 = INF, b1 = INF;
-        uint32_t va2 = s_w[2], va3 = s_w[3], vb2 = INF, vb3 = INF;      // entries 2 and 3 behind the heads (vector side)
-#pragma unroll 1
-        for (uint32_t step = 0; step + 1 < m; step++) {
-            const uint16_t node = (uint16_t)(m + nint);
-            uint32_t w;
-            if (a0 <= b0 && a1 <= b0) {                       // two leaves (a leaf wins ties)
-                w = a0 + a1;
-                s_par[ia] = node; s_par[ia + 1] = node; ia += 2;
-                a0 = sg(va2); a1 = sg(va3);
-            } else if (a0 > b0 && a0 > b1) {                  // two internal nodes
-                w = b0 + b1;
-                s_par[m + ib] = node; s_par[m + ib + 1] = node; ib += 2;
-                b0 = sg(vb2); b1 = sg(vb3);
-            } else {                                          // one of each
-                w = a0 + b0;
-                s_par[ia] = node; s_par[m + ib] = node; ia += 1; ib += 1;
-                a0 = a1; a1 = sg(va2);
-                b0 = b1; b1 = sg(vb2);
+        while (nint + 1 < m) {
+            const uint32_t la = s_w[ia + 2 * lane], lb = s_w[ia + 2 * lane + 1];       // leaf pair `lane`
+            const uint32_t na = s_int[ib + 2 * lane], nb = s_int[ib + 2 * lane + 1];   // node pair `lane` (INF: not created)
+            const uint32_t a0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)la), a1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)lb);
+            const uint32_t b0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)na), b1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)nb);
+            const uint32_t left = m - 1 - nint;               // nodes still to be made
+            if (a0 <= b0 && a1 <= b0) {                       // leaf + leaf
+                uint32_t L = 1;                               // empty node queue: the first new node becomes its head
+                if (b0 != INF) { const uint64_t ok = __ballot(lb <= b0); L = (~ok) ? (uint32_t)__builtin_ctzll(~ok) : 64u; }
+                L = L < left ? L : left;
+                if (lane < L) {
+                    const uint16_t node = (uint16_t)(m + nint + lane);
+                    s_int[nint + lane] = la + lb;
+                    s_par[ia + 2 * lane] = node; s_par[ia + 2 * lane + 1] = node;
+                }
+                ia += 2 * L; nint += L;
+            } else if (a0 > b0 && a0 > b1) {                  // node + node
+                const uint64_t ok = __ballot(a0 > nb);        // false where the pair's second node does not exist yet
+                uint32_t L = (~ok) ? (uint32_t)__builtin_ctzll(~ok) : 64u;
+                L = L < left ? L : left;
+                if (lane < L) {
+                    const uint16_t node = (uint16_t)(m + nint + lane);
+                    s_int[nint + lane] = na + nb;
+                    s_par[m + ib + 2 * lane] = node; s_par[m + ib + 2 * lane + 1] = node;
+                }
+                ib += 2 * L; nint += L;
+            } else {                                          // leaf + node
+                if (lane == 0) {
+                    const uint16_t node = (uint16_t)(m + nint);
+                    s_int[nint] = la + na;
+                    s_par[ia] = node; s_par[m + ib] = node;
+                }
+                ia += 1; ib += 1; nint += 1;
             }
-            s_int[nint] = w;
-            if (nint == ib) b0 = w; else if (nint == ib + 1) b1 = w;   // the new node is a queue head already
-            nint++;
-            va2 = s_w[ia + 2]; va3 = s_w[ia + 3];             // requested now, moved to scalars one step from now
-            vb2 = s_int[ib + 2]; vb3 = s_int[ib + 3];
         }
     }
     __syncthreads();
