@@ -533,3 +533,24 @@ def test_reduce_local_seeded_sweep(nz, seed):
     s1 = _check_reduce_local(nz, sa, x, eb, **kw)
     if s1.size:
         _check_reduce_local(nz, s1, a, eb, **kw)                                  # second ring step on wider codes
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_codebook_tie_heavy_histograms(nz, seed):
+    """Small frames of few equally likely codes: counts tie all the time, internal nodes tie with leaves, and the
+    merge alternates between long leaf-pair and node-pair runs -- the cases the run-at-a-time merge must get exactly
+    like the sequential two-queue rule (a leaf wins a tie)."""
+    rng = np.random.default_rng(5000 + seed)
+    eb = 1e-3
+    step = oracle.step_constants(eb)[0]
+    levels = int(rng.choice([2, 3, 5, 8, 17, 33, 100, 200]))
+    chunk = int(rng.choice([64, 256, 1000, 4096]))
+    n = chunk * int(rng.integers(3, 40)) + int(rng.integers(0, chunk))
+    q = rng.integers(-levels, levels + 1, n)
+    if seed % 2:
+        q = np.repeat(np.arange(-levels, levels + 1), n // (2 * levels + 1) + 1)[:n]      # exactly equal counts
+        rng.shuffle(q)
+    x = (q.astype(np.float32) * np.float32(step)).astype(np.float32)
+    K = int(rng.choice([16, 64, 256, 1024]))
+    ref, _ = check_compress(nz, x, eb, chunk_elems=chunk, alphabet=K, force_codec=2)
+    check_decompress(nz, ref, x, eb, chunk_elems=chunk, alphabet=K)
