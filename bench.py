@@ -170,7 +170,7 @@ def main():
     reduce_bytes = rr["bytes"]
 
     # per-stage and per-kernel times from HIP events the library records on its stream
-    names = {"compress": ["init", "stats", "codebook", "encode"], "decompress": ["init", "decode"],
+    names = {"compress": ["stats", "codebook", "encode"], "decompress": ["init", "decode"],
              "reduce": ["init", "stage_a", "add_b", "codebook", "encode"],
              "reduce_local": ["init", "add_local", "fix_local", "codebook", "encode"]}
     acc = {k: [0.0] * len(v) for k, v in names.items()}

@@ -121,9 +121,7 @@ nz_status nz_compress(const float* d_in, size_t n, float eb, void* d_out, size_t
     A.eb = eb; A.step = step; A.inv_step = inv; A.step_bits = bits_of(step);
     A.out = reinterpret_cast<uint8_t*>(d_out); A.out_cap = out_cap; A.ws = ws; A.L = L; A.res = d_res;
     trace_reset(); trace_mark(st);
-    if (launch_init(ws + L.ctrl, L.zero_end - L.ctrl, d_res, nfr, NZ_OK, st) != hipSuccess) return NZ_ERR_HIP;
-    trace_mark(st);
-    if (launch_stats(A, st) != hipSuccess) return NZ_ERR_HIP;
+    if (launch_stats(A, st) != hipSuccess) return NZ_ERR_HIP;     // also clears the control block and the result record
     trace_mark(st);
     if (launch_codebook(A, st) != hipSuccess) return NZ_ERR_HIP;
     trace_mark(st);

@@ -12,7 +12,8 @@
 namespace nz {
 
 // ------------------------------------------------------------------------------------------------
-// K0: clear the control block / look-back descriptors and initialise the result record
+// K0: clear the control block / look-back descriptors and initialise the result record (decompress and reduce;
+// nz_compress does this inside its statistics kernel)
 // ------------------------------------------------------------------------------------------------
 __global__ void k_init(uint32_t* zero_base, size_t zero_words, ResultRec* res, uint32_t n_frames, uint32_t status) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -32,6 +33,18 @@ __global__ __launch_bounds__(kStatThreads) void k_stats(CompressArgs A) {
     __shared__ uint32_t s_h[8192];
     __shared__ uint32_t s_zmax, s_unq;
     const uint32_t tid = threadIdx.x, lane = lane_id();
+    if (blockIdx.x == 0) {
+        // The control block, the frame descriptors and the result record are first used by the next kernel, so
+        // this kernel clears them on the side (no separate launch): nothing here reads or writes them.
+        uint32_t* z = reinterpret_cast<uint32_t*>(A.ws + A.L.ctrl);
+        const uint32_t words = (uint32_t)((A.L.zero_end - A.L.ctrl) / 4);
+        for (uint32_t i = tid; i < words; i += kStatThreads) z[i] = 0;
+        if (tid == 0) {
+            ResultRec* res = reinterpret_cast<ResultRec*>(A.res);
+            res->bytes = 0; res->status = ST_OK; res->n_frames = A.n_frames;
+            res->n_raw = 0; res->n_fixed = 0; res->n_huff = 0; res->reserved = 0;
+        }
+    }
     const uint32_t frame = blockIdx.x / A.sbpf, sb = blockIdx.x % A.sbpf;
     const uint64_t f0 = (uint64_t)frame * A.chunk;
     const uint32_t nf = (uint32_t)((A.n - f0 < A.chunk) ? (A.n - f0) : A.chunk);
