@@ -554,3 +554,44 @@ def test_codebook_tie_heavy_histograms(nz, seed):
     K = int(rng.choice([16, 64, 256, 1024]))
     ref, _ = check_compress(nz, x, eb, chunk_elems=chunk, alphabet=K, force_codec=2)
     check_decompress(nz, ref, x, eb, chunk_elems=chunk, alphabet=K)
+
+
+def test_more_than_2_to_31_elements(nz):
+    """Index arithmetic past 32 bits: 2^31 + 70001 elements (8.6 GB of fp32).  Too large for the oracle to hold, so
+    the check is by properties that hold at any size: frame count, stream header, |x - xhat| <= eb for every element,
+    a decoded stream of the expected length, and byte-identity of the first and last frames with the oracle's
+    encoding of the same frames."""
+    import torch
+    n = (1 << 31) + 70001
+    chunk = 1 << 20
+    eb = 1e-4
+    g = nz.make_opts(chunk_elems=chunk)
+    gen = torch.Generator(device="cuda:0"); gen.manual_seed(7)
+    x = torch.empty(n, dtype=torch.float32, device="cuda:0")
+    x.normal_(0.0, 1e-3, generator=gen)
+    sess = nz.Session(n, g, "cuda:0")
+    rc, out = sess.compress(x, eb)
+    r = sess.result()
+    nfr = (n + chunk - 1) // chunk
+    assert rc == 0 and r["status"] == 0 and r["n_frames"] == nfr and r["n_raw"] == 0
+    hdr = out[:64].cpu().numpy()
+    assert int(hdr[8:16].view(np.uint64)[0]) == n and int(hdr[40:48].view(np.uint64)[0]) == r["bytes"]
+    offs = out[64:64 + 8 * nfr].cpu().numpy().view(np.uint64).astype(np.int64)
+    assert (np.diff(offs) > 0).all() and offs[-1] < r["bytes"]
+    # first and last frame against the oracle's frame encoder
+    o = oracle.make_opts(chunk_elems=chunk)
+    step_bits = int(np.float32(oracle.step_constants(eb)[0]).view(np.uint32))
+    for k in (0, nfr - 1):
+        xf = x[k * chunk:min(n, (k + 1) * chunk)].cpu().numpy()
+        q, ok = oracle.quantize(xf, eb)
+        assert ok.all()
+        plan = oracle.frame_plan(q, o)
+        fr = oracle.frame_encode(q, plan["codec"], o, step_bits=step_bits)
+        got = out[int(offs[k]):int(offs[k]) + fr.size].cpu().numpy()
+        assert (got == fr).all()
+    y = torch.empty_like(x)
+    rc, y = sess.decompress(out, r["bytes"], n, eb, out=y)
+    r2 = sess.result()
+    assert rc == 0 and r2["status"] == 0 and r2["bytes"] == r["bytes"] and r2["n_huff"] + r2["n_fixed"] == nfr
+    err = (y.double() - x.double()).abs_().max().item()
+    assert err <= float(np.float32(eb))
