@@ -201,17 +201,34 @@ def test_decompress_rejections(nz):
         if orc:
             keep[16384:32768] = False
         assert (got.view(np.uint32)[keep] == ref.view(np.uint32)[keep]).all()
-    # garbage inside payloads: never faults; status is OK or CORRUPT like the oracle's
+    # garbage inside payloads: never faults; same verdict as the oracle; an accepted stream decodes identically
     rng = np.random.default_rng(3)
-    for _ in range(40):
+    for _ in range(60):
         t = s.copy()
         i = int(rng.integers(off + 32, s.size))
         t[i] ^= int(rng.integers(1, 256))
-        orc = oracle.decompress(t, x.size, eb)[2]
-        r = gpu_decompress(nz, t, x.size, eb, g)[1]
-        assert r["status"] in (nz.OK, nz.ERR_CORRUPT)
+        oref, _, orc = oracle.decompress(t, x.size, eb)
+        rc, r, got = gpu_decompress(nz, t, x.size, eb, g)
+        assert r["status"] == orc, (i, r, orc)
         if orc == 0:
-            assert r["status"] == 0
+            assert (got.view(np.uint32) == oref.view(np.uint32)).all()
+    # the same garbage through the reduce passes (as operand A, as operand B, and as the ring step's incoming stream)
+    go = oracle.make_opts(chunk_elems=16384)
+    for _ in range(20):
+        t = s.copy()
+        i = int(rng.integers(off + 32, s.size))
+        t[i] ^= int(rng.integers(1, 256))
+        for a, b in ((t, s), (s, t)):
+            ored, ores, orc = oracle.reduce_frames(a, b, x.size, eb, go)
+            rc, r, got = gpu_reduce(nz, a, b, x.size, eb, g)
+            assert r["status"] == orc, (i, r, orc)
+            if orc == 0:
+                assert r["bytes"] == ores.bytes and _first_diff(got, ored) == -1
+        ored, ores, orc = oracle.reduce_local(t, x, eb, go)
+        rc, r, got = gpu_reduce_local(nz, t, x, eb, g)
+        assert r["status"] == orc, (i, r, orc)
+        if orc == 0:
+            assert r["bytes"] == ores.bytes and _first_diff(got, ored) == -1
 
 
 # ------------------------------------------------------------------------------------------------
