@@ -190,6 +190,63 @@ def run_c5_overlap(args):
                               serialized_over_overlapped=t_ser / t_ovl)))
 
 
+def run_c4_ring(args):
+    """Config 4: one rank's share of a reduce-scatter ring over 8 peers: 7 fused steps acc = reduce(acc, peer_p) on
+    32 Mi-element messages (eb = 1e-5, 1 MiB frames), peers pre-compressed untimed.  Also the ring-step variant in
+    which the rank adds its own fp32 data (nz_reduce_local).  Prints one JSON line; not part of the headline metric."""
+    import numpy as np
+    import torch
+    from paper_2605_12396_amd import binding as nz, workloads as W
+
+    dev = torch.device("cuda:0")
+    n, eb, peers = 1 << 25, 1e-5, 8
+    opts = nz.make_opts(chunk_elems=262144, alphabet=args.alphabet)
+    sess = nz.Session(n, opts, dev, reduce=True)
+    msgs = [torch.from_numpy(W.gradient_like(n, seed=40 + p, outlier_frac=0.0)).to(dev) for p in range(peers)]
+    streams, sizes = [], []
+    for m in msgs:
+        rc, out = sess.compress(m, eb)
+        r = sess.result()
+        assert rc == 0 and r["status"] == 0
+        streams.append(out); sizes.append(r["bytes"])
+    bufs = [sess.new_stream_buffer() for _ in range(2)]
+
+    def chain(local):
+        acc, acc_bytes, per_step = streams[0], sizes[0], []
+        for p in range(1, peers):
+            ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            ev0.record()
+            if local:
+                rc, out = sess.reduce_local(acc, acc_bytes, msgs[p], n, eb, out=bufs[p % 2])
+            else:
+                rc, out = sess.reduce(acc, acc_bytes, streams[p], sizes[p], n, eb, out=bufs[p % 2])
+            ev1.record()
+            r = sess.result()                                     # synchronises: the next step needs the byte count
+            assert rc == 0 and r["status"] == 0
+            per_step.append(ev0.elapsed_time(ev1))
+            acc, acc_bytes = out, r["bytes"]
+        return per_step, acc_bytes
+
+    chain(False); chain(True)                                     # warm-up
+    reps = max(2, min(args.steps, 5))
+    best = {}
+    for local in (False, True):
+        runs = [chain(local) for _ in range(reps)]
+        steps_ms = [min(r[0][i] for r in runs) for i in range(peers - 1)]
+        best[local] = (steps_ms, runs[0][1])
+    gb = 4.0 * n / 1e9
+    print(json.dumps(dict(metric="fused reduce ring step, GB/s of fp32 input per step (config 4)", unit="GB/s", n_gpus=1,
+                          data="synthetic",
+                          config=dict(workload="c4: 8 peers x 32Mi fp32 Laplace(0,1e-3), eb=1e-5, 1MiB frames, 7 steps",
+                                      alphabet=args.alphabet),
+                          input_compression_ratio=4.0 * n / sizes[0], final_compression_ratio=4.0 * n / best[False][1],
+                          reduce_frames=dict(per_step_ms=best[False][0], total_ms=sum(best[False][0]),
+                                             GBps=gb * (peers - 1) / (sum(best[False][0]) * 1e-3)),
+                          reduce_local=dict(per_step_ms=best[True][0], total_ms=sum(best[True][0]),
+                                            GBps=gb * (peers - 1) / (sum(best[True][0]) * 1e-3)),
+                          final_bytes_equal=bool(best[False][1] == best[True][1]))))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -211,6 +268,8 @@ def main():
 
     if args.workload == "c5":
         return run_c5_overlap(args)
+    if args.workload == "c4ring":
+        return run_c4_ring(args)
 
     import numpy as np
     import torch
