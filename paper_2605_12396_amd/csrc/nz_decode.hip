@@ -61,6 +61,7 @@ struct FrameView {
     uint32_t nwords;
     const uint16_t* segt;
     uint64_t seg_prefix;      // bits before this workgroup's first segment
+    bool dense;               // HUFFMAN: 6 or more bits per symbol on average (the window is renewed every run, not every phase)
 };
 
 // Build-time scratch shared by both operands.
@@ -87,7 +88,7 @@ template <int NT>
 __device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t frame, uint32_t nf, uint32_t first_seg,
                                   const DecodeArgs& A, DecTables* T, BuildScratch* B, FrameView& V) {
     const uint32_t tid = threadIdx.x;
-    V.status = ST_CORRUPT; V.kind = KIND_ZERO; V.w = 0; V.words = nullptr; V.nwords = 0; V.segt = nullptr; V.seg_prefix = 0;
+    V.status = ST_CORRUPT; V.kind = KIND_ZERO; V.w = 0; V.words = nullptr; V.nwords = 0; V.segt = nullptr; V.seg_prefix = 0; V.dense = false;
     const uint64_t off = *reinterpret_cast<const uint64_t*>(s + kStreamHdr + 8ull * frame);
     if ((off & 15u) || off < kStreamHdr + pad16d(8ull * A.n_frames) || off + kHdrBytes > total) return;
     const uint8_t* fr = s + off;
@@ -219,6 +220,7 @@ __device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t fra
     }
     __syncthreads();
     V.status = ST_OK; V.kind = KIND_HUFF; V.segt = segt; V.seg_prefix = pre_bits;
+    V.dense = all_bits >= 6ull * nf;
     V.words = reinterpret_cast<const uint32_t*>(pay + tables); V.nwords = (uint32_t)((payload - tables) / 4);
 }
 
@@ -325,6 +327,24 @@ struct HuffReader {
             lo = P.x[0].x; hi = P.x[0].y; n1 = P.x[0].z; n2 = P.x[0].w;
             win_bit0 = (int32_t)(P.cur & ~31u);
             k = 0; sh = P.cur & 31u;
+        } else reload();
+    }
+    // install() for a window that was requested one run of symbols ago: the lane has moved on since, so its
+    // position is re-expressed inside the new window and the four words at it are read back from the window.  A
+    // lane that has outrun what the window can still serve refills on its own instead.
+    __device__ inline void install_at(const Pending& P) {
+        const uint32_t abs_pos = (uint32_t)(win_bit0 + (int32_t)pos());
+        const uint32_t rel = abs_pos - (P.cur & ~31u);                   // P.cur <= abs_pos: positions only grow
+        if (__builtin_expect(P.ok && rel < kWinRunLimit, 1)) {
+#pragma unroll
+            for (uint32_t c = 0; c < kWinWords / 4; c++) {
+                win[(4 * c + 0) * NT] = P.x[c].x; win[(4 * c + 1) * NT] = P.x[c].y;
+                win[(4 * c + 2) * NT] = P.x[c].z; win[(4 * c + 3) * NT] = P.x[c].w;
+            }
+            win_bit0 = (int32_t)(P.cur & ~31u);
+            k = rel >> 5; sh = rel & 31u;
+            const uint32_t* p = win + k * NT;
+            lo = p[0]; hi = p[NT]; n1 = p[2 * NT]; n2 = p[3 * NT];
         } else reload();
     }
     __device__ inline uint32_t consumed() const { return (uint32_t)(win_bit0 + (int32_t)pos()) - start_bit; }
@@ -531,7 +551,7 @@ struct AddCtx {
 // which leaves kWideMarker in the tile and raises a workgroup flag; only then does the consumer look for
 // markers.
 template <int MODE, int NT>
-__device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader<NT>& ra, DecShared<NT>* S,
+__device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader<NT>& ra, DecShared<NT>* S, bool dense,
                                 const AddCtx& X, bool a_wide, uint32_t (&zmax)[2], uint32_t& overflow) {
     const uint32_t tid = C.tid;
     uint16_t* tile = S->u.tile;
@@ -570,7 +590,11 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
         if (r0 + kTile16R <= C.cntseg) {
 #pragma unroll
             for (uint32_t h = 0; h < kTile16R; h += kRun) {
+                // dense frames (uniform over the workgroup): a phase uses up most of a window, so every run starts
+                // with a window requested at the start of the run before it; the others only watch their margin
+                if (dense && h > 0) ra.install_at(pend);
                 start_run();
+                if (dense && h + kRun < kTile16R) ra.request(pend);
 #pragma unroll
                 for (uint32_t r = 0; r < kRun; r += 2) {
                     const uint32_t q0 = next16(), q1 = next16();
@@ -757,7 +781,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
     if (MODE == MODE_DECOMPRESS && st_a) return;                        // nothing is written on a stream-level error
 
     FrameView V;
-    V.status = ST_OK; V.kind = KIND_ZERO; V.w = 0; V.words = nullptr; V.nwords = 0; V.segt = nullptr; V.seg_prefix = 0;
+    V.status = ST_OK; V.kind = KIND_ZERO; V.w = 0; V.words = nullptr; V.nwords = 0; V.segt = nullptr; V.seg_prefix = 0; V.dense = false;
     if (st_a == ST_OK && st_b == ST_OK) {
         open_frame<NT>(MODE == MODE_ADD_B ? A.b : A.a, MODE == MODE_ADD_B ? total_b : total_a, frame, nf, first_seg, A,
                        &s_t, &S.u.build, V);
@@ -816,7 +840,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
     }
 
     if (V.kind == KIND_HUFF) {
-        run_huff<MODE, NT>(A, C, ra, &S, X, a_wide, zmax, overflow);
+        run_huff<MODE, NT>(A, C, ra, &S, V.dense, X, a_wide, zmax, overflow);
         if (seg_valid && (ra.bad || ra.consumed() != seglen)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
     } else {
         run_elementwise<MODE, NT>(A, C, da, &S, X, zmax, overflow);
