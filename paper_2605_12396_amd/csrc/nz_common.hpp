@@ -110,14 +110,6 @@ __device__ inline void st_agent(uint32_t* p, uint32_t v) {
 // ---- wave64 helpers ----
 __device__ inline uint32_t lane_id() { return __lane_id(); }
 
-__device__ inline uint32_t wave_incl_scan(uint32_t v) {
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        uint32_t t = __shfl_up(v, d, 64);
-        if ((int)lane_id() >= d) v += t;
-    }
-    return v;
-}
 // Inclusive wave scan on the DPP network (no LDS traffic): Kogge-Stone inside each row of 16 lanes, then the
 // last lane of row 0 / 2 is added to row 1 / 3 and the last lane of the lower half to the upper half.
 __device__ inline uint32_t wave_incl_scan_dpp(uint32_t v) {
@@ -127,11 +119,6 @@ __device__ inline uint32_t wave_incl_scan_dpp(uint32_t v) {
     v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, true);   // row_shr:8
     v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false);  // row_bcast:15 into rows 1 and 3
     v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);  // row_bcast:31 into rows 2 and 3
-    return v;
-}
-__device__ inline uint32_t wave_sum(uint32_t v) {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
     return v;
 }
 __device__ inline uint64_t wave_sum64(uint64_t v) {
@@ -147,9 +134,9 @@ __device__ inline uint32_t wave_max(uint32_t v) {
 
 __device__ inline uint32_t zigzag(int32_t q) { return ((uint32_t)q << 1) ^ (uint32_t)(q >> 31); }
 __device__ inline int32_t unzigzag(uint32_t z) { return (int32_t)(z >> 1) ^ -(int32_t)(z & 1u); }
-__device__ inline uint32_t sym_of(uint32_t z, uint32_t K) { return z <= K - 2u ? z + 1u : 0u; }
-// Histogram bin of a zigzag code while counting: one min instead of the compare-and-select above; bin b < K-1
-// counts symbol b + 1 and bin K-1 counts the escape symbol 0 (bin_symbol maps back when the counts are written out).
+// Symbol of a zigzag code: z + 1 for z <= K-2, else the escape symbol 0.  Histogram bin while counting: min(z, K-1),
+// one instruction; bin b < K-1 counts symbol b + 1 and bin K-1 counts the escape symbol (bin_symbol maps back when
+// the counts are written out).  The encoder's codebook is indexed the same way.
 __device__ inline uint32_t bin_of(uint32_t z, uint32_t K) { return z < K - 1u ? z : K - 1u; }
 __device__ inline uint32_t bin_symbol(uint32_t b, uint32_t K) { return b == K - 1u ? 0u : b + 1u; }
 
@@ -174,7 +161,7 @@ __device__ inline float dequantize1(int32_t q, float step) {
 
 // Launchers (one per translation unit).
 struct CompressArgs {
-    const float* in;          // fp32 input (compress) or nullptr (reduce: symbols come from ws codes)
+    const float* in;          // fp32 input (compress) or nullptr (reduce: the sums staged in the workspace are encoded)
     uint64_t n;
     uint32_t chunk, n_frames, K, sbpf, stat_block;
     int32_t force_codec;
