@@ -531,6 +531,13 @@ def test_reduce_local_range_mismatch_capacity(nz):
     ref, ores, _ = oracle.reduce_local(sa, a, eb, o)
     rc, r, _ = gpu_reduce_local(nz, sa, a, eb, g, cap=int(ores.bytes) - 16)
     assert r["status"] == nz.ERR_CAPACITY and r["bytes"] == 0
+    # a broken stream header, a truncated stream
+    t = sa.copy(); t[0] ^= 1
+    assert oracle.reduce_local(t, a, eb, o)[2] == oracle.ERR_CORRUPT
+    rc, r, _ = gpu_reduce_local(nz, t, a, eb, g)
+    assert r["status"] == nz.ERR_CORRUPT and r["bytes"] == 0
+    rc, r, _ = gpu_reduce_local(nz, sa[:-16], a, eb, g)
+    assert r["status"] == oracle.reduce_local(sa[:-16], a, eb, o)[2] == nz.ERR_CORRUPT and r["bytes"] == 0
 
 
 @pytest.mark.parametrize("seed", range(12))
