@@ -619,3 +619,48 @@ def test_more_than_2_to_31_elements(nz):
     assert rc == 0 and r2["status"] == 0 and r2["bytes"] == r["bytes"] and r2["n_huff"] + r2["n_fixed"] == nfr
     err = (y.double() - x.double()).abs_().max().item()
     assert err <= float(np.float32(eb))
+
+
+def test_calls_can_be_captured_in_a_hip_graph(nz):
+    """The entry points only launch kernels (no allocation, no memset, no synchronisation), so a caller may record
+    them into a HIP graph.  Replays -- with eager work and synchronisations in between -- must reproduce the eager
+    result every time."""
+    import torch
+    n, eb = 300000, 1e-4
+    g, o = _opts_pair(nz, chunk_elems=65536)
+    x = W.gradient_like(n, seed=21)
+    peer = oracle.compress(W.gradient_like(n, seed=22), eb, o)[0]
+    ref = oracle.compress(x, eb, o)[0]
+    ref_red = oracle.reduce_frames(ref, peer, n, eb, o)[0]
+    dx = _to_dev(nz, x)
+    dpeer = _to_dev(nz, np.concatenate([peer, np.zeros((-peer.size) % 16, np.uint8)]))
+    sess = nz.Session(n, g, "cuda:0", reduce=True)
+    res_c = torch.zeros(nz.RESULT_BYTES, dtype=torch.uint8, device="cuda:0")
+    res_r = torch.zeros(nz.RESULT_BYTES, dtype=torch.uint8, device="cuda:0")
+    out, red = sess.new_stream_buffer(), sess.new_stream_buffer()
+    y = torch.empty(n, dtype=torch.float32, device="cuda:0")
+
+    def work():
+        assert nz.nz_compress(dx, n, eb, out, sess.cap, res_c, g, sess.ws, sess.ws_bytes) == 0
+        assert nz.nz_decompress(out, ref.size, y, n, eb, sess.res, g) == 0
+        assert nz.nz_reduce_frames(out, ref.size, dpeer, peer.size, red, sess.cap, n, eb, res_r, g, sess.ws, sess.ws_bytes) == 0
+
+    work()                                            # eager, also warms everything up
+    torch.cuda.synchronize()
+    y_ref = oracle.decompress(ref, n, eb)[0]
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        work()
+        graph.capture_end()
+    for rep in range(3):
+        out.zero_(); red.zero_(); y.zero_(); res_c.zero_(); res_r.zero_()      # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        rc_, rr_ = nz.read_result(res_c), nz.read_result(res_r)
+        assert rc_["status"] == 0 and rc_["bytes"] == ref.size and rr_["status"] == 0 and rr_["bytes"] == ref_red.size
+        assert _first_diff(out[:ref.size].cpu().numpy(), ref) == -1, rep
+        assert _first_diff(red[:ref_red.size].cpu().numpy(), ref_red) == -1, rep
+        assert (y.cpu().numpy().view(np.uint32) == y_ref.view(np.uint32)).all(), rep
