@@ -382,7 +382,7 @@ def main():
                     frac=achieved / HBM_PEAK_GBPS, traffic=read_traffic(args.traffic_file, wl["name"], "%s/%s" % dom),
                     kernel_ms=dom_ms, algorithmic_bytes=alg[dom])
 
-    out = dict(metric="compress+decompress+fused-reduce throughput on fp32 input bytes", value=3 * gb / (ms_per_step * 1e-3),
+    out = dict(metric="compress / decompress / fused-reduce GB/s (fp32 input): bytes of the three stages over the step time", value=3 * gb / (ms_per_step * 1e-3),
                unit="GB/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step,
                higher_is_better=True, scaling="weak", vs_baseline=None, dtype="f32+i32", data="synthetic",
                config=dict(workload=wl["desc"], n_elems=n, chunk_elems=wl["chunk"], alphabet=args.alphabet, eb=eb),
