@@ -11,7 +11,7 @@ import numpy as np
 
 from . import build as _build
 
-OK, ERR_INVALID, ERR_CAPACITY, ERR_RANGE, ERR_CORRUPT, ERR_MISMATCH = 0, 1, 2, 3, 4, 5
+OK, ERR_INVALID, ERR_CAPACITY, ERR_CORRUPT, ERR_MISMATCH = 0, 1, 2, 3, 4
 RAW, FIXEDLEN, HUFFMAN = 0, 1, 2
 HDR_BYTES = 32
 STREAM_HDR = 64

@@ -49,8 +49,7 @@
 /* ------------------------------------------------------------------ */
 
 /* Status codes are ordered by precedence: when several conditions hold the largest code is reported. */
-enum { NZO_OK = 0, NZO_ERR_INVALID = 1, NZO_ERR_CAPACITY = 2, NZO_ERR_RANGE = 3, NZO_ERR_CORRUPT = 4,
-       NZO_ERR_MISMATCH = 5 };
+enum { NZO_OK = 0, NZO_ERR_INVALID = 1, NZO_ERR_CAPACITY = 2, NZO_ERR_CORRUPT = 3, NZO_ERR_MISMATCH = 4 };
 
 enum { NZO_RAW = 0, NZO_FIXEDLEN = 1, NZO_HUFFMAN = 2 };
 
@@ -718,7 +717,7 @@ int nzo_decompress(const uint8_t* s, size_t bytes, float* out, size_t n, float e
 
 typedef struct {
     const int32_t* qa; const int32_t* qb; const uint32_t* ra; const uint32_t* rb;
-    const uint8_t* fa; const uint8_t* fb; float step; int overflow;
+    const uint8_t* fa; const uint8_t* fb; float step;
 } reduce_ctx;
 
 static uint32_t canon_sum_bits(float a, float b) {
@@ -730,19 +729,22 @@ static uint32_t canon_sum_bits(float a, float b) {
 
 /*
  * Frame k of the output: both inputs coded -> Q = qa + qb exactly (64-bit), re-planned and re-selected on
- * Q; a sum with |Q| > 2^30 cannot be carried further and makes the whole call fail with NZO_ERR_RANGE.
+ * Q.  A frame in which some |Q| > 2^30 cannot be carried further as integer codes; like every frame the
+ * entropy paths cannot take, it is committed as RAW (the safe fallback of Sec. IV-C / Algorithm 1,
+ * CommitRawOrFail) and holds fl32(fl32(qa*step) + fl32(qb*step)) for every element.
  * Either input RAW -> RAW frame holding the fp32 sum of the two (dequantized or raw) values.
  */
 static int reduce_src(void* vctx, uint32_t k, uint64_t i0, uint32_t nf, int32_t* q, uint32_t* rbits) {
     reduce_ctx* c = (reduce_ctx*)vctx;
     const int a_raw = c->fa[k] == 1, b_raw = c->fb[k] == 1;
-    if (!a_raw && !b_raw) {
+    int coded = !a_raw && !b_raw;
+    if (coded) {
         for (uint32_t i = 0; i < nf; i++) {
             int64_t Q = (int64_t)c->qa[i0 + i] + (int64_t)c->qb[i0 + i];
-            if (Q > NZO_QSUM_MAX || Q < -(int64_t)NZO_QSUM_MAX) { c->overflow = 1; Q = 0; }
+            if (Q > NZO_QSUM_MAX || Q < -(int64_t)NZO_QSUM_MAX) { coded = 0; break; }
             q[i] = (int32_t)Q;
         }
-        return 1;
+        if (coded) return 1;
     }
     for (uint32_t i = 0; i < nf; i++) {
         float va = a_raw ? bits_f32(c->ra[i0 + i]) : nzo_dequantize_one(c->qa[i0 + i], c->step);
@@ -774,14 +776,8 @@ int nzo_reduce_frames(const uint8_t* a, size_t a_bytes, const uint8_t* b, size_t
     if (!rc) rc = nzo_decode_codes(a, a_bytes, n, eb, qa, ra, fa, NULL);
     if (!rc) rc = nzo_decode_codes(b, b_bytes, n, eb, qb, rb, fb, NULL);
     if (!rc) {
-        reduce_ctx c = { qa, qb, ra, rb, fa, fb, step, 0 };
+        reduce_ctx c = { qa, qb, ra, rb, fa, fb, step };
         rc = emit_stream(reduce_src, &c, n, &o, f32_bits(step), out, cap, res);
-        if (c.overflow) {                       /* RANGE outranks CAPACITY; nothing is published */
-            rc = NZO_ERR_RANGE;
-            uint32_t nfr = res->n_frames;
-            memset(res, 0, sizeof *res);
-            res->n_frames = nfr; res->status = NZO_ERR_RANGE;
-        }
     } else {
         res->status = (uint32_t)rc;
     }
@@ -801,7 +797,8 @@ int nzo_reduce_frames(const uint8_t* a, size_t a_bytes, const uint8_t* b, size_t
  * quantize it (one unquantizable element makes its frame "raw": the original fp32 words stand for it), and
  * then takes the place of operand B of nzo_reduce_frames: both coded -> exact integer sum of the codes,
  * re-planned and re-selected; incoming frame RAW or local frame raw -> RAW frame of fp32 sums of the
- * (dequantized or raw) values.  |Q| > 2^30 in a coded frame -> NZO_ERR_RANGE.
+ * (dequantized or raw) values.  |Q| > 2^30 in a coded frame -> that frame is RAW and holds the fp32 sums of
+ * the two dequantized values (as in nzo_reduce_frames).
  */
 int nzo_reduce_local(const uint8_t* in, size_t in_bytes, const float* local, uint8_t* out, size_t cap,
                      size_t n, float eb, const nzo_opts* opts, nzo_result* res) {
@@ -832,14 +829,8 @@ int nzo_reduce_local(const uint8_t* in, size_t in_bytes, const float* local, uin
             }
             fb[k] = all_ok ? 0 : 1;
         }
-        reduce_ctx c = { qa, qb, ra, rb, fa, fb, step, 0 };
+        reduce_ctx c = { qa, qb, ra, rb, fa, fb, step };
         rc = emit_stream(reduce_src, &c, n, &o, f32_bits(step), out, cap, res);
-        if (c.overflow) {                       /* RANGE outranks CAPACITY; nothing is published */
-            rc = NZO_ERR_RANGE;
-            uint32_t nfr = res->n_frames;
-            memset(res, 0, sizeof *res);
-            res->n_frames = nfr; res->status = NZO_ERR_RANGE;
-        }
     } else {
         res->status = (uint32_t)rc;
     }

@@ -41,6 +41,25 @@ def test_quantizer_worked_values():
     assert xh.tolist() == [float(r[2]) for r in rows]
 
 
+def test_quantizer_exact_ties_round_to_even():
+    """Exact ties x/step = k + 1/2 (tests/golden/quantizer_ties.txt): with eb = fl32(32/63) both step and 1/step are
+    exactly 1.0 in fp32, so x = k + 0.5 is a tie with no rounding slack; the format rounds half to even."""
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "quantizer_ties.txt")) if l.strip() and l[0] != "#"]
+    eb = float(np.float32(32.0 / 63.0))
+    assert eb == 0.5079365372657776
+    step, inv = oracle.step_constants(eb)
+    assert float(step) == 1.0 and float(inv) == 1.0
+    x = np.array([float(r[0]) for r in rows], np.float32)
+    q, ok = oracle.quantize(x, eb)
+    assert ok.all()
+    assert q.tolist() == [int(r[1]) for r in rows]
+    assert oracle.dequantize(q, eb).tolist() == [float(r[2]) for r in rows]
+    # a frame made of ties only goes through compress / decompress with the same codes
+    s, res, rc = oracle.compress(x, eb, oracle.make_opts(chunk_elems=8))
+    y, _, rc2 = oracle.decompress(s, x.size, eb)
+    assert rc == 0 and rc2 == 0 and y.tolist() == [float(r[2]) for r in rows]
+
+
 @pytest.mark.parametrize("eb,scale", [(1e-4, 1.0), (1e-5, 1e-3), (2.7e-4, 0.3), (3.0, 5e4), (1e-30, 1e-26),
                                       (0.5, 16000.0), (1e-4, 3.2)])
 def test_error_bound_float64(eb, scale):
@@ -588,26 +607,101 @@ def test_reduce_raw_and_overflow_paths():
     qa = oracle.quantize(a[:1000], eb)[0]; qb = oracle.quantize(b[:1000], eb)[0]
     qd, _, kinds, _, _ = oracle.decode_codes(r, n, eb)
     assert kinds.tolist() == [0, 1, 1] and (qd[:1000] == qa + qb).all()
-    # overflow: doubling a stream 15 times reaches 32767 * 2^15 < 2^30; once more exceeds 2^30 -> RANGE error
-    x = np.zeros(1000, np.float32)
+    # overflow: doubling a stream 15 times reaches 32767 * 2^15 < 2^30; once more exceeds 2^30: the frame can no
+    # longer be carried as integer codes and is committed as RAW (Sec. IV-C safe fallback) holding the fp32 sums of
+    # the dequantized operands; the other frames of the message stay coded
+    x = W.gradient_like(3000, seed=72)
+    x[:1000] = 0.0
     step, _ = oracle.step_constants(eb)
     x[7] = np.float32(32767.0) * step
     s = oracle.compress(x, eb, opts)[0]
+    q0 = oracle.quantize(x, eb)[0].astype(np.int64)
     for i in range(15):
-        s2, res, rc = oracle.reduce_frames(s, s, 1000, eb, opts)
+        s2, res, rc = oracle.reduce_frames(s, s, 3000, eb, opts)
         assert rc == 0 and res.n_raw == 0
         s = s2
-    qd = oracle.decode_codes(s, 1000, eb)[0]
-    assert qd[7] == 32767 << 15
-    out = oracle.decompress(s, 1000, eb)[0]
+    qd = oracle.decode_codes(s, 3000, eb)[0]
+    assert qd[7] == 32767 << 15 and (qd == q0 << 15).all()
+    out = oracle.decompress(s, 3000, eb)[0]
     assert out[7] == np.float32(np.float32(32767 << 15) * step) and not out[:7].any()
-    s2, res, rc = oracle.reduce_frames(s, s, 1000, eb, opts)
-    assert rc == oracle.ERR_RANGE and res.bytes == 0 and res.status == oracle.ERR_RANGE
+    s2, res, rc = oracle.reduce_frames(s, s, 3000, eb, opts)
+    assert rc == 0 and res.status == 0 and (res.n_raw, res.n_frames) == (1, 3)
+    qd2, rb2, kinds2, _, _ = oracle.decode_codes(s2, 3000, eb)
+    assert kinds2.tolist() == [1, 0, 0] and (qd2[1000:] == q0[1000:] << 16).all()
+    v = (qd[:1000].astype(np.float32) * step).astype(np.float32)               # dequantized operand, fp32 product
+    assert (rb2[:1000] == (v + v).astype(np.float32).view(np.uint32)).all()
+    assert oracle.decompress(s2, 3000, eb)[0][7] == np.float32(2.0) * np.float32(np.float32(32767 << 15) * step)
+    # the threshold itself: |Q| = 2^30 is still an integer code, 2^30 + 1 is not
+    y = np.zeros(1000, np.float32); y[3] = step; y[4] = -step                    # codes +1 / -1
+    t = oracle.compress(y, eb, opts)[0]
+    for i in range(29):
+        t = oracle.reduce_frames(t, t, 1000, eb, opts)[0]                       # codes +-2^29
+    t30, res, rc = oracle.reduce_frames(t, t, 1000, eb, opts)
+    assert rc == 0 and res.n_raw == 0 and oracle.decode_codes(t30, 1000, eb)[0][[3, 4]].tolist() == [1 << 30, -(1 << 30)]
+    t1 = oracle.compress(y, eb, opts)[0]
+    over, res, rc = oracle.reduce_frames(t30, t1, 1000, eb, opts)               # 2^30 + 1 and -(2^30 + 1)
+    assert rc == 0 and res.n_raw == 1
+    rb = oracle.decode_codes(over, 1000, eb)[1]
+    big = np.float32(np.float32(1 << 30) * step)
+    assert rb[3] == np.float32(big + step).view(np.uint32) and rb[4] == np.float32(-big - step).view(np.uint32)
+    # a RAW frame stays RAW in later steps and adds in fp32
+    again, res, rc = oracle.reduce_frames(over, t1, 1000, eb, opts)
+    assert rc == 0 and res.n_raw == 1
+    assert oracle.decode_codes(again, 1000, eb)[1][3] == np.float32(np.float32(big + step) + step).view(np.uint32)
     # mismatching operands
     sc = oracle.compress(a, 2e-3, opts)[0]
     assert oracle.reduce_frames(sa, sc, n, eb, opts)[2] == oracle.ERR_MISMATCH
     sd = oracle.compress(a, eb, oracle.make_opts(chunk_elems=500))[0]
     assert oracle.reduce_frames(sa, sd, n, eb, opts)[2] == oracle.ERR_MISMATCH
+
+
+def test_zero_bit_huffman_frame_is_corrupt():
+    """A crafted HUFFMAN frame with a valid header, legal code lengths and an all-zero segment table (payload ends
+    after the tables) must be rejected: every symbol costs at least one bit (Algorithm 2, ValidateHeader /
+    DecodeOrMemcpy).  The rejected frame's output is zero-filled."""
+    from crafted import zero_bit_huffman_stream
+    eb = 1e-3
+    step_bits = int(np.float32(oracle.step_constants(eb)[0]).view(np.uint32))
+    for n in (1, 256, 300, 5000):
+        t = zero_bit_huffman_stream(n, step_bits)
+        out, res, rc = oracle.decompress(t, n, eb)
+        assert rc == oracle.ERR_CORRUPT and res.status == oracle.ERR_CORRUPT and not out.any()
+    # the same container with a 1-bit-per-symbol payload is accepted (the rejection is about the missing bits)
+    from crafted import frame_header, single_frame_stream
+    n = 300
+    ones = np.zeros(4 * ((n + 31) // 32), np.uint8)                   # n one-bits: symbol 1 (code 1) = zigzag code 0
+    ones[:n // 8] = 0xFF; ones[n // 8] = (1 << (n % 8)) - 1
+    payload = bytes([1, 1, 0, 0]) + np.array([256, 44], np.uint16).tobytes() + ones.tobytes()
+    fr = frame_header(2, 4 * n, len(payload), 2, 256 | (256 << 16), step_bits) + payload
+    out, res, rc = oracle.decompress(single_frame_stream(n, n, step_bits, fr), n, eb)
+    assert rc == 0 and res.n_huff == 1 and not out.any()
+
+
+def test_pinned_huffman_bound_covers_worst_case_streams():
+    """nzo_compress_bound with HUFFMAN pinned: a frame whose every symbol escapes (K = 2, no zero codes) spends
+    1 + 32 bits per symbol, more than RAW, so the all-RAW bound does not cover it; the pinned bound must, and the
+    stream must really be that large (Algorithm 1 capacity guard)."""
+    n = 5000
+    x = (np.arange(n) % 7 + 3).astype(np.float32)                     # codes >= 3: all escape under K = 2
+    eb = float(np.float32(32.0 / 63.0))                               # step = 1
+    for chunk in (1000, 4096, 5000):
+        o = oracle.make_opts(chunk_elems=chunk, alphabet=2, force_codec=2)
+        s, res, rc = oracle.compress(x, eb, o)
+        assert rc == 0 and res.n_huff == res.n_frames
+        raw_bound = oracle.compress_bound(n, oracle.make_opts(chunk_elems=chunk, alphabet=2))
+        assert s.size > raw_bound - 64 * res.n_frames                 # about 33 bits per symbol: RAW-sized or more
+        assert 33 * n // 8 <= s.size <= oracle.compress_bound(n, o)
+        y, _, rc2 = oracle.decompress(s, n, eb)
+        assert rc2 == 0 and (y == x).all()
+    # deepest codes: Fibonacci counts make the rarest symbols 27 bits long; an escape then costs 27 + 32 <= 60 bits
+    fib = [1, 1]
+    while len(fib) < 28:
+        fib.append(fib[-1] + fib[-2])
+    q = np.concatenate([np.full(c, (i + 1) // 2 * (1 if i % 2 else -1)) for i, c in enumerate(fib)])   # zigzag code i
+    assert q.size <= 1 << 20
+    o = oracle.make_opts(chunk_elems=1 << 20, alphabet=32, force_codec=2)
+    plan = oracle.frame_plan(q.astype(np.int32), o)
+    assert plan["len"].max() == 27 and plan["totals"][2] <= oracle.compress_bound(q.size, o)
 
 
 # ----------------------------------------------------------------------------
@@ -714,6 +808,11 @@ def test_reduce_local_raw_values_range_and_mismatch():
         s = oracle.reduce_frames(s, s, 1000, eb, o1)[0]
     s1, _, rc = oracle.reduce_local(s, z, eb, o1)                # 32767 * 2^15 + 32767 = 2^30 - 1: still carried
     assert rc == 0 and oracle.decode_codes(s1, 1000, eb)[0][7] == (1 << 30) - 1
-    assert oracle.reduce_local(s1, z, eb, o1)[2] == oracle.ERR_RANGE
+    s2, res2, rc = oracle.reduce_local(s1, z, eb, o1)            # 2^30 + 32766: the frame is committed as RAW
+    assert rc == 0 and res2.n_raw == 1
+    v = np.float32(np.float32((1 << 30) - 1) * np.float32(step)) + np.float32(np.float32(32767) * np.float32(step))
+    assert oracle.decode_codes(s2, 1000, eb)[1][7] == np.float32(v).view(np.uint32)
+    assert oracle.reduce_frames(s1, oracle.compress(z, eb, o1)[0], 1000, eb, o1)[0].tobytes() == s2.tobytes()
     z2 = z.copy(); z2[7] = -z[7]
-    assert oracle.reduce_local(s1, z2, eb, o1)[2] == 0
+    s3, res3, rc = oracle.reduce_local(s1, z2, eb, o1)
+    assert rc == 0 and res3.n_raw == 0
