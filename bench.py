@@ -331,9 +331,9 @@ def main():
     reduce_bytes = rr["bytes"]
 
     # per-stage and per-kernel times from HIP events the library records on its stream
-    names = {"compress": ["stats", "codebook", "encode"], "decompress": ["init", "decode"],
-             "reduce": ["init", "stage_a", "add_b", "codebook", "encode"],
-             "reduce_local": ["init", "add_local", "fix_local", "codebook", "encode"]}
+    names = {"compress": ["stats", "codebook", "encode"], "decompress": ["decode", "finish"],
+             "reduce": ["init", "stage_a", "add_b", "fix", "codebook", "encode"],
+             "reduce_local": ["init", "add_local", "fix", "codebook", "encode"]}
     acc = {k: [0.0] * len(v) for k, v in names.items()}
     reps = max(5, min(args.steps, 20))
     with nz.KernelTrace(8) as tr:

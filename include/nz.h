@@ -16,6 +16,8 @@
  *     state between calls, enqueues its kernels on `stream` (a hipStream_t
  *     passed as void*) and never synchronises it.  Two calls may run
  *     concurrently only if they use different workspaces and outputs.
+ *     (The optional benchmark aid in nz_trace.h is the one exception: it
+ *     keeps a per-host-thread pointer while armed.)
  *   - The return value reports what the host can check before launching
  *     (NZ_ERR_INVALID arguments, a workspace or output too small to hold even
  *     the stream header, a failed launch = NZ_ERR_HIP).  Everything detected
@@ -41,10 +43,9 @@ typedef enum {
     NZ_OK           = 0,
     NZ_ERR_INVALID  = 1,   /* bad argument (n = 0, eb out of range, misaligned pointer, bad opts)        */
     NZ_ERR_CAPACITY = 2,   /* output does not fit out_cap: nothing is published (Algorithm 1 returns 0) */
-    NZ_ERR_RANGE    = 3,   /* reduce: an integer sum exceeded 2^30 in magnitude                         */
-    NZ_ERR_CORRUPT  = 4,   /* a stream or frame failed validation (Algorithm 2, ValidateHeader)         */
-    NZ_ERR_MISMATCH = 5,   /* n, frame size, alphabet or quantization step differ from the stream's     */
-    NZ_ERR_HIP      = 6    /* a HIP launch failed (host return value only)                              */
+    NZ_ERR_CORRUPT  = 3,   /* a stream or frame failed validation (Algorithm 2, ValidateHeader)         */
+    NZ_ERR_MISMATCH = 4,   /* n, frame size, alphabet or quantization step differ from the stream's     */
+    NZ_ERR_HIP      = 5    /* a HIP launch failed (host return value only)                              */
 } nz_status;
 
 typedef enum { NZ_CODEC_RAW = 0, NZ_CODEC_FIXEDLEN = 1, NZ_CODEC_HUFFMAN = 2 } nz_codec;
@@ -53,8 +54,10 @@ typedef enum { NZ_CODEC_RAW = 0, NZ_CODEC_FIXEDLEN = 1, NZ_CODEC_HUFFMAN = 2 } n
 typedef struct {
     uint32_t chunk_elems;      /* fp32 elements per frame, 1..2^20 (the paper's frame is one 4 MiB channel
                                   buffer, Sec. IV-D "8-slot batching"); default 262144 (1 MiB)              */
-    uint32_t seg_syms;         /* symbols per independently decodable Huffman segment; this build
-                                  supports 256 only (0 or 256)                                              */
+    uint32_t seg_syms;         /* symbols per independently decodable Huffman segment.  The stream format
+                                  allows 32..1024; these kernels encode and decode one segment per wavefront
+                                  pass (64 lanes x 4 symbols), so only 256 (or 0 = default) is accepted and
+                                  any other value is NZ_ERR_INVALID from every entry point                  */
     uint32_t alphabet;         /* Huffman alphabet K (escape + K-1 symbols), power of two 2..1024;
                                   default 256 (the paper's selector profiles a 256-bin histogram, Sec. IV-C) */
     int32_t  force_codec;      /* -1 = arbitrate; 0/1/2 pin RAW/FIXEDLEN/HUFFMAN as the paper does for its
@@ -73,8 +76,10 @@ typedef struct {
     uint32_t reserved;
 } nz_result;
 
-/* Host, pure.  Worst-case stream bytes for n elements: every frame RAW (a pinned HUFFMAN can exceed that
- * and is bounded at 60 bits per symbol instead).  0 when n = 0 or opts are invalid. */
+/* Host, pure.  Capacity that always suffices (the payload budget of Algorithm 1, lines 1-4: a frame is
+ * committed only if it fits, and RAW must fit for the safe fallback to exist): every frame RAW.  A pinned
+ * HUFFMAN can exceed RAW and is bounded at 60 bits per symbol (a 28-bit code plus the 32 bits of an escaped
+ * value).  0 when n = 0 or opts are invalid. */
 size_t nz_compress_bound(size_t n, const nz_opts* opts);
 
 /* Host, pure.  Workspace bytes nz_compress / nz_decompress need for n elements (0 on invalid opts). */
@@ -100,12 +105,18 @@ nz_status nz_compress(const float* d_in, size_t n, float eb, void* d_out, size_t
                       const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream);
 
 /*
- * Validate and decode an NZ stream into d_out[0..n): xhat = fl32(float(q) *
+ * Receiver side of Algorithm 2 (ParseHeader, ValidateHeader, DecodeOrMemcpy):
+ * validate and decode an NZ stream into d_out[0..n): xhat = fl32(float(q) *
  * step); RAW frames are copied through.  n, eb and opts (chunk_elems,
  * alphabet) must be the ones the stream was produced with, otherwise
- * NZ_ERR_MISMATCH; a stream header or frame that fails validation sets
- * NZ_ERR_CORRUPT, the other frames are still decoded and the output range of a
- * rejected frame is unspecified (but written only inside its own range).
+ * NZ_ERR_MISMATCH and nothing is written.  A stream header that fails
+ * validation sets NZ_ERR_CORRUPT and nothing is written.  A frame that fails
+ * validation -- at its header, or because a segment does not use exactly its
+ * recorded bits -- sets NZ_ERR_CORRUPT, is not counted in n_raw/n_fixed/n_huff
+ * and its whole output range is filled with zeros (the paper's receiver copies
+ * rawBytes from an invalid frame; this format never hands bytes of an
+ * untrusted frame to the caller); the other frames are decoded normally.
+ *   d_ws/ws_bytes  device scratch of at least nz_workspace_bytes(n, opts).
  */
 nz_status nz_decompress(const void* d_stream, size_t stream_bytes, float* d_out, size_t n, float eb,
                         nz_result* d_res, const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream);
@@ -115,8 +126,11 @@ nz_status nz_decompress(const void* d_stream, size_t stream_bytes, float* d_out,
  * frame: the output decodes to qa+qb exactly, so no lossy step is repeated
  * (Sec. III "Error propagation").  A and B must have been produced with the
  * same n, eb and opts.  If either input frame is RAW the output frame is RAW
- * and holds the fp32 sum (NaN sums stored as 0x7FC00000).  A sum beyond 2^30
- * in magnitude sets NZ_ERR_RANGE and publishes nothing.
+ * and holds the fp32 sum (NaN sums stored as 0x7FC00000).  A frame in which a
+ * sum exceeds 2^30 in magnitude can no longer be carried as integer codes: it
+ * is committed as RAW (the selector's safe fallback, Sec. IV-C) and holds
+ * fl32(fl32(qa*step) + fl32(qb*step)).
+ *   d_ws/ws_bytes  device scratch of at least nz_reduce_workspace_bytes(n, opts).
  */
 nz_status nz_reduce_frames(const void* d_a, size_t a_bytes, const void* d_b, size_t b_bytes, void* d_out,
                            size_t out_cap, size_t n, float eb, nz_result* d_res, const nz_opts* opts,
@@ -137,17 +151,6 @@ nz_status nz_reduce_frames(const void* d_a, size_t a_bytes, const void* d_b, siz
 nz_status nz_reduce_local(const void* d_in, size_t in_bytes, const float* d_local, void* d_out, size_t out_cap,
                           size_t n, float eb, nz_result* d_res, const nz_opts* opts, void* d_ws, size_t ws_bytes,
                           void* stream);
-
-/*
- * Profiling aid for benchmarks (not part of the paper's path).  While armed for the calling thread, every
- * entry point above records events[0] on its stream before its first kernel and events[i] after its i-th
- * kernel, up to `count` events (hipEvent_t handles created by the caller, host array).  nz_trace_recorded()
- * returns how many events the last call recorded.  nz_trace_events(NULL, 0) disarms.  Kernel order:
- * compress = init, stats, codebook, encode; decompress = init, decode; reduce = init, decode+add, codebook,
- * encode.
- */
-void   nz_trace_events(void** events, size_t count);
-size_t nz_trace_recorded(void);
 
 /* Library version (format version in the high 16 bits, build in the low 16). */
 uint32_t nz_version(void);

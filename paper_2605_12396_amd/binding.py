@@ -10,7 +10,7 @@ import os
 
 import torch
 
-OK, ERR_INVALID, ERR_CAPACITY, ERR_RANGE, ERR_CORRUPT, ERR_MISMATCH, ERR_HIP = range(7)
+OK, ERR_INVALID, ERR_CAPACITY, ERR_CORRUPT, ERR_MISMATCH, ERR_HIP = range(6)
 RAW, FIXEDLEN, HUFFMAN = 0, 1, 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))

@@ -1,6 +1,7 @@
 // nz_api.hip -- extern "C" boundary: argument checks, workspace carve-up and kernel launches.
 // Host code only validates and launches; every step of the path runs in the kernels.
 #include "../../include/nz.h"
+#include "../../include/nz_trace.h"
 #include "nz_common.hpp"
 
 using namespace nz;
@@ -134,20 +135,22 @@ nz_status nz_decompress(const void* d_stream, size_t stream_bytes, float* d_out,
                         nz_result* d_res, const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream) {
     Opts o; float step, inv;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    (void)d_ws; (void)ws_bytes;                                 // decoding needs no scratch
-    if (!d_stream || !d_out || !d_res || !resolve(opts, o) || !geometry_ok(n, o) || !step_constants(eb, step, inv))
+    if (!d_stream || !d_out || !d_res || !d_ws || !resolve(opts, o) || !geometry_ok(n, o) || !step_constants(eb, step, inv))
         return NZ_ERR_INVALID;
-    if (!aligned16(d_stream) || !aligned16(d_out) || !aligned16(d_res)) return NZ_ERR_INVALID;
+    if (!aligned16(d_stream) || !aligned16(d_out) || !aligned16(d_res) || !aligned16(d_ws)) return NZ_ERR_INVALID;
+    const WsLayout L = ws_layout(n, o.chunk, kStatBlock, false);     // one verdict word per decode workgroup
+    if (ws_bytes < L.total) return NZ_ERR_INVALID;
     const uint32_t nfr = (uint32_t)((n + o.chunk - 1) / o.chunk);
     DecodeArgs A;
     A.a = reinterpret_cast<const uint8_t*>(d_stream); A.a_bytes = stream_bytes; A.b = nullptr; A.b_bytes = 0;
     A.out = d_out; A.local = nullptr; A.eb = eb; A.inv_step = 0.0f; A.n = n; A.chunk = o.chunk; A.n_frames = nfr; A.K = o.K;
     A.dbpf = (o.chunk + kDecBlock - 1) / kDecBlock;
-    A.step = step; A.step_bits = bits_of(step); A.ws = nullptr; A.L = WsLayout(); A.res = d_res;
+    A.step = step; A.step_bits = bits_of(step); A.ws = reinterpret_cast<uint8_t*>(d_ws); A.L = L; A.res = d_res;
+    static_assert(kDecBlock == kStatBlock, "the verdict words reuse the per-statistics-block slots of the workspace");
     trace_reset(); trace_mark(st);
-    if (launch_init(nullptr, 0, d_res, nfr, NZ_OK, st) != hipSuccess) return NZ_ERR_HIP;
-    trace_mark(st);
     if (launch_decode(A, 0, st) != hipSuccess) return NZ_ERR_HIP;
+    trace_mark(st);
+    if (launch_decode_finish(A, st) != hipSuccess) return NZ_ERR_HIP;   // result record; rejected frames zero-filled
     trace_mark(st);
     return NZ_OK;
 }
@@ -191,14 +194,14 @@ static nz_status reduce_impl(const void* d_a, size_t a_bytes, const void* d_b, s
     if (d_local) {
         if (launch_decode(D, 3, st) != hipSuccess) return NZ_ERR_HIP;       // decode incoming + quantize local + add
         trace_mark(st);
-        if (launch_fix_local(D, st) != hipSuccess) return NZ_ERR_HIP;       // frames the local data turns RAW; range error
-        trace_mark(st);
     } else {
         if (launch_decode(D, 1, st) != hipSuccess) return NZ_ERR_HIP;       // stage operand A
         trace_mark(st);
         if (launch_decode(D, 2, st) != hipSuccess) return NZ_ERR_HIP;       // decode operand B + add
         trace_mark(st);
     }
+    if (launch_fix(D, st) != hipSuccess) return NZ_ERR_HIP;                 // frames that turn RAW late (local data, sums past 2^30)
+    trace_mark(st);
     if (launch_codebook(A, st) != hipSuccess) return NZ_ERR_HIP;
     trace_mark(st);
     if (launch_encode(A, true, st) != hipSuccess) return NZ_ERR_HIP;

@@ -20,7 +20,7 @@ constexpr uint32_t kMaxK          = 1024;
 constexpr uint32_t kSeg           = 256;         // symbols per Huffman segment (one wave pass of 4 symbols/lane)
 constexpr uint32_t kMaxLen        = 28;          // deepest optimal code for <= 2^20 symbols (Fibonacci bound)
 
-enum : uint32_t { ST_OK = 0, ST_INVALID = 1, ST_CAPACITY = 2, ST_RANGE = 3, ST_CORRUPT = 4, ST_MISMATCH = 5 };
+enum : uint32_t { ST_OK = 0, ST_INVALID = 1, ST_CAPACITY = 2, ST_CORRUPT = 3, ST_MISMATCH = 4 };
 enum : uint32_t { CODEC_RAW = 0, CODEC_FIXED = 1, CODEC_HUFF = 2 };
 
 // ---- launch geometry ----
@@ -194,6 +194,7 @@ hipError_t launch_stats(const CompressArgs& A, hipStream_t st);
 hipError_t launch_codebook(const CompressArgs& A, hipStream_t st);
 hipError_t launch_encode(const CompressArgs& A, bool from_codes, hipStream_t st);
 hipError_t launch_decode(const DecodeArgs& A, int pass, hipStream_t st);   // 0 decompress, 1 / 2 reduce passes, 3 ring-step add
-hipError_t launch_fix_local(const DecodeArgs& A, hipStream_t st);
+hipError_t launch_fix(const DecodeArgs& A, hipStream_t st);
+hipError_t launch_decode_finish(const DecodeArgs& A, hipStream_t st);
 
 }  // namespace nz

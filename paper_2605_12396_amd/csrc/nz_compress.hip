@@ -159,6 +159,8 @@ __global__ __launch_bounds__(kBookThreads) void k_codebook(CompressArgs A) {
         const uint2 pm = reinterpret_cast<const uint2*>(A.ws + A.L.pmeta)[(size_t)fid * A.sbpf + tid];
         atomicMax(&s_zmax, pm.x);
         atomicMax(&s_unq, pm.y);
+        // reduce: a sum beyond 2^30 somewhere in the frame has turned it RAW (its fp32 sums were staged by k_fix)
+        if (!A.in) atomicMax(&s_unq, reinterpret_cast<const uint32_t*>(A.ws + A.L.cwide)[(size_t)fid * A.sbpf + tid] & 2u);
     }
     const bool used = f > 0;
     {

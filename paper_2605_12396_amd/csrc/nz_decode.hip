@@ -155,6 +155,7 @@ __device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t fra
     if ((r0 >> 48) || kraft == 0 || kraft > (1ull << kMaxLen)) return;
     const uint64_t avail = 8ull * (payload - tables);
     if (all_bits > avail || 4ull * ((all_bits + 31u) / 32u) != payload - tables) return;
+    if (all_bits < nf) return;            // every symbol costs at least one bit (so the bitstream is never empty here)
     // canonical tables and the first-level lookup
     uint32_t* s_cnt = T->cnt; uint32_t* s_first = T->first; uint32_t* s_idx0 = T->idx0;
     canonical_tables<NT>(B->len, K, B->wcnt, s_cnt, s_first, s_idx0, B->rank);
@@ -245,7 +246,6 @@ constexpr uint32_t kWinBits = 32 * kWinWords;
 // before the next check, and the escape's raw word is read there: kWinSlowLimit + 77 + 28 < kWinBits - 32.
 constexpr uint32_t kWinSlowLimit = kWinBits - 32 - 77 - 28 - 7;      // 240 for 12 words
 constexpr uint32_t kWinRunLimit = kWinSlowLimit - 16;                // reload at a run start when this far in
-constexpr uint32_t kWinOverRows = 2;                                 // rows a prefetch may reach past the window
 
 template <int NT>
 struct HuffReader {
@@ -261,7 +261,7 @@ struct HuffReader {
     __device__ inline void init(const FrameView& V, const DecTables* tables, uint32_t bitpos, const void* safe16,
                                 uint32_t* lane_window) {
         T = tables; bad = 0; win = lane_window; start_bit = bitpos;
-        if (V.nwords == 0 || V.kind != KIND_HUFF) {                      // nothing to read: point at valid memory
+        if (V.nwords == 0 || V.kind != KIND_HUFF) {                      // not a HUFFMAN frame: the reader is never used
             bits_addr = reinterpret_cast<uint64_t>(safe16); nwords = 1;
         } else {
             bits_addr = reinterpret_cast<uint64_t>(V.words); nwords = V.nwords;
@@ -303,8 +303,9 @@ struct HuffReader {
     // Scheduled refill in two halves, so that the global-load latency passes while the workgroup does something
     // else (its output phase): request() issues the loads for the window at the current position, install()
     // makes it the lane's window.  A lane too close to the end of the bitstream for 16-byte loads reads a
-    // harmless 48 bytes in front of the bitstream instead (always inside the stream: header and tables precede
-    // it) and refills the slow way at install time.
+    // harmless 48 bytes in front of the bitstream instead and refills the slow way at install time.  Only readers
+    // of an accepted HUFFMAN frame request windows; its bitstream (at least one word) is preceded by the 32-byte
+    // frame header, at least 8 bytes of tables and the stream header, so those 48 bytes lie inside the stream.
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     struct Pending { u32x4 x[kWinWords / 4]; uint32_t cur; bool ok; };
     __device__ inline void request(Pending& P) const {
@@ -448,7 +449,7 @@ enum : int { MODE_DECOMPRESS = 0, MODE_STAGE_A = 1, MODE_ADD_B = 2, MODE_ADD_LOC
 #define NZ_ADDS(M) ((M) == MODE_ADD_B || (M) == MODE_ADD_LOCAL)
 
 // Shared memory of one decode workgroup.  The window comes first and the tile follows it directly: a reader's
-// prefetch may touch up to kWinOverRows rows past its window, which then fall into the tile (valid shared
+// prefetch may touch up to two rows past its window, which then fall into the tile (valid shared
 // memory, values never used).
 template <int NT>
 struct __align__(16) DecShared {
@@ -773,26 +774,27 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
     const uint32_t st_a = check_stream(A.a, A.a_bytes, A, total_a);
     uint32_t st_b = ST_OK;
     if (MODE == MODE_STAGE_A || MODE == MODE_ADD_B) st_b = check_stream(A.b, A.b_bytes, A, total_b);
-    if (blockIdx.x == 0 && tid == 0) {
+    // decompress: one verdict word per workgroup (status | kind << 8), summed up by k_decode_finish; nothing here
+    // touches the result record.  The reduce passes report through the (pre-cleared) record with atomics.
+    uint32_t* verdict = reinterpret_cast<uint32_t*>(A.ws + A.L.pmeta);
+    if (MODE != MODE_DECOMPRESS && blockIdx.x == 0 && tid == 0) {
         if (st_a) atomicMax(&res->status, st_a);
         if (st_b) atomicMax(&res->status, st_b);
-        if (MODE == MODE_DECOMPRESS && st_a == ST_OK) res->bytes = total_a;
     }
-    if (MODE == MODE_DECOMPRESS && st_a) return;                        // nothing is written on a stream-level error
+    if (MODE == MODE_DECOMPRESS && st_a) {                              // nothing is written on a stream-level error
+        if (tid == 0) verdict[blockIdx.x] = st_a;
+        return;
+    }
 
     FrameView V;
     V.status = ST_OK; V.kind = KIND_ZERO; V.w = 0; V.words = nullptr; V.nwords = 0; V.segt = nullptr; V.seg_prefix = 0; V.dense = false;
     if (st_a == ST_OK && st_b == ST_OK) {
         open_frame<NT>(MODE == MODE_ADD_B ? A.b : A.a, MODE == MODE_ADD_B ? total_b : total_a, frame, nf, first_seg, A,
                        &s_t, &S.u.build, V);
-        if (tid == 0) {
-            if (V.status) atomicMax(&res->status, V.status);
-            if (MODE == MODE_DECOMPRESS && db == 0 && V.status == ST_OK)
-                atomicAdd(V.kind == KIND_RAW ? &res->n_raw : (V.kind == KIND_FIXED ? &res->n_fixed : &res->n_huff), 1u);
-        }
-        if (V.status) V.kind = KIND_ZERO;                               // reduce: a rejected frame counts as zeros
+        if (MODE != MODE_DECOMPRESS && tid == 0 && V.status) atomicMax(&res->status, V.status);
     }
-    if (MODE == MODE_DECOMPRESS && V.status) return;                    // rejected frame: its output range is left alone
+    const uint32_t found_kind = V.kind;
+    if (V.status) V.kind = KIND_ZERO;                                   // a rejected frame counts as zeros (and decodes to zeros)
 
     // bit offset of my segment inside a HUFFMAN bitstream: prefix of the segment table
     uint32_t bit0 = 0, seglen = 0;
@@ -839,13 +841,22 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
         __syncthreads();
     }
 
+    bool late = false;                                                  // a segment that did not use exactly its recorded bits
     if (V.kind == KIND_HUFF) {
         run_huff<MODE, NT>(A, C, ra, &S, V.dense, X, a_wide, zmax, overflow);
-        if (seg_valid && (ra.bad || ra.consumed() != seglen)) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
+        late = seg_valid && (ra.bad || ra.consumed() != seglen);
+        if (MODE != MODE_DECOMPRESS && late) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
     } else {
         run_elementwise<MODE, NT>(A, C, da, &S, X, zmax, overflow);
     }
-    if (MODE == MODE_DECOMPRESS) return;
+    if (MODE == MODE_DECOMPRESS) {
+        // a frame found corrupt only now has been written already: k_decode_finish clears it again
+        if (late) S.ovf = 1u;                                           // (cleared before the first barrier; otherwise unused here)
+        __syncthreads();
+        const uint32_t any_late = S.ovf;
+        if (tid == 0) verdict[blockIdx.x] = (V.status ? V.status : (any_late ? (uint32_t)ST_CORRUPT : (uint32_t)ST_OK)) | (found_kind << 8);
+        return;
+    }
 
     if (MODE == MODE_STAGE_A) {
         static_assert(MODE != MODE_STAGE_A || NT * kSeg == kHalf, "the first reduce pass works in halves");
@@ -857,10 +868,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
         return;
     }
     // ---- adding passes: statistics of the sum, per half ----
-    // (ring step: whether a sum out of range is an error depends on the whole frame -- a frame made RAW by the
-    // local data has no integer sums -- so the flag is left for k_fix_local)
-    if (MODE == MODE_ADD_B && overflow) atomicMax(&res->status, (uint32_t)ST_RANGE);
-    if (MODE == MODE_ADD_LOCAL && overflow) S.ovf = 1u;
+    // (a sum beyond 2^30 turns the whole frame RAW, which only k_fix can do once every workgroup of the frame is
+    // done; the flag travels with the half's statistics)
+    if (overflow) S.ovf = 1u;
 #pragma unroll
     for (uint32_t h = 0; h < 2; h++) {
         const uint32_t zm = wave_max(zmax[h]);
@@ -886,13 +896,15 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
     }
 }
 
-// Ring step, after the adding pass: a frame whose local data holds an element that cannot be quantized is RAW
-// (as the interface quantizer would have made it), so its payload is the fp32 sum of the incoming values and
-// the ORIGINAL local values.  Rare; one workgroup per half looks at the frame's flags and returns at once
-// otherwise.  The incoming code is recovered exactly from the staged sum (Q - q_local, q_local = 0 where the
-// element was not quantizable); a RAW incoming frame is read from the stream again.  Also settles the range
-// error: it only exists for frames that keep integer sums.
-__global__ __launch_bounds__(256) void k_fix_local(DecodeArgs A) {
+// After an adding pass: frames that turn RAW late.  (1) Ring step: a frame whose local data holds an element that
+// cannot be quantized is RAW (as the interface quantizer would have made it), so its payload is the fp32 sum of the
+// incoming values and the ORIGINAL local values.  (2) Either reduce: a frame in which some integer sum exceeds 2^30
+// in magnitude cannot be carried as codes any further; it is committed as RAW and holds the fp32 sum of the two
+// dequantized operands (RAW is the safe fallback of the selector, Sec. IV-C / Algorithm 1).  Both are rare; one
+// workgroup per half looks at the frame's flags and returns at once otherwise.  The operand codes are recovered
+// exactly from the staged sums: incoming = Q - q_local (q_local = 0 where the element was not quantizable), or
+// B = Q - A with the staged codes of A; a RAW incoming frame is read from the stream again.
+__global__ __launch_bounds__(256) void k_fix(DecodeArgs A) {
     const uint32_t tid = threadIdx.x;
     const uint32_t hpf = (A.chunk + kHalf - 1) / kHalf;
     const uint32_t frame = blockIdx.x / hpf, h = blockIdx.x % hpf;
@@ -901,42 +913,109 @@ __global__ __launch_bounds__(256) void k_fix_local(DecodeArgs A) {
     const uint32_t h0 = h * kHalf;
     if (h0 >= nf) return;
     const uint32_t cnt = (nf - h0 < kHalf) ? (nf - h0) : kHalf;
-    ResultRec* res = reinterpret_cast<ResultRec*>(A.res);
     const uint2* pm = reinterpret_cast<const uint2*>(A.ws + A.L.pmeta) + (size_t)frame * hpf;
     const uint32_t* cw = reinterpret_cast<const uint32_t*>(A.ws + A.L.cwide) + (size_t)frame * hpf;
-    uint32_t lunq = 0, ovf = 0;
-    for (uint32_t j = 0; j < hpf && j * kHalf < nf; j++) { lunq |= pm[j].y & 2u; ovf |= cw[j] & 2u; }
-    const bool in_raw = reinterpret_cast<const uint32_t*>(A.ws + A.L.akind)[frame] != 0;
-    if (!lunq) {
-        if (ovf && !in_raw && h == 0 && tid == 0) atomicMax(&res->status, (uint32_t)ST_RANGE);
-        return;
-    }
+    uint32_t lunq = 0, ovf = 0, raw = 0;
+    for (uint32_t j = 0; j < hpf && j * kHalf < nf; j++) { raw |= pm[j].y & 1u; lunq |= pm[j].y & 2u; ovf |= cw[j] & 2u; }
+    // an operand frame that is RAW already has fp32 sums staged (no integer sums, no range question); only the ring
+    // step's local data can still change what those sums must be
+    if (!lunq && (raw || !ovf)) return;
     uint32_t* codes = reinterpret_cast<uint32_t*>(A.ws + A.L.codes) + f0 + h0;
     const int16_t* c16 = reinterpret_cast<const int16_t*>(A.ws + A.L.c16) + f0 + h0;
-    const float* x = A.local + f0 + h0;
+    StageA sa;
+    sa.a16 = reinterpret_cast<int16_t*>(A.ws + A.L.a16); sa.a32 = reinterpret_cast<uint32_t*>(A.ws + A.L.a32);
     const uint32_t* raw_in = nullptr;
-    if (in_raw) {       // header and extent of a RAW incoming frame were validated by the adding pass
+    if (raw) {          // ring step, incoming frame RAW: header and extent were validated by the adding pass
         const uint64_t off = *reinterpret_cast<const uint64_t*>(A.a + kStreamHdr + 8ull * frame);
         raw_in = reinterpret_cast<const uint32_t*>(A.a + off + kHdrBytes) + h0;
     }
     uint32_t dummy = 0;
     for (uint32_t i = tid; i < cnt; i += 256) {
-        uint32_t ta;
-        if (in_raw) ta = raw_in[i];
+        uint32_t ta, tb; bool b_is_raw = false;
+        if (raw) { ta = raw_in[i]; tb = __float_as_uint(A.local[f0 + h0 + i]); b_is_raw = true; }
         else {
             const int32_t s16 = c16[i];
             const uint32_t Q = (s16 == kWideMarker) ? codes[i] : (uint32_t)s16;
-            int32_t q;
-            quantize1(x[i], A.eb, A.step, A.inv_step, q);
-            ta = Q - (uint32_t)q;
+            if (A.local) {
+                const float x = A.local[f0 + h0 + i];
+                int32_t q;
+                quantize1(x, A.eb, A.step, A.inv_step, q);
+                ta = Q - (uint32_t)q;                                   // the incoming code
+                if (lunq) { tb = __float_as_uint(x); b_is_raw = true; } else tb = (uint32_t)q;
+            } else {
+                ta = sa.get(f0, nf, h0 + i, false);
+                tb = Q - ta;
+            }
         }
-        codes[i] = combine<true>(ta, in_raw, __float_as_uint(x[i]), true, A.step, dummy);
+        codes[i] = combine<true>(ta, raw != 0, tb, b_is_raw, A.step, dummy);
     }
 }
 
-hipError_t launch_fix_local(const DecodeArgs& A, hipStream_t st) {
+hipError_t launch_fix(const DecodeArgs& A, hipStream_t st) {
     const uint32_t hpf = (A.chunk + kHalf - 1) / kHalf;
-    hipLaunchKernelGGL(k_fix_local, dim3(A.n_frames * hpf), dim3(256), 0, st, A);
+    hipLaunchKernelGGL(k_fix, dim3(A.n_frames * hpf), dim3(256), 0, st, A);
+    return hipGetLastError();
+}
+
+// Decompress, second kernel: sums the workgroups' verdicts up into the result record (plain stores: the record needs
+// no clearing beforehand) and zero-fills every rejected frame -- the ones rejected at the header decode to zeros
+// anyway, the ones found corrupt while decoding (a segment that did not use exactly its recorded bits) were written
+// before the verdict was known.  A rejected frame never hands untrusted bytes to the caller (the paper's receiver
+// copies rawBytes from an invalid frame, Algorithm 2; this format reports the frame and fills it with zeros).
+__global__ __launch_bounds__(256) void k_decode_finish(DecodeArgs A) {
+    __shared__ uint32_t s_status, s_cnt[3];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t* verdict = reinterpret_cast<const uint32_t*>(A.ws + A.L.pmeta);
+    uint64_t total = 0;
+    const uint32_t st_a = check_stream(A.a, A.a_bytes, A, total);
+    auto frame_verdict = [&](uint32_t frame, uint32_t& kind) -> uint32_t {
+        const uint64_t f0 = (uint64_t)frame * A.chunk;
+        const uint32_t nf = (uint32_t)((A.n - f0 < A.chunk) ? (A.n - f0) : A.chunk);
+        uint32_t st = 0;
+        for (uint32_t db = 0; db < A.dbpf && db * kDecBlock < nf; db++) {
+            const uint32_t v = verdict[(size_t)frame * A.dbpf + db];
+            st = (v & 0xFFu) > st ? (v & 0xFFu) : st;
+            if (db == 0) kind = v >> 8;
+        }
+        return st;
+    };
+    if (st_a == ST_OK) {
+        for (uint32_t frame = blockIdx.x; frame < A.n_frames; frame += gridDim.x) {
+            uint32_t kind;
+            if (frame_verdict(frame, kind) == ST_OK) continue;
+            const uint64_t f0 = (uint64_t)frame * A.chunk;
+            const uint32_t nf = (uint32_t)((A.n - f0 < A.chunk) ? (A.n - f0) : A.chunk);
+            for (uint32_t i = tid; i < nf; i += 256) A.out[f0 + i] = 0.0f;
+        }
+    }
+    if (blockIdx.x != 0) return;
+    if (tid == 0) { s_status = st_a; s_cnt[0] = 0; s_cnt[1] = 0; s_cnt[2] = 0; }
+    __syncthreads();
+    if (st_a == ST_OK) {
+        uint32_t worst = 0, c[3] = { 0, 0, 0 };
+        for (uint32_t frame = tid; frame < A.n_frames; frame += 256) {
+            uint32_t kind = KIND_ZERO;
+            const uint32_t st = frame_verdict(frame, kind);
+            worst = st > worst ? st : worst;
+            if (st == ST_OK && kind < 3u) c[kind]++;
+        }
+        if (worst) atomicMax(&s_status, worst);
+        for (int k = 0; k < 3; k++) if (c[k]) atomicAdd(&s_cnt[k], c[k]);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        ResultRec* res = reinterpret_cast<ResultRec*>(A.res);
+        res->bytes = (st_a == ST_OK) ? total : 0ull;
+        res->status = s_status; res->n_frames = A.n_frames;
+        res->n_raw = s_cnt[KIND_RAW]; res->n_fixed = s_cnt[KIND_FIXED]; res->n_huff = s_cnt[KIND_HUFF]; res->reserved = 0;
+    }
+}
+
+hipError_t launch_decode_finish(const DecodeArgs& A, hipStream_t st) {
+    DecodeArgs D = A;
+    D.dbpf = (A.chunk + kDecBlock - 1) / kDecBlock;
+    const uint32_t grid = A.n_frames < 1024u ? A.n_frames : 1024u;
+    hipLaunchKernelGGL(k_decode_finish, dim3(grid), dim3(256), 0, st, D);
     return hipGetLastError();
 }
 

@@ -23,11 +23,12 @@ def nz():
 
 
 def test_exports_every_declared_symbol(nz):
-    hdr = open(os.path.join(ROOT, "include", "nz.h")).read()
+    inc = os.path.join(ROOT, "include")
+    hdr = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
     hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
     names = set(re.findall(r"\b(nz_[a-z_]+)\s*\(", hdr))
     assert {"nz_compress", "nz_decompress", "nz_reduce_frames", "nz_reduce_local", "nz_compress_bound", "nz_workspace_bytes",
-            "nz_reduce_workspace_bytes", "nz_version"} <= names
+            "nz_reduce_workspace_bytes", "nz_version", "nz_trace_events", "nz_trace_recorded"} <= names
     L = nz.lib()
     for n in names:
         assert hasattr(L, n), n

@@ -190,28 +190,50 @@ def test_decompress_rejections(nz):
     t = s.copy(); t[0] ^= 1
     assert gpu_decompress(nz, t, x.size, eb, g)[1]["status"] == nz.ERR_CORRUPT
     assert gpu_decompress(nz, s[:-16], x.size, eb, g)[1]["status"] == nz.ERR_CORRUPT
-    # frame headers: same verdict as the oracle; accepted mutations decode identically; other frames unaffected
+    # frame headers: same verdict as the oracle, and the same output everywhere -- a rejected frame is zero-filled
     off = int(s[64 + 8:64 + 16].view(np.uint64)[0])
     for i in range(32):
         t = s.copy(); t[off + i] ^= 0x41
         oref, ores, orc = oracle.decompress(t, x.size, eb)
         rc, r, got = gpu_decompress(nz, t, x.size, eb, g)
         assert r["status"] == orc, (i, r, orc)
-        keep = np.ones(x.size, bool)
-        if orc:
-            keep[16384:32768] = False
-        assert (got.view(np.uint32)[keep] == ref.view(np.uint32)[keep]).all()
-    # garbage inside payloads: never faults; same verdict as the oracle; an accepted stream decodes identically
+        assert (r["n_raw"], r["n_fixed"], r["n_huff"], r["bytes"]) == (ores.n_raw, ores.n_fixed, ores.n_huff, ores.bytes)
+        assert (got.view(np.uint32) == oref.view(np.uint32)).all(), i
+    # garbage inside payloads: never faults; same verdict and same output as the oracle (a frame found corrupt while
+    # decoding is zero-filled as a whole, the others are untouched)
     rng = np.random.default_rng(3)
+    n_rejected = 0
     for _ in range(60):
         t = s.copy()
         i = int(rng.integers(off + 32, s.size))
         t[i] ^= int(rng.integers(1, 256))
-        oref, _, orc = oracle.decompress(t, x.size, eb)
+        oref, ores, orc = oracle.decompress(t, x.size, eb)
         rc, r, got = gpu_decompress(nz, t, x.size, eb, g)
         assert r["status"] == orc, (i, r, orc)
-        if orc == 0:
-            assert (got.view(np.uint32) == oref.view(np.uint32)).all()
+        assert (r["n_raw"], r["n_fixed"], r["n_huff"]) == (ores.n_raw, ores.n_fixed, ores.n_huff)
+        assert (got.view(np.uint32) == oref.view(np.uint32)).all(), i
+        n_rejected += orc != 0
+    assert n_rejected > 10
+    # a frame larger than one decode workgroup, broken in its last workgroup's share: the whole frame is cleared
+    g3, o3 = _opts_pair(nz, chunk_elems=200000)
+    x3 = W.gradient_like(450000, seed=16)
+    s3 = oracle.compress(x3, eb, o3)[0]
+    o1, o2 = [int(v) for v in s3[64 + 8:64 + 24].view(np.uint64)]
+    for pos in (o2 - 40, o1 + 3000, o2 - 20000):
+        t = s3.copy(); t[pos] ^= 0x10
+        oref, ores, orc = oracle.decompress(t, x3.size, eb)
+        rc, r, got = gpu_decompress(nz, t, x3.size, eb, g3)
+        assert r["status"] == orc
+        assert (got.view(np.uint32) == oref.view(np.uint32)).all(), pos
+    # regression: a HUFFMAN frame whose segment table claims zero bits (valid header and code lengths, payload ends
+    # after the tables) is rejected at validation, before any bit reader exists
+    from crafted import zero_bit_huffman_stream
+    step_bits = int(np.float32(oracle.step_constants(eb)[0]).view(np.uint32))
+    for n0 in (1, 300, 5000):
+        t = zero_bit_huffman_stream(n0, step_bits)
+        oref, ores, orc = oracle.decompress(t, n0, eb)
+        rc, r, got = gpu_decompress(nz, t, n0, eb, nz.make_opts(chunk_elems=n0))
+        assert orc == oracle.ERR_CORRUPT and r["status"] == nz.ERR_CORRUPT and not got.any()
     # the same garbage through the reduce passes (as operand A, as operand B, and as the ring step's incoming stream)
     go = oracle.make_opts(chunk_elems=16384)
     for _ in range(20):
@@ -293,7 +315,7 @@ def test_reduce_all_codec_pairs(nz, ca, cb):
     assert r["bytes"] == ores.bytes and _first_diff(got, ref) == -1
 
 
-def test_reduce_raw_nan_range_and_mismatch(nz):
+def test_reduce_raw_nan_overflow_and_mismatch(nz):
     n, eb = 3000, 1e-3
     g, o = _opts_pair(nz, chunk_elems=1000)
     a = W.gradient_like(n, seed=70); b = W.gradient_like(n, seed=71)
@@ -302,18 +324,18 @@ def test_reduce_raw_nan_range_and_mismatch(nz):
     ref, ores, orc = oracle.reduce_frames(sa, sb, n, eb, o)
     rc, r, got = gpu_reduce(nz, sa, sb, n, eb, g)
     assert orc == 0 and r["status"] == 0 and r["bytes"] == ores.bytes and _first_diff(got, ref) == -1
-    # range: double a stream until the sum passes 2^30
-    x = np.zeros(1000, np.float32)
+    # double a stream until a sum passes 2^30: that frame is committed as RAW with fp32 sums, the others stay coded
+    x = W.gradient_like(3000, seed=72)
+    x[:1000] = 0.0
     x[7] = np.float32(32767.0) * oracle.step_constants(eb)[0]
     s = oracle.compress(x, eb, o)[0]
-    for i in range(15):
-        s_o = oracle.reduce_frames(s, s, 1000, eb, o)[0]
-        rc, r, s_g = gpu_reduce(nz, s, s, 1000, eb, g)
-        assert r["status"] == 0 and _first_diff(s_g, s_o) == -1
+    for i in range(17):
+        s_o, ores, orc = oracle.reduce_frames(s, s, 3000, eb, o)
+        rc, r, s_g = gpu_reduce(nz, s, s, 3000, eb, g)
+        assert orc == 0 and r["status"] == 0 and r["bytes"] == ores.bytes and _first_diff(s_g, s_o) == -1, i
+        assert (r["n_raw"], r["n_fixed"], r["n_huff"]) == (ores.n_raw, ores.n_fixed, ores.n_huff)
         s = s_o
-    assert oracle.reduce_frames(s, s, 1000, eb, o)[2] == oracle.ERR_RANGE
-    rc, r, _ = gpu_reduce(nz, s, s, 1000, eb, g)
-    assert r["status"] == nz.ERR_RANGE and r["bytes"] == 0
+    assert ores.n_raw == 1
     # operands that disagree
     sc = oracle.compress(a, 2e-3, o)[0]
     assert gpu_reduce(nz, sa, sc, n, eb, g)[1]["status"] == nz.ERR_MISMATCH
@@ -510,7 +532,7 @@ def test_reduce_local_frame_kinds(nz, case):
     _check_reduce_local(nz, sa, x, eb, **kw)
 
 
-def test_reduce_local_range_mismatch_capacity(nz):
+def test_reduce_local_overflow_mismatch_capacity(nz):
     eb = 1e-3
     g, o = _opts_pair(nz, chunk_elems=1000)
     step = oracle.step_constants(eb)[0]
@@ -519,10 +541,24 @@ def test_reduce_local_range_mismatch_capacity(nz):
     for _ in range(15):
         s = oracle.reduce_frames(s, s, 1000, eb, o)[0]
     s1 = _check_reduce_local(nz, s, z, eb, chunk_elems=1000)                      # 2^30 - 1: still carried
-    rc, r, _ = gpu_reduce_local(nz, s1, z, eb, g)
-    assert r["status"] == nz.ERR_RANGE and r["bytes"] == 0
-    zn = z.copy(); zn[500] = np.nan                                              # the frame turns RAW: no range error
+    s2 = _check_reduce_local(nz, s1, z, eb, chunk_elems=1000)                     # past 2^30: the frame is committed as RAW
+    assert oracle.decode_codes(s2, 1000, eb)[2].tolist() == [1]
+    _check_reduce_local(nz, s2, z, eb, chunk_elems=1000)                          # and stays RAW
+    zn = z.copy(); zn[500] = np.nan                                              # the local data turns the frame RAW anyway
     _check_reduce_local(nz, s1, zn, eb, chunk_elems=1000)
+    # several frames, one of them overflowing in its second half only
+    big = W.gradient_like(300000, seed=73)
+    gk, ok = _opts_pair(nz, chunk_elems=140000)
+    big[140000 + 70000] = np.float32(32767.0) * step
+    sb = oracle.compress(big, eb, ok)[0]
+    for _ in range(15):
+        sb = oracle.reduce_frames(sb, sb, big.size, eb, ok)[0]
+    sb1 = _check_reduce_local(nz, sb, big, eb, chunk_elems=140000)
+    sb2 = _check_reduce_local(nz, sb1, big, eb, chunk_elems=140000)
+    assert oracle.decode_codes(sb2, big.size, eb)[2].tolist() == [0, 1, 0]
+    ref, ores, orc = oracle.reduce_frames(sb1, sb, big.size, eb, ok)
+    rc, r, got = gpu_reduce(nz, sb1, sb, big.size, eb, gk)
+    assert orc == 0 and r["status"] == 0 and ores.n_raw == 1 and _first_diff(got, ref) == -1
     a = W.gradient_like(3000, seed=70)
     sa = oracle.compress(a, eb, o)[0]
     assert gpu_reduce_local(nz, sa, a, 2e-3, g)[1]["status"] == nz.ERR_MISMATCH
@@ -642,7 +678,7 @@ def test_calls_can_be_captured_in_a_hip_graph(nz):
 
     def work():
         assert nz.nz_compress(dx, n, eb, out, sess.cap, res_c, g, sess.ws, sess.ws_bytes) == 0
-        assert nz.nz_decompress(out, ref.size, y, n, eb, sess.res, g) == 0
+        assert nz.nz_decompress(out, ref.size, y, n, eb, sess.res, g, sess.ws, sess.ws_bytes) == 0
         assert nz.nz_reduce_frames(out, ref.size, dpeer, peer.size, red, sess.cap, n, eb, res_r, g, sess.ws, sess.ws_bytes) == 0
 
     work()                                            # eager, also warms everything up
@@ -664,3 +700,129 @@ def test_calls_can_be_captured_in_a_hip_graph(nz):
         assert _first_diff(out[:ref.size].cpu().numpy(), ref) == -1, rep
         assert _first_diff(red[:ref_red.size].cpu().numpy(), ref_red) == -1, rep
         assert (y.cpu().numpy().view(np.uint32) == y_ref.view(np.uint32)).all(), rep
+
+
+# ------------------------------------------------------------------------------------------------
+# exact ties, deepest codes, many second-level tables, refused options
+# ------------------------------------------------------------------------------------------------
+
+def test_exact_ties_round_to_even(nz):
+    """eb = fl32(32/63) makes step and 1/step exactly 1.0, so x = k + 1/2 is an exact tie (the golden rows of the CPU
+    pin); a whole message of such ties and near-ties must give the oracle's bytes."""
+    eb = float(np.float32(32.0 / 63.0))
+    rng = np.random.default_rng(77)
+    k = rng.integers(-2000, 2000, 100000)
+    x = (k + 0.5).astype(np.float32)
+    x[::7] = np.nextafter(x[::7], np.float32(np.inf))            # just above a tie
+    x[3::7] = np.nextafter(x[3::7], np.float32(-np.inf))         # just below
+    rows = [l.split() for l in open(__file__.replace("test_gpu_parity.py", "golden/quantizer_ties.txt")) if l.strip() and l[0] != "#"]
+    x[:len(rows)] = [float(r[0]) for r in rows]
+    ref, _ = check_compress(nz, x, eb, chunk_elems=16384, alphabet=1024)
+    g, _ = _opts_pair(nz, chunk_elems=16384, alphabet=1024)
+    rc, r, got = gpu_decompress(nz, ref, x.size, eb, g)
+    assert r["status"] == 0 and got[:len(rows)].tolist() == [float(r_[2]) for r_ in rows]
+    check_decompress(nz, ref, x, eb, chunk_elems=16384, alphabet=1024)
+
+
+def _fibonacci_codes(adjacent_rare=True):
+    fib = [1, 1]
+    while len(fib) < 28:
+        fib.append(fib[-1] + fib[-2])
+    rng = np.random.default_rng(5)
+    z = np.concatenate([np.full(c, i) for i, c in enumerate(fib)])            # zigzag code i occurs fib[i] times
+    head, tail = z[:sum(fib[:8])], z[sum(fib[:8]):]
+    rng.shuffle(tail)
+    z = np.concatenate([head, tail]) if adjacent_rare else rng.permutation(z)  # the rarest (27-bit) codes side by side
+    return ((z >> 1) ^ -(z & 1)).astype(np.int32)
+
+
+@pytest.mark.parametrize("K", [32, 256])
+def test_deepest_codes_fibonacci_histogram(nz, K):
+    """Fibonacci counts give the deepest optimal code a 2^20-symbol frame can have (27 bits): the decoder's
+    range-compare path and the encoder's more-than-64-bits-per-thread path at their limit, through compress,
+    decompress, both reduces (the sums 2q keep the Fibonacci histogram)."""
+    q = _fibonacci_codes()
+    eb = float(np.float32(32.0 / 63.0))                                       # step = 1: x = q exactly
+    x = q.astype(np.float32)
+    kw = dict(chunk_elems=1 << 20, alphabet=K)
+    plan = oracle.frame_plan(q, oracle.make_opts(**kw))
+    assert plan["len"].max() == 27 and plan["codec"] == oracle.HUFFMAN
+    ref, _ = check_compress(nz, x, eb, **kw)
+    check_decompress(nz, ref, x, eb, **kw)
+    g, o = _opts_pair(nz, **kw)
+    red, ores, orc = oracle.reduce_frames(ref, ref, x.size, eb, o)
+    rc, r, got = gpu_reduce(nz, ref, ref, x.size, eb, g)
+    assert orc == 0 and r["status"] == 0 and r["bytes"] == ores.bytes and _first_diff(got, red) == -1
+    check_decompress(nz, red, 2 * x, eb, **kw)
+    _check_reduce_local(nz, ref, x, eb, **kw)
+    # and a second message with the symbols in another order as operand B
+    x2 = _fibonacci_codes(adjacent_rare=False).astype(np.float32)
+    ref2, _ = check_compress(nz, x2, eb, **kw)
+    red, ores, orc = oracle.reduce_frames(ref, ref2, x.size, eb, o)
+    rc, r, got = gpu_reduce(nz, ref, ref2, x.size, eb, g)
+    assert orc == 0 and r["status"] == 0 and _first_diff(got, red) == -1
+
+
+def test_more_than_32_second_level_tables(nz):
+    """K = 1024 with four heavy symbols and a thousand equally rare ones: the rare codes are 13-14 bits long and start
+    with some 200 different 11-bit prefixes, far more than the 32 second-level tables the decoder keeps."""
+    rng = np.random.default_rng(6)
+    n = 1 << 20
+    z = rng.integers(0, 4, n)
+    rare = rng.random(n) < 0.1
+    z[rare] = rng.integers(4, 1023, int(rare.sum()))
+    q = ((z >> 1) ^ -(z & 1)).astype(np.int32)
+    eb = float(np.float32(32.0 / 63.0))
+    x = q.astype(np.float32)
+    kw = dict(chunk_elems=1 << 20, alphabet=1024)
+    plan = oracle.frame_plan(q, oracle.make_opts(**kw))
+    long_codes = [(int(c) >> (int(l) - 11)) for c, l in zip(plan["code"], plan["len"]) if l > 11]
+    assert len(set(long_codes)) > 100 and plan["codec"] == oracle.HUFFMAN
+    ref, _ = check_compress(nz, x, eb, **kw)
+    check_decompress(nz, ref, x, eb, **kw)
+    g, o = _opts_pair(nz, **kw)
+    red, ores, orc = oracle.reduce_frames(ref, ref, n, eb, o)
+    rc, r, got = gpu_reduce(nz, ref, ref, n, eb, g)
+    assert orc == 0 and r["status"] == 0 and _first_diff(got, red) == -1
+    _check_reduce_local(nz, ref, x, eb, **kw)
+
+
+def test_pinned_huffman_all_escapes_fits_its_bound(nz):
+    """K = 2 and no zero codes: every symbol escapes (33 bits each), more than RAW; the pinned-HUFFMAN capacity bound
+    must cover the stream."""
+    n = 50000
+    x = (np.arange(n) % 7 + 3).astype(np.float32)
+    eb = float(np.float32(32.0 / 63.0))
+    kw = dict(chunk_elems=16384, alphabet=2, force_codec=2)
+    g, o = _opts_pair(nz, **kw)
+    ref, ores = check_compress(nz, x, eb, **kw)
+    assert ref.size > 4 * n and ref.size <= nz.nz_compress_bound(n, g) == oracle.compress_bound(n, o)
+    check_decompress(nz, ref, x, eb, **kw)
+
+
+@pytest.mark.parametrize("seg", [32, 64, 128, 512, 1024, 255])
+def test_other_segment_sizes_are_refused_by_every_entry_point(nz, seg):
+    """The format allows 32..1024 symbols per segment (the oracle handles them); these kernels are built around one
+    256-symbol segment per wavefront pass and refuse everything else, consistently."""
+    import torch
+    n, eb = 70000, 1e-4
+    x = W.gradient_like(n, seed=9)
+    good = nz.make_opts(chunk_elems=16384)
+    bad = nz.make_opts(chunk_elems=16384, seg_syms=seg)
+    sess = nz.Session(n, good, "cuda:0", reduce=True)
+    dx = _to_dev(nz, x)
+    rc, out = sess.compress(dx, eb)
+    nbytes = sess.result()["bytes"]
+    assert rc == 0 and nbytes > 0
+    y = torch.empty(n, dtype=torch.float32, device="cuda:0")
+    assert nz.nz_compress_bound(n, bad) == 0 and nz.nz_workspace_bytes(n, bad) == 0 and nz.nz_reduce_workspace_bytes(n, bad) == 0
+    assert nz.nz_compress(dx, n, eb, out, sess.cap, sess.res, bad, sess.ws, sess.ws_bytes) == nz.ERR_INVALID
+    assert nz.nz_decompress(out, nbytes, y, n, eb, sess.res, bad, sess.ws, sess.ws_bytes) == nz.ERR_INVALID
+    red = sess.new_stream_buffer()
+    assert nz.nz_reduce_frames(out, nbytes, out, nbytes, red, sess.cap, n, eb, sess.res, bad, sess.ws, sess.ws_bytes) == nz.ERR_INVALID
+    assert nz.nz_reduce_local(out, nbytes, dx, red, sess.cap, n, eb, sess.res, bad, sess.ws, sess.ws_bytes) == nz.ERR_INVALID
+    # a stream that was written with another segment size (by the oracle) does not match what these kernels decode
+    so = oracle.compress(x, eb, oracle.make_opts(chunk_elems=16384, seg_syms=seg))[0]
+    rc, r, _ = gpu_decompress(nz, so, n, eb, good)
+    assert r["status"] == nz.ERR_MISMATCH
+    torch.cuda.synchronize()
