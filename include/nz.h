@@ -105,6 +105,20 @@ nz_status nz_compress(const float* d_in, size_t n, float eb, void* d_out, size_t
                       const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream);
 
 /*
+ * nz_compress for callers that cannot allocate or hand over scratch memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same result, byte for byte, as nz_compress; the
+ * workspace is an array that lives inside the library on every GPU (nz_static_scratch_bytes() bytes, 8 MiB,
+ * resident until the process ends) and the call allocates nothing.  The message must be small enough for
+ * it: nz_workspace_bytes(n, opts) <= nz_static_scratch_bytes() (about 96 Mi elements in 1 MiB frames, 14 Mi
+ * elements in 64 KiB frames), otherwise NZ_ERR_INVALID and nothing is launched.  NZ_ERR_HIP if the array's
+ * address cannot be obtained on the current device.  All calls on one GPU share that GPU's array: calls that
+ * overlap in time on the same GPU (different streams or threads) race and must be serialised by the caller.
+ */
+size_t    nz_static_scratch_bytes(void);
+nz_status nz_compress_static(const float* d_in, size_t n, float eb, void* d_out, size_t out_cap, nz_result* d_res,
+                             const nz_opts* opts, void* stream);
+
+/*
  * Receiver side of Algorithm 2 (ParseHeader, ValidateHeader, DecodeOrMemcpy):
  * validate and decode an NZ stream into d_out[0..n): xhat = fl32(float(q) *
  * step); RAW frames are copied through.  n, eb and opts (chunk_elems,

@@ -47,6 +47,9 @@ def lib():
         L.nz_reduce_workspace_bytes.restype = sz
         L.nz_compress.argtypes = [vp, sz, f32, vp, sz, vp, po, vp, sz, vp]
         L.nz_compress.restype = C.c_int
+        L.nz_static_scratch_bytes.restype = sz
+        L.nz_compress_static.argtypes = [vp, sz, f32, vp, sz, vp, po, vp]
+        L.nz_compress_static.restype = C.c_int
         L.nz_decompress.argtypes = [vp, sz, vp, sz, f32, vp, po, vp, sz, vp]
         L.nz_decompress.restype = C.c_int
         L.nz_reduce_frames.argtypes = [vp, sz, vp, sz, vp, sz, sz, f32, vp, po, vp, sz, vp]
@@ -85,6 +88,16 @@ def nz_compress(d_in, n, eb, d_out, out_cap, d_res, opts, d_ws, ws_bytes, stream
     """d_in: float32 cuda tensor; d_out, d_ws: uint8 cuda tensors; d_res: uint8 cuda tensor of RESULT_BYTES."""
     return int(lib().nz_compress(d_in.data_ptr(), n, C.c_float(eb), d_out.data_ptr(), out_cap, d_res.data_ptr(),
                                  _po(opts), d_ws.data_ptr(), ws_bytes, _stream(stream)))
+
+
+def nz_static_scratch_bytes():
+    return int(lib().nz_static_scratch_bytes())
+
+
+def nz_compress_static(d_in, n, eb, d_out, out_cap, d_res, opts, stream=None):
+    """nz_compress with the library's resident scratch array as workspace (allocates nothing)."""
+    return int(lib().nz_compress_static(d_in.data_ptr(), n, C.c_float(eb), d_out.data_ptr(), out_cap, d_res.data_ptr(),
+                                        _po(opts), _stream(stream)))
 
 
 def nz_decompress(d_stream, stream_bytes, d_out, n, eb, d_res, opts, d_ws=None, ws_bytes=0, stream=None):

@@ -3,6 +3,7 @@
 #include "../../include/nz.h"
 #include "../../include/nz_trace.h"
 #include "nz_common.hpp"
+#include <mutex>
 
 using namespace nz;
 
@@ -60,6 +61,27 @@ inline void trace_mark(hipStream_t st) {
         (void)hipEventRecord(reinterpret_cast<hipEvent_t>(t_events[t_event_n]), st);
         t_event_n++;
     }
+}
+
+// Scratch of the entry point that allocates nothing: one array per GPU, resident until the process ends.
+constexpr size_t kStaticScratchBytes = 8u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};          // device address of `scratch` on each GPU, looked up on first use
+
+// The array's name is a host-side handle, not a device address: ask the runtime for the address on the current
+// device (every GPU holds its own copy at its own address) and use only that pointer from host code.
+void* static_scratch() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
 }
 
 constexpr uint64_t kMaxElems = 1ull << 38;      // keeps every grid below 2^31 workgroups for frames >= 8192 elements
@@ -129,6 +151,18 @@ nz_status nz_compress(const float* d_in, size_t n, float eb, void* d_out, size_t
     if (launch_encode(A, false, st) != hipSuccess) return NZ_ERR_HIP;
     trace_mark(st);
     return NZ_OK;
+}
+
+size_t nz_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+nz_status nz_compress_static(const float* d_in, size_t n, float eb, void* d_out, size_t out_cap, nz_result* d_res,
+                             const nz_opts* opts, void* stream) {
+    Opts o;
+    if (!resolve(opts, o) || !geometry_ok(n, o)) return NZ_ERR_INVALID;
+    if (ws_layout(n, o.chunk, kStatBlock, false).total > kStaticScratchBytes) return NZ_ERR_INVALID;   // message too large for the resident scratch
+    void* ws = static_scratch();
+    if (!ws) return NZ_ERR_HIP;
+    return nz_compress(d_in, n, eb, d_out, out_cap, d_res, opts, ws, kStaticScratchBytes, stream);
 }
 
 nz_status nz_decompress(const void* d_stream, size_t stream_bytes, float* d_out, size_t n, float eb,
