@@ -101,14 +101,20 @@ def run_c5_overlap(args):
     from paper_2605_12396_amd import binding as nz, workloads as W
 
     dev = torch.device("cuda:0")
-    n = 1 << 26                      # 256 MB message
-    slice_n = 1 << 22                # 16 MB slices of 16 frames of 1 MiB
-    n_slices = n // slice_n
-    opts = nz.make_opts(chunk_elems=262144, alphabet=args.alphabet)
     eb = 1e-4
     s_comp, s_copy = torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)     # default priority
-    for kind in ("laplace", "uniform", "sinusoid"):
-        x = torch.from_numpy(W.sweep_payload(kind, n, 50)).to(dev)
+    kinds = ("uniform", "laplace", "sinusoid")
+    # message sizes 64 KB .. 1 GB in powers of 4, the payload kind rotating with the size; 64 KiB frames up to 4 MB,
+    # 1 MiB frames above; slices of 16 MB (smaller messages are one slice)
+    for k, (n, kind) in enumerate([(16384 << (2 * i), kinds[i % 3]) for i in range(8)] +
+                                  [(1 << 26, "laplace"), (1 << 26, "uniform"), (1 << 26, "sinusoid")]):
+        if 4 * n > args.c5_max_bytes:
+            continue
+        chunk = 16384 if 4 * n <= (4 << 20) else 262144
+        slice_n = min(n, 1 << 22)
+        n_slices = n // slice_n
+        opts = nz.make_opts(chunk_elems=chunk, alphabet=args.alphabet)
+        x = torch.from_numpy(W.sweep_payload(kind, n, 50 + k)).to(dev)
         cap = nz.nz_compress_bound(slice_n, opts)
         wsb = nz.nz_workspace_bytes(slice_n, opts)
         outs = [torch.empty(cap, dtype=torch.uint8, device=dev) for _ in range(2)]       # two banks
@@ -176,18 +182,85 @@ def run_c5_overlap(args):
 
         for f in (serialized, copy_only, overlapped):
             f()                                                   # warm-up
-        reps = max(3, min(args.steps, 10))
+        reps = max(3, min(args.steps, 10)) if n >= (1 << 24) else 20
         t_ser = min(serialized() for _ in range(reps))
         t_cpy = min(copy_only() for _ in range(reps))
         t_ovl = min(overlapped() for _ in range(reps))
         total = float(sum(sizes))
         print(json.dumps(dict(metric="exposed compression time, sliced compress overlapped with D2H copy (config 5)",
-                              config=dict(workload="c5 %s, 256 MB message, 16 MB slices, eb=1e-4, 1MiB frames" % kind,
-                                          alphabet=args.alphabet),
+                              config=dict(workload="c5 %s, %d-byte message, %d slice(s) of %d bytes, eb=1e-4, %d-element frames" %
+                                                   (kind, 4 * n, n_slices, 4 * slice_n, chunk), alphabet=args.alphabet),
                               data="synthetic", n_gpus=1, compressed_bytes=total, compression_ratio=4.0 * n / total,
                               serialized_ms=t_ser * 1e3, copy_only_ms=t_cpy * 1e3, overlapped_ms=t_ovl * 1e3,
                               exposed_compression_ms=(t_ovl - t_cpy) * 1e3,
                               serialized_over_overlapped=t_ser / t_ovl)))
+
+
+def run_c3_bounds(args):
+    """Config 3: Gaussian random field 512^3 (P(k) ~ k^-3, unit variance), value-range-relative bound swept over
+    1e-2, 1e-3, 1e-4, 1 MiB frames: compression ratio against compress / decompress throughput per bound.  The field
+    is drawn on the GPU (torch, seeded) with the recipe of workloads.gaussian_random_field; a 4-frame sample is
+    compared with the oracle.  One JSON line per bound; not part of the headline metric."""
+    import numpy as np
+    import torch
+    import oracle
+    from paper_2605_12396_amd import binding as nz
+
+    dev = torch.device("cuda:0")
+    N = args.c3_side
+    gen = torch.Generator(device=dev); gen.manual_seed(3)
+    f = torch.randn((N, N, N), generator=gen, device=dev, dtype=torch.float32)
+    F = torch.fft.rfftn(f)
+    k1 = torch.fft.fftfreq(N, device=dev) * N
+    kz = torch.fft.rfftfreq(N, device=dev) * N
+    k = torch.sqrt(k1[:, None, None] ** 2 + k1[None, :, None] ** 2 + kz[None, None, :] ** 2)
+    k[0, 0, 0] = 1.0
+    amp = k ** -1.5
+    amp[0, 0, 0] = 0.0
+    F *= amp
+    del k, amp
+    f = torch.fft.irfftn(F, s=(N, N, N))
+    del F
+    f = ((f - f.mean()) / f.std()).float().contiguous().view(-1)
+    n = f.numel()
+    rng = float(f.max() - f.min())
+    opts = nz.make_opts(chunk_elems=262144, alphabet=args.alphabet)
+    sess = nz.Session(n, opts, dev)
+    out = sess.new_stream_buffer()
+    y = torch.empty_like(f)
+    gb = 4.0 * n / 1e9
+    for rel in (1e-2, 1e-3, 1e-4):
+        eb = float(np.float32(rel * rng))
+        def timed(fn, reps):
+            fn(); torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record(); torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+        reps = max(3, min(args.steps, 10))
+        t_c = timed(lambda: sess.compress(f, eb, out=out), reps)
+        r = sess.result()
+        assert r["status"] == 0
+        nbytes = r["bytes"]
+        t_d = timed(lambda: sess.decompress(out, nbytes, n, eb, out=y), reps)
+        assert sess.result()["status"] == 0
+        err = float((y.double() - f.double()).abs().max())
+        # first four frames against the oracle: same bytes
+        xs = f[:4 * 262144].cpu().numpy()
+        ref, ores, orc = oracle.compress(xs, eb, oracle.make_opts(chunk_elems=262144, alphabet=args.alphabet))
+        s4 = nz.Session(xs.size, opts, dev)
+        rc, o4 = s4.compress(f[:4 * 262144], eb)
+        r4 = s4.result()
+        same = bool(orc == 0 and r4["bytes"] == ores.bytes and (o4[:r4["bytes"]].cpu().numpy() == ref).all())
+        print(json.dumps(dict(metric="compression ratio vs throughput per bound (config 3)", n_gpus=1, data="synthetic",
+                              config=dict(workload="c3: Gaussian random field %d^3, P(k)~k^-3, REL=%g x range, 1MiB frames" % (N, rel),
+                                          alphabet=args.alphabet, eb=eb),
+                              compression_ratio=4.0 * n / nbytes, compress_GBps=gb / (t_c * 1e-3), decompress_GBps=gb / (t_d * 1e-3),
+                              compress_ms=t_c, decompress_ms=t_d, max_abs_err=err, bound_holds=bool(err <= eb),
+                              frames=dict(raw=r["n_raw"], fixed=r["n_fixed"], huffman=r["n_huff"]),
+                              first_4_frames_match_oracle=same)))
 
 
 def run_c4_ring(args):
@@ -252,15 +325,17 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--workload", default="c2", help="c2 (headline) | c1 | c4 | c3 | c4ring | c5")
     ap.add_argument("--alphabet", type=int, default=256, help="Huffman alphabet K (power of two, 2..1024)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--rotate", type=int, default=3, help="number of distinct input copies cycled through")
+    ap.add_argument("--rotate", type=int, default=3, help="number of distinct input / stream copies cycled through")
     ap.add_argument("--only", default="", help="profiling aid: time only this stage (compress|decompress|reduce)")
     ap.add_argument("--calib-copy", type=int, default=0,
                     help="profiling aid: also run this many plain 4n-byte copy kernels (counter calibration)")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "hbm_traffic_c2.txt"),
                     help="text summary of the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see pmc_summary.py)")
+    ap.add_argument("--c3-side", type=int, default=512, help="c3: side of the cubic random field")
+    ap.add_argument("--c5-max-bytes", type=int, default=1 << 30, help="c5: largest message of the size sweep")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py measures the one-GPU hot path only: run with --gpus 1 "
@@ -270,6 +345,8 @@ def main():
         return run_c5_overlap(args)
     if args.workload == "c4ring":
         return run_c4_ring(args)
+    if args.workload == "c3":
+        return run_c3_bounds(args)
 
     import numpy as np
     import torch
@@ -282,34 +359,36 @@ def main():
     opts = nz.make_opts(chunk_elems=wl["chunk"], alphabet=args.alphabet)
     sess = nz.Session(n, opts, dev, reduce=True)
 
-    xs = [torch.from_numpy(wl["x"]).to(dev) for _ in range(max(1, args.rotate))]
+    # R copies of everything a stage reads, so that no stage finds its input in the caches: step i compresses copy
+    # i % R of the message and decompresses / reduces the streams in buffers (i + 1) % R, which were written R - 1
+    # steps (several times the 256 MB Infinity Cache) earlier.  All copies hold the same bytes.
+    R = max(1, args.rotate)
+    xs = [torch.from_numpy(wl["x"]).to(dev) for _ in range(R)]
     xpeer = torch.from_numpy(wl["peer"]).to(dev)
-    outs = [sess.new_stream_buffer() for _ in range(len(xs))]
-    peer_stream = sess.new_stream_buffer()
+    outs = [sess.new_stream_buffer() for _ in range(R)]
+    peers = [sess.new_stream_buffer() for _ in range(R)]
     red_out = sess.new_stream_buffer()
     y = torch.empty(n, dtype=torch.float32, device=dev)
 
-    rc, _ = sess.compress(xpeer, eb, out=peer_stream)
-    r = sess.result()
-    assert rc == 0 and r["status"] == 0
-    peer_bytes = r["bytes"]
-    rc, _ = sess.compress(xs[0], eb, out=outs[0])
-    r0 = sess.result()
-    assert rc == 0 and r0["status"] == 0
-    stream_bytes = r0["bytes"]
-
-    for k in range(1, len(xs)):
-        sess.compress(xs[k], eb, out=outs[k])
+    for k in range(R):
+        rc, _ = sess.compress(xpeer, eb, out=peers[k])
+        r = sess.result()
+        assert rc == 0 and r["status"] == 0
+        peer_bytes = r["bytes"]
+        rc, _ = sess.compress(xs[k], eb, out=outs[k])
+        r0 = sess.result()
+        assert rc == 0 and r0["status"] == 0
+        stream_bytes = r0["bytes"]
 
     def step(i):
-        k = i % len(xs)
+        k, k2 = i % R, (i + 1) % R
         a = b = c = 0
+        if args.only in ("", "decompress"):
+            b = sess.decompress(outs[k2], stream_bytes, n, eb, out=y)[0]
+        if args.only in ("", "reduce"):
+            c = sess.reduce(outs[k2], stream_bytes, peers[k2], peer_bytes, n, eb, out=red_out)[0]
         if args.only in ("", "compress"):
             a = sess.compress(xs[k], eb, out=outs[k])[0]
-        if args.only in ("", "decompress"):
-            b = sess.decompress(outs[k], stream_bytes, n, eb, out=y)[0]
-        if args.only in ("", "reduce"):
-            c = sess.reduce(outs[k], stream_bytes, peer_stream, peer_bytes, n, eb, out=red_out)[0]
         return a | b | c
 
     for _ in range(args.calib_copy):          # elementwise kernel reading 4n bytes and writing 4n bytes
@@ -326,11 +405,12 @@ def main():
     if args.only:
         print(json.dumps(dict(only=args.only, ms_per_step=ms_per_step, GBps=4.0 * n / 1e9 / (ms_per_step * 1e-3))))
         return
+    sess.reduce(outs[0], stream_bytes, peers[0], peer_bytes, n, eb, out=red_out)
     rr = sess.result()
     assert rr["status"] == 0
     reduce_bytes = rr["bytes"]
 
-    # per-stage and per-kernel times from HIP events the library records on its stream
+    # per-stage and per-kernel times from HIP events the library records on its own stream between its kernels
     names = {"compress": ["stats", "codebook", "encode"], "decompress": ["decode", "finish"],
              "reduce": ["init", "stage_a", "add_b", "fix", "codebook", "encode"],
              "reduce_local": ["init", "add_local", "fix", "codebook", "encode"]}
@@ -338,72 +418,91 @@ def main():
     reps = max(5, min(args.steps, 20))
     with nz.KernelTrace(8) as tr:
         for i in range(reps):
-            k = i % len(xs)
-            sess.compress(xs[k], eb, out=outs[k])
-            for j, t in enumerate(tr.kernel_ms()):
-                acc["compress"][j] += t
-            sess.decompress(outs[k], stream_bytes, n, eb, out=y)
+            k, k2 = i % R, (i + 1) % R
+            sess.decompress(outs[k2], stream_bytes, n, eb, out=y)
             for j, t in enumerate(tr.kernel_ms()):
                 acc["decompress"][j] += t
-            sess.reduce(outs[k], stream_bytes, peer_stream, peer_bytes, n, eb, out=red_out)
+            sess.reduce(outs[k2], stream_bytes, peers[k2], peer_bytes, n, eb, out=red_out)
             for j, t in enumerate(tr.kernel_ms()):
                 acc["reduce"][j] += t
             # ring-step variant (not part of `value`): incoming stream + the rank's own fp32 data
-            sess.reduce_local(outs[k], stream_bytes, xpeer, n, eb, out=red_out)
+            sess.reduce_local(outs[k2], stream_bytes, xpeer, n, eb, out=red_out)
             for j, t in enumerate(tr.kernel_ms()):
                 acc["reduce_local"][j] += t
+            sess.compress(xs[k], eb, out=outs[k])
+            for j, t in enumerate(tr.kernel_ms()):
+                acc["compress"][j] += t
     kern = {st: {nm: acc[st][j] / reps for j, nm in enumerate(names[st])} for st in names}
     # what a plain streaming kernel reaches on this machine: elementwise copy of 4 messages' worth of data per launch
     # (16n bytes read + 16n written), large enough that the launch gap does not matter
-    big_in = torch.empty(4 * n, dtype=torch.float32, device=dev).normal_()
-    big_out = torch.empty_like(big_in)
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.add(big_in, 0.0, out=big_out)
-    ev0.record()
-    for i in range(5):
+    copy_gbps = None
+    if not args.calib_copy:                   # (a counter-calibration run keeps its copy kernels of one size only)
+        big_in = torch.empty(4 * n, dtype=torch.float32, device=dev).normal_()
+        big_out = torch.empty_like(big_in)
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.add(big_in, 0.0, out=big_out)
-    ev1.record()
-    torch.cuda.synchronize()
-    del big_in, big_out
-    copy_gbps = 2 * 16.0 * n / 1e9 / (ev0.elapsed_time(ev1) * 1e-3 / 5)
+        ev0.record()
+        for i in range(5):
+            torch.add(big_in, 0.0, out=big_out)
+        ev1.record()
+        torch.cuda.synchronize()
+        del big_in, big_out
+        copy_gbps = 2 * 16.0 * n / 1e9 / (ev0.elapsed_time(ev1) * 1e-3 / 5)
     stage_ms = {st: sum(kern[st].values()) for st in names}
     gb = 4.0 * n / 1e9
     cr = 4.0 * n / stream_bytes
-    # algorithmic bytes each kernel must move per launch (bytes per element x n): see the design doc
+    # Algorithmic bytes: what the method itself must move (fp32 in or out, compressed streams in or out), nothing
+    # this implementation stages in between.  Per operation: compress 4n + S, decompress S + 4n, reduce
+    # S_a + S_b + S_out, ring step S_in + 4n + S_out; per kernel: the part of those bytes that kernel touches.
+    alg_op = {"compress": 4.0 * n + stream_bytes, "decompress": stream_bytes + 4.0 * n,
+              "reduce": stream_bytes + peer_bytes + reduce_bytes, "reduce_local": stream_bytes + 4.0 * n + reduce_bytes}
     alg = {("compress", "stats"): 4.0 * n, ("compress", "encode"): 4.0 * n + stream_bytes,
            ("decompress", "decode"): 4.0 * n + stream_bytes,
-           ("reduce", "stage_a"): stream_bytes + 2.0 * n,
-           ("reduce", "add_b"): peer_bytes + 2.0 * n + 2.0 * n,
-           ("reduce", "encode"): 2.0 * n + reduce_bytes}      # kernels of the step only (the ring-step variant is extra)
+           ("reduce", "stage_a"): float(stream_bytes), ("reduce", "add_b"): float(peer_bytes),
+           ("reduce", "encode"): float(reduce_bytes)}      # kernels of the step only (the ring-step variant is extra)
     dom = max(alg, key=lambda k: kern[k[0]][k[1]])
     dom_ms = kern[dom[0]][dom[1]]
     achieved = alg[dom] / (dom_ms * 1e-3) / 1e9
     roofline = dict(bound="hbm", kernel="%s/%s" % dom, achieved=achieved, peak=HBM_PEAK_GBPS, unit="GB/s",
                     frac=achieved / HBM_PEAK_GBPS, traffic=read_traffic(args.traffic_file, wl["name"], "%s/%s" % dom),
                     kernel_ms=dom_ms, algorithmic_bytes=alg[dom])
+    # the three numbers per operation: fp32-input GB/s, algorithmic bytes / time as a fraction of the HBM peak, and
+    # counter-measured HBM bytes (sum over the operation's kernels in the committed summary) / time
+    ops = {}
+    for st in names:
+        t = stage_ms[st] * 1e-3
+        traffic = None
+        parts = [read_traffic(args.traffic_file, wl["name"], "%s/%s" % (st, nm)) for nm in names[st] if nm not in ("init", "fix", "finish")]
+        if parts and all(v is not None for v in parts):
+            traffic = sum(parts)
+        ops[st] = dict(ms=stage_ms[st], input_GBps=gb / t, input_frac_hbm=gb / t / HBM_PEAK_GBPS,
+                       algorithmic_bytes=alg_op[st], algorithmic_GBps=alg_op[st] / 1e9 / t,
+                       algorithmic_frac_hbm=alg_op[st] / 1e9 / t / HBM_PEAK_GBPS,
+                       traffic_bytes=traffic, traffic_GBps=(traffic / 1e9 / t if traffic else None),
+                       traffic_over_algorithmic=(traffic / alg_op[st] if traffic else None))
 
     out = dict(metric="compress / decompress / fused-reduce GB/s (fp32 input): bytes of the three stages over the step time", value=3 * gb / (ms_per_step * 1e-3),
                unit="GB/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step,
                higher_is_better=True, scaling="weak", vs_baseline=None, dtype="f32+i32", data="synthetic",
-               config=dict(workload=wl["desc"], n_elems=n, chunk_elems=wl["chunk"], alphabet=args.alphabet, eb=eb),
-               stages=dict(compress_GBps=gb / (stage_ms["compress"] * 1e-3),
-                           decompress_GBps=gb / (stage_ms["decompress"] * 1e-3),
-                           reduce_GBps=gb / (stage_ms["reduce"] * 1e-3),
-                           compress_frac_hbm=gb / (stage_ms["compress"] * 1e-3) / HBM_PEAK_GBPS,
-                           decompress_frac_hbm=gb / (stage_ms["decompress"] * 1e-3) / HBM_PEAK_GBPS,
-                           reduce_frac_hbm=gb / (stage_ms["reduce"] * 1e-3) / HBM_PEAK_GBPS,
-                           reduce_local_GBps=gb / (stage_ms["reduce_local"] * 1e-3),
+               config=dict(workload=wl["desc"], n_elems=n, chunk_elems=wl["chunk"], alphabet=args.alphabet, eb=eb,
+                           rotate=R),
+               stages=dict(compress_GBps=ops["compress"]["input_GBps"], decompress_GBps=ops["decompress"]["input_GBps"],
+                           reduce_GBps=ops["reduce"]["input_GBps"],
+                           compress_frac_hbm=ops["compress"]["input_frac_hbm"],
+                           decompress_frac_hbm=ops["decompress"]["input_frac_hbm"],
+                           reduce_frac_hbm=ops["reduce"]["input_frac_hbm"],
+                           reduce_local_GBps=ops["reduce_local"]["input_GBps"],
                            copy_kernel_GBps=copy_gbps,
                            compression_ratio=cr, stream_bytes=stream_bytes, reduce_stream_bytes=reduce_bytes,
                            frames=dict(raw=r0["n_raw"], fixed=r0["n_fixed"], huffman=r0["n_huff"]),
-                           kernel_ms=kern),
+                           kernel_ms=kern, operations=ops),
                roofline=roofline)
     if not args.no_cpu_baseline:
         base, ref_stream, ref_reduced = cpu_baseline(wl, args.alphabet)
         out["cpu_baseline"] = base
         got = outs[0][:stream_bytes].cpu().numpy()
         out["bytes_match_oracle"] = bool(got.size == ref_stream.size and (got == ref_stream).all())
-        sess.reduce(outs[0], stream_bytes, peer_stream, peer_bytes, n, eb, out=red_out)
+        sess.reduce(outs[0], stream_bytes, peers[0], peer_bytes, n, eb, out=red_out)
         got = red_out[:sess.result()["bytes"]].cpu().numpy()
         out["reduce_bytes_match_oracle"] = bool(got.size == ref_reduced.size and (got == ref_reduced).all())
         sess.decompress(outs[0], stream_bytes, n, eb, out=y)

@@ -17,10 +17,13 @@ import glob
 import os
 import sys
 
-KERNELS = [("k_stats", "compress/stats"), ("k_codebook", "*/codebook"), ("k_encode<0>", "compress/encode"),
-           ("k_encode<1>", "reduce/encode"), ("k_decode<0, 256>", "decompress/decode"),
-           ("k_decode<1, 256>", "reduce/stage_a"), ("k_decode<2, 512>", "reduce/add_b"),
-           ("k_decode<3, 512>", "reduce_local/add_local")]
+KERNELS = [("k_stats", ["compress/stats"]), ("k_codebook", ["compress/codebook", "reduce/codebook", "reduce_local/codebook"]),
+           ("k_encode<0>", ["compress/encode"]), ("k_encode<1>", ["reduce/encode", "reduce_local/encode"]),
+           ("k_decode<0, 256>", ["decompress/decode"]), ("k_decode_finish", ["decompress/finish"]),
+           ("k_decode<1, 256>", ["reduce/stage_a"]), ("k_decode<2, 512>", ["reduce/add_b"]),
+           ("k_decode<3, 512>", ["reduce_local/add_local"]), ("k_fix", ["reduce/fix", "reduce_local/fix"]),
+           ("k_rea_plan", ["compress_rea/plan"]), ("k_rea_encode", ["compress_rea/encode"]),
+           ("k_rea_finish", ["compress_rea/finish"])]
 
 
 def per_kernel(d, counter):
@@ -55,12 +58,11 @@ def main():
     sf, sw = copy_bytes / (cf * 1024.0), copy_bytes / (cw * 1024.0)
     print("# calibration: copy kernel of %d bytes each way read FETCH_SIZE=%.0f KiB, WRITE_SIZE=%.0f KiB "
           "-> scale %.4f / %.4f" % (copy_bytes, cf, cw, sf, sw))
-    for needle, name in KERNELS:
+    for needle, names in KERNELS:
         f, w = pick(fetch, needle), pick(write, needle)
         if not f or not w:
             continue
         fb, wb = sf * 1024.0 * sum(f) / len(f), sw * 1024.0 * sum(w) / len(w)
-        names = ["compress/codebook", "reduce/codebook"] if name.startswith("*") else [name]
         for nm in names:
             print("%s %s %.0f %.0f" % (workload, nm, fb, wb))
 
