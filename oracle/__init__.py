@@ -31,6 +31,27 @@ class Result(C.Structure):
         return {k: int(getattr(self, k)) for k, _ in self._fields_ if k != "reserved"}
 
 
+class Context(C.Structure):
+    _fields_ = [("valid", C.c_uint32), ("K", C.c_uint32), ("len", C.c_uint8 * 1024), ("code", C.c_uint32 * 1024)]
+
+
+class ReaOpts(C.Structure):
+    _fields_ = [("sample_bytes", C.c_uint32), ("small_batch_bytes", C.c_uint32)]
+
+
+class ReaResult(C.Structure):
+    _fields_ = [("span_bytes", C.c_uint64), ("wire_bytes", C.c_uint64), ("status", C.c_uint32), ("n_frames", C.c_uint32),
+                ("n_raw", C.c_uint32), ("n_fixed", C.c_uint32), ("n_huff", C.c_uint32), ("n_fallback", C.c_uint32)]
+
+    def as_dict(self):
+        return {k: int(getattr(self, k)) for k, _ in self._fields_}
+
+
+class ReaPlan(C.Structure):
+    _fields_ = [("n_s", C.c_uint32), ("sample_ok", C.c_uint32), ("w_s", C.c_uint32), ("sample_bits", C.c_uint64),
+                ("pred_payload", C.c_uint64 * 3), ("plan", C.c_int)]
+
+
 def make_opts(chunk_elems=0, seg_syms=0, alphabet=0, force_codec=-1, min_gain_permil=0, huff_min_bytes=0):
     return Opts(chunk_elems, seg_syms, alphabet, force_codec, min_gain_permil, huff_min_bytes)
 
@@ -65,6 +86,11 @@ def lib():
         L.nzo_frame_plan.argtypes = [vp, C.c_uint32, C.c_int, C.POINTER(Opts), vp, vp, vp, vp, vp, vp, vp]
         L.nzo_frame_encode.argtypes = [vp, vp, C.c_uint32, C.c_int, C.POINTER(Opts), C.c_uint32, vp, sz]
         L.nzo_frame_encode.restype = C.c_int64
+        L.nzo_context_build.argtypes = [vp, sz, f32, C.POINTER(Opts), C.POINTER(Context)]
+        L.nzo_rea_plan_frame.argtypes = [vp, C.c_uint32, f32, C.POINTER(Opts), C.POINTER(ReaOpts), C.POINTER(Context),
+                                         C.POINTER(ReaPlan)]
+        L.nzo_compress_rea.argtypes = [vp, sz, f32, C.POINTER(Opts), C.POINTER(ReaOpts), C.POINTER(Context), vp, sz,
+                                       C.POINTER(ReaResult), vp]
         _lib = L
     return _lib
 
@@ -213,3 +239,42 @@ def frame_encode(q, codec, opts=None, step_bits=0, rawbits=None):
     if t < 0:
         raise ValueError("frame_encode failed: %d" % t)
     return dst[:t].copy()
+
+
+def context_build(sample, eb, opts=None):
+    """Huffman context (cached codebook) from a calibration message of at most 2^20 values."""
+    x = np.ascontiguousarray(sample, dtype=np.float32)
+    ctx = Context()
+    rc = lib().nzo_context_build(_ptr(x), x.size, C.c_float(eb), C.byref(opts) if opts is not None else None, C.byref(ctx))
+    if rc:
+        raise ValueError("context_build failed: %d" % rc)
+    return ctx
+
+
+def rea_plan_frame(x, eb, opts=None, ropts=None, ctx=None):
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    P = ReaPlan()
+    rc = lib().nzo_rea_plan_frame(_ptr(x), x.size, C.c_float(eb), C.byref(opts) if opts is not None else None,
+                                  C.byref(ropts) if ropts is not None else None,
+                                  C.byref(ctx) if ctx is not None else None, C.byref(P))
+    if rc:
+        raise ValueError("rea_plan_frame failed: %d" % rc)
+    return dict(n_s=int(P.n_s), sample_ok=bool(P.sample_ok), w_s=int(P.w_s), sample_bits=int(P.sample_bits),
+                pred_payload=[int(v) for v in P.pred_payload], plan=int(P.plan))
+
+
+def compress_rea(x, eb, opts=None, ropts=None, ctx=None, cap=None):
+    """Sampled arbitration (Algorithm 1).  Returns (slotted stream trimmed to its span, ReaResult, rc, planned codec
+    per frame)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if cap is None:
+        o = opts if opts is not None else make_opts()
+        cap = compress_bound(x.size, make_opts(o.chunk_elems, o.seg_syms, o.alphabet, -1, 0, 0))
+    out = np.zeros(max(cap, 1), np.uint8)
+    res = ReaResult()
+    chunk = (opts.chunk_elems if opts is not None and opts.chunk_elems else 262144)
+    plans = np.zeros(max(1, (x.size + chunk - 1) // chunk), np.uint8)
+    rc = lib().nzo_compress_rea(_ptr(x), x.size, C.c_float(eb), C.byref(opts) if opts is not None else None,
+                                C.byref(ropts) if ropts is not None else None,
+                                C.byref(ctx) if ctx is not None else None, _ptr(out), cap, C.byref(res), _ptr(plans))
+    return out[:res.span_bytes].copy(), res, rc, plans

@@ -875,3 +875,233 @@ int64_t nzo_frame_encode(const int32_t* q, const uint32_t* rawbits, uint32_t nf,
     free(P);
     return t;
 }
+
+/* ------------------------------------------------------------------ */
+/* 10. sampled runtime entropy arbitration (REA), Sec. IV-C, Eq. 1-2,   */
+/*     Algorithm 1 taken literally: the plan is made from a bounded      */
+/*     sample and a cached Huffman context, only the selected codec      */
+/*     touches the full frame, the realized size is validated and RAW    */
+/*     is the fallback.                                                  */
+/* ------------------------------------------------------------------ */
+
+/*
+ * The Huffman context ("pre-initialized Huffman context huffCtx", "cached codebook", Sec. IV-C): one
+ * canonical prefix code over the K symbols of the alphabet, built ahead of time and shared by all frames.
+ * The paper does not say how it is initialised.  Format v1: from a calibration message of at most 2^20
+ * values (same quantizer), count the symbols, add one to every count (so that every symbol, the escape
+ * included, owns a code and any frame can be coded), build the optimal lengths with the two-queue rule of
+ * section 2 and assign canonical codes.  With at most 2^20 + K <= Fib(31) counted symbols no length exceeds 28.
+ */
+typedef struct {
+    uint32_t valid;                /* 1 once built; REA's "context validity" gate */
+    uint32_t K;                    /* alphabet the code was built for             */
+    uint8_t  len[NZO_MAX_K];
+    uint32_t code[NZO_MAX_K];
+} nzo_context;
+
+int nzo_context_build(const float* sample, size_t n_s, float eb, const nzo_opts* opts, nzo_context* ctx) {
+    nzo_opts o; float step, inv;
+    memset(ctx, 0, sizeof *ctx);
+    if (!sample || n_s == 0 || n_s > NZO_MAX_CHUNK) return NZO_ERR_INVALID;
+    if (resolve_opts(opts, &o) || nzo_step_constants(eb, &step, &inv)) return NZO_ERR_INVALID;
+    uint32_t f[NZO_MAX_K];
+    for (uint32_t s = 0; s < o.alphabet; s++) f[s] = 1;
+    for (size_t i = 0; i < n_s; i++) {
+        int32_t q = 0;
+        if (!nzo_quantize_one(sample[i], eb, step, inv, &q)) continue;    /* values that cannot be coded do not count */
+        f[sym_of(nzo_zigzag(q), o.alphabet)]++;
+    }
+    nzo_huffman_lengths(f, o.alphabet, ctx->len);
+    nzo_canonical_codes(ctx->len, o.alphabet, ctx->code);
+    ctx->K = o.alphabet;
+    ctx->valid = 1;
+    return NZO_OK;
+}
+
+typedef struct {
+    uint32_t sample_bytes;         /* SampleWindow: at most this many bytes of the frame's prefix; 0 -> 65536 (Sec. IV-C) */
+    uint32_t small_batch_bytes;    /* SmallBatchFastPath: frames with fewer raw bytes go RAW unprofiled; default 0        */
+} nzo_rea_opts;
+
+typedef struct {
+    uint64_t span_bytes;           /* extent of the slotted stream (what a decoder is handed)                 */
+    uint64_t wire_bytes;           /* stream header + offsets table + the realized frames: what is transmitted */
+    uint32_t status, n_frames, n_raw, n_fixed, n_huff;
+    uint32_t n_fallback;           /* frames planned as FIXEDLEN / HUFFMAN whose realized output was rejected  */
+} nzo_rea_result;
+
+/* One frame's plan (ProfileSample + ArbitratePlan), exposed for the pins. */
+typedef struct {
+    uint32_t n_s;                  /* sampled elements                                  */
+    uint32_t sample_ok;            /* every sampled element quantizable                 */
+    uint32_t w_s;                  /* width implied by the sample's largest zigzag code */
+    uint64_t sample_bits;          /* Huffman bits of the sample under the context      */
+    uint64_t pred_payload[3];      /* predicted payload bytes per codec                 */
+    int      plan;                 /* planned codec                                     */
+} nzo_rea_plan;
+
+/*
+ * ProfileSample + ArbitratePlan for one frame of nf elements starting at x (Algorithm 1, "Arbitration
+ * overhead"): the sample is the prefix of min(nf, sample_bytes/4) elements; FIXEDLEN's width is the bit
+ * length of the sample's largest zigzag code (the max-|x| scan); HUFFMAN's size follows the sample's
+ * K-bin histogram and the context's code lengths (expected code length), scaled from the sample to the
+ * frame with integer arithmetic, rounded up: bits = ceil(sample_bits * nf / n_s).  Predicted payloads
+ * include the codec's tables.  A candidate is admissible if its predicted payload fits the payload
+ * capacity (the RAW size: a frame's slot holds a RAW frame), meets the minimum gain, and -- HUFFMAN --
+ * the context is valid for this alphabet and rawBytes >= T_huff.  Eq. 2 with transmitted size as the
+ * cost: smallest predicted total, ties to the lower codec id; a pinned codec replaces the choice.
+ */
+static void rea_plan_frame(const float* x, uint32_t nf, float eb, float step, float inv, const nzo_opts* o,
+                           const nzo_rea_opts* ro, const nzo_context* ctx, nzo_rea_plan* P) {
+    memset(P, 0, sizeof *P);
+    const uint32_t K = o->alphabet;
+    const uint64_t rawb = 4ull * nf;
+    (void)step;
+    P->pred_payload[NZO_RAW] = rawb;
+    P->plan = NZO_RAW;
+    if (rawb < ro->small_batch_bytes) return;                    /* SmallBatchFastPath */
+    P->n_s = ro->sample_bytes / 4u < nf ? ro->sample_bytes / 4u : nf;
+    if (P->n_s == 0) return;
+    const int ctx_ok = ctx && ctx->valid && ctx->K == K;
+    uint32_t zmax = 0;
+    P->sample_ok = 1;
+    for (uint32_t i = 0; i < P->n_s; i++) {
+        int32_t q = 0;
+        if (!nzo_quantize_one(x[i], eb, step, inv, &q)) { P->sample_ok = 0; break; }
+        uint32_t z = nzo_zigzag(q);
+        if (z > zmax) zmax = z;
+        if (ctx_ok) { uint32_t s = sym_of(z, K); P->sample_bits += ctx->len[s] + (s == 0 ? 32u : 0u); }
+    }
+    if (!P->sample_ok) return;                                   /* the sample already shows the frame cannot be coded */
+    P->w_s = (uint32_t)bit_length32(zmax);
+    const uint64_t nseg = (nf + o->seg_syms - 1) / o->seg_syms;
+    const uint64_t pred_bits = (P->sample_bits * nf + P->n_s - 1) / P->n_s;
+    P->pred_payload[NZO_FIXEDLEN] = 4ull * (((uint64_t)nf * P->w_s + 31u) / 32u);
+    P->pred_payload[NZO_HUFFMAN] = pad4(K) + pad4(2ull * nseg) + 4ull * ((pred_bits + 31u) / 32u);
+    if (o->force_codec >= 0) {
+        P->plan = (o->force_codec == NZO_HUFFMAN && !ctx_ok) ? NZO_RAW : o->force_codec;
+        return;
+    }
+    uint64_t best_total = pad16(NZO_HDR_BYTES + rawb);
+    for (int c = NZO_FIXEDLEN; c <= NZO_HUFFMAN; c++) {
+        if (c == NZO_HUFFMAN && (!ctx_ok || rawb < o->huff_min_bytes)) continue;
+        const uint64_t p = P->pred_payload[c];
+        if (p > rawb) continue;                                  /* predicted payload must fit the payload capacity */
+        if ((rawb - p) * 1000ull < (uint64_t)o->min_gain_permil * rawb) continue;
+        const uint64_t t = pad16(NZO_HDR_BYTES + p);
+        if (t < best_total) { best_total = t; P->plan = c; }
+    }
+}
+
+int nzo_rea_plan_frame(const float* x, uint32_t nf, float eb, const nzo_opts* opts, const nzo_rea_opts* ropts,
+                       const nzo_context* ctx, nzo_rea_plan* P) {
+    nzo_opts o; float step, inv;
+    nzo_rea_opts ro = { 65536u, 0u };
+    if (ropts) { ro = *ropts; if (ro.sample_bytes == 0) ro.sample_bytes = 65536u; }
+    if (resolve_opts(opts, &o) || nzo_step_constants(eb, &step, &inv) || nf == 0 || nf > o.chunk_elems) return NZO_ERR_INVALID;
+    rea_plan_frame(x, nf, eb, step, inv, &o, &ro, ctx, P);
+    return NZO_OK;
+}
+
+/*
+ * EncodePlan + AcceptRealized + CommitRawOrFail for one frame, written at dst (a slot that holds a RAW
+ * frame).  FIXEDLEN is materialised with the sampled width, HUFFMAN with the context's code; either fails
+ * if an element cannot be quantized, FIXEDLEN also if a zigzag code needs more than w_s bits.  The
+ * realized payload P is accepted if the materialisation succeeded, P <= payload capacity (= rawBytes)
+ * and the minimum gain holds for P; otherwise the frame is committed as RAW with the original values.
+ * Returns the codec committed; *total = the frame's padded bytes; *fell_back = 1 if a non-RAW plan was
+ * rejected.
+ */
+static int rea_commit_frame(uint8_t* dst, const float* x, uint32_t nf, float eb, float step, float inv,
+                            const nzo_opts* o, const nzo_context* ctx, const nzo_rea_plan* P, uint32_t step_bits,
+                            int32_t* q, uint32_t* rb, frame_plan* FP, uint64_t* total, int* fell_back) {
+    const uint64_t rawb = 4ull * nf;
+    *fell_back = 0;
+    int ok = 1;
+    for (uint32_t i = 0; i < nf; i++) {
+        rb[i] = f32_bits(x[i]);
+        q[i] = 0;
+        if (P->plan != NZO_RAW && !nzo_quantize_one(x[i], eb, step, inv, &q[i])) ok = 0;
+    }
+    memset(FP, 0, sizeof *FP);
+    FP->payload[NZO_RAW] = rawb; FP->total[NZO_RAW] = pad16(NZO_HDR_BYTES + rawb);
+    int codec = NZO_RAW;
+    if (P->plan == NZO_FIXEDLEN && ok) {
+        const uint32_t w = P->w_s;
+        for (uint32_t i = 0; i < nf && ok; i++) if (w < 32u && (nzo_zigzag(q[i]) >> w) != 0u) ok = 0;
+        FP->w = w;
+        FP->payload[NZO_FIXEDLEN] = 4ull * (((uint64_t)nf * w + 31u) / 32u);
+        codec = NZO_FIXEDLEN;
+    } else if (P->plan == NZO_HUFFMAN && ok) {
+        const uint32_t K = o->alphabet;
+        FP->nsym = K;
+        memcpy(FP->len, ctx->len, K); memcpy(FP->code, ctx->code, 4u * K);
+        FP->nseg = (nf + o->seg_syms - 1) / o->seg_syms;
+        for (uint32_t i = 0; i < nf; i++) { uint32_t s = sym_of(nzo_zigzag(q[i]), K); FP->huff_bits += FP->len[s] + (s == 0 ? 32u : 0u); }
+        FP->payload[NZO_HUFFMAN] = pad4(K) + pad4(2ull * FP->nseg) + 4ull * ((FP->huff_bits + 31u) / 32u);
+        codec = NZO_HUFFMAN;
+    }
+    if (codec != NZO_RAW) {
+        const uint64_t p = FP->payload[codec];
+        if (!ok || p > rawb || (rawb - p) * 1000ull < (uint64_t)o->min_gain_permil * rawb) codec = NZO_RAW;   /* AcceptRealized */
+    }
+    if (codec == NZO_RAW && P->plan != NZO_RAW) *fell_back = 1;
+    FP->total[codec] = pad16(NZO_HDR_BYTES + FP->payload[codec]);
+    write_frame(dst, codec, q, rb, nf, FP, o, step_bits);
+    *total = FP->total[codec];
+    return codec;
+}
+
+/*
+ * Whole message.  Stream layout ("slotted"): the same container as nzo_compress, but frame k sits at the
+ * fixed offset base + k * slot, slot = pad16(32 + 4*chunk_elems) -- each frame is materialised in a slot
+ * that can hold its RAW form, as the paper's frames are materialised in a staging bank, and its
+ * byte-accurate length (header: payloadBytes) is what a transport would send (Sec. IV-D).  The bytes
+ * between a frame's end and the next slot are not part of the stream (zero here).  total_bytes in the
+ * stream header = end of the last frame.  cap must hold every slot (nzo_compress_bound), else
+ * NZO_ERR_CAPACITY and nothing is published.  The stream decodes with nzo_decompress unchanged.
+ */
+int nzo_compress_rea(const float* x, size_t n, float eb, const nzo_opts* opts, const nzo_rea_opts* ropts,
+                     const nzo_context* ctx, uint8_t* out, size_t cap, nzo_rea_result* res, uint8_t* plans) {
+    nzo_opts o; float step, inv;
+    nzo_rea_opts ro = { 65536u, 0u };
+    nzo_rea_result dummy;
+    if (!res) res = &dummy;
+    memset(res, 0, sizeof *res);
+    if (ropts) { ro = *ropts; if (ro.sample_bytes == 0) ro.sample_bytes = 65536u; }
+    if (n == 0 || !x || !out) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
+    if (resolve_opts(opts, &o) || nzo_step_constants(eb, &step, &inv)) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
+    const uint64_t nfr64 = (n + o.chunk_elems - 1) / o.chunk_elems;
+    if (nfr64 > 0xFFFFFFFFull) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
+    const uint32_t nfr = (uint32_t)nfr64;
+    res->n_frames = nfr;
+    const uint64_t base = frames_base(nfr), slot = pad16(NZO_HDR_BYTES + 4ull * o.chunk_elems);
+    const uint32_t last_nf = (uint32_t)(n - (uint64_t)(nfr - 1) * o.chunk_elems);
+    const uint64_t need = base + (uint64_t)(nfr - 1) * slot + pad16(NZO_HDR_BYTES + 4ull * last_nf);
+    if (need > cap) { res->status = NZO_ERR_CAPACITY; return NZO_ERR_CAPACITY; }
+    int32_t* q = (int32_t*)malloc(4ull * o.chunk_elems);
+    uint32_t* rb = (uint32_t*)malloc(4ull * o.chunk_elems);
+    frame_plan* FP = (frame_plan*)malloc(sizeof *FP);
+    if (!q || !rb || !FP) { free(q); free(rb); free(FP); res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
+    memset(out, 0, (size_t)need);
+    const uint32_t step_bits = f32_bits(step);
+    uint64_t wire = base, end = base;
+    for (uint32_t k = 0; k < nfr; k++) {
+        const uint64_t i0 = (uint64_t)k * o.chunk_elems;
+        const uint32_t nf = (uint32_t)((n - i0 < o.chunk_elems) ? (n - i0) : o.chunk_elems);
+        const uint64_t off = base + (uint64_t)k * slot;
+        nzo_rea_plan P;
+        uint64_t total = 0; int fb = 0;
+        rea_plan_frame(x + i0, nf, eb, step, inv, &o, &ro, ctx, &P);
+        int c = rea_commit_frame(out + off, x + i0, nf, eb, step, inv, &o, ctx, &P, step_bits, q, rb, FP, &total, &fb);
+        put_u64(out + NZO_STREAM_HDR + 8ull * k, off);
+        if (plans) plans[k] = (uint8_t)P.plan;
+        wire += total; end = off + total;
+        res->n_fallback += (uint32_t)fb;
+        if (c == NZO_RAW) res->n_raw++; else if (c == NZO_FIXEDLEN) res->n_fixed++; else res->n_huff++;
+    }
+    free(q); free(rb); free(FP);
+    write_stream_header(out, n, &o, nfr, step_bits, end);
+    res->span_bytes = end; res->wire_bytes = wire; res->status = NZO_OK;
+    return NZO_OK;
+}

@@ -32,6 +32,22 @@ static int run_case(size_t n, uint32_t chunk, uint32_t K, uint32_t seg, int forc
     nzo_opts od = o; od.force_codec = -1;
     if (nzo_reduce_frames(sa, ra.bytes, sb, rb.bytes, sc, cap, n, eb, &od, &rc)) return 5;
     if (nzo_reduce_local(sa, ra.bytes, y, sc, cap, n, eb, &od, &rc)) return 6;
+    /* sampled arbitration with a cached context: valid, pinned, without context, capacity one slot short */
+    {
+        nzo_context ctx; nzo_rea_result rr; nzo_rea_opts ro = { 4096u, 0u };
+        size_t cal = n < 5000 ? n : 5000;
+        if (nzo_context_build(y, cal, eb, &od, &ctx)) return 8;
+        size_t rcap = nzo_compress_bound(n, &od);
+        uint8_t* sr = (uint8_t*)malloc(rcap);
+        if (nzo_compress_rea(x, n, eb, &od, NULL, &ctx, sr, rcap, &rr, NULL)) return 9;
+        if (nzo_decompress(sr, rr.span_bytes, z, n, eb, &rc)) return 10;
+        for (size_t i = 0; i < n; i++) if (isfinite(x[i]) && fabs((double)x[i] - (double)z[i]) > (double)eb) return 11;
+        if (nzo_compress_rea(y, n, eb, &o, &ro, &ctx, sr, rcap, &rr, NULL)) return 12;
+        if (nzo_decompress(sr, rr.span_bytes, z, n, eb, &rc)) return 13;
+        if (nzo_compress_rea(y, n, eb, &od, &ro, NULL, sr, rcap, &rr, NULL)) return 14;
+        if (rcap > 16 && nzo_compress_rea(y, n, eb, &od, &ro, &ctx, sr, rcap - 16, &rr, NULL) != NZO_ERR_CAPACITY) return 15;
+        free(sr);
+    }
     /* too small an output: capacity error, nothing written past cap */
     uint8_t* small = (uint8_t*)malloc(ra.bytes > 16 ? ra.bytes - 16 : 1);
     if (nzo_compress(x, n, eb, &o, small, ra.bytes > 16 ? ra.bytes - 16 : 1, &rc) != NZO_ERR_CAPACITY) return 7;
