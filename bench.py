@@ -413,9 +413,24 @@ def main():
     # per-stage and per-kernel times from HIP events the library records on its own stream between its kernels
     names = {"compress": ["stats", "codebook", "encode"], "decompress": ["decode", "finish"],
              "reduce": ["init", "stage_a", "add_b", "fix", "codebook", "encode"],
-             "reduce_local": ["init", "add_local", "fix", "codebook", "encode"]}
+             "reduce_local": ["init", "add_local", "fix", "codebook", "encode"],
+             "compress_rea": ["plan", "encode", "finish"]}
     acc = {k: [0.0] * len(v) for k, v in names.items()}
     reps = max(5, min(args.steps, 20))
+    # the sampled-arbitration compress (Algorithm 1 taken literally; not part of `value`): context from the first
+    # 64 KiB-sample's worth of the message, one pass over the input, frames in RAW-sized slots
+    ctx = torch.zeros(nz.nz_context_bytes(), dtype=torch.uint8, device=dev)
+    assert nz.nz_context_build(xs[0], min(n, 65536), eb, opts, ctx, sess.ws, sess.ws_bytes) == 0
+    rea_out = torch.empty(sess.cap, dtype=torch.uint8, device=dev)
+    rea_res = torch.zeros(48, dtype=torch.uint8, device=dev)
+    rea_wsb = nz.nz_rea_workspace_bytes(n, opts)
+    rea_ws = torch.empty(rea_wsb, dtype=torch.uint8, device=dev)
+
+    def compress_rea(k):
+        return nz.nz_compress_rea(xs[k], n, eb, ctx, rea_out, sess.cap, rea_res, opts, None, rea_ws, rea_wsb)
+    assert compress_rea(0) == 0
+    rea = nz.read_rea_result(rea_res)
+    assert rea["status"] == 0
     with nz.KernelTrace(8) as tr:
         for i in range(reps):
             k, k2 = i % R, (i + 1) % R
@@ -432,7 +447,17 @@ def main():
             sess.compress(xs[k], eb, out=outs[k])
             for j, t in enumerate(tr.kernel_ms()):
                 acc["compress"][j] += t
+            compress_rea(k2)
+            for j, t in enumerate(tr.kernel_ms()):
+                acc["compress_rea"][j] += t
     kern = {st: {nm: acc[st][j] / reps for j, nm in enumerate(names[st])} for st in names}
+    # frames on which the sampled plan committed another codec than the exact selector (mis-selection count)
+    nfr = r0["n_frames"]
+    offs_e = outs[0][64:64 + 8 * nfr].cpu().numpy().view(np.uint64).astype(np.int64)
+    offs_r = rea_out[64:64 + 8 * nfr].cpu().numpy().view(np.uint64).astype(np.int64)
+    cod_e = outs[0].cpu().numpy()[(offs_e + 4)]
+    cod_r = rea_out.cpu().numpy()[(offs_r + 4)]
+    misselected = (cod_e != cod_r).sum()
     # what a plain streaming kernel reaches on this machine: elementwise copy of 4 messages' worth of data per launch
     # (16n bytes read + 16n written), large enough that the launch gap does not matter
     copy_gbps = None
@@ -455,7 +480,8 @@ def main():
     # this implementation stages in between.  Per operation: compress 4n + S, decompress S + 4n, reduce
     # S_a + S_b + S_out, ring step S_in + 4n + S_out; per kernel: the part of those bytes that kernel touches.
     alg_op = {"compress": 4.0 * n + stream_bytes, "decompress": stream_bytes + 4.0 * n,
-              "reduce": stream_bytes + peer_bytes + reduce_bytes, "reduce_local": stream_bytes + 4.0 * n + reduce_bytes}
+              "reduce": stream_bytes + peer_bytes + reduce_bytes, "reduce_local": stream_bytes + 4.0 * n + reduce_bytes,
+              "compress_rea": 4.0 * n + rea["wire_bytes"]}
     alg = {("compress", "stats"): 4.0 * n, ("compress", "encode"): 4.0 * n + stream_bytes,
            ("decompress", "decode"): 4.0 * n + stream_bytes,
            ("reduce", "stage_a"): float(stream_bytes), ("reduce", "add_b"): float(peer_bytes),
@@ -495,7 +521,13 @@ def main():
                            copy_kernel_GBps=copy_gbps,
                            compression_ratio=cr, stream_bytes=stream_bytes, reduce_stream_bytes=reduce_bytes,
                            frames=dict(raw=r0["n_raw"], fixed=r0["n_fixed"], huffman=r0["n_huff"]),
-                           kernel_ms=kern, operations=ops),
+                           kernel_ms=kern, operations=ops,
+                           compress_rea=dict(GBps=ops["compress_rea"]["input_GBps"], frac_hbm=ops["compress_rea"]["input_frac_hbm"],
+                                             wire_bytes=rea["wire_bytes"], compression_ratio=4.0 * n / rea["wire_bytes"],
+                                             ratio_loss_vs_exact=1.0 - stream_bytes / rea["wire_bytes"],
+                                             frames=dict(raw=rea["n_raw"], fixed=rea["n_fixed"], huffman=rea["n_huff"],
+                                                         fallback=rea["n_fallback"]),
+                                             frames_with_other_codec_than_exact=int(misselected))),
                roofline=roofline)
     if not args.no_cpu_baseline:
         base, ref_stream, ref_reduced = cpu_baseline(wl, args.alphabet)

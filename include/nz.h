@@ -105,6 +105,51 @@ nz_status nz_compress(const float* d_in, size_t n, float eb, void* d_out, size_t
                       const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream);
 
 /*
+ * Sampled runtime entropy arbitration: Algorithm 1 taken literally (Sec. IV-C).
+ *
+ * nz_context_build makes the "pre-initialized Huffman context" / "cached codebook" of Sec. IV-C: one canonical
+ * code over the K symbols of the alphabet, built from a calibration message d_sample[0..n_sample) (n_sample <=
+ * 2^20, quantized with eb like any message): symbol counts plus one each (every symbol, the escape included, owns
+ * a code), optimal lengths, canonical codes.  d_ctx: device memory of nz_context_bytes() bytes, 16-byte aligned,
+ * reusable for any number of messages; d_ws: at least 4096 bytes of device scratch.
+ *
+ * nz_compress_rea: per frame, ProfileSample reads a prefix of at most sample_bytes (64 KiB) of the frame;
+ * ArbitratePlan predicts FIXEDLEN from the width of the sample's largest code and HUFFMAN from the sample's
+ * expected code length under the context, applies the gates (SmallBatchFastPath, T_huff = huff_min_bytes, context
+ * valid for this alphabet, minimum gain, payload capacity) and takes the smallest predicted frame (Eq. 2 with
+ * transmitted size as the cost; force_codec pins the plan); EncodePlan runs only the planned codec over the frame,
+ * in one pass over the input; AcceptRealized checks the realized payload (materialised, fits, minimum gain) and
+ * CommitRawOrFail stores the frame RAW otherwise.  d_ctx may be NULL (no Huffman).
+ * Output: an NZ stream that nz_decompress / nz_reduce_* read like any other, except that frame k starts at the
+ * fixed offset 64 + pad16(8*n_frames) + k * pad16(32 + 4*chunk_elems): every frame is materialised in a slot that
+ * can hold its RAW form (the paper's staging bank) and carries its byte-accurate length in its header; the bytes
+ * between a frame's end and the next slot are not written.  out_cap must hold every slot (nz_compress_bound with
+ * force_codec = -1), else NZ_ERR_CAPACITY (return value and d_res->status) and nothing is written.
+ *   d_ws/ws_bytes  device scratch of at least nz_rea_workspace_bytes(n, opts).
+ */
+typedef struct {
+    uint32_t sample_bytes;       /* SampleWindow: bytes of the frame's prefix that are profiled; 0 = 65536       */
+    uint32_t small_batch_bytes;  /* SmallBatchFastPath: frames with fewer raw bytes are RAW unprofiled; default 0 */
+} nz_rea_opts;
+
+typedef struct {                 /* lives in DEVICE memory, 16-byte aligned */
+    uint64_t span_bytes;         /* extent of the slotted stream: what nz_decompress is handed (0 on error)      */
+    uint64_t wire_bytes;         /* stream header + offsets table + realized frames: what a transport sends      */
+    uint32_t status;             /* nz_status                                                                     */
+    uint32_t n_frames;
+    uint32_t n_raw, n_fixed, n_huff;   /* frames per committed codec                                              */
+    uint32_t n_fallback;         /* frames planned FIXEDLEN / HUFFMAN whose realized output was rejected (now RAW) */
+} nz_rea_result;
+
+size_t    nz_context_bytes(void);
+nz_status nz_context_build(const float* d_sample, size_t n_sample, float eb, const nz_opts* opts, void* d_ctx, void* d_ws,
+                           size_t ws_bytes, void* stream);
+size_t    nz_rea_workspace_bytes(size_t n, const nz_opts* opts);
+nz_status nz_compress_rea(const float* d_in, size_t n, float eb, const void* d_ctx, void* d_out, size_t out_cap,
+                          nz_rea_result* d_res, const nz_opts* opts, const nz_rea_opts* ropts, void* d_ws, size_t ws_bytes,
+                          void* stream);
+
+/*
  * nz_compress for callers that cannot allocate or hand over scratch memory: code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc.  Same result, byte for byte, as nz_compress; the
  * workspace is an array that lives inside the library on every GPU (nz_static_scratch_bytes() bytes, 8 MiB,

@@ -26,7 +26,12 @@ def make_opts(chunk_elems=0, seg_syms=0, alphabet=0, force_codec=-1, min_gain_pe
     return Opts(chunk_elems, seg_syms, alphabet, force_codec, min_gain_permil, huff_min_bytes)
 
 
+class ReaOpts(C.Structure):
+    _fields_ = [("sample_bytes", C.c_uint32), ("small_batch_bytes", C.c_uint32)]
+
+
 RESULT_BYTES = 32   # sizeof(nz_result)
+REA_RESULT_BYTES = 40   # sizeof(nz_rea_result)
 _lib = None
 
 
@@ -50,6 +55,13 @@ def lib():
         L.nz_static_scratch_bytes.restype = sz
         L.nz_compress_static.argtypes = [vp, sz, f32, vp, sz, vp, po, vp]
         L.nz_compress_static.restype = C.c_int
+        L.nz_context_bytes.restype = sz
+        L.nz_context_build.argtypes = [vp, sz, f32, po, vp, vp, sz, vp]
+        L.nz_context_build.restype = C.c_int
+        L.nz_rea_workspace_bytes.argtypes = [sz, po]
+        L.nz_rea_workspace_bytes.restype = sz
+        L.nz_compress_rea.argtypes = [vp, sz, f32, vp, vp, sz, vp, po, C.POINTER(ReaOpts), vp, sz, vp]
+        L.nz_compress_rea.restype = C.c_int
         L.nz_decompress.argtypes = [vp, sz, vp, sz, f32, vp, po, vp, sz, vp]
         L.nz_decompress.restype = C.c_int
         L.nz_reduce_frames.argtypes = [vp, sz, vp, sz, vp, sz, sz, f32, vp, po, vp, sz, vp]
@@ -98,6 +110,33 @@ def nz_compress_static(d_in, n, eb, d_out, out_cap, d_res, opts, stream=None):
     """nz_compress with the library's resident scratch array as workspace (allocates nothing)."""
     return int(lib().nz_compress_static(d_in.data_ptr(), n, C.c_float(eb), d_out.data_ptr(), out_cap, d_res.data_ptr(),
                                         _po(opts), _stream(stream)))
+
+
+def nz_context_bytes():
+    return int(lib().nz_context_bytes())
+
+
+def nz_context_build(d_sample, n_sample, eb, opts, d_ctx, d_ws, ws_bytes, stream=None):
+    return int(lib().nz_context_build(d_sample.data_ptr(), n_sample, C.c_float(eb), _po(opts), d_ctx.data_ptr(),
+                                      d_ws.data_ptr(), ws_bytes, _stream(stream)))
+
+
+def nz_rea_workspace_bytes(n, opts=None):
+    return int(lib().nz_rea_workspace_bytes(n, _po(opts)))
+
+
+def nz_compress_rea(d_in, n, eb, d_ctx, d_out, out_cap, d_res, opts, ropts, d_ws, ws_bytes, stream=None):
+    return int(lib().nz_compress_rea(d_in.data_ptr(), n, C.c_float(eb), d_ctx.data_ptr() if d_ctx is not None else None,
+                                     d_out.data_ptr(), out_cap, d_res.data_ptr(), _po(opts),
+                                     C.byref(ropts) if ropts is not None else None, d_ws.data_ptr(), ws_bytes,
+                                     _stream(stream)))
+
+
+def read_rea_result(d_res):
+    import struct
+    raw = bytes(d_res.cpu().numpy().tobytes()[:REA_RESULT_BYTES])
+    sp, wb, st, nfr, nraw, nfix, nhuf, nfb = struct.unpack("<QQIIIIII", raw)
+    return dict(span_bytes=sp, wire_bytes=wb, status=st, n_frames=nfr, n_raw=nraw, n_fixed=nfix, n_huff=nhuf, n_fallback=nfb)
 
 
 def nz_decompress(d_stream, stream_bytes, d_out, n, eb, d_res, opts, d_ws=None, ws_bytes=0, stream=None):

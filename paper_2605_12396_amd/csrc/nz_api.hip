@@ -165,6 +165,60 @@ nz_status nz_compress_static(const float* d_in, size_t n, float eb, void* d_out,
     return nz_compress(d_in, n, eb, d_out, out_cap, d_res, opts, ws, kStaticScratchBytes, stream);
 }
 
+size_t nz_context_bytes(void) { return sizeof(DevContext); }
+
+nz_status nz_context_build(const float* d_sample, size_t n_sample, float eb, const nz_opts* opts, void* d_ctx, void* d_ws,
+                           size_t ws_bytes, void* stream) {
+    Opts o; float step, inv;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (!d_sample || !d_ctx || !d_ws || n_sample == 0 || n_sample > kMaxChunk || !resolve(opts, o) || !step_constants(eb, step, inv))
+        return NZ_ERR_INVALID;
+    if (!aligned16(d_sample) || !aligned16(d_ctx) || !aligned16(d_ws) || ws_bytes < 4u * kMaxK) return NZ_ERR_INVALID;
+    if (launch_context(d_sample, n_sample, eb, step, inv, o.K, reinterpret_cast<uint32_t*>(d_ws),
+                       reinterpret_cast<DevContext*>(d_ctx), st) != hipSuccess) return NZ_ERR_HIP;
+    return NZ_OK;
+}
+
+size_t nz_rea_workspace_bytes(size_t n, const nz_opts* opts) {
+    Opts o;
+    if (!resolve(opts, o) || !geometry_ok(n, o)) return 0;
+    return rea_layout(n, o.chunk).total;
+}
+
+nz_status nz_compress_rea(const float* d_in, size_t n, float eb, const void* d_ctx, void* d_out, size_t out_cap,
+                          nz_rea_result* d_res, const nz_opts* opts, const nz_rea_opts* ropts, void* d_ws, size_t ws_bytes,
+                          void* stream) {
+    Opts o; float step, inv;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (!d_in || !d_out || !d_res || !d_ws || !resolve(opts, o) || !geometry_ok(n, o) || !step_constants(eb, step, inv))
+        return NZ_ERR_INVALID;
+    if (!aligned16(d_in) || !aligned16(d_out) || !aligned16(d_ws) || !aligned16(d_res) || !aligned16(d_ctx)) return NZ_ERR_INVALID;
+    const ReaLayout L = rea_layout(n, o.chunk);
+    if (ws_bytes < L.total) return NZ_ERR_INVALID;
+    const uint32_t nfr = (uint32_t)((n + o.chunk - 1) / o.chunk);
+    const uint64_t slot = pad16h(kHdrBytes + 4ull * o.chunk);
+    const uint64_t last = n - (uint64_t)(nfr - 1) * o.chunk;
+    const uint64_t need = kStreamHdr + pad16h(8ull * nfr) + (uint64_t)(nfr - 1) * slot + pad16h(kHdrBytes + 4ull * last);
+    if (out_cap < need) {                                          // every frame needs its RAW-sized slot: publish nothing
+        if (launch_rea_status(d_res, nfr, NZ_ERR_CAPACITY, st) != hipSuccess) return NZ_ERR_HIP;
+        return NZ_ERR_CAPACITY;
+    }
+    ReaArgs A;
+    A.in = d_in; A.n = n; A.chunk = o.chunk; A.n_frames = nfr; A.K = o.K;
+    A.spf = (o.chunk + kReaSub - 1) / kReaSub; A.gpf = (o.chunk + kEncGroup - 1) / kEncGroup;
+    A.force_codec = o.force; A.min_gain_permil = o.gain; A.huff_min_bytes = o.huff_min;
+    uint32_t sample_bytes = 65536u, small = 0u;
+    if (ropts) { if (ropts->sample_bytes) sample_bytes = ropts->sample_bytes; small = ropts->small_batch_bytes; }
+    A.sample_elems = sample_bytes / 4u; A.small_batch_bytes = small;
+    A.eb = eb; A.step = step; A.inv_step = inv; A.step_bits = bits_of(step);
+    A.ctx = reinterpret_cast<const DevContext*>(d_ctx);
+    A.out = reinterpret_cast<uint8_t*>(d_out); A.slot = slot;
+    A.ws = reinterpret_cast<uint8_t*>(d_ws); A.L = L; A.res = d_res;
+    trace_reset(); trace_mark(st);
+    if (launch_rea(A, st, trace_mark) != hipSuccess) return NZ_ERR_HIP;
+    return NZ_OK;
+}
+
 nz_status nz_decompress(const void* d_stream, size_t stream_bytes, float* d_out, size_t n, float eb,
                         nz_result* d_res, const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream) {
     Opts o; float step, inv;

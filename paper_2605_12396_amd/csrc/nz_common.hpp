@@ -159,7 +159,50 @@ __device__ inline float dequantize1(int32_t q, float step) {
     return (float)q * step;
 }
 
+// ---- sampled arbitration (REA): cached Huffman context and per-call arguments ----
+// Device-resident context record: one canonical code over the K symbols, every symbol coded (Sec. IV-C "cached codebook").
+struct DevContext {
+    uint32_t valid, K, pad_[2];
+    uint8_t  len[kMaxK];        // by symbol (0 = escape): code length, 1..28
+    uint64_t book[kMaxK];       // by min(z, K-1): bit-reversed code | length << 32 (entry K-1 = escape)
+};
+constexpr uint32_t kReaSub = 4096;            // symbols per independently placed piece of a HUFFMAN bitstream (= kEncBlock)
+
+struct ReaLayout { size_t ctrl, desc, fail, zero_end, meta, frag, total; };
+__host__ inline ReaLayout rea_layout(size_t n, uint32_t chunk) {
+    ReaLayout L;
+    const size_t n_frames = (n + chunk - 1) / chunk;
+    const size_t spf = (chunk + kReaSub - 1) / kReaSub;
+    size_t o = 0;
+    L.ctrl = o;  o += sizeof(Ctrl);
+    L.desc = o;  o += align_up(8 * n_frames * spf, 256);
+    L.fail = o;  o += align_up(4 * n_frames, 256);
+    L.zero_end = o;
+    L.meta = o;  o += align_up(sizeof(FrameMeta) * n_frames, 256);
+    L.frag = o;  o += align_up(8 * n_frames * spf, 256);
+    L.total = o;
+    return L;
+}
+
+struct ReaResultRec { uint64_t span_bytes, wire_bytes; uint32_t status, n_frames, n_raw, n_fixed, n_huff, n_fallback; };
+
+struct ReaArgs {
+    const float* in; uint64_t n;
+    uint32_t chunk, n_frames, K, spf, gpf;      // sub-blocks and encoder workgroups per frame
+    int32_t force_codec; uint32_t min_gain_permil, huff_min_bytes;
+    uint32_t sample_elems, small_batch_bytes;
+    float eb, step, inv_step; uint32_t step_bits;
+    const DevContext* ctx;
+    uint8_t* out; uint64_t slot;               // bytes between frame starts
+    uint8_t* ws; ReaLayout L;
+    void* res;                                 // nz_rea_result* (device)
+};
+
 // Launchers (one per translation unit).
+hipError_t launch_context(const float* sample, uint64_t n, float eb, float step, float inv_step, uint32_t K, uint32_t* ghist,
+                          DevContext* ctx, hipStream_t st);
+hipError_t launch_rea(const ReaArgs& A, hipStream_t st, void (*mark)(hipStream_t));
+hipError_t launch_rea_status(void* res, uint32_t n_frames, uint32_t status, hipStream_t st);
 struct CompressArgs {
     const float* in;          // fp32 input (compress) or nullptr (reduce: the sums staged in the workspace are encoded)
     uint64_t n;

@@ -124,68 +124,52 @@ __global__ __launch_bounds__(kStatThreads) void k_stats(CompressArgs A) {
 __device__ inline uint64_t pad4u(uint64_t v) { return (v + 3u) & ~(uint64_t)3u; }
 __device__ inline uint64_t pad16u(uint64_t v) { return (v + 15u) & ~(uint64_t)15u; }
 
-__global__ __launch_bounds__(kBookThreads) void k_codebook(CompressArgs A) {
-    __shared__ uint32_t s_f[kMaxK];
-    __shared__ __align__(16) uint32_t s_key[kMaxK];
-    __shared__ uint32_t s_sorted[kMaxK];
-    __shared__ uint32_t s_w[2 * (kMaxK + 128)];   // leaves [0, m) + sentinels; internal nodes from kMaxK + 128, then sentinels
-    __shared__ uint16_t s_par[2 * kMaxK];
-    __shared__ __align__(4) uint8_t s_len[kMaxK];
-    __shared__ uint16_t s_rank[kMaxK];
-    __shared__ uint32_t s_wcnt[16 * 32], s_cnt[32], s_first[32], s_idx0[32];
-    __shared__ uint64_t s_part[16];
-    __shared__ uint32_t s_fid, s_m, s_nsym, s_zmax, s_unq, s_codec, s_payload, s_total, s_w_fixed;
-    __shared__ uint64_t s_bits, s_off;
+// Shared memory of the code construction (one workgroup of kBookThreads threads, thread = symbol).
+struct BookShared {
+    __align__(16) uint32_t key[kMaxK];
+    uint32_t sorted[kMaxK];
+    uint32_t w[2 * (kMaxK + 128)];    // leaves [0, m) + sentinels; internal nodes from kMaxK + 128, then sentinels
+    uint16_t par[2 * kMaxK];
+    __align__(4) uint8_t len[kMaxK];
+    uint16_t rank[kMaxK];
+    uint32_t wcnt[16 * 32], cnt[32], first[32], idx0[32];
+    uint32_t m, nsym;
+};
 
+// Optimal prefix-code lengths and canonical codes for the counts f (one per thread = symbol; 0 = unused) of an
+// alphabet of K symbols.  Called by all kBookThreads threads of the workgroup.  On return B.len[] holds the lengths,
+// B.nsym = 1 + largest used symbol, and (L, code) are the calling thread's symbol's length and canonical code.
+__device__ inline void book_build(BookShared& B, uint32_t f, uint32_t K, uint32_t& L_out, uint32_t& code_out) {
     const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
-    const uint32_t K = A.K;
-    Ctrl* ctrl = reinterpret_cast<Ctrl*>(A.ws + A.L.ctrl);
-    if (tid == 0) { s_fid = atomicAdd(&ctrl->ticket_book, 1u); s_m = 0; s_nsym = 0; s_zmax = 0; s_unq = 0; }
+    if (tid == 0) { B.m = 0; B.nsym = 0; }
+    B.len[tid] = 0;
     __syncthreads();
-    const uint32_t fid = s_fid;
-    const uint64_t f0 = (uint64_t)fid * A.chunk;
-    const uint32_t nf = (uint32_t)((A.n - f0 < A.chunk) ? (A.n - f0) : A.chunk);
-    const uint32_t sbc = (nf + A.stat_block - 1) / A.stat_block;
-
-    // (1) frame histogram, zmax, quantizable flag
-    uint32_t f = 0;
-    if (tid < K) {
-        const uint32_t* ph = reinterpret_cast<const uint32_t*>(A.ws + A.L.phist) + (size_t)fid * A.sbpf * kMaxK + tid;
-        for (uint32_t b = 0; b < sbc; b++) f += ph[(size_t)b * kMaxK];
-    }
-    s_f[tid] = f;
-    s_len[tid] = 0;
-    if (tid < sbc) {
-        const uint2 pm = reinterpret_cast<const uint2*>(A.ws + A.L.pmeta)[(size_t)fid * A.sbpf + tid];
-        atomicMax(&s_zmax, pm.x);
-        atomicMax(&s_unq, pm.y);
-        // reduce: a sum beyond 2^30 somewhere in the frame has turned it RAW (its fp32 sums were staged by k_fix)
-        if (!A.in) atomicMax(&s_unq, reinterpret_cast<const uint32_t*>(A.ws + A.L.cwide)[(size_t)fid * A.sbpf + tid] & 2u);
-    }
     const bool used = f > 0;
     {
         const uint64_t um = __ballot(used);
-        if (lane == 0 && um) { atomicAdd(&s_m, (uint32_t)__popcll(um)); atomicMax(&s_nsym, wave * 64 + 64 - (uint32_t)__clzll(um)); }
+        if (lane == 0 && um) { atomicAdd(&B.m, (uint32_t)__popcll(um)); atomicMax(&B.nsym, wave * 64 + 64 - (uint32_t)__clzll(um)); }
     }
     // (2) sort used symbols ascending by (count, symbol): rank = number of smaller keys
     const uint32_t key = used ? ((f << 10) | tid) : 0xFFFFFFFFu;
-    s_key[tid] = key;
+    B.key[tid] = key;
     __syncthreads();
-    const uint32_t m = s_m, nsym = s_nsym;
+    const uint32_t m = B.m;
     if (used) {
         uint32_t rank = 0;
-        const uint4* k4 = reinterpret_cast<const uint4*>(s_key);
+        const uint4* k4 = reinterpret_cast<const uint4*>(B.key);
         for (uint32_t j = 0; j < K / 4 || j < 1; j++) {
             const uint4 t = k4[j];
             rank += (t.x < key) + (t.y < key) + (t.z < key) + (t.w < key);
         }
-        s_sorted[rank] = key;
+        B.sorted[rank] = key;
     }
     __syncthreads();
     // leaves in order, followed by sentinels; the internal-node queue starts out all sentinels
     constexpr uint32_t INF = 0xFFFFFFFFu;
-    uint32_t* s_int = s_w + kMaxK + 128;
-    if (tid < m) s_w[tid] = s_sorted[tid] >> 10;
+    uint32_t* s_w = B.w;
+    uint32_t* s_int = B.w + kMaxK + 128;
+    uint16_t* s_par = B.par;
+    if (tid < m) s_w[tid] = B.sorted[tid] >> 10;
     if (tid < 128) { s_w[m + tid] = INF; s_int[kMaxK + tid] = INF; }
     s_int[tid] = INF;
     __syncthreads();
@@ -244,13 +228,52 @@ __global__ __launch_bounds__(kBookThreads) void k_codebook(CompressArgs A) {
             d = 0;
             for (uint32_t x = tid; x != root; x = s_par[x]) d++;
         }
-        s_len[s_sorted[tid] & 1023u] = (uint8_t)d;
+        B.len[B.sorted[tid] & 1023u] = (uint8_t)d;
     }
     __syncthreads();
     // (5) canonical codes
-    canonical_tables<kBookThreads>(s_len, K, s_wcnt, s_cnt, s_first, s_idx0, s_rank);
-    const uint32_t L = s_len[tid];
-    const uint32_t code = L ? (s_first[L] + s_rank[tid]) : 0u;
+    canonical_tables<kBookThreads>(B.len, K, B.wcnt, B.cnt, B.first, B.idx0, B.rank);
+    L_out = B.len[tid];
+    code_out = L_out ? (B.first[L_out] + B.rank[tid]) : 0u;
+}
+
+__global__ __launch_bounds__(kBookThreads) void k_codebook(CompressArgs A) {
+    __shared__ uint32_t s_f[kMaxK];
+    __shared__ BookShared s_b;
+    __shared__ uint64_t s_part[16];
+    __shared__ uint32_t s_fid, s_zmax, s_unq, s_codec, s_payload, s_total, s_w_fixed;
+    __shared__ uint64_t s_bits, s_off;
+    uint32_t* const s_w = s_b.w;
+    uint8_t* const s_len = s_b.len;
+
+    const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const uint32_t K = A.K;
+    Ctrl* ctrl = reinterpret_cast<Ctrl*>(A.ws + A.L.ctrl);
+    if (tid == 0) { s_fid = atomicAdd(&ctrl->ticket_book, 1u); s_zmax = 0; s_unq = 0; }
+    __syncthreads();
+    const uint32_t fid = s_fid;
+    const uint64_t f0 = (uint64_t)fid * A.chunk;
+    const uint32_t nf = (uint32_t)((A.n - f0 < A.chunk) ? (A.n - f0) : A.chunk);
+    const uint32_t sbc = (nf + A.stat_block - 1) / A.stat_block;
+
+    // (1) frame histogram, zmax, quantizable flag
+    uint32_t f = 0;
+    if (tid < K) {
+        const uint32_t* ph = reinterpret_cast<const uint32_t*>(A.ws + A.L.phist) + (size_t)fid * A.sbpf * kMaxK + tid;
+        for (uint32_t b = 0; b < sbc; b++) f += ph[(size_t)b * kMaxK];
+    }
+    s_f[tid] = f;
+    if (tid < sbc) {
+        const uint2 pm = reinterpret_cast<const uint2*>(A.ws + A.L.pmeta)[(size_t)fid * A.sbpf + tid];
+        atomicMax(&s_zmax, pm.x);
+        atomicMax(&s_unq, pm.y);
+        // reduce: a sum beyond 2^30 somewhere in the frame has turned it RAW (its fp32 sums were staged by k_fix)
+        if (!A.in) atomicMax(&s_unq, reinterpret_cast<const uint32_t*>(A.ws + A.L.cwide)[(size_t)fid * A.sbpf + tid] & 2u);
+    }
+    // (2)-(5) code lengths and canonical codes
+    uint32_t L, code;
+    book_build(s_b, f, K, L, code);
+    const uint32_t nsym = s_b.nsym;
     // (6) exact Huffman bitstream length: sum f*len, an escape carries 32 more bits
     {
         uint64_t b = (uint64_t)f * L + (tid == 0 ? 32ull * f : 0ull);
@@ -688,6 +711,518 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
         const uint32_t w0 = (kHdrBytes + M.payload) / 4, w1 = M.total / 4;
         if (tid < w1 - w0) reinterpret_cast<uint32_t*>(fr)[w0 + tid] = 0;
     }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Sampled runtime entropy arbitration (Sec. IV-C, Eq. 1-2, Algorithm 1): a cached Huffman context, a plan per
+// frame from a bounded prefix sample, one pass of the selected codec over the frame, validation of the realized
+// size and RAW as the fallback.  Frames sit in RAW-sized slots (the paper's frames are materialised in a staging
+// bank and publish a byte-accurate length), so no frame has to wait for the size of another.
+// ------------------------------------------------------------------------------------------------
+
+// Context, step 1: symbol counts of the calibration message (values that cannot be quantized do not count).
+__global__ __launch_bounds__(256) void k_ctx_hist(const float* x, uint64_t n, float eb, float step, float inv, uint32_t K,
+                                                  uint32_t* ghist) {
+    __shared__ uint32_t s_h[kMaxK];
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t i = tid; i < K; i += 256) s_h[i] = 0;
+    __syncthreads();
+    const uint64_t i0 = (uint64_t)blockIdx.x * 4096u;
+    for (uint32_t k = tid; k < 4096u && i0 + k < n; k += 256) {
+        int32_t q;
+        if (quantize1(x[i0 + k], eb, step, inv, q)) {
+            const uint32_t z = zigzag(q);
+            atomicAdd(&s_h[z <= K - 2u ? z + 1u : 0u], 1u);
+        }
+    }
+    __syncthreads();
+    for (uint32_t i = tid; i < K; i += 256) if (s_h[i]) atomicAdd(&ghist[i], s_h[i]);
+}
+
+// Context, step 2: one more than every count (each symbol, the escape included, gets a code), optimal lengths by the
+// same two-queue rule as the per-frame codebooks, canonical codes, and the encoder's table.
+__global__ __launch_bounds__(kBookThreads) void k_context(const uint32_t* ghist, uint32_t K, DevContext* ctx) {
+    __shared__ BookShared s_b;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t f = tid < K ? ghist[tid] + 1u : 0u;
+    uint32_t L, code;
+    book_build(s_b, f, K, L, code);
+    if (tid < K) {
+        ctx->len[tid] = (uint8_t)L;
+        ctx->book[tid == 0 ? K - 1u : tid - 1u] = (uint64_t)(__brev(code) >> (32u - L)) | ((uint64_t)L << 32);
+    } else if (tid < kMaxK) { ctx->len[tid] = 0; ctx->book[tid] = 0; }
+    if (tid == 0) { ctx->valid = 1u; ctx->K = K; ctx->pad_[0] = 0; ctx->pad_[1] = 0; }
+}
+
+hipError_t launch_context(const float* sample, uint64_t n, float eb, float step, float inv_step, uint32_t K, uint32_t* ghist,
+                          DevContext* ctx, hipStream_t st) {
+    hipLaunchKernelGGL(k_init, dim3(kMaxK / 256), dim3(256), 0, st, ghist, (size_t)kMaxK, (ResultRec*)nullptr, 0u, 0u);
+    hipLaunchKernelGGL(k_ctx_hist, dim3((uint32_t)((n + 4095u) / 4096u)), dim3(256), 0, st, sample, n, eb, step, inv_step, K, ghist);
+    hipLaunchKernelGGL(k_context, dim3(1), dim3(kBookThreads), 0, st, ghist, K, ctx);
+    return hipGetLastError();
+}
+
+// ProfileSample + ArbitratePlan, one workgroup per frame: the sample is the frame's prefix; FIXEDLEN's width is the
+// bit length of the sample's largest zigzag code, HUFFMAN's size the sample's bits under the context scaled to the
+// frame (rounded up); admissibility (fits the payload capacity = RAW size, minimum gain, context valid, T_huff) and
+// Eq. 2 with transmitted size as the cost, ties to the lower codec id.  Also clears what the encoder's look-back
+// needs and writes the offsets table (slots are fixed) and the stream header.
+__global__ __launch_bounds__(256) void k_rea_plan(ReaArgs A) {
+    __shared__ uint8_t s_l[kMaxK];
+    __shared__ uint64_t s_bits[4];
+    __shared__ uint32_t s_zmax, s_bad;
+    const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    const uint32_t frame = blockIdx.x, K = A.K;
+    const uint64_t f0 = (uint64_t)frame * A.chunk;
+    const uint32_t nf = (uint32_t)((A.n - f0 < A.chunk) ? (A.n - f0) : A.chunk);
+    const uint64_t base = kStreamHdr + pad16u(8ull * A.n_frames);
+    const bool ctx_ok = A.ctx && A.ctx->valid == 1u && A.ctx->K == K;
+    // housekeeping for the next kernels
+    uint64_t* desc = reinterpret_cast<uint64_t*>(A.ws + A.L.desc) + (size_t)frame * A.spf;
+    for (uint32_t i = tid; i < A.spf; i += 256) desc[i] = 0;
+    if (tid == 0) {
+        reinterpret_cast<uint32_t*>(A.ws + A.L.fail)[frame] = 0;
+        *reinterpret_cast<uint64_t*>(A.out + kStreamHdr + 8ull * frame) = base + (uint64_t)frame * A.slot;
+        if (frame == A.n_frames - 1 && (A.n_frames & 1u)) *reinterpret_cast<uint64_t*>(A.out + kStreamHdr + 8ull * A.n_frames) = 0;
+        s_zmax = 0; s_bad = 0;
+    }
+    if (frame == 0 && tid == 0) {
+        reinterpret_cast<Ctrl*>(A.ws + A.L.ctrl)->ticket_book = 0;
+        ReaResultRec* res = reinterpret_cast<ReaResultRec*>(A.res);
+        res->span_bytes = 0; res->wire_bytes = 0; res->status = ST_OK; res->n_frames = A.n_frames;
+        res->n_raw = 0; res->n_fixed = 0; res->n_huff = 0; res->n_fallback = 0;
+        uint32_t* sh = reinterpret_cast<uint32_t*>(A.out);
+        sh[0] = kMagicStream; sh[1] = 1u; sh[2] = (uint32_t)A.n; sh[3] = (uint32_t)(A.n >> 32);
+        sh[4] = A.chunk; sh[5] = A.n_frames; sh[6] = A.step_bits; sh[7] = kSeg; sh[8] = K; sh[9] = 0;
+        sh[10] = 0; sh[11] = 0; sh[12] = 0; sh[13] = 0; sh[14] = 0; sh[15] = 0;     // total_bytes: the finishing kernel
+    }
+    if (ctx_ok) for (uint32_t b = tid; b < K; b += 256) s_l[b] = (uint8_t)((uint32_t)(A.ctx->book[b] >> 32) + (b == K - 1u ? 32u : 0u));
+    __syncthreads();
+    const uint64_t rawb = 4ull * nf;
+    const bool profiled = rawb >= A.small_batch_bytes;                   // SmallBatchFastPath
+    const uint32_t n_s = profiled ? (A.sample_elems < nf ? A.sample_elems : nf) : 0u;
+    uint32_t zmax = 0, bad = 0;
+    uint64_t bits = 0;
+    for (uint32_t i = tid; i < n_s; i += 256) {
+        int32_t q;
+        if (!quantize1(A.in[f0 + i], A.eb, A.step, A.inv_step, q)) bad = 1;
+        const uint32_t z = zigzag(q);
+        zmax = z > zmax ? z : zmax;
+        if (ctx_ok) bits += s_l[bin_of(z, K)];
+    }
+    zmax = wave_max(zmax); bad = wave_max(bad); bits = wave_sum64(bits);
+    if (lane == 0) { atomicMax(&s_zmax, zmax); atomicMax(&s_bad, bad); s_bits[wave] = bits; }
+    __syncthreads();
+    if (tid != 0) return;
+    uint32_t plan = CODEC_RAW;
+    const uint32_t w = s_zmax ? (32u - (uint32_t)__clz(s_zmax)) : 0u;
+    const uint32_t nseg = (nf + kSeg - 1) / kSeg;
+    if (n_s && !s_bad) {
+        const uint64_t sample_bits = s_bits[0] + s_bits[1] + s_bits[2] + s_bits[3];
+        const uint64_t pred_bits = (sample_bits * nf + n_s - 1) / n_s;
+        uint64_t pay[3];
+        pay[CODEC_RAW] = rawb;
+        pay[CODEC_FIXED] = 4ull * (((uint64_t)nf * w + 31u) / 32u);
+        pay[CODEC_HUFF] = pad4u(K) + pad4u(2ull * nseg) + 4ull * ((pred_bits + 31u) / 32u);
+        if (A.force_codec >= 0) plan = (A.force_codec == (int32_t)CODEC_HUFF && !ctx_ok) ? (uint32_t)CODEC_RAW : (uint32_t)A.force_codec;
+        else {
+            uint64_t best_total = pad16u(kHdrBytes + rawb);
+            for (uint32_t c = CODEC_FIXED; c <= CODEC_HUFF; c++) {
+                if (c == CODEC_HUFF && (!ctx_ok || rawb < A.huff_min_bytes)) continue;
+                if (pay[c] > rawb) continue;
+                if ((rawb - pay[c]) * 1000ull < (uint64_t)A.min_gain_permil * rawb) continue;
+                const uint64_t t = pad16u(kHdrBytes + pay[c]);
+                if (t < best_total) { best_total = t; plan = c; }
+            }
+        }
+    }
+    FrameMeta M;
+    M.offset = base + (uint64_t)frame * A.slot; M.total = 0; M.payload = 0; M.codec = plan; M.w = w; M.nsym = K; M.fits = 1u;
+    M.segt_off = kHdrBytes + (uint32_t)pad4u(K);
+    M.bits_off = (plan == CODEC_HUFF) ? (M.segt_off + (uint32_t)pad4u(2ull * nseg)) : kHdrBytes;
+    M.bits_words = 0; M.pad_ = 0; M.huff_bits = 0; M.pad2_ = 0;
+    reinterpret_cast<FrameMeta*>(A.ws + A.L.meta)[frame] = M;
+}
+
+// Lookup phase of one piece of kReaSub symbols (all kEncThreads threads): load, quantize with the acceptance tests
+// (nothing has looked at these values before), look every symbol up in the context's table, pack the 4 symbols of a
+// thread into 64 bits, scan the bit counts over the wave.  Pass `it` covers symbols it*1024 + tid*4 .. +3 of the piece.
+// wseg[it*4 + wave] receives the bit count of the segment the wave's pass covers.
+__device__ __forceinline__ void rea_phase1(const ReaArgs& A, const uint64_t* book, const uint32_t* src, uint32_t j, uint32_t nf,
+                                           bool vec_ok, uint32_t K, uint64_t (&pk)[kEncIters], uint32_t (&ln)[kEncIters],
+                                           uint32_t& wide, uint32_t& bad, uint32_t* wseg) {
+    const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6, kesc = K - 1u;
+    const uint32_t cnt = (nf - j * kReaSub < kReaSub) ? (nf - j * kReaSub) : kReaSub;
+    const uint32_t* p = src + j * kReaSub;
+    uint32_t raw[kEncIters][4];
+    if (vec_ok && cnt == kReaSub) {
+#pragma unroll
+        for (uint32_t it = 0; it < kEncIters; it++) {
+            const uint4 t = *reinterpret_cast<const uint4*>(p + it * 1024 + tid * 4);
+            raw[it][0] = t.x; raw[it][1] = t.y; raw[it][2] = t.z; raw[it][3] = t.w;
+        }
+    } else {
+#pragma unroll
+        for (uint32_t it = 0; it < kEncIters; it++)
+#pragma unroll
+            for (uint32_t jj = 0; jj < 4; jj++) {
+                const uint32_t i = it * 1024 + tid * 4 + jj;
+                raw[it][jj] = (i < cnt) ? p[i] : 0u;
+            }
+    }
+    wide = 0;
+#pragma unroll
+    for (uint32_t it = 0; it < kEncIters; it++) {
+        const uint32_t i = it * 1024 + tid * 4;
+        uint64_t acc = 0;
+        uint32_t tl = 0;
+#pragma unroll
+        for (uint32_t jj = 0; jj < 4; jj++) {
+            const bool valid = i + jj < cnt;
+            int32_t q;
+            if (!quantize1(__uint_as_float(raw[it][jj]), A.eb, A.step, A.inv_step, q) && valid) bad = 1;
+            const uint32_t z = zigzag(q);
+            const uint64_t b = book[z < kesc ? z : kesc];
+            const uint32_t len = valid ? (uint32_t)(b >> 32) : 0u, code = valid ? (uint32_t)b : 0u;
+            acc |= (uint64_t)code << (tl & 63u);              // garbage once tl > 64: the pass is then redone
+            tl += len;
+            if (z >= kesc && valid) { acc |= (uint64_t)z << (tl & 63u); tl += 32u; }
+        }
+        pk[it] = acc;
+        wide |= (tl > 64u ? 1u : 0u) << it;
+        const uint32_t incl = wave_incl_scan_dpp(tl);
+        ln[it] = incl - tl;
+        if (lane == 63) wseg[it * 4 + wave] = incl;
+    }
+}
+
+// EncodePlan: the planned codec over the whole frame, in one pass over the input.
+//   RAW       copy.
+//   FIXEDLEN  the sampled width at closed-form positions; a value that needs more bits, or cannot be quantized,
+//             raises the frame's failure flag.
+//   HUFFMAN   the context's code.  The frame's workgroups take its pieces of kReaSub symbols round robin; a piece's
+//             bit count is known after its lookup phase and its first bit follows from a decoupled look-back over
+//             the pieces before it (tickets make every wait end: a piece only waits for pieces that belong to
+//             workgroups that have started).  Whole words go straight to the frame; the first and last partial
+//             word of a piece are left in the workspace and merged with the neighbours' by the finishing kernel.
+__global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))) void k_rea_encode(ReaArgs A) {
+    __shared__ EncShared S;
+    __shared__ uint32_t s_ticket;
+    __shared__ uint64_t s_excl;
+    const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
+    if (tid == 0) s_ticket = atomicAdd(&reinterpret_cast<Ctrl*>(A.ws + A.L.ctrl)->ticket_book, 1u);
+    __syncthreads();
+    const uint32_t frame = s_ticket / A.gpf, wg = s_ticket % A.gpf;
+    const uint64_t f0 = (uint64_t)frame * A.chunk;
+    const uint32_t nf = (uint32_t)((A.n - f0 < A.chunk) ? (A.n - f0) : A.chunk);
+    const FrameMeta M = reinterpret_cast<const FrameMeta*>(A.ws + A.L.meta)[frame];
+    uint8_t* fr = A.out + M.offset;
+    uint32_t* fail = reinterpret_cast<uint32_t*>(A.ws + A.L.fail) + frame;
+    const uint32_t* src = reinterpret_cast<const uint32_t*>(A.in) + f0;
+    const bool vec_ok = ((f0 & 3u) == 0);
+    const uint32_t K = A.K, kesc = K - 1u;
+    uint32_t bad = 0;
+
+    if (M.codec != CODEC_HUFF) {
+        const uint32_t g0 = wg * kEncGroup;                               // a contiguous share of the frame
+        if (g0 >= nf) return;
+        const uint32_t gcnt = (nf - g0 < kEncGroup) ? (nf - g0) : kEncGroup;
+        if (M.codec == CODEC_RAW) {
+            uint32_t* dst = reinterpret_cast<uint32_t*>(fr + kHdrBytes) + g0;
+            for (uint32_t i = tid * 4; i < gcnt; i += kEncThreads * 4) {
+                if (vec_ok && i + 4 <= gcnt) *reinterpret_cast<uint4*>(dst + i) = *reinterpret_cast<const uint4*>(src + g0 + i);
+                else for (uint32_t j = 0; j < 4; j++) if (i + j < gcnt) dst[i + j] = src[g0 + i + j];
+            }
+            return;
+        }
+        const uint32_t w = M.w;
+        uint32_t* stage = S.stage[0];
+        uint32_t* bitsw = reinterpret_cast<uint32_t*>(fr + kHdrBytes) + (g0 / 32u) * w;
+        for (uint32_t p0 = 0; p0 < gcnt; p0 += 1024) {
+            const uint32_t pass_syms = (gcnt - p0 < 1024u) ? (gcnt - p0) : 1024u;
+            const uint32_t pass_words = (pass_syms * w + 31u) / 32u;
+            uint32_t z[4];
+#pragma unroll
+            for (uint32_t j = 0; j < 4; j++) {
+                z[j] = 0;
+                if (tid * 4 + j < pass_syms) {
+                    int32_t q;
+                    if (!quantize1(__uint_as_float(src[g0 + p0 + tid * 4 + j]), A.eb, A.step, A.inv_step, q)) bad = 1;
+                    z[j] = zigzag(q);
+                    if (w < 32u && (z[j] >> w)) { bad = 1; z[j] &= (1u << w) - 1u; }     // does not fit the sampled width
+                }
+            }
+            for (uint32_t k = tid; k < pass_words; k += kEncThreads) stage[k] = 0;
+            __syncthreads();
+            uint32_t pos = tid * 4 * w;
+#pragma unroll
+            for (uint32_t j = 0; j < 4; j++) {
+                if (tid * 4 + j < pass_syms && w) {
+                    const uint32_t sh = pos & 31u, wi = pos >> 5;
+                    atomicOr(&stage[wi], z[j] << sh);
+                    if (sh + w > 32u) atomicOr(&stage[wi + 1], z[j] >> (32u - sh));
+                    pos += w;
+                }
+            }
+            __syncthreads();
+            uint32_t* dst = bitsw + (p0 / 32u) * w;
+            for (uint32_t k = tid; k < pass_words; k += kEncThreads) dst[k] = stage[k];
+            __syncthreads();
+        }
+        if (bad) atomicOr(fail, 1u);
+        return;
+    }
+
+    // ---- HUFFMAN with the context's code ----
+    // The pieces of a workgroup are pipelined one deep: the lookup phase of the next piece runs (and its bit count is
+    // published) before the look-back of the current one is resolved, so the latency of the descriptors -- the
+    // frame's workgroups sit on different compute units -- passes behind useful work.
+    const uint32_t nsub = (nf + kReaSub - 1) / kReaSub;
+    if (wg >= nsub) return;
+    for (uint32_t b = tid; b < K; b += kEncThreads) S.book[b] = A.ctx->book[b];
+    for (uint32_t i = tid; i < 2 * (kStageWords + 4); i += kEncThreads) (&S.stage[0][0])[i] = 0;
+    uint64_t* desc = reinterpret_cast<uint64_t*>(A.ws + A.L.desc) + (size_t)frame * A.spf;
+    uint2* frag = reinterpret_cast<uint2*>(A.ws + A.L.frag) + (size_t)frame * A.spf;
+    uint16_t* segt = reinterpret_cast<uint16_t*>(fr + M.segt_off);
+    uint32_t* bits0 = reinterpret_cast<uint32_t*>(fr + M.bits_off);
+    const uint32_t nseg = (nf + kSeg - 1) / kSeg;
+    uint32_t* X = S.stage[0];
+    uint32_t* wt = S.stage[1];                 // the second stage is free here: per-segment bit counts of two pieces in flight
+    // EncodePlan works inside the payload capacity (Algorithm 1): nothing is written past the RAW size of the frame,
+    // which is what its slot holds.  Whatever is dropped belongs to a frame whose realized payload exceeds that size,
+    // which the finishing kernel rejects from the piece bit counts alone.
+    const uint32_t cap_end = kHdrBytes + 4u * nf;                         // first byte of the frame that is off limits
+    const uint32_t cap_segs = M.segt_off < cap_end ? (cap_end - M.segt_off) / 2u : 0u;      // segment-table entries that fit
+    const uint32_t cap_words = M.bits_off < cap_end ? (cap_end - M.bits_off) / 4u : 0u;     // bitstream words that fit
+    __syncthreads();
+
+    uint64_t pk0[kEncIters], pk1[kEncIters];   // the thread's 4 symbols of a pass packed LSB-first: current and next piece
+    uint32_t ln0[kEncIters], ln1[kEncIters];   // exclusive bit offset of the thread inside its wave's segment
+    uint32_t wide0 = 0, wide1 = 0;             // pass mask: the 4 symbols need more than 64 bits
+    uint32_t buf = 0;                          // which half of wt belongs to the current piece
+    rea_phase1(A, S.book, src, wg, nf, vec_ok, K, pk0, ln0, wide0, bad, wt);
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t T = 0;
+        for (uint32_t i = 0; i < kEncSegs; i++) T += wt[i];
+        st_agent(desc + wg, kDescA | (uint64_t)T);
+    }
+    for (uint32_t j = wg; j < nsub; j += A.gpf) {
+        const uint32_t cnt = (nf - j * kReaSub < kReaSub) ? (nf - j * kReaSub) : kReaSub;
+        const uint32_t jn = j + A.gpf;
+        uint32_t* wcur = wt + buf * kEncSegs;
+        uint32_t* wnxt = wt + (buf ^ 1u) * kEncSegs;
+        if (jn < nsub) rea_phase1(A, S.book, src, jn, nf, vec_ok, K, pk1, ln1, wide1, bad, wnxt);
+        __syncthreads();
+        if (wave == 0) {
+            uint32_t Tn = 0, T = 0;
+            for (uint32_t i = 0; i < kEncSegs; i++) { Tn += wnxt[i]; T += wcur[i]; }
+            if (jn < nsub && lane == 0) st_agent(desc + jn, kDescA | (uint64_t)Tn);
+            const uint64_t excl = lookback_exclusive(desc, 0, (int64_t)j, 0);
+            if (lane == 0) { st_agent(desc + j, kDescP | (excl + T)); s_excl = excl; }
+        }
+        if (tid < kEncSegs) {
+            const uint32_t gseg = j * kEncSegs + tid;
+            if (gseg < nseg && gseg < cap_segs) segt[gseg] = (uint16_t)wcur[tid];
+            if (gseg == nseg - 1 && (nseg & 1u) && nseg < cap_segs) segt[nseg] = 0;
+        }
+        __syncthreads();
+        uint32_t pbase[kEncIters + 1];
+        pbase[0] = 0;
+#pragma unroll
+        for (uint32_t it = 0; it < kEncIters; it++) {
+            const uint4 t = reinterpret_cast<const uint4*>(wcur)[it];
+            ln0[it] += (wave > 0 ? t.x : 0u) + (wave > 1 ? t.y : 0u) + (wave > 2 ? t.z : 0u);
+            pbase[it + 1] = pbase[it] + t.x + t.y + t.z + t.w;
+        }
+        const uint32_t T = pbase[kEncIters];
+        const uint64_t excl = s_excl;
+        const uint32_t rel = (uint32_t)(excl & 31u);
+        const uint64_t w0 = excl >> 5;                                   // first bitstream word this piece touches
+        // Place the passes behind the bits already in the stage, write the whole words, keep the partial one.  All
+        // four passes at once when they fit the stage, else pass by pass (a pass is at most 1024 * 60 bits).
+        const bool fits = rel + T <= 32u * kStageWords;
+        const uint32_t nchunk = fits ? 1u : kEncIters;
+        uint32_t runpos = rel, flushed = 0, lo = 0, hi = 0;
+#pragma unroll 1
+        for (uint32_t c = 0; c < nchunk; c++) {
+            uint32_t cb = 0, ce = T;                                     // bit range of this chunk inside the piece
+            if (!fits) {
+#pragma unroll
+                for (uint32_t it = 0; it < kEncIters; it++) if (it == c) { cb = pbase[it]; ce = pbase[it + 1]; }
+            }
+#pragma unroll
+            for (uint32_t it = 0; it < kEncIters; it++) {
+                if (!fits && it != c) continue;
+                uint32_t pos = runpos + (pbase[it] - cb) + ln0[it];
+                if (__builtin_expect(!((wide0 >> it) & 1u), 1)) {
+                    const uint64_t a = pk0[it];
+                    if (a) {
+                        const uint32_t sh = pos & 31u, wi = pos >> 5;
+                        const uint64_t t = a << sh;
+                        atomicOr(&X[wi], (uint32_t)t);
+                        if ((uint32_t)(t >> 32)) atomicOr(&X[wi + 1], (uint32_t)(t >> 32));
+                        if (sh) { const uint32_t h2 = (uint32_t)(a >> (64u - sh)); if (h2) atomicOr(&X[wi + 2], h2); }
+                    }
+                } else {
+                    // the thread's 4 symbols need more than 64 bits (rare): symbol by symbol, from the source words
+                    const uint32_t i = it * 1024 + tid * 4;
+                    for (uint32_t jj = 0; jj < 4; jj++) {
+                        if (i + jj < cnt) {
+                            int32_t q;
+                            quantize1(__uint_as_float(src[j * kReaSub + i + jj]), A.eb, A.step, A.inv_step, q);
+                            const uint32_t z = zigzag(q);
+                            const uint64_t b = S.book[z < kesc ? z : kesc];
+                            const uint32_t val = (uint32_t)b, len = (uint32_t)(b >> 32);
+                            {
+                                const uint32_t sh = pos & 31u, wi = pos >> 5;
+                                atomicOr(&X[wi], val << sh);
+                                if (sh + len > 32u) atomicOr(&X[wi + 1], val >> (32u - sh));
+                                pos += len;
+                            }
+                            if (z >= kesc) {
+                                const uint32_t sh = pos & 31u, wi = pos >> 5;
+                                atomicOr(&X[wi], z << sh);
+                                if (sh) atomicOr(&X[wi + 1], z >> (32u - sh));
+                                pos += 32u;
+                            }
+                        }
+                    }
+                }
+            }
+            __syncthreads();
+            const uint32_t nbits = runpos + (ce - cb);
+            const uint32_t nw = nbits >> 5;
+            for (uint32_t k = tid; k < nw; k += kEncThreads) {
+                const uint32_t wv = X[k];
+                X[k] = 0;
+                if (k == 0 && flushed == 0 && rel) lo = wv;             // shared with the piece before: merged later
+                else if (w0 + flushed + k < cap_words) bits0[w0 + flushed + k] = wv;
+            }
+            if (tid == 0) { const uint32_t cw = X[nw]; X[nw] = 0; X[0] = cw; }
+            flushed += nw;
+            runpos = nbits & 31u;
+            __syncthreads();
+        }
+        if (tid == 0) {
+            if (runpos) { const uint32_t v = X[0]; if (flushed == 0 && rel) lo = v; else hi = v; }
+            X[0] = 0;
+            frag[j] = make_uint2(lo, hi);
+        }
+#pragma unroll
+        for (uint32_t it = 0; it < kEncIters; it++) { pk0[it] = pk1[it]; ln0[it] = ln1[it]; }
+        wide0 = wide1;
+        buf ^= 1u;
+        __syncthreads();
+    }
+    if (bad) atomicOr(fail, 1u);
+}
+
+// AcceptRealized + CommitRawOrFail, and everything that needs the realized size: header, code-length table, the
+// words in which two pieces meet, padding, the result record.  A rejected frame is copied again as RAW by all of
+// its workgroups (rare).
+__global__ __launch_bounds__(256) void k_rea_finish(ReaArgs A) {
+    const uint32_t tid = threadIdx.x;
+    const uint32_t frame = blockIdx.x / A.gpf, wg = blockIdx.x % A.gpf;
+    const uint64_t f0 = (uint64_t)frame * A.chunk;
+    const uint32_t nf = (uint32_t)((A.n - f0 < A.chunk) ? (A.n - f0) : A.chunk);
+    const FrameMeta M = reinterpret_cast<const FrameMeta*>(A.ws + A.L.meta)[frame];
+    uint8_t* fr = A.out + M.offset;
+    const uint32_t K = A.K, plan = M.codec;
+    const uint32_t nsub = (nf + kReaSub - 1) / kReaSub, nseg = (nf + kSeg - 1) / kSeg;
+    const uint64_t* desc = reinterpret_cast<const uint64_t*>(A.ws + A.L.desc) + (size_t)frame * A.spf;
+    const uint64_t rawb = 4ull * nf;
+    uint64_t payload = rawb, bits = 0;
+    if (plan == CODEC_FIXED) payload = 4ull * (((uint64_t)nf * M.w + 31u) / 32u);
+    else if (plan == CODEC_HUFF) {
+        bits = desc[nsub - 1] & kDescMask;                               // inclusive prefix of the last piece
+        payload = pad4u(K) + pad4u(2ull * nseg) + 4ull * ((bits + 31u) / 32u);
+    }
+    uint32_t codec = plan;
+    if (plan != CODEC_RAW) {
+        const uint32_t failed = reinterpret_cast<const uint32_t*>(A.ws + A.L.fail)[frame];
+        if (failed || payload > rawb || (rawb - payload) * 1000ull < (uint64_t)A.min_gain_permil * rawb) codec = CODEC_RAW;
+    }
+    const bool fell_back = (codec == CODEC_RAW && plan != CODEC_RAW);
+    if (codec == CODEC_RAW) payload = rawb;
+    const uint32_t total = (uint32_t)pad16u(kHdrBytes + payload);
+    if (fell_back) {
+        const uint32_t g0 = wg * kEncGroup;
+        if (g0 < nf) {
+            const uint32_t gcnt = (nf - g0 < kEncGroup) ? (nf - g0) : kEncGroup;
+            const uint32_t* src = reinterpret_cast<const uint32_t*>(A.in) + f0 + g0;
+            uint32_t* dst = reinterpret_cast<uint32_t*>(fr + kHdrBytes) + g0;
+            for (uint32_t i = tid; i < gcnt; i += 256) dst[i] = src[i];
+        }
+    }
+    if (wg != 0) return;
+    if (codec == CODEC_HUFF) {
+        uint32_t* bits0 = reinterpret_cast<uint32_t*>(fr + M.bits_off);
+        const uint2* frag = reinterpret_cast<const uint2*>(A.ws + A.L.frag) + (size_t)frame * A.spf;
+        for (uint32_t j = tid + 1; j < nsub; j += 256) {                 // the word in which pieces j-1 and j meet
+            const uint64_t Sj = desc[j - 1] & kDescMask;
+            if (Sj & 31u) bits0[Sj >> 5] = frag[j - 1].y | frag[j].x;
+        }
+        if (tid == 0 && (bits & 31u)) {                                  // the frame's last, partial word
+            const uint64_t Sl = nsub > 1 ? (desc[nsub - 2] & kDescMask) : 0ull;
+            if ((bits >> 5) != (Sl >> 5) || !(Sl & 31u)) bits0[bits >> 5] = frag[nsub - 1].y;
+        }
+        const uint32_t words = (uint32_t)(pad4u(K) / 4);                 // code lengths, one byte per symbol, zero padded
+        for (uint32_t i = tid; i < words; i += 256) {
+            uint32_t v = 0;
+            for (uint32_t b = 0; b < 4; b++) if (4 * i + b < K) v |= (uint32_t)A.ctx->len[4 * i + b] << (8 * b);
+            reinterpret_cast<uint32_t*>(fr + kHdrBytes)[i] = v;
+        }
+    }
+    {
+        const uint32_t w0 = (uint32_t)((kHdrBytes + payload) / 4), w1 = total / 4;
+        if (tid < w1 - w0) reinterpret_cast<uint32_t*>(fr)[w0 + tid] = 0;
+    }
+    if (tid == 0) {
+        uint32_t h[8];
+        h[0] = kMagicFrame; h[1] = codec; h[2] = 4u * nf; h[3] = (uint32_t)payload;
+        h[4] = (codec == CODEC_FIXED) ? M.w : (codec == CODEC_HUFF ? K : 0u);
+        h[5] = (codec == CODEC_HUFF) ? (kSeg | (K << 16)) : 0u;
+        h[6] = A.step_bits;
+        uint32_t x = kCheckXor;
+        for (int i = 0; i < 7; i++) x ^= h[i];
+        h[7] = x;
+        uint4* dst = reinterpret_cast<uint4*>(fr);
+        dst[0] = make_uint4(h[0], h[1], h[2], h[3]);
+        dst[1] = make_uint4(h[4], h[5], h[6], h[7]);
+        ReaResultRec* res = reinterpret_cast<ReaResultRec*>(A.res);
+        atomicAdd(codec == CODEC_RAW ? &res->n_raw : (codec == CODEC_FIXED ? &res->n_fixed : &res->n_huff), 1u);
+        if (fell_back) atomicAdd(&res->n_fallback, 1u);
+        uint64_t wire = total;
+        if (frame == A.n_frames - 1) {
+            const uint64_t end = M.offset + total;
+            wire += kStreamHdr + pad16u(8ull * A.n_frames);
+            res->span_bytes = end;
+            uint32_t* sh = reinterpret_cast<uint32_t*>(A.out);
+            sh[10] = (uint32_t)end; sh[11] = (uint32_t)(end >> 32);
+        }
+        atomicAdd(reinterpret_cast<unsigned long long*>(&res->wire_bytes), (unsigned long long)wire);
+    }
+}
+
+__global__ void k_rea_status(ReaResultRec* res, uint32_t n_frames, uint32_t status) {
+    res->span_bytes = 0; res->wire_bytes = 0; res->status = status; res->n_frames = n_frames;
+    res->n_raw = 0; res->n_fixed = 0; res->n_huff = 0; res->n_fallback = 0;
+}
+
+hipError_t launch_rea_status(void* res, uint32_t n_frames, uint32_t status, hipStream_t st) {
+    hipLaunchKernelGGL(k_rea_status, dim3(1), dim3(1), 0, st, reinterpret_cast<ReaResultRec*>(res), n_frames, status);
+    return hipGetLastError();
+}
+
+hipError_t launch_rea(const ReaArgs& A, hipStream_t st, void (*mark)(hipStream_t)) {
+    hipLaunchKernelGGL(k_rea_plan, dim3(A.n_frames), dim3(256), 0, st, A);
+    mark(st);
+    hipLaunchKernelGGL(k_rea_encode, dim3(A.n_frames * A.gpf), dim3(kEncThreads), 0, st, A);
+    mark(st);
+    hipLaunchKernelGGL(k_rea_finish, dim3(A.n_frames * A.gpf), dim3(256), 0, st, A);
+    mark(st);
+    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------------------------------------
