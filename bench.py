@@ -329,7 +329,7 @@ def main():
     ap.add_argument("--alphabet", type=int, default=256, help="Huffman alphabet K (power of two, 2..1024)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rotate", type=int, default=3, help="number of distinct input / stream copies cycled through")
-    ap.add_argument("--only", default="", help="profiling aid: time only this stage (compress|decompress|reduce)")
+    ap.add_argument("--only", default="", help="profiling aid: time only this stage (compress|decompress|reduce|compress_rea)")
     ap.add_argument("--calib-copy", type=int, default=0,
                     help="profiling aid: also run this many plain 4n-byte copy kernels (counter calibration)")
     ap.add_argument("--traffic-file", default=os.path.join(ROOT, "profiles", "hbm_traffic_c2.txt"),
@@ -380,9 +380,23 @@ def main():
         assert rc == 0 and r0["status"] == 0
         stream_bytes = r0["bytes"]
 
+    # the sampled-arbitration compress (Algorithm 1 taken literally; not part of `value`): context from the first
+    # 64 KiB-sample's worth of the message, one pass over the input, frames in RAW-sized slots
+    ctx = torch.zeros(nz.nz_context_bytes(), dtype=torch.uint8, device=dev)
+    assert nz.nz_context_build(xs[0], min(n, 65536), eb, opts, ctx, sess.ws, sess.ws_bytes) == 0
+    rea_out = torch.empty(sess.cap, dtype=torch.uint8, device=dev)
+    rea_res = torch.zeros(48, dtype=torch.uint8, device=dev)
+    rea_wsb = nz.nz_rea_workspace_bytes(n, opts)
+    rea_ws = torch.empty(rea_wsb, dtype=torch.uint8, device=dev)
+
+    def compress_rea_call(k):
+        return nz.nz_compress_rea(xs[k], n, eb, ctx, rea_out, sess.cap, rea_res, opts, None, rea_ws, rea_wsb)
+
     def step(i):
         k, k2 = i % R, (i + 1) % R
         a = b = c = 0
+        if args.only == "compress_rea":
+            return compress_rea_call(k)
         if args.only in ("", "decompress"):
             b = sess.decompress(outs[k2], stream_bytes, n, eb, out=y)[0]
         if args.only in ("", "reduce"):
@@ -417,17 +431,9 @@ def main():
              "compress_rea": ["plan", "encode", "finish"]}
     acc = {k: [0.0] * len(v) for k, v in names.items()}
     reps = max(5, min(args.steps, 20))
-    # the sampled-arbitration compress (Algorithm 1 taken literally; not part of `value`): context from the first
-    # 64 KiB-sample's worth of the message, one pass over the input, frames in RAW-sized slots
-    ctx = torch.zeros(nz.nz_context_bytes(), dtype=torch.uint8, device=dev)
-    assert nz.nz_context_build(xs[0], min(n, 65536), eb, opts, ctx, sess.ws, sess.ws_bytes) == 0
-    rea_out = torch.empty(sess.cap, dtype=torch.uint8, device=dev)
-    rea_res = torch.zeros(48, dtype=torch.uint8, device=dev)
-    rea_wsb = nz.nz_rea_workspace_bytes(n, opts)
-    rea_ws = torch.empty(rea_wsb, dtype=torch.uint8, device=dev)
 
     def compress_rea(k):
-        return nz.nz_compress_rea(xs[k], n, eb, ctx, rea_out, sess.cap, rea_res, opts, None, rea_ws, rea_wsb)
+        return compress_rea_call(k)
     assert compress_rea(0) == 0
     rea = nz.read_rea_result(rea_res)
     assert rea["status"] == 0

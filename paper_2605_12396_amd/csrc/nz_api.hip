@@ -205,7 +205,7 @@ nz_status nz_compress_rea(const float* d_in, size_t n, float eb, const void* d_c
     }
     ReaArgs A;
     A.in = d_in; A.n = n; A.chunk = o.chunk; A.n_frames = nfr; A.K = o.K;
-    A.spf = (o.chunk + kReaSub - 1) / kReaSub; A.gpf = (o.chunk + kEncGroup - 1) / kEncGroup;
+    A.gpf = (o.chunk + kEncGroup - 1) / kEncGroup;
     A.force_codec = o.force; A.min_gain_permil = o.gain; A.huff_min_bytes = o.huff_min;
     uint32_t sample_bytes = 65536u, small = 0u;
     if (ropts) { if (ropts->sample_bytes) sample_bytes = ropts->sample_bytes; small = ropts->small_batch_bytes; }
@@ -214,6 +214,7 @@ nz_status nz_compress_rea(const float* d_in, size_t n, float eb, const void* d_c
     A.ctx = reinterpret_cast<const DevContext*>(d_ctx);
     A.out = reinterpret_cast<uint8_t*>(d_out); A.slot = slot;
     A.ws = reinterpret_cast<uint8_t*>(d_ws); A.L = L; A.res = d_res;
+    A.tmp_base = reinterpret_cast<uint32_t*>(A.ws + L.tmp);
     trace_reset(); trace_mark(st);
     if (launch_rea(A, st, trace_mark) != hipSuccess) return NZ_ERR_HIP;
     return NZ_OK;

@@ -142,16 +142,20 @@ __device__ inline uint32_t bin_symbol(uint32_t b, uint32_t K) { return b == K - 
 
 // Quantize one value (interface quantizer, Sec. IV-B): u = fl(x*inv_step), q = rne(u), accepted when
 // |u| <= 32767 and fl(|x - fl(q*step)|) <= eb.  Every product and difference is rounded on its own.
-__device__ inline bool quantize1(float x, float eb, float step, float inv_step, int32_t& q) {
+// (r = rne(u) is an integer-valued float, so float(q) = r whenever |u| <= 32767; otherwise the value is rejected
+// whatever the second test says.)
+__device__ inline bool quantize_ok(float x, float eb, float step, float inv_step, float& r) {
 #pragma clang fp contract(off)
-    float u = x * inv_step;
-    bool ok = fabsf(u) <= 32767.0f;            // false for NaN
-    float r = __builtin_rintf(u);              // ties to even
-    int32_t qi = ok ? (int32_t)r : 0;
-    float xh = (float)qi * step;
-    float d = x - xh;
-    ok = ok && (fabsf(d) <= eb);
-    q = ok ? qi : 0;
+    const float u = x * inv_step;
+    r = __builtin_rintf(u);                    // ties to even
+    const float xh = r * step;
+    const float d = x - xh;
+    return (fabsf(u) <= 32767.0f) && (fabsf(d) <= eb);   // false for NaN
+}
+__device__ inline bool quantize1(float x, float eb, float step, float inv_step, int32_t& q) {
+    float r;
+    const bool ok = quantize_ok(x, eb, step, inv_step, r);
+    q = ok ? (int32_t)r : 0;
     return ok;
 }
 __device__ inline float dequantize1(int32_t q, float step) {
@@ -166,20 +170,19 @@ struct DevContext {
     uint8_t  len[kMaxK];        // by symbol (0 = escape): code length, 1..28
     uint64_t book[kMaxK];       // by min(z, K-1): bit-reversed code | length << 32 (entry K-1 = escape)
 };
-constexpr uint32_t kReaSub = 4096;            // symbols per independently placed piece of a HUFFMAN bitstream (= kEncBlock)
+// A group of kEncGroup symbols never needs more bitstream words than this (28-bit code + 32 escaped bits per symbol).
+constexpr uint32_t kReaTmpWords = kEncGroup * 60u / 32u;
 
-struct ReaLayout { size_t ctrl, desc, fail, zero_end, meta, frag, total; };
+struct ReaLayout { size_t fail, meta, gbits, tmp, total; };
 __host__ inline ReaLayout rea_layout(size_t n, uint32_t chunk) {
     ReaLayout L;
     const size_t n_frames = (n + chunk - 1) / chunk;
-    const size_t spf = (chunk + kReaSub - 1) / kReaSub;
+    const size_t gpf = (chunk + kEncGroup - 1) / kEncGroup;
     size_t o = 0;
-    L.ctrl = o;  o += sizeof(Ctrl);
-    L.desc = o;  o += align_up(8 * n_frames * spf, 256);
     L.fail = o;  o += align_up(4 * n_frames, 256);
-    L.zero_end = o;
     L.meta = o;  o += align_up(sizeof(FrameMeta) * n_frames, 256);
-    L.frag = o;  o += align_up(8 * n_frames * spf, 256);
+    L.gbits = o; o += align_up(4 * n_frames * gpf, 256);
+    L.tmp = o;   o += gpf > 1 ? align_up(4 * (size_t)kReaTmpWords * n_frames * gpf, 256) : 0;   // (a one-group frame is coded in place)
     L.total = o;
     return L;
 }
@@ -188,13 +191,14 @@ struct ReaResultRec { uint64_t span_bytes, wire_bytes; uint32_t status, n_frames
 
 struct ReaArgs {
     const float* in; uint64_t n;
-    uint32_t chunk, n_frames, K, spf, gpf;      // sub-blocks and encoder workgroups per frame
+    uint32_t chunk, n_frames, K, gpf;           // encoder workgroups (groups of kEncGroup symbols) per frame
     int32_t force_codec; uint32_t min_gain_permil, huff_min_bytes;
     uint32_t sample_elems, small_batch_bytes;
     float eb, step, inv_step; uint32_t step_bits;
     const DevContext* ctx;
     uint8_t* out; uint64_t slot;               // bytes between frame starts
     uint8_t* ws; ReaLayout L;
+    uint32_t* tmp_base;                        // scratch regions of kReaTmpWords words per (frame, group)
     void* res;                                 // nz_rea_result* (device)
 };
 
@@ -214,6 +218,9 @@ struct CompressArgs {
     uint8_t* out; uint64_t out_cap;
     uint8_t* ws; WsLayout L;
     void* res;                // nz_result* (device)
+    // sampled arbitration only (encoder source 2): the cached code, where each group's bitstream is materialised
+    // before the frame's groups are packed together, the groups' realized bit counts and the frames' failure flags
+    const DevContext* rea_ctx; uint32_t* rea_tmp; uint32_t* rea_gbits; uint32_t* rea_fail;
 };
 
 // Result record as laid out by nz_result in the public header.

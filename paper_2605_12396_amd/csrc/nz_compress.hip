@@ -430,15 +430,22 @@ struct EncShared {
     __align__(16) uint32_t wtot[kEncSegs];     // bit count of each of the sub-block's segments
 };
 
-// zigzag code of a source word.  Only coded (FIXEDLEN / HUFFMAN) frames come here, and a frame is coded only if
-// the statistics pass found every element quantizable, so the acceptance tests of the quantizer are known to pass
-// and q is simply rne(x * inv_step).
+// zigzag code of a source word.  Sources 0 and 1: only coded (FIXEDLEN / HUFFMAN) frames come here, and a frame is
+// coded only if the statistics pass found every element quantizable, so the acceptance tests of the quantizer are
+// known to pass and q is simply rne(x * inv_step).  Source 2 (sampled arbitration): nothing has looked at the values
+// before, so the quantizer runs with its tests; a value that fails them counts as code 0 and clears *ok.
 template <int SRC>
-__device__ inline uint32_t enc_zz(uint32_t w, const CompressArgs& A) {
+__device__ inline uint32_t enc_zz(uint32_t w, const CompressArgs& A, bool* ok = nullptr) {
     if (SRC == 0) {
 #pragma clang fp contract(off)
         const float u = __uint_as_float(w) * A.inv_step;
         return zigzag((int32_t)__builtin_rintf(u));
+    }
+    if (SRC == 2) {
+        int32_t q;
+        const bool good = quantize1(__uint_as_float(w), A.eb, A.step, A.inv_step, q);
+        if (ok && !good) *ok = false;
+        return zigzag(q);
     }
     return zigzag((int32_t)w);
 }
@@ -454,7 +461,7 @@ struct EncGroup {
 // Source word i of the group: fp32 bits (SRC 0) or the summed code (SRC 1, coded frames).
 template <int SRC>
 __device__ inline uint32_t enc_word(const EncGroup& G, uint32_t i) {
-    if (SRC == 0) return G.src[i];
+    if (SRC != 1) return G.src[i];
     const int32_t q = G.src16[i];
     return (q == -32768) ? G.src[i] : (uint32_t)q;
 }
@@ -465,10 +472,10 @@ __device__ inline void enc_load(const EncGroup& G, uint32_t sb, uint32_t (&raw)[
     const uint32_t tid = threadIdx.x;
     const uint32_t* src = G.src + sb * kEncBlock;
     const uint32_t cnt = (sb < G.nsub) ? ((G.gcnt - sb * kEncBlock < kEncBlock) ? (G.gcnt - sb * kEncBlock) : kEncBlock) : 0u;
-    if (G.vec_ok && cnt == kEncBlock && (SRC == 0 || !G.wide16)) {       // uniform: the common, branch-free case
+    if (G.vec_ok && cnt == kEncBlock && (SRC != 1 || !G.wide16)) {       // uniform: the common, branch-free case
 #pragma unroll
         for (uint32_t it = 0; it < kEncIters; it++) {
-            if (SRC == 0) {
+            if (SRC != 1) {
                 const uint4 t = *reinterpret_cast<const uint4*>(src + it * 1024 + tid * 4);
                 raw[it][0] = t.x; raw[it][1] = t.y; raw[it][2] = t.z; raw[it][3] = t.w;
             } else {
@@ -492,7 +499,8 @@ __device__ inline void enc_load(const EncGroup& G, uint32_t sb, uint32_t (&raw)[
 }
 
 template <int SRC>
-__device__ inline void enc_raw_fixed(const CompressArgs& A, const EncGroup& G, const FrameMeta& M, uint8_t* fr, uint32_t* stage) {
+__device__ inline void enc_raw_fixed(const CompressArgs& A, const EncGroup& G, const FrameMeta& M, uint8_t* fr, uint32_t* stage,
+                                     uint32_t& bad) {
     const uint32_t tid = threadIdx.x;
     if (M.codec == CODEC_RAW) {
         uint32_t* dst = reinterpret_cast<uint32_t*>(fr + kHdrBytes) + G.g0;
@@ -510,7 +518,15 @@ __device__ inline void enc_raw_fixed(const CompressArgs& A, const EncGroup& G, c
         const uint32_t pass_words = (pass_syms * w + 31u) / 32u;
         uint32_t z[4];
 #pragma unroll
-        for (uint32_t j = 0; j < 4; j++) z[j] = (tid * 4 + j < pass_syms) ? enc_zz<SRC>(enc_word<SRC>(G, p0 + tid * 4 + j), A) : 0u;
+        for (uint32_t j = 0; j < 4; j++) {
+            z[j] = 0;
+            if (tid * 4 + j < pass_syms) {
+                bool ok = true;
+                z[j] = enc_zz<SRC>(enc_word<SRC>(G, p0 + tid * 4 + j), A, &ok);
+                if (SRC == 2 && w < 32u && (z[j] >> w)) { ok = false; z[j] &= (1u << w) - 1u; }   // wider than the sampled width
+                if (SRC == 2 && !ok) bad = 1;
+            }
+        }
         for (uint32_t k = tid; k < pass_words; k += kEncThreads) stage[k] = 0;
         __syncthreads();
         uint32_t pos = tid * 4 * w;
@@ -545,8 +561,8 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
     G.gcnt = (G.nf - G.g0 < kEncGroup) ? (G.nf - G.g0) : kEncGroup;
     G.last_grp = (G.g0 + G.gcnt == G.nf);
     G.nsub = (G.gcnt + kEncBlock - 1) / kEncBlock;
-    // source words: fp32 input (SRC 0) or the staged codes / fp32 sums of the reduce (SRC 1)
-    G.src = (SRC == 0 ? reinterpret_cast<const uint32_t*>(A.in) : reinterpret_cast<const uint32_t*>(A.ws + A.L.codes)) + f0 + G.g0;
+    // source words: fp32 input (SRC 0, 2) or the staged codes / fp32 sums of the reduce (SRC 1)
+    G.src = (SRC != 1 ? reinterpret_cast<const uint32_t*>(A.in) : reinterpret_cast<const uint32_t*>(A.ws + A.L.codes)) + f0 + G.g0;
     G.vec_ok = (((f0 + G.g0) & 3u) == 0);                                // kEncBlock is a multiple of 4
     G.src16 = reinterpret_cast<const int16_t*>(A.ws + A.L.c16) + f0 + G.g0;
     G.wide16 = false;
@@ -556,19 +572,35 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
     const FrameMeta M = reinterpret_cast<const FrameMeta*>(A.ws + A.L.meta)[frame];
     if (!M.fits) return;
     uint8_t* fr = A.out + M.offset;
-    if (M.codec != CODEC_HUFF) enc_raw_fixed<SRC>(A, G, M, fr, S.stage[0]);
+    uint32_t bad = 0;                             // SRC 2: a value that cannot be coded as planned fails the frame
+    if (M.codec != CODEC_HUFF) enc_raw_fixed<SRC>(A, G, M, fr, S.stage[0], bad);
     else {
         uint32_t raw[kEncIters][4];
         enc_load<SRC>(G, 0, raw);
-        for (uint32_t s = tid; s < K; s += kEncThreads) {
-            const uint32_t sy = (s == kesc) ? 0u : s + 1u;
-            const uint32_t c = reinterpret_cast<const uint32_t*>(A.ws + A.L.book_code)[(size_t)frame * kMaxK + sy];
-            const uint32_t l = (A.ws + A.L.book_len)[(size_t)frame * kMaxK + sy];
-            S.book[s] = (uint64_t)c | ((uint64_t)l << 32);
+        if (SRC == 2) {
+            for (uint32_t s = tid; s < K; s += kEncThreads) S.book[s] = A.rea_ctx->book[s];
+        } else {
+            for (uint32_t s = tid; s < K; s += kEncThreads) {
+                const uint32_t sy = (s == kesc) ? 0u : s + 1u;
+                const uint32_t c = reinterpret_cast<const uint32_t*>(A.ws + A.L.book_code)[(size_t)frame * kMaxK + sy];
+                const uint32_t l = (A.ws + A.L.book_len)[(size_t)frame * kMaxK + sy];
+                S.book[s] = (uint64_t)c | ((uint64_t)l << 32);
+            }
         }
         for (uint32_t i = tid; i < 2 * (kStageWords + 4); i += kEncThreads) (&S.stage[0][0])[i] = 0;
-        const uint32_t start_bit = reinterpret_cast<const uint32_t*>(A.ws + A.L.grp_start)[(size_t)frame * A.sbpf + G.g0 / A.stat_block];
+        // Where the group's bits go.  Sources 0, 1: the exact position in the frame's bitstream, known from the block
+        // histograms.  Source 2: sizes are only known once realized, so the frame's first group is materialised in
+        // place (from bit 0) and every other group from bit 0 of a scratch region of its own; the finishing kernel
+        // packs them behind each other.  In place nothing is written past the payload capacity (the RAW size of the
+        // frame: Algorithm 1's EncodePlan works inside payloadCap); what is dropped belongs to a frame whose realized
+        // payload exceeds that size and is rejected for it.
+        const uint32_t start_bit = (SRC == 2) ? 0u
+            : reinterpret_cast<const uint32_t*>(A.ws + A.L.grp_start)[(size_t)frame * A.sbpf + G.g0 / A.stat_block];
         uint32_t* bits = reinterpret_cast<uint32_t*>(fr + M.bits_off) + (start_bit >> 5);   // first word this group touches
+        if (SRC == 2 && G.gb > 0) bits = A.rea_tmp + ((size_t)frame * gpf + G.gb) * kReaTmpWords;
+        const uint32_t cap_end = kHdrBytes + 4u * G.nf;                   // SRC 2: first byte of the frame that is off limits
+        const uint32_t cap_segs = (SRC == 2) ? (M.segt_off < cap_end ? (cap_end - M.segt_off) / 2u : 0u) : 0xFFFFFFFFu;
+        const uint32_t cap_words = (SRC == 2 && G.gb == 0) ? (M.bits_off < cap_end ? (cap_end - M.bits_off) / 4u : 0u) : 0xFFFFFFFFu;
         uint16_t* segt = reinterpret_cast<uint16_t*>(fr + M.segt_off);
         const uint32_t nseg = (G.nf + kSeg - 1) / kSeg;
         uint32_t rel = start_bit & 31u;           // bits already in the current stage (carried over)
@@ -584,8 +616,8 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
             for (uint32_t k = tid; k < nw; k += kEncThreads) {
                 const uint32_t wv = X[k];
                 X[k] = 0;
-                if (G.gb > 0 && flushed == 0 && k == 0) atomicOr(dst, wv);   // word shared with the previous group
-                else dst[k] = wv;
+                if (SRC != 2 && G.gb > 0 && flushed == 0 && k == 0) atomicOr(dst, wv);   // word shared with the previous group
+                else if (flushed + k < cap_words) dst[k] = wv;
             }
             if (tid == 0) { carry = X[nw]; X[nw] = 0; Y[0] = carry; }
             flushed += nw;
@@ -625,10 +657,12 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
                     uint32_t tl = 0;
 #pragma unroll
                     for (uint32_t j = 0; j < 4; j++) {
-                        const uint32_t z = enc_zz<SRC>(raw[it][j], A);
+                        const bool valid = WHOLE || i + j < cnt;
+                        bool ok = true;
+                        const uint32_t z = enc_zz<SRC>(raw[it][j], A, &ok);
+                        if (SRC == 2 && valid && !ok) bad = 1;
                         zs[it][j] = z;
                         const uint64_t b = S.book[z < kesc ? z : kesc];
-                        const bool valid = WHOLE || i + j < cnt;
                         const uint32_t len = valid ? (uint32_t)(b >> 32) : 0u, code = valid ? (uint32_t)b : 0u;
                         acc |= (uint64_t)code << (tl & 63u);              // garbage once tl > 64: the pass is then redone
                         tl += len;
@@ -654,8 +688,8 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
             }
             if (tid < kEncSegs) {
                 const uint32_t gseg = (G.g0 + sb * kEncBlock) / kSeg + tid;
-                if (gseg < nseg) segt[gseg] = (uint16_t)S.wtot[tid];
-                if (gseg == nseg - 1 && (nseg & 1u)) segt[nseg] = 0;      // pad4 of the table
+                if (gseg < nseg && gseg < cap_segs) segt[gseg] = (uint16_t)S.wtot[tid];
+                if (gseg == nseg - 1 && (nseg & 1u) && nseg < cap_segs) segt[nseg] = 0;      // pad4 of the table
             }
             uint32_t* X = S.stage[cur];
             if (__builtin_expect(rel + pbase[kEncIters] <= 32u * kStageWords, 1)) {
@@ -703,9 +737,15 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
         // the last, partial word: shared with the next group, or the frame's last bitstream word
         if (tid == 0 && rel) {
             uint32_t* dst = bits + flushed;
-            if (!G.last_grp || (G.gb > 0 && flushed == 0)) atomicOr(dst, carry);
+            if (SRC == 2) { if (flushed < cap_words) *dst = carry; }
+            else if (!G.last_grp || (G.gb > 0 && flushed == 0)) atomicOr(dst, carry);
             else *dst = carry;
         }
+        if (SRC == 2 && tid == 0) A.rea_gbits[(size_t)frame * gpf + G.gb] = flushed * 32u + rel;     // realized bits of the group
+    }
+    if (SRC == 2) {              // (header, padding and the packing of the groups are the finishing kernel's)
+        if (bad) atomicOr(A.rea_fail + frame, 1u);
+        return;
     }
     if (G.last_grp) {            // the frame's last group zero-fills the padding after the payload
         const uint32_t w0 = (kHdrBytes + M.payload) / 4, w1 = M.total / 4;
@@ -778,8 +818,6 @@ __global__ __launch_bounds__(256) void k_rea_plan(ReaArgs A) {
     const uint64_t base = kStreamHdr + pad16u(8ull * A.n_frames);
     const bool ctx_ok = A.ctx && A.ctx->valid == 1u && A.ctx->K == K;
     // housekeeping for the next kernels
-    uint64_t* desc = reinterpret_cast<uint64_t*>(A.ws + A.L.desc) + (size_t)frame * A.spf;
-    for (uint32_t i = tid; i < A.spf; i += 256) desc[i] = 0;
     if (tid == 0) {
         reinterpret_cast<uint32_t*>(A.ws + A.L.fail)[frame] = 0;
         *reinterpret_cast<uint64_t*>(A.out + kStreamHdr + 8ull * frame) = base + (uint64_t)frame * A.slot;
@@ -787,7 +825,6 @@ __global__ __launch_bounds__(256) void k_rea_plan(ReaArgs A) {
         s_zmax = 0; s_bad = 0;
     }
     if (frame == 0 && tid == 0) {
-        reinterpret_cast<Ctrl*>(A.ws + A.L.ctrl)->ticket_book = 0;
         ReaResultRec* res = reinterpret_cast<ReaResultRec*>(A.res);
         res->span_bytes = 0; res->wire_bytes = 0; res->status = ST_OK; res->n_frames = A.n_frames;
         res->n_raw = 0; res->n_fixed = 0; res->n_huff = 0; res->n_fallback = 0;
@@ -803,13 +840,26 @@ __global__ __launch_bounds__(256) void k_rea_plan(ReaArgs A) {
     const uint32_t n_s = profiled ? (A.sample_elems < nf ? A.sample_elems : nf) : 0u;
     uint32_t zmax = 0, bad = 0;
     uint64_t bits = 0;
-    for (uint32_t i = tid; i < n_s; i += 256) {
+    auto profile1 = [&](float x) {
         int32_t q;
-        if (!quantize1(A.in[f0 + i], A.eb, A.step, A.inv_step, q)) bad = 1;
+        if (!quantize1(x, A.eb, A.step, A.inv_step, q)) bad = 1;
         const uint32_t z = zigzag(q);
         zmax = z > zmax ? z : zmax;
         if (ctx_ok) bits += s_l[bin_of(z, K)];
+    };
+    const float* sp = A.in + f0;
+    uint32_t i = 0;
+    if ((f0 & 3u) == 0) {                        // eight 16-byte loads in flight per thread
+        constexpr uint32_t kBatch = 8 * 256 * 4;
+        for (; i + kBatch <= n_s; i += kBatch) {
+            float4 t[8];
+#pragma unroll
+            for (uint32_t u = 0; u < 8; u++) t[u] = reinterpret_cast<const float4*>(sp + i)[u * 256 + tid];
+#pragma unroll
+            for (uint32_t u = 0; u < 8; u++) { profile1(t[u].x); profile1(t[u].y); profile1(t[u].z); profile1(t[u].w); }
+        }
     }
+    for (uint32_t k = i + tid; k < n_s; k += 256) profile1(sp[k]);
     zmax = wave_max(zmax); bad = wave_max(bad); bits = wave_sum64(bits);
     if (lane == 0) { atomicMax(&s_zmax, zmax); atomicMax(&s_bad, bad); s_bits[wave] = bits; }
     __syncthreads();
@@ -844,298 +894,52 @@ __global__ __launch_bounds__(256) void k_rea_plan(ReaArgs A) {
     reinterpret_cast<FrameMeta*>(A.ws + A.L.meta)[frame] = M;
 }
 
-// Lookup phase of one piece of kReaSub symbols (all kEncThreads threads): load, quantize with the acceptance tests
-// (nothing has looked at these values before), look every symbol up in the context's table, pack the 4 symbols of a
-// thread into 64 bits, scan the bit counts over the wave.  Pass `it` covers symbols it*1024 + tid*4 .. +3 of the piece.
-// wseg[it*4 + wave] receives the bit count of the segment the wave's pass covers.
-__device__ __forceinline__ void rea_phase1(const ReaArgs& A, const uint64_t* book, const uint32_t* src, uint32_t j, uint32_t nf,
-                                           bool vec_ok, uint32_t K, uint64_t (&pk)[kEncIters], uint32_t (&ln)[kEncIters],
-                                           uint32_t& wide, uint32_t& bad, uint32_t* wseg) {
-    const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6, kesc = K - 1u;
-    const uint32_t cnt = (nf - j * kReaSub < kReaSub) ? (nf - j * kReaSub) : kReaSub;
-    const uint32_t* p = src + j * kReaSub;
-    uint32_t raw[kEncIters][4];
-    if (vec_ok && cnt == kReaSub) {
-#pragma unroll
-        for (uint32_t it = 0; it < kEncIters; it++) {
-            const uint4 t = *reinterpret_cast<const uint4*>(p + it * 1024 + tid * 4);
-            raw[it][0] = t.x; raw[it][1] = t.y; raw[it][2] = t.z; raw[it][3] = t.w;
-        }
+// AcceptRealized + CommitRawOrFail, and everything that needs the realized size: the groups of a HUFFMAN frame are
+// packed behind each other (every group but the first was materialised from bit 0 of a scratch region), then header,
+// code-length table, padding, the result record.  A rejected frame is copied again as RAW by all of its workgroups.
+//
+// Bits of the stream `src` (len bits, starting at bit `start` of the frame's bitstream) that fall into word w of
+// the frame's bitstream; words of src at or beyond nwords are not read.
+__device__ inline uint32_t rea_contrib(const uint32_t* src, uint64_t start, uint64_t len, uint64_t w) {
+    const int64_t r = (int64_t)(32ull * w) - (int64_t)start;            // first bit of word w, relative to the stream
+    if (r <= -32 || r >= (int64_t)len) return 0;
+    const uint64_t nwords = (len + 31u) >> 5;
+    uint32_t v;
+    uint64_t have;                                                       // valid bits from the low end of v (before masking)
+    if (r >= 0) {
+        const uint64_t a = (uint64_t)r >> 5;
+        const uint32_t s = (uint32_t)r & 31u;
+        const uint32_t lo = src[a], hi = (s && a + 1 < nwords) ? src[a + 1] : 0u;
+        v = s ? ((lo >> s) | (hi << (32u - s))) : lo;
+        have = len - (uint64_t)r;
+        if (have < 32u) v &= (1u << have) - 1u;
     } else {
-#pragma unroll
-        for (uint32_t it = 0; it < kEncIters; it++)
-#pragma unroll
-            for (uint32_t jj = 0; jj < 4; jj++) {
-                const uint32_t i = it * 1024 + tid * 4 + jj;
-                raw[it][jj] = (i < cnt) ? p[i] : 0u;
-            }
+        const uint32_t sh = (uint32_t)(-r);
+        uint32_t lo = src[0];
+        if (len < 32u) lo &= (1u << len) - 1u;
+        v = lo << sh;
     }
-    wide = 0;
-#pragma unroll
-    for (uint32_t it = 0; it < kEncIters; it++) {
-        const uint32_t i = it * 1024 + tid * 4;
-        uint64_t acc = 0;
-        uint32_t tl = 0;
-#pragma unroll
-        for (uint32_t jj = 0; jj < 4; jj++) {
-            const bool valid = i + jj < cnt;
-            int32_t q;
-            if (!quantize1(__uint_as_float(raw[it][jj]), A.eb, A.step, A.inv_step, q) && valid) bad = 1;
-            const uint32_t z = zigzag(q);
-            const uint64_t b = book[z < kesc ? z : kesc];
-            const uint32_t len = valid ? (uint32_t)(b >> 32) : 0u, code = valid ? (uint32_t)b : 0u;
-            acc |= (uint64_t)code << (tl & 63u);              // garbage once tl > 64: the pass is then redone
-            tl += len;
-            if (z >= kesc && valid) { acc |= (uint64_t)z << (tl & 63u); tl += 32u; }
-        }
-        pk[it] = acc;
-        wide |= (tl > 64u ? 1u : 0u) << it;
-        const uint32_t incl = wave_incl_scan_dpp(tl);
-        ln[it] = incl - tl;
-        if (lane == 63) wseg[it * 4 + wave] = incl;
-    }
+    return v;
 }
 
-// EncodePlan: the planned codec over the whole frame, in one pass over the input.
-//   RAW       copy.
-//   FIXEDLEN  the sampled width at closed-form positions; a value that needs more bits, or cannot be quantized,
-//             raises the frame's failure flag.
-//   HUFFMAN   the context's code.  The frame's workgroups take its pieces of kReaSub symbols round robin; a piece's
-//             bit count is known after its lookup phase and its first bit follows from a decoupled look-back over
-//             the pieces before it (tickets make every wait end: a piece only waits for pieces that belong to
-//             workgroups that have started).  Whole words go straight to the frame; the first and last partial
-//             word of a piece are left in the workspace and merged with the neighbours' by the finishing kernel.
-__global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))) void k_rea_encode(ReaArgs A) {
-    __shared__ EncShared S;
-    __shared__ uint32_t s_ticket;
-    __shared__ uint64_t s_excl;
-    const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
-    if (tid == 0) s_ticket = atomicAdd(&reinterpret_cast<Ctrl*>(A.ws + A.L.ctrl)->ticket_book, 1u);
-    __syncthreads();
-    const uint32_t frame = s_ticket / A.gpf, wg = s_ticket % A.gpf;
-    const uint64_t f0 = (uint64_t)frame * A.chunk;
-    const uint32_t nf = (uint32_t)((A.n - f0 < A.chunk) ? (A.n - f0) : A.chunk);
-    const FrameMeta M = reinterpret_cast<const FrameMeta*>(A.ws + A.L.meta)[frame];
-    uint8_t* fr = A.out + M.offset;
-    uint32_t* fail = reinterpret_cast<uint32_t*>(A.ws + A.L.fail) + frame;
-    const uint32_t* src = reinterpret_cast<const uint32_t*>(A.in) + f0;
-    const bool vec_ok = ((f0 & 3u) == 0);
-    const uint32_t K = A.K, kesc = K - 1u;
-    uint32_t bad = 0;
-
-    if (M.codec != CODEC_HUFF) {
-        const uint32_t g0 = wg * kEncGroup;                               // a contiguous share of the frame
-        if (g0 >= nf) return;
-        const uint32_t gcnt = (nf - g0 < kEncGroup) ? (nf - g0) : kEncGroup;
-        if (M.codec == CODEC_RAW) {
-            uint32_t* dst = reinterpret_cast<uint32_t*>(fr + kHdrBytes) + g0;
-            for (uint32_t i = tid * 4; i < gcnt; i += kEncThreads * 4) {
-                if (vec_ok && i + 4 <= gcnt) *reinterpret_cast<uint4*>(dst + i) = *reinterpret_cast<const uint4*>(src + g0 + i);
-                else for (uint32_t j = 0; j < 4; j++) if (i + j < gcnt) dst[i + j] = src[g0 + i + j];
-            }
-            return;
-        }
-        const uint32_t w = M.w;
-        uint32_t* stage = S.stage[0];
-        uint32_t* bitsw = reinterpret_cast<uint32_t*>(fr + kHdrBytes) + (g0 / 32u) * w;
-        for (uint32_t p0 = 0; p0 < gcnt; p0 += 1024) {
-            const uint32_t pass_syms = (gcnt - p0 < 1024u) ? (gcnt - p0) : 1024u;
-            const uint32_t pass_words = (pass_syms * w + 31u) / 32u;
-            uint32_t z[4];
-#pragma unroll
-            for (uint32_t j = 0; j < 4; j++) {
-                z[j] = 0;
-                if (tid * 4 + j < pass_syms) {
-                    int32_t q;
-                    if (!quantize1(__uint_as_float(src[g0 + p0 + tid * 4 + j]), A.eb, A.step, A.inv_step, q)) bad = 1;
-                    z[j] = zigzag(q);
-                    if (w < 32u && (z[j] >> w)) { bad = 1; z[j] &= (1u << w) - 1u; }     // does not fit the sampled width
-                }
-            }
-            for (uint32_t k = tid; k < pass_words; k += kEncThreads) stage[k] = 0;
-            __syncthreads();
-            uint32_t pos = tid * 4 * w;
-#pragma unroll
-            for (uint32_t j = 0; j < 4; j++) {
-                if (tid * 4 + j < pass_syms && w) {
-                    const uint32_t sh = pos & 31u, wi = pos >> 5;
-                    atomicOr(&stage[wi], z[j] << sh);
-                    if (sh + w > 32u) atomicOr(&stage[wi + 1], z[j] >> (32u - sh));
-                    pos += w;
-                }
-            }
-            __syncthreads();
-            uint32_t* dst = bitsw + (p0 / 32u) * w;
-            for (uint32_t k = tid; k < pass_words; k += kEncThreads) dst[k] = stage[k];
-            __syncthreads();
-        }
-        if (bad) atomicOr(fail, 1u);
-        return;
-    }
-
-    // ---- HUFFMAN with the context's code ----
-    // The pieces of a workgroup are pipelined one deep: the lookup phase of the next piece runs (and its bit count is
-    // published) before the look-back of the current one is resolved, so the latency of the descriptors -- the
-    // frame's workgroups sit on different compute units -- passes behind useful work.
-    const uint32_t nsub = (nf + kReaSub - 1) / kReaSub;
-    if (wg >= nsub) return;
-    for (uint32_t b = tid; b < K; b += kEncThreads) S.book[b] = A.ctx->book[b];
-    for (uint32_t i = tid; i < 2 * (kStageWords + 4); i += kEncThreads) (&S.stage[0][0])[i] = 0;
-    uint64_t* desc = reinterpret_cast<uint64_t*>(A.ws + A.L.desc) + (size_t)frame * A.spf;
-    uint2* frag = reinterpret_cast<uint2*>(A.ws + A.L.frag) + (size_t)frame * A.spf;
-    uint16_t* segt = reinterpret_cast<uint16_t*>(fr + M.segt_off);
-    uint32_t* bits0 = reinterpret_cast<uint32_t*>(fr + M.bits_off);
-    const uint32_t nseg = (nf + kSeg - 1) / kSeg;
-    uint32_t* X = S.stage[0];
-    uint32_t* wt = S.stage[1];                 // the second stage is free here: per-segment bit counts of two pieces in flight
-    // EncodePlan works inside the payload capacity (Algorithm 1): nothing is written past the RAW size of the frame,
-    // which is what its slot holds.  Whatever is dropped belongs to a frame whose realized payload exceeds that size,
-    // which the finishing kernel rejects from the piece bit counts alone.
-    const uint32_t cap_end = kHdrBytes + 4u * nf;                         // first byte of the frame that is off limits
-    const uint32_t cap_segs = M.segt_off < cap_end ? (cap_end - M.segt_off) / 2u : 0u;      // segment-table entries that fit
-    const uint32_t cap_words = M.bits_off < cap_end ? (cap_end - M.bits_off) / 4u : 0u;     // bitstream words that fit
-    __syncthreads();
-
-    uint64_t pk0[kEncIters], pk1[kEncIters];   // the thread's 4 symbols of a pass packed LSB-first: current and next piece
-    uint32_t ln0[kEncIters], ln1[kEncIters];   // exclusive bit offset of the thread inside its wave's segment
-    uint32_t wide0 = 0, wide1 = 0;             // pass mask: the 4 symbols need more than 64 bits
-    uint32_t buf = 0;                          // which half of wt belongs to the current piece
-    rea_phase1(A, S.book, src, wg, nf, vec_ok, K, pk0, ln0, wide0, bad, wt);
-    __syncthreads();
-    if (tid == 0) {
-        uint32_t T = 0;
-        for (uint32_t i = 0; i < kEncSegs; i++) T += wt[i];
-        st_agent(desc + wg, kDescA | (uint64_t)T);
-    }
-    for (uint32_t j = wg; j < nsub; j += A.gpf) {
-        const uint32_t cnt = (nf - j * kReaSub < kReaSub) ? (nf - j * kReaSub) : kReaSub;
-        const uint32_t jn = j + A.gpf;
-        uint32_t* wcur = wt + buf * kEncSegs;
-        uint32_t* wnxt = wt + (buf ^ 1u) * kEncSegs;
-        if (jn < nsub) rea_phase1(A, S.book, src, jn, nf, vec_ok, K, pk1, ln1, wide1, bad, wnxt);
-        __syncthreads();
-        if (wave == 0) {
-            uint32_t Tn = 0, T = 0;
-            for (uint32_t i = 0; i < kEncSegs; i++) { Tn += wnxt[i]; T += wcur[i]; }
-            if (jn < nsub && lane == 0) st_agent(desc + jn, kDescA | (uint64_t)Tn);
-            const uint64_t excl = lookback_exclusive(desc, 0, (int64_t)j, 0);
-            if (lane == 0) { st_agent(desc + j, kDescP | (excl + T)); s_excl = excl; }
-        }
-        if (tid < kEncSegs) {
-            const uint32_t gseg = j * kEncSegs + tid;
-            if (gseg < nseg && gseg < cap_segs) segt[gseg] = (uint16_t)wcur[tid];
-            if (gseg == nseg - 1 && (nseg & 1u) && nseg < cap_segs) segt[nseg] = 0;
-        }
-        __syncthreads();
-        uint32_t pbase[kEncIters + 1];
-        pbase[0] = 0;
-#pragma unroll
-        for (uint32_t it = 0; it < kEncIters; it++) {
-            const uint4 t = reinterpret_cast<const uint4*>(wcur)[it];
-            ln0[it] += (wave > 0 ? t.x : 0u) + (wave > 1 ? t.y : 0u) + (wave > 2 ? t.z : 0u);
-            pbase[it + 1] = pbase[it] + t.x + t.y + t.z + t.w;
-        }
-        const uint32_t T = pbase[kEncIters];
-        const uint64_t excl = s_excl;
-        const uint32_t rel = (uint32_t)(excl & 31u);
-        const uint64_t w0 = excl >> 5;                                   // first bitstream word this piece touches
-        // Place the passes behind the bits already in the stage, write the whole words, keep the partial one.  All
-        // four passes at once when they fit the stage, else pass by pass (a pass is at most 1024 * 60 bits).
-        const bool fits = rel + T <= 32u * kStageWords;
-        const uint32_t nchunk = fits ? 1u : kEncIters;
-        uint32_t runpos = rel, flushed = 0, lo = 0, hi = 0;
-#pragma unroll 1
-        for (uint32_t c = 0; c < nchunk; c++) {
-            uint32_t cb = 0, ce = T;                                     // bit range of this chunk inside the piece
-            if (!fits) {
-#pragma unroll
-                for (uint32_t it = 0; it < kEncIters; it++) if (it == c) { cb = pbase[it]; ce = pbase[it + 1]; }
-            }
-#pragma unroll
-            for (uint32_t it = 0; it < kEncIters; it++) {
-                if (!fits && it != c) continue;
-                uint32_t pos = runpos + (pbase[it] - cb) + ln0[it];
-                if (__builtin_expect(!((wide0 >> it) & 1u), 1)) {
-                    const uint64_t a = pk0[it];
-                    if (a) {
-                        const uint32_t sh = pos & 31u, wi = pos >> 5;
-                        const uint64_t t = a << sh;
-                        atomicOr(&X[wi], (uint32_t)t);
-                        if ((uint32_t)(t >> 32)) atomicOr(&X[wi + 1], (uint32_t)(t >> 32));
-                        if (sh) { const uint32_t h2 = (uint32_t)(a >> (64u - sh)); if (h2) atomicOr(&X[wi + 2], h2); }
-                    }
-                } else {
-                    // the thread's 4 symbols need more than 64 bits (rare): symbol by symbol, from the source words
-                    const uint32_t i = it * 1024 + tid * 4;
-                    for (uint32_t jj = 0; jj < 4; jj++) {
-                        if (i + jj < cnt) {
-                            int32_t q;
-                            quantize1(__uint_as_float(src[j * kReaSub + i + jj]), A.eb, A.step, A.inv_step, q);
-                            const uint32_t z = zigzag(q);
-                            const uint64_t b = S.book[z < kesc ? z : kesc];
-                            const uint32_t val = (uint32_t)b, len = (uint32_t)(b >> 32);
-                            {
-                                const uint32_t sh = pos & 31u, wi = pos >> 5;
-                                atomicOr(&X[wi], val << sh);
-                                if (sh + len > 32u) atomicOr(&X[wi + 1], val >> (32u - sh));
-                                pos += len;
-                            }
-                            if (z >= kesc) {
-                                const uint32_t sh = pos & 31u, wi = pos >> 5;
-                                atomicOr(&X[wi], z << sh);
-                                if (sh) atomicOr(&X[wi + 1], z >> (32u - sh));
-                                pos += 32u;
-                            }
-                        }
-                    }
-                }
-            }
-            __syncthreads();
-            const uint32_t nbits = runpos + (ce - cb);
-            const uint32_t nw = nbits >> 5;
-            for (uint32_t k = tid; k < nw; k += kEncThreads) {
-                const uint32_t wv = X[k];
-                X[k] = 0;
-                if (k == 0 && flushed == 0 && rel) lo = wv;             // shared with the piece before: merged later
-                else if (w0 + flushed + k < cap_words) bits0[w0 + flushed + k] = wv;
-            }
-            if (tid == 0) { const uint32_t cw = X[nw]; X[nw] = 0; X[0] = cw; }
-            flushed += nw;
-            runpos = nbits & 31u;
-            __syncthreads();
-        }
-        if (tid == 0) {
-            if (runpos) { const uint32_t v = X[0]; if (flushed == 0 && rel) lo = v; else hi = v; }
-            X[0] = 0;
-            frag[j] = make_uint2(lo, hi);
-        }
-#pragma unroll
-        for (uint32_t it = 0; it < kEncIters; it++) { pk0[it] = pk1[it]; ln0[it] = ln1[it]; }
-        wide0 = wide1;
-        buf ^= 1u;
-        __syncthreads();
-    }
-    if (bad) atomicOr(fail, 1u);
-}
-
-// AcceptRealized + CommitRawOrFail, and everything that needs the realized size: header, code-length table, the
-// words in which two pieces meet, padding, the result record.  A rejected frame is copied again as RAW by all of
-// its workgroups (rare).
 __global__ __launch_bounds__(256) void k_rea_finish(ReaArgs A) {
     const uint32_t tid = threadIdx.x;
     const uint32_t frame = blockIdx.x / A.gpf, wg = blockIdx.x % A.gpf;
     const uint64_t f0 = (uint64_t)frame * A.chunk;
     const uint32_t nf = (uint32_t)((A.n - f0 < A.chunk) ? (A.n - f0) : A.chunk);
+    const uint32_t g0 = wg * kEncGroup;
+    if (g0 >= nf) return;
+    const uint32_t ngrp = (nf + kEncGroup - 1) / kEncGroup;
     const FrameMeta M = reinterpret_cast<const FrameMeta*>(A.ws + A.L.meta)[frame];
     uint8_t* fr = A.out + M.offset;
     const uint32_t K = A.K, plan = M.codec;
-    const uint32_t nsub = (nf + kReaSub - 1) / kReaSub, nseg = (nf + kSeg - 1) / kSeg;
-    const uint64_t* desc = reinterpret_cast<const uint64_t*>(A.ws + A.L.desc) + (size_t)frame * A.spf;
+    const uint32_t nseg = (nf + kSeg - 1) / kSeg;
+    const uint32_t* gbits = reinterpret_cast<const uint32_t*>(A.ws + A.L.gbits) + (size_t)frame * A.gpf;
     const uint64_t rawb = 4ull * nf;
-    uint64_t payload = rawb, bits = 0;
+    uint64_t payload = rawb, bits = 0, start = 0;                       // start: first bit of this workgroup's group
     if (plan == CODEC_FIXED) payload = 4ull * (((uint64_t)nf * M.w + 31u) / 32u);
     else if (plan == CODEC_HUFF) {
-        bits = desc[nsub - 1] & kDescMask;                               // inclusive prefix of the last piece
+        for (uint32_t g = 0; g < ngrp; g++) { if (g == wg) start = bits; bits += gbits[g]; }
         payload = pad4u(K) + pad4u(2ull * nseg) + 4ull * ((bits + 31u) / 32u);
     }
     uint32_t codec = plan;
@@ -1147,30 +951,45 @@ __global__ __launch_bounds__(256) void k_rea_finish(ReaArgs A) {
     if (codec == CODEC_RAW) payload = rawb;
     const uint32_t total = (uint32_t)pad16u(kHdrBytes + payload);
     if (fell_back) {
-        const uint32_t g0 = wg * kEncGroup;
-        if (g0 < nf) {
-            const uint32_t gcnt = (nf - g0 < kEncGroup) ? (nf - g0) : kEncGroup;
-            const uint32_t* src = reinterpret_cast<const uint32_t*>(A.in) + f0 + g0;
-            uint32_t* dst = reinterpret_cast<uint32_t*>(fr + kHdrBytes) + g0;
-            for (uint32_t i = tid; i < gcnt; i += 256) dst[i] = src[i];
+        const uint32_t gcnt = (nf - g0 < kEncGroup) ? (nf - g0) : kEncGroup;
+        const uint32_t* src = reinterpret_cast<const uint32_t*>(A.in) + f0 + g0;
+        uint32_t* dst = reinterpret_cast<uint32_t*>(fr + kHdrBytes) + g0;
+        for (uint32_t i = tid; i < gcnt; i += 256) dst[i] = src[i];
+    }
+    if (codec == CODEC_HUFF && wg > 0) {
+        // Pack this group behind the one before it.  It writes every word its bits reach, the first one together
+        // with the tail of the group before (which left that word alone unless it is the frame's first group, whose
+        // tail is already in place), and leaves its own last word to the next group if it is partial.
+        uint32_t* bits0 = reinterpret_cast<uint32_t*>(fr + M.bits_off);
+        const uint32_t* tmp = A.tmp_base + ((size_t)frame * A.gpf + wg) * kReaTmpWords;
+        const uint64_t len = gbits[wg], end = start + len;
+        const uint64_t W0 = start >> 5;
+        const uint64_t W1 = (wg == ngrp - 1 || (end & 31u) == 0) ? ((end + 31u) >> 5) : (end >> 5);   // one past the last word written
+        const uint64_t plen = gbits[wg - 1], pstart = start - plen;
+        const uint32_t* ptmp = A.tmp_base + ((size_t)frame * A.gpf + wg - 1) * kReaTmpWords;
+        const uint32_t sh = (uint32_t)(start & 31u), back = sh ? 1u : 0u, s = (32u - sh) & 31u;
+        const uint32_t nw = (uint32_t)(W1 - W0);
+        const uint32_t interior = (uint32_t)(len >> 5);                   // words w of the frame with k - back + 1 < interior need no care
+        uint32_t* dst = bits0 + W0;
+        for (uint32_t k = tid; k < nw; k += 256) {
+            uint32_t v;
+            if (k >= back && k - back + 1 < interior) {
+                const uint32_t a = k - back;                              // group bits [32a + s', ...) with s' = s
+                v = __builtin_amdgcn_alignbit(tmp[a + 1], tmp[a], s);
+            } else {
+                v = rea_contrib(tmp, start, len, W0 + k);
+                if (k == 0 && sh) v |= (wg == 1) ? dst[0] : rea_contrib(ptmp, pstart, plen, W0);
+            }
+            dst[k] = v;
         }
     }
     if (wg != 0) return;
     if (codec == CODEC_HUFF) {
-        uint32_t* bits0 = reinterpret_cast<uint32_t*>(fr + M.bits_off);
-        const uint2* frag = reinterpret_cast<const uint2*>(A.ws + A.L.frag) + (size_t)frame * A.spf;
-        for (uint32_t j = tid + 1; j < nsub; j += 256) {                 // the word in which pieces j-1 and j meet
-            const uint64_t Sj = desc[j - 1] & kDescMask;
-            if (Sj & 31u) bits0[Sj >> 5] = frag[j - 1].y | frag[j].x;
-        }
-        if (tid == 0 && (bits & 31u)) {                                  // the frame's last, partial word
-            const uint64_t Sl = nsub > 1 ? (desc[nsub - 2] & kDescMask) : 0ull;
-            if ((bits >> 5) != (Sl >> 5) || !(Sl & 31u)) bits0[bits >> 5] = frag[nsub - 1].y;
-        }
         const uint32_t words = (uint32_t)(pad4u(K) / 4);                 // code lengths, one byte per symbol, zero padded
+        const uint32_t* lw = reinterpret_cast<const uint32_t*>(A.ctx->len);
         for (uint32_t i = tid; i < words; i += 256) {
-            uint32_t v = 0;
-            for (uint32_t b = 0; b < 4; b++) if (4 * i + b < K) v |= (uint32_t)A.ctx->len[4 * i + b] << (8 * b);
+            uint32_t v = lw[i];
+            if (4 * i + 4 > K) v &= (1u << (8 * (K - 4 * i))) - 1u;      // K = 2: two lengths, two bytes of padding
             reinterpret_cast<uint32_t*>(fr + kHdrBytes)[i] = v;
         }
     }
@@ -1218,7 +1037,16 @@ hipError_t launch_rea_status(void* res, uint32_t n_frames, uint32_t status, hipS
 hipError_t launch_rea(const ReaArgs& A, hipStream_t st, void (*mark)(hipStream_t)) {
     hipLaunchKernelGGL(k_rea_plan, dim3(A.n_frames), dim3(256), 0, st, A);
     mark(st);
-    hipLaunchKernelGGL(k_rea_encode, dim3(A.n_frames * A.gpf), dim3(kEncThreads), 0, st, A);
+    // EncodePlan: the shared encoder with the sampled-arbitration source (quantizer tests on, the context's code,
+    // group bitstreams from bit 0)
+    CompressArgs C = {};
+    C.in = A.in; C.n = A.n; C.chunk = A.chunk; C.n_frames = A.n_frames; C.K = A.K; C.sbpf = A.gpf; C.stat_block = kEncGroup;
+    C.force_codec = A.force_codec; C.min_gain_permil = A.min_gain_permil; C.huff_min_bytes = A.huff_min_bytes;
+    C.eb = A.eb; C.step = A.step; C.inv_step = A.inv_step; C.step_bits = A.step_bits;
+    C.out = A.out; C.out_cap = 0; C.ws = A.ws; C.L = WsLayout(); C.L.meta = A.L.meta; C.res = A.res;
+    C.rea_ctx = A.ctx; C.rea_tmp = A.tmp_base; C.rea_gbits = reinterpret_cast<uint32_t*>(A.ws + A.L.gbits);
+    C.rea_fail = reinterpret_cast<uint32_t*>(A.ws + A.L.fail);
+    hipLaunchKernelGGL(k_encode<2>, dim3(A.n_frames * A.gpf), dim3(kEncThreads), 0, st, C);
     mark(st);
     hipLaunchKernelGGL(k_rea_finish, dim3(A.n_frames * A.gpf), dim3(256), 0, st, A);
     mark(st);
