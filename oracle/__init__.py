@@ -86,6 +86,14 @@ def lib():
         L.nzo_frame_plan.argtypes = [vp, C.c_uint32, C.c_int, C.POINTER(Opts), vp, vp, vp, vp, vp, vp, vp]
         L.nzo_frame_encode.argtypes = [vp, vp, C.c_uint32, C.c_int, C.POINTER(Opts), C.c_uint32, vp, sz]
         L.nzo_frame_encode.restype = C.c_int64
+        L.nzo_sr_draw.argtypes = [C.c_uint32, C.c_uint64]
+        L.nzo_sr_draw.restype = C.c_uint32
+        L.nzo_sr_quantize.argtypes = [vp, sz, f32, C.c_uint32, C.c_uint64, vp, vp]
+        L.nzo_qsgd_step.argtypes = [vp, sz, C.c_uint32, C.POINTER(f32)]
+        L.nzo_compress_sr.argtypes = [vp, sz, f32, C.c_uint32, C.POINTER(Opts), vp, sz, C.POINTER(Result)]
+        L.nzo_decompress_step.argtypes = [vp, sz, vp, sz, f32, C.POINTER(Result)]
+        L.nzo_decode_codes_step.argtypes = [vp, sz, sz, f32, vp, vp, vp, C.POINTER(Result)]
+        L.nzo_reduce_frames_step.argtypes = [vp, sz, vp, sz, vp, sz, sz, f32, C.POINTER(Opts), C.POINTER(Result)]
         L.nzo_context_build.argtypes = [vp, sz, f32, C.POINTER(Opts), C.POINTER(Context)]
         L.nzo_rea_plan_frame.argtypes = [vp, C.c_uint32, f32, C.POINTER(Opts), C.POINTER(ReaOpts), C.POINTER(Context),
                                          C.POINTER(ReaPlan)]
@@ -278,3 +286,69 @@ def compress_rea(x, eb, opts=None, ropts=None, ctx=None, cap=None):
                                 C.byref(ropts) if ropts is not None else None,
                                 C.byref(ctx) if ctx is not None else None, _ptr(out), cap, C.byref(res), _ptr(plans))
     return out[:res.span_bytes].copy(), res, rc, plans
+
+
+def sr_draw(seed, i):
+    return int(lib().nzo_sr_draw(seed, i))
+
+
+def sr_quantize(x, step, seed, first_index=0):
+    """Stochastic (QSGD-style) rounding to multiples of step; element k uses draw (seed, first_index + k)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    q = np.empty(x.size, np.int32)
+    ok = np.empty(x.size, np.uint8)
+    rc = lib().nzo_sr_quantize(_ptr(x), x.size, C.c_float(step), seed, first_index, _ptr(q), _ptr(ok))
+    if rc:
+        raise ValueError("invalid step")
+    return q, ok.astype(bool)
+
+
+def qsgd_step(x, levels):
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    st = C.c_float()
+    rc = lib().nzo_qsgd_step(_ptr(x), x.size, levels, C.byref(st))
+    if rc:
+        raise ValueError("qsgd_step failed: %d" % rc)
+    return float(st.value)
+
+
+def compress_sr(x, step, seed, opts=None, cap=None):
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if cap is None:
+        cap = compress_bound(x.size, opts)
+    out = np.zeros(max(cap, 1), np.uint8)
+    res = Result()
+    rc = lib().nzo_compress_sr(_ptr(x), x.size, C.c_float(step), seed, C.byref(opts) if opts is not None else None,
+                               _ptr(out), cap, C.byref(res))
+    return out[:res.bytes].copy(), res, rc
+
+
+def decompress_step(stream, n, step):
+    s = np.ascontiguousarray(stream, dtype=np.uint8)
+    out = np.zeros(n, np.float32)
+    res = Result()
+    rc = lib().nzo_decompress_step(_ptr(s), s.size, _ptr(out), n, C.c_float(step), C.byref(res))
+    return out, res, rc
+
+
+def decode_codes_step(stream, n, step):
+    s = np.ascontiguousarray(stream, dtype=np.uint8)
+    q = np.zeros(n, np.int32)
+    rb = np.zeros(n, np.uint32)
+    nfr = int(np.frombuffer(s[20:24].tobytes(), np.uint32)[0]) if s.size >= 24 else 1
+    kinds = np.zeros(max(nfr, 1), np.uint8)
+    res = Result()
+    rc = lib().nzo_decode_codes_step(_ptr(s), s.size, n, C.c_float(step), _ptr(q), _ptr(rb), _ptr(kinds), C.byref(res))
+    return q, rb, kinds, res, rc
+
+
+def reduce_frames_step(a, b, n, step, opts=None, cap=None):
+    a = np.ascontiguousarray(a, dtype=np.uint8)
+    b = np.ascontiguousarray(b, dtype=np.uint8)
+    if cap is None:
+        cap = compress_bound(n, opts)
+    out = np.zeros(max(cap, 1), np.uint8)
+    res = Result()
+    rc = lib().nzo_reduce_frames_step(_ptr(a), a.size, _ptr(b), b.size, _ptr(out), cap, n, C.c_float(step),
+                                      C.byref(opts) if opts is not None else None, C.byref(res))
+    return out[:res.bytes].copy(), res, rc

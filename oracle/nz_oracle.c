@@ -644,14 +644,17 @@ static int decode_frame(const uint8_t* s, uint64_t total, uint64_t off, uint32_t
  * frame k was RAW (then rawbits holds its elements, q is 0 there), 0 when
  * coded (q valid), 2 when the frame was rejected (both zero-filled).
  */
-int nzo_decode_codes(const uint8_t* s, size_t bytes, size_t n, float eb, int32_t* q, uint32_t* rawbits,
-                     uint8_t* frame_raw, nzo_result* res) {
-    stream_hdr sh; float step, inv;
+static int step_ok(float step) { return step >= 0x1p-100f && step <= 0x1p101f; }   /* also rejects NaN */
+
+/* The receiver needs the bin width only; the *_step forms take it directly (a stream made by the stochastic
+ * quantizer of section 11 has a width that is not derived from an error bound), the others derive it from eb. */
+int nzo_decode_codes_step(const uint8_t* s, size_t bytes, size_t n, float step, int32_t* q, uint32_t* rawbits,
+                          uint8_t* frame_raw, nzo_result* res) {
+    stream_hdr sh;
     nzo_result dummy;
     if (!res) res = &dummy;
     memset(res, 0, sizeof *res);
-    if (n == 0 || !s) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
-    if (nzo_step_constants(eb, &step, &inv)) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
+    if (n == 0 || !s || !step_ok(step)) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
     int rc = parse_stream(s, bytes, &sh);
     if (rc) { res->status = (uint32_t)rc; return rc; }
     if (sh.n != n || sh.step_bits != f32_bits(step)) { res->status = NZO_ERR_MISMATCH; return NZO_ERR_MISMATCH; }
@@ -680,15 +683,22 @@ int nzo_decode_codes(const uint8_t* s, size_t bytes, size_t n, float eb, int32_t
     return worst;
 }
 
+int nzo_decode_codes(const uint8_t* s, size_t bytes, size_t n, float eb, int32_t* q, uint32_t* rawbits,
+                     uint8_t* frame_raw, nzo_result* res) {
+    float step, inv;
+    if (nzo_step_constants(eb, &step, &inv)) { if (res) { memset(res, 0, sizeof *res); res->status = NZO_ERR_INVALID; } return NZO_ERR_INVALID; }
+    return nzo_decode_codes_step(s, bytes, n, step, q, rawbits, frame_raw, res);
+}
+
 /* Decompress: decode then xhat = fl32(float(q)*step); RAW frames pass through.
  * A stream-level error (bad stream header, n or step mismatch) writes nothing;
  * a rejected frame is zero-filled and reported in the status. */
-int nzo_decompress(const uint8_t* s, size_t bytes, float* out, size_t n, float eb, nzo_result* res) {
-    float step, inv; stream_hdr sh;
+int nzo_decompress_step(const uint8_t* s, size_t bytes, float* out, size_t n, float step, nzo_result* res) {
+    stream_hdr sh;
     nzo_result dummy;
     if (!res) res = &dummy;
     memset(res, 0, sizeof *res);
-    if (n == 0 || !out || !s || nzo_step_constants(eb, &step, &inv)) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
+    if (n == 0 || !out || !s || !step_ok(step)) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
     int rc = parse_stream(s, bytes, &sh);
     if (rc) { res->status = (uint32_t)rc; return rc; }
     if (sh.n != n || sh.step_bits != f32_bits(step)) { res->status = NZO_ERR_MISMATCH; return NZO_ERR_MISMATCH; }
@@ -696,7 +706,7 @@ int nzo_decompress(const uint8_t* s, size_t bytes, float* out, size_t n, float e
     uint32_t* rb = (uint32_t*)malloc(4ull * n);
     uint8_t* fr = (uint8_t*)calloc(sh.n_frames, 1);
     if (!q || !rb || !fr) { free(q); free(rb); free(fr); return NZO_ERR_INVALID; }
-    rc = nzo_decode_codes(s, bytes, n, eb, q, rb, fr, res);
+    rc = nzo_decode_codes_step(s, bytes, n, step, q, rb, fr, res);
     for (uint32_t k = 0; k < sh.n_frames; k++) {
         uint64_t i0 = (uint64_t)k * sh.chunk;
         uint32_t nf = (uint32_t)((n - i0 < sh.chunk) ? (n - i0) : sh.chunk);
@@ -708,6 +718,12 @@ int nzo_decompress(const uint8_t* s, size_t bytes, float* out, size_t n, float e
     }
     free(q); free(rb); free(fr);
     return rc;
+}
+
+int nzo_decompress(const uint8_t* s, size_t bytes, float* out, size_t n, float eb, nzo_result* res) {
+    float step, inv;
+    if (nzo_step_constants(eb, &step, &inv)) { if (res) { memset(res, 0, sizeof *res); res->status = NZO_ERR_INVALID; } return NZO_ERR_INVALID; }
+    return nzo_decompress_step(s, bytes, out, n, step, res);
 }
 
 /* ------------------------------------------------------------------ */
@@ -755,14 +771,14 @@ static int reduce_src(void* vctx, uint32_t k, uint64_t i0, uint32_t nf, int32_t*
     return 0;
 }
 
-int nzo_reduce_frames(const uint8_t* a, size_t a_bytes, const uint8_t* b, size_t b_bytes, uint8_t* out, size_t cap,
-                      size_t n, float eb, const nzo_opts* opts, nzo_result* res) {
-    nzo_opts o; stream_hdr ha, hb; float step, inv;
+int nzo_reduce_frames_step(const uint8_t* a, size_t a_bytes, const uint8_t* b, size_t b_bytes, uint8_t* out, size_t cap,
+                           size_t n, float step, const nzo_opts* opts, nzo_result* res) {
+    nzo_opts o; stream_hdr ha, hb;
     nzo_result dummy;
     if (!res) res = &dummy;
     memset(res, 0, sizeof *res);
     if (n == 0 || !a || !b || !out) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
-    if (resolve_opts(opts, &o) || nzo_step_constants(eb, &step, &inv)) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
+    if (resolve_opts(opts, &o) || !step_ok(step)) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
     int rc = parse_stream(a, a_bytes, &ha);
     if (!rc) rc = parse_stream(b, b_bytes, &hb);
     if (rc) { res->status = (uint32_t)rc; return rc; }
@@ -773,8 +789,8 @@ int nzo_reduce_frames(const uint8_t* a, size_t a_bytes, const uint8_t* b, size_t
     uint32_t* ra = (uint32_t*)malloc(4ull * n); uint32_t* rb = (uint32_t*)malloc(4ull * n);
     uint8_t* fa = (uint8_t*)calloc(ha.n_frames, 1); uint8_t* fb = (uint8_t*)calloc(ha.n_frames, 1);
     if (!qa || !qb || !ra || !rb || !fa || !fb) rc = NZO_ERR_INVALID;
-    if (!rc) rc = nzo_decode_codes(a, a_bytes, n, eb, qa, ra, fa, NULL);
-    if (!rc) rc = nzo_decode_codes(b, b_bytes, n, eb, qb, rb, fb, NULL);
+    if (!rc) rc = nzo_decode_codes_step(a, a_bytes, n, step, qa, ra, fa, NULL);
+    if (!rc) rc = nzo_decode_codes_step(b, b_bytes, n, step, qb, rb, fb, NULL);
     if (!rc) {
         reduce_ctx c = { qa, qb, ra, rb, fa, fb, step };
         rc = emit_stream(reduce_src, &c, n, &o, f32_bits(step), out, cap, res);
@@ -783,6 +799,13 @@ int nzo_reduce_frames(const uint8_t* a, size_t a_bytes, const uint8_t* b, size_t
     }
     free(qa); free(qb); free(ra); free(rb); free(fa); free(fb);
     return rc;
+}
+
+int nzo_reduce_frames(const uint8_t* a, size_t a_bytes, const uint8_t* b, size_t b_bytes, uint8_t* out, size_t cap,
+                      size_t n, float eb, const nzo_opts* opts, nzo_result* res) {
+    float step, inv;
+    if (nzo_step_constants(eb, &step, &inv)) { if (res) { memset(res, 0, sizeof *res); res->status = NZO_ERR_INVALID; } return NZO_ERR_INVALID; }
+    return nzo_reduce_frames_step(a, a_bytes, b, b_bytes, out, cap, n, step, opts, res);
 }
 
 /* ------------------------------------------------------------------ */
@@ -1104,4 +1127,105 @@ int nzo_compress_rea(const float* x, size_t n, float eb, const nzo_opts* opts, c
     write_stream_header(out, n, &o, nfr, step_bits, end);
     res->span_bytes = end; res->wire_bytes = wire; res->status = NZO_OK;
     return NZO_OK;
+}
+
+
+/* ------------------------------------------------------------------ */
+/* 11. stochastic interface quantizer (QSGD, Sec. II-B "Quantization",  */
+/*     Sec. IV-B): randomized rounding to a neighbouring level with      */
+/*     probability proportional to the distance, unbiased                */
+/* ------------------------------------------------------------------ */
+
+/*
+ * The random draw of element i under a 32-bit seed: a counter-based generator, so that every implementation
+ * draws the same bits whatever order it visits the elements in.  Format v1: the 32-bit finalizer of the
+ * public-domain MurmurHash3 (two multiply / xor-shift rounds), keyed with the seed and the high half of the
+ * index; the top 24 bits are the draw.
+ */
+static uint32_t fmix32(uint32_t h) {
+    h ^= h >> 16; h *= 0x85EBCA6Bu;
+    h ^= h >> 13; h *= 0xC2B2AE35u;
+    h ^= h >> 16;
+    return h;
+}
+uint32_t nzo_sr_draw(uint32_t seed, uint64_t i) {
+    uint32_t key = fmix32(seed + 0x9E3779B9u * (uint32_t)(i >> 32));
+    return fmix32((uint32_t)i ^ key) >> 8;
+}
+
+/*
+ * Quantize one value with bin width step (inv_step = fl32(1/step)) and a 24-bit draw: a = fl32(|x|*inv_step),
+ * unquantizable unless a <= 32767 (catches NaN); l = floor(a), f = a - l (exact in fp32); the level is l + 1
+ * with probability f -- draw * 2^-24 < f -- else l (QSGD: probability proportional to the distance from the
+ * lower level, so E[q] = a); q takes the sign of x.  Belt and braces as for the deterministic quantizer:
+ * unquantizable unless fl32(|x - fl32(q*step)|) <= fl32(step * (1 + 2^-6)).
+ */
+int nzo_sr_quantize_one(float x, float step, float inv_step, uint32_t draw24, int32_t* q) {
+    volatile float a = fabsf(x) * inv_step;
+    if (!(a <= 32767.0f)) return 0;
+    float l = floorf(a);
+    volatile float f = a - l;
+    volatile float u = (float)draw24 * 0x1p-24f;
+    int32_t qi = (int32_t)l + (u < f ? 1 : 0);
+    if (x < 0.0f) qi = -qi;
+    volatile float xh = (float)qi * step;
+    volatile float d = x - xh;
+    volatile float lim = step * 1.015625f;
+    if (!(fabsf(d) <= lim)) return 0;
+    *q = qi;
+    return 1;
+}
+
+/* Bin width of QSGD with `levels` levels per sign: step = ||x||_2 / levels (sum of squares in float64, in index
+ * order), at least 2^-100 (an all-zero message quantizes to zeros under any width). */
+int nzo_qsgd_step(const float* x, size_t n, uint32_t levels, float* step) {
+    if (!x || n == 0 || levels == 0 || levels > (uint32_t)NZO_QMAX) return NZO_ERR_INVALID;
+    double ssq = 0.0;
+    for (size_t i = 0; i < n; i++) ssq += (double)x[i] * (double)x[i];
+    double st = sqrt(ssq) / (double)levels;
+    if (!(st <= 0x1p100)) return NZO_ERR_INVALID;                /* non-finite input */
+    if (st < 0x1p-100) st = 0x1p-100;
+    *step = (float)st;
+    return NZO_OK;
+}
+
+int nzo_sr_quantize(const float* x, size_t n, float step, uint32_t seed, uint64_t first_index, int32_t* q, uint8_t* ok) {
+    if (!step_ok(step)) return NZO_ERR_INVALID;
+    volatile float inv = 1.0f / step;
+    for (size_t i = 0; i < n; i++) {
+        int32_t v = 0;
+        ok[i] = (uint8_t)nzo_sr_quantize_one(x[i], step, inv, nzo_sr_draw(seed, first_index + i), &v);
+        q[i] = ok[i] ? v : 0;
+    }
+    return NZO_OK;
+}
+
+typedef struct { const float* x; float step, inv; uint32_t seed; } sr_ctx;
+
+static int sr_src(void* vctx, uint32_t k, uint64_t i0, uint32_t nf, int32_t* q, uint32_t* rb) {
+    (void)k;
+    sr_ctx* c = (sr_ctx*)vctx;
+    int all_ok = 1;
+    for (uint32_t i = 0; i < nf; i++) {
+        float x = c->x[i0 + i];
+        rb[i] = f32_bits(x);
+        int32_t v = 0;
+        if (!nzo_sr_quantize_one(x, c->step, c->inv, nzo_sr_draw(c->seed, i0 + i), &v)) all_ok = 0;
+        q[i] = v;
+    }
+    return all_ok;
+}
+
+/* Compress with the stochastic quantizer in the place of the deterministic one: same statistics, selector and
+ * frames; the stream records step, and element i of the message uses draw (seed, i). */
+int nzo_compress_sr(const float* x, size_t n, float step, uint32_t seed, const nzo_opts* opts, uint8_t* out, size_t cap,
+                    nzo_result* res) {
+    nzo_opts o; sr_ctx c;
+    nzo_result dummy;
+    if (!res) res = &dummy;
+    memset(res, 0, sizeof *res);
+    if (n == 0 || !x || !out || !step_ok(step) || resolve_opts(opts, &o)) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
+    volatile float inv = 1.0f / step;
+    c.x = x; c.step = step; c.inv = inv; c.seed = seed;
+    return emit_stream(sr_src, &c, n, &o, f32_bits(step), out, cap, res);
 }

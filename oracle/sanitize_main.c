@@ -48,6 +48,18 @@ static int run_case(size_t n, uint32_t chunk, uint32_t K, uint32_t seg, int forc
         if (rcap > 16 && nzo_compress_rea(y, n, eb, &od, &ro, &ctx, sr, rcap - 16, &rr, NULL) != NZO_ERR_CAPACITY) return 15;
         free(sr);
     }
+    /* stochastic quantizer: compress, decode with the recorded width, reduce */
+    {
+        float st; nzo_result r1, r2;
+        if (nzo_qsgd_step(y, n, 64, &st) && !poison) return 16;
+        if (poison) st = 1e-3f;
+        size_t scap = nzo_compress_bound(n, &od);
+        uint8_t* s1 = (uint8_t*)malloc(scap); uint8_t* s2 = (uint8_t*)malloc(scap); uint8_t* s3 = (uint8_t*)malloc(scap);
+        if (nzo_compress_sr(y, n, st, 7u, &od, s1, scap, &r1) || nzo_compress_sr(x, n, st, 8u, &od, s2, scap, &r2)) return 17;
+        if (nzo_decompress_step(s1, r1.bytes, z, n, st, &rc)) return 18;
+        if (nzo_reduce_frames_step(s1, r1.bytes, s2, r2.bytes, s3, scap, n, st, &od, &rc)) return 19;
+        free(s1); free(s2); free(s3);
+    }
     /* too small an output: capacity error, nothing written past cap */
     uint8_t* small = (uint8_t*)malloc(ra.bytes > 16 ? ra.bytes - 16 : 1);
     if (nzo_compress(x, n, eb, &o, small, ra.bytes > 16 ? ra.bytes - 16 : 1, &rc) != NZO_ERR_CAPACITY) return 7;
