@@ -150,6 +150,28 @@ nz_status nz_compress_rea(const float* d_in, size_t n, float eb, const void* d_c
                           void* stream);
 
 /*
+ * Stochastic interface quantizer (QSGD, Sec. II-B "Quantization", Sec. IV-B): nz_compress_sr is nz_compress with
+ * randomized rounding in the place of round-to-nearest.  Values are rounded to multiples of `step` (finite,
+ * 2^-100 <= step <= 2^101): with a = |x| / step the level is floor(a) + 1 with probability a - floor(a), else
+ * floor(a), so E[xhat] = x; |x - xhat| <= step * (1 + 2^-6); a value with a > 32767 or NaN makes its frame RAW.
+ * Element i of the message draws from a counter-based generator keyed by (seed, i) -- the 32-bit finalizer of
+ * MurmurHash3, top 24 bits -- so the result does not depend on how the work is scheduled.  Statistics, selector
+ * and frames are those of nz_compress; the stream records `step`, and its receivers are the *_step forms below
+ * (nz_decompress / nz_reduce_frames derive the width from an error bound, which such a stream does not have).
+ * nz_qsgd_step writes QSGD's width for `levels` levels per sign, ||x||_2 / levels (at least 2^-100; NaN if the
+ * message is not finite), to the device float *d_step; d_ws: at least 8192 bytes of device scratch.  Ranks that
+ * reduce their streams must agree on one width (e.g. the largest).
+ */
+nz_status nz_qsgd_step(const float* d_in, size_t n, uint32_t levels, float* d_step, void* d_ws, size_t ws_bytes, void* stream);
+nz_status nz_compress_sr(const float* d_in, size_t n, float step, uint32_t seed, void* d_out, size_t out_cap, nz_result* d_res,
+                         const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream);
+nz_status nz_decompress_step(const void* d_stream, size_t stream_bytes, float* d_out, size_t n, float step,
+                             nz_result* d_res, const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream);
+nz_status nz_reduce_frames_step(const void* d_a, size_t a_bytes, const void* d_b, size_t b_bytes, void* d_out,
+                                size_t out_cap, size_t n, float step, nz_result* d_res, const nz_opts* opts,
+                                void* d_ws, size_t ws_bytes, void* stream);
+
+/*
  * nz_compress for callers that cannot allocate or hand over scratch memory: code under HIP graph capture,
  * tight serving loops, harnesses that forbid hipMalloc.  Same result, byte for byte, as nz_compress; the
  * workspace is an array that lives inside the library on every GPU (nz_static_scratch_bytes() bytes, 8 MiB,

@@ -55,6 +55,14 @@ def lib():
         L.nz_static_scratch_bytes.restype = sz
         L.nz_compress_static.argtypes = [vp, sz, f32, vp, sz, vp, po, vp]
         L.nz_compress_static.restype = C.c_int
+        L.nz_qsgd_step.argtypes = [vp, sz, C.c_uint32, vp, vp, sz, vp]
+        L.nz_qsgd_step.restype = C.c_int
+        L.nz_compress_sr.argtypes = [vp, sz, f32, C.c_uint32, vp, sz, vp, po, vp, sz, vp]
+        L.nz_compress_sr.restype = C.c_int
+        L.nz_decompress_step.argtypes = [vp, sz, vp, sz, f32, vp, po, vp, sz, vp]
+        L.nz_decompress_step.restype = C.c_int
+        L.nz_reduce_frames_step.argtypes = [vp, sz, vp, sz, vp, sz, sz, f32, vp, po, vp, sz, vp]
+        L.nz_reduce_frames_step.restype = C.c_int
         L.nz_context_bytes.restype = sz
         L.nz_context_build.argtypes = [vp, sz, f32, po, vp, vp, sz, vp]
         L.nz_context_build.restype = C.c_int
@@ -110,6 +118,26 @@ def nz_compress_static(d_in, n, eb, d_out, out_cap, d_res, opts, stream=None):
     """nz_compress with the library's resident scratch array as workspace (allocates nothing)."""
     return int(lib().nz_compress_static(d_in.data_ptr(), n, C.c_float(eb), d_out.data_ptr(), out_cap, d_res.data_ptr(),
                                         _po(opts), _stream(stream)))
+
+
+def nz_qsgd_step(d_in, n, levels, d_step, d_ws, ws_bytes, stream=None):
+    return int(lib().nz_qsgd_step(d_in.data_ptr(), n, levels, d_step.data_ptr(), d_ws.data_ptr(), ws_bytes, _stream(stream)))
+
+
+def nz_compress_sr(d_in, n, step, seed, d_out, out_cap, d_res, opts, d_ws, ws_bytes, stream=None):
+    return int(lib().nz_compress_sr(d_in.data_ptr(), n, C.c_float(step), seed, d_out.data_ptr(), out_cap, d_res.data_ptr(),
+                                    _po(opts), d_ws.data_ptr(), ws_bytes, _stream(stream)))
+
+
+def nz_decompress_step(d_stream, stream_bytes, d_out, n, step, d_res, opts, d_ws, ws_bytes, stream=None):
+    return int(lib().nz_decompress_step(d_stream.data_ptr(), stream_bytes, d_out.data_ptr(), n, C.c_float(step),
+                                        d_res.data_ptr(), _po(opts), d_ws.data_ptr(), ws_bytes, _stream(stream)))
+
+
+def nz_reduce_frames_step(d_a, a_bytes, d_b, b_bytes, d_out, out_cap, n, step, d_res, opts, d_ws, ws_bytes, stream=None):
+    return int(lib().nz_reduce_frames_step(d_a.data_ptr(), a_bytes, d_b.data_ptr(), b_bytes, d_out.data_ptr(), out_cap, n,
+                                           C.c_float(step), d_res.data_ptr(), _po(opts), d_ws.data_ptr(), ws_bytes,
+                                           _stream(stream)))
 
 
 def nz_context_bytes():

@@ -122,11 +122,20 @@ size_t nz_reduce_workspace_bytes(size_t n, const nz_opts* opts) {
     return ws_layout(n, o.chunk, kDecBlock, true).total;
 }
 
-nz_status nz_compress(const float* d_in, size_t n, float eb, void* d_out, size_t out_cap, nz_result* d_res,
-                      const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream) {
-    Opts o; float step, inv;
+// Bin width given directly (stochastic quantizer; receivers of its streams): same range as step_constants produces.
+static bool step_given(float step, float& inv) {
+    if (!(step >= 0x1p-100f && step <= 0x1p101f)) return false;
+    volatile float r = 1.0f / step;
+    inv = r;
+    return true;
+}
+
+static nz_status compress_impl(const float* d_in, size_t n, float eb, float step, float inv, bool stochastic, uint32_t seed,
+                               void* d_out, size_t out_cap, nz_result* d_res, const nz_opts* opts, void* d_ws,
+                               size_t ws_bytes, void* stream) {
+    Opts o;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    if (!d_in || !d_out || !d_res || !d_ws || !resolve(opts, o) || !geometry_ok(n, o) || !step_constants(eb, step, inv))
+    if (!d_in || !d_out || !d_res || !d_ws || !resolve(opts, o) || !geometry_ok(n, o))
         return NZ_ERR_INVALID;
     if (!aligned16(d_in) || !aligned16(d_out) || !aligned16(d_ws) || !aligned16(d_res)) return NZ_ERR_INVALID;
     const WsLayout L = ws_layout(n, o.chunk, kStatBlock, false);
@@ -141,15 +150,38 @@ nz_status nz_compress(const float* d_in, size_t n, float eb, void* d_out, size_t
     A.in = d_in; A.n = n; A.chunk = o.chunk; A.n_frames = nfr; A.K = o.K;
     A.stat_block = kStatBlock; A.sbpf = (o.chunk + kStatBlock - 1) / kStatBlock;
     A.force_codec = o.force; A.min_gain_permil = o.gain; A.huff_min_bytes = o.huff_min;
-    A.eb = eb; A.step = step; A.inv_step = inv; A.step_bits = bits_of(step);
+    A.eb = eb; A.step = step; A.inv_step = inv; A.step_bits = bits_of(step); A.seed = seed;
     A.out = reinterpret_cast<uint8_t*>(d_out); A.out_cap = out_cap; A.ws = ws; A.L = L; A.res = d_res;
+    A.rea_ctx = nullptr; A.rea_tmp = nullptr; A.rea_gbits = nullptr; A.rea_fail = nullptr;
     trace_reset(); trace_mark(st);
-    if (launch_stats(A, st) != hipSuccess) return NZ_ERR_HIP;     // also clears the control block and the result record
+    if (launch_stats(A, stochastic, st) != hipSuccess) return NZ_ERR_HIP;     // also clears the control block and the result record
     trace_mark(st);
     if (launch_codebook(A, st) != hipSuccess) return NZ_ERR_HIP;
     trace_mark(st);
-    if (launch_encode(A, false, st) != hipSuccess) return NZ_ERR_HIP;
+    if (launch_encode(A, false, stochastic, st) != hipSuccess) return NZ_ERR_HIP;
     trace_mark(st);
+    return NZ_OK;
+}
+
+nz_status nz_compress(const float* d_in, size_t n, float eb, void* d_out, size_t out_cap, nz_result* d_res,
+                      const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream) {
+    float step, inv;
+    if (!step_constants(eb, step, inv)) return NZ_ERR_INVALID;
+    return compress_impl(d_in, n, eb, step, inv, false, 0u, d_out, out_cap, d_res, opts, d_ws, ws_bytes, stream);
+}
+
+nz_status nz_compress_sr(const float* d_in, size_t n, float step, uint32_t seed, void* d_out, size_t out_cap, nz_result* d_res,
+                         const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream) {
+    float inv;
+    if (!step_given(step, inv)) return NZ_ERR_INVALID;
+    return compress_impl(d_in, n, 0.0f, step, inv, true, seed, d_out, out_cap, d_res, opts, d_ws, ws_bytes, stream);
+}
+
+nz_status nz_qsgd_step(const float* d_in, size_t n, uint32_t levels, float* d_step, void* d_ws, size_t ws_bytes, void* stream) {
+    if (!d_in || !d_step || !d_ws || n == 0 || levels == 0 || levels > (uint32_t)kQMax) return NZ_ERR_INVALID;
+    if (!aligned16(d_in) || !aligned16(d_ws) || (reinterpret_cast<uintptr_t>(d_step) & 3u) || ws_bytes < 8192) return NZ_ERR_INVALID;
+    if (launch_qsgd_step(d_in, n, levels, d_step, reinterpret_cast<double*>(d_ws), reinterpret_cast<hipStream_t>(stream)) != hipSuccess)
+        return NZ_ERR_HIP;
     return NZ_OK;
 }
 
@@ -220,11 +252,11 @@ nz_status nz_compress_rea(const float* d_in, size_t n, float eb, const void* d_c
     return NZ_OK;
 }
 
-nz_status nz_decompress(const void* d_stream, size_t stream_bytes, float* d_out, size_t n, float eb,
-                        nz_result* d_res, const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream) {
-    Opts o; float step, inv;
+static nz_status decompress_impl(const void* d_stream, size_t stream_bytes, float* d_out, size_t n, float step,
+                                 nz_result* d_res, const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream) {
+    Opts o;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    if (!d_stream || !d_out || !d_res || !d_ws || !resolve(opts, o) || !geometry_ok(n, o) || !step_constants(eb, step, inv))
+    if (!d_stream || !d_out || !d_res || !d_ws || !resolve(opts, o) || !geometry_ok(n, o))
         return NZ_ERR_INVALID;
     if (!aligned16(d_stream) || !aligned16(d_out) || !aligned16(d_res) || !aligned16(d_ws)) return NZ_ERR_INVALID;
     const WsLayout L = ws_layout(n, o.chunk, kStatBlock, false);     // one verdict word per decode workgroup
@@ -232,7 +264,7 @@ nz_status nz_decompress(const void* d_stream, size_t stream_bytes, float* d_out,
     const uint32_t nfr = (uint32_t)((n + o.chunk - 1) / o.chunk);
     DecodeArgs A;
     A.a = reinterpret_cast<const uint8_t*>(d_stream); A.a_bytes = stream_bytes; A.b = nullptr; A.b_bytes = 0;
-    A.out = d_out; A.local = nullptr; A.eb = eb; A.inv_step = 0.0f; A.n = n; A.chunk = o.chunk; A.n_frames = nfr; A.K = o.K;
+    A.out = d_out; A.local = nullptr; A.eb = 0.0f; A.inv_step = 0.0f; A.n = n; A.chunk = o.chunk; A.n_frames = nfr; A.K = o.K;
     A.dbpf = (o.chunk + kDecBlock - 1) / kDecBlock;
     A.step = step; A.step_bits = bits_of(step); A.ws = reinterpret_cast<uint8_t*>(d_ws); A.L = L; A.res = d_res;
     static_assert(kDecBlock == kStatBlock, "the verdict words reuse the per-statistics-block slots of the workspace");
@@ -244,15 +276,28 @@ nz_status nz_decompress(const void* d_stream, size_t stream_bytes, float* d_out,
     return NZ_OK;
 }
 
+nz_status nz_decompress(const void* d_stream, size_t stream_bytes, float* d_out, size_t n, float eb,
+                        nz_result* d_res, const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream) {
+    float step, inv;
+    if (!step_constants(eb, step, inv)) return NZ_ERR_INVALID;
+    return decompress_impl(d_stream, stream_bytes, d_out, n, step, d_res, opts, d_ws, ws_bytes, stream);
+}
+
+nz_status nz_decompress_step(const void* d_stream, size_t stream_bytes, float* d_out, size_t n, float step,
+                             nz_result* d_res, const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream) {
+    float inv;
+    if (!step_given(step, inv)) return NZ_ERR_INVALID;
+    return decompress_impl(d_stream, stream_bytes, d_out, n, step, d_res, opts, d_ws, ws_bytes, stream);
+}
+
 // The two reduce entry points differ only in the second operand: a stream (d_b) or the rank's own fp32 data (d_local).
 static nz_status reduce_impl(const void* d_a, size_t a_bytes, const void* d_b, size_t b_bytes, const float* d_local,
-                             void* d_out, size_t out_cap, size_t n, float eb, nz_result* d_res, const nz_opts* opts,
-                             void* d_ws, size_t ws_bytes, void* stream) {
-    Opts o; float step, inv;
+                             void* d_out, size_t out_cap, size_t n, float eb, float step, float inv, nz_result* d_res,
+                             const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream) {
+    Opts o;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const void* second = d_local ? static_cast<const void*>(d_local) : d_b;
-    if (!d_a || !second || !d_out || !d_res || !d_ws || !resolve(opts, o) || !geometry_ok(n, o) ||
-        !step_constants(eb, step, inv))
+    if (!d_a || !second || !d_out || !d_res || !d_ws || !resolve(opts, o) || !geometry_ok(n, o))
         return NZ_ERR_INVALID;
     if (!aligned16(d_a) || !aligned16(second) || !aligned16(d_out) || !aligned16(d_ws) || !aligned16(d_res))
         return NZ_ERR_INVALID;
@@ -275,8 +320,9 @@ static nz_status reduce_impl(const void* d_a, size_t a_bytes, const void* d_b, s
     A.in = nullptr; A.n = n; A.chunk = o.chunk; A.n_frames = nfr; A.K = o.K;
     A.stat_block = kDecBlock; A.sbpf = D.dbpf;
     A.force_codec = o.force; A.min_gain_permil = o.gain; A.huff_min_bytes = o.huff_min;
-    A.eb = eb; A.step = step; A.inv_step = inv; A.step_bits = bits_of(step);
+    A.eb = eb; A.step = step; A.inv_step = inv; A.step_bits = bits_of(step); A.seed = 0;
     A.out = reinterpret_cast<uint8_t*>(d_out); A.out_cap = out_cap; A.ws = ws; A.L = L; A.res = d_res;
+    A.rea_ctx = nullptr; A.rea_tmp = nullptr; A.rea_gbits = nullptr; A.rea_fail = nullptr;
     trace_reset(); trace_mark(st);
     if (launch_init(ws + L.ctrl, L.zero_end - L.ctrl, d_res, nfr, NZ_OK, st) != hipSuccess) return NZ_ERR_HIP;
     trace_mark(st);
@@ -293,7 +339,7 @@ static nz_status reduce_impl(const void* d_a, size_t a_bytes, const void* d_b, s
     trace_mark(st);
     if (launch_codebook(A, st) != hipSuccess) return NZ_ERR_HIP;
     trace_mark(st);
-    if (launch_encode(A, true, st) != hipSuccess) return NZ_ERR_HIP;
+    if (launch_encode(A, true, false, st) != hipSuccess) return NZ_ERR_HIP;
     trace_mark(st);
     return NZ_OK;
 }
@@ -301,14 +347,25 @@ static nz_status reduce_impl(const void* d_a, size_t a_bytes, const void* d_b, s
 nz_status nz_reduce_frames(const void* d_a, size_t a_bytes, const void* d_b, size_t b_bytes, void* d_out,
                            size_t out_cap, size_t n, float eb, nz_result* d_res, const nz_opts* opts,
                            void* d_ws, size_t ws_bytes, void* stream) {
-    return reduce_impl(d_a, a_bytes, d_b, b_bytes, nullptr, d_out, out_cap, n, eb, d_res, opts, d_ws, ws_bytes, stream);
+    float step, inv;
+    if (!step_constants(eb, step, inv)) return NZ_ERR_INVALID;
+    return reduce_impl(d_a, a_bytes, d_b, b_bytes, nullptr, d_out, out_cap, n, eb, step, inv, d_res, opts, d_ws, ws_bytes, stream);
+}
+
+nz_status nz_reduce_frames_step(const void* d_a, size_t a_bytes, const void* d_b, size_t b_bytes, void* d_out,
+                                size_t out_cap, size_t n, float step, nz_result* d_res, const nz_opts* opts,
+                                void* d_ws, size_t ws_bytes, void* stream) {
+    float inv;
+    if (!step_given(step, inv)) return NZ_ERR_INVALID;
+    return reduce_impl(d_a, a_bytes, d_b, b_bytes, nullptr, d_out, out_cap, n, 0.0f, step, inv, d_res, opts, d_ws, ws_bytes, stream);
 }
 
 nz_status nz_reduce_local(const void* d_in, size_t in_bytes, const float* d_local, void* d_out, size_t out_cap,
                           size_t n, float eb, nz_result* d_res, const nz_opts* opts, void* d_ws, size_t ws_bytes,
                           void* stream) {
-    if (!d_local) return NZ_ERR_INVALID;
-    return reduce_impl(d_in, in_bytes, nullptr, 0, d_local, d_out, out_cap, n, eb, d_res, opts, d_ws, ws_bytes, stream);
+    float step, inv;
+    if (!d_local || !step_constants(eb, step, inv)) return NZ_ERR_INVALID;
+    return reduce_impl(d_in, in_bytes, nullptr, 0, d_local, d_out, out_cap, n, eb, step, inv, d_res, opts, d_ws, ws_bytes, stream);
 }
 
 }  // extern "C"

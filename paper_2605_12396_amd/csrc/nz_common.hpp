@@ -158,6 +158,48 @@ __device__ inline bool quantize1(float x, float eb, float step, float inv_step, 
     q = ok ? (int32_t)r : 0;
     return ok;
 }
+// ---- stochastic interface quantizer (QSGD, Sec. II-B "Quantization", Sec. IV-B) ----
+// Counter-based draw of message element i under a seed: the 32-bit finalizer of MurmurHash3, keyed by the seed and
+// the high half of the index; the top 24 bits are the draw (so every pass over the data sees the same bits).
+__device__ inline uint32_t fmix32(uint32_t h) {
+    h ^= h >> 16; h *= 0x85EBCA6Bu;
+    h ^= h >> 13; h *= 0xC2B2AE35u;
+    h ^= h >> 16;
+    return h;
+}
+__device__ inline uint32_t sr_key(uint32_t seed, uint64_t i) { return fmix32(seed + 0x9E3779B9u * (uint32_t)(i >> 32)); }
+__device__ inline uint32_t sr_draw(uint32_t key, uint32_t i_lo) { return fmix32(i_lo ^ key) >> 8; }
+// Draws for the elements base + off, off < 2^32, of a piece of work: the key changes where the low half of the index
+// wraps, so two keys cover the piece.
+struct SrKeys {
+    uint32_t base_lo, key0, key1;
+    __device__ inline void init(uint32_t seed, uint64_t base) {
+        base_lo = (uint32_t)base; key0 = sr_key(seed, base); key1 = sr_key(seed, base + (1ull << 32));
+    }
+    __device__ inline uint32_t draw(uint32_t off) const {
+        const uint32_t lo = base_lo + off;
+        return sr_draw(lo < base_lo ? key1 : key0, lo);
+    }
+};
+// a = fl(|x|*inv_step), l = floor(a), level l + 1 with probability a - l (draw * 2^-24 < a - l), sign of x;
+// accepted when a <= 32767 and fl(|x - fl(q*step)|) <= fl(step * (1 + 2^-6)).
+__device__ inline bool sr_quantize1(float x, float step, float inv_step, uint32_t draw24, int32_t& q) {
+#pragma clang fp contract(off)
+    const float a = fabsf(x) * inv_step;
+    const bool ok1 = a <= 32767.0f;                       // false for NaN
+    const float l = __builtin_floorf(a);
+    const float f = a - l;
+    const float u = (float)draw24 * 0x1p-24f;
+    float m = l + ((u < f) ? 1.0f : 0.0f);                // exact: integers below 2^24
+    m = (x < 0.0f) ? -m : m;
+    const float xh = m * step;
+    const float d = x - xh;
+    const float lim = step * 1.015625f;
+    const bool ok = ok1 && (fabsf(d) <= lim);
+    q = ok ? (int32_t)m : 0;
+    return ok;
+}
+
 __device__ inline float dequantize1(int32_t q, float step) {
 #pragma clang fp contract(off)
     return (float)q * step;
@@ -215,6 +257,7 @@ struct CompressArgs {
     uint32_t min_gain_permil, huff_min_bytes;
     float eb, step, inv_step;
     uint32_t step_bits;
+    uint32_t seed;            // stochastic quantizer only (kernels built with QM = 1)
     uint8_t* out; uint64_t out_cap;
     uint8_t* ws; WsLayout L;
     void* res;                // nz_result* (device)
@@ -240,9 +283,10 @@ struct DecodeArgs {
 };
 
 hipError_t launch_init(void* zero_base, size_t zero_bytes, void* res, uint32_t n_frames, uint32_t status, hipStream_t st);
-hipError_t launch_stats(const CompressArgs& A, hipStream_t st);
+hipError_t launch_stats(const CompressArgs& A, bool stochastic, hipStream_t st);
 hipError_t launch_codebook(const CompressArgs& A, hipStream_t st);
-hipError_t launch_encode(const CompressArgs& A, bool from_codes, hipStream_t st);
+hipError_t launch_encode(const CompressArgs& A, bool from_codes, bool stochastic, hipStream_t st);
+hipError_t launch_qsgd_step(const float* in, uint64_t n, uint32_t levels, float* step_out, double* partials, hipStream_t st);
 hipError_t launch_decode(const DecodeArgs& A, int pass, hipStream_t st);   // 0 decompress, 1 / 2 reduce passes, 3 ring-step add
 hipError_t launch_fix(const DecodeArgs& A, hipStream_t st);
 hipError_t launch_decode_finish(const DecodeArgs& A, hipStream_t st);

@@ -29,6 +29,7 @@ __global__ void k_init(uint32_t* zero_base, size_t zero_words, ResultRec* res, u
 // quantize, zigzag, lane-replicated LDS histogram, zmax and the "cannot be quantized" flag.
 // The partial histogram goes to the workspace with plain stores; the codebook kernel adds the partials.
 // ------------------------------------------------------------------------------------------------
+template <int QM>     // QM 0: deterministic error-bounded quantizer; 1: stochastic rounding to multiples of step
 __global__ __launch_bounds__(kStatThreads) void k_stats(CompressArgs A) {
     __shared__ uint32_t s_h[8192];
     __shared__ uint32_t s_zmax, s_unq;
@@ -63,12 +64,16 @@ __global__ __launch_bounds__(kStatThreads) void k_stats(CompressArgs A) {
     const float* src = A.in + f0 + b0;
     const bool vec_ok = (((f0 + b0) & 3u) == 0);
     uint32_t zmax = 0, unq = 0;
-    auto count4 = [&](const float (&v)[4], uint32_t m) {
+    SrKeys keys;
+    if (QM == 1) keys.init(A.seed, f0 + b0);
+    auto count4 = [&](const float (&v)[4], uint32_t m, uint32_t off) {   // off: position of the first value in the block
 #pragma unroll
         for (uint32_t j = 0; j < 4; j++) {
             if (j < m) {
                 int32_t q;
-                if (!quantize1(v[j], A.eb, A.step, A.inv_step, q)) unq = 1;
+                const bool okq = (QM == 1) ? sr_quantize1(v[j], A.step, A.inv_step, keys.draw(off + j), q)
+                                           : quantize1(v[j], A.eb, A.step, A.inv_step, q);
+                if (!okq) unq = 1;
                 const uint32_t z = zigzag(q);
                 zmax = z > zmax ? z : zmax;
                 atomicAdd(&s_h[(bin_of(z, K) << ncs) + copy], 1u);
@@ -88,7 +93,7 @@ __global__ __launch_bounds__(kStatThreads) void k_stats(CompressArgs A) {
 #pragma unroll
             for (uint32_t u = 0; u < kDepth; u++) {
                 const float v[4] = { t[u].x, t[u].y, t[u].z, t[u].w };
-                count4(v, 4);
+                count4(v, 4, ((g + u) * kStatThreads + tid) * 4u);
             }
         }
     } else {
@@ -96,7 +101,7 @@ __global__ __launch_bounds__(kStatThreads) void k_stats(CompressArgs A) {
             float v[4];
             const uint32_t m = (cnt - i < 4) ? (cnt - i) : 4;
             for (uint32_t j = 0; j < 4; j++) v[j] = (j < m) ? src[i + j] : 0.0f;
-            count4(v, m);
+            count4(v, m, i);
         }
     }
     zmax = wave_max(zmax);
@@ -434,8 +439,14 @@ struct EncShared {
 // coded only if the statistics pass found every element quantizable, so the acceptance tests of the quantizer are
 // known to pass and q is simply rne(x * inv_step).  Source 2 (sampled arbitration): nothing has looked at the values
 // before, so the quantizer runs with its tests; a value that fails them counts as code 0 and clears *ok.
-template <int SRC>
-__device__ inline uint32_t enc_zz(uint32_t w, const CompressArgs& A, bool* ok = nullptr) {
+// QM = 1 (source 0 only): the stochastic quantizer, with the draw of the element (its tests are known to pass too).
+template <int SRC, int QM = 0>
+__device__ inline uint32_t enc_zz(uint32_t w, const CompressArgs& A, bool* ok = nullptr, uint32_t draw24 = 0) {
+    if (SRC == 0 && QM == 1) {
+        int32_t q;
+        sr_quantize1(__uint_as_float(w), A.step, A.inv_step, draw24, q);
+        return zigzag(q);
+    }
     if (SRC == 0) {
 #pragma clang fp contract(off)
         const float u = __uint_as_float(w) * A.inv_step;
@@ -498,9 +509,9 @@ __device__ inline void enc_load(const EncGroup& G, uint32_t sb, uint32_t (&raw)[
     }
 }
 
-template <int SRC>
+template <int SRC, int QM>
 __device__ inline void enc_raw_fixed(const CompressArgs& A, const EncGroup& G, const FrameMeta& M, uint8_t* fr, uint32_t* stage,
-                                     uint32_t& bad) {
+                                     uint32_t& bad, const SrKeys& keys) {
     const uint32_t tid = threadIdx.x;
     if (M.codec == CODEC_RAW) {
         uint32_t* dst = reinterpret_cast<uint32_t*>(fr + kHdrBytes) + G.g0;
@@ -522,7 +533,7 @@ __device__ inline void enc_raw_fixed(const CompressArgs& A, const EncGroup& G, c
             z[j] = 0;
             if (tid * 4 + j < pass_syms) {
                 bool ok = true;
-                z[j] = enc_zz<SRC>(enc_word<SRC>(G, p0 + tid * 4 + j), A, &ok);
+                z[j] = enc_zz<SRC, QM>(enc_word<SRC>(G, p0 + tid * 4 + j), A, &ok, QM ? keys.draw(p0 + tid * 4 + j) : 0u);
                 if (SRC == 2 && w < 32u && (z[j] >> w)) { ok = false; z[j] &= (1u << w) - 1u; }   // wider than the sampled width
                 if (SRC == 2 && !ok) bad = 1;
             }
@@ -546,7 +557,7 @@ __device__ inline void enc_raw_fixed(const CompressArgs& A, const EncGroup& G, c
     }
 }
 
-template <int SRC>
+template <int SRC, int QM = 0>
 __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))) void k_encode(CompressArgs A) {
     __shared__ EncShared S;
     const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
@@ -573,7 +584,9 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
     if (!M.fits) return;
     uint8_t* fr = A.out + M.offset;
     uint32_t bad = 0;                             // SRC 2: a value that cannot be coded as planned fails the frame
-    if (M.codec != CODEC_HUFF) enc_raw_fixed<SRC>(A, G, M, fr, S.stage[0], bad);
+    SrKeys keys;                                  // QM 1: draws of the group's elements, by position in the group
+    if (QM == 1) keys.init(A.seed, f0 + G.g0); else { keys.base_lo = 0; keys.key0 = 0; keys.key1 = 0; }
+    if (M.codec != CODEC_HUFF) enc_raw_fixed<SRC, QM>(A, G, M, fr, S.stage[0], bad, keys);
     else {
         uint32_t raw[kEncIters][4];
         enc_load<SRC>(G, 0, raw);
@@ -659,7 +672,7 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
                     for (uint32_t j = 0; j < 4; j++) {
                         const bool valid = WHOLE || i + j < cnt;
                         bool ok = true;
-                        const uint32_t z = enc_zz<SRC>(raw[it][j], A, &ok);
+                        const uint32_t z = enc_zz<SRC, QM>(raw[it][j], A, &ok, QM ? keys.draw(sb * kEncBlock + i + j) : 0u);
                         if (SRC == 2 && valid && !ok) bad = 1;
                         zs[it][j] = z;
                         const uint64_t b = S.book[z < kesc ? z : kesc];
@@ -727,7 +740,8 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
                     for (uint32_t q = 0; q < kEncIters; q++) if (q == it) { lnit = ln[q]; pbits = pbase[q + 1] - pbase[q]; }
                     uint32_t pos = rel + lnit;
                     for (uint32_t j = 0; j < 4; j++)
-                        if (i + j < cnt) put_symbol(X, enc_zz<SRC>(enc_word<SRC>(G, sb * kEncBlock + i + j), A), pos);
+                        if (i + j < cnt) put_symbol(X, enc_zz<SRC, QM>(enc_word<SRC>(G, sb * kEncBlock + i + j), A, nullptr,
+                                                                       QM ? keys.draw(sb * kEncBlock + i + j) : 0u), pos);
                     __syncthreads();
                     flush(X, X, rel + pbits);
                     __syncthreads();
@@ -1046,7 +1060,7 @@ hipError_t launch_rea(const ReaArgs& A, hipStream_t st, void (*mark)(hipStream_t
     C.out = A.out; C.out_cap = 0; C.ws = A.ws; C.L = WsLayout(); C.L.meta = A.L.meta; C.res = A.res;
     C.rea_ctx = A.ctx; C.rea_tmp = A.tmp_base; C.rea_gbits = reinterpret_cast<uint32_t*>(A.ws + A.L.gbits);
     C.rea_fail = reinterpret_cast<uint32_t*>(A.ws + A.L.fail);
-    hipLaunchKernelGGL(k_encode<2>, dim3(A.n_frames * A.gpf), dim3(kEncThreads), 0, st, C);
+    hipLaunchKernelGGL((k_encode<2, 0>), dim3(A.n_frames * A.gpf), dim3(kEncThreads), 0, st, C);
     mark(st);
     hipLaunchKernelGGL(k_rea_finish, dim3(A.n_frames * A.gpf), dim3(256), 0, st, A);
     mark(st);
@@ -1065,8 +1079,40 @@ hipError_t launch_init(void* zero_base, size_t zero_bytes, void* res, uint32_t n
     return hipGetLastError();
 }
 
-hipError_t launch_stats(const CompressArgs& A, hipStream_t st) {
-    hipLaunchKernelGGL(k_stats, dim3(A.n_frames * A.sbpf), dim3(kStatThreads), 0, st, A);
+hipError_t launch_stats(const CompressArgs& A, bool stochastic, hipStream_t st) {
+    if (stochastic) hipLaunchKernelGGL(k_stats<1>, dim3(A.n_frames * A.sbpf), dim3(kStatThreads), 0, st, A);
+    else hipLaunchKernelGGL(k_stats<0>, dim3(A.n_frames * A.sbpf), dim3(kStatThreads), 0, st, A);
+    return hipGetLastError();
+}
+
+// Bin width of QSGD with `levels` levels per sign: ||x||_2 / levels.  Squares are summed in float64 by a fixed grid in
+// a fixed order (per-thread strided partial sums, wave and workgroup trees, then the workgroups' partials in index
+// order), so the result does not depend on scheduling.
+constexpr uint32_t kSsqBlocks = 1024;
+__global__ __launch_bounds__(256) void k_ssq(const float* x, uint64_t n, double* partials) {
+    __shared__ double s_w[4];
+    double acc = 0.0;
+    for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (uint64_t)kSsqBlocks * 256) {
+        const double v = (double)x[i];
+        acc += v * v;
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, 64);
+    if (lane_id() == 0) s_w[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) partials[blockIdx.x] = (s_w[0] + s_w[1]) + (s_w[2] + s_w[3]);
+}
+__global__ void k_qsgd_step(const double* partials, uint32_t levels, float* step_out) {
+    double ssq = 0.0;
+    for (uint32_t b = 0; b < kSsqBlocks; b++) ssq += partials[b];
+    double st = sqrt(ssq) / (double)levels;
+    if (!(st <= 0x1p100)) st = __longlong_as_double(0x7FF8000000000000ll);     // non-finite input: the caller sees NaN
+    else if (st < 0x1p-100) st = 0x1p-100;
+    *step_out = (float)st;
+}
+hipError_t launch_qsgd_step(const float* in, uint64_t n, uint32_t levels, float* step_out, double* partials, hipStream_t st) {
+    hipLaunchKernelGGL(k_ssq, dim3(kSsqBlocks), dim3(256), 0, st, in, n, partials);
+    hipLaunchKernelGGL(k_qsgd_step, dim3(1), dim3(1), 0, st, partials, levels, step_out);
     return hipGetLastError();
 }
 
@@ -1075,9 +1121,11 @@ hipError_t launch_codebook(const CompressArgs& A, hipStream_t st) {
     return hipGetLastError();
 }
 
-hipError_t launch_encode(const CompressArgs& A, bool from_codes, hipStream_t st) {
-    if (from_codes) hipLaunchKernelGGL(k_encode<1>, dim3(A.n_frames * ((A.chunk + kEncGroup - 1) / kEncGroup)), dim3(kEncThreads), 0, st, A);
-    else hipLaunchKernelGGL(k_encode<0>, dim3(A.n_frames * ((A.chunk + kEncGroup - 1) / kEncGroup)), dim3(kEncThreads), 0, st, A);
+hipError_t launch_encode(const CompressArgs& A, bool from_codes, bool stochastic, hipStream_t st) {
+    const dim3 grid(A.n_frames * ((A.chunk + kEncGroup - 1) / kEncGroup));
+    if (from_codes) hipLaunchKernelGGL((k_encode<1, 0>), grid, dim3(kEncThreads), 0, st, A);
+    else if (stochastic) hipLaunchKernelGGL((k_encode<0, 1>), grid, dim3(kEncThreads), 0, st, A);
+    else hipLaunchKernelGGL((k_encode<0, 0>), grid, dim3(kEncThreads), 0, st, A);
     return hipGetLastError();
 }
 
