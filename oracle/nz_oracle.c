@@ -60,6 +60,8 @@ typedef struct {
     int32_t  force_codec;     /* -1 auto, 0/1/2 pin a codec (Sec. V-B pins codecs)    */
     uint32_t min_gain_permil; /* minimum-gain threshold of Algorithm 1, default 0     */
     uint32_t huff_min_bytes;  /* Huffman size threshold T_huff of Algorithm 1         */
+    uint32_t predictor;       /* 0 none; 1 delta on the codes (section 12, an extension) */
+    uint32_t reserved;        /* 0                                                    */
 } nzo_opts;
 
 typedef struct {
@@ -106,7 +108,7 @@ static int is_pow2(uint32_t v) { return v && !(v & (v - 1)); }
 
 /* Fill in defaults and check ranges.  Returns NZO_OK or NZO_ERR_INVALID. */
 static int resolve_opts(const nzo_opts* in, nzo_opts* o) {
-    nzo_opts d = { 0, 0, 0, -1, 0, 0 };
+    nzo_opts d = { 0, 0, 0, -1, 0, 0, 0, 0 };
     if (in) d = *in;
     if (d.chunk_elems == 0) d.chunk_elems = 262144u;
     if (d.seg_syms == 0) d.seg_syms = 256u;
@@ -116,6 +118,7 @@ static int resolve_opts(const nzo_opts* in, nzo_opts* o) {
     if (d.alphabet < 2u || d.alphabet > NZO_MAX_K || !is_pow2(d.alphabet)) return NZO_ERR_INVALID;
     if (d.force_codec < -1 || d.force_codec > 2) return NZO_ERR_INVALID;
     if (d.min_gain_permil > 1000u) return NZO_ERR_INVALID;
+    if (d.predictor > 1u || d.reserved) return NZO_ERR_INVALID;
     *o = d;
     return NZO_OK;
 }
@@ -306,11 +309,24 @@ typedef struct {
 /* symbol of a zigzag code under alphabet K: z+1 when z <= K-2, else ESC = 0 */
 static uint32_t sym_of(uint32_t z, uint32_t K) { return z <= K - 2u ? z + 1u : 0u; }
 
+/*
+ * 12. Prediction before the entropy stage (the first stage of the SZ-style pipeline that Sec. II-B lists:
+ * prediction, quantization, entropy coding).  The paper's own path has no predictor; this is an extension,
+ * lossless and linear, so the integer reduce still holds.  predictor = 1 (delta): what the entropy stage codes
+ * for element i of a frame is v_i = q_i - q_{i-1}, taken modulo 2^32, except at the start of every segment of
+ * seg_syms elements, where v_i = q_i (segments stay independently decodable).  The receiver adds up again:
+ * q_i = q_{i-1} + v_i modulo 2^32.  FIXEDLEN and HUFFMAN work on zigzag(v); the selector sizes them on v.
+ */
+static int32_t coded_value(const int32_t* q, uint32_t i, const nzo_opts* o) {
+    if (o->predictor == 1u && (i % o->seg_syms) != 0u) return (int32_t)((uint32_t)q[i] - (uint32_t)q[i - 1]);
+    return q[i];
+}
+
 static void plan_frame(const int32_t* q, uint32_t nf, const nzo_opts* o, frame_plan* P) {
     memset(P, 0, sizeof *P);
     const uint32_t K = o->alphabet;
     for (uint32_t i = 0; i < nf; i++) {
-        uint32_t z = nzo_zigzag(q[i]);
+        uint32_t z = nzo_zigzag(coded_value(q, i, o));
         if (z > P->zmax) P->zmax = z;
         P->f[sym_of(z, K)]++;
     }
@@ -374,7 +390,7 @@ static void write_header(uint8_t* dst, uint32_t codec, uint32_t raw_bytes, uint3
  *             code most-significant bit first, an ESC code followed by the 32
  *             bits of z bit 0 first; segments back to back, no padding between
  *             them.  p0 = nsym, p1 = seg_syms | K<<16 (both are <= 1024, so each
- *             fits its 16-bit half).
+ *             fits its 16-bit half) | predictor<<31; FIXEDLEN: p1 = predictor<<31.
  */
 static void write_frame(uint8_t* dst, int codec, const int32_t* q, const uint32_t* rawbits, uint32_t nf,
                         const frame_plan* P, const nzo_opts* o, uint32_t step_bits) {
@@ -384,12 +400,12 @@ static void write_frame(uint8_t* dst, int codec, const int32_t* q, const uint32_
         write_header(dst, NZO_RAW, 4u * nf, (uint32_t)P->payload[NZO_RAW], 0, 0, step_bits);
         for (uint32_t i = 0; i < nf; i++) put_u32(pay + 4ull * i, rawbits[i]);
     } else if (codec == NZO_FIXEDLEN) {
-        write_header(dst, NZO_FIXEDLEN, 4u * nf, (uint32_t)P->payload[NZO_FIXEDLEN], P->w, 0, step_bits);
+        write_header(dst, NZO_FIXEDLEN, 4u * nf, (uint32_t)P->payload[NZO_FIXEDLEN], P->w, o->predictor << 31, step_bits);
         bitw_t b = { pay, 0 };
-        for (uint32_t i = 0; i < nf; i++) bw_put_lsb(&b, nzo_zigzag(q[i]), (int)P->w);
+        for (uint32_t i = 0; i < nf; i++) bw_put_lsb(&b, nzo_zigzag(coded_value(q, i, o)), (int)P->w);
     } else {
         write_header(dst, NZO_HUFFMAN, 4u * nf, (uint32_t)P->payload[NZO_HUFFMAN], P->nsym,
-                     o->seg_syms | (o->alphabet << 16), step_bits);
+                     o->seg_syms | (o->alphabet << 16) | (o->predictor << 31), step_bits);
         uint8_t* lens = pay;
         uint8_t* segt = pay + pad4(P->nsym);
         uint8_t* bits = segt + pad4(2ull * P->nseg);
@@ -400,7 +416,7 @@ static void write_frame(uint8_t* dst, int codec, const int32_t* q, const uint32_
             uint32_t i0 = g * o->seg_syms, i1 = i0 + o->seg_syms;
             if (i1 > nf) i1 = nf;
             for (uint32_t i = i0; i < i1; i++) {
-                uint32_t z = nzo_zigzag(q[i]);
+                uint32_t z = nzo_zigzag(coded_value(q, i, o));
                 uint32_t s = sym_of(z, o->alphabet);
                 bw_put_msb(&b, P->code[s], P->len[s]);
                 if (s == 0) bw_put_lsb(&b, z, 32);
@@ -425,6 +441,7 @@ static void write_stream_header(uint8_t* out, uint64_t n, const nzo_opts* o, uin
     put_u32(out + 24, step_bits);
     put_u32(out + 28, o->seg_syms);
     put_u32(out + 32, o->alphabet);
+    put_u32(out + 36, o->predictor);
     put_u64(out + 40, total);
 }
 
@@ -530,7 +547,7 @@ int nzo_compress(const float* x, size_t n, float eb, const nzo_opts* opts, uint8
 /* ------------------------------------------------------------------ */
 
 typedef struct {
-    uint64_t n; uint32_t chunk, n_frames, step_bits, seg_syms, K; uint64_t total;
+    uint64_t n; uint32_t chunk, n_frames, step_bits, seg_syms, K, predictor; uint64_t total;
 } stream_hdr;
 
 static int parse_stream(const uint8_t* s, size_t bytes, stream_hdr* h) {
@@ -538,13 +555,22 @@ static int parse_stream(const uint8_t* s, size_t bytes, stream_hdr* h) {
     if (get_u32(s) != NZO_MAGIC_STREAM || get_u32(s + 4) != 1u) return NZO_ERR_CORRUPT;
     h->n = get_u64(s + 8); h->chunk = get_u32(s + 16); h->n_frames = get_u32(s + 20);
     h->step_bits = get_u32(s + 24); h->seg_syms = get_u32(s + 28); h->K = get_u32(s + 32);
+    h->predictor = get_u32(s + 36);
     h->total = get_u64(s + 40);
+    if (h->predictor > 1u) return NZO_ERR_CORRUPT;
     if (h->n == 0 || h->chunk == 0 || h->chunk > NZO_MAX_CHUNK) return NZO_ERR_CORRUPT;
     if (h->seg_syms < 32u || h->seg_syms > 1024u) return NZO_ERR_CORRUPT;
     if (h->K < 2u || h->K > NZO_MAX_K || !is_pow2(h->K)) return NZO_ERR_CORRUPT;
     if ((h->n + h->chunk - 1) / h->chunk != h->n_frames) return NZO_ERR_CORRUPT;
     if (h->total > bytes || h->total < frames_base(h->n_frames)) return NZO_ERR_CORRUPT;
     return NZO_OK;
+}
+
+/* Receiver side of the delta predictor: running sums modulo 2^32, restarted at every segment. */
+static void undo_prediction(int32_t* q, uint32_t nf, const stream_hdr* sh) {
+    if (sh->predictor != 1u) return;
+    for (uint32_t i = 0; i < nf; i++)
+        if ((i % sh->seg_syms) != 0u) q[i] = (int32_t)((uint32_t)q[i] + (uint32_t)q[i - 1]);
 }
 
 /*
@@ -577,14 +603,17 @@ static int decode_frame(const uint8_t* s, uint64_t total, uint64_t off, uint32_t
         return NZO_OK;
     }
     if (codec == NZO_FIXEDLEN) {
-        if (p0 > 32u || p1) return NZO_ERR_CORRUPT;
+        if (p0 > 32u || (p1 & 0x7FFFFFFFu) || (p1 >> 31) != sh->predictor) return NZO_ERR_CORRUPT;
         if (payload != 4ull * (((uint64_t)nf * p0 + 31u) / 32u)) return NZO_ERR_CORRUPT;
         bitr_t b = { pay, 0, 8ull * payload, 0 };
         for (uint32_t i = 0; i < nf; i++) q[i] = nzo_unzigzag(br_get_lsb(&b, (int)p0));
-        return b.overrun ? NZO_ERR_CORRUPT : NZO_OK;
+        if (b.overrun) return NZO_ERR_CORRUPT;
+        undo_prediction(q, nf, sh);
+        return NZO_OK;
     }
     /* HUFFMAN */
-    const uint32_t nsym = p0, seg = p1 & 0xFFFFu, K = p1 >> 16;
+    const uint32_t nsym = p0, seg = p1 & 0xFFFFu, K = (p1 >> 16) & 0x7FFFu;
+    if ((p1 >> 31) != sh->predictor) return NZO_ERR_CORRUPT;
     if (seg != sh->seg_syms || K != sh->K || nsym == 0 || nsym > K) return NZO_ERR_CORRUPT;
     const uint32_t nseg = (nf + seg - 1) / seg;
     const uint64_t tables = pad4(nsym) + pad4(2ull * nseg);
@@ -636,6 +665,7 @@ static int decode_frame(const uint8_t* s, uint64_t total, uint64_t off, uint32_t
         if (b.pos != b.end) return NZO_ERR_CORRUPT;
         pos += sl;
     }
+    undo_prediction(q, nf, sh);
     return NZO_OK;
 }
 
@@ -784,7 +814,8 @@ int nzo_reduce_frames_step(const uint8_t* a, size_t a_bytes, const uint8_t* b, s
     if (rc) { res->status = (uint32_t)rc; return rc; }
     /* both operands and the output agree on n, frame size and step */
     if (ha.n != n || hb.n != n || ha.chunk != hb.chunk || ha.chunk != o.chunk_elems ||
-        ha.step_bits != hb.step_bits || ha.step_bits != f32_bits(step)) { res->status = NZO_ERR_MISMATCH; return NZO_ERR_MISMATCH; }
+        ha.step_bits != hb.step_bits || ha.step_bits != f32_bits(step) ||
+        ha.predictor != o.predictor || hb.predictor != o.predictor) { res->status = NZO_ERR_MISMATCH; return NZO_ERR_MISMATCH; }
     int32_t* qa = (int32_t*)malloc(4ull * n); int32_t* qb = (int32_t*)malloc(4ull * n);
     uint32_t* ra = (uint32_t*)malloc(4ull * n); uint32_t* rb = (uint32_t*)malloc(4ull * n);
     uint8_t* fa = (uint8_t*)calloc(ha.n_frames, 1); uint8_t* fb = (uint8_t*)calloc(ha.n_frames, 1);
@@ -833,7 +864,9 @@ int nzo_reduce_local(const uint8_t* in, size_t in_bytes, const float* local, uin
     if (resolve_opts(opts, &o) || nzo_step_constants(eb, &step, &inv)) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
     int rc = parse_stream(in, in_bytes, &hi);
     if (rc) { res->status = (uint32_t)rc; return rc; }
-    if (hi.n != n || hi.chunk != o.chunk_elems || hi.step_bits != f32_bits(step)) { res->status = NZO_ERR_MISMATCH; return NZO_ERR_MISMATCH; }
+    if (hi.n != n || hi.chunk != o.chunk_elems || hi.step_bits != f32_bits(step) || hi.predictor != o.predictor) {
+        res->status = NZO_ERR_MISMATCH; return NZO_ERR_MISMATCH;
+    }
     int32_t* qa = (int32_t*)malloc(4ull * n); int32_t* qb = (int32_t*)malloc(4ull * n);
     uint32_t* ra = (uint32_t*)malloc(4ull * n); uint32_t* rb = (uint32_t*)malloc(4ull * n);
     uint8_t* fa = (uint8_t*)calloc(hi.n_frames, 1); uint8_t* fb = (uint8_t*)calloc(hi.n_frames, 1);
@@ -1094,6 +1127,7 @@ int nzo_compress_rea(const float* x, size_t n, float eb, const nzo_opts* opts, c
     if (ropts) { ro = *ropts; if (ro.sample_bytes == 0) ro.sample_bytes = 65536u; }
     if (n == 0 || !x || !out) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
     if (resolve_opts(opts, &o) || nzo_step_constants(eb, &step, &inv)) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
+    if (o.predictor) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }     /* the sampled path codes the codes themselves */
     const uint64_t nfr64 = (n + o.chunk_elems - 1) / o.chunk_elems;
     if (nfr64 > 0xFFFFFFFFull) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
     const uint32_t nfr = (uint32_t)nfr64;
@@ -1224,7 +1258,7 @@ int nzo_compress_sr(const float* x, size_t n, float step, uint32_t seed, const n
     nzo_result dummy;
     if (!res) res = &dummy;
     memset(res, 0, sizeof *res);
-    if (n == 0 || !x || !out || !step_ok(step) || resolve_opts(opts, &o)) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
+    if (n == 0 || !x || !out || !step_ok(step) || resolve_opts(opts, &o) || o.predictor) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
     volatile float inv = 1.0f / step;
     c.x = x; c.step = step; c.inv = inv; c.seed = seed;
     return emit_stream(sr_src, &c, n, &o, f32_bits(step), out, cap, res);

@@ -18,7 +18,7 @@ static float laplace_like(float b) {
 }
 
 static int run_case(size_t n, uint32_t chunk, uint32_t K, uint32_t seg, int force, float eb, int poison) {
-    nzo_opts o = { chunk, seg, K, force, 0, 0 };
+    nzo_opts o = { chunk, seg, K, force, 0, 0, 0, 0 };
     float* x = (float*)malloc(4 * n); float* y = (float*)malloc(4 * n); float* z = (float*)malloc(4 * n);
     for (size_t i = 0; i < n; i++) { x[i] = laplace_like(1e-3f); y[i] = laplace_like(3e-2f); }
     if (poison && n > 3) { x[n / 2] = NAN; y[n - 1] = INFINITY; x[1] = 1e30f; }
@@ -47,6 +47,20 @@ static int run_case(size_t n, uint32_t chunk, uint32_t K, uint32_t seg, int forc
         if (nzo_compress_rea(y, n, eb, &od, &ro, NULL, sr, rcap, &rr, NULL)) return 14;
         if (rcap > 16 && nzo_compress_rea(y, n, eb, &od, &ro, &ctx, sr, rcap - 16, &rr, NULL) != NZO_ERR_CAPACITY) return 15;
         free(sr);
+    }
+    /* delta predictor: compress, decode, reduce */
+    {
+        nzo_opts op = od; op.predictor = 1u;
+        nzo_result r1, r2;
+        size_t pcap = nzo_compress_bound(n, &op);
+        uint8_t* s1 = (uint8_t*)malloc(pcap); uint8_t* s2 = (uint8_t*)malloc(pcap); uint8_t* s3 = (uint8_t*)malloc(pcap);
+        if (nzo_compress(x, n, eb, &op, s1, pcap, &r1) || nzo_compress(y, n, eb, &op, s2, pcap, &r2)) return 20;
+        if (nzo_decompress(s1, r1.bytes, z, n, eb, &rc)) return 21;
+        for (size_t i = 0; i < n; i++) if (isfinite(x[i]) && fabs((double)x[i] - (double)z[i]) > (double)eb) return 22;
+        if (nzo_reduce_frames(s1, r1.bytes, s2, r2.bytes, s3, pcap, n, eb, &op, &rc)) return 23;
+        if (nzo_reduce_local(s1, r1.bytes, y, s3, pcap, n, eb, &op, &rc)) return 24;
+        for (int t = 0; t < 20; t++) { s1[rnd() % r1.bytes] ^= (uint8_t)(1u + rnd() % 255u); (void)nzo_decompress(s1, r1.bytes, z, n, eb, &rc); }
+        free(s1); free(s2); free(s3);
     }
     /* stochastic quantizer: compress, decode with the recorded width, reduce */
     {
