@@ -64,6 +64,14 @@ typedef struct {
                                   ratio study (Sec. V-B)                                                    */
     uint32_t min_gain_permil;  /* minimum-gain threshold of Algorithm 1 (minGainPermil), 0..1000            */
     uint32_t huff_min_bytes;   /* Huffman size threshold T_huff of Algorithm 1 on the frame's raw bytes     */
+    uint32_t predictor;        /* 0 = none (the paper's path).  1 = delta, an extension in front of the entropy
+                                  stage (the prediction stage of the SZ-style pipeline of Sec. II-B): what is
+                                  coded for element i of a frame is q[i] - q[i-1] modulo 2^32, q[i] itself at
+                                  the start of every 256-symbol segment; lossless and linear, so streams still
+                                  reduce exactly.  A stream records its predictor; decompress and reduce must
+                                  be called with the same value (else NZ_ERR_MISMATCH).  nz_compress_rea and
+                                  nz_compress_sr accept 0 only.                                              */
+    uint32_t reserved;         /* 0                                                                        */
 } nz_opts;
 
 /* Result record, lives in DEVICE memory, valid once the stream has executed the call. */

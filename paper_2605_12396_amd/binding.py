@@ -19,11 +19,13 @@ LIB_PATH = os.path.join(_HERE, "libnz.so")
 
 class Opts(C.Structure):
     _fields_ = [("chunk_elems", C.c_uint32), ("seg_syms", C.c_uint32), ("alphabet", C.c_uint32),
-                ("force_codec", C.c_int32), ("min_gain_permil", C.c_uint32), ("huff_min_bytes", C.c_uint32)]
+                ("force_codec", C.c_int32), ("min_gain_permil", C.c_uint32), ("huff_min_bytes", C.c_uint32),
+                ("predictor", C.c_uint32), ("reserved", C.c_uint32)]
 
 
-def make_opts(chunk_elems=0, seg_syms=0, alphabet=0, force_codec=-1, min_gain_permil=0, huff_min_bytes=0):
-    return Opts(chunk_elems, seg_syms, alphabet, force_codec, min_gain_permil, huff_min_bytes)
+def make_opts(chunk_elems=0, seg_syms=0, alphabet=0, force_codec=-1, min_gain_permil=0, huff_min_bytes=0, predictor=0,
+              reserved=0):
+    return Opts(chunk_elems, seg_syms, alphabet, force_codec, min_gain_permil, huff_min_bytes, predictor, reserved)
 
 
 class ReaOpts(C.Structure):

@@ -9,16 +9,19 @@ using namespace nz;
 
 namespace {
 
-struct Opts { uint32_t chunk, seg, K; int32_t force; uint32_t gain, huff_min; };
+struct Opts { uint32_t chunk, seg, K; int32_t force; uint32_t gain, huff_min, pred; };
 
 bool resolve(const nz_opts* in, Opts& o) {
-    o.chunk = 262144u; o.seg = kSeg; o.K = 256u; o.force = -1; o.gain = 0; o.huff_min = 0;
+    o.chunk = 262144u; o.seg = kSeg; o.K = 256u; o.force = -1; o.gain = 0; o.huff_min = 0; o.pred = 0;
     if (in) {
         if (in->chunk_elems) o.chunk = in->chunk_elems;
         if (in->seg_syms) o.seg = in->seg_syms;
         if (in->alphabet) o.K = in->alphabet;
         o.force = in->force_codec; o.gain = in->min_gain_permil; o.huff_min = in->huff_min_bytes;
+        o.pred = in->predictor;
+        if (in->reserved) return false;
     }
+    if (o.pred > 1u) return false;
     if (o.chunk > kMaxChunk) return false;
     if (o.seg != kSeg) return false;                                   // the kernels decode 256-symbol segments
     if (o.K < 2u || o.K > kMaxK || (o.K & (o.K - 1u))) return false;
@@ -150,9 +153,10 @@ static nz_status compress_impl(const float* d_in, size_t n, float eb, float step
     A.in = d_in; A.n = n; A.chunk = o.chunk; A.n_frames = nfr; A.K = o.K;
     A.stat_block = kStatBlock; A.sbpf = (o.chunk + kStatBlock - 1) / kStatBlock;
     A.force_codec = o.force; A.min_gain_permil = o.gain; A.huff_min_bytes = o.huff_min;
-    A.eb = eb; A.step = step; A.inv_step = inv; A.step_bits = bits_of(step); A.seed = seed;
+    A.eb = eb; A.step = step; A.inv_step = inv; A.step_bits = bits_of(step); A.seed = seed; A.pred = o.pred;
     A.out = reinterpret_cast<uint8_t*>(d_out); A.out_cap = out_cap; A.ws = ws; A.L = L; A.res = d_res;
     A.rea_ctx = nullptr; A.rea_tmp = nullptr; A.rea_gbits = nullptr; A.rea_fail = nullptr;
+    if (stochastic && o.pred) return NZ_ERR_INVALID;              // (the stochastic quantizer is not built with the predictor)
     trace_reset(); trace_mark(st);
     if (launch_stats(A, stochastic, st) != hipSuccess) return NZ_ERR_HIP;     // also clears the control block and the result record
     trace_mark(st);
@@ -225,6 +229,7 @@ nz_status nz_compress_rea(const float* d_in, size_t n, float eb, const void* d_c
     if (!d_in || !d_out || !d_res || !d_ws || !resolve(opts, o) || !geometry_ok(n, o) || !step_constants(eb, step, inv))
         return NZ_ERR_INVALID;
     if (!aligned16(d_in) || !aligned16(d_out) || !aligned16(d_ws) || !aligned16(d_res) || !aligned16(d_ctx)) return NZ_ERR_INVALID;
+    if (o.pred) return NZ_ERR_INVALID;                            // the sampled path codes the codes themselves
     const ReaLayout L = rea_layout(n, o.chunk);
     if (ws_bytes < L.total) return NZ_ERR_INVALID;
     const uint32_t nfr = (uint32_t)((n + o.chunk - 1) / o.chunk);
@@ -265,7 +270,7 @@ static nz_status decompress_impl(const void* d_stream, size_t stream_bytes, floa
     DecodeArgs A;
     A.a = reinterpret_cast<const uint8_t*>(d_stream); A.a_bytes = stream_bytes; A.b = nullptr; A.b_bytes = 0;
     A.out = d_out; A.local = nullptr; A.eb = 0.0f; A.inv_step = 0.0f; A.n = n; A.chunk = o.chunk; A.n_frames = nfr; A.K = o.K;
-    A.dbpf = (o.chunk + kDecBlock - 1) / kDecBlock;
+    A.dbpf = (o.chunk + kDecBlock - 1) / kDecBlock; A.pred = o.pred;
     A.step = step; A.step_bits = bits_of(step); A.ws = reinterpret_cast<uint8_t*>(d_ws); A.L = L; A.res = d_res;
     static_assert(kDecBlock == kStatBlock, "the verdict words reuse the per-statistics-block slots of the workspace");
     trace_reset(); trace_mark(st);
@@ -314,13 +319,13 @@ static nz_status reduce_impl(const void* d_a, size_t a_bytes, const void* d_b, s
     D.b = reinterpret_cast<const uint8_t*>(d_b); D.b_bytes = b_bytes;
     D.out = nullptr; D.local = d_local; D.eb = eb; D.inv_step = inv;
     D.n = n; D.chunk = o.chunk; D.n_frames = nfr; D.K = o.K;
-    D.dbpf = (o.chunk + kDecBlock - 1) / kDecBlock;
+    D.dbpf = (o.chunk + kDecBlock - 1) / kDecBlock; D.pred = o.pred;
     D.step = step; D.step_bits = bits_of(step); D.ws = ws; D.L = L; D.res = d_res;
     CompressArgs A;
     A.in = nullptr; A.n = n; A.chunk = o.chunk; A.n_frames = nfr; A.K = o.K;
     A.stat_block = kDecBlock; A.sbpf = D.dbpf;
     A.force_codec = o.force; A.min_gain_permil = o.gain; A.huff_min_bytes = o.huff_min;
-    A.eb = eb; A.step = step; A.inv_step = inv; A.step_bits = bits_of(step); A.seed = 0;
+    A.eb = eb; A.step = step; A.inv_step = inv; A.step_bits = bits_of(step); A.seed = 0; A.pred = o.pred;
     A.out = reinterpret_cast<uint8_t*>(d_out); A.out_cap = out_cap; A.ws = ws; A.L = L; A.res = d_res;
     A.rea_ctx = nullptr; A.rea_tmp = nullptr; A.rea_gbits = nullptr; A.rea_fail = nullptr;
     trace_reset(); trace_mark(st);
@@ -337,6 +342,9 @@ static nz_status reduce_impl(const void* d_a, size_t a_bytes, const void* d_b, s
     }
     if (launch_fix(D, st) != hipSuccess) return NZ_ERR_HIP;                 // frames that turn RAW late (local data, sums past 2^30)
     trace_mark(st);
+    // with the delta predictor the encoder codes differences of the sums: their statistics come from a pass over the
+    // staged sums (the adding pass counted the sums themselves)
+    if (o.pred && launch_stats_codes(A, st) != hipSuccess) return NZ_ERR_HIP;
     if (launch_codebook(A, st) != hipSuccess) return NZ_ERR_HIP;
     trace_mark(st);
     if (launch_encode(A, true, false, st) != hipSuccess) return NZ_ERR_HIP;

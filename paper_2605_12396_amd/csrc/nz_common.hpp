@@ -258,6 +258,7 @@ struct CompressArgs {
     float eb, step, inv_step;
     uint32_t step_bits;
     uint32_t seed;            // stochastic quantizer only (kernels built with QM = 1)
+    uint32_t pred;            // predictor of the stream: 0 none, 1 delta on the codes (kernels built with DELTA = 1)
     uint8_t* out; uint64_t out_cap;
     uint8_t* ws; WsLayout L;
     void* res;                // nz_result* (device)
@@ -276,7 +277,7 @@ struct DecodeArgs {
     const float* local;                       // ring-step reduce only: the rank's own fp32 message
     float eb, inv_step;                       // ring-step reduce only: the quantizer's bound and 1/step
     uint64_t n;
-    uint32_t chunk, n_frames, K, dbpf;
+    uint32_t chunk, n_frames, K, dbpf, pred;
     float step; uint32_t step_bits;
     uint8_t* ws; WsLayout L;                  // reduce only: staged codes, partial histograms
     void* res;
@@ -284,6 +285,7 @@ struct DecodeArgs {
 
 hipError_t launch_init(void* zero_base, size_t zero_bytes, void* res, uint32_t n_frames, uint32_t status, hipStream_t st);
 hipError_t launch_stats(const CompressArgs& A, bool stochastic, hipStream_t st);
+hipError_t launch_stats_codes(const CompressArgs& A, hipStream_t st);   // reduce with the delta predictor: statistics of the staged sums
 hipError_t launch_codebook(const CompressArgs& A, hipStream_t st);
 hipError_t launch_encode(const CompressArgs& A, bool from_codes, bool stochastic, hipStream_t st);
 hipError_t launch_qsgd_step(const float* in, uint64_t n, uint32_t levels, float* step_out, double* partials, hipStream_t st);

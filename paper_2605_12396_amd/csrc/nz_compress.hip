@@ -29,12 +29,17 @@ __global__ void k_init(uint32_t* zero_base, size_t zero_words, ResultRec* res, u
 // quantize, zigzag, lane-replicated LDS histogram, zmax and the "cannot be quantized" flag.
 // The partial histogram goes to the workspace with plain stores; the codebook kernel adds the partials.
 // ------------------------------------------------------------------------------------------------
-template <int QM>     // QM 0: deterministic error-bounded quantizer; 1: stochastic rounding to multiples of step
+// QM 0: deterministic error-bounded quantizer; 1: stochastic rounding to multiples of step.
+// DELTA 1: the statistics are those of the differences q[i] - q[i-1] (modulo 2^32; q[i] itself at the start of every
+// segment), which is what the entropy stage codes under the delta predictor.  A wavefront always covers exactly one
+// segment (64 lanes x 4 consecutive values), so a thread gets its predecessor's last code from the lane below.
+// SRC 0: fp32 input.  SRC 1 (reduce with the delta predictor): the integer sums staged by the adding pass.
+template <int QM, int DELTA, int SRC>
 __global__ __launch_bounds__(kStatThreads) void k_stats(CompressArgs A) {
     __shared__ uint32_t s_h[8192];
     __shared__ uint32_t s_zmax, s_unq;
     const uint32_t tid = threadIdx.x, lane = lane_id();
-    if (blockIdx.x == 0) {
+    if (SRC == 0 && blockIdx.x == 0) {
         // The control block, the frame descriptors and the result record are first used by the next kernel, so
         // this kernel clears them on the side (no separate launch): nothing here reads or writes them.
         uint32_t* z = reinterpret_cast<uint32_t*>(A.ws + A.L.ctrl);
@@ -53,6 +58,8 @@ __global__ __launch_bounds__(kStatThreads) void k_stats(CompressArgs A) {
     if (b0 >= nf) return;
     const uint32_t cnt = (nf - b0 < kStatBlock) ? (nf - b0) : kStatBlock;
     const uint32_t K = A.K;
+    uint2* pm = reinterpret_cast<uint2*>(A.ws + A.L.pmeta) + blockIdx.x;
+    if (SRC == 1 && (pm->y & 3u)) return;      // a frame with fp32 sums (RAW operand, local data not quantizable) has no codes
     // replicate the histogram over lanes: 8192/K copies (at most 32) so hot bins do not serialise
     uint32_t ncs = 0;
     while ((K << (ncs + 1)) <= 8192u && ncs < 5) ncs++;
@@ -62,25 +69,41 @@ __global__ __launch_bounds__(kStatThreads) void k_stats(CompressArgs A) {
     __syncthreads();
 
     const float* src = A.in + f0 + b0;
+    const int16_t* c16 = reinterpret_cast<const int16_t*>(A.ws + A.L.c16) + f0 + b0;         // SRC 1
+    const uint32_t* c32 = reinterpret_cast<const uint32_t*>(A.ws + A.L.codes) + f0 + b0;
     const bool vec_ok = (((f0 + b0) & 3u) == 0);
     uint32_t zmax = 0, unq = 0;
     SrKeys keys;
     if (QM == 1) keys.init(A.seed, f0 + b0);
-    auto count4 = [&](const float (&v)[4], uint32_t m, uint32_t off) {   // off: position of the first value in the block
+    // four consecutive codes of the block starting at position off (m of them exist); every lane of the wave calls this
+    auto count4 = [&](const int32_t (&q)[4], uint32_t m) {
+        uint32_t v[4] = { (uint32_t)q[0], (uint32_t)q[1], (uint32_t)q[2], (uint32_t)q[3] };
+        if (DELTA) {
+            const uint32_t below = (uint32_t)__shfl_up(q[3], 1, 64);
+            const uint32_t prev = lane ? below : 0u;                  // lane 0 starts a segment
+            v[3] -= v[2]; v[2] -= v[1]; v[1] -= v[0]; v[0] -= prev;
+        }
 #pragma unroll
         for (uint32_t j = 0; j < 4; j++) {
             if (j < m) {
-                int32_t q;
-                const bool okq = (QM == 1) ? sr_quantize1(v[j], A.step, A.inv_step, keys.draw(off + j), q)
-                                           : quantize1(v[j], A.eb, A.step, A.inv_step, q);
-                if (!okq) unq = 1;
-                const uint32_t z = zigzag(q);
+                const uint32_t z = zigzag((int32_t)v[j]);
                 zmax = z > zmax ? z : zmax;
                 atomicAdd(&s_h[(bin_of(z, K) << ncs) + copy], 1u);
             }
         }
     };
-    if (vec_ok && cnt == kStatBlock) {
+    auto quant4 = [&](const float (&x)[4], uint32_t m, uint32_t off, int32_t (&q)[4]) {
+#pragma unroll
+        for (uint32_t j = 0; j < 4; j++) {
+            q[j] = 0;
+            if (j < m) {
+                const bool okq = (QM == 1) ? sr_quantize1(x[j], A.step, A.inv_step, keys.draw(off + j), q[j])
+                                           : quantize1(x[j], A.eb, A.step, A.inv_step, q[j]);
+                if (!okq) unq = 1;
+            }
+        }
+    };
+    if (SRC == 0 && vec_ok && cnt == kStatBlock) {
         // whole block: eight 16-byte loads in flight per thread, no bounds checks
         constexpr uint32_t kIters = kStatBlock / (kStatThreads * 4), kDepth = 8;
         static_assert(kIters % kDepth == 0, "statistics block must be a whole number of load groups");
@@ -92,16 +115,28 @@ __global__ __launch_bounds__(kStatThreads) void k_stats(CompressArgs A) {
             for (uint32_t u = 0; u < kDepth; u++) t[u] = src4[(g + u) * kStatThreads];
 #pragma unroll
             for (uint32_t u = 0; u < kDepth; u++) {
-                const float v[4] = { t[u].x, t[u].y, t[u].z, t[u].w };
-                count4(v, 4, ((g + u) * kStatThreads + tid) * 4u);
+                const float x[4] = { t[u].x, t[u].y, t[u].z, t[u].w };
+                int32_t q[4];
+                quant4(x, 4, ((g + u) * kStatThreads + tid) * 4u, q);
+                count4(q, 4);
             }
         }
     } else {
-        for (uint32_t i = tid * 4; i < cnt; i += kStatThreads * 4) {
-            float v[4];
-            const uint32_t m = (cnt - i < 4) ? (cnt - i) : 4;
-            for (uint32_t j = 0; j < 4; j++) v[j] = (j < m) ? src[i + j] : 0.0f;
-            count4(v, m, i);
+        for (uint32_t base = 0; base < cnt; base += kStatThreads * 4) {      // (uniform trip count: count4 shuffles)
+            const uint32_t i = base + tid * 4;
+            const uint32_t m = (i < cnt) ? ((cnt - i < 4) ? (cnt - i) : 4u) : 0u;
+            int32_t q[4];
+            if (SRC == 0) {
+                float x[4];
+                for (uint32_t j = 0; j < 4; j++) x[j] = (j < m) ? src[i + j] : 0.0f;
+                quant4(x, m, i, q);
+            } else {
+                for (uint32_t j = 0; j < 4; j++) {
+                    q[j] = 0;
+                    if (j < m) { const int32_t h = c16[i + j]; q[j] = (h == -32768) ? (int32_t)c32[i + j] : h; }
+                }
+            }
+            count4(q, m);
         }
     }
     zmax = wave_max(zmax);
@@ -115,8 +150,8 @@ __global__ __launch_bounds__(kStatThreads) void k_stats(CompressArgs A) {
         ph[bin_symbol(s, K)] = t;
     }
     if (tid == 0) {
-        uint2* pm = reinterpret_cast<uint2*>(A.ws + A.L.pmeta) + blockIdx.x;
-        *pm = make_uint2(s_zmax, s_unq);
+        if (SRC == 1) pm->x = s_zmax;          // (the flags of the adding pass stay)
+        else *pm = make_uint2(s_zmax, s_unq);
     }
 }
 
@@ -347,7 +382,7 @@ __global__ __launch_bounds__(kBookThreads) void k_codebook(CompressArgs A) {
             uint32_t h[8];
             h[0] = kMagicFrame; h[1] = codec; h[2] = 4u * nf; h[3] = payload;
             h[4] = (codec == CODEC_FIXED) ? s_w_fixed : (codec == CODEC_HUFF ? nsym : 0u);
-            h[5] = (codec == CODEC_HUFF) ? (kSeg | (K << 16)) : 0u;
+            h[5] = (codec == CODEC_HUFF) ? (kSeg | (K << 16) | (A.pred << 31)) : (codec == CODEC_FIXED ? (A.pred << 31) : 0u);
             h[6] = A.step_bits;
             uint32_t x = kCheckXor;
             for (int i = 0; i < 7; i++) x ^= h[i];
@@ -364,7 +399,7 @@ __global__ __launch_bounds__(kBookThreads) void k_codebook(CompressArgs A) {
             uint32_t* sh = reinterpret_cast<uint32_t*>(A.out);
             sh[0] = kMagicStream; sh[1] = 1u;
             sh[2] = (uint32_t)A.n; sh[3] = (uint32_t)(A.n >> 32);
-            sh[4] = A.chunk; sh[5] = A.n_frames; sh[6] = A.step_bits; sh[7] = kSeg; sh[8] = K; sh[9] = 0;
+            sh[4] = A.chunk; sh[5] = A.n_frames; sh[6] = A.step_bits; sh[7] = kSeg; sh[8] = K; sh[9] = A.pred;
             sh[10] = (uint32_t)stream_total; sh[11] = (uint32_t)(stream_total >> 32);
             sh[12] = 0; sh[13] = 0; sh[14] = 0; sh[15] = 0;
             const uint32_t st = atomicMax(&res->status, 0u);
@@ -441,26 +476,38 @@ struct EncShared {
 // before, so the quantizer runs with its tests; a value that fails them counts as code 0 and clears *ok.
 // QM = 1 (source 0 only): the stochastic quantizer, with the draw of the element (its tests are known to pass too).
 template <int SRC, int QM = 0>
-__device__ inline uint32_t enc_zz(uint32_t w, const CompressArgs& A, bool* ok = nullptr, uint32_t draw24 = 0) {
+__device__ inline int32_t enc_q(uint32_t w, const CompressArgs& A, bool* ok = nullptr, uint32_t draw24 = 0) {
     if (SRC == 0 && QM == 1) {
         int32_t q;
         sr_quantize1(__uint_as_float(w), A.step, A.inv_step, draw24, q);
-        return zigzag(q);
+        return q;
     }
     if (SRC == 0) {
 #pragma clang fp contract(off)
         const float u = __uint_as_float(w) * A.inv_step;
-        return zigzag((int32_t)__builtin_rintf(u));
+        return (int32_t)__builtin_rintf(u);
     }
     if (SRC == 2) {
         int32_t q;
         const bool good = quantize1(__uint_as_float(w), A.eb, A.step, A.inv_step, q);
         if (ok && !good) *ok = false;
-        return zigzag(q);
+        return q;
     }
-    return zigzag((int32_t)w);
+    return (int32_t)w;
 }
-
+template <int SRC, int QM = 0>
+__device__ inline uint32_t enc_zz(uint32_t w, const CompressArgs& A, bool* ok = nullptr, uint32_t draw24 = 0) {
+    return zigzag(enc_q<SRC, QM>(w, A, ok, draw24));
+}
+// Delta predictor: four consecutive codes of one thread become differences to their predecessors (modulo 2^32).
+// A wavefront's 64 x 4 values are exactly one segment, so the predecessor of a thread's first code is the last code
+// of the lane below, and lane 0 starts the segment with the code itself.  Every lane of the wave must call this.
+__device__ inline void delta4(int32_t (&q)[4]) {
+    const uint32_t below = (uint32_t)__shfl_up(q[3], 1, 64);
+    const uint32_t prev = lane_id() ? below : 0u;
+    const uint32_t v0 = (uint32_t)q[0], v1 = (uint32_t)q[1], v2 = (uint32_t)q[2], v3 = (uint32_t)q[3];
+    q[0] = (int32_t)(v0 - prev); q[1] = (int32_t)(v1 - v0); q[2] = (int32_t)(v2 - v1); q[3] = (int32_t)(v3 - v2);
+}
 // Geometry of one encode workgroup.
 struct EncGroup {
     const uint32_t* src;      // first 32-bit source word of the group (fp32 input; reduce: wide sums, fp32 sums of RAW frames)
@@ -475,6 +522,14 @@ __device__ inline uint32_t enc_word(const EncGroup& G, uint32_t i) {
     if (SRC != 1) return G.src[i];
     const int32_t q = G.src16[i];
     return (q == -32768) ? G.src[i] : (uint32_t)q;
+}
+
+// The coded value of group element i, the slow way (the element and, under the delta predictor, the one before it).
+template <int SRC, int QM, int DELTA>
+__device__ inline uint32_t enc_zz_at(const EncGroup& G, const CompressArgs& A, const SrKeys& keys, uint32_t i) {
+    int32_t q = enc_q<SRC, QM>(enc_word<SRC>(G, i), A, nullptr, QM ? keys.draw(i) : 0u);
+    if (DELTA && (i & (kSeg - 1u))) q = (int32_t)((uint32_t)q - (uint32_t)enc_q<SRC, QM>(enc_word<SRC>(G, i - 1u), A, nullptr, 0u));
+    return zigzag(q);
 }
 
 // Source words of sub-block sb: pass `it` covers its symbols it*1024 + tid*4 .. +3 (zero past the end).
@@ -509,7 +564,7 @@ __device__ inline void enc_load(const EncGroup& G, uint32_t sb, uint32_t (&raw)[
     }
 }
 
-template <int SRC, int QM>
+template <int SRC, int QM, int DELTA>
 __device__ inline void enc_raw_fixed(const CompressArgs& A, const EncGroup& G, const FrameMeta& M, uint8_t* fr, uint32_t* stage,
                                      uint32_t& bad, const SrKeys& keys) {
     const uint32_t tid = threadIdx.x;
@@ -528,15 +583,21 @@ __device__ inline void enc_raw_fixed(const CompressArgs& A, const EncGroup& G, c
         const uint32_t pass_syms = (G.gcnt - p0 < 1024u) ? (G.gcnt - p0) : 1024u;
         const uint32_t pass_words = (pass_syms * w + 31u) / 32u;
         uint32_t z[4];
+        int32_t q[4];
 #pragma unroll
         for (uint32_t j = 0; j < 4; j++) {
-            z[j] = 0;
+            q[j] = 0;
             if (tid * 4 + j < pass_syms) {
                 bool ok = true;
-                z[j] = enc_zz<SRC, QM>(enc_word<SRC>(G, p0 + tid * 4 + j), A, &ok, QM ? keys.draw(p0 + tid * 4 + j) : 0u);
-                if (SRC == 2 && w < 32u && (z[j] >> w)) { ok = false; z[j] &= (1u << w) - 1u; }   // wider than the sampled width
+                q[j] = enc_q<SRC, QM>(enc_word<SRC>(G, p0 + tid * 4 + j), A, &ok, QM ? keys.draw(p0 + tid * 4 + j) : 0u);
                 if (SRC == 2 && !ok) bad = 1;
             }
+        }
+        if (DELTA) delta4(q);                         // (a pass is four whole segments, one per wave)
+#pragma unroll
+        for (uint32_t j = 0; j < 4; j++) {
+            z[j] = zigzag(q[j]);
+            if (SRC == 2 && tid * 4 + j < pass_syms && w < 32u && (z[j] >> w)) { bad = 1; z[j] &= (1u << w) - 1u; }   // wider than the sampled width
         }
         for (uint32_t k = tid; k < pass_words; k += kEncThreads) stage[k] = 0;
         __syncthreads();
@@ -557,7 +618,7 @@ __device__ inline void enc_raw_fixed(const CompressArgs& A, const EncGroup& G, c
     }
 }
 
-template <int SRC, int QM = 0>
+template <int SRC, int QM = 0, int DELTA = 0>
 __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))) void k_encode(CompressArgs A) {
     __shared__ EncShared S;
     const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
@@ -586,7 +647,7 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
     uint32_t bad = 0;                             // SRC 2: a value that cannot be coded as planned fails the frame
     SrKeys keys;                                  // QM 1: draws of the group's elements, by position in the group
     if (QM == 1) keys.init(A.seed, f0 + G.g0); else { keys.base_lo = 0; keys.key0 = 0; keys.key1 = 0; }
-    if (M.codec != CODEC_HUFF) enc_raw_fixed<SRC, QM>(A, G, M, fr, S.stage[0], bad, keys);
+    if (M.codec != CODEC_HUFF) enc_raw_fixed<SRC, QM, DELTA>(A, G, M, fr, S.stage[0], bad, keys);
     else {
         uint32_t raw[kEncIters][4];
         enc_load<SRC>(G, 0, raw);
@@ -668,12 +729,19 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
                     const uint32_t i = it * 1024 + tid * 4;
                     uint64_t acc = 0;
                     uint32_t tl = 0;
+                    int32_t q4[4];
 #pragma unroll
                     for (uint32_t j = 0; j < 4; j++) {
                         const bool valid = WHOLE || i + j < cnt;
                         bool ok = true;
-                        const uint32_t z = enc_zz<SRC, QM>(raw[it][j], A, &ok, QM ? keys.draw(sb * kEncBlock + i + j) : 0u);
+                        q4[j] = enc_q<SRC, QM>(raw[it][j], A, &ok, QM ? keys.draw(sb * kEncBlock + i + j) : 0u);   // (words past the end are 0)
                         if (SRC == 2 && valid && !ok) bad = 1;
+                    }
+                    if (DELTA) delta4(q4);            // (a pass is four whole segments, one per wave)
+#pragma unroll
+                    for (uint32_t j = 0; j < 4; j++) {
+                        const bool valid = WHOLE || i + j < cnt;
+                        const uint32_t z = zigzag(q4[j]);
                         zs[it][j] = z;
                         const uint64_t b = S.book[z < kesc ? z : kesc];
                         const uint32_t len = valid ? (uint32_t)(b >> 32) : 0u, code = valid ? (uint32_t)b : 0u;
@@ -740,8 +808,7 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
                     for (uint32_t q = 0; q < kEncIters; q++) if (q == it) { lnit = ln[q]; pbits = pbase[q + 1] - pbase[q]; }
                     uint32_t pos = rel + lnit;
                     for (uint32_t j = 0; j < 4; j++)
-                        if (i + j < cnt) put_symbol(X, enc_zz<SRC, QM>(enc_word<SRC>(G, sb * kEncBlock + i + j), A, nullptr,
-                                                                       QM ? keys.draw(sb * kEncBlock + i + j) : 0u), pos);
+                        if (i + j < cnt) put_symbol(X, enc_zz_at<SRC, QM, DELTA>(G, A, keys, sb * kEncBlock + i + j), pos);
                     __syncthreads();
                     flush(X, X, rel + pbits);
                     __syncthreads();
@@ -1060,7 +1127,7 @@ hipError_t launch_rea(const ReaArgs& A, hipStream_t st, void (*mark)(hipStream_t
     C.out = A.out; C.out_cap = 0; C.ws = A.ws; C.L = WsLayout(); C.L.meta = A.L.meta; C.res = A.res;
     C.rea_ctx = A.ctx; C.rea_tmp = A.tmp_base; C.rea_gbits = reinterpret_cast<uint32_t*>(A.ws + A.L.gbits);
     C.rea_fail = reinterpret_cast<uint32_t*>(A.ws + A.L.fail);
-    hipLaunchKernelGGL((k_encode<2, 0>), dim3(A.n_frames * A.gpf), dim3(kEncThreads), 0, st, C);
+    hipLaunchKernelGGL((k_encode<2, 0, 0>), dim3(A.n_frames * A.gpf), dim3(kEncThreads), 0, st, C);
     mark(st);
     hipLaunchKernelGGL(k_rea_finish, dim3(A.n_frames * A.gpf), dim3(256), 0, st, A);
     mark(st);
@@ -1080,8 +1147,16 @@ hipError_t launch_init(void* zero_base, size_t zero_bytes, void* res, uint32_t n
 }
 
 hipError_t launch_stats(const CompressArgs& A, bool stochastic, hipStream_t st) {
-    if (stochastic) hipLaunchKernelGGL(k_stats<1>, dim3(A.n_frames * A.sbpf), dim3(kStatThreads), 0, st, A);
-    else hipLaunchKernelGGL(k_stats<0>, dim3(A.n_frames * A.sbpf), dim3(kStatThreads), 0, st, A);
+    const dim3 grid(A.n_frames * A.sbpf);
+    if (stochastic) hipLaunchKernelGGL((k_stats<1, 0, 0>), grid, dim3(kStatThreads), 0, st, A);
+    else if (A.pred) hipLaunchKernelGGL((k_stats<0, 1, 0>), grid, dim3(kStatThreads), 0, st, A);
+    else hipLaunchKernelGGL((k_stats<0, 0, 0>), grid, dim3(kStatThreads), 0, st, A);
+    return hipGetLastError();
+}
+
+hipError_t launch_stats_codes(const CompressArgs& A, hipStream_t st) {
+    static_assert(kStatBlock == kEncGroup, "the reduce's statistics blocks are the encoder's groups");
+    hipLaunchKernelGGL((k_stats<0, 1, 1>), dim3(A.n_frames * A.sbpf), dim3(kStatThreads), 0, st, A);
     return hipGetLastError();
 }
 
@@ -1123,9 +1198,11 @@ hipError_t launch_codebook(const CompressArgs& A, hipStream_t st) {
 
 hipError_t launch_encode(const CompressArgs& A, bool from_codes, bool stochastic, hipStream_t st) {
     const dim3 grid(A.n_frames * ((A.chunk + kEncGroup - 1) / kEncGroup));
-    if (from_codes) hipLaunchKernelGGL((k_encode<1, 0>), grid, dim3(kEncThreads), 0, st, A);
-    else if (stochastic) hipLaunchKernelGGL((k_encode<0, 1>), grid, dim3(kEncThreads), 0, st, A);
-    else hipLaunchKernelGGL((k_encode<0, 0>), grid, dim3(kEncThreads), 0, st, A);
+    if (from_codes && A.pred) hipLaunchKernelGGL((k_encode<1, 0, 1>), grid, dim3(kEncThreads), 0, st, A);
+    else if (from_codes) hipLaunchKernelGGL((k_encode<1, 0, 0>), grid, dim3(kEncThreads), 0, st, A);
+    else if (stochastic) hipLaunchKernelGGL((k_encode<0, 1, 0>), grid, dim3(kEncThreads), 0, st, A);
+    else if (A.pred) hipLaunchKernelGGL((k_encode<0, 0, 1>), grid, dim3(kEncThreads), 0, st, A);
+    else hipLaunchKernelGGL((k_encode<0, 0, 0>), grid, dim3(kEncThreads), 0, st, A);
     return hipGetLastError();
 }
 

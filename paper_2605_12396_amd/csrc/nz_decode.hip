@@ -25,15 +25,16 @@ __device__ inline uint32_t check_stream(const uint8_t* s, uint64_t bytes, const 
     const uint32_t* h = reinterpret_cast<const uint32_t*>(s);
     if (h[0] != kMagicStream || h[1] != 1u) return ST_CORRUPT;
     const uint64_t n = (uint64_t)h[2] | ((uint64_t)h[3] << 32);
-    const uint32_t chunk = h[4], nfr = h[5], stepb = h[6], seg = h[7], K = h[8];
+    const uint32_t chunk = h[4], nfr = h[5], stepb = h[6], seg = h[7], K = h[8], pred = h[9];
     total = (uint64_t)h[10] | ((uint64_t)h[11] << 32);
     if (n == 0 || chunk == 0 || chunk > kMaxChunk) return ST_CORRUPT;
     if (seg < 32u || seg > 1024u) return ST_CORRUPT;
     if (K < 2u || K > kMaxK || (K & (K - 1u))) return ST_CORRUPT;
+    if (pred > 1u) return ST_CORRUPT;
     if ((n + chunk - 1) / chunk != (uint64_t)nfr) return ST_CORRUPT;
     if (total > bytes || total < kStreamHdr + pad16d(8ull * nfr)) return ST_CORRUPT;
     if (n != A.n || stepb != A.step_bits) return ST_MISMATCH;
-    if (chunk != A.chunk || K != A.K || seg != kSeg) return ST_MISMATCH;
+    if (chunk != A.chunk || K != A.K || seg != kSeg || pred != A.pred) return ST_MISMATCH;
     return ST_OK;
 }
 
@@ -106,7 +107,7 @@ __device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t fra
         return;
     }
     if (codec == CODEC_FIXED) {
-        if (p0 > 32u || p1) return;
+        if (p0 > 32u || (p1 & 0x7FFFFFFFu) || (p1 >> 31) != A.pred) return;   // (the stream's predictor is the caller's: checked before)
         const uint64_t need = 4ull * (((uint64_t)nf * p0 + 31u) / 32u);
         if (payload != need) return;
         V.status = ST_OK; V.kind = KIND_FIXED; V.w = p0;
@@ -114,7 +115,8 @@ __device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t fra
         return;
     }
     // HUFFMAN
-    const uint32_t nsym = p0, seg = p1 & 0xFFFFu, K = p1 >> 16;
+    const uint32_t nsym = p0, seg = p1 & 0xFFFFu, K = (p1 >> 16) & 0x7FFFu;
+    if ((p1 >> 31) != A.pred) return;
     if (seg != kSeg || K != A.K || nsym == 0 || nsym > K) return;
     const uint32_t nseg = (nf + kSeg - 1) / kSeg;
     const uint64_t tables = pad4d(nsym) + pad4d(2ull * nseg);
@@ -551,7 +553,9 @@ struct AddCtx {
 // A code that does not fit 16 bits (an escape with a large value) is finished by the decoding lane itself,
 // which leaves kWideMarker in the tile and raises a workgroup flag; only then does the consumer look for
 // markers.
-template <int MODE, int NT>
+// DELTA: the stream carries differences; the thread keeps the running sum of its segment (modulo 2^32) and a sum
+// that does not fit 16 bits is finished by the decoding lane like a wide escape.
+template <int MODE, int NT, int DELTA>
 __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader<NT>& ra, DecShared<NT>* S, bool dense,
                                 const AddCtx& X, bool a_wide, uint32_t (&zmax)[2], uint32_t& overflow) {
     const uint32_t tid = C.tid;
@@ -564,17 +568,28 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
     typename HuffReader<NT>::Pending pend;
     ra.request(pend);
     auto start_run = [&]() { if (ra.pos() >= kWinRunLimit) ra.reload(); };
-    auto wide = [&](uint32_t z) -> int32_t {          // only an escape can carry a code of 16 bits or more
-        int32_t q = unzigzag(z);
-        if (z >= 0xFFFFu) {
-            if (MODE == MODE_DECOMPRESS) A.out[C.f0 + C.e0 + e] = dequantize1(q, A.step);
-            else if (MODE == MODE_STAGE_A) X.sa.a32[C.f0 + C.e0 + e] = (uint32_t)q;
-            else X.finish(C, C.e0 + e, (uint32_t)q, zmax, overflow);
-            q = kWideMarker; S->flags = 1u;
-        }
-        return q;
+    auto wide_code = [&](int32_t q) -> int32_t {      // a code outside the tile's 16 bits: finished here, marked there
+        if (MODE == MODE_DECOMPRESS) A.out[C.f0 + C.e0 + e] = dequantize1(q, A.step);
+        else if (MODE == MODE_STAGE_A) X.sa.a32[C.f0 + C.e0 + e] = (uint32_t)q;
+        else X.finish(C, C.e0 + e, (uint32_t)q, zmax, overflow);
+        S->flags = 1u;
+        return kWideMarker;
     };
-    auto next16 = [&]() -> uint32_t { const int32_t q = ra.next(wide); e++; return (uint32_t)q; };
+    auto wide = [&](uint32_t z) -> int32_t {          // without a predictor only an escape can carry a code of 16 bits or more
+        const int32_t q = unzigzag(z);
+        if (DELTA) return q;
+        return (z >= 0xFFFFu) ? wide_code(q) : q;
+    };
+    uint32_t acc = 0;                                 // DELTA: the code before this one (0 at the segment start)
+    auto next16 = [&]() -> uint32_t {
+        int32_t q = ra.next(wide);
+        if (DELTA) {
+            acc += (uint32_t)q; q = (int32_t)acc;
+            if (__builtin_expect(q > 32767 || q <= kWideMarker, 0)) q = wide_code(q);
+        }
+        e++;
+        return (uint32_t)q;
+    };
     constexpr uint32_t LPR = kTile16R / 4;            // 8 lanes consume one row
     constexpr uint32_t RPK = NT / LPR;                // rows covered by one step k of the consumer
     // consumer: thread (row rw0 + RPK k, columns c .. c+3) for k = 0..7
@@ -727,18 +742,30 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
 }
 
 // Frames without a HUFFMAN bitstream (RAW, FIXEDLEN, or rejected = all zero): element-parallel.
-template <int MODE, int NT>
+// DELTA (FIXEDLEN frames): a wavefront's 64 x 4 elements are one segment, so the running sums of the differences are
+// a scan over the wave (modulo 2^32); the loop's trip count is uniform for that.
+template <int MODE, int NT, int DELTA>
 __device__ inline void run_elementwise(const DecodeArgs& A, const SegCtx& C, const DirectFetch& da, DecShared<NT>* S,
                                        const AddCtx& X, uint32_t (&zmax)[2], uint32_t& overflow) {
     const uint32_t cnt = (C.nf - C.blk0 < NT * kSeg) ? (C.nf - C.blk0) : NT * kSeg;
     const bool raw = da.kind == KIND_RAW;
     uint32_t wide_seen = 0;
-    for (uint32_t i = C.tid * 4; i < cnt; i += NT * 4) {
-        const uint32_t m = (cnt - i < 4) ? (cnt - i) : 4u;
+    for (uint32_t base = 0; base < cnt; base += NT * 4) {
+        const uint32_t i = base + C.tid * 4;
+        const uint32_t m = (i < cnt) ? ((cnt - i < 4) ? (cnt - i) : 4u) : 0u;
+        uint32_t tv[4] = { 0, 0, 0, 0 };
+        for (uint32_t j = 0; j < m; j++) {
+            tv[j] = da.get(C.blk0 + i + j);                                       // fp32 bits (RAW) or zigzag code
+            if (!raw) tv[j] = (uint32_t)unzigzag(tv[j]);
+        }
+        if (DELTA && !raw) {                                                      // (uniform: the frame's kind)
+            tv[1] += tv[0]; tv[2] += tv[1]; tv[3] += tv[2];
+            const uint32_t before = wave_incl_scan_dpp(tv[3]) - tv[3];
+            tv[0] += before; tv[1] += before; tv[2] += before; tv[3] += before;
+        }
         for (uint32_t j = 0; j < m; j++) {
             const uint32_t e = C.blk0 + i + j;
-            uint32_t t = da.get(e);                                               // fp32 bits (RAW) or zigzag code
-            if (!raw) t = (uint32_t)unzigzag(t);
+            const uint32_t t = tv[j];
             if (MODE == MODE_DECOMPRESS) A.out[C.f0 + e] = raw ? __uint_as_float(t) : dequantize1((int32_t)t, A.step);
             else if (MODE == MODE_STAGE_A) { if (raw) X.sa.a32[C.f0 + e] = t; else X.sa.put_code(C.f0, C.nf, e, (int32_t)t, wide_seen); }
             else X.finish(C, e, t, zmax, overflow);
@@ -748,7 +775,7 @@ __device__ inline void run_elementwise(const DecodeArgs& A, const SegCtx& C, con
 }
 
 // One workgroup per NT segments of one frame.
-template <int MODE, int NT>
+template <int MODE, int NT, int DELTA>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_decode(DecodeArgs A) {
     __shared__ DecTables s_t;
     __shared__ DecShared<NT> S;
@@ -843,11 +870,11 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
 
     bool late = false;                                                  // a segment that did not use exactly its recorded bits
     if (V.kind == KIND_HUFF) {
-        run_huff<MODE, NT>(A, C, ra, &S, V.dense, X, a_wide, zmax, overflow);
+        run_huff<MODE, NT, DELTA>(A, C, ra, &S, V.dense, X, a_wide, zmax, overflow);
         late = seg_valid && (ra.bad || ra.consumed() != seglen);
         if (MODE != MODE_DECOMPRESS && late) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
     } else {
-        run_elementwise<MODE, NT>(A, C, da, &S, X, zmax, overflow);
+        run_elementwise<MODE, NT, DELTA>(A, C, da, &S, X, zmax, overflow);
     }
     if (MODE == MODE_DECOMPRESS) {
         // a frame found corrupt only now has been written already: k_decode_finish clears it again
@@ -1021,21 +1048,26 @@ hipError_t launch_decode_finish(const DecodeArgs& A, hipStream_t st) {
 
 constexpr int kAddThreads = 512;        // second reduce pass: two halves per workgroup, four waves per SIMD at 2 workgroups per CU
 
-hipError_t launch_decode(const DecodeArgs& A, int pass, hipStream_t st) {
-    DecodeArgs D = A;
+template <int DELTA>
+static void launch_decode_t(DecodeArgs& D, const DecodeArgs& A, int pass, hipStream_t st) {
     if (pass == 0) {
         D.dbpf = (A.chunk + kDecBlock - 1) / kDecBlock;
-        hipLaunchKernelGGL((k_decode<MODE_DECOMPRESS, kDecThreads>), dim3(D.n_frames * D.dbpf), dim3(kDecThreads), 0, st, D);
+        hipLaunchKernelGGL((k_decode<MODE_DECOMPRESS, kDecThreads, DELTA>), dim3(D.n_frames * D.dbpf), dim3(kDecThreads), 0, st, D);
     } else if (pass == 1) {
         D.dbpf = (A.chunk + kDecBlock - 1) / kDecBlock;
-        hipLaunchKernelGGL((k_decode<MODE_STAGE_A, kDecThreads>), dim3(D.n_frames * D.dbpf), dim3(kDecThreads), 0, st, D);
+        hipLaunchKernelGGL((k_decode<MODE_STAGE_A, kDecThreads, DELTA>), dim3(D.n_frames * D.dbpf), dim3(kDecThreads), 0, st, D);
     } else if (pass == 2) {
         D.dbpf = (A.chunk + kAddThreads * kSeg - 1) / (kAddThreads * kSeg);
-        hipLaunchKernelGGL((k_decode<MODE_ADD_B, kAddThreads>), dim3(D.n_frames * D.dbpf), dim3(kAddThreads), 0, st, D);
+        hipLaunchKernelGGL((k_decode<MODE_ADD_B, kAddThreads, DELTA>), dim3(D.n_frames * D.dbpf), dim3(kAddThreads), 0, st, D);
     } else {
         D.dbpf = (A.chunk + kAddThreads * kSeg - 1) / (kAddThreads * kSeg);
-        hipLaunchKernelGGL((k_decode<MODE_ADD_LOCAL, kAddThreads>), dim3(D.n_frames * D.dbpf), dim3(kAddThreads), 0, st, D);
+        hipLaunchKernelGGL((k_decode<MODE_ADD_LOCAL, kAddThreads, DELTA>), dim3(D.n_frames * D.dbpf), dim3(kAddThreads), 0, st, D);
     }
+}
+
+hipError_t launch_decode(const DecodeArgs& A, int pass, hipStream_t st) {
+    DecodeArgs D = A;
+    if (A.pred) launch_decode_t<1>(D, A, pass, st); else launch_decode_t<0>(D, A, pass, st);
     return hipGetLastError();
 }
 

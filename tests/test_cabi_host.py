@@ -36,7 +36,7 @@ def test_exports_every_declared_symbol(nz):
 
 
 def test_struct_layouts_match_header(nz):
-    assert C.sizeof(nz.Opts) == 24 and nz.RESULT_BYTES == 32 == C.sizeof(oracle.Result)
+    assert C.sizeof(nz.Opts) == 32 == C.sizeof(oracle.Opts) and nz.RESULT_BYTES == 32 == C.sizeof(oracle.Result)
 
 
 def test_compress_bound_equals_oracle_bound(nz):
