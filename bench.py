@@ -263,6 +263,66 @@ def run_c3_bounds(args):
                               first_4_frames_match_oracle=same)))
 
 
+def run_predictor(args):
+    """The delta predictor on the codes (opts.predictor = 1) against the plain path: compression ratio and compress /
+    decompress throughput on three inputs -- the config-1 field (3-D, its fastest axis has only 64 points per line, so
+    a 1-D difference removes little), a 256^3 cut of the config-3 recipe at REL 1e-3, and a smooth 1-D signal
+    (sin(i/300) + N(0, 1e-4), the case a 1-D predictor is made for).  The first frames of every run are compared with
+    the oracle.  One JSON line per (input, predictor); not part of the headline metric."""
+    import numpy as np
+    import torch
+    import oracle
+    from paper_2605_12396_amd import binding as nz, workloads as W
+
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(7)
+    n1d = 1 << 24
+    inputs = [("c1: 256x64x64 smooth field + N(0,1e-3), eb=1e-4, 64KiB frames", W.smooth_field((256, 64, 64), seed=1), 1e-4, 16384),
+              ("c3 recipe at 256^3, REL=1e-3 x range, 1MiB frames", W.gaussian_random_field(256, seed=3).reshape(-1), None, 262144),
+              ("smooth 1-D: sin(i/300) + N(0,1e-4), 16Mi elements, eb=1e-4, 1MiB frames",
+               (np.sin(np.arange(n1d) / 300.0) + 1e-4 * rng.normal(size=n1d)).astype(np.float32), 1e-4, 262144)]
+    for desc, x, eb, chunk in inputs:
+        x = np.ascontiguousarray(x, dtype=np.float32)
+        n = x.size
+        eb = float(np.float32(eb if eb is not None else 1e-3 * float(x.max() - x.min())))
+        f = torch.from_numpy(x).to(dev)
+        y = torch.empty_like(f)
+        gb = 4.0 * n / 1e9
+        for pred in (0, 1):
+            opts = nz.make_opts(chunk_elems=chunk, alphabet=args.alphabet, predictor=pred)
+            sess = nz.Session(n, opts, dev)
+            out = sess.new_stream_buffer()
+
+            def timed(fn, reps):
+                fn(); torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(reps):
+                    fn()
+                e1.record(); torch.cuda.synchronize()
+                return e0.elapsed_time(e1) / reps
+            reps = max(3, min(args.steps, 20))
+            t_c = timed(lambda: sess.compress(f, eb, out=out), reps)
+            r = sess.result()
+            assert r["status"] == 0
+            nbytes = r["bytes"]
+            t_d = timed(lambda: sess.decompress(out, nbytes, n, eb, out=y), reps)
+            assert sess.result()["status"] == 0
+            err = float((y.double() - f.double()).abs().max())
+            m = min(n, 4 * chunk)
+            ref, ores, orc = oracle.compress(x[:m], eb, oracle.make_opts(chunk_elems=chunk, alphabet=args.alphabet, predictor=pred))
+            s4 = nz.Session(m, opts, dev)
+            rc, o4 = s4.compress(f[:m], eb)
+            r4 = s4.result()
+            same = bool(orc == 0 and r4["bytes"] == ores.bytes and (o4[:r4["bytes"]].cpu().numpy() == ref).all())
+            print(json.dumps(dict(metric="compression ratio and throughput with / without the delta predictor", n_gpus=1,
+                                  data="synthetic", config=dict(workload=desc, predictor=pred, alphabet=args.alphabet, eb=eb),
+                                  compression_ratio=4.0 * n / nbytes, compress_GBps=gb / (t_c * 1e-3),
+                                  decompress_GBps=gb / (t_d * 1e-3), compress_ms=t_c, decompress_ms=t_d, max_abs_err=err,
+                                  bound_holds=bool(err <= eb), frames=dict(raw=r["n_raw"], fixed=r["n_fixed"], huffman=r["n_huff"]),
+                                  first_frames_match_oracle=same)))
+
+
 def run_c4_ring(args):
     """Config 4: one rank's share of a reduce-scatter ring over 8 peers: 7 fused steps acc = reduce(acc, peer_p) on
     32 Mi-element messages (eb = 1e-5, 1 MiB frames), peers pre-compressed untimed.  Also the ring-step variant in
@@ -325,7 +385,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c2", help="c2 (headline) | c1 | c4 | c3 | c4ring | c5")
+    ap.add_argument("--workload", default="c2", help="c2 (headline) | c1 | c4 | c3 | c4ring | c5 | pred")
     ap.add_argument("--alphabet", type=int, default=256, help="Huffman alphabet K (power of two, 2..1024)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rotate", type=int, default=3, help="number of distinct input / stream copies cycled through")
@@ -347,6 +407,8 @@ def main():
         return run_c4_ring(args)
     if args.workload == "c3":
         return run_c3_bounds(args)
+    if args.workload == "pred":
+        return run_predictor(args)
 
     import numpy as np
     import torch

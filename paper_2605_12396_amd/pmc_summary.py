@@ -17,12 +17,12 @@ import glob
 import os
 import sys
 
-KERNELS = [("k_stats", ["compress/stats"]), ("k_codebook", ["compress/codebook", "reduce/codebook", "reduce_local/codebook"]),
-           ("k_encode<0>", ["compress/encode"]), ("k_encode<1>", ["reduce/encode", "reduce_local/encode"]),
-           ("k_decode<0, 256>", ["decompress/decode"]), ("k_decode_finish", ["decompress/finish"]),
-           ("k_decode<1, 256>", ["reduce/stage_a"]), ("k_decode<2, 512>", ["reduce/add_b"]),
-           ("k_decode<3, 512>", ["reduce_local/add_local"]), ("k_fix", ["reduce/fix", "reduce_local/fix"]),
-           ("k_rea_plan", ["compress_rea/plan"]), ("k_rea_encode", ["compress_rea/encode"]),
+KERNELS = [("k_stats<0, 0, 0>", ["compress/stats"]), ("k_codebook", ["compress/codebook", "reduce/codebook", "reduce_local/codebook"]),
+           ("k_encode<0, 0, 0>", ["compress/encode"]), ("k_encode<1, 0, 0>", ["reduce/encode", "reduce_local/encode"]),
+           ("k_decode<0, 256, 0>", ["decompress/decode"]), ("k_decode_finish", ["decompress/finish"]),
+           ("k_decode<1, 256, 0>", ["reduce/stage_a"]), ("k_decode<2, 512, 0>", ["reduce/add_b"]),
+           ("k_decode<3, 512, 0>", ["reduce_local/add_local"]), ("k_fix", ["reduce/fix", "reduce_local/fix"]),
+           ("k_rea_plan", ["compress_rea/plan"]), ("k_encode<2, 0, 0>", ["compress_rea/encode"]),
            ("k_rea_finish", ["compress_rea/finish"])]
 
 
