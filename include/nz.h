@@ -44,7 +44,7 @@ typedef enum {
     NZ_ERR_INVALID  = 1,   /* bad argument (n = 0, eb out of range, misaligned pointer, bad opts)        */
     NZ_ERR_CAPACITY = 2,   /* output does not fit out_cap: nothing is published (Algorithm 1 returns 0) */
     NZ_ERR_CORRUPT  = 3,   /* a stream or frame failed validation (Algorithm 2, ValidateHeader)         */
-    NZ_ERR_MISMATCH = 4,   /* n, frame size, alphabet or quantization step differ from the stream's     */
+    NZ_ERR_MISMATCH = 4,   /* n, frame size, alphabet, predictor or quantization step differ from the stream's */
     NZ_ERR_HIP      = 5    /* a HIP launch failed (host return value only)                              */
 } nz_status;
 
