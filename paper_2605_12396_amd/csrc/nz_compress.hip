@@ -576,45 +576,82 @@ __device__ inline void enc_raw_fixed(const CompressArgs& A, const EncGroup& G, c
         }
         return;
     }
-    // FIXEDLEN: passes of 1024 codes = 32*w whole words, staged in LDS and written coalesced
+    // FIXEDLEN: a pass of 1024 codes is 32*w whole words.  The codes of up to four passes (as many as fit a stage) are
+    // ORed into one of two LDS stages at their bit positions; after a barrier the words are written out coalesced and
+    // cleared, while the next round already fills the other stage (a stage is used again two rounds later, behind the
+    // barrier in between): one barrier per round.  The source words of the next pass are requested before the current
+    // ones are worked on.
     const uint32_t w = M.w;
     uint32_t* bits = reinterpret_cast<uint32_t*>(fr + M.bits_off) + (G.g0 / 32u) * w;
-    for (uint32_t p0 = 0; p0 < G.gcnt; p0 += 1024) {
-        const uint32_t pass_syms = (G.gcnt - p0 < 1024u) ? (G.gcnt - p0) : 1024u;
-        const uint32_t pass_words = (pass_syms * w + 31u) / 32u;
-        uint32_t z[4];
-        int32_t q[4];
+    constexpr uint32_t kStage2 = kStageWords + 4;                        // the second stage follows the first
+    static_assert(kStageWords == 2048, "the passes per round below are sized for stages of 2048 words");
+    const uint32_t ppr = (w <= 16u) ? 4u : (w <= 21u ? 3u : 2u);          // passes per round: ppr * 32 * w <= 2048 words
+    for (uint32_t k = tid; k < kStageWords + 1u; k += kEncThreads) { stage[k] = 0; stage[kStage2 + k] = 0; }
+    // source words of the thread's four codes in the pass that starts at p0 (zero past the end)
+    auto load4 = [&](uint32_t p0, uint32_t (&x)[4]) {
+        const uint32_t i = p0 + tid * 4;
+        x[0] = x[1] = x[2] = x[3] = 0;
+        if (i >= G.gcnt) return;
+        if (G.vec_ok && i + 4 <= G.gcnt && (SRC != 1 || !G.wide16)) {
+            if (SRC != 1) {
+                const uint4 t = *reinterpret_cast<const uint4*>(G.src + i);
+                x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+            } else {
+                const uint2 t = *reinterpret_cast<const uint2*>(G.src16 + i);
+                x[0] = (uint32_t)(int32_t)(int16_t)(t.x & 0xFFFFu); x[1] = (uint32_t)((int32_t)t.x >> 16);
+                x[2] = (uint32_t)(int32_t)(int16_t)(t.y & 0xFFFFu); x[3] = (uint32_t)((int32_t)t.y >> 16);
+            }
+        } else {
+            for (uint32_t j = 0; j < 4; j++) if (i + j < G.gcnt) x[j] = enc_word<SRC>(G, i + j);
+        }
+    };
+    uint32_t cur[4], nxt[4];
+    load4(0, nxt);
+    __syncthreads();
+    uint32_t ri = 0;
+    for (uint32_t r0 = 0; r0 < G.gcnt; r0 += ppr * 1024u, ri++) {
+        const uint32_t round_syms = (G.gcnt - r0 < ppr * 1024u) ? (G.gcnt - r0) : ppr * 1024u;
+        const uint32_t round_words = (round_syms * w + 31u) / 32u;
+        uint32_t* buf = stage + (ri & 1u) * kStage2;
+        for (uint32_t u = 0; u < ppr; u++) {
+            const uint32_t p0 = r0 + u * 1024u;
+            if (p0 >= G.gcnt) break;
+            const uint32_t pass_syms = (G.gcnt - p0 < 1024u) ? (G.gcnt - p0) : 1024u;
 #pragma unroll
-        for (uint32_t j = 0; j < 4; j++) {
-            q[j] = 0;
-            if (tid * 4 + j < pass_syms) {
+            for (uint32_t j = 0; j < 4; j++) cur[j] = nxt[j];
+            load4(p0 + 1024u, nxt);
+            int32_t q[4];
+#pragma unroll
+            for (uint32_t j = 0; j < 4; j++) {
                 bool ok = true;
-                q[j] = enc_q<SRC, QM>(enc_word<SRC>(G, p0 + tid * 4 + j), A, &ok, QM ? keys.draw(p0 + tid * 4 + j) : 0u);
-                if (SRC == 2 && !ok) bad = 1;
+                q[j] = enc_q<SRC, QM>(cur[j], A, &ok, QM ? keys.draw(p0 + tid * 4 + j) : 0u);     // (words past the end are 0)
+                if (SRC == 2 && tid * 4 + j < pass_syms && !ok) bad = 1;
             }
-        }
-        if (DELTA) delta4(q);                         // (a pass is four whole segments, one per wave)
+            if (DELTA) delta4(q);                     // (a pass is four whole segments, one per wave)
+            uint32_t pos = (u * 1024u + tid * 4u) * w;
 #pragma unroll
-        for (uint32_t j = 0; j < 4; j++) {
-            z[j] = zigzag(q[j]);
-            if (SRC == 2 && tid * 4 + j < pass_syms && w < 32u && (z[j] >> w)) { bad = 1; z[j] &= (1u << w) - 1u; }   // wider than the sampled width
-        }
-        for (uint32_t k = tid; k < pass_words; k += kEncThreads) stage[k] = 0;
-        __syncthreads();
-        uint32_t pos = tid * 4 * w;
-#pragma unroll
-        for (uint32_t j = 0; j < 4; j++) {
-            if (tid * 4 + j < pass_syms && w) {
-                const uint32_t sh = pos & 31u, wi = pos >> 5;
-                atomicOr(&stage[wi], z[j] << sh);
-                if (sh + w > 32u) atomicOr(&stage[wi + 1], z[j] >> (32u - sh));
-                pos += w;
+            for (uint32_t j = 0; j < 4; j++) {
+                uint32_t z = zigzag(q[j]);
+                if (tid * 4 + j < pass_syms && w) {
+                    if (SRC == 2 && w < 32u && (z >> w)) { bad = 1; z &= (1u << w) - 1u; }   // wider than the sampled width
+                    const uint32_t sh = pos & 31u, wi = pos >> 5;
+                    atomicOr(&buf[wi], z << sh);
+                    if (sh + w > 32u) atomicOr(&buf[wi + 1], z >> (32u - sh));
+                    pos += w;
+                } else if (SRC == 2 && tid * 4 + j < pass_syms && z) bad = 1;               // (sampled width 0, value not 0)
             }
         }
         __syncthreads();
-        uint32_t* dst = bits + (p0 / 32u) * w;
-        for (uint32_t k = tid; k < pass_words; k += kEncThreads) dst[k] = stage[k];
-        __syncthreads();
+        uint32_t* dst = bits + (r0 / 32u) * w;
+        for (uint32_t k = 4u * tid; k < round_words; k += 4u * kEncThreads) {     // 16 bytes per thread and step
+            if (k + 4u <= round_words) {
+                const uint4 v = *reinterpret_cast<const uint4*>(buf + k);
+                *reinterpret_cast<uint4*>(buf + k) = make_uint4(0u, 0u, 0u, 0u);
+                *reinterpret_cast<uint4*>(dst + k) = v;
+            } else {
+                for (uint32_t kk = k; kk < round_words; kk++) { dst[kk] = buf[kk]; buf[kk] = 0; }
+            }
+        }
     }
 }
 
@@ -1052,7 +1089,32 @@ __global__ __launch_bounds__(256) void k_rea_finish(ReaArgs A) {
         const uint32_t nw = (uint32_t)(W1 - W0);
         const uint32_t interior = (uint32_t)(len >> 5);                   // words w of the frame with k - back + 1 < interior need no care
         uint32_t* dst = bits0 + W0;
-        for (uint32_t k = tid; k < nw; k += 256) {
+        // interior words (k = back + a, a + 1 < interior) are a funnel shift of two words of the group: four per thread
+        // and pass, several passes in flight (16-byte accesses that are only dword aligned)
+        typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+        typedef u32x4 u32x4_a4 __attribute__((aligned(4)));
+        const uint32_t fast = interior ? ((interior - 1u) & ~3u) : 0u;    // a in [0, fast) goes the fast way
+        constexpr uint32_t kPasses = 4;
+        for (uint32_t a0 = tid * 4; a0 < fast; a0 += 256 * 4 * kPasses) {
+            u32x4 x[kPasses]; uint32_t y[kPasses];
+#pragma unroll
+            for (uint32_t u = 0; u < kPasses; u++) {
+                const uint32_t a = a0 + u * 1024;
+                if (a < fast) { x[u] = *reinterpret_cast<const u32x4_a4*>(tmp + a); y[u] = tmp[a + 4]; }
+            }
+#pragma unroll
+            for (uint32_t u = 0; u < kPasses; u++) {
+                const uint32_t a = a0 + u * 1024;
+                if (a < fast) {
+                    u32x4 v;
+                    v.x = __builtin_amdgcn_alignbit(x[u].y, x[u].x, s); v.y = __builtin_amdgcn_alignbit(x[u].z, x[u].y, s);
+                    v.z = __builtin_amdgcn_alignbit(x[u].w, x[u].z, s); v.w = __builtin_amdgcn_alignbit(y[u], x[u].w, s);
+                    *reinterpret_cast<u32x4_a4*>(dst + back + a) = v;
+                }
+            }
+        }
+        for (uint32_t j = tid; j < nw - fast; j += 256) {                 // the words in front of and behind the fast part
+            const uint32_t k = j < back ? j : j + fast;
             uint32_t v;
             if (k >= back && k - back + 1 < interior) {
                 const uint32_t a = k - back;                              // group bits [32a + s', ...) with s' = s

@@ -741,34 +741,98 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
     }
 }
 
-// Frames without a HUFFMAN bitstream (RAW, FIXEDLEN, or rejected = all zero): element-parallel.
-// DELTA (FIXEDLEN frames): a wavefront's 64 x 4 elements are one segment, so the running sums of the differences are
-// a scan over the wave (modulo 2^32); the loop's trip count is uniform for that.
-template <int MODE, int NT, int DELTA>
+// RAW frames and rejected frames (= all zero): element-parallel.
+template <int MODE, int NT>
 __device__ inline void run_elementwise(const DecodeArgs& A, const SegCtx& C, const DirectFetch& da, DecShared<NT>* S,
                                        const AddCtx& X, uint32_t (&zmax)[2], uint32_t& overflow) {
     const uint32_t cnt = (C.nf - C.blk0 < NT * kSeg) ? (C.nf - C.blk0) : NT * kSeg;
     const bool raw = da.kind == KIND_RAW;
     uint32_t wide_seen = 0;
-    for (uint32_t base = 0; base < cnt; base += NT * 4) {
-        const uint32_t i = base + C.tid * 4;
-        const uint32_t m = (i < cnt) ? ((cnt - i < 4) ? (cnt - i) : 4u) : 0u;
-        uint32_t tv[4] = { 0, 0, 0, 0 };
-        for (uint32_t j = 0; j < m; j++) {
-            tv[j] = da.get(C.blk0 + i + j);                                       // fp32 bits (RAW) or zigzag code
-            if (!raw) tv[j] = (uint32_t)unzigzag(tv[j]);
+    for (uint32_t i = C.tid * 4; i < cnt; i += NT * 4) {
+        const uint32_t m = (cnt - i < 4) ? (cnt - i) : 4u;
+        if (MODE == MODE_DECOMPRESS && raw && m == 4u && C.vec_ok) {      // a RAW frame is a copy (payload and output 16-byte aligned)
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+            const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(da.words + C.blk0 + i));
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(A.out + C.f0 + C.blk0 + i));
+            continue;
         }
-        if (DELTA && !raw) {                                                      // (uniform: the frame's kind)
+        for (uint32_t j = 0; j < m; j++) {
+            const uint32_t e = C.blk0 + i + j;
+            uint32_t t = da.get(e);                                               // fp32 bits (RAW) or zero
+            if (!raw) t = (uint32_t)unzigzag(t);
+            if (MODE == MODE_DECOMPRESS) A.out[C.f0 + e] = raw ? __uint_as_float(t) : dequantize1((int32_t)t, A.step);
+            else if (MODE == MODE_STAGE_A) { if (raw) X.sa.a32[C.f0 + e] = t; else X.sa.put_code(C.f0, C.nf, e, (int32_t)t, wide_seen); }
+            else X.finish(C, e, t, zmax, overflow);
+        }
+    }
+    if (MODE == MODE_STAGE_A && wide_seen) S->flags = 1u;
+}
+
+// FIXEDLEN frames, the streaming way: a pass of NT * 4 elements is NT * w / 8 whole words of the payload (at a 16-byte
+// boundary), which the workgroup copies into shared memory with 16-byte loads (the next pass's words are requested
+// before this pass is worked on); every thread then cuts its four consecutive codes out of the copy.  Two copies
+// alternate (they live in the window area, which only HUFFMAN frames use), so one barrier per pass is enough.
+// DELTA: the running sums of a segment are a scan over the wavefront that holds it.
+template <int MODE, int NT, int DELTA>
+__device__ inline void run_fixed(const DecodeArgs& A, const SegCtx& C, const FrameView& V, DecShared<NT>* S,
+                                 const AddCtx& X, uint32_t (&zmax)[2], uint32_t& overflow) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    constexpr uint32_t kPass = NT * 4;                                   // elements per pass
+    static_assert(2 * (kPass + 8) <= NT * kWinWords, "two pass copies fit the window area");
+    const uint32_t cnt = (C.nf - C.blk0 < NT * kSeg) ? (C.nf - C.blk0) : NT * kSeg;
+    const uint32_t w = V.w, tid = C.tid;
+    const uint32_t mask = (w >= 32u) ? 0xFFFFFFFFu : ((1u << w) - 1u);
+    const uint32_t pass_words = (kPass / 32u) * w;                       // words of a whole pass (at most kPass)
+    uint32_t wide_seen = 0;
+    // words [4 tid, 4 tid + 4) of the pass that starts at element `base` of the block (zero where the payload ends)
+    auto fetch = [&](uint32_t base) -> u32x4 {
+        u32x4 x = { 0u, 0u, 0u, 0u };
+        if (base >= cnt) return x;
+        const uint32_t g0 = ((C.blk0 + base) >> 5) * w + 4u * tid;        // first of my words in the payload
+        if (4u * tid >= pass_words || g0 >= V.nwords) return x;
+        if (g0 + 4u <= V.nwords) return *reinterpret_cast<const u32x4*>(V.words + g0);
+        x.x = V.words[g0];
+        if (g0 + 1u < V.nwords) x.y = V.words[g0 + 1u];
+        if (g0 + 2u < V.nwords) x.z = V.words[g0 + 2u];
+        return x;
+    };
+    u32x4 nxt = fetch(0);
+    uint32_t it = 0;
+    for (uint32_t base = 0; base < cnt; base += kPass, it++) {
+        uint32_t* buf = S->win + (it & 1u) * (kPass + 8u);
+        *reinterpret_cast<u32x4*>(buf + 4u * tid) = nxt;
+        nxt = fetch(base + kPass);
+        __syncthreads();
+        const uint32_t i = base + tid * 4u;
+        const uint32_t m = (i < cnt) ? ((cnt - i < 4u) ? (cnt - i) : 4u) : 0u;
+        uint32_t tv[4];
+        uint32_t pos = tid * 4u * w;
+#pragma unroll
+        for (uint32_t j = 0; j < 4; j++) {
+            const uint32_t k = pos >> 5;                                  // (k + 1 <= kPass + 3: inside the copy's slack)
+            tv[j] = (uint32_t)unzigzag(__builtin_amdgcn_alignbit(buf[k + 1u], buf[k], pos & 31u) & mask);
+            pos += w;
+        }
+        if (DELTA) {
+#pragma unroll
+            for (uint32_t j = 0; j < 4; j++) if (j >= m) tv[j] = 0;       // (elements past the end add nothing)
             tv[1] += tv[0]; tv[2] += tv[1]; tv[3] += tv[2];
             const uint32_t before = wave_incl_scan_dpp(tv[3]) - tv[3];
             tv[0] += before; tv[1] += before; tv[2] += before; tv[3] += before;
         }
-        for (uint32_t j = 0; j < m; j++) {
-            const uint32_t e = C.blk0 + i + j;
-            const uint32_t t = tv[j];
-            if (MODE == MODE_DECOMPRESS) A.out[C.f0 + e] = raw ? __uint_as_float(t) : dequantize1((int32_t)t, A.step);
-            else if (MODE == MODE_STAGE_A) { if (raw) X.sa.a32[C.f0 + e] = t; else X.sa.put_code(C.f0, C.nf, e, (int32_t)t, wide_seen); }
-            else X.finish(C, e, t, zmax, overflow);
+        if (MODE == MODE_DECOMPRESS && m == 4u && C.vec_ok) {
+            f32x4 v;
+            v.x = dequantize1((int32_t)tv[0], A.step); v.y = dequantize1((int32_t)tv[1], A.step);
+            v.z = dequantize1((int32_t)tv[2], A.step); v.w = dequantize1((int32_t)tv[3], A.step);
+            __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(A.out + C.f0 + C.blk0 + i));
+        } else {
+            for (uint32_t j = 0; j < m; j++) {
+                const uint32_t e = C.blk0 + i + j;
+                if (MODE == MODE_DECOMPRESS) A.out[C.f0 + e] = dequantize1((int32_t)tv[j], A.step);
+                else if (MODE == MODE_STAGE_A) X.sa.put_code(C.f0, C.nf, e, (int32_t)tv[j], wide_seen);
+                else X.finish(C, e, tv[j], zmax, overflow);
+            }
         }
     }
     if (MODE == MODE_STAGE_A && wide_seen) S->flags = 1u;
@@ -873,8 +937,10 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
         run_huff<MODE, NT, DELTA>(A, C, ra, &S, V.dense, X, a_wide, zmax, overflow);
         late = seg_valid && (ra.bad || ra.consumed() != seglen);
         if (MODE != MODE_DECOMPRESS && late) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
+    } else if (V.kind == KIND_FIXED) {
+        run_fixed<MODE, NT, DELTA>(A, C, V, &S, X, zmax, overflow);
     } else {
-        run_elementwise<MODE, NT, DELTA>(A, C, da, &S, X, zmax, overflow);
+        run_elementwise<MODE, NT>(A, C, da, &S, X, zmax, overflow);
     }
     if (MODE == MODE_DECOMPRESS) {
         // a frame found corrupt only now has been written already: k_decode_finish clears it again
