@@ -826,3 +826,32 @@ def test_other_segment_sizes_are_refused_by_every_entry_point(nz, seg):
     rc, r, _ = gpu_decompress(nz, so, n, eb, good)
     assert r["status"] == nz.ERR_MISMATCH
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("predictor", [0, 1], ids=["plain", "delta"])
+def test_fixedlen_every_width_by_doubling(nz, predictor):
+    """Pinned FIXEDLEN through a chain of self-reductions: every reduce doubles the codes, so the width grows by one
+    bit per step from what the data needs up to 31 (32 with the predictor), until a sum passes 2^30 and its frame
+    turns RAW.  Frames of 20000 elements with a ragged tail, so passes end inside a word and inside a 16-byte group."""
+    n, eb = 70001, float(np.float32(32.0 / 63.0))                       # step = 1: x = q
+    rng = np.random.default_rng(77)
+    q = rng.integers(-5, 6, n).astype(np.float32)
+    q[[3, 4, 20000, 45000, n - 1]] = [32767.0, -32767.0, -32767.0, 20001.0, -17.0]   # full-range codes, two of them adjacent
+    kw = dict(chunk_elems=20000, force_codec=1, predictor=predictor)
+    g, o = _opts_pair(nz, **kw)
+    acc, ores, orc = oracle.compress(q, eb, o)
+    rc, r, got = gpu_compress(nz, q, eb, g)
+    assert orc == 0 and r["status"] == 0 and _first_diff(got, acc) == -1
+    saw_raw = False
+    for step in range(17):
+        ref, ores, orc = oracle.reduce_frames(acc, acc, n, eb, o)
+        rc, r, got = gpu_reduce(nz, acc, acc, n, eb, g)
+        assert orc == 0 and rc == 0 and r["status"] == 0, (step, r)
+        assert (r["n_raw"], r["n_fixed"], r["n_huff"], r["bytes"]) == (ores.n_raw, ores.n_fixed, ores.n_huff, ores.bytes), step
+        assert _first_diff(got, ref) == -1, (step, _first_diff(got, ref))
+        rc, r, y = gpu_decompress(nz, ref, n, eb, g)
+        want = oracle.decompress(ref, n, eb)[0]
+        assert r["status"] == 0 and (y.view(np.uint32) == want.view(np.uint32)).all(), step
+        saw_raw = saw_raw or ores.n_raw > 0
+        acc = ref
+    assert saw_raw                                                      # 32767 * 2^16 > 2^30: the chain reached the RAW fallback
