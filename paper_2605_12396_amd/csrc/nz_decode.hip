@@ -63,6 +63,7 @@ struct FrameView {
     const uint16_t* segt;
     uint64_t seg_prefix;      // bits before this workgroup's first segment
     bool dense;               // HUFFMAN: 6 or more bits per symbol on average (the window is renewed every run, not every phase)
+    bool hot_esc;             // escapes are frequent in this frame (short escape code / codes wider than the alphabet)
 };
 
 // Build-time scratch shared by both operands.
@@ -90,6 +91,7 @@ __device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t fra
                                   const DecodeArgs& A, DecTables* T, BuildScratch* B, FrameView& V) {
     const uint32_t tid = threadIdx.x;
     V.status = ST_CORRUPT; V.kind = KIND_ZERO; V.w = 0; V.words = nullptr; V.nwords = 0; V.segt = nullptr; V.seg_prefix = 0; V.dense = false;
+    V.hot_esc = false;
     const uint64_t off = *reinterpret_cast<const uint64_t*>(s + kStreamHdr + 8ull * frame);
     if ((off & 15u) || off < kStreamHdr + pad16d(8ull * A.n_frames) || off + kHdrBytes > total) return;
     const uint8_t* fr = s + off;
@@ -110,7 +112,7 @@ __device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t fra
         if (p0 > 32u || (p1 & 0x7FFFFFFFu) || (p1 >> 31) != A.pred) return;   // (the stream's predictor is the caller's: checked before)
         const uint64_t need = 4ull * (((uint64_t)nf * p0 + 31u) / 32u);
         if (payload != need) return;
-        V.status = ST_OK; V.kind = KIND_FIXED; V.w = p0;
+        V.status = ST_OK; V.kind = KIND_FIXED; V.w = p0; V.hot_esc = (p0 >= 32u) || ((1u << p0) > A.K);
         V.words = reinterpret_cast<const uint32_t*>(pay); V.nwords = payload / 4;
         return;
     }
@@ -224,6 +226,7 @@ __device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t fra
     __syncthreads();
     V.status = ST_OK; V.kind = KIND_HUFF; V.segt = segt; V.seg_prefix = pre_bits;
     V.dense = all_bits >= 6ull * nf;
+    V.hot_esc = B->len[0] != 0 && B->len[0] <= 6u;                   // the escape symbol has a probability of a percent or more
     V.words = reinterpret_cast<const uint32_t*>(pay + tables); V.nwords = (uint32_t)((payload - tables) / 4);
 }
 
@@ -557,7 +560,7 @@ struct AddCtx {
 // that does not fit 16 bits is finished by the decoding lane like a wide escape.
 template <int MODE, int NT, int DELTA>
 __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader<NT>& ra, DecShared<NT>* S, bool dense,
-                                const AddCtx& X, bool a_wide, uint32_t (&zmax)[2], uint32_t& overflow) {
+                                bool hot_esc, const AddCtx& X, bool a_wide, uint32_t (&zmax)[2], uint32_t& overflow) {
     const uint32_t tid = C.tid;
     uint16_t* tile = S->u.tile;
     uint32_t* row32 = reinterpret_cast<uint32_t*>(tile + tid * kTile16Stride);
@@ -694,11 +697,27 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
                 Q[2] = (int32_t)(int16_t)(p1 & 0xFFFFu) + (int32_t)(int16_t)(pa[k].y & 0xFFFFu);
                 Q[3] = ((int32_t)p1 >> 16) + ((int32_t)pa[k].y >> 16);
                 }
+                if (hot_esc) {
+                    // Where escapes are frequent (sums of many peers: most codes leave the alphabet) they all hit one
+                    // bin, whose few copies serialise the wave.  They are counted per wavefront and added once; the
+                    // whole wave is here and h is the same for all of it.  (Uniform branch: the incoming frame's kind.)
+                    uint32_t wave_esc = 0;
 #pragma unroll
-                for (uint32_t j = 0; j < 4; j++) {
-                    const uint32_t z = zigzag(Q[j]);
-                    zmax[h] = z > zmax[h] ? z : zmax[h];
-                    atomicAdd(&X.s_h[h * 1024u + (bin_of(z, X.K) << X.ncs) + X.copy], 1u);
+                    for (uint32_t j = 0; j < 4; j++) {
+                        const uint32_t z = zigzag(Q[j]);
+                        zmax[h] = z > zmax[h] ? z : zmax[h];
+                        const bool esc = z >= X.K - 1u;
+                        wave_esc += (uint32_t)__builtin_popcountll(__ballot(esc));
+                        if (!esc) atomicAdd(&X.s_h[h * 1024u + (z << X.ncs) + X.copy], 1u);
+                    }
+                    if (C.lane == 0 && wave_esc) atomicAdd(&X.s_h[h * 1024u + ((X.K - 1u) << X.ncs)], wave_esc);
+                } else {
+#pragma unroll
+                    for (uint32_t j = 0; j < 4; j++) {
+                        const uint32_t z = zigzag(Q[j]);
+                        zmax[h] = z > zmax[h] ? z : zmax[h];
+                        atomicAdd(&X.s_h[h * 1024u + (bin_of(z, X.K) << X.ncs) + X.copy], 1u);
+                    }
                 }
                 // operands of 16 bits (|q| <= 32767 from the quantizer too): |Q| <= 65534; a sum outside the 16-bit codes
                 // is rare and goes to the 32-bit array
@@ -879,6 +898,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
 
     FrameView V;
     V.status = ST_OK; V.kind = KIND_ZERO; V.w = 0; V.words = nullptr; V.nwords = 0; V.segt = nullptr; V.seg_prefix = 0; V.dense = false;
+    V.hot_esc = false;
     if (st_a == ST_OK && st_b == ST_OK) {
         open_frame<NT>(MODE == MODE_ADD_B ? A.b : A.a, MODE == MODE_ADD_B ? total_b : total_a, frame, nf, first_seg, A,
                        &s_t, &S.u.build, V);
@@ -934,7 +954,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
 
     bool late = false;                                                  // a segment that did not use exactly its recorded bits
     if (V.kind == KIND_HUFF) {
-        run_huff<MODE, NT, DELTA>(A, C, ra, &S, V.dense, X, a_wide, zmax, overflow);
+        run_huff<MODE, NT, DELTA>(A, C, ra, &S, V.dense, V.hot_esc, X, a_wide, zmax, overflow);
         late = seg_valid && (ra.bad || ra.consumed() != seglen);
         if (MODE != MODE_DECOMPRESS && late) atomicMax(&res->status, (uint32_t)ST_CORRUPT);
     } else if (V.kind == KIND_FIXED) {
