@@ -281,7 +281,7 @@ __global__ __launch_bounds__(kBookThreads) void k_codebook(CompressArgs A) {
     __shared__ uint32_t s_f[kMaxK];
     __shared__ BookShared s_b;
     __shared__ uint64_t s_part[16];
-    __shared__ uint32_t s_fid, s_zmax, s_unq, s_codec, s_payload, s_total, s_w_fixed;
+    __shared__ uint32_t s_fid, s_zmax, s_unq, s_codec, s_payload, s_total, s_w_fixed, s_skip;
     __shared__ uint64_t s_bits, s_off;
     uint32_t* const s_w = s_b.w;
     uint8_t* const s_len = s_b.len;
@@ -310,12 +310,28 @@ __global__ __launch_bounds__(kBookThreads) void k_codebook(CompressArgs A) {
         // reduce: a sum beyond 2^30 somewhere in the frame has turned it RAW (its fp32 sums were staged by k_fix)
         if (!A.in) atomicMax(&s_unq, reinterpret_cast<const uint32_t*>(A.ws + A.L.cwide)[(size_t)fid * A.sbpf + tid] & 2u);
     }
+    __syncthreads();
+    // Frames that cannot end up HUFFMAN skip the code construction (most of this kernel's latency): a frame that is
+    // RAW anyway, a pinned RAW / FIXEDLEN, and a frame whose HUFFMAN bitstream is bound to be at least as long as
+    // FIXEDLEN's -- every symbol costs a bit and every escape 32 more, so bits >= n_f + 32 * escapes; if that reaches
+    // n_f * w, HUFFMAN's payload (tables on top) exceeds FIXEDLEN's and FIXEDLEN, the lower codec id, wins any tie,
+    // while a gate that rejects FIXEDLEN's payload rejects the larger one too.
+    if (tid == 0) {
+        const uint32_t zmax = s_zmax;
+        const uint64_t w = zmax ? (32u - (uint32_t)__clz(zmax)) : 0u;
+        bool skip = s_unq != 0;
+        if (A.force_codec >= 0) skip = skip || A.force_codec != (int32_t)CODEC_HUFF;
+        else skip = skip || ((uint64_t)nf + 32ull * s_f[0] >= (uint64_t)nf * w);
+        s_skip = skip ? 1u : 0u;
+    }
+    __syncthreads();
+    const bool skip = s_skip != 0;
     // (2)-(5) code lengths and canonical codes
-    uint32_t L, code;
-    book_build(s_b, f, K, L, code);
-    const uint32_t nsym = s_b.nsym;
-    // (6) exact Huffman bitstream length: sum f*len, an escape carries 32 more bits
-    {
+    uint32_t L = 0, code = 0, nsym = 0;
+    if (!skip) {
+        book_build(s_b, f, K, L, code);
+        nsym = s_b.nsym;
+        // (6) exact Huffman bitstream length: sum f*len, an escape carries 32 more bits
         uint64_t b = (uint64_t)f * L + (tid == 0 ? 32ull * f : 0ull);
         b = wave_sum64(b);
         if (lane == 0) s_part[wave] = b;
@@ -323,8 +339,8 @@ __global__ __launch_bounds__(kBookThreads) void k_codebook(CompressArgs A) {
     __syncthreads();
     // (7) sizes and arbitration (Eq. 2: argmin of frame bytes over RAW + admissible codecs, ties to the lower id)
     if (tid == 0) {
-        uint64_t bits = 0;
-        for (int i = 0; i < 16; i++) bits += s_part[i];
+        uint64_t bits = skip ? (1ull << 40) : 0ull;               // (skipped: larger than any RAW payload, never admissible)
+        if (!skip) for (int i = 0; i < 16; i++) bits += s_part[i];
         const uint32_t zmax = s_zmax;
         const uint32_t w = zmax ? (32u - (uint32_t)__clz(zmax)) : 0u;
         const uint32_t nseg = (nf + kSeg - 1) / kSeg;
