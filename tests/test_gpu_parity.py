@@ -702,6 +702,45 @@ def test_calls_can_be_captured_in_a_hip_graph(nz):
         assert (y.cpu().numpy().view(np.uint32) == y_ref.view(np.uint32)).all(), rep
 
 
+def test_calls_on_two_streams_with_their_own_buffers_run_side_by_side(nz):
+    """Two calls may overlap in time when they share nothing but read-only inputs: each stream here has its own
+    workspace, output and result record (the library keeps no state).  Both results must be the oracle's, run after
+    run."""
+    import torch
+    n, eb = 700000, 1e-4
+    g, o = _opts_pair(nz, chunk_elems=65536)
+    xs = [W.gradient_like(n, seed=31), W.sweep_payload("uniform", n, 32)]
+    refs = [oracle.compress(x, eb, o)[0] for x in xs]
+    ref_red = oracle.reduce_frames(refs[0], refs[1], n, eb, o)[0]
+    dxs = [_to_dev(nz, x) for x in xs]
+    sess = [nz.Session(n, g, "cuda:0", reduce=True) for _ in range(2)]
+    outs = [s_.new_stream_buffer() for s_ in sess]
+    ys = [torch.empty(n, dtype=torch.float32, device="cuda:0") for _ in range(2)]
+    reds = [s_.new_stream_buffer() for s_ in sess]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]                 # default priority
+    torch.cuda.synchronize()
+    for rep in range(4):
+        for k in range(2):
+            with torch.cuda.stream(streams[k]):
+                st = streams[k]
+                assert nz.nz_compress(dxs[k], n, eb, outs[k], sess[k].cap, sess[k].res, g, sess[k].ws, sess[k].ws_bytes, stream=st) == 0
+        torch.cuda.synchronize()
+        for k in range(2):
+            r = sess[k].result()
+            assert r["status"] == 0 and r["bytes"] == refs[k].size and _first_diff(outs[k][:r["bytes"]].cpu().numpy(), refs[k]) == -1, (rep, k)
+        # a decompress of stream 0 beside a reduce of both
+        with torch.cuda.stream(streams[0]):
+            assert nz.nz_decompress(outs[0], refs[0].size, ys[0], n, eb, sess[0].res, g, sess[0].ws, sess[0].ws_bytes,
+                                    stream=streams[0]) == 0
+        with torch.cuda.stream(streams[1]):
+            assert nz.nz_reduce_frames(outs[0], refs[0].size, outs[1], refs[1].size, reds[1], sess[1].cap, n, eb, sess[1].res, g,
+                                       sess[1].ws, sess[1].ws_bytes, stream=streams[1]) == 0
+        torch.cuda.synchronize()
+        assert sess[0].result()["status"] == 0 and sess[1].result()["status"] == 0
+        assert (ys[0].cpu().numpy().view(np.uint32) == oracle.decompress(refs[0], n, eb)[0].view(np.uint32)).all(), rep
+        assert _first_diff(reds[1][:ref_red.size].cpu().numpy(), ref_red) == -1, rep
+
+
 # ------------------------------------------------------------------------------------------------
 # exact ties, deepest codes, many second-level tables, refused options
 # ------------------------------------------------------------------------------------------------
