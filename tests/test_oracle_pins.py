@@ -816,3 +816,35 @@ def test_reduce_local_raw_values_range_and_mismatch():
     z2 = z.copy(); z2[7] = -z[7]
     s3, res3, rc = oracle.reduce_local(s1, z2, eb, o1)
     assert rc == 0 and res3.n_raw == 0
+
+
+@pytest.mark.parametrize("eb", [2.0 ** -100, 2.0 ** -60, 1e-10, 1e-5, 2.656e-4, 0.5079365, 1.0, 7.3, 1e10, 2.0 ** 100])
+def test_range_test_alone_decides_quantizability(eb):
+    """The acceptance rule has two tests, |u| <= 32767 and fl32(|x - xhat|) <= eb.  With bins of eb*63/32 the second
+    follows from the first: |x - xhat| <= step*(1/2 + 32767*(2^-23 + 2^-24)) = 0.50586*step < eb = 0.50794*step.  So the
+    oracle's verdict must equal the range test alone -- on rounding boundaries, at the ends of the range, on random
+    values, on denormals and non-finite values -- which is what lets a kernel skip the second test."""
+    eb = float(np.float32(eb))
+    step, inv = oracle.step_constants(eb)
+    rng = np.random.default_rng(int(abs(np.log2(eb)) * 1000) + 1)
+    k = np.concatenate([np.arange(-32775, -32700), np.arange(-40, 40), np.arange(32700, 32775),
+                        rng.integers(-32768, 32768, 200000)]).astype(np.float64)
+    parts = []
+    with np.errstate(over="ignore", invalid="ignore"):
+        for frac in (0.5, 0.0, 0.25, 0.49999, 0.50001):
+            c = ((k + frac) * np.float64(step)).astype(np.float32)
+            for d in (-2, -1, 0, 1, 2):                                  # the value and its neighbours in fp32
+                parts.append((c.view(np.int32) + d).view(np.float32))
+        parts.append((rng.uniform(-33000, 33000, 500000) * np.float64(step)).astype(np.float32))
+    tiny = np.array([0.0, -0.0, 1e-45, -1e-45, 1.1754942e-38, -1.1754942e-38, 1.1754944e-38, np.inf, -np.inf, np.nan,
+                     3.4028235e38, -3.4028235e38], np.float32)
+    x = np.concatenate(parts + [tiny])
+    q, ok = oracle.quantize(x, eb)
+    with np.errstate(over="ignore", invalid="ignore"):
+        u = x * inv                                                        # one fp32 product, as the quantizer forms it
+        want = np.abs(u) <= np.float32(32767.0)                            # False for NaN
+    assert (ok == want).all(), x[ok != want][:8]
+    # and the bound itself, in float64, wherever a value was accepted
+    xh = q[ok].astype(np.float64) * np.float64(step)
+    fin = np.isfinite(x[ok])
+    assert fin.all() and (np.abs(x[ok].astype(np.float64) - np.float32(xh).astype(np.float64)) <= eb).all()
