@@ -566,9 +566,10 @@ def main():
     for st in names:
         t = stage_ms[st] * 1e-3
         traffic = None
-        parts = [read_traffic(args.traffic_file, wl["name"], "%s/%s" % (st, nm)) for nm in names[st] if nm not in ("init", "fix", "finish")]
-        if parts and all(v is not None for v in parts):
-            traffic = sum(parts)
+        # every kernel of the operation that the counter summary lists (the tiny init kernel may be absent from it)
+        parts = {nm: read_traffic(args.traffic_file, wl["name"], "%s/%s" % (st, nm)) for nm in names[st]}
+        if all(v is not None for nm, v in parts.items() if nm != "init"):
+            traffic = sum(v for v in parts.values() if v is not None)
         ops[st] = dict(ms=stage_ms[st], input_GBps=gb / t, input_frac_hbm=gb / t / HBM_PEAK_GBPS,
                        algorithmic_bytes=alg_op[st], algorithmic_GBps=alg_op[st] / 1e9 / t,
                        algorithmic_frac_hbm=alg_op[st] / 1e9 / t / HBM_PEAK_GBPS,
