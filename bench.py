@@ -490,7 +490,7 @@ def main():
     names = {"compress": ["stats", "codebook", "encode"], "decompress": ["decode", "finish"],
              "reduce": ["init", "stage_a", "add_b", "fix", "codebook", "encode"],
              "reduce_local": ["init", "add_local", "fix", "codebook", "encode"],
-             "compress_rea": ["plan", "encode", "finish"]}
+             "compress_rea": ["encode", "finish"]}
     acc = {k: [0.0] * len(v) for k, v in names.items()}
     reps = max(5, min(args.steps, 20))
 

@@ -10,7 +10,7 @@
  *   nz_decompress     decode, finish (result record, zero-fill of rejected frames)
  *   nz_reduce_frames  init, stage A, decode B + add, fix (late RAW frames), codebook + selector, encode
  *   nz_reduce_local   init, decode + quantize local + add, fix, codebook + selector, encode
- *   nz_compress_rea   plan, encode, finish
+ *   nz_compress_rea   encode (every workgroup profiles the frame's sample first), finish
  * (nz_compress_sr, nz_compress_static: as nz_compress; the *_step forms as their namesakes.  With the delta
  * predictor the reduces run one more kernel, the statistics of the staged sums, inside the "codebook" interval.)
  */

@@ -224,7 +224,7 @@ __host__ inline ReaLayout rea_layout(size_t n, uint32_t chunk) {
     const size_t n_frames = (n + chunk - 1) / chunk;
     const size_t gpf = (chunk + kEncGroup - 1) / kEncGroup;
     size_t o = 0;
-    L.fail = o;  o += align_up(4 * n_frames, 256);
+    L.fail = o;  o += align_up(4 * n_frames * gpf, 256);          // one failure flag per encoder group
     L.meta = o;  o += align_up(sizeof(FrameMeta) * n_frames, 256);
     L.gbits = o; o += align_up(4 * n_frames * gpf, 256);
     L.tmp = o;   o += gpf > 1 ? align_up(4 * (size_t)kReaTmpWords * n_frames * gpf, 256) : 0;   // (a one-group frame is coded in place)
@@ -268,6 +268,8 @@ struct CompressArgs {
     // sampled arbitration only (encoder source 2): the cached code, where each group's bitstream is materialised
     // before the frame's groups are packed together, the groups' realized bit counts and the frames' failure flags
     const DevContext* rea_ctx; uint32_t* rea_tmp; uint32_t* rea_gbits; uint32_t* rea_fail;
+    uint32_t rea_sample_elems, rea_small_batch_bytes;   // SampleWindow in elements, SmallBatchFastPath threshold
+    uint64_t rea_slot;        // bytes between frame starts of the slotted stream
 };
 
 // Result record as laid out by nz_result in the public header.

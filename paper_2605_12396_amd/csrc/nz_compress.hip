@@ -671,6 +671,102 @@ __device__ inline void enc_raw_fixed(const CompressArgs& A, const EncGroup& G, c
     }
 }
 
+// Sampled arbitration, ProfileSample + ArbitratePlan (Sec. IV-C, Algorithm 1), run by every encoder workgroup of a frame
+// for itself (the sample is at most 64 KiB and hot in L2 after its first reader; a kernel of its own would cost more
+// than the repeated profiling).  The sample is the frame's prefix; FIXEDLEN's width is the bit length of the sample's
+// largest zigzag code, HUFFMAN's size the sample's bits under the context scaled to the frame (rounded up);
+// admissibility (fits the payload capacity = RAW size, minimum gain, context valid, T_huff) and Eq. 2 with transmitted
+// size as the cost, ties to the lower codec id.  Leaves the context's code in S.book when the context is valid.  The
+// frame's first group also writes the plan, the frame's entry of the offsets table (slots are fixed) and, for frame 0,
+// the stream header and the cleared result record, for the finishing kernel.
+__device__ inline FrameMeta rea_plan_frame(const CompressArgs& A, uint32_t frame, uint64_t f0, uint32_t nf, uint32_t gb, EncShared& S) {
+    const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6, K = A.K;
+    const bool ctx_ok = A.rea_ctx && A.rea_ctx->valid == 1u && A.rea_ctx->K == K;
+    const uint64_t base = kStreamHdr + pad16u(8ull * A.n_frames);
+    uint32_t* s_red = S.wtot;                    // [0] largest zigzag code, [1] unquantizable flag, [2..9] the waves' bit sums
+    static_assert(kEncSegs >= 10 && kEncThreads == 256, "the reduction scratch of the plan fits the segment totals");
+    if (tid == 0) {
+        s_red[0] = 0; s_red[1] = 0;
+        A.rea_fail[(size_t)frame * A.sbpf + gb] = 0;
+        if (gb == 0) {
+            *reinterpret_cast<uint64_t*>(A.out + kStreamHdr + 8ull * frame) = base + (uint64_t)frame * A.rea_slot;
+            if (frame == A.n_frames - 1 && (A.n_frames & 1u)) *reinterpret_cast<uint64_t*>(A.out + kStreamHdr + 8ull * A.n_frames) = 0;
+            if (frame == 0) {
+                ReaResultRec* res = reinterpret_cast<ReaResultRec*>(A.res);
+                res->span_bytes = 0; res->wire_bytes = 0; res->status = ST_OK; res->n_frames = A.n_frames;
+                res->n_raw = 0; res->n_fixed = 0; res->n_huff = 0; res->n_fallback = 0;
+                uint32_t* sh = reinterpret_cast<uint32_t*>(A.out);
+                sh[0] = kMagicStream; sh[1] = 1u; sh[2] = (uint32_t)A.n; sh[3] = (uint32_t)(A.n >> 32);
+                sh[4] = A.chunk; sh[5] = A.n_frames; sh[6] = A.step_bits; sh[7] = kSeg; sh[8] = K; sh[9] = 0;
+                sh[10] = 0; sh[11] = 0; sh[12] = 0; sh[13] = 0; sh[14] = 0; sh[15] = 0;     // total_bytes: the finishing kernel
+            }
+        }
+    }
+    if (ctx_ok) for (uint32_t b = tid; b < K; b += kEncThreads) S.book[b] = A.rea_ctx->book[b];
+    __syncthreads();
+    const uint64_t rawb = 4ull * nf;
+    const bool profiled = rawb >= A.rea_small_batch_bytes;               // SmallBatchFastPath
+    const uint32_t n_s = profiled ? (A.rea_sample_elems < nf ? A.rea_sample_elems : nf) : 0u;
+    uint32_t zmax = 0, bad = 0;
+    uint64_t bits = 0;
+    auto profile1 = [&](float x) {
+        int32_t q;
+        if (!quantize1(x, A.eb, A.step, A.inv_step, q)) bad = 1;
+        const uint32_t z = zigzag(q);
+        zmax = z > zmax ? z : zmax;
+        if (ctx_ok) { const uint32_t b = bin_of(z, K); bits += (uint32_t)(S.book[b] >> 32) + (b == K - 1u ? 32u : 0u); }
+    };
+    const float* sp = A.in + f0;
+    uint32_t i = 0;
+    if ((f0 & 3u) == 0) {                        // eight 16-byte loads in flight per thread
+        constexpr uint32_t kBatch = 8 * kEncThreads * 4;
+        for (; i + kBatch <= n_s; i += kBatch) {
+            float4 t[8];
+#pragma unroll
+            for (uint32_t u = 0; u < 8; u++) t[u] = reinterpret_cast<const float4*>(sp + i)[u * kEncThreads + tid];
+#pragma unroll
+            for (uint32_t u = 0; u < 8; u++) { profile1(t[u].x); profile1(t[u].y); profile1(t[u].z); profile1(t[u].w); }
+        }
+    }
+    for (uint32_t k = i + tid; k < n_s; k += kEncThreads) profile1(sp[k]);
+    zmax = wave_max(zmax); bad = wave_max(bad); bits = wave_sum64(bits);
+    if (lane == 0) { atomicMax(&s_red[0], zmax); atomicMax(&s_red[1], bad); reinterpret_cast<uint64_t*>(s_red + 2)[wave] = bits; }
+    __syncthreads();
+    // every thread draws the same conclusion from the same numbers
+    uint32_t plan = CODEC_RAW;
+    const uint32_t zm = s_red[0];
+    const uint32_t w = zm ? (32u - (uint32_t)__clz(zm)) : 0u;
+    const uint32_t nseg = (nf + kSeg - 1) / kSeg;
+    if (n_s && !s_red[1]) {
+        const uint64_t* wb = reinterpret_cast<const uint64_t*>(s_red + 2);
+        const uint64_t sample_bits = wb[0] + wb[1] + wb[2] + wb[3];
+        const uint64_t pred_bits = (sample_bits * nf + n_s - 1) / n_s;
+        uint64_t pay[3];
+        pay[CODEC_RAW] = rawb;
+        pay[CODEC_FIXED] = 4ull * (((uint64_t)nf * w + 31u) / 32u);
+        pay[CODEC_HUFF] = pad4u(K) + pad4u(2ull * nseg) + 4ull * ((pred_bits + 31u) / 32u);
+        if (A.force_codec >= 0) plan = (A.force_codec == (int32_t)CODEC_HUFF && !ctx_ok) ? (uint32_t)CODEC_RAW : (uint32_t)A.force_codec;
+        else {
+            uint64_t best_total = pad16u(kHdrBytes + rawb);
+            for (uint32_t c = CODEC_FIXED; c <= CODEC_HUFF; c++) {
+                if (c == CODEC_HUFF && (!ctx_ok || rawb < A.huff_min_bytes)) continue;
+                if (pay[c] > rawb) continue;
+                if ((rawb - pay[c]) * 1000ull < (uint64_t)A.min_gain_permil * rawb) continue;
+                const uint64_t t = pad16u(kHdrBytes + pay[c]);
+                if (t < best_total) { best_total = t; plan = c; }
+            }
+        }
+    }
+    FrameMeta M;
+    M.offset = base + (uint64_t)frame * A.rea_slot; M.total = 0; M.payload = 0; M.codec = plan; M.w = w; M.nsym = K; M.fits = 1u;
+    M.segt_off = kHdrBytes + (uint32_t)pad4u(K);
+    M.bits_off = (plan == CODEC_HUFF) ? (M.segt_off + (uint32_t)pad4u(2ull * nseg)) : kHdrBytes;
+    M.bits_words = 0; M.pad_ = 0; M.huff_bits = 0; M.pad2_ = 0;
+    if (gb == 0 && tid == 0) reinterpret_cast<FrameMeta*>(A.ws + A.L.meta)[frame] = M;
+    __syncthreads();                             // the scratch is the encoder's again
+    return M;
+}
+
 template <int SRC, int QM = 0, int DELTA = 0>
 __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))) void k_encode(CompressArgs A) {
     __shared__ EncShared S;
@@ -694,7 +790,9 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
     if (SRC == 1) G.wide16 = reinterpret_cast<const uint32_t*>(A.ws + A.L.cwide)[(size_t)frame * A.sbpf + G.g0 / A.stat_block] != 0;
     const uint32_t K = A.K, kesc = K - 1u;
 
-    const FrameMeta M = reinterpret_cast<const FrameMeta*>(A.ws + A.L.meta)[frame];
+    FrameMeta M;
+    if (SRC == 2) M = rea_plan_frame(A, frame, f0, G.nf, G.gb, S);
+    else M = reinterpret_cast<const FrameMeta*>(A.ws + A.L.meta)[frame];
     if (!M.fits) return;
     uint8_t* fr = A.out + M.offset;
     uint32_t bad = 0;                             // SRC 2: a value that cannot be coded as planned fails the frame
@@ -705,7 +803,7 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
         uint32_t raw[kEncIters][4];
         enc_load<SRC>(G, 0, raw);
         if (SRC == 2) {
-            for (uint32_t s = tid; s < K; s += kEncThreads) S.book[s] = A.rea_ctx->book[s];
+            // (the plan left the context's code in S.book)
         } else {
             for (uint32_t s = tid; s < K; s += kEncThreads) {
                 const uint32_t sy = (s == kesc) ? 0u : s + 1u;
@@ -878,7 +976,7 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
         if (SRC == 2 && tid == 0) A.rea_gbits[(size_t)frame * gpf + G.gb] = flushed * 32u + rel;     // realized bits of the group
     }
     if (SRC == 2) {              // (header, padding and the packing of the groups are the finishing kernel's)
-        if (bad) atomicOr(A.rea_fail + frame, 1u);
+        if (bad) atomicOr(A.rea_fail + (size_t)frame * gpf + G.gb, 1u);
         return;
     }
     if (G.last_grp) {            // the frame's last group zero-fills the padding after the payload
@@ -936,98 +1034,6 @@ hipError_t launch_context(const float* sample, uint64_t n, float eb, float step,
     return hipGetLastError();
 }
 
-// ProfileSample + ArbitratePlan, one workgroup per frame: the sample is the frame's prefix; FIXEDLEN's width is the
-// bit length of the sample's largest zigzag code, HUFFMAN's size the sample's bits under the context scaled to the
-// frame (rounded up); admissibility (fits the payload capacity = RAW size, minimum gain, context valid, T_huff) and
-// Eq. 2 with transmitted size as the cost, ties to the lower codec id.  Also clears what the encoder's look-back
-// needs and writes the offsets table (slots are fixed) and the stream header.
-__global__ __launch_bounds__(256) void k_rea_plan(ReaArgs A) {
-    __shared__ uint8_t s_l[kMaxK];
-    __shared__ uint64_t s_bits[4];
-    __shared__ uint32_t s_zmax, s_bad;
-    const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
-    const uint32_t frame = blockIdx.x, K = A.K;
-    const uint64_t f0 = (uint64_t)frame * A.chunk;
-    const uint32_t nf = (uint32_t)((A.n - f0 < A.chunk) ? (A.n - f0) : A.chunk);
-    const uint64_t base = kStreamHdr + pad16u(8ull * A.n_frames);
-    const bool ctx_ok = A.ctx && A.ctx->valid == 1u && A.ctx->K == K;
-    // housekeeping for the next kernels
-    if (tid == 0) {
-        reinterpret_cast<uint32_t*>(A.ws + A.L.fail)[frame] = 0;
-        *reinterpret_cast<uint64_t*>(A.out + kStreamHdr + 8ull * frame) = base + (uint64_t)frame * A.slot;
-        if (frame == A.n_frames - 1 && (A.n_frames & 1u)) *reinterpret_cast<uint64_t*>(A.out + kStreamHdr + 8ull * A.n_frames) = 0;
-        s_zmax = 0; s_bad = 0;
-    }
-    if (frame == 0 && tid == 0) {
-        ReaResultRec* res = reinterpret_cast<ReaResultRec*>(A.res);
-        res->span_bytes = 0; res->wire_bytes = 0; res->status = ST_OK; res->n_frames = A.n_frames;
-        res->n_raw = 0; res->n_fixed = 0; res->n_huff = 0; res->n_fallback = 0;
-        uint32_t* sh = reinterpret_cast<uint32_t*>(A.out);
-        sh[0] = kMagicStream; sh[1] = 1u; sh[2] = (uint32_t)A.n; sh[3] = (uint32_t)(A.n >> 32);
-        sh[4] = A.chunk; sh[5] = A.n_frames; sh[6] = A.step_bits; sh[7] = kSeg; sh[8] = K; sh[9] = 0;
-        sh[10] = 0; sh[11] = 0; sh[12] = 0; sh[13] = 0; sh[14] = 0; sh[15] = 0;     // total_bytes: the finishing kernel
-    }
-    if (ctx_ok) for (uint32_t b = tid; b < K; b += 256) s_l[b] = (uint8_t)((uint32_t)(A.ctx->book[b] >> 32) + (b == K - 1u ? 32u : 0u));
-    __syncthreads();
-    const uint64_t rawb = 4ull * nf;
-    const bool profiled = rawb >= A.small_batch_bytes;                   // SmallBatchFastPath
-    const uint32_t n_s = profiled ? (A.sample_elems < nf ? A.sample_elems : nf) : 0u;
-    uint32_t zmax = 0, bad = 0;
-    uint64_t bits = 0;
-    auto profile1 = [&](float x) {
-        int32_t q;
-        if (!quantize1(x, A.eb, A.step, A.inv_step, q)) bad = 1;
-        const uint32_t z = zigzag(q);
-        zmax = z > zmax ? z : zmax;
-        if (ctx_ok) bits += s_l[bin_of(z, K)];
-    };
-    const float* sp = A.in + f0;
-    uint32_t i = 0;
-    if ((f0 & 3u) == 0) {                        // eight 16-byte loads in flight per thread
-        constexpr uint32_t kBatch = 8 * 256 * 4;
-        for (; i + kBatch <= n_s; i += kBatch) {
-            float4 t[8];
-#pragma unroll
-            for (uint32_t u = 0; u < 8; u++) t[u] = reinterpret_cast<const float4*>(sp + i)[u * 256 + tid];
-#pragma unroll
-            for (uint32_t u = 0; u < 8; u++) { profile1(t[u].x); profile1(t[u].y); profile1(t[u].z); profile1(t[u].w); }
-        }
-    }
-    for (uint32_t k = i + tid; k < n_s; k += 256) profile1(sp[k]);
-    zmax = wave_max(zmax); bad = wave_max(bad); bits = wave_sum64(bits);
-    if (lane == 0) { atomicMax(&s_zmax, zmax); atomicMax(&s_bad, bad); s_bits[wave] = bits; }
-    __syncthreads();
-    if (tid != 0) return;
-    uint32_t plan = CODEC_RAW;
-    const uint32_t w = s_zmax ? (32u - (uint32_t)__clz(s_zmax)) : 0u;
-    const uint32_t nseg = (nf + kSeg - 1) / kSeg;
-    if (n_s && !s_bad) {
-        const uint64_t sample_bits = s_bits[0] + s_bits[1] + s_bits[2] + s_bits[3];
-        const uint64_t pred_bits = (sample_bits * nf + n_s - 1) / n_s;
-        uint64_t pay[3];
-        pay[CODEC_RAW] = rawb;
-        pay[CODEC_FIXED] = 4ull * (((uint64_t)nf * w + 31u) / 32u);
-        pay[CODEC_HUFF] = pad4u(K) + pad4u(2ull * nseg) + 4ull * ((pred_bits + 31u) / 32u);
-        if (A.force_codec >= 0) plan = (A.force_codec == (int32_t)CODEC_HUFF && !ctx_ok) ? (uint32_t)CODEC_RAW : (uint32_t)A.force_codec;
-        else {
-            uint64_t best_total = pad16u(kHdrBytes + rawb);
-            for (uint32_t c = CODEC_FIXED; c <= CODEC_HUFF; c++) {
-                if (c == CODEC_HUFF && (!ctx_ok || rawb < A.huff_min_bytes)) continue;
-                if (pay[c] > rawb) continue;
-                if ((rawb - pay[c]) * 1000ull < (uint64_t)A.min_gain_permil * rawb) continue;
-                const uint64_t t = pad16u(kHdrBytes + pay[c]);
-                if (t < best_total) { best_total = t; plan = c; }
-            }
-        }
-    }
-    FrameMeta M;
-    M.offset = base + (uint64_t)frame * A.slot; M.total = 0; M.payload = 0; M.codec = plan; M.w = w; M.nsym = K; M.fits = 1u;
-    M.segt_off = kHdrBytes + (uint32_t)pad4u(K);
-    M.bits_off = (plan == CODEC_HUFF) ? (M.segt_off + (uint32_t)pad4u(2ull * nseg)) : kHdrBytes;
-    M.bits_words = 0; M.pad_ = 0; M.huff_bits = 0; M.pad2_ = 0;
-    reinterpret_cast<FrameMeta*>(A.ws + A.L.meta)[frame] = M;
-}
-
 // AcceptRealized + CommitRawOrFail, and everything that needs the realized size: the groups of a HUFFMAN frame are
 // packed behind each other (every group but the first was materialised from bit 0 of a scratch region), then header,
 // code-length table, padding, the result record.  A rejected frame is copied again as RAW by all of its workgroups.
@@ -1078,7 +1084,8 @@ __global__ __launch_bounds__(256) void k_rea_finish(ReaArgs A) {
     }
     uint32_t codec = plan;
     if (plan != CODEC_RAW) {
-        const uint32_t failed = reinterpret_cast<const uint32_t*>(A.ws + A.L.fail)[frame];
+        uint32_t failed = 0;
+        for (uint32_t g = 0; g < ngrp; g++) failed |= reinterpret_cast<const uint32_t*>(A.ws + A.L.fail)[(size_t)frame * A.gpf + g];
         if (failed || payload > rawb || (rawb - payload) * 1000ull < (uint64_t)A.min_gain_permil * rawb) codec = CODEC_RAW;
     }
     const bool fell_back = (codec == CODEC_RAW && plan != CODEC_RAW);
@@ -1194,9 +1201,7 @@ hipError_t launch_rea_status(void* res, uint32_t n_frames, uint32_t status, hipS
 }
 
 hipError_t launch_rea(const ReaArgs& A, hipStream_t st, void (*mark)(hipStream_t)) {
-    hipLaunchKernelGGL(k_rea_plan, dim3(A.n_frames), dim3(256), 0, st, A);
-    mark(st);
-    // EncodePlan: the shared encoder with the sampled-arbitration source (quantizer tests on, the context's code,
+    // ProfileSample, ArbitratePlan, EncodePlan: the shared encoder with the sampled-arbitration source (quantizer tests on, the context's code,
     // group bitstreams from bit 0)
     CompressArgs C = {};
     C.in = A.in; C.n = A.n; C.chunk = A.chunk; C.n_frames = A.n_frames; C.K = A.K; C.sbpf = A.gpf; C.stat_block = kEncGroup;
@@ -1205,6 +1210,7 @@ hipError_t launch_rea(const ReaArgs& A, hipStream_t st, void (*mark)(hipStream_t
     C.out = A.out; C.out_cap = 0; C.ws = A.ws; C.L = WsLayout(); C.L.meta = A.L.meta; C.res = A.res;
     C.rea_ctx = A.ctx; C.rea_tmp = A.tmp_base; C.rea_gbits = reinterpret_cast<uint32_t*>(A.ws + A.L.gbits);
     C.rea_fail = reinterpret_cast<uint32_t*>(A.ws + A.L.fail);
+    C.rea_sample_elems = A.sample_elems; C.rea_small_batch_bytes = A.small_batch_bytes; C.rea_slot = A.slot;
     hipLaunchKernelGGL((k_encode<2, 0, 0>), dim3(A.n_frames * A.gpf), dim3(kEncThreads), 0, st, C);
     mark(st);
     hipLaunchKernelGGL(k_rea_finish, dim3(A.n_frames * A.gpf), dim3(256), 0, st, A);
