@@ -245,3 +245,35 @@ def test_seeded_sweep(nz, seed):
     red, ores, orc = oracle.reduce_frames(ref, sy, n, eb, oracle.make_opts(**kw))
     rc, r, got = gpu_reduce(nz, ref, sy, n, eb, nz.make_opts(**kw))
     assert orc == 0 and rc == 0 and r["status"] == 0 and _first_diff(got, red) == -1
+
+
+def test_full_size_message_with_the_predictor(nz):
+    """A 64 Mi-element message in 1 MiB frames (the headline geometry) with the predictor on: a smooth signal plus
+    gradient-like noise, compressed stream, decompressed values and the ring-step reduce against the oracle."""
+    import torch
+    n = 1 << 26
+    noise = W.gradient_like(n, seed=5)
+    x = (np.sin(np.arange(n, dtype=np.float64) / 700.0) + noise).astype(np.float32)
+    eb = float(np.float32(W.abs_bound_from_rel(x, 1e-4)))
+    kw = dict(chunk_elems=262144, predictor=1)
+    g, o = nz.make_opts(**kw), oracle.make_opts(**kw)
+    sess = nz.Session(n, g, "cuda:0", reduce=True)
+    rc, out = sess.compress(torch.from_numpy(x).to("cuda:0"), eb)
+    r = sess.result()
+    ref, ores, orc = oracle.compress(x, eb, o)
+    assert rc == 0 and orc == 0 and r["status"] == 0 and r["bytes"] == ores.bytes
+    assert (r["n_raw"], r["n_fixed"], r["n_huff"]) == (ores.n_raw, ores.n_fixed, ores.n_huff)
+    assert _first_diff(out[:r["bytes"]].cpu().numpy(), ref) == -1
+    nbytes = r["bytes"]
+    rc, y = sess.decompress(out, nbytes, n, eb)
+    assert rc == 0 and sess.result()["status"] == 0
+    yo = oracle.decompress(ref, n, eb)[0]
+    y = y.cpu().numpy()
+    assert (y.view(np.uint32) == yo.view(np.uint32)).all()
+    assert float(np.max(np.abs(y.astype(np.float64) - x.astype(np.float64)))) <= float(np.float32(eb))
+    del y, yo
+    rc, red = sess.reduce_local(out, nbytes, torch.from_numpy(noise).to("cuda:0"), n, eb)
+    rr = sess.result()
+    ro, rres, rrc = oracle.reduce_local(ref, noise, eb, o)
+    assert rc == 0 and rrc == 0 and rr["status"] == 0 and rr["bytes"] == rres.bytes
+    assert _first_diff(red[:rr["bytes"]].cpu().numpy(), ro) == -1
