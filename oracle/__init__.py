@@ -37,7 +37,9 @@ class Context(C.Structure):
 
 
 class ReaOpts(C.Structure):
-    _fields_ = [("sample_bytes", C.c_uint32), ("small_batch_bytes", C.c_uint32)]
+    _fields_ = [("sample_bytes", C.c_uint32), ("small_batch_bytes", C.c_uint32), ("link_ps_per_byte", C.c_uint32),
+                ("fixed_alpha_ns", C.c_uint32), ("fixed_ps_per_byte", C.c_uint32), ("huff_alpha_ns", C.c_uint32),
+                ("huff_ps_per_byte", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 class ReaResult(C.Structure):

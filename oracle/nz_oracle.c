@@ -977,6 +977,15 @@ int nzo_context_build(const float* sample, size_t n_s, float eb, const nzo_opts*
 typedef struct {
     uint32_t sample_bytes;         /* SampleWindow: at most this many bytes of the frame's prefix; 0 -> 65536 (Sec. IV-C) */
     uint32_t small_batch_bytes;    /* SmallBatchFastPath: frames with fewer raw bytes go RAW unprofiled; default 0        */
+    /* Cost model of Eq. 1, T_c = alpha_c + lambda_enc*E_c + P_c/beta_eff(pi) + lambda_dec*D_c, in integers.  The
+     * caller supplies what TransportHint and calibration would: link_ps_per_byte = 1/beta_eff in picoseconds per
+     * byte (0 = no hint: the cost is the transmitted size alone), and per entropy codec the fixed cost alpha_c in
+     * nanoseconds and the exposed codec time lambda_enc*E_c + lambda_dec*D_c as picoseconds per raw byte.  RAW has
+     * no codec cost (Sec. IV-C). */
+    uint32_t link_ps_per_byte;
+    uint32_t fixed_alpha_ns, fixed_ps_per_byte;
+    uint32_t huff_alpha_ns, huff_ps_per_byte;
+    uint32_t reserved;             /* 0 */
 } nzo_rea_opts;
 
 typedef struct {
@@ -1004,9 +1013,19 @@ typedef struct {
  * frame with integer arithmetic, rounded up: bits = ceil(sample_bits * nf / n_s).  Predicted payloads
  * include the codec's tables.  A candidate is admissible if its predicted payload fits the payload
  * capacity (the RAW size: a frame's slot holds a RAW frame), meets the minimum gain, and -- HUFFMAN --
- * the context is valid for this alphabet and rawBytes >= T_huff.  Eq. 2 with transmitted size as the
- * cost: smallest predicted total, ties to the lower codec id; a pinned codec replaces the choice.
+ * the context is valid for this alphabet and rawBytes >= T_huff.  Eq. 2: the candidate of least predicted
+ * cost, ties to the lower codec id; a pinned codec replaces the choice.  The cost is Eq. 1 evaluated in
+ * picoseconds with the caller's transport hint and codec costs, T_c = 1000*alpha_c + codec_ps_c*rawBytes +
+ * link_ps*total_c (RAW: link_ps*total_RAW), or the predicted total bytes when there is no hint.
  */
+static uint64_t rea_cost(const nzo_rea_opts* ro, int codec, uint64_t rawb, uint64_t total) {
+    if (ro->link_ps_per_byte == 0u) return total;
+    uint64_t t = (uint64_t)ro->link_ps_per_byte * total;
+    if (codec == NZO_FIXEDLEN) t += 1000ull * ro->fixed_alpha_ns + (uint64_t)ro->fixed_ps_per_byte * rawb;
+    if (codec == NZO_HUFFMAN) t += 1000ull * ro->huff_alpha_ns + (uint64_t)ro->huff_ps_per_byte * rawb;
+    return t;
+}
+
 static void rea_plan_frame(const float* x, uint32_t nf, float eb, float step, float inv, const nzo_opts* o,
                            const nzo_rea_opts* ro, const nzo_context* ctx, nzo_rea_plan* P) {
     memset(P, 0, sizeof *P);
@@ -1038,22 +1057,23 @@ static void rea_plan_frame(const float* x, uint32_t nf, float eb, float step, fl
         P->plan = (o->force_codec == NZO_HUFFMAN && !ctx_ok) ? NZO_RAW : o->force_codec;
         return;
     }
-    uint64_t best_total = pad16(NZO_HDR_BYTES + rawb);
+    uint64_t best_cost = rea_cost(ro, NZO_RAW, rawb, pad16(NZO_HDR_BYTES + rawb));
     for (int c = NZO_FIXEDLEN; c <= NZO_HUFFMAN; c++) {
         if (c == NZO_HUFFMAN && (!ctx_ok || rawb < o->huff_min_bytes)) continue;
         const uint64_t p = P->pred_payload[c];
         if (p > rawb) continue;                                  /* predicted payload must fit the payload capacity */
         if ((rawb - p) * 1000ull < (uint64_t)o->min_gain_permil * rawb) continue;
-        const uint64_t t = pad16(NZO_HDR_BYTES + p);
-        if (t < best_total) { best_total = t; P->plan = c; }
+        const uint64_t t = rea_cost(ro, c, rawb, pad16(NZO_HDR_BYTES + p));
+        if (t < best_cost) { best_cost = t; P->plan = c; }
     }
 }
 
 int nzo_rea_plan_frame(const float* x, uint32_t nf, float eb, const nzo_opts* opts, const nzo_rea_opts* ropts,
                        const nzo_context* ctx, nzo_rea_plan* P) {
     nzo_opts o; float step, inv;
-    nzo_rea_opts ro = { 65536u, 0u };
+    nzo_rea_opts ro = { 65536u, 0u, 0u, 0u, 0u, 0u, 0u, 0u };
     if (ropts) { ro = *ropts; if (ro.sample_bytes == 0) ro.sample_bytes = 65536u; }
+    if (ro.reserved) return NZO_ERR_INVALID;
     if (resolve_opts(opts, &o) || nzo_step_constants(eb, &step, &inv) || nf == 0 || nf > o.chunk_elems) return NZO_ERR_INVALID;
     rea_plan_frame(x, nf, eb, step, inv, &o, &ro, ctx, P);
     return NZO_OK;
@@ -1120,12 +1140,12 @@ static int rea_commit_frame(uint8_t* dst, const float* x, uint32_t nf, float eb,
 int nzo_compress_rea(const float* x, size_t n, float eb, const nzo_opts* opts, const nzo_rea_opts* ropts,
                      const nzo_context* ctx, uint8_t* out, size_t cap, nzo_rea_result* res, uint8_t* plans) {
     nzo_opts o; float step, inv;
-    nzo_rea_opts ro = { 65536u, 0u };
+    nzo_rea_opts ro = { 65536u, 0u, 0u, 0u, 0u, 0u, 0u, 0u };
     nzo_rea_result dummy;
     if (!res) res = &dummy;
     memset(res, 0, sizeof *res);
     if (ropts) { ro = *ropts; if (ro.sample_bytes == 0) ro.sample_bytes = 65536u; }
-    if (n == 0 || !x || !out) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
+    if (n == 0 || !x || !out || ro.reserved) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
     if (resolve_opts(opts, &o) || nzo_step_constants(eb, &step, &inv)) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
     if (o.predictor) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }     /* the sampled path codes the codes themselves */
     const uint64_t nfr64 = (n + o.chunk_elems - 1) / o.chunk_elems;

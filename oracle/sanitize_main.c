@@ -34,7 +34,7 @@ static int run_case(size_t n, uint32_t chunk, uint32_t K, uint32_t seg, int forc
     if (nzo_reduce_local(sa, ra.bytes, y, sc, cap, n, eb, &od, &rc)) return 6;
     /* sampled arbitration with a cached context: valid, pinned, without context, capacity one slot short */
     {
-        nzo_context ctx; nzo_rea_result rr; nzo_rea_opts ro = { 4096u, 0u };
+        nzo_context ctx; nzo_rea_result rr; nzo_rea_opts ro = { 4096u, 0u, 0u, 0u, 0u, 0u, 0u, 0u };
         size_t cal = n < 5000 ? n : 5000;
         if (nzo_context_build(y, cal, eb, &od, &ctx)) return 8;
         size_t rcap = nzo_compress_bound(n, &od);

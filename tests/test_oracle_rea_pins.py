@@ -255,3 +255,108 @@ def test_against_the_exact_selector_on_gradient_like_data():
     assert all(a[3] >= b[3] - 256 for a, b in zip(fr_r, fr_e))    # (the exact frame may carry a shorter length table)
     assert [a[1] for a in fr_r] == [b[1] for b in fr_e]           # same decisions here
     assert res.wire_bytes <= 1.01 * e.size and res.n_fallback == 0
+
+
+# ------------------------------------------------------------------------------------------------
+# Eq. 1 with a transport hint: break-even points in closed form, the limits, and the no-hint case
+# ------------------------------------------------------------------------------------------------
+
+def _pad16(v):
+    return (v + 15) // 16 * 16
+
+
+def _model(link=0, fa=0, fp=0, ha=0, hp=0, sample_bytes=0):
+    return oracle.ReaOpts(sample_bytes, 0, link, fa, fp, ha, hp, 0)
+
+
+def test_raw_against_fixedlen_flips_exactly_at_the_break_even_bandwidth():
+    """Without a context only RAW and FIXEDLEN compete.  Eq. 1 puts the break-even where the transfer time saved equals
+    the codec's exposed time: link_ps * (total_RAW - total_FIXED) = 1000 * alpha_ns + codec_ps * rawBytes.  At that
+    point (if it is an integer) and on every faster link RAW is planned, one picosecond per byte slower FIXEDLEN."""
+    nf = 50000
+    rng = np.random.default_rng(3)
+    x = rng.integers(-100, 101, nf).astype(np.float32)                  # zigzag up to 200: w = 8
+    o = oracle.make_opts(chunk_elems=nf)
+    rawb = 4 * nf
+    tot_raw, tot_fix = _pad16(32 + rawb), _pad16(32 + 4 * ((nf * 8 + 31) // 32))
+    assert oracle.rea_plan_frame(x, EB1, o, _model(), None)["pred_payload"][1] == tot_fix - 32
+    for fa, fp in ((0, 7), (5000, 0), (1234, 3), (0, 1), (4000000, 4000)):
+        cost = 1000 * fa + fp * rawb
+        be = cost // (tot_raw - tot_fix)                                # largest link_ps at which RAW is still not worse
+        if be >= 1:
+            assert oracle.rea_plan_frame(x, EB1, o, _model(be, fa, fp), None)["plan"] == oracle.RAW, (fa, fp)
+        assert oracle.rea_plan_frame(x, EB1, o, _model(be + 1, fa, fp), None)["plan"] == oracle.FIXEDLEN, (fa, fp)
+        if cost % (tot_raw - tot_fix) == 0 and be >= 1:                  # exact tie: the cheaper codec (lower id)
+            assert oracle.rea_plan_frame(x, EB1, o, _model(be, fa, fp), None)["plan"] == oracle.RAW
+    # an exact tie on purpose: 3 ps per raw byte cost 600000 ps, four times the 150000 bytes saved -> tie at 4 ps/byte
+    assert (tot_raw - tot_fix, rawb) == (150000, 200000)
+    assert oracle.rea_plan_frame(x, EB1, o, _model(4, 0, 3), None)["plan"] == oracle.RAW
+    assert oracle.rea_plan_frame(x, EB1, o, _model(5, 0, 3), None)["plan"] == oracle.FIXEDLEN
+
+
+def test_huffman_must_amortize_its_extra_codec_cost_over_fixedlen():
+    """With a context all three compete.  On a slow link with free codecs the smallest frame wins (HUFFMAN here); as
+    HUFFMAN's exposed time per byte grows, FIXEDLEN takes over exactly where
+    link * (total_FIXED - total_HUFF) = (huff_ps - fixed_ps) * rawBytes + 1000 * (huff_alpha - fixed_alpha)."""
+    nf = 60000
+    x = W.gradient_like(nf, seed=6)
+    eb = 1e-4
+    o = oracle.make_opts(chunk_elems=nf)
+    ctx = oracle.context_build(x[:20000], eb, o)
+    P = oracle.rea_plan_frame(x, eb, o, _model(), ctx)
+    assert P["plan"] == oracle.HUFFMAN
+    rawb = 4 * nf
+    tot = [_pad16(32 + p) for p in P["pred_payload"]]
+    assert tot[2] < tot[1] < tot[0]
+    link, fp, fa, ha = 400, 2, 100, 700                                 # 2.5 GB/s: the transfer dominates
+    saved = link * (tot[1] - tot[2]) - 1000 * (ha - fa)
+    hp_be = fp + saved // rawb                                          # largest huff_ps with cost_H <= cost_F ...
+    # ... cost_H < cost_F  <=>  (hp - fp) * rawb < saved
+    hp_last = fp + (saved - 1) // rawb
+    assert oracle.rea_plan_frame(x, eb, o, _model(link, fa, fp, ha, hp_last), ctx)["plan"] == oracle.HUFFMAN
+    assert oracle.rea_plan_frame(x, eb, o, _model(link, fa, fp, ha, hp_last + 1), ctx)["plan"] == oracle.FIXEDLEN
+    assert hp_be in (hp_last, hp_last + 1)
+    # and on a link so fast that neither codec pays for itself, RAW: the optimal high-bandwidth decision
+    assert oracle.rea_plan_frame(x, eb, o, _model(1, 0, 5, 0, 5), ctx)["plan"] == oracle.RAW
+    # the gates still apply: a pinned codec ignores the model, T_huff and the minimum gain are checked before the cost
+    assert oracle.rea_plan_frame(x, eb, oracle.make_opts(chunk_elems=nf, force_codec=2), _model(1, 0, 5, 0, 5), ctx)["plan"] == oracle.HUFFMAN
+    assert oracle.rea_plan_frame(x, eb, oracle.make_opts(chunk_elems=nf, huff_min_bytes=rawb + 1), _model(link), ctx)["plan"] == oracle.FIXEDLEN
+
+
+def test_no_hint_means_size_only_and_free_codecs_on_any_link_too():
+    rng = np.random.default_rng(8)
+    nf = 30000
+    o = oracle.make_opts(chunk_elems=nf)
+    for seed in range(6):
+        x = W.gradient_like(nf, seed=20 + seed) if seed % 2 else W.sweep_payload("uniform", nf, 30 + seed)
+        eb = float(10.0 ** rng.uniform(-5, -3))
+        ctx = oracle.context_build(x[:8000], eb, o)
+        base = oracle.rea_plan_frame(x, eb, o, _model(), ctx)
+        # link = 0: the other numbers are not looked at
+        junk = _model(0, *[int(v) for v in rng.integers(0, 2 ** 31, 4)])
+        assert oracle.rea_plan_frame(x, eb, o, junk, ctx) == base
+        # codecs that cost nothing: cost = link * total, the same order as the sizes, whatever the link
+        for link in (1, 37, 4000, 2 ** 32 - 1):
+            assert oracle.rea_plan_frame(x, eb, o, _model(link), ctx)["plan"] == base["plan"]
+
+
+def test_whole_message_under_a_transport_hint():
+    n = 200000
+    x = W.gradient_like(n, seed=9)
+    eb = 1e-4
+    o = oracle.make_opts(chunk_elems=32768)
+    ctx = oracle.context_build(x[:16384], eb, o)
+    plain, pres, rc0, plans0 = oracle.compress_rea(x, eb, o, _model(), ctx)
+    # fast link: every frame is planned RAW (no fallback involved), the message comes back bit for bit
+    fast, fres, rc1, plans1 = oracle.compress_rea(x, eb, o, _model(1, 0, 5, 0, 5), ctx)
+    assert rc0 == 0 and rc1 == 0 and (plans1 == oracle.RAW).all() and fres.n_raw == fres.n_frames and fres.n_fallback == 0
+    y, _, drc = oracle.decompress(fast, n, eb)
+    assert drc == 0 and (y.view(np.uint32) == x.view(np.uint32)).all()
+    # slow link, free codecs: the very same stream as without a hint
+    slow, sres, rc2, plans2 = oracle.compress_rea(x, eb, o, _model(5000), ctx)
+    assert rc2 == 0 and (plans2 == plans0).all() and slow.size == plain.size and (slow == plain).all()
+    # a reserved field that is not zero is refused
+    bad = oracle.ReaOpts(0, 0, 0, 0, 0, 0, 0, 1)
+    assert oracle.compress_rea(x, eb, o, bad, ctx)[2] == oracle.ERR_INVALID
+    with pytest.raises(ValueError):
+        oracle.rea_plan_frame(x[:1000], eb, o, bad, ctx)
