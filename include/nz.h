@@ -124,8 +124,8 @@ nz_status nz_compress(const float* d_in, size_t n, float eb, void* d_out, size_t
  * nz_compress_rea: per frame, ProfileSample reads a prefix of at most sample_bytes (64 KiB) of the frame;
  * ArbitratePlan predicts FIXEDLEN from the width of the sample's largest code and HUFFMAN from the sample's
  * expected code length under the context, applies the gates (SmallBatchFastPath, T_huff = huff_min_bytes, context
- * valid for this alphabet, minimum gain, payload capacity) and takes the smallest predicted frame (Eq. 2 with
- * transmitted size as the cost; force_codec pins the plan); EncodePlan runs only the planned codec over the frame,
+ * valid for this alphabet, minimum gain, payload capacity) and takes the candidate of least predicted cost (Eq. 2;
+ * the cost is Eq. 1 under the caller's transport hint, or the transmitted size without one; force_codec pins the plan); EncodePlan runs only the planned codec over the frame,
  * in one pass over the input; AcceptRealized checks the realized payload (materialised, fits, minimum gain) and
  * CommitRawOrFail stores the frame RAW otherwise.  d_ctx may be NULL (no Huffman).
  * Output: an NZ stream that nz_decompress / nz_reduce_* read like any other, except that frame k starts at the
@@ -138,6 +138,17 @@ nz_status nz_compress(const float* d_in, size_t n, float eb, void* d_out, size_t
 typedef struct {
     uint32_t sample_bytes;       /* SampleWindow: bytes of the frame's prefix that are profiled; 0 = 65536       */
     uint32_t small_batch_bytes;  /* SmallBatchFastPath: frames with fewer raw bytes are RAW unprofiled; default 0 */
+    /* Cost model of Eq. 1, T_c = alpha_c + lambda_enc*E_c + P_c/beta_eff(pi) + lambda_dec*D_c, in integers.  The
+     * caller supplies what TransportHint and its calibration would: link_ps_per_byte = 1/beta_eff in picoseconds per
+     * byte (8 TB/s = 0.125, 25 GB/s = 40; 0 = no hint: the cost is the predicted transmitted size alone), and for
+     * each entropy codec the fixed cost alpha_c in nanoseconds and the exposed codec time lambda_enc*E_c +
+     * lambda_dec*D_c in picoseconds per raw byte.  ArbitratePlan takes the admissible candidate with the least
+     * T_c = 1000*alpha_c + codec_ps_c*rawBytes + link_ps*predictedTotal_c (RAW: link_ps*total_RAW), ties to the
+     * lower codec id: on a fast link RAW is the planned outcome, not a fallback (Sec. IV-C). */
+    uint32_t link_ps_per_byte;
+    uint32_t fixed_alpha_ns, fixed_ps_per_byte;
+    uint32_t huff_alpha_ns, huff_ps_per_byte;
+    uint32_t reserved;           /* 0 */
 } nz_rea_opts;
 
 typedef struct {                 /* lives in DEVICE memory, 16-byte aligned */

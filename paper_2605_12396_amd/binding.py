@@ -29,7 +29,9 @@ def make_opts(chunk_elems=0, seg_syms=0, alphabet=0, force_codec=-1, min_gain_pe
 
 
 class ReaOpts(C.Structure):
-    _fields_ = [("sample_bytes", C.c_uint32), ("small_batch_bytes", C.c_uint32)]
+    _fields_ = [("sample_bytes", C.c_uint32), ("small_batch_bytes", C.c_uint32), ("link_ps_per_byte", C.c_uint32),
+                ("fixed_alpha_ns", C.c_uint32), ("fixed_ps_per_byte", C.c_uint32), ("huff_alpha_ns", C.c_uint32),
+                ("huff_ps_per_byte", C.c_uint32), ("reserved", C.c_uint32)]
 
 
 RESULT_BYTES = 32   # sizeof(nz_result)

@@ -245,7 +245,15 @@ nz_status nz_compress_rea(const float* d_in, size_t n, float eb, const void* d_c
     A.gpf = (o.chunk + kEncGroup - 1) / kEncGroup;
     A.force_codec = o.force; A.min_gain_permil = o.gain; A.huff_min_bytes = o.huff_min;
     uint32_t sample_bytes = 65536u, small = 0u;
-    if (ropts) { if (ropts->sample_bytes) sample_bytes = ropts->sample_bytes; small = ropts->small_batch_bytes; }
+    A.link_ps = 0; A.fixed_alpha_ns = 0; A.fixed_ps = 0; A.huff_alpha_ns = 0; A.huff_ps = 0;
+    if (ropts) {
+        if (ropts->reserved) return NZ_ERR_INVALID;
+        if (ropts->sample_bytes) sample_bytes = ropts->sample_bytes;
+        small = ropts->small_batch_bytes;
+        A.link_ps = ropts->link_ps_per_byte;
+        A.fixed_alpha_ns = ropts->fixed_alpha_ns; A.fixed_ps = ropts->fixed_ps_per_byte;
+        A.huff_alpha_ns = ropts->huff_alpha_ns; A.huff_ps = ropts->huff_ps_per_byte;
+    }
     A.sample_elems = sample_bytes / 4u; A.small_batch_bytes = small;
     A.eb = eb; A.step = step; A.inv_step = inv; A.step_bits = bits_of(step);
     A.ctx = reinterpret_cast<const DevContext*>(d_ctx);

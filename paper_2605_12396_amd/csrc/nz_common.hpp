@@ -239,6 +239,7 @@ struct ReaArgs {
     uint32_t chunk, n_frames, K, gpf;           // encoder workgroups (groups of kEncGroup symbols) per frame
     int32_t force_codec; uint32_t min_gain_permil, huff_min_bytes;
     uint32_t sample_elems, small_batch_bytes;
+    uint32_t link_ps, fixed_alpha_ns, fixed_ps, huff_alpha_ns, huff_ps;   // cost model of Eq. 1 (link_ps 0: size only)
     float eb, step, inv_step; uint32_t step_bits;
     const DevContext* ctx;
     uint8_t* out; uint64_t slot;               // bytes between frame starts
@@ -269,6 +270,7 @@ struct CompressArgs {
     // before the frame's groups are packed together, the groups' realized bit counts and the frames' failure flags
     const DevContext* rea_ctx; uint32_t* rea_tmp; uint32_t* rea_gbits; uint32_t* rea_fail;
     uint32_t rea_sample_elems, rea_small_batch_bytes;   // SampleWindow in elements, SmallBatchFastPath threshold
+    uint32_t rea_link_ps, rea_fixed_alpha_ns, rea_fixed_ps, rea_huff_alpha_ns, rea_huff_ps;   // cost model of Eq. 1
     uint64_t rea_slot;        // bytes between frame starts of the slotted stream
 };
 

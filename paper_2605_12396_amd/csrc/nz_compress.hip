@@ -747,13 +747,21 @@ __device__ inline FrameMeta rea_plan_frame(const CompressArgs& A, uint32_t frame
         pay[CODEC_HUFF] = pad4u(K) + pad4u(2ull * nseg) + 4ull * ((pred_bits + 31u) / 32u);
         if (A.force_codec >= 0) plan = (A.force_codec == (int32_t)CODEC_HUFF && !ctx_ok) ? (uint32_t)CODEC_RAW : (uint32_t)A.force_codec;
         else {
-            uint64_t best_total = pad16u(kHdrBytes + rawb);
+            // Eq. 1 in picoseconds under the caller's transport hint (no hint: the predicted total bytes)
+            auto cost = [&](uint32_t c, uint64_t total) -> uint64_t {
+                if (A.rea_link_ps == 0u) return total;
+                uint64_t t = (uint64_t)A.rea_link_ps * total;
+                if (c == CODEC_FIXED) t += 1000ull * A.rea_fixed_alpha_ns + (uint64_t)A.rea_fixed_ps * rawb;
+                if (c == CODEC_HUFF) t += 1000ull * A.rea_huff_alpha_ns + (uint64_t)A.rea_huff_ps * rawb;
+                return t;
+            };
+            uint64_t best_cost = cost(CODEC_RAW, pad16u(kHdrBytes + rawb));
             for (uint32_t c = CODEC_FIXED; c <= CODEC_HUFF; c++) {
                 if (c == CODEC_HUFF && (!ctx_ok || rawb < A.huff_min_bytes)) continue;
                 if (pay[c] > rawb) continue;
                 if ((rawb - pay[c]) * 1000ull < (uint64_t)A.min_gain_permil * rawb) continue;
-                const uint64_t t = pad16u(kHdrBytes + pay[c]);
-                if (t < best_total) { best_total = t; plan = c; }
+                const uint64_t t = cost(c, pad16u(kHdrBytes + pay[c]));
+                if (t < best_cost) { best_cost = t; plan = c; }
             }
         }
     }
@@ -1211,6 +1219,8 @@ hipError_t launch_rea(const ReaArgs& A, hipStream_t st, void (*mark)(hipStream_t
     C.rea_ctx = A.ctx; C.rea_tmp = A.tmp_base; C.rea_gbits = reinterpret_cast<uint32_t*>(A.ws + A.L.gbits);
     C.rea_fail = reinterpret_cast<uint32_t*>(A.ws + A.L.fail);
     C.rea_sample_elems = A.sample_elems; C.rea_small_batch_bytes = A.small_batch_bytes; C.rea_slot = A.slot;
+    C.rea_link_ps = A.link_ps; C.rea_fixed_alpha_ns = A.fixed_alpha_ns; C.rea_fixed_ps = A.fixed_ps;
+    C.rea_huff_alpha_ns = A.huff_alpha_ns; C.rea_huff_ps = A.huff_ps;
     hipLaunchKernelGGL((k_encode<2, 0, 0>), dim3(A.n_frames * A.gpf), dim3(kEncThreads), 0, st, C);
     mark(st);
     hipLaunchKernelGGL(k_rea_finish, dim3(A.n_frames * A.gpf), dim3(256), 0, st, A);

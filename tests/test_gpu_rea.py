@@ -239,3 +239,41 @@ def test_rea_repeatable_and_c2_full_size(nz):
         rc, r2, out2 = gpu_rea(nz, x, eb, g, None, gctx)
         for off, codec, payload, total in _frames(ref)[::17]:
             assert bool((out2[off:off + total] == first[off:off + total]).all())
+
+
+@pytest.mark.parametrize("model", [
+    (0, 0, 1, 0, 5, 0, 5, 0),                # a link so fast that no codec pays for itself: every frame planned RAW
+    (0, 0, 40, 100, 2, 700, 6, 0),           # 25 GB/s, HUFFMAN three times as expensive as FIXEDLEN
+    (0, 0, 400, 100, 2, 700, 60, 0),         # 2.5 GB/s, HUFFMAN's exposed time too high: FIXEDLEN or RAW
+    (0, 0, 5000, 0, 0, 0, 0, 0),             # slow link, free codecs: the sizes decide
+    (4096, 0, 12, 20000, 0, 20000, 0, 0),    # fixed costs only, short sample window
+], ids=["fast_link", "mid_link", "huffman_too_slow", "slow_link_free_codecs", "fixed_costs"])
+def test_plans_under_a_transport_hint_match_the_oracle(nz, model):
+    """Eq. 1 with the caller's transport hint and codec costs: same plans, same frames, same counters as the oracle, on
+    a message whose frames differ in compressibility (gradient-like, uniform, smooth, all zero)."""
+    n = 6 * 32768 + 1234
+    x = np.concatenate([W.gradient_like(2 * 32768, seed=3), W.sweep_payload("uniform", 2 * 32768, 4),
+                        W.smooth_field((32, 32, 32), seed=5).reshape(-1), np.zeros(32768 + 1234, np.float32)])
+    assert x.size == n
+    ref, ores, out, r, plans = check_rea(nz, x, 1e-4, cal=x[:65536], ropts=model, chunk_elems=32768)
+    if model[2] == 1:
+        assert (plans == oracle.RAW).all() and r["n_raw"] == r["n_frames"] and r["n_fallback"] == 0
+    if model[2] == 5000:
+        plain = oracle.compress_rea(x, 1e-4, oracle.make_opts(chunk_elems=32768), None,
+                                    oracle.context_build(x[:65536], 1e-4, oracle.make_opts(chunk_elems=32768)))[0]
+        assert plain.size == ref.size and (plain == ref).all()
+
+
+def test_reserved_option_field_is_refused(nz):
+    import torch
+    n = 1000
+    g = nz.make_opts(chunk_elems=256)
+    x = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    cap = nz.nz_compress_bound(n, g)
+    out = torch.empty(cap, dtype=torch.uint8, device="cuda:0")
+    res = torch.zeros(48, dtype=torch.uint8, device="cuda:0")
+    wsb = nz.nz_rea_workspace_bytes(n, g)
+    ws = torch.empty(max(wsb, 256), dtype=torch.uint8, device="cuda:0")
+    bad = nz.ReaOpts(0, 0, 0, 0, 0, 0, 0, 1)
+    assert nz.nz_compress_rea(x, n, 1e-4, None, out, cap, res, g, bad, ws, wsb) == nz.ERR_INVALID
+    torch.cuda.synchronize()
