@@ -98,6 +98,7 @@ def lib():
         L.nzo_decompress_step.argtypes = [vp, sz, vp, sz, f32, C.POINTER(Result)]
         L.nzo_decode_codes_step.argtypes = [vp, sz, sz, f32, vp, vp, vp, C.POINTER(Result)]
         L.nzo_reduce_frames_step.argtypes = [vp, sz, vp, sz, vp, sz, sz, f32, C.POINTER(Opts), C.POINTER(Result)]
+        L.nzo_reduce_local_sr.argtypes = [vp, sz, vp, vp, sz, sz, f32, C.c_uint32, C.POINTER(Opts), C.POINTER(Result)]
         L.nzo_context_build.argtypes = [vp, sz, f32, C.POINTER(Opts), C.POINTER(Context)]
         L.nzo_rea_plan_frame.argtypes = [vp, C.c_uint32, f32, C.POINTER(Opts), C.POINTER(ReaOpts), C.POINTER(Context),
                                          C.POINTER(ReaPlan)]
@@ -344,6 +345,20 @@ def decode_codes_step(stream, n, step):
     res = Result()
     rc = lib().nzo_decode_codes_step(_ptr(s), s.size, n, C.c_float(step), _ptr(q), _ptr(rb), _ptr(kinds), C.byref(res))
     return q, rb, kinds, res, rc
+
+
+def reduce_local_sr(a, x, step, seed, opts=None, cap=None):
+    """Ring-step reduce with the stochastic quantizer: incoming stream `a` plus the rank's own fp32 message `x`."""
+    a = np.ascontiguousarray(a, dtype=np.uint8)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    n = x.size
+    if cap is None:
+        cap = compress_bound(n, opts)
+    out = np.zeros(max(cap, 1), np.uint8)
+    res = Result()
+    rc = lib().nzo_reduce_local_sr(_ptr(a), a.size, _ptr(x), _ptr(out), cap, n, C.c_float(step), seed,
+                                   C.byref(opts) if opts is not None else None, C.byref(res))
+    return out[:res.bytes].copy(), res, rc
 
 
 def reduce_frames_step(a, b, n, step, opts=None, cap=None):

@@ -1283,3 +1283,50 @@ int nzo_compress_sr(const float* x, size_t n, float step, uint32_t seed, const n
     c.x = x; c.step = step; c.inv = inv; c.seed = seed;
     return emit_stream(sr_src, &c, n, &o, f32_bits(step), out, cap, res);
 }
+
+/*
+ * Ring-step reduce with the stochastic interface quantizer (the receive-reduce-send step of Sec. IV-D for a QSGD
+ * collective): out = incoming (+) local, where the local message is quantized as nzo_compress_sr would quantize it
+ * (element i draws (seed, i)) and never entropy coded.  Frame rules as in nzo_reduce_local: both coded -> exact
+ * integer sum, re-planned and re-selected; incoming frame RAW, or a local element that cannot be quantized -> RAW
+ * frame of fp32 sums; |Q| > 2^30 -> RAW frame of the dequantized sums.  The stream must have been made with `step`.
+ */
+int nzo_reduce_local_sr(const uint8_t* in, size_t in_bytes, const float* local, uint8_t* out, size_t cap, size_t n,
+                        float step, uint32_t seed, const nzo_opts* opts, nzo_result* res) {
+    nzo_opts o; stream_hdr hi;
+    nzo_result dummy;
+    if (!res) res = &dummy;
+    memset(res, 0, sizeof *res);
+    if (n == 0 || !in || !local || !out) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
+    if (resolve_opts(opts, &o) || !step_ok(step) || o.predictor) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
+    int rc = parse_stream(in, in_bytes, &hi);
+    if (rc) { res->status = (uint32_t)rc; return rc; }
+    if (hi.n != n || hi.chunk != o.chunk_elems || hi.step_bits != f32_bits(step) || hi.predictor != 0u) {
+        res->status = NZO_ERR_MISMATCH; return NZO_ERR_MISMATCH;
+    }
+    volatile float inv = 1.0f / step;
+    int32_t* qa = (int32_t*)malloc(4ull * n); int32_t* qb = (int32_t*)malloc(4ull * n);
+    uint32_t* ra = (uint32_t*)malloc(4ull * n); uint32_t* rb = (uint32_t*)malloc(4ull * n);
+    uint8_t* fa = (uint8_t*)calloc(hi.n_frames, 1); uint8_t* fb = (uint8_t*)calloc(hi.n_frames, 1);
+    if (!qa || !qb || !ra || !rb || !fa || !fb) rc = NZO_ERR_INVALID;
+    if (!rc) rc = nzo_decode_codes_step(in, in_bytes, n, step, qa, ra, fa, NULL);
+    if (!rc) {
+        for (uint32_t k = 0; k < hi.n_frames; k++) {
+            const uint64_t i0 = (uint64_t)k * o.chunk_elems;
+            const uint64_t i1 = (i0 + o.chunk_elems < n) ? i0 + o.chunk_elems : n;
+            int all_ok = 1;
+            for (uint64_t i = i0; i < i1; i++) {
+                int32_t v = 0;
+                if (!nzo_sr_quantize_one(local[i], step, inv, nzo_sr_draw(seed, i), &v)) all_ok = 0;
+                qb[i] = v; rb[i] = f32_bits(local[i]);
+            }
+            fb[k] = all_ok ? 0 : 1;
+        }
+        reduce_ctx c = { qa, qb, ra, rb, fa, fb, step };
+        rc = emit_stream(reduce_src, &c, n, &o, f32_bits(step), out, cap, res);
+    } else {
+        res->status = (uint32_t)rc;
+    }
+    free(qa); free(qb); free(ra); free(rb); free(fa); free(fb);
+    return rc;
+}

@@ -147,3 +147,42 @@ def test_stream_is_the_coded_stochastic_codes_and_reduces_exactly():
     assert rc == 0 and rz.n_raw == 1
     outz = oracle.decompress_step(sz, n, step)[0]
     assert (outz[20000:40000].view(np.uint32) == z[20000:40000].view(np.uint32)).all()
+
+
+def test_ring_step_with_the_stochastic_quantizer():
+    """nzo_reduce_local_sr(in, x) must be, byte for byte, the two-stream reduce of `in` with the stochastic stream of x
+    (same seed), its codes the exact sums of the incoming codes and the drawn codes, and its special frames (incoming
+    RAW, local value that cannot be quantized, sums past 2^30) must follow the same rules."""
+    n = 70001
+    o = oracle.make_opts(chunk_elems=20000)
+    a, x = W.gradient_like(n, seed=61), W.gradient_like(n, seed=62)
+    step = float(np.float32(max(oracle.qsgd_step(a, 128), oracle.qsgd_step(x, 128))))
+    sa, _, rc = oracle.compress_sr(a, step, 11, o)
+    sx, _, rc2 = oracle.compress_sr(x, step, 12, o)
+    two, tres, rc3 = oracle.reduce_frames_step(sa, sx, n, step, o)
+    one, ores, rc4 = oracle.reduce_local_sr(sa, x, step, 12, o)
+    assert rc == 0 and rc2 == 0 and rc3 == 0 and rc4 == 0 and one.size == two.size and (one == two).all()
+    qa, _ = oracle.sr_quantize(a, step, 11)
+    qx, _ = oracle.sr_quantize(x, step, 12)
+    q, rb, kinds, _, drc = oracle.decode_codes_step(one, n, step)
+    assert drc == 0 and not kinds.any() and (q == qa + qx).all()
+    # another seed gives another stream; the deterministic ring step too
+    assert not np.array_equal(oracle.reduce_local_sr(sa, x, step, 13, o)[0], one)
+    # incoming RAW frame, local frame with a value that cannot be quantized
+    a2, x2 = a.copy(), x.copy()
+    a2[5] = np.inf; x2[45000] = np.nan
+    sa2, _, _ = oracle.compress_sr(a2, step, 11, o)
+    sx2, _, _ = oracle.compress_sr(x2, step, 12, o)
+    one2, r2, rc5 = oracle.reduce_local_sr(sa2, x2, step, 12, o)
+    two2, _, _ = oracle.reduce_frames_step(sa2, sx2, n, step, o)
+    assert rc5 == 0 and r2.n_raw == 2 and (one2 == two2).all()
+    y, _, _ = oracle.decompress_step(one2, n, step)
+    st = np.float32(step)
+    assert np.isinf(y[5]) and np.isnan(y[45000])
+    assert y[6] == np.float32(a2[6] + np.float32(np.float32(qx[6]) * st))               # raw incoming value + local code
+    assert y[45001] == np.float32(np.float32(np.float32(qa[45001]) * st) + x2[45001])   # incoming code + original local value
+    # mismatches and refusals
+    assert oracle.reduce_local_sr(sa, x, step * 2, 12, o)[2] == oracle.ERR_MISMATCH
+    assert oracle.reduce_local_sr(sa, x[:-1], step, 12, o)[2] == oracle.ERR_MISMATCH
+    assert oracle.reduce_local_sr(sa, x, step, 12, oracle.make_opts(chunk_elems=20000, predictor=1))[2] == oracle.ERR_INVALID
+    assert oracle.reduce_local_sr(sa, x, 0.0, 12, o)[2] == oracle.ERR_INVALID
