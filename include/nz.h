@@ -189,6 +189,12 @@ nz_status nz_decompress_step(const void* d_stream, size_t stream_bytes, float* d
 nz_status nz_reduce_frames_step(const void* d_a, size_t a_bytes, const void* d_b, size_t b_bytes, void* d_out,
                                 size_t out_cap, size_t n, float step, nz_result* d_res, const nz_opts* opts,
                                 void* d_ws, size_t ws_bytes, void* stream);
+/* The ring step of such a collective (Sec. IV-D, receive-reduce-send): nz_reduce_local with the stochastic quantizer
+ * on the rank's own data, element i drawing from (seed, i); byte-identical to
+ * nz_reduce_frames_step(d_in, nz_compress_sr(d_local, step, seed)).  opts.predictor must be 0. */
+nz_status nz_reduce_local_sr(const void* d_in, size_t in_bytes, const float* d_local, void* d_out, size_t out_cap,
+                             size_t n, float step, uint32_t seed, nz_result* d_res, const nz_opts* opts, void* d_ws,
+                             size_t ws_bytes, void* stream);
 
 /*
  * nz_compress for callers that cannot allocate or hand over scratch memory: code under HIP graph capture,

@@ -79,6 +79,8 @@ def lib():
         L.nz_reduce_frames.argtypes = [vp, sz, vp, sz, vp, sz, sz, f32, vp, po, vp, sz, vp]
         L.nz_reduce_frames.restype = C.c_int
         L.nz_reduce_local.argtypes = [vp, sz, vp, vp, sz, sz, f32, vp, po, vp, sz, vp]
+        L.nz_reduce_local_sr.argtypes = [vp, sz, vp, vp, sz, sz, f32, C.c_uint32, vp, po, vp, sz, vp]
+        L.nz_reduce_local_sr.restype = C.c_int
         L.nz_reduce_local.restype = C.c_int
         L.nz_trace_events.argtypes = [C.POINTER(C.c_void_p), sz]
         L.nz_trace_events.restype = None
@@ -187,6 +189,12 @@ def nz_reduce_local(d_in, in_bytes, d_local, d_out, out_cap, n, eb, d_res, opts,
     return int(lib().nz_reduce_local(d_in.data_ptr(), in_bytes, d_local.data_ptr(), d_out.data_ptr(), out_cap, n,
                                      C.c_float(eb), d_res.data_ptr(), _po(opts), d_ws.data_ptr(), ws_bytes,
                                      _stream(stream)))
+
+
+def nz_reduce_local_sr(d_in, in_bytes, d_local, d_out, out_cap, n, step, seed, d_res, opts, d_ws, ws_bytes, stream=None):
+    return int(lib().nz_reduce_local_sr(d_in.data_ptr(), in_bytes, d_local.data_ptr(), d_out.data_ptr(), out_cap, n,
+                                        C.c_float(step), seed, d_res.data_ptr(), _po(opts), d_ws.data_ptr(), ws_bytes,
+                                        _stream(stream)))
 
 
 def read_result(d_res):

@@ -306,12 +306,14 @@ nz_status nz_decompress_step(const void* d_stream, size_t stream_bytes, float* d
 // The two reduce entry points differ only in the second operand: a stream (d_b) or the rank's own fp32 data (d_local).
 static nz_status reduce_impl(const void* d_a, size_t a_bytes, const void* d_b, size_t b_bytes, const float* d_local,
                              void* d_out, size_t out_cap, size_t n, float eb, float step, float inv, nz_result* d_res,
-                             const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream) {
+                             const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream, bool stochastic = false,
+                             uint32_t seed = 0) {
     Opts o;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const void* second = d_local ? static_cast<const void*>(d_local) : d_b;
     if (!d_a || !second || !d_out || !d_res || !d_ws || !resolve(opts, o) || !geometry_ok(n, o))
         return NZ_ERR_INVALID;
+    if (stochastic && o.pred) return NZ_ERR_INVALID;               // (the stochastic quantizer is not built with the predictor)
     if (!aligned16(d_a) || !aligned16(second) || !aligned16(d_out) || !aligned16(d_ws) || !aligned16(d_res))
         return NZ_ERR_INVALID;
     const WsLayout L = ws_layout(n, o.chunk, kDecBlock, true);
@@ -325,7 +327,7 @@ static nz_status reduce_impl(const void* d_a, size_t a_bytes, const void* d_b, s
     DecodeArgs D;
     D.a = reinterpret_cast<const uint8_t*>(d_a); D.a_bytes = a_bytes;
     D.b = reinterpret_cast<const uint8_t*>(d_b); D.b_bytes = b_bytes;
-    D.out = nullptr; D.local = d_local; D.eb = eb; D.inv_step = inv;
+    D.out = nullptr; D.local = d_local; D.eb = eb; D.inv_step = inv; D.sr = stochastic ? 1u : 0u; D.seed = seed;
     D.n = n; D.chunk = o.chunk; D.n_frames = nfr; D.K = o.K;
     D.dbpf = (o.chunk + kDecBlock - 1) / kDecBlock; D.pred = o.pred;
     D.step = step; D.step_bits = bits_of(step); D.ws = ws; D.L = L; D.res = d_res;
@@ -340,7 +342,7 @@ static nz_status reduce_impl(const void* d_a, size_t a_bytes, const void* d_b, s
     if (launch_init(ws + L.ctrl, L.zero_end - L.ctrl, d_res, nfr, NZ_OK, st) != hipSuccess) return NZ_ERR_HIP;
     trace_mark(st);
     if (d_local) {
-        if (launch_decode(D, 3, st) != hipSuccess) return NZ_ERR_HIP;       // decode incoming + quantize local + add
+        if (launch_decode(D, stochastic ? 4 : 3, st) != hipSuccess) return NZ_ERR_HIP;   // decode incoming + quantize local + add
         trace_mark(st);
     } else {
         if (launch_decode(D, 1, st) != hipSuccess) return NZ_ERR_HIP;       // stage operand A
@@ -382,6 +384,15 @@ nz_status nz_reduce_local(const void* d_in, size_t in_bytes, const float* d_loca
     float step, inv;
     if (!d_local || !step_constants(eb, step, inv)) return NZ_ERR_INVALID;
     return reduce_impl(d_in, in_bytes, nullptr, 0, d_local, d_out, out_cap, n, eb, step, inv, d_res, opts, d_ws, ws_bytes, stream);
+}
+
+nz_status nz_reduce_local_sr(const void* d_in, size_t in_bytes, const float* d_local, void* d_out, size_t out_cap,
+                             size_t n, float step, uint32_t seed, nz_result* d_res, const nz_opts* opts, void* d_ws,
+                             size_t ws_bytes, void* stream) {
+    float inv;
+    if (!d_local || !step_given(step, inv)) return NZ_ERR_INVALID;
+    return reduce_impl(d_in, in_bytes, nullptr, 0, d_local, d_out, out_cap, n, 0.0f, step, inv, d_res, opts, d_ws, ws_bytes, stream,
+                       true, seed);
 }
 
 }  // extern "C"

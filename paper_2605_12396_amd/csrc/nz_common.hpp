@@ -283,6 +283,7 @@ struct DecodeArgs {
     float* out;                               // decompress only
     const float* local;                       // ring-step reduce only: the rank's own fp32 message
     float eb, inv_step;                       // ring-step reduce only: the quantizer's bound and 1/step
+    uint32_t sr, seed;                        // ring-step reduce only: local data quantized stochastically, with this seed
     uint64_t n;
     uint32_t chunk, n_frames, K, dbpf, pred;
     float step; uint32_t step_bits;

@@ -449,9 +449,11 @@ constexpr uint32_t kTile16Stride = kTile16R + 2;     // halfwords per row: 17 wo
 constexpr int32_t kWideMarker = -32768;              // "this code does not fit 16 bits"
 constexpr uint32_t kHalf = 65536;                    // statistics granularity of the reduce (one encoder group)
 
-enum : int { MODE_DECOMPRESS = 0, MODE_STAGE_A = 1, MODE_ADD_B = 2, MODE_ADD_LOCAL = 3 };
-// the two adding passes: ADD_B adds the staged codes of operand A, ADD_LOCAL the rank's own fp32 data, quantized on the fly
-#define NZ_ADDS(M) ((M) == MODE_ADD_B || (M) == MODE_ADD_LOCAL)
+enum : int { MODE_DECOMPRESS = 0, MODE_STAGE_A = 1, MODE_ADD_B = 2, MODE_ADD_LOCAL = 3, MODE_ADD_LOCAL_SR = 4 };
+// the adding passes: ADD_B adds the staged codes of operand A, ADD_LOCAL the rank's own fp32 data, quantized on the fly
+// (ADD_LOCAL_SR: by the stochastic quantizer)
+#define NZ_LOCAL(M) ((M) == MODE_ADD_LOCAL || (M) == MODE_ADD_LOCAL_SR)
+#define NZ_ADDS(M) ((M) == MODE_ADD_B || NZ_LOCAL(M))
 
 // Shared memory of one decode workgroup.  The window comes first and the tile follows it directly: a reader's
 // prefetch may touch up to two rows past its window, which then fall into the tile (valid shared
@@ -525,6 +527,7 @@ static_assert(kTile16R == 32 && kSeg == 256, "at16 assumes 8 phases of 32 symbol
 struct AddCtx {
     StageA sa; uint32_t* codes; int16_t* c16; uint32_t* s_h; uint32_t* s_cwide; uint32_t* s_lunq;
     const float* local; float eb, inv;
+    bool sr; SrKeys keys;      // stochastic local quantizer: draws by element offset from the workgroup's block
     uint32_t ncs, copy, K; float step; bool a_raw, b_raw;
     __device__ inline void finish(const SegCtx& C, uint32_t i, uint32_t tb, uint32_t (&zmax)[2], uint32_t& overflow) const {
         const uint64_t g = C.f0 + i;
@@ -532,7 +535,8 @@ struct AddCtx {
         uint32_t ta;
         if (local) {
             int32_t q;
-            if (!quantize1(local[g], eb, step, inv, q)) s_lunq[h] = 1u;
+            const bool okq = sr ? sr_quantize1(local[g], step, inv, keys.draw(i - C.blk0), q) : quantize1(local[g], eb, step, inv, q);
+            if (!okq) s_lunq[h] = 1u;
             ta = (uint32_t)q;
         } else ta = sa.get(C.f0, C.nf, i, a_raw);
         if (a_raw || b_raw) { codes[g] = combine<true>(ta, a_raw, tb, b_raw, step, overflow); return; }
@@ -605,7 +609,7 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
         ra.install(pend);
         uint2 pa[LPR];                                // MODE_ADD_B: the staged codes of A this thread will add
         typedef float f32x4 __attribute__((ext_vector_type(4)));
-        f32x4 pl[MODE == MODE_ADD_LOCAL ? LPR : 1];   // MODE_ADD_LOCAL: the rank's own values this thread will add
+        f32x4 pl[NZ_LOCAL(MODE) ? LPR : 1];           // ring step: the rank's own values this thread will add
         if (r0 + kTile16R <= C.cntseg) {
 #pragma unroll
             for (uint32_t h = 0; h < kTile16R; h += kRun) {
@@ -669,7 +673,7 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
                     pa[k] = make_uint2(v.x, v.y);
                 }
             }
-            if (MODE == MODE_ADD_LOCAL) {
+            if (NZ_LOCAL(MODE)) {
                 const float* lp = X.local + C.f0 + eo0 + r0;
 #pragma unroll
                 for (uint32_t k = 0; k < LPR; k++)
@@ -681,13 +685,16 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
                 const uint32_t p0 = src[0], p1 = src[1];
                 const uint32_t h = (k * RPK >= kHalf / kSeg) ? 1u : 0u;       // which half of the block this row is in
                 int32_t Q[4];
-                if (MODE == MODE_ADD_LOCAL) {
+                if (NZ_LOCAL(MODE)) {
                     // quantize the rank's own values; one that cannot be quantized counts as 0 and flags its half
                     int32_t ql[4];
                     const float xl[4] = { pl[k].x, pl[k].y, pl[k].z, pl[k].w };
                     bool ok = true;
+                    const uint32_t off = eo0 + r0 + k * RPK * kSeg - C.blk0;      // element offset inside the workgroup's block
 #pragma unroll
-                    for (uint32_t j = 0; j < 4; j++) ok = quantize1(xl[j], X.eb, X.step, X.inv, ql[j]) && ok;
+                    for (uint32_t j = 0; j < 4; j++)
+                        ok = (MODE == MODE_ADD_LOCAL_SR ? sr_quantize1(xl[j], X.step, X.inv, X.keys.draw(off + j), ql[j])
+                                                        : quantize1(xl[j], X.eb, X.step, X.inv, ql[j])) && ok;
                     if (!ok) X.s_lunq[h] = 1u;
                     Q[0] = (int32_t)(int16_t)(p0 & 0xFFFFu) + ql[0]; Q[1] = ((int32_t)p0 >> 16) + ql[1];
                     Q[2] = (int32_t)(int16_t)(p1 & 0xFFFFu) + ql[2]; Q[3] = ((int32_t)p1 >> 16) + ql[3];
@@ -934,7 +941,9 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
     X.sa.a16 = reinterpret_cast<int16_t*>(A.ws + A.L.a16); X.sa.a32 = reinterpret_cast<uint32_t*>(A.ws + A.L.a32);
     X.codes = reinterpret_cast<uint32_t*>(A.ws + A.L.codes); X.c16 = reinterpret_cast<int16_t*>(A.ws + A.L.c16);
     X.s_cwide = S.cwide; X.s_lunq = S.lunq;
-    X.local = (MODE == MODE_ADD_LOCAL) ? A.local : nullptr; X.eb = A.eb; X.inv = A.inv_step;
+    X.local = NZ_LOCAL(MODE) ? A.local : nullptr; X.eb = A.eb; X.inv = A.inv_step;
+    X.sr = (MODE == MODE_ADD_LOCAL_SR);
+    if (MODE == MODE_ADD_LOCAL_SR) X.keys.init(A.seed, f0 + blk0); else { X.keys.base_lo = 0; X.keys.key0 = 0; X.keys.key1 = 0; }
     X.s_h = s_h; X.K = A.K; X.step = A.step; X.ncs = 0; X.copy = 0; X.a_raw = false; X.b_raw = false;
     uint32_t* akind = reinterpret_cast<uint32_t*>(A.ws + A.L.akind);   // per frame: operand A is RAW
     uint32_t* awide = reinterpret_cast<uint32_t*>(A.ws + A.L.awide);   // per half: some code of A needs 32 bits
@@ -1052,7 +1061,9 @@ __global__ __launch_bounds__(256) void k_fix(DecodeArgs A) {
             if (A.local) {
                 const float x = A.local[f0 + h0 + i];
                 int32_t q;
-                quantize1(x, A.eb, A.step, A.inv_step, q);
+                const uint64_t g = f0 + h0 + i;
+                if (A.sr) sr_quantize1(x, A.step, A.inv_step, sr_draw(sr_key(A.seed, g), (uint32_t)g), q);
+                else quantize1(x, A.eb, A.step, A.inv_step, q);
                 ta = Q - (uint32_t)q;                                   // the incoming code
                 if (lunq) { tb = __float_as_uint(x); b_is_raw = true; } else tb = (uint32_t)q;
             } else {
@@ -1145,9 +1156,12 @@ static void launch_decode_t(DecodeArgs& D, const DecodeArgs& A, int pass, hipStr
     } else if (pass == 2) {
         D.dbpf = (A.chunk + kAddThreads * kSeg - 1) / (kAddThreads * kSeg);
         hipLaunchKernelGGL((k_decode<MODE_ADD_B, kAddThreads, DELTA>), dim3(D.n_frames * D.dbpf), dim3(kAddThreads), 0, st, D);
-    } else {
+    } else if (pass == 3) {
         D.dbpf = (A.chunk + kAddThreads * kSeg - 1) / (kAddThreads * kSeg);
         hipLaunchKernelGGL((k_decode<MODE_ADD_LOCAL, kAddThreads, DELTA>), dim3(D.n_frames * D.dbpf), dim3(kAddThreads), 0, st, D);
+    } else if constexpr (DELTA == 0) {          // (the stochastic ring step is not built with the predictor)
+        D.dbpf = (A.chunk + kAddThreads * kSeg - 1) / (kAddThreads * kSeg);
+        hipLaunchKernelGGL((k_decode<MODE_ADD_LOCAL_SR, kAddThreads, 0>), dim3(D.n_frames * D.dbpf), dim3(kAddThreads), 0, st, D);
     }
 }
 

@@ -138,3 +138,62 @@ def test_sr_index_past_32_bits(nz):
         fr = oracle.frame_encode(q, plan["codec"], o, step_bits=step_bits)
         got = out[int(offs[k]):int(offs[k]) + fr.size].cpu().numpy()
         assert (got == fr).all(), k
+
+
+def _gpu_reduce_local_sr(nz, a_stream, x, step, seed, g):
+    import torch
+    n = x.size
+    sess = nz.Session(n, g, "cuda:0", reduce=True)
+    da = _dev(np.concatenate([a_stream, np.zeros((-a_stream.size) % 16, np.uint8)]))
+    out = sess.new_stream_buffer()
+    rc = nz.nz_reduce_local_sr(da, a_stream.size, _dev(x), out, sess.cap, n, step, seed, sess.res, g, sess.ws, sess.ws_bytes)
+    r = sess.result()
+    return rc, r, out[:r["bytes"]].cpu().numpy()
+
+
+@pytest.mark.parametrize("name", ["ring_chain", "ragged_small_frames", "raw_and_unquantizable", "big_frames", "fixedlen_in"])
+def test_ring_step_with_the_stochastic_quantizer(nz, name):
+    """nz_reduce_local_sr against the oracle: bytes of every step of a chain, frames that turn RAW, large frames on the
+    vectorised path, and the refusals."""
+    if name == "ring_chain":
+        n, kw, peers = 300000, dict(chunk_elems=65536), 4
+    elif name == "ragged_small_frames":
+        n, kw, peers = 30011, dict(chunk_elems=10003), 3
+    elif name == "big_frames":
+        n, kw, peers = 2 * 262144 + 70001, dict(chunk_elems=262144), 3
+    else:
+        n, kw, peers = 100000, dict(chunk_elems=16384), 2
+    g, o = nz.make_opts(**kw), oracle.make_opts(**kw)
+    xs = [W.gradient_like(n, seed=200 + p) for p in range(peers)]
+    if name == "fixedlen_in":
+        xs[0] = W.sweep_payload("uniform", n, 77)
+    step = float(np.float32(max(oracle.qsgd_step(x, 200) for x in xs)))
+    if name == "raw_and_unquantizable":
+        xs[0][5] = np.inf                                   # incoming RAW frame
+        xs[1][40000] = np.nan                               # local value that cannot be quantized
+        xs[1][70000] = np.float32(40000.0 * step)           # beyond 32767 bins
+    acc, _, rc = oracle.compress_sr(xs[0], step, 100, o)
+    assert rc == 0
+    for p in range(1, peers):
+        ref, ores, orc = oracle.reduce_local_sr(acc, xs[p], step, 100 + p, o)
+        rc, r, got = _gpu_reduce_local_sr(nz, acc, xs[p], step, 100 + p, g)
+        assert orc == 0 and rc == 0 and r["status"] == 0, (p, r)
+        assert (r["n_raw"], r["n_fixed"], r["n_huff"], r["bytes"]) == (ores.n_raw, ores.n_fixed, ores.n_huff, ores.bytes)
+        d = np.nonzero(got != ref)[0]
+        assert d.size == 0, "step %d: first differing byte %d" % (p, int(d[0]))
+        acc = ref
+    if name == "raw_and_unquantizable":
+        assert ores.n_raw == 3
+    if name == "ring_chain":
+        import torch
+        sess = nz.Session(n, g, "cuda:0", reduce=True)
+        da = _dev(np.concatenate([acc, np.zeros((-acc.size) % 16, np.uint8)]))
+        out = sess.new_stream_buffer()
+        dx = _dev(xs[1])
+        # a stream made with another width, a predictor, a bad width
+        assert nz.nz_reduce_local_sr(da, acc.size, dx, out, sess.cap, n, step * 2, 1, sess.res, g, sess.ws, sess.ws_bytes) == 0
+        assert sess.result()["status"] == nz.ERR_MISMATCH
+        gp = nz.make_opts(predictor=1, **kw)
+        assert nz.nz_reduce_local_sr(da, acc.size, dx, out, sess.cap, n, step, 1, sess.res, gp, sess.ws, sess.ws_bytes) == nz.ERR_INVALID
+        assert nz.nz_reduce_local_sr(da, acc.size, dx, out, sess.cap, n, float("nan"), 1, sess.res, g, sess.ws, sess.ws_bytes) == nz.ERR_INVALID
+        torch.cuda.synchronize()
