@@ -277,3 +277,41 @@ def test_full_size_message_with_the_predictor(nz):
     ro, rres, rrc = oracle.reduce_local(ref, noise, eb, o)
     assert rc == 0 and rrc == 0 and rr["status"] == 0 and rr["bytes"] == rres.bytes
     assert _first_diff(red[:rr["bytes"]].cpu().numpy(), ro) == -1
+
+
+@pytest.mark.parametrize("predictor", [1, 0], ids=["delta", "plain"])
+def test_garbage_in_streams_with_fixedlen_and_huffman_frames(nz, predictor):
+    """Byte flips anywhere behind the stream header of a stream that holds HUFFMAN, FIXEDLEN and RAW frames: never a
+    fault, the oracle's verdict, and the oracle's output in every element (FIXEDLEN and RAW payloads cannot be told
+    from valid ones: their garbage decodes to the same values on both sides; with the predictor a flipped difference
+    moves the rest of its segment)."""
+    n = 5 * 16384 + 777
+    x = np.concatenate([W.gradient_like(2 * 16384, seed=91), W.sweep_payload("uniform", 2 * 16384, 92),
+                        W.gradient_like(16384 + 777, seed=93)])
+    x[3 * 16384 + 5] = np.inf                                           # frame 3 is RAW
+    eb = 1e-4
+    kw = dict(chunk_elems=16384, predictor=predictor)
+    g, o = nz.make_opts(**kw), oracle.make_opts(**kw)
+    s, sres, rc = oracle.compress(x, eb, o)
+    assert rc == 0 and sres.n_raw == 1 and sres.n_fixed >= 1 and sres.n_huff >= 2
+    rng = np.random.default_rng(17 + predictor)
+    base = 64 + 8 * 6
+    n_rejected = 0
+    for trial in range(80):
+        t = s.copy()
+        for _ in range(int(rng.integers(1, 4))):
+            t[int(rng.integers(base, s.size))] ^= int(rng.integers(1, 256))
+        oref, ores, orc = oracle.decompress(t, n, eb)
+        rc, r, got = gpu_decompress(nz, t, n, eb, g)
+        assert r["status"] == orc, (trial, r, orc)
+        if orc in (0, nz.ERR_CORRUPT) and ores.bytes:
+            assert (r["n_raw"], r["n_fixed"], r["n_huff"]) == (ores.n_raw, ores.n_fixed, ores.n_huff), trial
+            assert (got.view(np.uint32) == oref.view(np.uint32)).all(), trial
+        n_rejected += orc != 0
+        if trial % 4 == 0:                                               # the same stream through the ring step
+            ored, rres, rrc = oracle.reduce_local(t, x, eb, o)
+            rc2, r2, got2 = gpu_reduce_local(nz, t, x, eb, g)
+            assert r2["status"] == rrc, (trial, r2, rrc)
+            if rrc == 0:
+                assert r2["bytes"] == rres.bytes and _first_diff(got2, ored) == -1, trial
+    assert n_rejected > 10
