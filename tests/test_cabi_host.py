@@ -75,3 +75,22 @@ def test_product_package_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".hpp", ".h")):
                 src = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in src and "from oracle" not in src and "nz_oracle" not in src, f
+
+
+def test_public_headers_are_plain_c_and_agree_with_the_bindings(tmp_path):
+    """include/*.h must compile as C99 on their own (no HIP or C++ types in the boundary), and the structures the
+    Python bindings mirror must have the sizes the C compiler gives them."""
+    import ctypes as C
+    import subprocess
+    import oracle
+    from paper_2605_12396_amd import binding as nz
+    src = tmp_path / "h.c"
+    src.write_text('#include "nz.h"\n#include "nz_trace.h"\n#include <stdio.h>\n'
+                   'int main(void) { printf("%zu %zu %zu %zu\\n", sizeof(nz_opts), sizeof(nz_result), sizeof(nz_rea_opts), '
+                   'sizeof(nz_rea_result)); return 0; }\n')
+    exe = tmp_path / "h"
+    inc = os.path.join(ROOT, "include")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", inc, "-o", str(exe), str(src)], check=True)
+    sizes = [int(v) for v in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()]
+    assert sizes == [C.sizeof(nz.Opts), nz.RESULT_BYTES, C.sizeof(nz.ReaOpts), nz.REA_RESULT_BYTES]
+    assert sizes == [C.sizeof(oracle.Opts), C.sizeof(oracle.Result), C.sizeof(oracle.ReaOpts), C.sizeof(oracle.ReaResult)]
