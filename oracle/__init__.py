@@ -104,6 +104,8 @@ def lib():
                                          C.POINTER(ReaPlan)]
         L.nzo_compress_rea.argtypes = [vp, sz, f32, C.POINTER(Opts), C.POINTER(ReaOpts), C.POINTER(Context), vp, sz,
                                        C.POINTER(ReaResult), vp]
+        L.nzo_reduce_local_rea.argtypes = [vp, sz, vp, sz, f32, C.POINTER(Opts), C.POINTER(ReaOpts), C.POINTER(Context), vp, sz,
+                                           C.POINTER(ReaResult), vp]
         _lib = L
     return _lib
 
@@ -290,6 +292,24 @@ def compress_rea(x, eb, opts=None, ropts=None, ctx=None, cap=None):
     rc = lib().nzo_compress_rea(_ptr(x), x.size, C.c_float(eb), C.byref(opts) if opts is not None else None,
                                 C.byref(ropts) if ropts is not None else None,
                                 C.byref(ctx) if ctx is not None else None, _ptr(out), cap, C.byref(res), _ptr(plans))
+    return out[:res.span_bytes].copy(), res, rc, plans
+
+
+def reduce_local_rea(a, x, eb, opts=None, ropts=None, ctx=None, cap=None):
+    """Ring-step reduce with the sampled arbitration on the way out.  Returns (slotted stream trimmed to its span,
+    ReaResult, rc, planned codec per frame)."""
+    a = np.ascontiguousarray(a, dtype=np.uint8)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    if cap is None:
+        o = opts if opts is not None else make_opts()
+        cap = compress_bound(x.size, make_opts(o.chunk_elems, o.seg_syms, o.alphabet, -1, 0, 0))
+    out = np.zeros(max(cap, 1), np.uint8)
+    res = ReaResult()
+    chunk = (opts.chunk_elems if opts is not None and opts.chunk_elems else 262144)
+    plans = np.zeros(max(1, (x.size + chunk - 1) // chunk), np.uint8)
+    rc = lib().nzo_reduce_local_rea(_ptr(a), a.size, _ptr(x), x.size, C.c_float(eb), C.byref(opts) if opts is not None else None,
+                                    C.byref(ropts) if ropts is not None else None,
+                                    C.byref(ctx) if ctx is not None else None, _ptr(out), cap, C.byref(res), _ptr(plans))
     return out[:res.span_bytes].copy(), res, rc, plans
 
 

@@ -1026,6 +1026,29 @@ static uint64_t rea_cost(const nzo_rea_opts* ro, int codec, uint64_t rawb, uint6
     return t;
 }
 
+/* ArbitratePlan on a profiled sample (P->n_s, P->sample_ok, P->w_s, P->sample_bits filled in). */
+static void rea_arbitrate(uint32_t nf, const nzo_opts* o, const nzo_rea_opts* ro, int ctx_ok, nzo_rea_plan* P) {
+    const uint32_t K = o->alphabet;
+    const uint64_t rawb = 4ull * nf;
+    const uint64_t nseg = (nf + o->seg_syms - 1) / o->seg_syms;
+    const uint64_t pred_bits = (P->sample_bits * nf + P->n_s - 1) / P->n_s;
+    P->pred_payload[NZO_FIXEDLEN] = 4ull * (((uint64_t)nf * P->w_s + 31u) / 32u);
+    P->pred_payload[NZO_HUFFMAN] = pad4(K) + pad4(2ull * nseg) + 4ull * ((pred_bits + 31u) / 32u);
+    if (o->force_codec >= 0) {
+        P->plan = (o->force_codec == NZO_HUFFMAN && !ctx_ok) ? NZO_RAW : o->force_codec;
+        return;
+    }
+    uint64_t best_cost = rea_cost(ro, NZO_RAW, rawb, pad16(NZO_HDR_BYTES + rawb));
+    for (int c = NZO_FIXEDLEN; c <= NZO_HUFFMAN; c++) {
+        if (c == NZO_HUFFMAN && (!ctx_ok || rawb < o->huff_min_bytes)) continue;
+        const uint64_t p = P->pred_payload[c];
+        if (p > rawb) continue;                                  /* predicted payload must fit the payload capacity */
+        if ((rawb - p) * 1000ull < (uint64_t)o->min_gain_permil * rawb) continue;
+        const uint64_t t = rea_cost(ro, c, rawb, pad16(NZO_HDR_BYTES + p));
+        if (t < best_cost) { best_cost = t; P->plan = c; }
+    }
+}
+
 static void rea_plan_frame(const float* x, uint32_t nf, float eb, float step, float inv, const nzo_opts* o,
                            const nzo_rea_opts* ro, const nzo_context* ctx, nzo_rea_plan* P) {
     memset(P, 0, sizeof *P);
@@ -1049,23 +1072,31 @@ static void rea_plan_frame(const float* x, uint32_t nf, float eb, float step, fl
     }
     if (!P->sample_ok) return;                                   /* the sample already shows the frame cannot be coded */
     P->w_s = (uint32_t)bit_length32(zmax);
-    const uint64_t nseg = (nf + o->seg_syms - 1) / o->seg_syms;
-    const uint64_t pred_bits = (P->sample_bits * nf + P->n_s - 1) / P->n_s;
-    P->pred_payload[NZO_FIXEDLEN] = 4ull * (((uint64_t)nf * P->w_s + 31u) / 32u);
-    P->pred_payload[NZO_HUFFMAN] = pad4(K) + pad4(2ull * nseg) + 4ull * ((pred_bits + 31u) / 32u);
-    if (o->force_codec >= 0) {
-        P->plan = (o->force_codec == NZO_HUFFMAN && !ctx_ok) ? NZO_RAW : o->force_codec;
-        return;
+    rea_arbitrate(nf, o, ro, ctx_ok, P);
+}
+
+/* The same for a frame that exists as integer codes already (the sums of a reduce step): the sample is the prefix
+ * of the codes, every code is codable. */
+static void rea_plan_codes(const int32_t* q, uint32_t nf, const nzo_opts* o, const nzo_rea_opts* ro,
+                           const nzo_context* ctx, nzo_rea_plan* P) {
+    memset(P, 0, sizeof *P);
+    const uint32_t K = o->alphabet;
+    const uint64_t rawb = 4ull * nf;
+    P->pred_payload[NZO_RAW] = rawb;
+    P->plan = NZO_RAW;
+    if (rawb < ro->small_batch_bytes) return;
+    P->n_s = ro->sample_bytes / 4u < nf ? ro->sample_bytes / 4u : nf;
+    if (P->n_s == 0) return;
+    const int ctx_ok = ctx && ctx->valid && ctx->K == K;
+    uint32_t zmax = 0;
+    P->sample_ok = 1;
+    for (uint32_t i = 0; i < P->n_s; i++) {
+        uint32_t z = nzo_zigzag(q[i]);
+        if (z > zmax) zmax = z;
+        if (ctx_ok) { uint32_t s = sym_of(z, K); P->sample_bits += ctx->len[s] + (s == 0 ? 32u : 0u); }
     }
-    uint64_t best_cost = rea_cost(ro, NZO_RAW, rawb, pad16(NZO_HDR_BYTES + rawb));
-    for (int c = NZO_FIXEDLEN; c <= NZO_HUFFMAN; c++) {
-        if (c == NZO_HUFFMAN && (!ctx_ok || rawb < o->huff_min_bytes)) continue;
-        const uint64_t p = P->pred_payload[c];
-        if (p > rawb) continue;                                  /* predicted payload must fit the payload capacity */
-        if ((rawb - p) * 1000ull < (uint64_t)o->min_gain_permil * rawb) continue;
-        const uint64_t t = rea_cost(ro, c, rawb, pad16(NZO_HDR_BYTES + p));
-        if (t < best_cost) { best_cost = t; P->plan = c; }
-    }
+    P->w_s = (uint32_t)bit_length32(zmax);
+    rea_arbitrate(nf, o, ro, ctx_ok, P);
 }
 
 int nzo_rea_plan_frame(const float* x, uint32_t nf, float eb, const nzo_opts* opts, const nzo_rea_opts* ropts,
@@ -1088,17 +1119,11 @@ int nzo_rea_plan_frame(const float* x, uint32_t nf, float eb, const nzo_opts* op
  * Returns the codec committed; *total = the frame's padded bytes; *fell_back = 1 if a non-RAW plan was
  * rejected.
  */
-static int rea_commit_frame(uint8_t* dst, const float* x, uint32_t nf, float eb, float step, float inv,
-                            const nzo_opts* o, const nzo_context* ctx, const nzo_rea_plan* P, uint32_t step_bits,
-                            int32_t* q, uint32_t* rb, frame_plan* FP, uint64_t* total, int* fell_back) {
+static int rea_commit_codes(uint8_t* dst, const int32_t* q, const uint32_t* rb, int ok, uint32_t nf, const nzo_opts* o,
+                            const nzo_context* ctx, const nzo_rea_plan* P, uint32_t step_bits, frame_plan* FP,
+                            uint64_t* total, int* fell_back) {
     const uint64_t rawb = 4ull * nf;
     *fell_back = 0;
-    int ok = 1;
-    for (uint32_t i = 0; i < nf; i++) {
-        rb[i] = f32_bits(x[i]);
-        q[i] = 0;
-        if (P->plan != NZO_RAW && !nzo_quantize_one(x[i], eb, step, inv, &q[i])) ok = 0;
-    }
     memset(FP, 0, sizeof *FP);
     FP->payload[NZO_RAW] = rawb; FP->total[NZO_RAW] = pad16(NZO_HDR_BYTES + rawb);
     int codec = NZO_RAW;
@@ -1126,6 +1151,18 @@ static int rea_commit_frame(uint8_t* dst, const float* x, uint32_t nf, float eb,
     write_frame(dst, codec, q, rb, nf, FP, o, step_bits);
     *total = FP->total[codec];
     return codec;
+}
+
+static int rea_commit_frame(uint8_t* dst, const float* x, uint32_t nf, float eb, float step, float inv,
+                            const nzo_opts* o, const nzo_context* ctx, const nzo_rea_plan* P, uint32_t step_bits,
+                            int32_t* q, uint32_t* rb, frame_plan* FP, uint64_t* total, int* fell_back) {
+    int ok = 1;
+    for (uint32_t i = 0; i < nf; i++) {
+        rb[i] = f32_bits(x[i]);
+        q[i] = 0;
+        if (P->plan != NZO_RAW && !nzo_quantize_one(x[i], eb, step, inv, &q[i])) ok = 0;
+    }
+    return rea_commit_codes(dst, q, rb, ok, nf, o, ctx, P, step_bits, FP, total, fell_back);
 }
 
 /*
@@ -1183,6 +1220,94 @@ int nzo_compress_rea(const float* x, size_t n, float eb, const nzo_opts* opts, c
     return NZO_OK;
 }
 
+
+/*
+ * Ring-step reduce with the sampled arbitration on the way out (the receive-reduce-send step of Sec. IV-D with the
+ * selector of Sec. IV-C / Algorithm 1 in front of the send, as the paper's pipeline has it): the incoming stream is
+ * decoded, the rank's own data quantized and added exactly as in nzo_reduce_local; every output frame is then
+ * committed by Algorithm 1 on its integer sums -- plan from a prefix sample of the sums and the cached context, only
+ * the planned codec materialised, realized size validated, RAW otherwise -- into the slotted stream of
+ * nzo_compress_rea.  A frame that has no integer sums (incoming frame RAW, local element that cannot be quantized, a
+ * sum beyond 2^30) is RAW with the fp32 sums of nzo_reduce_local and counts neither as planned nor as fallback.  The
+ * RAW form of a coded frame whose realized output is rejected holds the sums of the dequantized operands,
+ * fl32(fl32(qa*step) + fl32(qb*step)), like any frame whose codes cannot be carried on.
+ */
+int nzo_reduce_local_rea(const uint8_t* in, size_t in_bytes, const float* local, size_t n, float eb, const nzo_opts* opts,
+                         const nzo_rea_opts* ropts, const nzo_context* ctx, uint8_t* out, size_t cap, nzo_rea_result* res,
+                         uint8_t* plans) {
+    nzo_opts o; stream_hdr hi; float step, inv;
+    nzo_rea_opts ro = { 65536u, 0u, 0u, 0u, 0u, 0u, 0u, 0u };
+    nzo_rea_result dummy;
+    if (!res) res = &dummy;
+    memset(res, 0, sizeof *res);
+    if (ropts) { ro = *ropts; if (ro.sample_bytes == 0) ro.sample_bytes = 65536u; }
+    if (n == 0 || !in || !local || !out || ro.reserved) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
+    if (resolve_opts(opts, &o) || nzo_step_constants(eb, &step, &inv) || o.predictor) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
+    int rc = parse_stream(in, in_bytes, &hi);
+    if (rc) { res->status = (uint32_t)rc; return rc; }
+    if (hi.n != n || hi.chunk != o.chunk_elems || hi.step_bits != f32_bits(step) || hi.predictor != 0u) {
+        res->status = NZO_ERR_MISMATCH; return NZO_ERR_MISMATCH;
+    }
+    const uint32_t nfr = hi.n_frames;
+    res->n_frames = nfr;
+    const uint64_t base = frames_base(nfr), slot = pad16(NZO_HDR_BYTES + 4ull * o.chunk_elems);
+    const uint32_t last_nf = (uint32_t)(n - (uint64_t)(nfr - 1) * o.chunk_elems);
+    const uint64_t need = base + (uint64_t)(nfr - 1) * slot + pad16(NZO_HDR_BYTES + 4ull * last_nf);
+    if (need > cap) { res->status = NZO_ERR_CAPACITY; return NZO_ERR_CAPACITY; }
+    int32_t* qa = (int32_t*)malloc(4ull * n); int32_t* qb = (int32_t*)malloc(4ull * n);
+    uint32_t* ra = (uint32_t*)malloc(4ull * n); uint32_t* rb = (uint32_t*)malloc(4ull * n);
+    uint8_t* fa = (uint8_t*)calloc(nfr, 1); uint8_t* fb = (uint8_t*)calloc(nfr, 1);
+    int32_t* q = (int32_t*)malloc(4ull * o.chunk_elems);
+    uint32_t* rw = (uint32_t*)malloc(4ull * o.chunk_elems);
+    frame_plan* FP = (frame_plan*)malloc(sizeof *FP);
+    if (!qa || !qb || !ra || !rb || !fa || !fb || !q || !rw || !FP) rc = NZO_ERR_INVALID;
+    if (!rc) rc = nzo_decode_codes(in, in_bytes, n, eb, qa, ra, fa, NULL);
+    if (!rc) {
+        for (uint32_t k = 0; k < nfr; k++) {
+            const uint64_t i0 = (uint64_t)k * o.chunk_elems;
+            const uint64_t i1 = (i0 + o.chunk_elems < n) ? i0 + o.chunk_elems : n;
+            int all_ok = 1;
+            for (uint64_t i = i0; i < i1; i++) {
+                int32_t v = 0;
+                if (!nzo_quantize_one(local[i], eb, step, inv, &v)) all_ok = 0;
+                qb[i] = v; rb[i] = f32_bits(local[i]);
+            }
+            fb[k] = all_ok ? 0 : 1;
+        }
+        memset(out, 0, (size_t)need);
+        const uint32_t step_bits = f32_bits(step);
+        reduce_ctx c = { qa, qb, ra, rb, fa, fb, step };
+        uint64_t wire = base, end = base;
+        for (uint32_t k = 0; k < nfr; k++) {
+            const uint64_t i0 = (uint64_t)k * o.chunk_elems;
+            const uint32_t nf = (uint32_t)((n - i0 < o.chunk_elems) ? (n - i0) : o.chunk_elems);
+            const uint64_t off = base + (uint64_t)k * slot;
+            nzo_rea_plan P;
+            uint64_t total = 0; int fell = 0;
+            const int coded = reduce_src(&c, k, i0, nf, q, rw);          /* integer sums, or the fp32 sums of a frame without them */
+            if (coded) {
+                for (uint32_t i = 0; i < nf; i++)                        /* what the frame holds should it end up RAW */
+                    rw[i] = canon_sum_bits(nzo_dequantize_one(qa[i0 + i], step), nzo_dequantize_one(qb[i0 + i], step));
+                rea_plan_codes(q, nf, &o, &ro, ctx, &P);
+            } else {
+                memset(&P, 0, sizeof P);
+                P.plan = NZO_RAW;
+            }
+            int cdc = rea_commit_codes(out + off, q, rw, 1, nf, &o, ctx, &P, step_bits, FP, &total, &fell);
+            put_u64(out + NZO_STREAM_HDR + 8ull * k, off);
+            if (plans) plans[k] = (uint8_t)P.plan;
+            wire += total; end = off + total;
+            res->n_fallback += (uint32_t)fell;
+            if (cdc == NZO_RAW) res->n_raw++; else if (cdc == NZO_FIXEDLEN) res->n_fixed++; else res->n_huff++;
+        }
+        write_stream_header(out, n, &o, nfr, step_bits, end);
+        res->span_bytes = end; res->wire_bytes = wire; res->status = NZO_OK;
+    } else {
+        res->status = (uint32_t)rc;
+    }
+    free(qa); free(qb); free(ra); free(rb); free(fa); free(fb); free(q); free(rw); free(FP);
+    return rc;
+}
 
 /* ------------------------------------------------------------------ */
 /* 11. stochastic interface quantizer (QSGD, Sec. II-B "Quantization",  */

@@ -46,6 +46,10 @@ static int run_case(size_t n, uint32_t chunk, uint32_t K, uint32_t seg, int forc
         if (nzo_decompress(sr, rr.span_bytes, z, n, eb, &rc)) return 13;
         if (nzo_compress_rea(y, n, eb, &od, &ro, NULL, sr, rcap, &rr, NULL)) return 14;
         if (rcap > 16 && nzo_compress_rea(y, n, eb, &od, &ro, &ctx, sr, rcap - 16, &rr, NULL) != NZO_ERR_CAPACITY) return 15;
+        /* the ring step with the sampled arbitration on the way out */
+        if (nzo_reduce_local_rea(sa, ra.bytes, y, n, eb, &od, &ro, &ctx, sr, rcap, &rr, NULL)) return 16;
+        if (nzo_decompress(sr, rr.span_bytes, z, n, eb, &rc)) return 17;
+        if (nzo_reduce_local_rea(sa, ra.bytes, y, n, eb, &od, NULL, NULL, sr, rcap, &rr, NULL)) return 18;
         free(sr);
     }
     /* delta predictor: compress, decode, reduce */
@@ -72,6 +76,7 @@ static int run_case(size_t n, uint32_t chunk, uint32_t K, uint32_t seg, int forc
         if (nzo_compress_sr(y, n, st, 7u, &od, s1, scap, &r1) || nzo_compress_sr(x, n, st, 8u, &od, s2, scap, &r2)) return 17;
         if (nzo_decompress_step(s1, r1.bytes, z, n, st, &rc)) return 18;
         if (nzo_reduce_frames_step(s1, r1.bytes, s2, r2.bytes, s3, scap, n, st, &od, &rc)) return 19;
+        if (nzo_reduce_local_sr(s1, r1.bytes, x, s3, scap, n, st, 8u, &od, &rc)) return 24;
         free(s1); free(s2); free(s3);
     }
     /* too small an output: capacity error, nothing written past cap */

@@ -360,3 +360,80 @@ def test_whole_message_under_a_transport_hint():
     assert oracle.compress_rea(x, eb, o, bad, ctx)[2] == oracle.ERR_INVALID
     with pytest.raises(ValueError):
         oracle.rea_plan_frame(x[:1000], eb, o, bad, ctx)
+
+
+# ------------------------------------------------------------------------------------------------
+# the ring step with the sampled arbitration on the way out
+# ------------------------------------------------------------------------------------------------
+
+def _frame_bytes(stream, k):
+    off = int(stream[64 + 8 * k:64 + 8 * k + 8].view(np.uint64)[0])
+    payload = int(stream[off + 12:off + 16].view(np.uint32)[0])
+    return stream[off:off + 32 + payload]
+
+
+def test_ring_step_frames_are_the_sampled_frames_of_the_summed_codes():
+    """With step = 1 the integer sums of the ring step are themselves fp32 values that quantize to exactly those sums,
+    so nzo_reduce_local_rea(in, x) must write, frame for frame and byte for byte, what the (separately pinned)
+    nzo_compress_rea writes for the message a + x: same plans, same realized frames, same fallbacks, same counters."""
+    rng = np.random.default_rng(41)
+    nf, nfr = 20000, 6
+    n = nf * nfr - 777
+    za = rng.integers(0, 40, n)
+    zx = rng.integers(0, 40, n)
+    za[2 * nf:3 * nf] = rng.integers(0, 30000, nf)            # frame 2: wide codes -> FIXEDLEN or RAW territory
+    zx[3 * nf + 9000] = 20000                                 # frame 3: one wide value behind the sample -> fallback for FIXEDLEN
+    za[4 * nf:5 * nf] = 0; zx[4 * nf:5 * nf] = 0              # frame 4: all zero
+    a, x = _unzig(za), _unzig(zx)
+    assert np.abs(a + x).max() <= 32767
+    for kw, rop in ((dict(), None), (dict(force_codec=1), None), (dict(force_codec=2), None), (dict(min_gain_permil=600), None),
+                    (dict(), oracle.ReaOpts(4096, 0, 0, 0, 0, 0, 0, 0)), (dict(), oracle.ReaOpts(0, 0, 40, 100, 2, 700, 6, 0))):
+        o = oracle.make_opts(chunk_elems=nf, **kw)
+        ctx = oracle.context_build(_unzig(rng.integers(0, 60, 30000)), EB1, oracle.make_opts(chunk_elems=nf))
+        sa, _, rc = oracle.compress(a, EB1, oracle.make_opts(chunk_elems=nf))
+        out, res, rc2, plans = oracle.reduce_local_rea(sa, x, EB1, o, rop, ctx)
+        ref, rres, rc3, rplans = oracle.compress_rea(a + x, EB1, o, rop, ctx)
+        assert rc == 0 and rc2 == 0 and rc3 == 0
+        assert res.as_dict() == rres.as_dict() and (plans == rplans).all(), (kw, res.as_dict(), rres.as_dict())
+        for k in range(nfr):
+            assert np.array_equal(_frame_bytes(out, k), _frame_bytes(ref, k)), (kw, k)
+    assert res.n_frames == nfr
+
+
+def test_ring_step_codes_raw_rules_and_fallback_values():
+    n = 70001
+    kw = dict(chunk_elems=20000)
+    o = oracle.make_opts(**kw)
+    eb = 1e-4
+    a, x = W.gradient_like(n, seed=51), W.gradient_like(n, seed=52)
+    a[25000] = np.inf                                         # incoming frame 1 RAW
+    x[45000] = np.nan                                         # local frame 2 cannot be quantized
+    ctx = oracle.context_build(W.gradient_like(30000, seed=53), eb, o)
+    sa, _, _ = oracle.compress(a, eb, o)
+    out, res, rc, plans = oracle.reduce_local_rea(sa, x, eb, o, None, ctx)
+    exact, eres, erc = oracle.reduce_local(sa, x, eb, o)
+    assert rc == 0 and erc == 0 and res.n_raw == 2 and res.n_fallback == 0 and list(plans[1:3]) == [0, 0]
+    # coded frames carry the exact integer sums; frames without integer sums are the exact path's RAW frames
+    q, rb, kinds, _, drc = oracle.decode_codes(out, n, eb)
+    qe, rbe, kindse, _, _ = oracle.decode_codes(exact, n, eb)
+    assert drc == 0 and (kinds == kindse).all() and (q == qe).all() and (rb == rbe).all()
+    qa, _ = oracle.quantize(np.where(np.isfinite(a), a, 0), eb)
+    qx, _ = oracle.quantize(np.where(np.isfinite(x), x, 0), eb)
+    coded = np.repeat(kinds == 0, 20000)[:n]
+    assert (q[coded] == (qa + qx)[coded]).all()
+    # the exact selector never loses to the sampled one, frame by frame
+    for k in range(4):
+        assert _frame_bytes(out, k).size >= _frame_bytes(exact, k).size
+    # a coded frame whose realized output is rejected holds the sums of the dequantized operands
+    om = oracle.make_opts(min_gain_permil=990, force_codec=2, **kw)
+    out2, res2, rc2, plans2 = oracle.reduce_local_rea(sa, x, eb, om, None, ctx)
+    assert rc2 == 0 and res2.n_fallback == 2 and res2.n_raw == 4
+    y, _, _ = oracle.decompress(out2, n, eb)
+    st = oracle.step_constants(eb)[0]
+    want = (qa[:20000].astype(np.float32) * st) + (qx[:20000].astype(np.float32) * st)
+    assert (y[:20000].view(np.uint32) == want.astype(np.float32).view(np.uint32)).all()
+    # refusals
+    assert oracle.reduce_local_rea(sa, x, 2e-4, o, None, ctx)[2] == oracle.ERR_MISMATCH
+    assert oracle.reduce_local_rea(sa, x, eb, oracle.make_opts(predictor=1, **kw), None, ctx)[2] == oracle.ERR_INVALID
+    assert oracle.reduce_local_rea(sa, x, eb, o, oracle.ReaOpts(0, 0, 0, 0, 0, 0, 0, 7), ctx)[2] == oracle.ERR_INVALID
+    assert oracle.reduce_local_rea(sa, x, eb, o, None, ctx, cap=1000)[2] == oracle.ERR_CAPACITY
