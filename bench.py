@@ -454,6 +454,15 @@ def main():
     def compress_rea_call(k):
         return nz.nz_compress_rea(xs[k], n, eb, ctx, rea_out, sess.cap, rea_res, opts, None, rea_ws, rea_wsb)
 
+    # the ring step with the sampled arbitration on the way out (not part of `value` either)
+    rr_wsb = nz.nz_reduce_rea_workspace_bytes(n, opts)
+    rr_ws = torch.empty(rr_wsb, dtype=torch.uint8, device=dev)
+    rr_res = torch.zeros(48, dtype=torch.uint8, device=dev)
+    rr_out = torch.empty(sess.cap, dtype=torch.uint8, device=dev)
+
+    def reduce_local_rea_call(k2):
+        return nz.nz_reduce_local_rea(outs[k2], stream_bytes, xpeer, n, eb, ctx, rr_out, sess.cap, rr_res, opts, None, rr_ws, rr_wsb)
+
     def step(i):
         k, k2 = i % R, (i + 1) % R
         a = b = c = 0
@@ -490,7 +499,8 @@ def main():
     names = {"compress": ["stats", "codebook", "encode"], "decompress": ["decode", "finish"],
              "reduce": ["init", "stage_a", "add_b", "fix", "codebook", "encode"],
              "reduce_local": ["init", "add_local", "fix", "codebook", "encode"],
-             "compress_rea": ["encode", "finish"]}
+             "compress_rea": ["encode", "finish"],
+             "reduce_local_rea": ["init", "add_local", "fix", "encode", "finish"]}
     acc = {k: [0.0] * len(v) for k, v in names.items()}
     reps = max(5, min(args.steps, 20))
 
@@ -518,6 +528,9 @@ def main():
             compress_rea(k2)
             for j, t in enumerate(tr.kernel_ms()):
                 acc["compress_rea"][j] += t
+            assert reduce_local_rea_call(k2) == 0
+            for j, t in enumerate(tr.kernel_ms()):
+                acc["reduce_local_rea"][j] += t
     kern = {st: {nm: acc[st][j] / reps for j, nm in enumerate(names[st])} for st in names}
     # frames on which the sampled plan committed another codec than the exact selector (mis-selection count)
     nfr = r0["n_frames"]
@@ -550,6 +563,9 @@ def main():
     alg_op = {"compress": 4.0 * n + stream_bytes, "decompress": stream_bytes + 4.0 * n,
               "reduce": stream_bytes + peer_bytes + reduce_bytes, "reduce_local": stream_bytes + 4.0 * n + reduce_bytes,
               "compress_rea": 4.0 * n + rea["wire_bytes"]}
+    rrea = nz.read_rea_result(rr_res)
+    assert rrea["status"] == 0
+    alg_op["reduce_local_rea"] = stream_bytes + 4.0 * n + rrea["wire_bytes"]
     alg = {("compress", "stats"): 4.0 * n, ("compress", "encode"): 4.0 * n + stream_bytes,
            ("decompress", "decode"): 4.0 * n + stream_bytes,
            ("reduce", "stage_a"): float(stream_bytes), ("reduce", "add_b"): float(peer_bytes),
@@ -596,7 +612,11 @@ def main():
                                              ratio_loss_vs_exact=1.0 - stream_bytes / rea["wire_bytes"],
                                              frames=dict(raw=rea["n_raw"], fixed=rea["n_fixed"], huffman=rea["n_huff"],
                                                          fallback=rea["n_fallback"]),
-                                             frames_with_other_codec_than_exact=int(misselected))),
+                                             frames_with_other_codec_than_exact=int(misselected)),
+                           reduce_local_rea=dict(GBps=ops["reduce_local_rea"]["input_GBps"], frac_hbm=ops["reduce_local_rea"]["input_frac_hbm"],
+                                                 wire_bytes=rrea["wire_bytes"], exact_bytes=reduce_bytes,
+                                                 frames=dict(raw=rrea["n_raw"], fixed=rrea["n_fixed"], huffman=rrea["n_huff"],
+                                                             fallback=rrea["n_fallback"]))),
                roofline=roofline)
     if not args.no_cpu_baseline:
         base, ref_stream, ref_reduced = cpu_baseline(wl, args.alphabet)

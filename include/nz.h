@@ -169,6 +169,23 @@ nz_status nz_compress_rea(const float* d_in, size_t n, float eb, const void* d_c
                           void* stream);
 
 /*
+ * The ring step with the sampled arbitration on the way out: nz_reduce_local whose output frames are committed by
+ * Algorithm 1 instead of the exact selector, as in the paper's receive-reduce-send pipeline (Sec. IV-D with Sec. IV-C
+ * in front of the send).  The incoming stream is decoded and the rank's own data quantized and added as in
+ * nz_reduce_local; every frame of integer sums is then planned from a prefix sample of its sums and the cached
+ * context, only the planned codec is materialised, the realized size validated, and the frame stored RAW otherwise.
+ * A RAW frame of integer sums (planned so, or fallen back) holds fl32(fl32(qa*step) + fl32(qb*step)); a frame that
+ * has no integer sums (incoming frame RAW, local value that cannot be quantized, a sum beyond 2^30) is RAW with the
+ * fp32 sums of nz_reduce_local and counts neither as planned nor as fallback.  Output: the slotted stream of
+ * nz_compress_rea; d_res as there (status carries an error of the incoming stream; then nothing is published).
+ *   d_ws/ws_bytes  device scratch of at least nz_reduce_rea_workspace_bytes(n, opts).  opts.predictor must be 0.
+ */
+size_t    nz_reduce_rea_workspace_bytes(size_t n, const nz_opts* opts);
+nz_status nz_reduce_local_rea(const void* d_in, size_t in_bytes, const float* d_local, size_t n, float eb, const void* d_ctx,
+                              void* d_out, size_t out_cap, nz_rea_result* d_res, const nz_opts* opts, const nz_rea_opts* ropts,
+                              void* d_ws, size_t ws_bytes, void* stream);
+
+/*
  * Stochastic interface quantizer (QSGD, Sec. II-B "Quantization", Sec. IV-B): nz_compress_sr is nz_compress with
  * randomized rounding in the place of round-to-nearest.  Values are rounded to multiples of `step` (finite,
  * 2^-100 <= step <= 2^101): with a = |x| / step the level is floor(a) + 1 with probability a - floor(a), else

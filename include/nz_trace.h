@@ -11,6 +11,7 @@
  *   nz_reduce_frames  init, stage A, decode B + add, fix (late RAW frames), codebook + selector, encode
  *   nz_reduce_local   init, decode + quantize local + add, fix, codebook + selector, encode
  *   nz_compress_rea   encode (every workgroup profiles the frame's sample first), finish
+ *   nz_reduce_local_rea   init, decode + quantize local + add, fix, encode (profiles the staged sums first), finish
  * (nz_compress_sr, nz_compress_static: as nz_compress; the *_step forms as their namesakes.  With the delta
  * predictor the reduces run one more kernel, the statistics of the staged sums, inside the "codebook" interval.)
  */

@@ -74,6 +74,10 @@ def lib():
         L.nz_rea_workspace_bytes.restype = sz
         L.nz_compress_rea.argtypes = [vp, sz, f32, vp, vp, sz, vp, po, C.POINTER(ReaOpts), vp, sz, vp]
         L.nz_compress_rea.restype = C.c_int
+        L.nz_reduce_rea_workspace_bytes.argtypes = [sz, po]
+        L.nz_reduce_rea_workspace_bytes.restype = sz
+        L.nz_reduce_local_rea.argtypes = [vp, sz, vp, sz, f32, vp, vp, sz, vp, po, C.POINTER(ReaOpts), vp, sz, vp]
+        L.nz_reduce_local_rea.restype = C.c_int
         L.nz_decompress.argtypes = [vp, sz, vp, sz, f32, vp, po, vp, sz, vp]
         L.nz_decompress.restype = C.c_int
         L.nz_reduce_frames.argtypes = [vp, sz, vp, sz, vp, sz, sz, f32, vp, po, vp, sz, vp]
@@ -164,6 +168,17 @@ def nz_compress_rea(d_in, n, eb, d_ctx, d_out, out_cap, d_res, opts, ropts, d_ws
                                      d_out.data_ptr(), out_cap, d_res.data_ptr(), _po(opts),
                                      C.byref(ropts) if ropts is not None else None, d_ws.data_ptr(), ws_bytes,
                                      _stream(stream)))
+
+
+def nz_reduce_rea_workspace_bytes(n, opts=None):
+    return int(lib().nz_reduce_rea_workspace_bytes(n, _po(opts)))
+
+
+def nz_reduce_local_rea(d_in, in_bytes, d_local, n, eb, d_ctx, d_out, out_cap, d_res, opts, ropts, d_ws, ws_bytes, stream=None):
+    return int(lib().nz_reduce_local_rea(d_in.data_ptr(), in_bytes, d_local.data_ptr(), n, C.c_float(eb),
+                                         d_ctx.data_ptr() if d_ctx is not None else None, d_out.data_ptr(), out_cap,
+                                         d_res.data_ptr(), _po(opts), C.byref(ropts) if ropts is not None else None,
+                                         d_ws.data_ptr(), ws_bytes, _stream(stream)))
 
 
 def read_rea_result(d_res):

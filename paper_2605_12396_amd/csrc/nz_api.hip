@@ -386,6 +386,84 @@ nz_status nz_reduce_local(const void* d_in, size_t in_bytes, const float* d_loca
     return reduce_impl(d_in, in_bytes, nullptr, 0, d_local, d_out, out_cap, n, eb, step, inv, d_res, opts, d_ws, ws_bytes, stream);
 }
 
+// Workspace of the sampled ring step: the adding pass's workspace, a result record of its own for that pass, and
+// the sampled path's part (plans are kept in the first, realized sizes, flags and group scratch in the last).
+struct RedReaLayout { WsLayout R; size_t add_res; size_t rea; ReaLayout E; size_t total; };
+static RedReaLayout red_rea_layout(size_t n, uint32_t chunk) {
+    RedReaLayout L;
+    L.R = ws_layout(n, chunk, kDecBlock, true);
+    L.add_res = (L.R.total + 255u) & ~(size_t)255u;
+    L.rea = L.add_res + 256u;
+    L.E = rea_layout(n, chunk);
+    L.total = L.rea + L.E.total;
+    return L;
+}
+
+size_t nz_reduce_rea_workspace_bytes(size_t n, const nz_opts* opts) {
+    Opts o;
+    if (!resolve(opts, o) || !geometry_ok(n, o)) return 0;
+    return red_rea_layout(n, o.chunk).total;
+}
+
+nz_status nz_reduce_local_rea(const void* d_in, size_t in_bytes, const float* d_local, size_t n, float eb, const void* d_ctx,
+                              void* d_out, size_t out_cap, nz_rea_result* d_res, const nz_opts* opts, const nz_rea_opts* ropts,
+                              void* d_ws, size_t ws_bytes, void* stream) {
+    Opts o; float step, inv;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (!d_in || !d_local || !d_out || !d_res || !d_ws || !resolve(opts, o) || !geometry_ok(n, o) || !step_constants(eb, step, inv))
+        return NZ_ERR_INVALID;
+    if (!aligned16(d_in) || !aligned16(d_local) || !aligned16(d_out) || !aligned16(d_ws) || !aligned16(d_res) ||
+        (d_ctx && !aligned16(d_ctx))) return NZ_ERR_INVALID;
+    if (o.pred) return NZ_ERR_INVALID;                            // the sampled path codes the codes themselves
+    if (ropts && ropts->reserved) return NZ_ERR_INVALID;
+    const RedReaLayout L = red_rea_layout(n, o.chunk);
+    if (ws_bytes < L.total) return NZ_ERR_INVALID;
+    const uint32_t nfr = (uint32_t)((n + o.chunk - 1) / o.chunk);
+    const uint64_t slot = pad16h(kHdrBytes + 4ull * o.chunk);
+    const uint64_t last = n - (uint64_t)(nfr - 1) * o.chunk;
+    const uint64_t need = kStreamHdr + pad16h(8ull * nfr) + (uint64_t)(nfr - 1) * slot + pad16h(kHdrBytes + 4ull * last);
+    if (out_cap < need) {                                          // every frame needs its RAW-sized slot: publish nothing
+        if (launch_rea_status(d_res, nfr, NZ_ERR_CAPACITY, st) != hipSuccess) return NZ_ERR_HIP;
+        return NZ_ERR_CAPACITY;
+    }
+    uint8_t* ws = reinterpret_cast<uint8_t*>(d_ws);
+    DecodeArgs D;
+    D.a = reinterpret_cast<const uint8_t*>(d_in); D.a_bytes = in_bytes; D.b = nullptr; D.b_bytes = 0;
+    D.out = nullptr; D.local = d_local; D.eb = eb; D.inv_step = inv; D.sr = 0; D.seed = 0;
+    D.n = n; D.chunk = o.chunk; D.n_frames = nfr; D.K = o.K;
+    D.dbpf = (o.chunk + kDecBlock - 1) / kDecBlock; D.pred = 0;
+    D.step = step; D.step_bits = bits_of(step); D.ws = ws; D.L = L.R; D.res = ws + L.add_res;
+    ReaArgs A;
+    A.in = nullptr; A.n = n; A.chunk = o.chunk; A.n_frames = nfr; A.K = o.K;
+    A.gpf = (o.chunk + kEncGroup - 1) / kEncGroup;
+    A.force_codec = o.force; A.min_gain_permil = o.gain; A.huff_min_bytes = o.huff_min;
+    uint32_t sample_bytes = 65536u, small = 0u;
+    A.link_ps = 0; A.fixed_alpha_ns = 0; A.fixed_ps = 0; A.huff_alpha_ns = 0; A.huff_ps = 0;
+    if (ropts) {
+        if (ropts->sample_bytes) sample_bytes = ropts->sample_bytes;
+        small = ropts->small_batch_bytes;
+        A.link_ps = ropts->link_ps_per_byte;
+        A.fixed_alpha_ns = ropts->fixed_alpha_ns; A.fixed_ps = ropts->fixed_ps_per_byte;
+        A.huff_alpha_ns = ropts->huff_alpha_ns; A.huff_ps = ropts->huff_ps_per_byte;
+    }
+    A.sample_elems = sample_bytes / 4u; A.small_batch_bytes = small;
+    A.eb = eb; A.step = step; A.inv_step = inv; A.step_bits = bits_of(step);
+    A.ctx = reinterpret_cast<const DevContext*>(d_ctx);
+    A.out = reinterpret_cast<uint8_t*>(d_out); A.slot = slot;
+    A.ws = ws + L.rea; A.L = L.E; A.res = d_res;
+    A.tmp_base = reinterpret_cast<uint32_t*>(A.ws + L.E.tmp);
+    A.red_ws = ws; A.RL = L.R; A.local = d_local; A.add_res = ws + L.add_res;
+    trace_reset(); trace_mark(st);
+    if (launch_init(ws + L.R.ctrl, L.R.zero_end - L.R.ctrl, ws + L.add_res, nfr, NZ_OK, st) != hipSuccess) return NZ_ERR_HIP;
+    trace_mark(st);
+    if (launch_decode(D, 5, st) != hipSuccess) return NZ_ERR_HIP;        // decode incoming + quantize local + add (no statistics)
+    trace_mark(st);
+    if (launch_fix(D, st) != hipSuccess) return NZ_ERR_HIP;              // frames without integer sums: fp32 sums
+    trace_mark(st);
+    if (launch_rea(A, st, trace_mark) != hipSuccess) return NZ_ERR_HIP;  // plan + encode, then accept / pack / header
+    return NZ_OK;
+}
+
 nz_status nz_reduce_local_sr(const void* d_in, size_t in_bytes, const float* d_local, void* d_out, size_t out_cap,
                              size_t n, float step, uint32_t seed, nz_result* d_res, const nz_opts* opts, void* d_ws,
                              size_t ws_bytes, void* stream) {

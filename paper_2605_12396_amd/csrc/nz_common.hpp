@@ -47,7 +47,7 @@ struct FrameMeta {
     uint32_t segt_off;    // byte offset of the segment table inside the frame
     uint32_t bits_off;    // byte offset of the bitstream inside the frame
     uint32_t bits_words;  // bitstream length in 32-bit words
-    uint32_t pad_;
+    uint32_t pad_;        // sampled ring step: 1 = the frame has no integer sums (its fp32 sums are staged); else 0
     uint64_t huff_bits;
     uint64_t pad2_;
 };
@@ -243,15 +243,18 @@ struct ReaArgs {
     float eb, step, inv_step; uint32_t step_bits;
     const DevContext* ctx;
     uint8_t* out; uint64_t slot;               // bytes between frame starts
-    uint8_t* ws; ReaLayout L;
+    uint8_t* ws; ReaLayout L;                  // the sampled path's part of the workspace (ws + L.*)
     uint32_t* tmp_base;                        // scratch regions of kReaTmpWords words per (frame, group)
     void* res;                                 // nz_rea_result* (device)
+    // ring step only (in == nullptr): the adding pass's workspace with the staged sums, the rank's own data, and
+    // the adding pass's own result record (its status is carried over)
+    uint8_t* red_ws; WsLayout RL; const float* local; const void* add_res;
 };
 
 // Launchers (one per translation unit).
 hipError_t launch_context(const float* sample, uint64_t n, float eb, float step, float inv_step, uint32_t K, uint32_t* ghist,
                           DevContext* ctx, hipStream_t st);
-hipError_t launch_rea(const ReaArgs& A, hipStream_t st, void (*mark)(hipStream_t));
+hipError_t launch_rea(const ReaArgs& A, hipStream_t st, void (*mark)(hipStream_t));   // A.in: compress; else the ring step's encode + finish
 hipError_t launch_rea_status(void* res, uint32_t n_frames, uint32_t status, hipStream_t st);
 struct CompressArgs {
     const float* in;          // fp32 input (compress) or nullptr (reduce: the sums staged in the workspace are encoded)

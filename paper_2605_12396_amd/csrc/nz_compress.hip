@@ -491,6 +491,11 @@ struct EncShared {
 // known to pass and q is simply rne(x * inv_step).  Source 2 (sampled arbitration): nothing has looked at the values
 // before, so the quantizer runs with its tests; a value that fails them counts as code 0 and clears *ok.
 // QM = 1 (source 0 only): the stochastic quantizer, with the draw of the element (its tests are known to pass too).
+// Sources 1 and 3 take their symbols from the sums a reduce staged; sources 2 and 3 are the sampled arbitration (the
+// context's code, every group materialised from bit 0, realized sizes reported to the finishing kernel).
+constexpr bool src_codes(int SRC) { return SRC == 1 || SRC == 3; }
+constexpr bool src_rea(int SRC) { return SRC == 2 || SRC == 3; }
+
 template <int SRC, int QM = 0>
 __device__ inline int32_t enc_q(uint32_t w, const CompressArgs& A, bool* ok = nullptr, uint32_t draw24 = 0) {
     if (SRC == 0 && QM == 1) {
@@ -535,7 +540,7 @@ struct EncGroup {
 // Source word i of the group: fp32 bits (SRC 0) or the summed code (SRC 1, coded frames).
 template <int SRC>
 __device__ inline uint32_t enc_word(const EncGroup& G, uint32_t i) {
-    if (SRC != 1) return G.src[i];
+    if (!src_codes(SRC)) return G.src[i];
     const int32_t q = G.src16[i];
     return (q == -32768) ? G.src[i] : (uint32_t)q;
 }
@@ -554,10 +559,10 @@ __device__ inline void enc_load(const EncGroup& G, uint32_t sb, uint32_t (&raw)[
     const uint32_t tid = threadIdx.x;
     const uint32_t* src = G.src + sb * kEncBlock;
     const uint32_t cnt = (sb < G.nsub) ? ((G.gcnt - sb * kEncBlock < kEncBlock) ? (G.gcnt - sb * kEncBlock) : kEncBlock) : 0u;
-    if (G.vec_ok && cnt == kEncBlock && (SRC != 1 || !G.wide16)) {       // uniform: the common, branch-free case
+    if (G.vec_ok && cnt == kEncBlock && (!src_codes(SRC) || !G.wide16)) {       // uniform: the common, branch-free case
 #pragma unroll
         for (uint32_t it = 0; it < kEncIters; it++) {
-            if (SRC != 1) {
+            if (!src_codes(SRC)) {
                 const uint4 t = *reinterpret_cast<const uint4*>(src + it * 1024 + tid * 4);
                 raw[it][0] = t.x; raw[it][1] = t.y; raw[it][2] = t.z; raw[it][3] = t.w;
             } else {
@@ -608,8 +613,8 @@ __device__ inline void enc_raw_fixed(const CompressArgs& A, const EncGroup& G, c
         const uint32_t i = p0 + tid * 4;
         x[0] = x[1] = x[2] = x[3] = 0;
         if (i >= G.gcnt) return;
-        if (G.vec_ok && i + 4 <= G.gcnt && (SRC != 1 || !G.wide16)) {
-            if (SRC != 1) {
+        if (G.vec_ok && i + 4 <= G.gcnt && (!src_codes(SRC) || !G.wide16)) {
+            if (!src_codes(SRC)) {
                 const uint4 t = *reinterpret_cast<const uint4*>(G.src + i);
                 x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
             } else {
@@ -641,7 +646,7 @@ __device__ inline void enc_raw_fixed(const CompressArgs& A, const EncGroup& G, c
             for (uint32_t j = 0; j < 4; j++) {
                 bool ok = true;
                 q[j] = enc_q<SRC, QM>(cur[j], A, &ok, QM ? keys.draw(p0 + tid * 4 + j) : 0u);     // (words past the end are 0)
-                if (SRC == 2 && tid * 4 + j < pass_syms && !ok) bad = 1;
+                if (src_rea(SRC) && tid * 4 + j < pass_syms && !ok) bad = 1;
             }
             if (DELTA) delta4(q);                     // (a pass is four whole segments, one per wave)
             uint32_t pos = (u * 1024u + tid * 4u) * w;
@@ -649,12 +654,12 @@ __device__ inline void enc_raw_fixed(const CompressArgs& A, const EncGroup& G, c
             for (uint32_t j = 0; j < 4; j++) {
                 uint32_t z = zigzag(q[j]);
                 if (tid * 4 + j < pass_syms && w) {
-                    if (SRC == 2 && w < 32u && (z >> w)) { bad = 1; z &= (1u << w) - 1u; }   // wider than the sampled width
+                    if (src_rea(SRC) && w < 32u && (z >> w)) { bad = 1; z &= (1u << w) - 1u; }   // wider than the sampled width
                     const uint32_t sh = pos & 31u, wi = pos >> 5;
                     atomicOr(&buf[wi], z << sh);
                     if (sh + w > 32u) atomicOr(&buf[wi + 1], z >> (32u - sh));
                     pos += w;
-                } else if (SRC == 2 && tid * 4 + j < pass_syms && z) bad = 1;               // (sampled width 0, value not 0)
+                } else if (src_rea(SRC) && tid * 4 + j < pass_syms && z) bad = 1;               // (sampled width 0, value not 0)
             }
         }
         __syncthreads();
@@ -679,6 +684,10 @@ __device__ inline void enc_raw_fixed(const CompressArgs& A, const EncGroup& G, c
 // size as the cost, ties to the lower codec id.  Leaves the context's code in S.book when the context is valid.  The
 // frame's first group also writes the plan, the frame's entry of the offsets table (slots are fixed) and, for frame 0,
 // the stream header and the cleared result record, for the finishing kernel.
+// Source 3 (the ring step): the frame exists as integer sums staged by the adding pass, the sample is their prefix and
+// every code is codable; a frame that has no integer sums (an operand RAW, a sum out of range: flags of the adding
+// pass) is RAW without arbitration and holds the fp32 sums staged for it.
+template <int SRC>
 __device__ inline FrameMeta rea_plan_frame(const CompressArgs& A, uint32_t frame, uint64_t f0, uint32_t nf, uint32_t gb, EncShared& S) {
     const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6, K = A.K;
     const bool ctx_ok = A.rea_ctx && A.rea_ctx->valid == 1u && A.rea_ctx->K == K;
@@ -716,9 +725,50 @@ __device__ inline FrameMeta rea_plan_frame(const CompressArgs& A, uint32_t frame
         zmax = z > zmax ? z : zmax;
         if (ctx_ok) { const uint32_t b = bin_of(z, K); bits += (uint32_t)(S.book[b] >> 32) + (b == K - 1u ? 32u : 0u); }
     };
+    if (SRC == 3) {
+        const int16_t* c16 = reinterpret_cast<const int16_t*>(A.ws + A.L.c16) + f0;
+        const uint32_t* c32 = reinterpret_cast<const uint32_t*>(A.ws + A.L.codes) + f0;
+        const uint32_t hpf = A.sbpf, halves = (nf + kEncGroup - 1) / kEncGroup;
+        if (tid < halves && tid < hpf) {          // no integer sums in this frame?
+            const uint32_t y = reinterpret_cast<const uint2*>(A.ws + A.L.pmeta)[(size_t)frame * hpf + tid].y;
+            const uint32_t cw = reinterpret_cast<const uint32_t*>(A.ws + A.L.cwide)[(size_t)frame * hpf + tid];
+            if ((y & 3u) || (cw & 2u)) bad = 1;
+        }
+        auto profile_code = [&](int32_t h, uint32_t k) {
+            const uint32_t z = zigzag(h == -32768 ? (int32_t)c32[k] : h);
+            zmax = z > zmax ? z : zmax;
+            if (ctx_ok) { const uint32_t b = bin_of(z, K); bits += (uint32_t)(S.book[b] >> 32) + (b == K - 1u ? 32u : 0u); }
+        };
+        uint32_t k0 = 0;
+        if ((f0 & 7u) == 0) {                    // eight 16-bit codes per 16-byte load, up to eight loads in flight per thread
+            constexpr uint32_t kBatch = 8 * kEncThreads * 8;
+            for (; k0 < (n_s & ~7u); k0 += kBatch) {
+                uint4 t[8];
+#pragma unroll
+                for (uint32_t u = 0; u < 8; u++) {
+                    const uint32_t k = k0 + (u * kEncThreads + tid) * 8u;
+                    t[u] = (k + 8u <= n_s) ? *reinterpret_cast<const uint4*>(c16 + k) : make_uint4(0u, 0u, 0u, 0u);
+                }
+#pragma unroll
+                for (uint32_t u = 0; u < 8; u++) {
+                    const uint32_t k = k0 + (u * kEncThreads + tid) * 8u;
+                    if (k + 8u <= n_s) {
+                        const uint32_t wds[4] = { t[u].x, t[u].y, t[u].z, t[u].w };
+#pragma unroll
+                        for (uint32_t j = 0; j < 4; j++) {
+                            profile_code((int32_t)(int16_t)(wds[j] & 0xFFFFu), k + 2u * j);
+                            profile_code((int32_t)wds[j] >> 16, k + 2u * j + 1u);
+                        }
+                    }
+                }
+            }
+            k0 = n_s & ~7u;
+        }
+        for (uint32_t k = k0 + tid; k < n_s; k += kEncThreads) profile_code(c16[k], k);
+    }
     const float* sp = A.in + f0;
-    uint32_t i = 0;
-    if ((f0 & 3u) == 0) {                        // eight 16-byte loads in flight per thread
+    uint32_t i = (SRC == 3) ? n_s : 0u;
+    if (SRC != 3 && (f0 & 3u) == 0) {            // eight 16-byte loads in flight per thread
         constexpr uint32_t kBatch = 8 * kEncThreads * 4;
         for (; i + kBatch <= n_s; i += kBatch) {
             float4 t[8];
@@ -737,7 +787,7 @@ __device__ inline FrameMeta rea_plan_frame(const CompressArgs& A, uint32_t frame
     const uint32_t zm = s_red[0];
     const uint32_t w = zm ? (32u - (uint32_t)__clz(zm)) : 0u;
     const uint32_t nseg = (nf + kSeg - 1) / kSeg;
-    if (n_s && !s_red[1]) {
+    if (n_s && !s_red[1]) {                      // (source 3: the flag also stands for "no integer sums")
         const uint64_t* wb = reinterpret_cast<const uint64_t*>(s_red + 2);
         const uint64_t sample_bits = wb[0] + wb[1] + wb[2] + wb[3];
         const uint64_t pred_bits = (sample_bits * nf + n_s - 1) / n_s;
@@ -769,7 +819,7 @@ __device__ inline FrameMeta rea_plan_frame(const CompressArgs& A, uint32_t frame
     M.offset = base + (uint64_t)frame * A.rea_slot; M.total = 0; M.payload = 0; M.codec = plan; M.w = w; M.nsym = K; M.fits = 1u;
     M.segt_off = kHdrBytes + (uint32_t)pad4u(K);
     M.bits_off = (plan == CODEC_HUFF) ? (M.segt_off + (uint32_t)pad4u(2ull * nseg)) : kHdrBytes;
-    M.bits_words = 0; M.pad_ = 0; M.huff_bits = 0; M.pad2_ = 0;
+    M.bits_words = 0; M.pad_ = (SRC == 3 && s_red[1]) ? 1u : 0u; M.huff_bits = 0; M.pad2_ = 0;
     if (gb == 0 && tid == 0) reinterpret_cast<FrameMeta*>(A.ws + A.L.meta)[frame] = M;
     __syncthreads();                             // the scratch is the encoder's again
     return M;
@@ -791,26 +841,28 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
     G.last_grp = (G.g0 + G.gcnt == G.nf);
     G.nsub = (G.gcnt + kEncBlock - 1) / kEncBlock;
     // source words: fp32 input (SRC 0, 2) or the staged codes / fp32 sums of the reduce (SRC 1)
-    G.src = (SRC != 1 ? reinterpret_cast<const uint32_t*>(A.in) : reinterpret_cast<const uint32_t*>(A.ws + A.L.codes)) + f0 + G.g0;
+    G.src = (!src_codes(SRC) ? reinterpret_cast<const uint32_t*>(A.in) : reinterpret_cast<const uint32_t*>(A.ws + A.L.codes)) + f0 + G.g0;
     G.vec_ok = (((f0 + G.g0) & 3u) == 0);                                // kEncBlock is a multiple of 4
     G.src16 = reinterpret_cast<const int16_t*>(A.ws + A.L.c16) + f0 + G.g0;
     G.wide16 = false;
-    if (SRC == 1) G.wide16 = reinterpret_cast<const uint32_t*>(A.ws + A.L.cwide)[(size_t)frame * A.sbpf + G.g0 / A.stat_block] != 0;
+    if (src_codes(SRC)) G.wide16 = (reinterpret_cast<const uint32_t*>(A.ws + A.L.cwide)[(size_t)frame * A.sbpf + G.g0 / A.stat_block] & 1u) != 0;
     const uint32_t K = A.K, kesc = K - 1u;
 
     FrameMeta M;
-    if (SRC == 2) M = rea_plan_frame(A, frame, f0, G.nf, G.gb, S);
+    if (src_rea(SRC)) M = rea_plan_frame<SRC>(A, frame, f0, G.nf, G.gb, S);
     else M = reinterpret_cast<const FrameMeta*>(A.ws + A.L.meta)[frame];
     if (!M.fits) return;
     uint8_t* fr = A.out + M.offset;
     uint32_t bad = 0;                             // SRC 2: a value that cannot be coded as planned fails the frame
     SrKeys keys;                                  // QM 1: draws of the group's elements, by position in the group
     if (QM == 1) keys.init(A.seed, f0 + G.g0); else { keys.base_lo = 0; keys.key0 = 0; keys.key1 = 0; }
-    if (M.codec != CODEC_HUFF) enc_raw_fixed<SRC, QM, DELTA>(A, G, M, fr, S.stage[0], bad, keys);
+    if (SRC == 3 && M.codec == CODEC_RAW && !M.pad_) {
+        // (a frame of integer sums that goes RAW holds the sums of the dequantized operands: the finishing kernel's)
+    } else if (M.codec != CODEC_HUFF) enc_raw_fixed<SRC, QM, DELTA>(A, G, M, fr, S.stage[0], bad, keys);
     else {
         uint32_t raw[kEncIters][4];
         enc_load<SRC>(G, 0, raw);
-        if (SRC == 2) {
+        if (src_rea(SRC)) {
             // (the plan left the context's code in S.book)
         } else {
             for (uint32_t s = tid; s < K; s += kEncThreads) {
@@ -827,13 +879,13 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
         // packs them behind each other.  In place nothing is written past the payload capacity (the RAW size of the
         // frame: Algorithm 1's EncodePlan works inside payloadCap); what is dropped belongs to a frame whose realized
         // payload exceeds that size and is rejected for it.
-        const uint32_t start_bit = (SRC == 2) ? 0u
+        const uint32_t start_bit = src_rea(SRC) ? 0u
             : reinterpret_cast<const uint32_t*>(A.ws + A.L.grp_start)[(size_t)frame * A.sbpf + G.g0 / A.stat_block];
         uint32_t* bits = reinterpret_cast<uint32_t*>(fr + M.bits_off) + (start_bit >> 5);   // first word this group touches
-        if (SRC == 2 && G.gb > 0) bits = A.rea_tmp + ((size_t)frame * gpf + G.gb) * kReaTmpWords;
+        if (src_rea(SRC) && G.gb > 0) bits = A.rea_tmp + ((size_t)frame * gpf + G.gb) * kReaTmpWords;
         const uint32_t cap_end = kHdrBytes + 4u * G.nf;                   // SRC 2: first byte of the frame that is off limits
-        const uint32_t cap_segs = (SRC == 2) ? (M.segt_off < cap_end ? (cap_end - M.segt_off) / 2u : 0u) : 0xFFFFFFFFu;
-        const uint32_t cap_words = (SRC == 2 && G.gb == 0) ? (M.bits_off < cap_end ? (cap_end - M.bits_off) / 4u : 0u) : 0xFFFFFFFFu;
+        const uint32_t cap_segs = src_rea(SRC) ? (M.segt_off < cap_end ? (cap_end - M.segt_off) / 2u : 0u) : 0xFFFFFFFFu;
+        const uint32_t cap_words = (src_rea(SRC) && G.gb == 0) ? (M.bits_off < cap_end ? (cap_end - M.bits_off) / 4u : 0u) : 0xFFFFFFFFu;
         uint16_t* segt = reinterpret_cast<uint16_t*>(fr + M.segt_off);
         const uint32_t nseg = (G.nf + kSeg - 1) / kSeg;
         uint32_t rel = start_bit & 31u;           // bits already in the current stage (carried over)
@@ -849,7 +901,7 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
             for (uint32_t k = tid; k < nw; k += kEncThreads) {
                 const uint32_t wv = X[k];
                 X[k] = 0;
-                if (SRC != 2 && G.gb > 0 && flushed == 0 && k == 0) atomicOr(dst, wv);   // word shared with the previous group
+                if (!src_rea(SRC) && G.gb > 0 && flushed == 0 && k == 0) atomicOr(dst, wv);   // word shared with the previous group
                 else if (flushed + k < cap_words) dst[k] = wv;
             }
             if (tid == 0) { carry = X[nw]; X[nw] = 0; Y[0] = carry; }
@@ -894,7 +946,7 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
                         const bool valid = WHOLE || i + j < cnt;
                         bool ok = true;
                         q4[j] = enc_q<SRC, QM>(raw[it][j], A, &ok, QM ? keys.draw(sb * kEncBlock + i + j) : 0u);   // (words past the end are 0)
-                        if (SRC == 2 && valid && !ok) bad = 1;
+                        if (src_rea(SRC) && valid && !ok) bad = 1;
                     }
                     if (DELTA) delta4(q4);            // (a pass is four whole segments, one per wave)
 #pragma unroll
@@ -977,13 +1029,13 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
         // the last, partial word: shared with the next group, or the frame's last bitstream word
         if (tid == 0 && rel) {
             uint32_t* dst = bits + flushed;
-            if (SRC == 2) { if (flushed < cap_words) *dst = carry; }
+            if (src_rea(SRC)) { if (flushed < cap_words) *dst = carry; }
             else if (!G.last_grp || (G.gb > 0 && flushed == 0)) atomicOr(dst, carry);
             else *dst = carry;
         }
-        if (SRC == 2 && tid == 0) A.rea_gbits[(size_t)frame * gpf + G.gb] = flushed * 32u + rel;     // realized bits of the group
+        if (src_rea(SRC) && tid == 0) A.rea_gbits[(size_t)frame * gpf + G.gb] = flushed * 32u + rel;     // realized bits of the group
     }
-    if (SRC == 2) {              // (header, padding and the packing of the groups are the finishing kernel's)
+    if (src_rea(SRC)) {          // (header, padding and the packing of the groups are the finishing kernel's)
         if (bad) atomicOr(A.rea_fail + (size_t)frame * gpf + G.gb, 1u);
         return;
     }
@@ -1078,7 +1130,8 @@ __global__ __launch_bounds__(256) void k_rea_finish(ReaArgs A) {
     const uint32_t g0 = wg * kEncGroup;
     if (g0 >= nf) return;
     const uint32_t ngrp = (nf + kEncGroup - 1) / kEncGroup;
-    const FrameMeta M = reinterpret_cast<const FrameMeta*>(A.ws + A.L.meta)[frame];
+    const FrameMeta M = A.in ? reinterpret_cast<const FrameMeta*>(A.ws + A.L.meta)[frame]
+                             : reinterpret_cast<const FrameMeta*>(A.red_ws + A.RL.meta)[frame];
     uint8_t* fr = A.out + M.offset;
     const uint32_t K = A.K, plan = M.codec;
     const uint32_t nseg = (nf + kSeg - 1) / kSeg;
@@ -1099,11 +1152,32 @@ __global__ __launch_bounds__(256) void k_rea_finish(ReaArgs A) {
     const bool fell_back = (codec == CODEC_RAW && plan != CODEC_RAW);
     if (codec == CODEC_RAW) payload = rawb;
     const uint32_t total = (uint32_t)pad16u(kHdrBytes + payload);
-    if (fell_back) {
+    if (A.in) {
+        if (fell_back) {
+            const uint32_t gcnt = (nf - g0 < kEncGroup) ? (nf - g0) : kEncGroup;
+            const uint32_t* src = reinterpret_cast<const uint32_t*>(A.in) + f0 + g0;
+            uint32_t* dst = reinterpret_cast<uint32_t*>(fr + kHdrBytes) + g0;
+            for (uint32_t i = tid; i < gcnt; i += 256) dst[i] = src[i];
+        }
+    } else if (codec == CODEC_RAW && !M.pad_) {
+        // Ring step, a frame of integer sums that ends up RAW (planned so, or its realized output was rejected): it
+        // holds fl(fl(qa*step) + fl(qb*step)), the sums of the dequantized operands.  qb is the rank's own value
+        // quantized again (it was quantizable, or the frame would have no integer sums), qa = Q - qb.
+#pragma clang fp contract(off)
         const uint32_t gcnt = (nf - g0 < kEncGroup) ? (nf - g0) : kEncGroup;
-        const uint32_t* src = reinterpret_cast<const uint32_t*>(A.in) + f0 + g0;
-        uint32_t* dst = reinterpret_cast<uint32_t*>(fr + kHdrBytes) + g0;
-        for (uint32_t i = tid; i < gcnt; i += 256) dst[i] = src[i];
+        const int16_t* c16 = reinterpret_cast<const int16_t*>(A.red_ws + A.RL.c16) + f0 + g0;
+        const uint32_t* c32 = reinterpret_cast<const uint32_t*>(A.red_ws + A.RL.codes) + f0 + g0;
+        const float* loc = A.local + f0 + g0;
+        float* dst = reinterpret_cast<float*>(fr + kHdrBytes) + g0;
+        for (uint32_t i = tid; i < gcnt; i += 256) {
+            const int32_t h = c16[i];
+            const int32_t Q = (h == -32768) ? (int32_t)c32[i] : h;
+            int32_t qb;
+            quantize1(loc[i], A.eb, A.step, A.inv_step, qb);
+            const float va = (float)(Q - qb) * A.step, vb = (float)qb * A.step;
+            const float sum = va + vb;
+            reinterpret_cast<uint32_t*>(dst)[i] = (sum != sum) ? 0x7FC00000u : __float_as_uint(sum);   // (one canonical NaN)
+        }
     }
     if (codec == CODEC_HUFF && wg > 0) {
         // Pack this group behind the one before it.  It writes every word its bits reach, the first one together
@@ -1184,6 +1258,12 @@ __global__ __launch_bounds__(256) void k_rea_finish(ReaArgs A) {
         dst[0] = make_uint4(h[0], h[1], h[2], h[3]);
         dst[1] = make_uint4(h[4], h[5], h[6], h[7]);
         ReaResultRec* res = reinterpret_cast<ReaResultRec*>(A.res);
+        // ring step: a stream-level or frame-level error found by the adding pass voids the output (nothing published)
+        const uint32_t add_status = A.in ? (uint32_t)ST_OK : reinterpret_cast<const ResultRec*>(A.add_res)->status;
+        if (add_status != ST_OK) {
+            if (frame == A.n_frames - 1) res->status = add_status;
+            return;
+        }
         atomicAdd(codec == CODEC_RAW ? &res->n_raw : (codec == CODEC_FIXED ? &res->n_fixed : &res->n_huff), 1u);
         if (fell_back) atomicAdd(&res->n_fallback, 1u);
         uint64_t wire = total;
@@ -1215,13 +1295,16 @@ hipError_t launch_rea(const ReaArgs& A, hipStream_t st, void (*mark)(hipStream_t
     C.in = A.in; C.n = A.n; C.chunk = A.chunk; C.n_frames = A.n_frames; C.K = A.K; C.sbpf = A.gpf; C.stat_block = kEncGroup;
     C.force_codec = A.force_codec; C.min_gain_permil = A.min_gain_permil; C.huff_min_bytes = A.huff_min_bytes;
     C.eb = A.eb; C.step = A.step; C.inv_step = A.inv_step; C.step_bits = A.step_bits;
-    C.out = A.out; C.out_cap = 0; C.ws = A.ws; C.L = WsLayout(); C.L.meta = A.L.meta; C.res = A.res;
+    C.out = A.out; C.out_cap = 0; C.res = A.res;
+    if (A.in) { C.ws = A.ws; C.L = WsLayout(); C.L.meta = A.L.meta; }
+    else { C.ws = A.red_ws; C.L = A.RL; }        // ring step: the adding pass's workspace (staged sums, flags, frame plans)
     C.rea_ctx = A.ctx; C.rea_tmp = A.tmp_base; C.rea_gbits = reinterpret_cast<uint32_t*>(A.ws + A.L.gbits);
     C.rea_fail = reinterpret_cast<uint32_t*>(A.ws + A.L.fail);
     C.rea_sample_elems = A.sample_elems; C.rea_small_batch_bytes = A.small_batch_bytes; C.rea_slot = A.slot;
     C.rea_link_ps = A.link_ps; C.rea_fixed_alpha_ns = A.fixed_alpha_ns; C.rea_fixed_ps = A.fixed_ps;
     C.rea_huff_alpha_ns = A.huff_alpha_ns; C.rea_huff_ps = A.huff_ps;
-    hipLaunchKernelGGL((k_encode<2, 0, 0>), dim3(A.n_frames * A.gpf), dim3(kEncThreads), 0, st, C);
+    if (A.in) hipLaunchKernelGGL((k_encode<2, 0, 0>), dim3(A.n_frames * A.gpf), dim3(kEncThreads), 0, st, C);
+    else hipLaunchKernelGGL((k_encode<3, 0, 0>), dim3(A.n_frames * A.gpf), dim3(kEncThreads), 0, st, C);
     mark(st);
     hipLaunchKernelGGL(k_rea_finish, dim3(A.n_frames * A.gpf), dim3(256), 0, st, A);
     mark(st);

@@ -449,10 +449,13 @@ constexpr uint32_t kTile16Stride = kTile16R + 2;     // halfwords per row: 17 wo
 constexpr int32_t kWideMarker = -32768;              // "this code does not fit 16 bits"
 constexpr uint32_t kHalf = 65536;                    // statistics granularity of the reduce (one encoder group)
 
-enum : int { MODE_DECOMPRESS = 0, MODE_STAGE_A = 1, MODE_ADD_B = 2, MODE_ADD_LOCAL = 3, MODE_ADD_LOCAL_SR = 4 };
+enum : int { MODE_DECOMPRESS = 0, MODE_STAGE_A = 1, MODE_ADD_B = 2, MODE_ADD_LOCAL = 3, MODE_ADD_LOCAL_SR = 4,
+             MODE_ADD_LOCAL_PLAIN = 5 };
 // the adding passes: ADD_B adds the staged codes of operand A, ADD_LOCAL the rank's own fp32 data, quantized on the fly
-// (ADD_LOCAL_SR: by the stochastic quantizer)
-#define NZ_LOCAL(M) ((M) == MODE_ADD_LOCAL || (M) == MODE_ADD_LOCAL_SR)
+// (ADD_LOCAL_SR: by the stochastic quantizer; ADD_LOCAL_PLAIN: without the statistics of the sums, for the sampled
+// arbitration, which profiles a prefix of the staged sums instead)
+#define NZ_LOCAL(M) ((M) == MODE_ADD_LOCAL || (M) == MODE_ADD_LOCAL_SR || (M) == MODE_ADD_LOCAL_PLAIN)
+#define NZ_STATS(M) ((M) == MODE_ADD_B || (M) == MODE_ADD_LOCAL || (M) == MODE_ADD_LOCAL_SR)
 #define NZ_ADDS(M) ((M) == MODE_ADD_B || NZ_LOCAL(M))
 
 // Shared memory of one decode workgroup.  The window comes first and the tile follows it directly: a reader's
@@ -528,6 +531,7 @@ struct AddCtx {
     StageA sa; uint32_t* codes; int16_t* c16; uint32_t* s_h; uint32_t* s_cwide; uint32_t* s_lunq;
     const float* local; float eb, inv;
     bool sr; SrKeys keys;      // stochastic local quantizer: draws by element offset from the workgroup's block
+    bool stats;                // the pass gathers the statistics of the sums
     uint32_t ncs, copy, K; float step; bool a_raw, b_raw;
     __device__ inline void finish(const SegCtx& C, uint32_t i, uint32_t tb, uint32_t (&zmax)[2], uint32_t& overflow) const {
         const uint64_t g = C.f0 + i;
@@ -544,6 +548,7 @@ struct AddCtx {
         const int32_t Q = (int32_t)t;
         if (Q > 32767 || Q <= kWideMarker) { c16[g] = (int16_t)kWideMarker; codes[g] = t; s_cwide[h] = 1u; }
         else c16[g] = (int16_t)Q;
+        if (!stats) return;
         const uint32_t z = zigzag(Q);
         zmax[h] = z > zmax[h] ? z : zmax[h];
         atomicAdd(&s_h[h * 1024u + (bin_of(z, K) << ncs) + copy], 1u);
@@ -704,7 +709,9 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
                 Q[2] = (int32_t)(int16_t)(p1 & 0xFFFFu) + (int32_t)(int16_t)(pa[k].y & 0xFFFFu);
                 Q[3] = ((int32_t)p1 >> 16) + ((int32_t)pa[k].y >> 16);
                 }
-                if (hot_esc) {
+                if (!NZ_STATS(MODE)) {
+                    // (no statistics in this pass)
+                } else if (hot_esc) {
                     // Where escapes are frequent (sums of many peers: most codes leave the alphabet) they all hit one
                     // bin, whose few copies serialise the wave.  They are counted per wavefront and added once; the
                     // whole wave is here and h is the same for all of it.  (Uniform branch: the incoming frame's kind.)
@@ -869,7 +876,7 @@ template <int MODE, int NT, int DELTA>
 __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_decode(DecodeArgs A) {
     __shared__ DecTables s_t;
     __shared__ DecShared<NT> S;
-    __shared__ uint32_t s_h[NZ_ADDS(MODE) ? 2048 : 1];
+    __shared__ uint32_t s_h[NZ_STATS(MODE) ? 2048 : 1];
 
     const uint32_t tid = threadIdx.x, lane = lane_id(), wave = tid >> 6;
     const uint32_t frame = blockIdx.x / A.dbpf, db = blockIdx.x % A.dbpf;
@@ -942,7 +949,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
     X.codes = reinterpret_cast<uint32_t*>(A.ws + A.L.codes); X.c16 = reinterpret_cast<int16_t*>(A.ws + A.L.c16);
     X.s_cwide = S.cwide; X.s_lunq = S.lunq;
     X.local = NZ_LOCAL(MODE) ? A.local : nullptr; X.eb = A.eb; X.inv = A.inv_step;
-    X.sr = (MODE == MODE_ADD_LOCAL_SR);
+    X.sr = (MODE == MODE_ADD_LOCAL_SR); X.stats = NZ_STATS(MODE);
     if (MODE == MODE_ADD_LOCAL_SR) X.keys.init(A.seed, f0 + blk0); else { X.keys.base_lo = 0; X.keys.key0 = 0; X.keys.key1 = 0; }
     X.s_h = s_h; X.K = A.K; X.step = A.step; X.ncs = 0; X.copy = 0; X.a_raw = false; X.b_raw = false;
     uint32_t* akind = reinterpret_cast<uint32_t*>(A.ws + A.L.akind);   // per frame: operand A is RAW
@@ -951,7 +958,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
     if (NZ_ADDS(MODE)) {
         while ((A.K << (X.ncs + 1)) <= 1024u && X.ncs < 5) X.ncs++;
         X.copy = lane & ((1u << X.ncs) - 1u);
-        for (uint32_t i = tid; i < 2048u; i += NT) s_h[i] = 0;
+        if (NZ_STATS(MODE)) for (uint32_t i = tid; i < 2048u; i += NT) s_h[i] = 0;
         X.b_raw = V.kind == KIND_RAW;
         if (MODE == MODE_ADD_B) {
             X.a_raw = akind[frame] != 0;
@@ -1004,7 +1011,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
         if (blk0 + h * kHalf >= nf) break;
         const size_t hb = (size_t)frame * hpf + blk0 / kHalf + h;
         uint32_t* ph = reinterpret_cast<uint32_t*>(A.ws + A.L.phist) + hb * kMaxK;
-        for (uint32_t sy = tid; sy < A.K; sy += NT) {
+        if (NZ_STATS(MODE)) for (uint32_t sy = tid; sy < A.K; sy += NT) {
             uint32_t t = 0;
             for (uint32_t cc = 0; cc < (1u << X.ncs); cc++) t += s_h[h * 1024u + (sy << X.ncs) + cc];
             ph[bin_symbol(sy, A.K)] = t;
@@ -1159,9 +1166,10 @@ static void launch_decode_t(DecodeArgs& D, const DecodeArgs& A, int pass, hipStr
     } else if (pass == 3) {
         D.dbpf = (A.chunk + kAddThreads * kSeg - 1) / (kAddThreads * kSeg);
         hipLaunchKernelGGL((k_decode<MODE_ADD_LOCAL, kAddThreads, DELTA>), dim3(D.n_frames * D.dbpf), dim3(kAddThreads), 0, st, D);
-    } else if constexpr (DELTA == 0) {          // (the stochastic ring step is not built with the predictor)
+    } else if constexpr (DELTA == 0) {          // (the stochastic and the sampled ring step are not built with the predictor)
         D.dbpf = (A.chunk + kAddThreads * kSeg - 1) / (kAddThreads * kSeg);
-        hipLaunchKernelGGL((k_decode<MODE_ADD_LOCAL_SR, kAddThreads, 0>), dim3(D.n_frames * D.dbpf), dim3(kAddThreads), 0, st, D);
+        if (pass == 4) hipLaunchKernelGGL((k_decode<MODE_ADD_LOCAL_SR, kAddThreads, 0>), dim3(D.n_frames * D.dbpf), dim3(kAddThreads), 0, st, D);
+        else hipLaunchKernelGGL((k_decode<MODE_ADD_LOCAL_PLAIN, kAddThreads, 0>), dim3(D.n_frames * D.dbpf), dim3(kAddThreads), 0, st, D);
     }
 }
 

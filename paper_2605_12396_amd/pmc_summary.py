@@ -21,9 +21,10 @@ KERNELS = [("k_stats<0, 0, 0>", ["compress/stats"]), ("k_codebook", ["compress/c
            ("k_encode<0, 0, 0>", ["compress/encode"]), ("k_encode<1, 0, 0>", ["reduce/encode", "reduce_local/encode"]),
            ("k_decode<0, 256, 0>", ["decompress/decode"]), ("k_decode_finish", ["decompress/finish"]),
            ("k_decode<1, 256, 0>", ["reduce/stage_a"]), ("k_decode<2, 512, 0>", ["reduce/add_b"]),
-           ("k_decode<3, 512, 0>", ["reduce_local/add_local"]), ("k_fix", ["reduce/fix", "reduce_local/fix"]),
+           ("k_decode<3, 512, 0>", ["reduce_local/add_local"]), ("k_fix", ["reduce/fix", "reduce_local/fix", "reduce_local_rea/fix"]),
            ("k_encode<2, 0, 0>", ["compress_rea/encode"]),
-           ("k_rea_finish", ["compress_rea/finish"])]
+           ("k_rea_finish", ["compress_rea/finish", "reduce_local_rea/finish"]),
+           ("k_decode<5, 512, 0>", ["reduce_local_rea/add_local"]), ("k_encode<3, 0, 0>", ["reduce_local_rea/encode"])]
 
 
 def per_kernel(d, counter):

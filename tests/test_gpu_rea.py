@@ -277,3 +277,110 @@ def test_reserved_option_field_is_refused(nz):
     bad = nz.ReaOpts(0, 0, 0, 0, 0, 0, 0, 1)
     assert nz.nz_compress_rea(x, n, 1e-4, None, out, cap, res, g, bad, ws, wsb) == nz.ERR_INVALID
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------------------------------------
+# the ring step with the sampled arbitration on the way out
+# ------------------------------------------------------------------------------------------------
+
+def gpu_reduce_local_rea(nz, a_stream, x, eb, g, ropts, ctx, cap=None):
+    import torch
+    n = x.size
+    bound = nz.nz_compress_bound(n, nz.make_opts(chunk_elems=g.chunk_elems, alphabet=g.alphabet))
+    cap = bound if cap is None else cap
+    out = torch.full((max(bound, 16),), 0xAB, dtype=torch.uint8, device="cuda:0")
+    res = torch.zeros(nz.REA_RESULT_BYTES + 8, dtype=torch.uint8, device="cuda:0")
+    wsb = nz.nz_reduce_rea_workspace_bytes(n, g)
+    ws = torch.empty(wsb, dtype=torch.uint8, device="cuda:0")
+    da = _dev(np.concatenate([a_stream, np.zeros((-a_stream.size) % 16, np.uint8)]))
+    rc = nz.nz_reduce_local_rea(da, a_stream.size, _dev(x), n, eb, ctx, out, cap, res, g, ropts, ws, wsb)
+    return rc, nz.read_rea_result(res), out
+
+
+def check_ring_rea(nz, a, x, eb, ropts=None, with_ctx=True, a_kw=None, **kw):
+    g, o = nz.make_opts(**kw), oracle.make_opts(**kw)
+    ro_g = nz.ReaOpts(*ropts) if ropts else None
+    ro_o = oracle.ReaOpts(*ropts) if ropts else None
+    base_kw = dict(chunk_elems=kw.get("chunk_elems", 0), alphabet=kw.get("alphabet", 0))
+    sa, _, rc0 = oracle.compress(a, eb, oracle.make_opts(**(a_kw or base_kw)))
+    cal = x[:min(x.size, 65536)]
+    octx = oracle.context_build(cal, eb, o) if with_ctx else None
+    gctx = gpu_context(nz, cal, eb, g) if with_ctx else None
+    ref, ores, orc, plans = oracle.reduce_local_rea(sa, x, eb, o, ro_o, octx)
+    rc, r, out = gpu_reduce_local_rea(nz, sa, x, eb, g, ro_g, gctx)
+    assert rc0 == 0 and rc == 0 and orc == 0 and r == ores.as_dict(), (r, ores.as_dict())
+    got = out[:r["span_bytes"]].cpu().numpy()
+    base = 64 + (8 * ores.n_frames + 15) // 16 * 16
+    assert (got[:base] == ref[:base]).all()
+    for off, codec, payload, total in _frames(ref):
+        d = np.nonzero(got[off:off + total] != ref[off:off + total])[0]
+        assert d.size == 0, "frame at %d (codec %d): first differing byte %d" % (off, codec, int(d[0]))
+    return ref, ores, out, r, plans
+
+
+def _ring_cases():
+    n = 300000
+    a, x = W.gradient_like(n, seed=71), W.gradient_like(n, seed=72)
+    yield "gradient_256KBframes", a, x, 1e-4, None, dict(chunk_elems=65536)
+    yield "gradient_1MBframes", W.gradient_like(700000, seed=73), W.gradient_like(700000, seed=74), 1e-4, None, dict(chunk_elems=262144)
+    yield "K1024", a, x, 1e-5, None, dict(chunk_elems=100000, alphabet=1024)
+    yield "ragged_small_frames", a[:30011], x[:30011], 1e-4, None, dict(chunk_elems=10003)
+    yield "tiny", a[:37], x[:37], 1e-4, None, dict(chunk_elems=16)
+    yield "uniform_fixedlen", W.sweep_payload("uniform", 200000, 75), W.sweep_payload("uniform", 200000, 76), 1e-4, None, dict(chunk_elems=65536)
+    yield "pinned_huffman", a, x, 1e-4, None, dict(chunk_elems=65536, force_codec=2)
+    yield "pinned_fixedlen", a, x, 1e-4, None, dict(chunk_elems=65536, force_codec=1)
+    yield "pinned_raw", a, x, 1e-4, None, dict(chunk_elems=65536, force_codec=0)
+    yield "min_gain_rejects_everything", a, x, 1e-4, None, dict(chunk_elems=65536, min_gain_permil=990)
+    yield "short_sample", a, x, 1e-4, (1024, 0, 0, 0, 0, 0, 0, 0), dict(chunk_elems=65536)
+    yield "small_batch_fast_path", a, x, 1e-4, (0, 1 << 20, 0, 0, 0, 0, 0, 0), dict(chunk_elems=65536)
+    yield "fast_link_all_raw", a, x, 1e-4, (0, 0, 1, 0, 5, 0, 5, 0), dict(chunk_elems=65536)
+    yield "mid_link", a, x, 1e-4, (0, 0, 40, 100, 2, 700, 6, 0), dict(chunk_elems=65536)
+    a2, x2 = a.copy(), x.copy()
+    a2[70000] = np.inf; x2[140000] = np.nan; x2[250000] = 1e30
+    yield "frames_without_integer_sums", a2, x2, 1e-4, None, dict(chunk_elems=65536)
+    # one value behind the sample (the first 64 KiB of a frame) is wider than anything in it: a FIXEDLEN plan fails when
+    # realized, a HUFFMAN plan escapes it
+    a3, x3 = a.copy(), x.copy()
+    x3[65536 + 30000] = 6.0                                            # 16 bits, wider than anything in the sample
+    yield "wide_behind_the_sample", a3, x3, 1e-4, None, dict(chunk_elems=65536)
+    yield "wide_behind_the_sample_fixedlen", a3, x3, 1e-4, None, dict(chunk_elems=65536, force_codec=1)
+
+
+@pytest.mark.parametrize("name,a,x,eb,ropts,kw", list(_ring_cases()), ids=[c[0] for c in _ring_cases()])
+def test_ring_step_with_sampled_arbitration_matches_oracle(nz, name, a, x, eb, ropts, kw):
+    ref, ores, out, r, plans = check_ring_rea(nz, a, x, eb, ropts=ropts, **kw)
+    if name == "fast_link_all_raw":
+        assert (plans == oracle.RAW).all() and r["n_fallback"] == 0
+    if name == "frames_without_integer_sums":
+        assert r["n_raw"] >= 3 and r["n_fallback"] == 0
+    if name == "wide_behind_the_sample_fixedlen":
+        assert r["n_fallback"] >= 1
+    if name == "min_gain_rejects_everything":
+        assert r["n_raw"] == r["n_frames"]
+
+
+def test_ring_step_sampled_without_context_and_errors(nz):
+    import torch
+    n = 100000
+    a, x = W.gradient_like(n, seed=81), W.gradient_like(n, seed=82)
+    kw = dict(chunk_elems=32768)
+    check_ring_rea(nz, a, x, 1e-4, with_ctx=False, **kw)                 # no context: FIXEDLEN or RAW only
+    g, o = nz.make_opts(**kw), oracle.make_opts(**kw)
+    sa, _, _ = oracle.compress(a, 1e-4, o)
+    # a stream made with another bound, a corrupted frame: status carried over, nothing published
+    rc, r, out = gpu_reduce_local_rea(nz, sa, x, 2e-4, g, None, None)
+    assert rc == 0 and r["status"] == nz.ERR_MISMATCH and r["span_bytes"] == 0 and r["wire_bytes"] == 0
+    bad = sa.copy()
+    off = int(bad[64 + 8:64 + 16].view(np.uint64)[0])
+    bad[off + 4] ^= 0x40
+    rc, r, out = gpu_reduce_local_rea(nz, bad, x, 1e-4, g, None, None)
+    assert rc == 0 and r["status"] == nz.ERR_CORRUPT and r["span_bytes"] == 0
+    assert oracle.reduce_local_rea(bad, x, 1e-4, o, None, None)[2] == oracle.ERR_CORRUPT
+    # capacity one slot short, predictor, reserved field
+    bound = nz.nz_compress_bound(n, g)
+    rc, r, out = gpu_reduce_local_rea(nz, sa, x, 1e-4, g, None, None, cap=bound - 16)
+    assert rc == nz.ERR_CAPACITY and r["status"] == nz.ERR_CAPACITY
+    assert gpu_reduce_local_rea(nz, sa, x, 1e-4, nz.make_opts(predictor=1, **kw), None, None)[0] == nz.ERR_INVALID
+    assert gpu_reduce_local_rea(nz, sa, x, 1e-4, g, nz.ReaOpts(0, 0, 0, 0, 0, 0, 0, 3), None)[0] == nz.ERR_INVALID
+    assert nz.nz_reduce_rea_workspace_bytes(n, nz.make_opts(seg_syms=64)) == 0
+    torch.cuda.synchronize()
