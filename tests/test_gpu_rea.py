@@ -384,3 +384,14 @@ def test_ring_step_sampled_without_context_and_errors(nz):
     assert gpu_reduce_local_rea(nz, sa, x, 1e-4, g, nz.ReaOpts(0, 0, 0, 0, 0, 0, 0, 3), None)[0] == nz.ERR_INVALID
     assert nz.nz_reduce_rea_workspace_bytes(n, nz.make_opts(seg_syms=64)) == 0
     torch.cuda.synchronize()
+
+
+def test_ring_step_sampled_c2_full_size(nz):
+    """The headline geometry (64 Mi elements, 1 MiB frames) through the sampled ring step, in the launch configuration
+    bench.py times: every frame against the oracle."""
+    n = 1 << 26
+    a = W.gradient_like(n, seed=2)
+    x = W.gradient_like(n, seed=102)
+    eb = float(np.float32(W.abs_bound_from_rel(a, 1e-4)))
+    ref, ores, out, r, plans = check_ring_rea(nz, a, x, eb, chunk_elems=262144)
+    assert ores.n_huff == 256 and ores.n_fallback == 0
