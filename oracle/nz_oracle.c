@@ -779,6 +779,9 @@ static uint32_t canon_sum_bits(float a, float b) {
  * entropy paths cannot take, it is committed as RAW (the safe fallback of Sec. IV-C / Algorithm 1,
  * CommitRawOrFail) and holds fl32(fl32(qa*step) + fl32(qb*step)) for every element.
  * Either input RAW -> RAW frame holding the fp32 sum of the two (dequantized or raw) values.
+ * A frame of integer sums that the selector commits RAW all the same (codec pinned to RAW, no entropy candidate
+ * passes the gates, or RAW wins the size tie at a width of 32 bits) holds the same fp32 sums of the dequantized
+ * operands: a RAW frame always carries what the receiver would have computed from the two operands.
  */
 static int reduce_src(void* vctx, uint32_t k, uint64_t i0, uint32_t nf, int32_t* q, uint32_t* rbits) {
     reduce_ctx* c = (reduce_ctx*)vctx;
@@ -790,7 +793,13 @@ static int reduce_src(void* vctx, uint32_t k, uint64_t i0, uint32_t nf, int32_t*
             if (Q > NZO_QSUM_MAX || Q < -(int64_t)NZO_QSUM_MAX) { coded = 0; break; }
             q[i] = (int32_t)Q;
         }
-        if (coded) return 1;
+        if (coded) {
+            /* the selector may still commit the frame RAW (pinned RAW, minimum gain, a width of 32 bits): like every
+             * RAW frame of a reduce it then holds the fp32 sums of the two dequantized operands */
+            for (uint32_t i = 0; i < nf; i++)
+                rbits[i] = canon_sum_bits(nzo_dequantize_one(c->qa[i0 + i], c->step), nzo_dequantize_one(c->qb[i0 + i], c->step));
+            return 1;
+        }
     }
     for (uint32_t i = 0; i < nf; i++) {
         float va = a_raw ? bits_f32(c->ra[i0 + i]) : nzo_dequantize_one(c->qa[i0 + i], c->step);

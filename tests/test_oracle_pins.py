@@ -585,6 +585,31 @@ def test_reduce_is_exact_integer_sum_and_order_free():
     assert (np.abs(out.astype(np.float64) - true) <= 4 * float(np.float32(eb))).all()
 
 
+@pytest.mark.parametrize("kw", [dict(force_codec=0), dict(min_gain_permil=999), dict(min_gain_permil=650, huff_min_bytes=1 << 20)])
+def test_reduce_frame_committed_raw_by_the_selector_holds_the_fp32_sums(kw):
+    # Sec. IV-C: RAW is the fallback every frame can take.  A frame of integer sums that the selector commits RAW
+    # (codec pinned, no entropy candidate passes the gates) carries what the receiver would have computed from the
+    # two operands: numpy's fp32 sum of the two separately decompressed (separately pinned) operands.
+    n, eb = 3500, 1e-4
+    plain = oracle.make_opts(chunk_elems=1000)
+    opts = oracle.make_opts(chunk_elems=1000, **kw)
+    a = W.gradient_like(n, seed=75); b = W.gradient_like(n, seed=76)
+    sa = oracle.compress(a, eb, plain)[0]; sb = oracle.compress(b, eb, plain)[0]
+    da = oracle.decompress(sa, n, eb)[0]; db = oracle.decompress(sb, n, eb)[0]
+    r, res, rc = oracle.reduce_frames(sa, sb, n, eb, opts)
+    assert rc == 0 and res.n_raw > 0
+    out = oracle.decompress(r, n, eb)[0]
+    kinds = oracle.decode_codes(r, n, eb)[2]
+    want = (da + db).astype(np.float32)
+    for f in range(4):
+        sl = slice(1000 * f, min(n, 1000 * (f + 1)))
+        if kinds[f]:
+            assert np.array_equal(out[sl].view(np.uint32), want[sl].view(np.uint32))
+    # the ring step: the local operand is the rank's own data, quantized at the interface and dequantized again
+    r2, res2, rc2 = oracle.reduce_local(sa, b, eb, opts)
+    assert rc2 == 0 and res2.n_raw == res.n_raw and np.array_equal(r2, r)
+
+
 def test_reduce_raw_and_overflow_paths():
     n, eb = 3000, 1e-3
     opts = oracle.make_opts(chunk_elems=1000)
