@@ -87,6 +87,7 @@ def lib():
         L.nzo_decode_codes.argtypes = [vp, sz, sz, f32, vp, vp, vp, C.POINTER(Result)]
         L.nzo_reduce_frames.argtypes = [vp, sz, vp, sz, vp, sz, sz, f32, C.POINTER(Opts), C.POINTER(Result)]
         L.nzo_reduce_local.argtypes = [vp, sz, vp, vp, sz, sz, f32, C.POINTER(Opts), C.POINTER(Result)]
+        L.nzo_reduce_k.argtypes = [vp, vp, C.c_uint32, vp, sz, sz, f32, C.POINTER(Opts), C.POINTER(Result)]
         L.nzo_frame_plan.argtypes = [vp, C.c_uint32, C.c_int, C.POINTER(Opts), vp, vp, vp, vp, vp, vp, vp]
         L.nzo_frame_encode.argtypes = [vp, vp, C.c_uint32, C.c_int, C.POINTER(Opts), C.c_uint32, vp, sz]
         L.nzo_frame_encode.restype = C.c_int64
@@ -206,6 +207,21 @@ def reduce_frames(a, b, n, eb, opts=None, cap=None):
     res = Result()
     rc = lib().nzo_reduce_frames(_ptr(a), a.size, _ptr(b), b.size, _ptr(out), cap, n, C.c_float(eb),
                                  C.byref(opts) if opts is not None else None, C.byref(res))
+    return out[:res.bytes].copy(), res, rc
+
+
+def reduce_k(streams, n, eb, opts=None, cap=None):
+    """k-ary reduce: one output stream from the operand streams, taken in the order given."""
+    arrs = [np.ascontiguousarray(s, dtype=np.uint8) for s in streams]
+    k = len(arrs)
+    ptrs = (C.c_void_p * max(k, 1))(*[a.ctypes.data for a in arrs])
+    sizes = (C.c_size_t * max(k, 1))(*[a.size for a in arrs])
+    if cap is None:
+        cap = compress_bound(n, opts)
+    out = np.zeros(max(cap, 1), np.uint8)
+    res = Result()
+    rc = lib().nzo_reduce_k(ptrs, sizes, k, _ptr(out), cap, n, C.c_float(eb),
+                            C.byref(opts) if opts is not None else None, C.byref(res))
     return out[:res.bytes].copy(), res, rc
 
 

@@ -78,6 +78,7 @@ typedef struct {
 #define NZO_QSUM_MAX       (1 << 30)
 #define NZO_MAX_CHUNK      (1u << 20)
 #define NZO_MAX_K          1024u
+#define NZO_MAX_OPERANDS   64u          /* operands of one k-ary reduce */
 #define NZO_MAGIC_FRAME    0x31465A4Eu   /* bytes 'N','Z','F','1' */
 #define NZO_MAGIC_STREAM   0x31535A4Eu   /* bytes 'N','Z','S','1' */
 #define NZO_CHECK_XOR      0x5A5A5A5Au
@@ -900,6 +901,100 @@ int nzo_reduce_local(const uint8_t* in, size_t in_bytes, const float* local, uin
         res->status = (uint32_t)rc;
     }
     free(qa); free(qb); free(ra); free(rb); free(fa); free(fb);
+    return rc;
+}
+
+/* ------------------------------------------------------------------ */
+/* 8c. k-ary reduce: one output stream from k operand streams           */
+/*     (the reduction of Sec. IV-D "In-Primitive Overlap" taken over    */
+/*     all the contributions a rank holds at once, e.g. the k chunks    */
+/*     that arrive in a direct or tree-shaped reduce-scatter)           */
+/* ------------------------------------------------------------------ */
+
+typedef struct { const int32_t* q; const uint32_t* r; const uint8_t* f; } acc_ctx;
+
+static int acc_src(void* vctx, uint32_t k, uint64_t i0, uint32_t nf, int32_t* q, uint32_t* rbits) {
+    acc_ctx* c = (acc_ctx*)vctx;
+    memcpy(q, c->q + i0, 4ull * nf);
+    memcpy(rbits, c->r + i0, 4ull * nf);
+    return c->f[k] == 0;
+}
+
+/*
+ * out = s_0 (+) s_1 (+) ... (+) s_{k-1}, the operands taken in the order given: a left fold of the two-operand rule
+ * of nzo_reduce_frames, frame by frame, without the intermediate streams.  A frame's running value is either integer
+ * codes or fp32 words.  Adding operand p: while the running value and the operand's frame are both coded, the codes
+ * are added exactly; if some partial sum passes 2^30 in magnitude at this operand, or the operand's frame is RAW,
+ * the running value becomes fp32 -- fl32(v + v_p) element by element with v the running value (dequantized if it
+ * was coded) and v_p the operand's value (dequantized or raw) -- and stays fp32 for the operands that follow.
+ * Frames that end coded are re-planned and re-selected on the sums (one that the selector commits RAW holds the fp32
+ * form of the last step, as in nzo_reduce_frames); the others are RAW.  Since a frame of codes (or of fp32 words)
+ * survives being written and read back unchanged, the result is, byte for byte, what the chain
+ * nzo_reduce_frames(... nzo_reduce_frames(nzo_reduce_frames(s_0, s_1), s_2) ..., s_{k-1}) gives as long as the
+ * chain's intermediate streams keep integer sums as codes (no pinned RAW, no gate that turns such a frame RAW on the
+ * way: those options then apply to the final stream only).
+ */
+int nzo_reduce_k(const uint8_t* const* streams, const size_t* bytes, uint32_t k, uint8_t* out, size_t cap,
+                 size_t n, float eb, const nzo_opts* opts, nzo_result* res) {
+    nzo_opts o; float step, inv;
+    nzo_result dummy;
+    if (!res) res = &dummy;
+    memset(res, 0, sizeof *res);
+    if (n == 0 || !streams || !bytes || !out || k < 2 || k > NZO_MAX_OPERANDS) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
+    for (uint32_t p = 0; p < k; p++) if (!streams[p]) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
+    if (resolve_opts(opts, &o) || nzo_step_constants(eb, &step, &inv)) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
+    int rc = NZO_OK;
+    uint32_t n_frames = 0;
+    for (uint32_t p = 0; p < k && !rc; p++) {
+        stream_hdr h;
+        rc = parse_stream(streams[p], bytes[p], &h);
+        if (!rc && (h.n != n || h.chunk != o.chunk_elems || h.step_bits != f32_bits(step) || h.predictor != o.predictor))
+            rc = NZO_ERR_MISMATCH;
+        n_frames = h.n_frames;
+    }
+    if (rc) { res->status = (uint32_t)rc; return rc; }
+    int32_t* qs = (int32_t*)malloc(4ull * n); int32_t* qp = (int32_t*)malloc(4ull * n);
+    uint32_t* rs = (uint32_t*)malloc(4ull * n); uint32_t* rp = (uint32_t*)malloc(4ull * n);
+    uint8_t* fs = (uint8_t*)calloc(n_frames, 1); uint8_t* fp = (uint8_t*)calloc(n_frames, 1);
+    if (!qs || !qp || !rs || !rp || !fs || !fp) rc = NZO_ERR_INVALID;
+    if (!rc) rc = nzo_decode_codes(streams[0], bytes[0], n, eb, qs, rs, fs, NULL);      /* the running value starts as s_0 */
+    for (uint32_t p = 1; p < k && !rc; p++) {
+        rc = nzo_decode_codes(streams[p], bytes[p], n, eb, qp, rp, fp, NULL);
+        if (rc) break;
+        for (uint32_t f = 0; f < n_frames; f++) {
+            const uint64_t i0 = (uint64_t)f * o.chunk_elems;
+            const uint64_t i1 = (i0 + o.chunk_elems < n) ? i0 + o.chunk_elems : n;
+            int coded = fs[f] == 0 && fp[f] == 0;
+            if (coded)
+                for (uint64_t i = i0; i < i1; i++) {
+                    const int64_t Q = (int64_t)qs[i] + (int64_t)qp[i];
+                    if (Q > NZO_QSUM_MAX || Q < -(int64_t)NZO_QSUM_MAX) { coded = 0; break; }
+                }
+            if (coded) {
+                /* (the fp32 form of this step is kept beside the codes: if it is the last one and the selector commits
+                 * the frame RAW, that is what the frame holds, as in nzo_reduce_frames) */
+                for (uint64_t i = i0; i < i1; i++) {
+                    rs[i] = canon_sum_bits(nzo_dequantize_one(qs[i], step), nzo_dequantize_one(qp[i], step));
+                    qs[i] += qp[i];
+                }
+                continue;
+            }
+            for (uint64_t i = i0; i < i1; i++) {
+                const float v = fs[f] ? bits_f32(rs[i]) : nzo_dequantize_one(qs[i], step);
+                const float vp = fp[f] ? bits_f32(rp[i]) : nzo_dequantize_one(qp[i], step);
+                rs[i] = canon_sum_bits(v, vp);
+                qs[i] = 0;
+            }
+            fs[f] = 1;
+        }
+    }
+    if (!rc) {
+        acc_ctx c = { qs, rs, fs };
+        rc = emit_stream(acc_src, &c, n, &o, f32_bits(step), out, cap, res);
+    } else {
+        res->status = (uint32_t)rc;
+    }
+    free(qs); free(qp); free(rs); free(rp); free(fs); free(fp);
     return rc;
 }
 

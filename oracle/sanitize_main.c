@@ -32,6 +32,10 @@ static int run_case(size_t n, uint32_t chunk, uint32_t K, uint32_t seg, int forc
     nzo_opts od = o; od.force_codec = -1;
     if (nzo_reduce_frames(sa, ra.bytes, sb, rb.bytes, sc, cap, n, eb, &od, &rc)) return 5;
     if (nzo_reduce_local(sa, ra.bytes, y, sc, cap, n, eb, &od, &rc)) return 6;
+    {
+        const uint8_t* ops[3] = { sa, sb, sa }; const size_t lens[3] = { ra.bytes, rb.bytes, ra.bytes };
+        if (nzo_reduce_k(ops, lens, 3, sc, cap, n, eb, &od, &rc)) return 7;
+    }
     /* sampled arbitration with a cached context: valid, pinned, without context, capacity one slot short */
     {
         nzo_context ctx; nzo_rea_result rr; nzo_rea_opts ro = { 4096u, 0u, 0u, 0u, 0u, 0u, 0u, 0u };
@@ -94,6 +98,10 @@ static int run_case(size_t n, uint32_t chunk, uint32_t K, uint32_t seg, int forc
         (void)nzo_decompress(m, len, z, n, eb, &rc);
         (void)nzo_reduce_frames(m, len, sb, rb.bytes, sc, cap, n, eb, &od, &rc);
         (void)nzo_reduce_local(m, len, y, sc, cap, n, eb, &od, &rc);
+        {
+            const uint8_t* ops[3] = { sb, m, sb }; const size_t lens[3] = { rb.bytes, len, rb.bytes };
+            (void)nzo_reduce_k(ops, lens, 3, sc, cap, n, eb, &od, &rc);
+        }
         free(m);
     }
     free(x); free(y); free(z); free(sa); free(sb); free(sc);
