@@ -154,6 +154,7 @@ static nz_status compress_impl(const float* d_in, size_t n, float eb, float step
     A.stat_block = kStatBlock; A.sbpf = (o.chunk + kStatBlock - 1) / kStatBlock;
     A.force_codec = o.force; A.min_gain_permil = o.gain; A.huff_min_bytes = o.huff_min;
     A.eb = eb; A.step = step; A.inv_step = inv; A.step_bits = bits_of(step); A.seed = seed; A.pred = o.pred;
+    A.red_local = nullptr; A.red_sr = 0;
     A.out = reinterpret_cast<uint8_t*>(d_out); A.out_cap = out_cap; A.ws = ws; A.L = L; A.res = d_res;
     A.rea_ctx = nullptr; A.rea_tmp = nullptr; A.rea_gbits = nullptr; A.rea_fail = nullptr;
     if (stochastic && o.pred) return NZ_ERR_INVALID;              // (the stochastic quantizer is not built with the predictor)
@@ -335,7 +336,8 @@ static nz_status reduce_impl(const void* d_a, size_t a_bytes, const void* d_b, s
     A.in = nullptr; A.n = n; A.chunk = o.chunk; A.n_frames = nfr; A.K = o.K;
     A.stat_block = kDecBlock; A.sbpf = D.dbpf;
     A.force_codec = o.force; A.min_gain_permil = o.gain; A.huff_min_bytes = o.huff_min;
-    A.eb = eb; A.step = step; A.inv_step = inv; A.step_bits = bits_of(step); A.seed = 0; A.pred = o.pred;
+    A.eb = eb; A.step = step; A.inv_step = inv; A.step_bits = bits_of(step); A.seed = seed; A.pred = o.pred;
+    A.red_local = d_local; A.red_sr = stochastic ? 1u : 0u;
     A.out = reinterpret_cast<uint8_t*>(d_out); A.out_cap = out_cap; A.ws = ws; A.L = L; A.res = d_res;
     A.rea_ctx = nullptr; A.rea_tmp = nullptr; A.rea_gbits = nullptr; A.rea_fail = nullptr;
     trace_reset(); trace_mark(st);

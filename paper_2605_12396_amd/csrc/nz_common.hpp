@@ -47,7 +47,7 @@ struct FrameMeta {
     uint32_t segt_off;    // byte offset of the segment table inside the frame
     uint32_t bits_off;    // byte offset of the bitstream inside the frame
     uint32_t bits_words;  // bitstream length in 32-bit words
-    uint32_t pad_;        // sampled ring step: 1 = the frame has no integer sums (its fp32 sums are staged); else 0
+    uint32_t pad_;        // reduce: 1 = the frame has no integer sums (its fp32 sums are staged); else 0
     uint64_t huff_bits;
     uint64_t pad2_;
 };
@@ -256,6 +256,36 @@ hipError_t launch_context(const float* sample, uint64_t n, float eb, float step,
                           DevContext* ctx, hipStream_t st);
 hipError_t launch_rea(const ReaArgs& A, hipStream_t st, void (*mark)(hipStream_t));   // A.in: compress; else the ring step's encode + finish
 hipError_t launch_rea_status(void* res, uint32_t n_frames, uint32_t status, hipStream_t st);
+// ---- staging of the reduce (workspace) ----
+constexpr uint32_t kTile16R = 32;                    // symbols a decoding thread produces between two output phases
+constexpr int32_t kWideMarker = -32768;              // "this code does not fit 16 bits"
+constexpr uint32_t kHalf = 65536;                    // statistics granularity of the reduce (one encoder group)
+
+// Staging of operand A between the two reduce passes (workspace): a16 holds one 16-bit code per element,
+// kWideMarker where the code needs 32 bits, which then sits in a32; a RAW frame keeps its fp32 words in a32.
+// a32 is indexed by the element's position in the message.  a16 is too, except that inside every full half
+// (kHalf elements = 256 segments) the order is phase-major -- [phase of 32 symbols][segment][32] -- so that
+// what a wave stores or loads in one phase (8 segments x 32 codes) is 512 contiguous bytes, not eight half lines.
+struct StageA {
+    int16_t* a16; uint32_t* a32;
+    // position in a16 of frame element i (frame starts at message element f0 and has nf elements)
+    __device__ static inline uint64_t at16(uint64_t f0, uint32_t nf, uint32_t i) {
+        const uint32_t base = i & ~(kHalf - 1u), j = i & (kHalf - 1u);
+        const bool full = base + kHalf <= nf;
+        return f0 + base + (full ? ((j & (kSeg - 1u)) >> 5) * (kHalf / 8u) + (j >> 8) * kTile16R + (j & 31u) : j);
+    }
+    __device__ inline void put_code(uint64_t f0, uint32_t nf, uint32_t i, int32_t q, uint32_t& wide_seen) const {
+        if (q > 32767 || q <= kWideMarker) { a16[at16(f0, nf, i)] = (int16_t)kWideMarker; a32[f0 + i] = (uint32_t)q; wide_seen = 1; }
+        else a16[at16(f0, nf, i)] = (int16_t)q;
+    }
+    __device__ inline uint32_t get(uint64_t f0, uint32_t nf, uint32_t i, bool a_raw) const {   // fp32 bits (RAW) or the code
+        if (a_raw) return a32[f0 + i];
+        const int32_t q = a16[at16(f0, nf, i)];
+        return (q == kWideMarker) ? a32[f0 + i] : (uint32_t)q;
+    }
+};
+static_assert(kTile16R == 32 && kSeg == 256, "at16 assumes 8 phases of 32 symbols per segment");
+
 struct CompressArgs {
     const float* in;          // fp32 input (compress) or nullptr (reduce: the sums staged in the workspace are encoded)
     uint64_t n;
@@ -264,7 +294,9 @@ struct CompressArgs {
     uint32_t min_gain_permil, huff_min_bytes;
     float eb, step, inv_step;
     uint32_t step_bits;
-    uint32_t seed;            // stochastic quantizer only (kernels built with QM = 1)
+    uint32_t seed;            // stochastic quantizer only (kernels built with QM = 1; reduce: the ring step's local quantizer)
+    const float* red_local;   // reduce only: the rank's own fp32 message of a ring step (nullptr: two coded operands)
+    uint32_t red_sr;          // reduce only: the ring step quantizes its local data stochastically
     uint32_t pred;            // predictor of the stream: 0 none, 1 delta on the codes (kernels built with DELTA = 1)
     uint8_t* out; uint64_t out_cap;
     uint8_t* ws; WsLayout L;

@@ -392,7 +392,8 @@ __global__ __launch_bounds__(kBookThreads) void k_codebook(CompressArgs A) {
         M.bits_off = (codec == CODEC_HUFF) ? (M.segt_off + (uint32_t)pad4u(2ull * nseg)) : kHdrBytes;
         M.bits_words = (codec == CODEC_HUFF) ? (uint32_t)((s_bits + 31u) / 32u)
                                              : (uint32_t)(((uint64_t)nf * s_w_fixed + 31u) / 32u);
-        M.pad_ = 0; M.huff_bits = s_bits; M.pad2_ = 0;
+        M.pad_ = (!A.in && s_unq) ? 1u : 0u;      // reduce: the frame's fp32 sums are staged, there are no integer sums
+        M.huff_bits = s_bits; M.pad2_ = 0;
         reinterpret_cast<FrameMeta*>(A.ws + A.L.meta)[fid] = M;
         if (fits) {
             uint32_t h[8];
@@ -582,6 +583,34 @@ __device__ inline void enc_load(const EncGroup& G, uint32_t sb, uint32_t (&raw)[
             for (uint32_t q = 0; q < kEncIters; q++)
                 if (q == it) { raw[q][0] = t[0]; raw[q][1] = t[1]; raw[q][2] = t[2]; raw[q][3] = t[3]; }
         }
+    }
+}
+
+// Reduce, a frame of integer sums that the selector commits RAW (codec pinned to RAW, no entropy candidate passes the
+// gates, a width of 32 bits): like every RAW frame of a reduce it holds fl(fl(qa*step) + fl(qb*step)), the sums of the
+// two dequantized operands (RAW is the fallback every frame can take, Sec. IV-C).  The operands are recovered from the
+// staged sums Q: two streams -- qa from the staged codes of operand A, qb = Q - qa; ring step -- qb is the rank's own
+// value quantized again (it was quantizable, or the frame would have no integer sums), qa = Q - qb.
+__device__ inline void enc_raw_sums(const CompressArgs& A, const EncGroup& G, uint64_t f0, uint8_t* fr) {
+#pragma clang fp contract(off)
+    StageA sa;
+    sa.a16 = reinterpret_cast<int16_t*>(A.ws + A.L.a16); sa.a32 = reinterpret_cast<uint32_t*>(A.ws + A.L.a32);
+    uint32_t* dst = reinterpret_cast<uint32_t*>(fr + kHdrBytes) + G.g0;
+    for (uint32_t i = threadIdx.x; i < G.gcnt; i += kEncThreads) {
+        const int32_t Q = (int32_t)enc_word<1>(G, i);
+        int32_t qa, qb;
+        if (A.red_local) {
+            const uint64_t g = f0 + G.g0 + i;
+            const float x = A.red_local[g];
+            if (A.red_sr) sr_quantize1(x, A.step, A.inv_step, sr_draw(sr_key(A.seed, g), (uint32_t)g), qb);
+            else quantize1(x, A.eb, A.step, A.inv_step, qb);
+            qa = (int32_t)((uint32_t)Q - (uint32_t)qb);
+        } else {
+            qa = (int32_t)sa.get(f0, G.nf, G.g0 + i, false);
+            qb = (int32_t)((uint32_t)Q - (uint32_t)qa);
+        }
+        const float sum = dequantize1(qa, A.step) + dequantize1(qb, A.step);
+        dst[i] = (sum != sum) ? kCanonNaN : __float_as_uint(sum);
     }
 }
 
@@ -858,7 +887,8 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
     if (QM == 1) keys.init(A.seed, f0 + G.g0); else { keys.base_lo = 0; keys.key0 = 0; keys.key1 = 0; }
     if (SRC == 3 && M.codec == CODEC_RAW && !M.pad_) {
         // (a frame of integer sums that goes RAW holds the sums of the dequantized operands: the finishing kernel's)
-    } else if (M.codec != CODEC_HUFF) enc_raw_fixed<SRC, QM, DELTA>(A, G, M, fr, S.stage[0], bad, keys);
+    } else if (SRC == 1 && M.codec == CODEC_RAW && !M.pad_) enc_raw_sums(A, G, f0, fr);
+    else if (M.codec != CODEC_HUFF) enc_raw_fixed<SRC, QM, DELTA>(A, G, M, fr, S.stage[0], bad, keys);
     else {
         uint32_t raw[kEncIters][4];
         enc_load<SRC>(G, 0, raw);

@@ -444,10 +444,7 @@ struct DirectFetch {
 
 // The tile: 16-bit quantization codes, 32 per thread between two output phases, so that eight lanes write
 // one thread's run of 32 consecutive elements together (a full 128-byte line of fp32 or int32 output).
-constexpr uint32_t kTile16R = 32;
 constexpr uint32_t kTile16Stride = kTile16R + 2;     // halfwords per row: 17 words, an odd word stride
-constexpr int32_t kWideMarker = -32768;              // "this code does not fit 16 bits"
-constexpr uint32_t kHalf = 65536;                    // statistics granularity of the reduce (one encoder group)
 
 enum : int { MODE_DECOMPRESS = 0, MODE_STAGE_A = 1, MODE_ADD_B = 2, MODE_ADD_LOCAL = 3, MODE_ADD_LOCAL_SR = 4,
              MODE_ADD_LOCAL_PLAIN = 5 };
@@ -496,30 +493,6 @@ __device__ inline uint32_t combine(uint32_t ta, bool a_raw, uint32_t tb, bool b_
     return (uint32_t)qa + (uint32_t)qb;
 }
 
-// Staging of operand A between the two reduce passes (workspace): a16 holds one 16-bit code per element,
-// kWideMarker where the code needs 32 bits, which then sits in a32; a RAW frame keeps its fp32 words in a32.
-// a32 is indexed by the element's position in the message.  a16 is too, except that inside every full half
-// (kHalf elements = 256 segments) the order is phase-major -- [phase of 32 symbols][segment][32] -- so that
-// what a wave stores or loads in one phase (8 segments x 32 codes) is 512 contiguous bytes, not eight half lines.
-struct StageA {
-    int16_t* a16; uint32_t* a32;
-    // position in a16 of frame element i (frame starts at message element f0 and has nf elements)
-    __device__ static inline uint64_t at16(uint64_t f0, uint32_t nf, uint32_t i) {
-        const uint32_t base = i & ~(kHalf - 1u), j = i & (kHalf - 1u);
-        const bool full = base + kHalf <= nf;
-        return f0 + base + (full ? ((j & (kSeg - 1u)) >> 5) * (kHalf / 8u) + (j >> 8) * kTile16R + (j & 31u) : j);
-    }
-    __device__ inline void put_code(uint64_t f0, uint32_t nf, uint32_t i, int32_t q, uint32_t& wide_seen) const {
-        if (q > 32767 || q <= kWideMarker) { a16[at16(f0, nf, i)] = (int16_t)kWideMarker; a32[f0 + i] = (uint32_t)q; wide_seen = 1; }
-        else a16[at16(f0, nf, i)] = (int16_t)q;
-    }
-    __device__ inline uint32_t get(uint64_t f0, uint32_t nf, uint32_t i, bool a_raw) const {   // fp32 bits (RAW) or the code
-        if (a_raw) return a32[f0 + i];
-        const int32_t q = a16[at16(f0, nf, i)];
-        return (q == kWideMarker) ? a32[f0 + i] : (uint32_t)q;
-    }
-};
-static_assert(kTile16R == 32 && kSeg == 256, "at16 assumes 8 phases of 32 symbols per segment");
 
 // Second reduce pass, one element the general way: fetch A, combine, stage the sum, count its symbol.
 // The sums are staged for the encoder as 16-bit codes in c16 (message order), kWideMarker where a sum needs 32

@@ -315,6 +315,33 @@ def test_reduce_all_codec_pairs(nz, ca, cb):
     assert r["bytes"] == ores.bytes and _first_diff(got, ref) == -1
 
 
+@pytest.mark.parametrize("kw", [dict(force_codec=0), dict(min_gain_permil=999), dict(min_gain_permil=650, huff_min_bytes=1 << 20),
+                                dict(force_codec=0, predictor=1)])
+@pytest.mark.parametrize("n,chunk", [(70001, 20000), (300000, 131072)])
+def test_reduce_integer_sums_committed_raw(nz, kw, n, chunk):
+    """A frame of integer sums that the selector commits RAW (pinned, gated) holds the fp32 sums of the dequantized
+    operands: two streams (incl. wide codes and a RAW operand frame beside it) and the ring step, bytes against the oracle."""
+    eb = 1e-4
+    pred = kw.get("predictor", 0)
+    a = W.gradient_like(n, seed=84)
+    b = W.gradient_like(n, seed=85, b=3e-3)
+    a[5] = 2.5; a[chunk + 7] = -3.0                              # codes that need more than 16 bits in the staging
+    b[n - 3] = np.nan                                            # the last frame of b is RAW
+    plain = oracle.make_opts(chunk_elems=chunk, predictor=pred)
+    sa = oracle.compress(a, eb, plain)[0]
+    sb = oracle.compress(b, eb, plain)[0]
+    g, o = _opts_pair(nz, chunk_elems=chunk, **kw)
+    ref, ores, orc = oracle.reduce_frames(sa, sb, n, eb, o)
+    rc, r, got = gpu_reduce(nz, sa, sb, n, eb, g)
+    assert rc == 0 and orc == 0 and r["status"] == 0 and ores.n_raw > 1
+    assert (r["n_raw"], r["n_fixed"], r["n_huff"]) == (ores.n_raw, ores.n_fixed, ores.n_huff)
+    assert r["bytes"] == ores.bytes and _first_diff(got, ref) == -1
+    ref, ores, orc = oracle.reduce_local(sa, b, eb, o)
+    rc, r, got = gpu_reduce_local(nz, sa, b, eb, g)
+    assert rc == 0 and orc == 0 and r["status"] == 0 and ores.n_raw > 1
+    assert r["bytes"] == ores.bytes and _first_diff(got, ref) == -1
+
+
 def test_reduce_raw_nan_overflow_and_mismatch(nz):
     n, eb = 3000, 1e-3
     g, o = _opts_pair(nz, chunk_elems=1000)

@@ -197,3 +197,21 @@ def test_ring_step_with_the_stochastic_quantizer(nz, name):
         assert nz.nz_reduce_local_sr(da, acc.size, dx, out, sess.cap, n, step, 1, sess.res, gp, sess.ws, sess.ws_bytes) == nz.ERR_INVALID
         assert nz.nz_reduce_local_sr(da, acc.size, dx, out, sess.cap, n, float("nan"), 1, sess.res, g, sess.ws, sess.ws_bytes) == nz.ERR_INVALID
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("kw", [dict(force_codec=0), dict(min_gain_permil=999)])
+def test_ring_step_sums_committed_raw_with_the_stochastic_quantizer(nz, kw):
+    """A frame of integer sums that the selector commits RAW holds the fp32 sums of the dequantized operands; the
+    stochastic ring step recovers the rank's own codes with the same draws."""
+    n, chunk = 150001, 65536
+    g, o = nz.make_opts(chunk_elems=chunk, **kw), oracle.make_opts(chunk_elems=chunk, **kw)
+    xs = [W.gradient_like(n, seed=230 + p) for p in range(2)]
+    step = float(np.float32(max(oracle.qsgd_step(x, 200) for x in xs)))
+    acc, _, rc = oracle.compress_sr(xs[0], step, 7, oracle.make_opts(chunk_elems=chunk))
+    assert rc == 0
+    ref, ores, orc = oracle.reduce_local_sr(acc, xs[1], step, 8, o)
+    rc, r, got = _gpu_reduce_local_sr(nz, acc, xs[1], step, 8, g)
+    assert orc == 0 and rc == 0 and r["status"] == 0 and ores.n_raw == 3
+    assert (r["n_raw"], r["bytes"]) == (ores.n_raw, ores.bytes)
+    d = np.nonzero(got != ref)[0]
+    assert d.size == 0, "first differing byte %d" % int(d[0])
