@@ -252,12 +252,38 @@ nz_status nz_decompress(const void* d_stream, size_t stream_bytes, float* d_out,
  * and holds the fp32 sum (NaN sums stored as 0x7FC00000).  A frame in which a
  * sum exceeds 2^30 in magnitude can no longer be carried as integer codes: it
  * is committed as RAW (the selector's safe fallback, Sec. IV-C) and holds
- * fl32(fl32(qa*step) + fl32(qb*step)).
+ * fl32(fl32(qa*step) + fl32(qb*step)); so does a frame of integer sums that
+ * the selector commits RAW all the same (codec pinned to RAW, no entropy
+ * candidate passes the gates): a RAW frame of a reduce always carries what the
+ * receiver would have computed from the two operands.
  *   d_ws/ws_bytes  device scratch of at least nz_reduce_workspace_bytes(n, opts).
  */
 nz_status nz_reduce_frames(const void* d_a, size_t a_bytes, const void* d_b, size_t b_bytes, void* d_out,
                            size_t out_cap, size_t n, float eb, nz_result* d_res, const nz_opts* opts,
                            void* d_ws, size_t ws_bytes, void* stream);
+
+/*
+ * k-ary reduce (the reduction of Sec. IV-D "In-Primitive Overlap" over all the
+ * contributions a rank holds at once, e.g. the chunks of a direct or
+ * tree-shaped reduce-scatter): out = s_0 (+) s_1 (+) ... (+) s_{k-1}, every
+ * operand decoded once and the sum encoded once.  The operands are folded in
+ * the order given with the rule of nz_reduce_frames, frame by frame: codes are
+ * added exactly while the running value and the operand's frame are both coded;
+ * at the operand where a partial sum passes 2^30 in magnitude, or whose frame
+ * is RAW, the running value becomes fp32 (fl32(v + v_p), v and v_p dequantized
+ * or raw) and stays fp32.  Byte-identical to the chain nz_reduce_frames(...
+ * nz_reduce_frames(s_0, s_1) ..., s_{k-1}) as long as the chain's intermediate
+ * streams keep integer sums as codes; opts that turn such frames RAW (pinned
+ * RAW, gates) apply to the final stream only.  k = 2 is nz_reduce_frames.
+ *   d_streams / stream_bytes  HOST arrays of k device pointers (16-byte aligned
+ *                  NZ streams made with the same n, eb and opts) and their sizes;
+ *                  read during the call only.  2 <= k <= 64, else NZ_ERR_INVALID.
+ *   d_ws/ws_bytes  device scratch of at least nz_reduce_workspace_bytes(n, opts).
+ * Errors as for nz_reduce_frames (a stream-level or frame-level error in any
+ * operand fails the call: status set, bytes = 0).
+ */
+nz_status nz_reduce_k(const void* const* d_streams, const size_t* stream_bytes, uint32_t k, void* d_out, size_t out_cap,
+                      size_t n, float eb, nz_result* d_res, const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream);
 
 /*
  * Ring-step reduce (the receive-reduce-send step of Sec. IV-D "In-Primitive

@@ -9,6 +9,8 @@
  *   nz_compress       statistics, codebook + selector, encode
  *   nz_decompress     decode, finish (result record, zero-fill of rejected frames)
  *   nz_reduce_frames  init, stage A, decode B + add, fix (late RAW frames), codebook + selector, encode
+ *   nz_reduce_k       init, stage operand 0, one interval per accumulated operand (add + fix), decode the last + add, fix,
+ *                     codebook + selector, encode
  *   nz_reduce_local   init, decode + quantize local + add, fix, codebook + selector, encode
  *   nz_compress_rea   encode (every workgroup profiles the frame's sample first), finish
  *   nz_reduce_local_rea   init, decode + quantize local + add, fix, encode (profiles the staged sums first), finish

@@ -82,6 +82,8 @@ def lib():
         L.nz_decompress.restype = C.c_int
         L.nz_reduce_frames.argtypes = [vp, sz, vp, sz, vp, sz, sz, f32, vp, po, vp, sz, vp]
         L.nz_reduce_frames.restype = C.c_int
+        L.nz_reduce_k.argtypes = [vp, vp, C.c_uint32, vp, sz, sz, f32, vp, po, vp, sz, vp]
+        L.nz_reduce_k.restype = C.c_int
         L.nz_reduce_local.argtypes = [vp, sz, vp, vp, sz, sz, f32, vp, po, vp, sz, vp]
         L.nz_reduce_local_sr.argtypes = [vp, sz, vp, vp, sz, sz, f32, C.c_uint32, vp, po, vp, sz, vp]
         L.nz_reduce_local_sr.restype = C.c_int
@@ -200,6 +202,15 @@ def nz_reduce_frames(d_a, a_bytes, d_b, b_bytes, d_out, out_cap, n, eb, d_res, o
                                       _stream(stream)))
 
 
+def nz_reduce_k(d_streams, stream_bytes, d_out, out_cap, n, eb, d_res, opts, d_ws, ws_bytes, stream=None):
+    """d_streams: sequence of device tensors, stream_bytes: their sizes (host arrays of pointers / sizes are built here)."""
+    k = len(d_streams)
+    ptrs = (C.c_void_p * max(k, 1))(*[t.data_ptr() for t in d_streams])
+    sizes = (C.c_size_t * max(k, 1))(*[int(b) for b in stream_bytes])
+    return int(lib().nz_reduce_k(ptrs, sizes, k, d_out.data_ptr(), out_cap, n, C.c_float(eb), d_res.data_ptr(), _po(opts),
+                                 d_ws.data_ptr(), ws_bytes, _stream(stream)))
+
+
 def nz_reduce_local(d_in, in_bytes, d_local, d_out, out_cap, n, eb, d_res, opts, d_ws, ws_bytes, stream=None):
     return int(lib().nz_reduce_local(d_in.data_ptr(), in_bytes, d_local.data_ptr(), d_out.data_ptr(), out_cap, n,
                                      C.c_float(eb), d_res.data_ptr(), _po(opts), d_ws.data_ptr(), ws_bytes,
@@ -251,6 +262,12 @@ class Session:
         out = out if out is not None else self.new_stream_buffer()
         rc = nz_reduce_frames(a, a_bytes, b, b_bytes, out, self.cap if cap is None else cap, n, eb, self.res,
                               self.opts, self.ws, self.ws_bytes)
+        return rc, out
+
+    def reduce_k(self, streams, sizes, n, eb, out=None, cap=None):
+        out = out if out is not None else self.new_stream_buffer()
+        rc = nz_reduce_k(streams, sizes, out, self.cap if cap is None else cap, n, eb, self.res, self.opts, self.ws,
+                         self.ws_bytes)
         return rc, out
 
     def reduce_local(self, a, a_bytes, x, n, eb, out=None, cap=None):

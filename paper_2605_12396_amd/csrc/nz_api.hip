@@ -278,7 +278,7 @@ static nz_status decompress_impl(const void* d_stream, size_t stream_bytes, floa
     const uint32_t nfr = (uint32_t)((n + o.chunk - 1) / o.chunk);
     DecodeArgs A;
     A.a = reinterpret_cast<const uint8_t*>(d_stream); A.a_bytes = stream_bytes; A.b = nullptr; A.b_bytes = 0;
-    A.out = d_out; A.local = nullptr; A.eb = 0.0f; A.inv_step = 0.0f; A.n = n; A.chunk = o.chunk; A.n_frames = nfr; A.K = o.K;
+    A.out = d_out; A.local = nullptr; A.eb = 0.0f; A.inv_step = 0.0f; A.sr = 0; A.seed = 0; A.set_in = 0; A.n = n; A.chunk = o.chunk; A.n_frames = nfr; A.K = o.K;
     A.dbpf = (o.chunk + kDecBlock - 1) / kDecBlock; A.pred = o.pred;
     A.step = step; A.step_bits = bits_of(step); A.ws = reinterpret_cast<uint8_t*>(d_ws); A.L = L; A.res = d_res;
     static_assert(kDecBlock == kStatBlock, "the verdict words reuse the per-statistics-block slots of the workspace");
@@ -305,17 +305,24 @@ nz_status nz_decompress_step(const void* d_stream, size_t stream_bytes, float* d
 }
 
 // The two reduce entry points differ only in the second operand: a stream (d_b) or the rank's own fp32 data (d_local).
-static nz_status reduce_impl(const void* d_a, size_t a_bytes, const void* d_b, size_t b_bytes, const float* d_local,
+constexpr uint32_t kMaxOperands = 64;         // operand streams of one k-ary reduce
+
+// The reduce entry points: k operand streams (k >= 2), or one incoming stream and the rank's own fp32 message.
+// k > 2: the running value lives in one of two staging sets of the workspace; every operand between the first and
+// the last is added by an accumulating pass that reads one set and writes the other (the set of the first pass is
+// chosen so that the last accumulating pass leaves the running value where the statistics pass expects operand A).
+static nz_status reduce_impl(const void* const* d_ops, const size_t* op_bytes, uint32_t k, const float* d_local,
                              void* d_out, size_t out_cap, size_t n, float eb, float step, float inv, nz_result* d_res,
                              const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream, bool stochastic = false,
                              uint32_t seed = 0) {
     Opts o;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
-    const void* second = d_local ? static_cast<const void*>(d_local) : d_b;
-    if (!d_a || !second || !d_out || !d_res || !d_ws || !resolve(opts, o) || !geometry_ok(n, o))
+    if (!d_ops || !op_bytes || k < 1 || k > kMaxOperands || (!d_local && k < 2) || (d_local && k != 1)) return NZ_ERR_INVALID;
+    for (uint32_t p = 0; p < k; p++) if (!d_ops[p] || !aligned16(d_ops[p])) return NZ_ERR_INVALID;
+    if (!d_out || !d_res || !d_ws || !resolve(opts, o) || !geometry_ok(n, o))
         return NZ_ERR_INVALID;
     if (stochastic && o.pred) return NZ_ERR_INVALID;               // (the stochastic quantizer is not built with the predictor)
-    if (!aligned16(d_a) || !aligned16(second) || !aligned16(d_out) || !aligned16(d_ws) || !aligned16(d_res))
+    if ((d_local && !aligned16(d_local)) || !aligned16(d_out) || !aligned16(d_ws) || !aligned16(d_res))
         return NZ_ERR_INVALID;
     const WsLayout L = ws_layout(n, o.chunk, kDecBlock, true);
     if (ws_bytes < L.total) return NZ_ERR_INVALID;
@@ -326,9 +333,10 @@ static nz_status reduce_impl(const void* d_a, size_t a_bytes, const void* d_b, s
         return NZ_ERR_CAPACITY;
     }
     DecodeArgs D;
-    D.a = reinterpret_cast<const uint8_t*>(d_a); D.a_bytes = a_bytes;
-    D.b = reinterpret_cast<const uint8_t*>(d_b); D.b_bytes = b_bytes;
+    D.a = reinterpret_cast<const uint8_t*>(d_ops[0]); D.a_bytes = op_bytes[0];
+    D.b = k > 1 ? reinterpret_cast<const uint8_t*>(d_ops[1]) : nullptr; D.b_bytes = k > 1 ? op_bytes[1] : 0;
     D.out = nullptr; D.local = d_local; D.eb = eb; D.inv_step = inv; D.sr = stochastic ? 1u : 0u; D.seed = seed;
+    D.set_in = 0;
     D.n = n; D.chunk = o.chunk; D.n_frames = nfr; D.K = o.K;
     D.dbpf = (o.chunk + kDecBlock - 1) / kDecBlock; D.pred = o.pred;
     D.step = step; D.step_bits = bits_of(step); D.ws = ws; D.L = L; D.res = d_res;
@@ -347,9 +355,18 @@ static nz_status reduce_impl(const void* d_a, size_t a_bytes, const void* d_b, s
         if (launch_decode(D, stochastic ? 4 : 3, st) != hipSuccess) return NZ_ERR_HIP;   // decode incoming + quantize local + add
         trace_mark(st);
     } else {
-        if (launch_decode(D, 1, st) != hipSuccess) return NZ_ERR_HIP;       // stage operand A
+        D.set_in = (k - 2u) & 1u;                                           // where the first pass stages operand 0
+        if (launch_decode(D, 1, st) != hipSuccess) return NZ_ERR_HIP;       // stage operand 0
         trace_mark(st);
-        if (launch_decode(D, 2, st) != hipSuccess) return NZ_ERR_HIP;       // decode operand B + add
+        for (uint32_t p = 1; p + 1 < k; p++) {                              // operands 1 .. k-2: running value += operand
+            D.b = reinterpret_cast<const uint8_t*>(d_ops[p]); D.b_bytes = op_bytes[p];
+            if (launch_decode(D, 6, st) != hipSuccess) return NZ_ERR_HIP;
+            if (launch_fix_acc(D, st) != hipSuccess) return NZ_ERR_HIP;     // frames whose partial sums left the range
+            trace_mark(st);
+            D.set_in ^= 1u;
+        }
+        D.b = reinterpret_cast<const uint8_t*>(d_ops[k - 1]); D.b_bytes = op_bytes[k - 1];
+        if (launch_decode(D, 2, st) != hipSuccess) return NZ_ERR_HIP;       // decode the last operand + add + statistics
         trace_mark(st);
     }
     if (launch_fix(D, st) != hipSuccess) return NZ_ERR_HIP;                 // frames that turn RAW late (local data, sums past 2^30)
@@ -369,7 +386,8 @@ nz_status nz_reduce_frames(const void* d_a, size_t a_bytes, const void* d_b, siz
                            void* d_ws, size_t ws_bytes, void* stream) {
     float step, inv;
     if (!step_constants(eb, step, inv)) return NZ_ERR_INVALID;
-    return reduce_impl(d_a, a_bytes, d_b, b_bytes, nullptr, d_out, out_cap, n, eb, step, inv, d_res, opts, d_ws, ws_bytes, stream);
+    const void* ops[2] = { d_a, d_b }; const size_t lens[2] = { a_bytes, b_bytes };
+    return reduce_impl(ops, lens, 2, nullptr, d_out, out_cap, n, eb, step, inv, d_res, opts, d_ws, ws_bytes, stream);
 }
 
 nz_status nz_reduce_frames_step(const void* d_a, size_t a_bytes, const void* d_b, size_t b_bytes, void* d_out,
@@ -377,7 +395,15 @@ nz_status nz_reduce_frames_step(const void* d_a, size_t a_bytes, const void* d_b
                                 void* d_ws, size_t ws_bytes, void* stream) {
     float inv;
     if (!step_given(step, inv)) return NZ_ERR_INVALID;
-    return reduce_impl(d_a, a_bytes, d_b, b_bytes, nullptr, d_out, out_cap, n, 0.0f, step, inv, d_res, opts, d_ws, ws_bytes, stream);
+    const void* ops[2] = { d_a, d_b }; const size_t lens[2] = { a_bytes, b_bytes };
+    return reduce_impl(ops, lens, 2, nullptr, d_out, out_cap, n, 0.0f, step, inv, d_res, opts, d_ws, ws_bytes, stream);
+}
+
+nz_status nz_reduce_k(const void* const* d_streams, const size_t* stream_bytes, uint32_t k, void* d_out, size_t out_cap,
+                      size_t n, float eb, nz_result* d_res, const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream) {
+    float step, inv;
+    if (k < 2 || !step_constants(eb, step, inv)) return NZ_ERR_INVALID;
+    return reduce_impl(d_streams, stream_bytes, k, nullptr, d_out, out_cap, n, eb, step, inv, d_res, opts, d_ws, ws_bytes, stream);
 }
 
 nz_status nz_reduce_local(const void* d_in, size_t in_bytes, const float* d_local, void* d_out, size_t out_cap,
@@ -385,7 +411,7 @@ nz_status nz_reduce_local(const void* d_in, size_t in_bytes, const float* d_loca
                           void* stream) {
     float step, inv;
     if (!d_local || !step_constants(eb, step, inv)) return NZ_ERR_INVALID;
-    return reduce_impl(d_in, in_bytes, nullptr, 0, d_local, d_out, out_cap, n, eb, step, inv, d_res, opts, d_ws, ws_bytes, stream);
+    return reduce_impl(&d_in, &in_bytes, 1, d_local, d_out, out_cap, n, eb, step, inv, d_res, opts, d_ws, ws_bytes, stream);
 }
 
 // Workspace of the sampled ring step: the adding pass's workspace, a result record of its own for that pass, and
@@ -431,7 +457,7 @@ nz_status nz_reduce_local_rea(const void* d_in, size_t in_bytes, const float* d_
     uint8_t* ws = reinterpret_cast<uint8_t*>(d_ws);
     DecodeArgs D;
     D.a = reinterpret_cast<const uint8_t*>(d_in); D.a_bytes = in_bytes; D.b = nullptr; D.b_bytes = 0;
-    D.out = nullptr; D.local = d_local; D.eb = eb; D.inv_step = inv; D.sr = 0; D.seed = 0;
+    D.out = nullptr; D.local = d_local; D.eb = eb; D.inv_step = inv; D.sr = 0; D.seed = 0; D.set_in = 0;
     D.n = n; D.chunk = o.chunk; D.n_frames = nfr; D.K = o.K;
     D.dbpf = (o.chunk + kDecBlock - 1) / kDecBlock; D.pred = 0;
     D.step = step; D.step_bits = bits_of(step); D.ws = ws; D.L = L.R; D.res = ws + L.add_res;
@@ -471,7 +497,7 @@ nz_status nz_reduce_local_sr(const void* d_in, size_t in_bytes, const float* d_l
                              size_t ws_bytes, void* stream) {
     float inv;
     if (!d_local || !step_given(step, inv)) return NZ_ERR_INVALID;
-    return reduce_impl(d_in, in_bytes, nullptr, 0, d_local, d_out, out_cap, n, 0.0f, step, inv, d_res, opts, d_ws, ws_bytes, stream,
+    return reduce_impl(&d_in, &in_bytes, 1, d_local, d_out, out_cap, n, 0.0f, step, inv, d_res, opts, d_ws, ws_bytes, stream,
                        true, seed);
 }
 

@@ -63,7 +63,7 @@ static_assert(sizeof(Ctrl) == 64, "Ctrl is 64 bytes");
 // Workspace carve-up; computed identically on host for sizing and launch.
 struct WsLayout {
     size_t ctrl, frame_desc, zero_end;      // [ctrl, zero_end) is cleared per call
-    size_t meta, book_code, book_len, phist, pmeta, grp_start, codes, c16, cwide, a16, a32, akind, awide, total;
+    size_t meta, book_code, book_len, phist, pmeta, grp_start, codes, c16, cwide, a16, a32, akind, awide, akind1, awide1, total;
 };
 
 __host__ __device__ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -89,6 +89,8 @@ __host__ inline WsLayout ws_layout(size_t n, uint32_t chunk, uint32_t stat_block
     L.a32 = o;         if (with_codes) o += align_up(4 * n, 256);      // reduce: operand A, wide codes and RAW words
     L.akind = o;       if (with_codes) o += align_up(4 * n_frames, 256);
     L.awide = o;       if (with_codes) o += align_up(4 * n_frames * sbpf, 256);
+    L.akind1 = o;      if (with_codes) o += align_up(4 * n_frames, 256);           // k-ary reduce: flags of the second staging set
+    L.awide1 = o;      if (with_codes) o += align_up(4 * n_frames * sbpf, 256);
     L.total = o;
     return L;
 }
@@ -319,6 +321,7 @@ struct DecodeArgs {
     const float* local;                       // ring-step reduce only: the rank's own fp32 message
     float eb, inv_step;                       // ring-step reduce only: the quantizer's bound and 1/step
     uint32_t sr, seed;                        // ring-step reduce only: local data quantized stochastically, with this seed
+    uint32_t set_in;                          // k-ary reduce: the staging set that holds the running value (see k_decode)
     uint64_t n;
     uint32_t chunk, n_frames, K, dbpf, pred;
     float step; uint32_t step_bits;
@@ -332,8 +335,9 @@ hipError_t launch_stats_codes(const CompressArgs& A, hipStream_t st);   // reduc
 hipError_t launch_codebook(const CompressArgs& A, hipStream_t st);
 hipError_t launch_encode(const CompressArgs& A, bool from_codes, bool stochastic, hipStream_t st);
 hipError_t launch_qsgd_step(const float* in, uint64_t n, uint32_t levels, float* step_out, double* partials, hipStream_t st);
-hipError_t launch_decode(const DecodeArgs& A, int pass, hipStream_t st);   // 0 decompress, 1 / 2 reduce passes, 3 ring-step add
+hipError_t launch_decode(const DecodeArgs& A, int pass, hipStream_t st);   // 0 decompress, 1 / 2 reduce passes, 3-5 ring-step adds, 6 accumulate
 hipError_t launch_fix(const DecodeArgs& A, hipStream_t st);
+hipError_t launch_fix_acc(const DecodeArgs& A, hipStream_t st);   // k-ary reduce: after an accumulating pass
 hipError_t launch_decode_finish(const DecodeArgs& A, hipStream_t st);
 
 }  // namespace nz

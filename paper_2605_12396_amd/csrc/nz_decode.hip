@@ -447,13 +447,16 @@ struct DirectFetch {
 constexpr uint32_t kTile16Stride = kTile16R + 2;     // halfwords per row: 17 words, an odd word stride
 
 enum : int { MODE_DECOMPRESS = 0, MODE_STAGE_A = 1, MODE_ADD_B = 2, MODE_ADD_LOCAL = 3, MODE_ADD_LOCAL_SR = 4,
-             MODE_ADD_LOCAL_PLAIN = 5 };
+             MODE_ADD_LOCAL_PLAIN = 5, MODE_ACC = 6 };
 // the adding passes: ADD_B adds the staged codes of operand A, ADD_LOCAL the rank's own fp32 data, quantized on the fly
 // (ADD_LOCAL_SR: by the stochastic quantizer; ADD_LOCAL_PLAIN: without the statistics of the sums, for the sampled
 // arbitration, which profiles a prefix of the staged sums instead)
 #define NZ_LOCAL(M) ((M) == MODE_ADD_LOCAL || (M) == MODE_ADD_LOCAL_SR || (M) == MODE_ADD_LOCAL_PLAIN)
 #define NZ_STATS(M) ((M) == MODE_ADD_B || (M) == MODE_ADD_LOCAL || (M) == MODE_ADD_LOCAL_SR)
-#define NZ_ADDS(M) ((M) == MODE_ADD_B || NZ_LOCAL(M))
+#define NZ_ADDS(M) ((M) == MODE_ADD_B || (M) == MODE_ACC || NZ_LOCAL(M))
+// the passes whose other operand is the staged running value (operand A of the two-stream reduce); ACC, the
+// accumulating pass of the k-ary reduce, stages its sums in operand A's format again, without statistics
+#define NZ_STAGED(M) ((M) == MODE_ADD_B || (M) == MODE_ACC)
 
 // Shared memory of one decode workgroup.  The window comes first and the tile follows it directly: a reader's
 // prefetch may touch up to two rows past its window, which then fall into the tile (valid shared
@@ -502,6 +505,7 @@ __device__ inline uint32_t combine(uint32_t ta, bool a_raw, uint32_t tb, bool b_
 // that cannot be quantized counts as code 0 and raises lunq[h]: its frame becomes RAW and is redone by k_fix_local.
 struct AddCtx {
     StageA sa; uint32_t* codes; int16_t* c16; uint32_t* s_h; uint32_t* s_cwide; uint32_t* s_lunq;
+    StageA so; bool acc;       // accumulating pass of the k-ary reduce: the sums go to this staging set, in operand A's format
     const float* local; float eb, inv;
     bool sr; SrKeys keys;      // stochastic local quantizer: draws by element offset from the workgroup's block
     bool stats;                // the pass gathers the statistics of the sums
@@ -516,6 +520,13 @@ struct AddCtx {
             if (!okq) s_lunq[h] = 1u;
             ta = (uint32_t)q;
         } else ta = sa.get(C.f0, C.nf, i, a_raw);
+        if (acc) {
+            if (a_raw || b_raw) { so.a32[g] = combine<true>(ta, a_raw, tb, b_raw, step, overflow); return; }
+            uint32_t wide_seen = 0;
+            so.put_code(C.f0, C.nf, i, (int32_t)combine<false>(ta, false, tb, false, step, overflow), wide_seen);
+            if (wide_seen) s_cwide[h] = 1u;
+            return;
+        }
         if (a_raw || b_raw) { codes[g] = combine<true>(ta, a_raw, tb, b_raw, step, overflow); return; }
         const uint32_t t = combine<false>(ta, false, tb, false, step, overflow);
         const int32_t Q = (int32_t)t;
@@ -639,7 +650,7 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
             int16_t* dst = X.c16 + C.f0 + eo0 + r0;
             // the other operand is requested here rather than across the decode phase (no registers held, no spills);
             // the other workgroup of the CU covers the wait
-            if (MODE == MODE_ADD_B) {
+            if (NZ_STAGED(MODE)) {
                 // row rw0 + RPK k of this block, phase r0 / 32 (both halves are full here)
                 const int16_t* ap = X.sa.a16 + C.f0 + C.blk0 + (r0 / kTile16R) * (kHalf / 8u) + c;
 #pragma unroll
@@ -711,7 +722,7 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
                 const int32_t qhi = max(max(Q[0], Q[1]), max(Q[2], Q[3])), qlo = min(min(Q[0], Q[1]), min(Q[2], Q[3]));
                 uint32_t w0 = ((uint32_t)Q[0] & 0xFFFFu) | ((uint32_t)Q[1] << 16), w1 = ((uint32_t)Q[2] & 0xFFFFu) | ((uint32_t)Q[3] << 16);
                 if (__builtin_expect(qhi > 32767 || qlo <= kWideMarker, 0)) {
-                    uint32_t* c32 = X.codes + C.f0 + eo0 + r0 + (size_t)k * RPK * kSeg;
+                    uint32_t* c32 = (MODE == MODE_ACC ? X.so.a32 : X.codes) + C.f0 + eo0 + r0 + (size_t)k * RPK * kSeg;
                     uint32_t hw[4];
 #pragma unroll
                     for (uint32_t j = 0; j < 4; j++) {
@@ -724,6 +735,12 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
                 }
                 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
                 u32x2 v; v.x = w0; v.y = w1;
+                if (MODE == MODE_ACC) {
+                    // the running value keeps operand A's phase-major layout: the position the codes of A came from
+                    const uint32_t rw = rw0 + k * RPK;
+                    int16_t* ad = X.so.a16 + C.f0 + C.blk0 + (r0 / kTile16R) * (kHalf / 8u) + c + (size_t)(rw / kSeg) * kHalf + (rw % kSeg) * kTile16R;
+                    *reinterpret_cast<u32x2*>(ad) = v;
+                } else
                 __builtin_nontemporal_store(v, reinterpret_cast<u32x2*>(dst + (size_t)k * RPK * kSeg));   // streaming, as above
             }
         } else {
@@ -870,7 +887,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
     uint64_t total_a = 0, total_b = 0;
     const uint32_t st_a = check_stream(A.a, A.a_bytes, A, total_a);
     uint32_t st_b = ST_OK;
-    if (MODE == MODE_STAGE_A || MODE == MODE_ADD_B) st_b = check_stream(A.b, A.b_bytes, A, total_b);
+    if (MODE == MODE_STAGE_A || NZ_STAGED(MODE)) st_b = check_stream(A.b, A.b_bytes, A, total_b);
     // decompress: one verdict word per workgroup (status | kind << 8), summed up by k_decode_finish; nothing here
     // touches the result record.  The reduce passes report through the (pre-cleared) record with atomics.
     uint32_t* verdict = reinterpret_cast<uint32_t*>(A.ws + A.L.pmeta);
@@ -887,7 +904,7 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
     V.status = ST_OK; V.kind = KIND_ZERO; V.w = 0; V.words = nullptr; V.nwords = 0; V.segt = nullptr; V.seg_prefix = 0; V.dense = false;
     V.hot_esc = false;
     if (st_a == ST_OK && st_b == ST_OK) {
-        open_frame<NT>(MODE == MODE_ADD_B ? A.b : A.a, MODE == MODE_ADD_B ? total_b : total_a, frame, nf, first_seg, A,
+        open_frame<NT>(NZ_STAGED(MODE) ? A.b : A.a, NZ_STAGED(MODE) ? total_b : total_a, frame, nf, first_seg, A,
                        &s_t, &S.u.build, V);
         if (MODE != MODE_DECOMPRESS && tid == 0 && V.status) atomicMax(&res->status, V.status);
     }
@@ -917,23 +934,33 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
     uint32_t overflow = 0;
     uint32_t zmax[2] = { 0, 0 };
 
+    // Two staging sets in operand A's format: set 0 = (a16, a32, akind, awide), set 1 = the arrays of the sums (c16,
+    // codes) with flag arrays of its own.  The two-stream reduce only knows set 0.  In the k-ary reduce the running
+    // value alternates: the staging pass writes set A.set_in, an accumulating pass reads set A.set_in and writes the
+    // other one, and the last accumulating pass ends in set 0, where the statistics pass (ADD_B) reads operand A
+    // while it writes the sums in their own format to c16 / codes.
+    const uint32_t si = (MODE == MODE_STAGE_A || MODE == MODE_ACC) ? (A.set_in & 1u) : 0u;
     AddCtx X;
-    X.sa.a16 = reinterpret_cast<int16_t*>(A.ws + A.L.a16); X.sa.a32 = reinterpret_cast<uint32_t*>(A.ws + A.L.a32);
+    X.sa.a16 = reinterpret_cast<int16_t*>(A.ws + (si ? A.L.c16 : A.L.a16)); X.sa.a32 = reinterpret_cast<uint32_t*>(A.ws + (si ? A.L.codes : A.L.a32));
+    X.so.a16 = reinterpret_cast<int16_t*>(A.ws + (si ? A.L.a16 : A.L.c16)); X.so.a32 = reinterpret_cast<uint32_t*>(A.ws + (si ? A.L.a32 : A.L.codes));
+    X.acc = (MODE == MODE_ACC);
     X.codes = reinterpret_cast<uint32_t*>(A.ws + A.L.codes); X.c16 = reinterpret_cast<int16_t*>(A.ws + A.L.c16);
     X.s_cwide = S.cwide; X.s_lunq = S.lunq;
     X.local = NZ_LOCAL(MODE) ? A.local : nullptr; X.eb = A.eb; X.inv = A.inv_step;
     X.sr = (MODE == MODE_ADD_LOCAL_SR); X.stats = NZ_STATS(MODE);
     if (MODE == MODE_ADD_LOCAL_SR) X.keys.init(A.seed, f0 + blk0); else { X.keys.base_lo = 0; X.keys.key0 = 0; X.keys.key1 = 0; }
     X.s_h = s_h; X.K = A.K; X.step = A.step; X.ncs = 0; X.copy = 0; X.a_raw = false; X.b_raw = false;
-    uint32_t* akind = reinterpret_cast<uint32_t*>(A.ws + A.L.akind);   // per frame: operand A is RAW
-    uint32_t* awide = reinterpret_cast<uint32_t*>(A.ws + A.L.awide);   // per half: some code of A needs 32 bits
+    uint32_t* akind = reinterpret_cast<uint32_t*>(A.ws + (si ? A.L.akind1 : A.L.akind));   // per frame: operand A is RAW
+    uint32_t* awide = reinterpret_cast<uint32_t*>(A.ws + (si ? A.L.awide1 : A.L.awide));   // per half: some code of A needs 32 bits
+    uint32_t* akind_out = reinterpret_cast<uint32_t*>(A.ws + (si ? A.L.akind : A.L.akind1));   // (accumulating pass: the set it writes)
+    uint32_t* awide_out = reinterpret_cast<uint32_t*>(A.ws + (si ? A.L.awide : A.L.awide1));
     bool a_wide = false;
     if (NZ_ADDS(MODE)) {
         while ((A.K << (X.ncs + 1)) <= 1024u && X.ncs < 5) X.ncs++;
         X.copy = lane & ((1u << X.ncs) - 1u);
         if (NZ_STATS(MODE)) for (uint32_t i = tid; i < 2048u; i += NT) s_h[i] = 0;
         X.b_raw = V.kind == KIND_RAW;
-        if (MODE == MODE_ADD_B) {
+        if (NZ_STAGED(MODE)) {
             X.a_raw = akind[frame] != 0;
             for (uint32_t h = 0; h < NT * kSeg / kHalf; h++)
                 if (blk0 + h * kHalf < nf) a_wide = a_wide || (awide[(size_t)frame * hpf + blk0 / kHalf + h] != 0);
@@ -980,6 +1007,20 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
     }
     __syncthreads();
     const bool out_raw = X.a_raw || X.b_raw;                            // uniform over the frame
+    if (MODE == MODE_ACC) {
+        // the running value's flags, in the set just written; the range flag goes where k_fix_acc looks for it
+        if (tid == 0) {
+            for (uint32_t h = 0; h < NT * kSeg / kHalf; h++) {
+                if (blk0 + h * kHalf >= nf) break;
+                const size_t hb = (size_t)frame * hpf + blk0 / kHalf + h;
+                awide_out[hb] = S.cwide[h] ? 1u : 0u;
+                reinterpret_cast<uint2*>(A.ws + A.L.pmeta)[hb] = make_uint2(0u, out_raw ? 1u : 0u);
+                reinterpret_cast<uint32_t*>(A.ws + A.L.cwide)[hb] = S.ovf ? 2u : 0u;
+            }
+            if (db == 0) akind_out[frame] = out_raw ? 1u : 0u;
+        }
+        return;
+    }
     for (uint32_t h = 0; h < NT * kSeg / kHalf; h++) {
         if (blk0 + h * kHalf >= nf) break;
         const size_t hb = (size_t)frame * hpf + blk0 / kHalf + h;
@@ -1053,6 +1094,43 @@ __global__ __launch_bounds__(256) void k_fix(DecodeArgs A) {
         }
         codes[i] = combine<true>(ta, raw != 0, tb, b_is_raw, A.step, dummy);
     }
+}
+
+// After an accumulating pass of the k-ary reduce: a frame in which a partial sum passed 2^30 in magnitude leaves the
+// integer domain at this operand.  Its running value becomes fp32 -- fl(fl(v*step) + fl(q*step)) with v the running
+// code before this operand (still in the set the pass read) and q the operand's code, recovered as the staged sum
+// minus v -- and the frame counts as RAW for the operands that follow.  One workgroup per half; rare.
+__global__ __launch_bounds__(256) void k_fix_acc(DecodeArgs A) {
+    const uint32_t tid = threadIdx.x;
+    const uint32_t hpf = (A.chunk + kHalf - 1) / kHalf;
+    const uint32_t frame = blockIdx.x / hpf, h = blockIdx.x % hpf;
+    const uint64_t f0 = (uint64_t)frame * A.chunk;
+    const uint32_t nf = (uint32_t)((A.n - f0 < A.chunk) ? (A.n - f0) : A.chunk);
+    const uint32_t h0 = h * kHalf;
+    if (h0 >= nf) return;
+    const uint32_t cnt = (nf - h0 < kHalf) ? (nf - h0) : kHalf;
+    const uint2* pm = reinterpret_cast<const uint2*>(A.ws + A.L.pmeta) + (size_t)frame * hpf;
+    const uint32_t* cw = reinterpret_cast<const uint32_t*>(A.ws + A.L.cwide) + (size_t)frame * hpf;
+    uint32_t ovf = 0, raw = 0;
+    for (uint32_t j = 0; j < hpf && j * kHalf < nf; j++) { raw |= pm[j].y & 1u; ovf |= cw[j] & 2u; }
+    if (raw || !ovf) return;                  // (a frame that was fp32 already has no integer sums to go out of range)
+    const uint32_t si = A.set_in & 1u;
+    StageA sa, so;
+    sa.a16 = reinterpret_cast<int16_t*>(A.ws + (si ? A.L.c16 : A.L.a16)); sa.a32 = reinterpret_cast<uint32_t*>(A.ws + (si ? A.L.codes : A.L.a32));
+    so.a16 = reinterpret_cast<int16_t*>(A.ws + (si ? A.L.a16 : A.L.c16)); so.a32 = reinterpret_cast<uint32_t*>(A.ws + (si ? A.L.a32 : A.L.codes));
+    uint32_t dummy = 0;
+    for (uint32_t i = tid; i < cnt; i += 256) {
+        const uint32_t ta = sa.get(f0, nf, h0 + i, false);
+        const uint32_t tb = so.get(f0, nf, h0 + i, false) - ta;
+        so.a32[f0 + h0 + i] = combine<true>(ta, false, tb, false, A.step, dummy);
+    }
+    if (h == 0 && tid == 0) reinterpret_cast<uint32_t*>(A.ws + (si ? A.L.akind : A.L.akind1))[frame] = 1u;
+}
+
+hipError_t launch_fix_acc(const DecodeArgs& A, hipStream_t st) {
+    const uint32_t hpf = (A.chunk + kHalf - 1) / kHalf;
+    hipLaunchKernelGGL(k_fix_acc, dim3(A.n_frames * hpf), dim3(256), 0, st, A);
+    return hipGetLastError();
 }
 
 hipError_t launch_fix(const DecodeArgs& A, hipStream_t st) {
@@ -1139,6 +1217,9 @@ static void launch_decode_t(DecodeArgs& D, const DecodeArgs& A, int pass, hipStr
     } else if (pass == 3) {
         D.dbpf = (A.chunk + kAddThreads * kSeg - 1) / (kAddThreads * kSeg);
         hipLaunchKernelGGL((k_decode<MODE_ADD_LOCAL, kAddThreads, DELTA>), dim3(D.n_frames * D.dbpf), dim3(kAddThreads), 0, st, D);
+    } else if (pass == 6) {
+        D.dbpf = (A.chunk + kAddThreads * kSeg - 1) / (kAddThreads * kSeg);
+        hipLaunchKernelGGL((k_decode<MODE_ACC, kAddThreads, DELTA>), dim3(D.n_frames * D.dbpf), dim3(kAddThreads), 0, st, D);
     } else if constexpr (DELTA == 0) {          // (the stochastic and the sampled ring step are not built with the predictor)
         D.dbpf = (A.chunk + kAddThreads * kSeg - 1) / (kAddThreads * kSeg);
         if (pass == 4) hipLaunchKernelGGL((k_decode<MODE_ADD_LOCAL_SR, kAddThreads, 0>), dim3(D.n_frames * D.dbpf), dim3(kAddThreads), 0, st, D);
