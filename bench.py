@@ -367,6 +367,25 @@ def run_c4_ring(args):
         runs = [chain(local) for _ in range(reps)]
         steps_ms = [min(r[0][i] for r in runs) for i in range(peers - 1)]
         best[local] = (steps_ms, runs[0][1])
+    # all eight contributions at once: every operand decoded once, the sum encoded once (nz_reduce_k); the result is
+    # the chain's final stream byte for byte
+    kout = sess.new_stream_buffer()
+    def kary():
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record()
+        rc, _ = sess.reduce_k(streams, sizes, n, eb, out=kout)
+        ev1.record()
+        r = sess.result()
+        assert rc == 0 and r["status"] == 0
+        return ev0.elapsed_time(ev1), r["bytes"]
+    kary()
+    k_ms, k_bytes = min(kary() for _ in range(reps))
+    with nz.KernelTrace(16) as tr:
+        sess.reduce_k(streams, sizes, n, eb, out=kout)
+        k_kernels = tr.kernel_ms()
+    chain_ms, chain_bytes = chain(False)
+    final = bufs[(peers - 1) % 2]
+    k_equal = bool(k_bytes == chain_bytes and torch.equal(kout[:k_bytes], final[:chain_bytes]))
     gb = 4.0 * n / 1e9
     print(json.dumps(dict(metric="fused reduce ring step, GB/s of fp32 input per step (config 4)", unit="GB/s", n_gpus=1,
                           data="synthetic",
@@ -377,6 +396,10 @@ def run_c4_ring(args):
                                              GBps=gb * (peers - 1) / (sum(best[False][0]) * 1e-3)),
                           reduce_local=dict(per_step_ms=best[True][0], total_ms=sum(best[True][0]),
                                             GBps=gb * (peers - 1) / (sum(best[True][0]) * 1e-3)),
+                          reduce_k=dict(total_ms=k_ms, GBps=gb * peers / (k_ms * 1e-3),
+                                        kernel_ms=dict(zip(["init", "stage_0"] + ["acc_%d" % p for p in range(1, peers - 1)] +
+                                                           ["add_last", "fix", "codebook", "encode"], k_kernels)),
+                                        stream_equals_chain=k_equal),
                           final_bytes_equal=bool(best[False][1] == best[True][1]))))
 
 
