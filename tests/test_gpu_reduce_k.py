@@ -154,3 +154,32 @@ def test_refusals(nz):
     ref, ores, orc = oracle.reduce_k([ss[p % 3] for p in range(64)], n, eb, o)
     assert rc == 0 and orc == 0 and r["status"] == 0 and np.array_equal(got, ref)
     torch.cuda.synchronize()
+
+
+def test_c4_full_size(nz):
+    """Config 4 as bench.py runs it: eight peers of 32 Mi elements (eb = 1e-5, 1 MiB frames) reduced at once; the
+    GPU compresses the peers (compress parity at this shape is covered elsewhere, and checked here for the first
+    peer), the oracle reduces the same eight streams, whole message."""
+    import torch
+    n, eb, peers = 1 << 25, 1e-5, 8
+    g, o = nz.make_opts(chunk_elems=262144), oracle.make_opts(chunk_elems=262144)
+    sess = nz.Session(n, g, "cuda:0", reduce=True)
+    host, dev, sizes = [], [], []
+    for p in range(peers):
+        x = W.gradient_like(n, seed=40 + p, outlier_frac=0.0)
+        rc, out = sess.compress(torch.from_numpy(x).to("cuda:0"), eb)
+        r = sess.result()
+        assert rc == 0 and r["status"] == 0
+        s = out[:r["bytes"]].cpu().numpy()
+        if p == 0:
+            assert np.array_equal(s, oracle.compress(x, eb, o)[0])
+        host.append(s); dev.append(out); sizes.append(r["bytes"])
+        del x
+    rc, red = sess.reduce_k(dev, sizes, n, eb)
+    rr = sess.result()
+    ref, ores, orc = oracle.reduce_k(host, n, eb, o)
+    assert rc == 0 and orc == 0 and rr["status"] == 0 and rr["bytes"] == ores.bytes
+    assert (rr["n_raw"], rr["n_fixed"], rr["n_huff"]) == (ores.n_raw, ores.n_fixed, ores.n_huff)
+    got = red[:rr["bytes"]].cpu().numpy()
+    d = np.nonzero(got != ref)[0]
+    assert d.size == 0, "first differing byte %d" % int(d[0])
