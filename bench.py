@@ -439,6 +439,7 @@ def main():
     ap.add_argument("--workload", default="c2", help="c2 (headline) | c1 | c4 | c3 | c4ring | c5 | pred")
     ap.add_argument("--alphabet", type=int, default=256, help="Huffman alphabet K (power of two, 2..1024)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true", help="also time the step replayed from a HIP graph (reported beside ms_per_step)")
     ap.add_argument("--rotate", type=int, default=3, help="number of distinct input / stream copies cycled through")
     ap.add_argument("--only", default="", help="profiling aid: time only this stage (compress|decompress|reduce|compress_rea)")
     ap.add_argument("--calib-copy", type=int, default=0,
@@ -538,6 +539,24 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    # the same step replayed from a HIP graph (launch-bound small messages): one capture of step 0, `steps` replays
+    graph_ms = None
+    if args.graph and not args.only:
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            graph.capture_begin()
+            step(0)
+            graph.capture_end()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        tg0 = time.perf_counter()
+        for i in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - tg0) * 1e3 / args.steps
     if args.only:
         print(json.dumps(dict(only=args.only, ms_per_step=ms_per_step, GBps=4.0 * n / 1e9 / (ms_per_step * 1e-3))))
         return
@@ -644,7 +663,7 @@ def main():
                        traffic_over_algorithmic=(traffic / alg_op[st] if traffic else None))
 
     out = dict(metric="compress / decompress / fused-reduce GB/s (fp32 input): bytes of the three stages over the step time", value=3 * gb / (ms_per_step * 1e-3),
-               unit="GB/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step,
+               unit="GB/s", n_gpus=1, steps=args.steps, warmup=args.warmup, ms_per_step=ms_per_step, graph_ms_per_step=graph_ms,
                higher_is_better=True, scaling="weak", vs_baseline=None, dtype="f32+i32", data="synthetic",
                config=dict(workload=wl["desc"], n_elems=n, chunk_elems=wl["chunk"], alphabet=args.alphabet, eb=eb,
                            rotate=R),
