@@ -88,6 +88,7 @@ def lib():
         L.nzo_reduce_frames.argtypes = [vp, sz, vp, sz, vp, sz, sz, f32, C.POINTER(Opts), C.POINTER(Result)]
         L.nzo_reduce_local.argtypes = [vp, sz, vp, vp, sz, sz, f32, C.POINTER(Opts), C.POINTER(Result)]
         L.nzo_reduce_k.argtypes = [vp, vp, C.c_uint32, vp, sz, sz, f32, C.POINTER(Opts), C.POINTER(Result)]
+        L.nzo_reduce_k_step.argtypes = [vp, vp, C.c_uint32, vp, sz, sz, f32, C.POINTER(Opts), C.POINTER(Result)]
         L.nzo_frame_plan.argtypes = [vp, C.c_uint32, C.c_int, C.POINTER(Opts), vp, vp, vp, vp, vp, vp, vp]
         L.nzo_frame_encode.argtypes = [vp, vp, C.c_uint32, C.c_int, C.POINTER(Opts), C.c_uint32, vp, sz]
         L.nzo_frame_encode.restype = C.c_int64
@@ -210,8 +211,9 @@ def reduce_frames(a, b, n, eb, opts=None, cap=None):
     return out[:res.bytes].copy(), res, rc
 
 
-def reduce_k(streams, n, eb, opts=None, cap=None):
-    """k-ary reduce: one output stream from the operand streams, taken in the order given."""
+def reduce_k(streams, n, eb, opts=None, cap=None, step=None):
+    """k-ary reduce: one output stream from the operand streams, taken in the order given (step: the bin width of
+    streams made by the stochastic quantizer, in the place of the error bound)."""
     arrs = [np.ascontiguousarray(s, dtype=np.uint8) for s in streams]
     k = len(arrs)
     ptrs = (C.c_void_p * max(k, 1))(*[a.ctypes.data for a in arrs])
@@ -220,8 +222,9 @@ def reduce_k(streams, n, eb, opts=None, cap=None):
         cap = compress_bound(n, opts)
     out = np.zeros(max(cap, 1), np.uint8)
     res = Result()
-    rc = lib().nzo_reduce_k(ptrs, sizes, k, _ptr(out), cap, n, C.c_float(eb),
-                            C.byref(opts) if opts is not None else None, C.byref(res))
+    fn = lib().nzo_reduce_k if step is None else lib().nzo_reduce_k_step
+    rc = fn(ptrs, sizes, k, _ptr(out), cap, n, C.c_float(eb if step is None else step),
+            C.byref(opts) if opts is not None else None, C.byref(res))
     return out[:res.bytes].copy(), res, rc
 
 

@@ -934,15 +934,15 @@ static int acc_src(void* vctx, uint32_t k, uint64_t i0, uint32_t nf, int32_t* q,
  * chain's intermediate streams keep integer sums as codes (no pinned RAW, no gate that turns such a frame RAW on the
  * way: those options then apply to the final stream only).
  */
-int nzo_reduce_k(const uint8_t* const* streams, const size_t* bytes, uint32_t k, uint8_t* out, size_t cap,
-                 size_t n, float eb, const nzo_opts* opts, nzo_result* res) {
-    nzo_opts o; float step, inv;
+int nzo_reduce_k_step(const uint8_t* const* streams, const size_t* bytes, uint32_t k, uint8_t* out, size_t cap,
+                      size_t n, float step, const nzo_opts* opts, nzo_result* res) {
+    nzo_opts o;
     nzo_result dummy;
     if (!res) res = &dummy;
     memset(res, 0, sizeof *res);
     if (n == 0 || !streams || !bytes || !out || k < 2 || k > NZO_MAX_OPERANDS) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
     for (uint32_t p = 0; p < k; p++) if (!streams[p]) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
-    if (resolve_opts(opts, &o) || nzo_step_constants(eb, &step, &inv)) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
+    if (resolve_opts(opts, &o) || !step_ok(step)) { res->status = NZO_ERR_INVALID; return NZO_ERR_INVALID; }
     int rc = NZO_OK;
     uint32_t n_frames = 0;
     for (uint32_t p = 0; p < k && !rc; p++) {
@@ -957,9 +957,9 @@ int nzo_reduce_k(const uint8_t* const* streams, const size_t* bytes, uint32_t k,
     uint32_t* rs = (uint32_t*)malloc(4ull * n); uint32_t* rp = (uint32_t*)malloc(4ull * n);
     uint8_t* fs = (uint8_t*)calloc(n_frames, 1); uint8_t* fp = (uint8_t*)calloc(n_frames, 1);
     if (!qs || !qp || !rs || !rp || !fs || !fp) rc = NZO_ERR_INVALID;
-    if (!rc) rc = nzo_decode_codes(streams[0], bytes[0], n, eb, qs, rs, fs, NULL);      /* the running value starts as s_0 */
+    if (!rc) rc = nzo_decode_codes_step(streams[0], bytes[0], n, step, qs, rs, fs, NULL);   /* the running value starts as s_0 */
     for (uint32_t p = 1; p < k && !rc; p++) {
-        rc = nzo_decode_codes(streams[p], bytes[p], n, eb, qp, rp, fp, NULL);
+        rc = nzo_decode_codes_step(streams[p], bytes[p], n, step, qp, rp, fp, NULL);
         if (rc) break;
         for (uint32_t f = 0; f < n_frames; f++) {
             const uint64_t i0 = (uint64_t)f * o.chunk_elems;
@@ -996,6 +996,13 @@ int nzo_reduce_k(const uint8_t* const* streams, const size_t* bytes, uint32_t k,
     }
     free(qs); free(qp); free(rs); free(rp); free(fs); free(fp);
     return rc;
+}
+
+int nzo_reduce_k(const uint8_t* const* streams, const size_t* bytes, uint32_t k, uint8_t* out, size_t cap,
+                 size_t n, float eb, const nzo_opts* opts, nzo_result* res) {
+    float step, inv;
+    if (nzo_step_constants(eb, &step, &inv)) { if (res) { memset(res, 0, sizeof *res); res->status = NZO_ERR_INVALID; } return NZO_ERR_INVALID; }
+    return nzo_reduce_k_step(streams, bytes, k, out, cap, n, step, opts, res);
 }
 
 /* ------------------------------------------------------------------ */

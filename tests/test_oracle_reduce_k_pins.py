@@ -178,3 +178,23 @@ def test_refusals():
     r2, res2, rc2 = oracle.reduce_k(ss, n, eb, opts, cap=r.size - 1)
     assert rc2 == oracle.ERR_CAPACITY and res2.bytes == 0
     assert np.array_equal(oracle.reduce_k(ss, n, eb, opts, cap=r.size)[0], r)
+
+
+def test_streams_of_the_stochastic_quantizer_reduce_by_their_bin_width():
+    # the *_step form is the same fold on streams that record a width instead of a bound: the chain of the pinned
+    # two-operand *_step reduce byte for byte, and the sum of the drawn codes
+    n = 5000
+    opts = oracle.make_opts(chunk_elems=1024)
+    xs = [W.gradient_like(n, seed=350 + p) for p in range(4)]
+    step = float(np.float32(max(oracle.qsgd_step(x, 100) for x in xs)))
+    ss = [oracle.compress_sr(x, step, 10 + p, opts)[0] for p, x in enumerate(xs)]
+    r, res, rc = oracle.reduce_k(ss, n, None, opts, step=step)
+    assert rc == 0
+    acc = ss[0]
+    for s2 in ss[1:]:
+        acc = oracle.reduce_frames_step(acc, s2, n, step, opts)[0]
+    assert np.array_equal(r, acc)
+    q = sum(oracle.sr_quantize(x, step, 10 + p)[0].astype(np.int64) for p, x in enumerate(xs))
+    assert (oracle.decode_codes_step(r, n, step)[0] == q).all()
+    assert oracle.reduce_k(ss, n, None, opts, step=step * 2)[2] == oracle.ERR_MISMATCH
+    assert oracle.reduce_k(ss, n, None, opts, step=float("nan"))[2] == oracle.ERR_INVALID
