@@ -193,7 +193,8 @@ nz_status nz_reduce_local_rea(const void* d_in, size_t in_bytes, const float* d_
  * Element i of the message draws from a counter-based generator keyed by (seed, i) -- the 32-bit finalizer of
  * MurmurHash3, top 24 bits -- so the result does not depend on how the work is scheduled.  Statistics, selector
  * and frames are those of nz_compress; the stream records `step`, and its receivers are the *_step forms below
- * (nz_decompress / nz_reduce_frames derive the width from an error bound, which such a stream does not have).
+ * (nz_decompress / nz_reduce_frames / nz_reduce_k derive the width from an error bound, which such a stream does
+ * not have).
  * nz_qsgd_step writes QSGD's width for `levels` levels per sign, ||x||_2 / levels (at least 2^-100; NaN if the
  * message is not finite), to the device float *d_step; d_ws: at least 8192 bytes of device scratch.  Ranks that
  * reduce their streams must agree on one width (e.g. the largest).
@@ -206,6 +207,8 @@ nz_status nz_decompress_step(const void* d_stream, size_t stream_bytes, float* d
 nz_status nz_reduce_frames_step(const void* d_a, size_t a_bytes, const void* d_b, size_t b_bytes, void* d_out,
                                 size_t out_cap, size_t n, float step, nz_result* d_res, const nz_opts* opts,
                                 void* d_ws, size_t ws_bytes, void* stream);
+nz_status nz_reduce_k_step(const void* const* d_streams, const size_t* stream_bytes, uint32_t k, void* d_out, size_t out_cap,
+                           size_t n, float step, nz_result* d_res, const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream);
 /* The ring step of such a collective (Sec. IV-D, receive-reduce-send): nz_reduce_local with the stochastic quantizer
  * on the rank's own data, element i drawing from (seed, i); byte-identical to
  * nz_reduce_frames_step(d_in, nz_compress_sr(d_local, step, seed)).  opts.predictor must be 0. */

@@ -84,6 +84,8 @@ def lib():
         L.nz_reduce_frames.restype = C.c_int
         L.nz_reduce_k.argtypes = [vp, vp, C.c_uint32, vp, sz, sz, f32, vp, po, vp, sz, vp]
         L.nz_reduce_k.restype = C.c_int
+        L.nz_reduce_k_step.argtypes = [vp, vp, C.c_uint32, vp, sz, sz, f32, vp, po, vp, sz, vp]
+        L.nz_reduce_k_step.restype = C.c_int
         L.nz_reduce_local.argtypes = [vp, sz, vp, vp, sz, sz, f32, vp, po, vp, sz, vp]
         L.nz_reduce_local_sr.argtypes = [vp, sz, vp, vp, sz, sz, f32, C.c_uint32, vp, po, vp, sz, vp]
         L.nz_reduce_local_sr.restype = C.c_int
@@ -202,13 +204,21 @@ def nz_reduce_frames(d_a, a_bytes, d_b, b_bytes, d_out, out_cap, n, eb, d_res, o
                                       _stream(stream)))
 
 
-def nz_reduce_k(d_streams, stream_bytes, d_out, out_cap, n, eb, d_res, opts, d_ws, ws_bytes, stream=None):
-    """d_streams: sequence of device tensors, stream_bytes: their sizes (host arrays of pointers / sizes are built here)."""
+def _reduce_k(fn, d_streams, stream_bytes, d_out, out_cap, n, width, d_res, opts, d_ws, ws_bytes, stream):
     k = len(d_streams)
     ptrs = (C.c_void_p * max(k, 1))(*[t.data_ptr() for t in d_streams])
     sizes = (C.c_size_t * max(k, 1))(*[int(b) for b in stream_bytes])
-    return int(lib().nz_reduce_k(ptrs, sizes, k, d_out.data_ptr(), out_cap, n, C.c_float(eb), d_res.data_ptr(), _po(opts),
-                                 d_ws.data_ptr(), ws_bytes, _stream(stream)))
+    return int(fn(ptrs, sizes, k, d_out.data_ptr(), out_cap, n, C.c_float(width), d_res.data_ptr(), _po(opts),
+                  d_ws.data_ptr(), ws_bytes, _stream(stream)))
+
+
+def nz_reduce_k(d_streams, stream_bytes, d_out, out_cap, n, eb, d_res, opts, d_ws, ws_bytes, stream=None):
+    """d_streams: sequence of device tensors, stream_bytes: their sizes (host arrays of pointers / sizes are built here)."""
+    return _reduce_k(lib().nz_reduce_k, d_streams, stream_bytes, d_out, out_cap, n, eb, d_res, opts, d_ws, ws_bytes, stream)
+
+
+def nz_reduce_k_step(d_streams, stream_bytes, d_out, out_cap, n, step, d_res, opts, d_ws, ws_bytes, stream=None):
+    return _reduce_k(lib().nz_reduce_k_step, d_streams, stream_bytes, d_out, out_cap, n, step, d_res, opts, d_ws, ws_bytes, stream)
 
 
 def nz_reduce_local(d_in, in_bytes, d_local, d_out, out_cap, n, eb, d_res, opts, d_ws, ws_bytes, stream=None):

@@ -406,6 +406,13 @@ nz_status nz_reduce_k(const void* const* d_streams, const size_t* stream_bytes, 
     return reduce_impl(d_streams, stream_bytes, k, nullptr, d_out, out_cap, n, eb, step, inv, d_res, opts, d_ws, ws_bytes, stream);
 }
 
+nz_status nz_reduce_k_step(const void* const* d_streams, const size_t* stream_bytes, uint32_t k, void* d_out, size_t out_cap,
+                           size_t n, float step, nz_result* d_res, const nz_opts* opts, void* d_ws, size_t ws_bytes, void* stream) {
+    float inv;
+    if (k < 2 || !step_given(step, inv)) return NZ_ERR_INVALID;
+    return reduce_impl(d_streams, stream_bytes, k, nullptr, d_out, out_cap, n, 0.0f, step, inv, d_res, opts, d_ws, ws_bytes, stream);
+}
+
 nz_status nz_reduce_local(const void* d_in, size_t in_bytes, const float* d_local, void* d_out, size_t out_cap,
                           size_t n, float eb, nz_result* d_res, const nz_opts* opts, void* d_ws, size_t ws_bytes,
                           void* stream) {

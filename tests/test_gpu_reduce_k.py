@@ -183,3 +183,22 @@ def test_c4_full_size(nz):
     got = red[:rr["bytes"]].cpu().numpy()
     d = np.nonzero(got != ref)[0]
     assert d.size == 0, "first differing byte %d" % int(d[0])
+
+
+def test_streams_of_the_stochastic_quantizer(nz):
+    n, chunk = 200000, 65536
+    g, o = nz.make_opts(chunk_elems=chunk), oracle.make_opts(chunk_elems=chunk)
+    xs = [W.gradient_like(n, seed=470 + p) for p in range(5)]
+    step = float(np.float32(max(oracle.qsgd_step(x, 200) for x in xs)))
+    ss = [oracle.compress_sr(x, step, 20 + p, o)[0] for p, x in enumerate(xs)]
+    ref, ores, orc = oracle.reduce_k(ss, n, None, o, step=step)
+    sess = nz.Session(n, g, "cuda:0", reduce=True)
+    ds = [_dev(np.concatenate([s, np.zeros((-s.size) % 16, np.uint8)])) for s in ss]
+    out = sess.new_stream_buffer()
+    rc = nz.nz_reduce_k_step(ds, [s.size for s in ss], out, sess.cap, n, step, sess.res, g, sess.ws, sess.ws_bytes)
+    r = sess.result()
+    assert rc == 0 and orc == 0 and r["status"] == 0 and r["bytes"] == ores.bytes
+    assert np.array_equal(out[:r["bytes"]].cpu().numpy(), ref)
+    assert nz.nz_reduce_k_step(ds, [s.size for s in ss], out, sess.cap, n, step * 2, sess.res, g, sess.ws, sess.ws_bytes) == 0
+    assert sess.result()["status"] == nz.ERR_MISMATCH
+    assert nz.nz_reduce_k_step(ds, [s.size for s in ss], out, sess.cap, n, float("nan"), sess.res, g, sess.ws, sess.ws_bytes) == nz.ERR_INVALID
