@@ -176,6 +176,24 @@ struct BookShared {
     uint32_t m, nsym;
 };
 
+// Value of lane (lane ^ d), d a power of two (compile-time after unrolling); up = (lane & d) != 0.  Distances inside a row
+// of 16 lanes go over the DPP network (quad permutes, or the row shifted both ways), the others through the LDS crossbar.
+__device__ inline uint32_t lane_xor(uint32_t v, uint32_t d, bool up) {
+    if (d == 1) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true);    // quad_perm [1,0,3,2]
+    if (d == 2) return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true);    // quad_perm [2,3,0,1]
+    if (d == 4) {
+        const uint32_t below = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x114, 0xF, 0xF, true);   // row_shr:4 = lane - 4
+        const uint32_t above = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x104, 0xF, 0xF, true);   // row_shl:4 = lane + 4
+        return up ? below : above;
+    }
+    if (d == 8) {
+        const uint32_t below = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x118, 0xF, 0xF, true);
+        const uint32_t above = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x108, 0xF, 0xF, true);
+        return up ? below : above;
+    }
+    return (uint32_t)__shfl_xor((int)v, (int)d, 64);
+}
+
 // Optimal prefix-code lengths and canonical codes for the counts f (one per thread = symbol; 0 = unused) of an
 // alphabet of K symbols.  Called by all kBookThreads threads of the workgroup.  On return B.len[] holds the lengths,
 // B.nsym = 1 + largest used symbol, and (L, code) are the calling thread's symbol's length and canonical code.
@@ -189,20 +207,33 @@ __device__ inline void book_build(BookShared& B, uint32_t f, uint32_t K, uint32_
         const uint64_t um = __ballot(used);
         if (lane == 0 && um) { atomicAdd(&B.m, (uint32_t)__popcll(um)); atomicMax(&B.nsym, wave * 64 + 64 - (uint32_t)__clzll(um)); }
     }
-    // (2) sort used symbols ascending by (count, symbol): rank = number of smaller keys
+    // (2) sort used symbols ascending by (count, symbol): rank = number of smaller keys, counted by several threads
+    // per symbol over disjoint parts of the key array (the workgroup has more threads than a small alphabet has symbols)
     const uint32_t key = used ? ((f << 10) | tid) : 0xFFFFFFFFu;
     B.key[tid] = key;
+    B.w[tid] = 0;                                             // rank accumulators (the queues are set up later)
     __syncthreads();
     const uint32_t m = B.m;
-    if (used) {
-        uint32_t rank = 0;
-        const uint4* k4 = reinterpret_cast<const uint4*>(B.key);
-        for (uint32_t j = 0; j < K / 4 || j < 1; j++) {
-            const uint4 t = k4[j];
-            rank += (t.x < key) + (t.y < key) + (t.z < key) + (t.w < key);
+    {
+        const uint32_t parts = (kBookThreads / K) < 16u ? (kBookThreads / K) : 16u;   // K is a power of two <= kBookThreads
+        const uint32_t sy = tid & (K - 1u), part = tid / K;
+        const uint32_t ks = B.key[sy];
+        if (part < parts && ks != 0xFFFFFFFFu) {
+            const uint32_t nch = K >= 4u ? K / 4u : 1u;       // (keys past K are sentinels)
+            const uint32_t per = (nch + parts - 1u) / parts;
+            const uint32_t j0 = part * per, j1 = (j0 + per < nch) ? j0 + per : nch;
+            const uint4* k4 = reinterpret_cast<const uint4*>(B.key);
+            uint32_t cnt = 0;
+#pragma unroll 8
+            for (uint32_t j = j0; j < j1; j++) {
+                const uint4 t = k4[j];
+                cnt += (t.x < ks) + (t.y < ks) + (t.z < ks) + (t.w < ks);
+            }
+            if (cnt) atomicAdd(&B.w[sy], cnt);
         }
-        B.sorted[rank] = key;
     }
+    __syncthreads();
+    if (used) B.sorted[B.w[tid]] = key;
     __syncthreads();
     // leaves in order, followed by sentinels; the internal-node queue starts out all sentinels
     constexpr uint32_t INF = 0xFFFFFFFFu;
@@ -214,49 +245,59 @@ __device__ inline void book_build(BookShared& B, uint32_t f, uint32_t K, uint32_
     s_int[tid] = INF;
     __syncthreads();
 
-    // (3) two-queue merge by wave 0, a run of steps at a time.  The merge alternates between runs of
-    // leaf + leaf steps, runs of node + node steps and single leaf + node steps.  During a leaf + leaf run the
-    // head of the node queue does not change (new nodes join its tail), so the run goes on exactly while the
-    // second leaf of the next pair is <= that head: lane j tests pair j and all pairs that pass are merged at
-    // once.  A node + node run goes on while the second node of the next pair exists and is < the leaf head; only
-    // nodes that existed when the round began are paired, the rest follows in the next round.  The result is the
-    // sequential construction step for step (a leaf wins a tie), in far fewer dependent rounds.
+    // (3) two-queue merge by wave 0, many steps per round.  The sequential construction picks, step after step, the two
+    // smallest items of the leaf queue and the node queue (a leaf wins a weight tie against a node, nodes leave in the
+    // order they were made) and appends their sum to the node queue.  New nodes never weigh less than older ones, so the
+    // picks of the steps to come are simply the merged order of the remaining leaves and the nodes that exist now, up to
+    // the point where the first node made in this round (weight T = the sum of the first pair) would be picked: that is,
+    // all existing nodes and all leaves of weight <= T.  A round therefore merges a window of 64 leaves and 64 nodes --
+    // packed keys weight << 11 | kind << 10 | index order exactly like the picks; an item counts only if no item
+    // outside the window could precede it -- with a bitonic network over the wavefront, pairs consecutive items, and
+    // lets lane j make node j of the round.  The first pair always qualifies, so every round makes progress; the result
+    // is the sequential construction step for step, in a number of rounds that grows with the logarithm of the weight
+    // range instead of the number of alternations between the queues.
     if (wave == 0 && m >= 2) {
         uint32_t ia = 0, ib = 0, nint = 0;                    // heads: leaf ia, internal node ib; nodes created
         while (nint + 1 < m) {
-            const uint32_t la = s_w[ia + 2 * lane], lb = s_w[ia + 2 * lane + 1];       // leaf pair `lane`
-            const uint32_t na = s_int[ib + 2 * lane], nb = s_int[ib + 2 * lane + 1];   // node pair `lane` (INF: not created)
-            const uint32_t a0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)la), a1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)lb);
-            const uint32_t b0 = (uint32_t)__builtin_amdgcn_readfirstlane((int)na), b1 = (uint32_t)__builtin_amdgcn_readfirstlane((int)nb);
             const uint32_t left = m - 1 - nint;               // nodes still to be made
-            if (a0 <= b0 && a1 <= b0) {                       // leaf + leaf
-                uint32_t L = 1;                               // empty node queue: the first new node becomes its head
-                if (b0 != INF) { const uint64_t ok = __ballot(lb <= b0); L = (~ok) ? (uint32_t)__builtin_ctzll(~ok) : 64u; }
-                L = L < left ? L : left;
-                if (lane < L) {
-                    const uint16_t node = (uint16_t)(m + nint + lane);
-                    s_int[nint + lane] = la + lb;
-                    s_par[ia + 2 * lane] = node; s_par[ia + 2 * lane + 1] = node;
-                }
-                ia += 2 * L; nint += L;
-            } else if (a0 > b0 && a0 > b1) {                  // node + node
-                const uint64_t ok = __ballot(a0 > nb);        // false where the pair's second node does not exist yet
-                uint32_t L = (~ok) ? (uint32_t)__builtin_ctzll(~ok) : 64u;
-                L = L < left ? L : left;
-                if (lane < L) {
-                    const uint16_t node = (uint16_t)(m + nint + lane);
-                    s_int[nint + lane] = na + nb;
-                    s_par[m + ib + 2 * lane] = node; s_par[m + ib + 2 * lane + 1] = node;
-                }
-                ib += 2 * L; nint += L;
-            } else {                                          // leaf + node
-                if (lane == 0) {
-                    const uint16_t node = (uint16_t)(m + nint);
-                    s_int[nint] = la + na;
-                    s_par[ia] = node; s_par[m + ib] = node;
-                }
-                ia += 1; ib += 1; nint += 1;
+            const uint32_t lw = s_w[ia + lane], nw = s_int[ib + lane];          // the windows (INF: no such leaf / node yet)
+            const uint32_t lbeyond = s_w[ia + 64], nbeyond = s_int[ib + 64];    // first items outside the windows
+            const uint32_t a0 = (uint32_t)__builtin_amdgcn_readlane((int)lw, 0), a1 = (uint32_t)__builtin_amdgcn_readlane((int)lw, 1);
+            const uint32_t b0 = (uint32_t)__builtin_amdgcn_readlane((int)nw, 0), b1 = (uint32_t)__builtin_amdgcn_readlane((int)nw, 1);
+            uint32_t T;                                       // weight of the first node of this round
+            if (a0 <= b0) T = a0 + (a1 <= b0 ? a1 : b0); else T = b0 + (a0 <= b1 ? a0 : b1);
+            const bool lv = lw <= T && lw <= nbeyond;         // (an equal node outside the window comes after the leaf)
+            const bool nv = nw != INF && nw < lbeyond;        // (an equal leaf outside the window comes before the node)
+            const uint32_t kl = lv ? ((lw << 11) | lane) : INF;
+            const uint32_t kn = nv ? ((nw << 11) | (1u << 10) | lane) : INF;
+            const uint32_t items = (uint32_t)__popcll(__ballot(lv)) + (uint32_t)__popcll(__ballot(nv));
+            uint32_t P = items / 2u;                          // pairs of this round (at least 1)
+            P = P < left ? P : left;
+            // bitonic merge of the two ascending key sequences
+            const uint32_t knr = (uint32_t)__shfl((int)kn, 63 - (int)lane, 64);
+            uint32_t lo = kl < knr ? kl : knr, hi = kl < knr ? knr : kl;
+#pragma unroll
+            for (uint32_t d = 32; d >= 1; d >>= 1) {
+                const bool up = (lane & d) != 0;
+                const uint32_t plo = lane_xor(lo, d, up), phi = lane_xor(hi, d, up);
+                lo = up ? (lo > plo ? lo : plo) : (lo < plo ? lo : plo);
+                hi = up ? (hi > phi ? hi : phi) : (hi < phi ? hi : phi);
             }
+            // merged item p sits in lo of lane p (p < 64) or hi of lane p - 64; lane j pairs items 2j and 2j + 1
+            const int src = (int)((2u * lane) & 63u);
+            const uint32_t e0l = (uint32_t)__shfl((int)lo, src, 64), e1l = (uint32_t)__shfl((int)lo, src + 1, 64);
+            const uint32_t e0h = (uint32_t)__shfl((int)hi, src, 64), e1h = (uint32_t)__shfl((int)hi, src + 1, 64);
+            const uint32_t e0 = lane < 32u ? e0l : e0h, e1 = lane < 32u ? e1l : e1h;
+            if (lane < P) {
+                const uint16_t node = (uint16_t)(m + nint + lane);
+                s_int[nint + lane] = (e0 >> 11) + (e1 >> 11);
+                s_par[((e0 >> 10) & 1u) ? (m + ib + (e0 & 1023u)) : (ia + (e0 & 1023u))] = node;      // (bits 0..9: index in its window)
+                s_par[((e1 >> 10) & 1u) ? (m + ib + (e1 & 1023u)) : (ia + (e1 & 1023u))] = node;
+            }
+            // heads: leaves and nodes among the first 2 P merged items
+            const uint32_t cl = (uint32_t)__popcll(__ballot(lane < 2u * P && !((lo >> 10) & 1u))) +
+                                (uint32_t)__popcll(__ballot(lane + 64u < 2u * P && !((hi >> 10) & 1u)));
+            ia += cl; ib += 2u * P - cl; nint += P;
         }
     }
     __syncthreads();
