@@ -260,21 +260,20 @@ __device__ inline void book_build(BookShared& B, uint32_t f, uint32_t K, uint32_
         uint32_t ia = 0, ib = 0, nint = 0;                    // heads: leaf ia, internal node ib; nodes created
         while (nint + 1 < m) {
             const uint32_t left = m - 1 - nint;               // nodes still to be made
-            const uint32_t lw = s_w[ia + lane], nw = s_int[ib + lane];          // the windows (INF: no such leaf / node yet)
+            const uint32_t lw = s_w[ia + lane], nwr = s_int[ib + 63u - lane];   // the windows (INF: no such leaf / node yet); nodes reversed
             const uint32_t lbeyond = s_w[ia + 64], nbeyond = s_int[ib + 64];    // first items outside the windows
             const uint32_t a0 = (uint32_t)__builtin_amdgcn_readlane((int)lw, 0), a1 = (uint32_t)__builtin_amdgcn_readlane((int)lw, 1);
-            const uint32_t b0 = (uint32_t)__builtin_amdgcn_readlane((int)nw, 0), b1 = (uint32_t)__builtin_amdgcn_readlane((int)nw, 1);
+            const uint32_t b0 = (uint32_t)__builtin_amdgcn_readlane((int)nwr, 63), b1 = (uint32_t)__builtin_amdgcn_readlane((int)nwr, 62);
             uint32_t T;                                       // weight of the first node of this round
             if (a0 <= b0) T = a0 + (a1 <= b0 ? a1 : b0); else T = b0 + (a0 <= b1 ? a0 : b1);
             const bool lv = lw <= T && lw <= nbeyond;         // (an equal node outside the window comes after the leaf)
-            const bool nv = nw != INF && nw < lbeyond;        // (an equal leaf outside the window comes before the node)
+            const bool nv = nwr != INF && nwr < lbeyond;      // (an equal leaf outside the window comes before the node)
             const uint32_t kl = lv ? ((lw << 11) | lane) : INF;
-            const uint32_t kn = nv ? ((nw << 11) | (1u << 10) | lane) : INF;
+            const uint32_t knr = nv ? ((nwr << 11) | (1u << 10) | (63u - lane)) : INF;
             const uint32_t items = (uint32_t)__popcll(__ballot(lv)) + (uint32_t)__popcll(__ballot(nv));
             uint32_t P = items / 2u;                          // pairs of this round (at least 1)
             P = P < left ? P : left;
-            // bitonic merge of the two ascending key sequences
-            const uint32_t knr = (uint32_t)__shfl((int)kn, 63 - (int)lane, 64);
+            // bitonic merge of the ascending leaf keys and the descending node keys
             uint32_t lo = kl < knr ? kl : knr, hi = kl < knr ? knr : kl;
 #pragma unroll
             for (uint32_t d = 32; d >= 1; d >>= 1) {
@@ -283,16 +282,19 @@ __device__ inline void book_build(BookShared& B, uint32_t f, uint32_t K, uint32_
                 lo = up ? (lo > plo ? lo : plo) : (lo < plo ? lo : plo);
                 hi = up ? (hi > phi ? hi : phi) : (hi < phi ? hi : phi);
             }
-            // merged item p sits in lo of lane p (p < 64) or hi of lane p - 64; lane j pairs items 2j and 2j + 1
-            const int src = (int)((2u * lane) & 63u);
-            const uint32_t e0l = (uint32_t)__shfl((int)lo, src, 64), e1l = (uint32_t)__shfl((int)lo, src + 1, 64);
-            const uint32_t e0h = (uint32_t)__shfl((int)hi, src, 64), e1h = (uint32_t)__shfl((int)hi, src + 1, 64);
-            const uint32_t e0 = lane < 32u ? e0l : e0h, e1 = lane < 32u ? e1l : e1h;
-            if (lane < P) {
-                const uint16_t node = (uint16_t)(m + nint + lane);
-                s_int[nint + lane] = (e0 >> 11) + (e1 >> 11);
-                s_par[((e0 >> 10) & 1u) ? (m + ib + (e0 & 1023u)) : (ia + (e0 & 1023u))] = node;      // (bits 0..9: index in its window)
-                s_par[((e1 >> 10) & 1u) ? (m + ib + (e1 & 1023u)) : (ia + (e1 & 1023u))] = node;
+            // merged item p sits in lo of lane p (p < 64) or hi of lane p - 64; items 2j and 2j + 1 make node j of the
+            // round: the even lane of a pair writes the node, every lane the parent of its own item
+            {
+                const uint32_t qlo = lane_xor(lo, 1, (lane & 1u) != 0), qhi = lane_xor(hi, 1, (lane & 1u) != 0);
+                const uint32_t jlo = lane >> 1, jhi = 32u + (lane >> 1);
+                if (jlo < P) {
+                    if (!(lane & 1u)) s_int[nint + jlo] = (lo >> 11) + (qlo >> 11);
+                    s_par[((lo >> 10) & 1u) ? (m + ib + (lo & 1023u)) : (ia + (lo & 1023u))] = (uint16_t)(m + nint + jlo);   // (bits 0..9: index in its window)
+                }
+                if (jhi < P) {
+                    if (!(lane & 1u)) s_int[nint + jhi] = (hi >> 11) + (qhi >> 11);
+                    s_par[((hi >> 10) & 1u) ? (m + ib + (hi & 1023u)) : (ia + (hi & 1023u))] = (uint16_t)(m + nint + jhi);
+                }
             }
             // heads: leaves and nodes among the first 2 P merged items
             const uint32_t cl = (uint32_t)__popcll(__ballot(lane < 2u * P && !((lo >> 10) & 1u))) +
