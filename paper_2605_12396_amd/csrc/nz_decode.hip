@@ -71,31 +71,41 @@ struct BuildScratch {
     __align__(4) uint8_t len[kMaxK];
     uint16_t rank[kMaxK];
     uint32_t wcnt[16 * 32];
-    uint64_t red[2][8];
+    uint32_t red[5][8];
 };
 
-// Sums of two 64-bit values over the workgroup, one barrier pair for both.
+// Sums over the workgroup of five 32-bit values (the caller keeps every total below 2^32): wave totals over the DPP
+// network (no shared-memory crossbar), one barrier pair for all of them.
 template <int NT>
-__device__ inline void block_sum64x2(uint64_t& a, uint64_t& b, uint64_t (*s_red)[8]) {
-    a = wave_sum64(a); b = wave_sum64(b);
+__device__ inline void block_sum32x5(uint32_t (&v)[5], uint32_t (*s_red)[8]) {
+    static_assert(NT / 64 <= 8, "one slot per wavefront");
+#pragma unroll
+    for (int k = 0; k < 5; k++) v[k] = wave_incl_scan_dpp(v[k]);          // lane 63: the wave's total
     __syncthreads();
-    if (lane_id() == 0) { s_red[0][threadIdx.x >> 6] = a; s_red[1][threadIdx.x >> 6] = b; }
+    if (lane_id() == 63) {
+#pragma unroll
+        for (int k = 0; k < 5; k++) s_red[k][threadIdx.x >> 6] = v[k];
+    }
     __syncthreads();
-    a = 0; b = 0;
-    for (int i = 0; i < NT / 64; i++) { a += s_red[0][i]; b += s_red[1][i]; }
+#pragma unroll
+    for (int k = 0; k < 5; k++) { v[k] = 0; for (int i = 0; i < NT / 64; i++) v[k] += s_red[k][i]; }
 }
 
 // Validate one frame and prepare its decoder (all threads of the workgroup call this together).
 template <int NT>
-__device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t frame, uint32_t nf, uint32_t first_seg,
+__device__ inline void open_frame(const uint8_t* s, uint64_t total, uint64_t off, uint64_t bytes, uint32_t nf, uint32_t first_seg,
                                   const DecodeArgs& A, DecTables* T, BuildScratch* B, FrameView& V) {
+    // off: the frame's entry of the offsets table, read by the caller at kernel start; bytes: size of the stream buffer
+    // (total <= bytes was checked with the stream header), the bound of the early read of the code lengths below
     const uint32_t tid = threadIdx.x;
     V.status = ST_CORRUPT; V.kind = KIND_ZERO; V.w = 0; V.words = nullptr; V.nwords = 0; V.segt = nullptr; V.seg_prefix = 0; V.dense = false;
     V.hot_esc = false;
-    const uint64_t off = *reinterpret_cast<const uint64_t*>(s + kStreamHdr + 8ull * frame);
     if ((off & 15u) || off < kStreamHdr + pad16d(8ull * A.n_frames) || off + kHdrBytes > total) return;
     const uint8_t* fr = s + off;
     const uint4 h0 = reinterpret_cast<const uint4*>(fr)[0], h1 = reinterpret_cast<const uint4*>(fr)[1];
+    // the code-length table of a HUFFMAN frame starts right behind the header: its words are requested together with
+    // the header (inside the stream buffer; used only once the header has shown that they belong to the table)
+    const uint32_t lens_word = (off + kHdrBytes + 4ull * tid + 4ull <= bytes) ? reinterpret_cast<const uint32_t*>(fr + kHdrBytes)[tid] : 0u;
     const uint32_t x = kCheckXor ^ h0.x ^ h0.y ^ h0.z ^ h0.w ^ h1.x ^ h1.y ^ h1.z;
     if (h0.x != kMagicFrame || h1.w != x) return;
     const uint32_t codec = h0.y, raw_bytes = h0.z, payload = h0.w, p0 = h1.x, p1 = h1.y;
@@ -123,14 +133,13 @@ __device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t fra
     const uint32_t nseg = (nf + kSeg - 1) / kSeg;
     const uint64_t tables = pad4d(nsym) + pad4d(2ull * nseg);
     if (payload < tables || (payload & 3u)) return;
-    const uint8_t* lens = pay;
     const uint16_t* segt = reinterpret_cast<const uint16_t*>(pay + pad4d(nsym));
     // code lengths (4 per thread): <= 28, padding zero, at least one used, Kraft sum <= 1
     static_assert(NT * 4 >= kMaxK, "one pass over the code lengths");
     uint32_t bad = 0;
     uint64_t kraft = 0;
     {
-        const uint32_t lw = (4u * tid < (uint32_t)pad4d(nsym)) ? reinterpret_cast<const uint32_t*>(lens)[tid] : 0u;
+        const uint32_t lw = (4u * tid < (uint32_t)pad4d(nsym)) ? lens_word : 0u;
         uint32_t clean = 0;
 #pragma unroll
         for (uint32_t j = 0; j < 4; j++) {
@@ -152,11 +161,14 @@ __device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t fra
             else if (v1) bad = 1;                                      // padding entry of an odd table
         }
     }
-    uint64_t r0 = kraft + ((uint64_t)bad << 48), r1 = (uint64_t)pre | ((uint64_t)all << 32);
-    block_sum64x2<NT>(r0, r1, B->red);
-    kraft = r0 & ((1ull << 48) - 1ull);
-    const uint64_t pre_bits = r1 & 0xFFFFFFFFull, all_bits = r1 >> 32;
-    if ((r0 >> 48) || kraft == 0 || kraft > (1ull << kMaxLen)) return;
+    // workgroup sums: the Kraft sum in two halves (a thread adds at most 4 x 2^27: the low 16 bits and the rest each
+    // sum to less than 2^32 over the workgroup), the bits of the whole frame and those before this workgroup (a segment
+    // has at most 65535 bits, a frame at most 4096 segments), and the number of threads that saw something illegal
+    uint32_t sums[5] = { (uint32_t)(kraft & 0xFFFFu), (uint32_t)(kraft >> 16), all, pre, bad };
+    block_sum32x5<NT>(sums, B->red);
+    kraft = (uint64_t)sums[0] + ((uint64_t)sums[1] << 16);
+    const uint64_t pre_bits = sums[3], all_bits = sums[2];
+    if (sums[4] || kraft == 0 || kraft > (1ull << kMaxLen)) return;
     const uint64_t avail = 8ull * (payload - tables);
     if (all_bits > avail || 4ull * ((all_bits + 31u) / 32u) != payload - tables) return;
     if (all_bits < nf) return;            // every symbol costs at least one bit (so the bitstream is never empty here)
@@ -184,17 +196,29 @@ __device__ inline void open_frame(const uint8_t* s, uint64_t total, uint32_t fra
         uint32_t lim[kPrimaryBits + 1];                                // end of the codes of length <= l, 11-bit scale
 #pragma unroll
         for (uint32_t l = 1; l <= kPrimaryBits; l++) lim[l] = (s_first[l] + s_cnt[l]) << (kPrimaryBits - l);
+        // a thread's entries in three sweeps (lengths and sorted positions, symbols, entries), so that the shared-memory
+        // reads of all of them are in flight together
+        constexpr uint32_t EPT = (1u << kPrimaryBits) / NT;
+        uint32_t LL[EPT], pos[EPT], sym[EPT];
+        bool has[EPT];
 #pragma unroll
-        for (uint32_t i = tid; i < (1u << kPrimaryBits); i += NT) {
+        for (uint32_t k = 0; k < EPT; k++) {
+            const uint32_t i = tid + k * NT;
             const uint32_t v = __brev(i) >> (32 - kPrimaryBits);       // stream order: first bit is the code's MSB
             uint32_t L = 1;
 #pragma unroll
             for (uint32_t l = 1; l < kPrimaryBits; l++) L += (v >= lim[l]) ? 1u : 0u;
+            LL[k] = L; has[k] = v < lim[kPrimaryBits];
+            pos[k] = has[k] ? (uint32_t)((int32_t)(v >> (kPrimaryBits - L)) + T->base[L]) : 0u;
+        }
+#pragma unroll
+        for (uint32_t k = 0; k < EPT; k++) sym[k] = T->sorted[pos[k]];
+#pragma unroll
+        for (uint32_t k = 0; k < EPT; k++) {
+            const uint32_t i = tid + k * NT, L = LL[k], sy = sym[k];
             uint32_t e = 0xC000u;
-            if (v < lim[kPrimaryBits]) {
-                const uint32_t sy = T->sorted[s_idx0[L] + (v >> (kPrimaryBits - L)) - s_first[L]];
-                e = sy ? (((uint32_t)unzigzag(sy - 1u) & 1023u) | (L << 10)) : (0x8000u | (L << 10));
-            } else {
+            if (has[k]) e = sy ? (((uint32_t)unzigzag(sy - 1u) & 1023u) | (L << 10)) : (0x8000u | (L << 10));
+            else {
                 const uint32_t id = atomicAdd(&T->nsub, 1u);
                 if (id < kMaxSub) { e |= id; T->sub_prefix[id] = (uint16_t)i; } else e |= 0x3FFu;
             }
@@ -595,6 +619,16 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
     const bool whole = C.vec_ok && (C.first_seg + NT) * kSeg <= C.nf;   // every access is a full, aligned group of 4
     const bool fast_add = NZ_ADDS(MODE) && whole && !a_wide && !X.a_raw;
     for (uint32_t r0 = 0; r0 < kSeg; r0 += kTile16R) {
+        // Instruction issue favours the wavefronts that were started first, so the workgroups that share a compute unit
+        // would finish one after the other and leave it half empty towards the end of the kernel (there is nothing left
+        // to start in their place).  A wavefront's priority falls as it gets through its segment, which lets the ones
+        // that are behind catch up: the workgroups of a compute unit finish closer together.
+        switch (r0 / (2u * kTile16R)) {
+            case 0: __builtin_amdgcn_s_setprio(3); break;
+            case 1: __builtin_amdgcn_s_setprio(2); break;
+            case 2: __builtin_amdgcn_s_setprio(1); break;
+            default: __builtin_amdgcn_s_setprio(0); break;
+        }
         ra.install(pend);
         uint2 pa[LPR];                                // MODE_ADD_B: the staged codes of A this thread will add
         typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -883,6 +917,14 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
     const uint32_t cntseg = seg_valid ? ((nf - e0 < kSeg) ? (nf - e0) : kSeg) : 0u;
     const uint32_t hpf = (A.chunk + kHalf - 1) / kHalf;                 // halves (statistics blocks) per frame
 
+    // the frame's entry of the offsets table is requested before the stream header is looked at (its place does not
+    // depend on the header; the entry is only believed once the header is)
+    uint64_t frame_off = 0;
+    {
+        const uint8_t* sp = NZ_STAGED(MODE) ? A.b : A.a;
+        const uint64_t sb = NZ_STAGED(MODE) ? A.b_bytes : A.a_bytes;
+        if (kStreamHdr + 8ull * frame + 8ull <= sb) frame_off = *reinterpret_cast<const uint64_t*>(sp + kStreamHdr + 8ull * frame);
+    }
     // stream headers: the reduce passes look at both operands, so that neither goes on after a stream-level error
     uint64_t total_a = 0, total_b = 0;
     const uint32_t st_a = check_stream(A.a, A.a_bytes, A, total_a);
@@ -904,8 +946,8 @@ __global__ __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(4))) void k_
     V.status = ST_OK; V.kind = KIND_ZERO; V.w = 0; V.words = nullptr; V.nwords = 0; V.segt = nullptr; V.seg_prefix = 0; V.dense = false;
     V.hot_esc = false;
     if (st_a == ST_OK && st_b == ST_OK) {
-        open_frame<NT>(NZ_STAGED(MODE) ? A.b : A.a, NZ_STAGED(MODE) ? total_b : total_a, frame, nf, first_seg, A,
-                       &s_t, &S.u.build, V);
+        open_frame<NT>(NZ_STAGED(MODE) ? A.b : A.a, NZ_STAGED(MODE) ? total_b : total_a, frame_off,
+                       NZ_STAGED(MODE) ? A.b_bytes : A.a_bytes, nf, first_seg, A, &s_t, &S.u.build, V);
         if (MODE != MODE_DECOMPRESS && tid == 0 && V.status) atomicMax(&res->status, V.status);
     }
     const uint32_t found_kind = V.kind;

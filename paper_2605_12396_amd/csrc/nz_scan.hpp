@@ -48,23 +48,23 @@ template <int NT>
 __device__ inline void canonical_tables(const uint8_t* s_len, uint32_t K, uint32_t* s_wcnt, uint32_t* s_cnt,
                                         uint32_t* s_first, uint32_t* s_idx0, uint16_t* s_rank) {
     const uint32_t tid = threadIdx.x, lane = lane_id();
-    for (uint32_t i = tid; i < 16 * 32; i += NT) s_wcnt[i] = 0;
-    __syncthreads();
-    // rank inside each group of 64 consecutive symbols, by ballots over the distinct lengths present
+    // rank inside each group of 64 consecutive symbols (one wavefront), and the group's count per length: one ballot per
+    // possible length, no shared memory inside the loop.  Lane l of the wavefront keeps the count of length l and writes
+    // it (every entry of a group that some wavefront covers has exactly one writer; the other groups are cleared here).
+    const uint32_t covered = ((K + NT - 1) / NT) * (NT / 64);         // groups the loop below writes
+    for (uint32_t i = covered * 32 + tid; i < 16 * 32; i += NT) s_wcnt[i] = 0;
     for (uint32_t base = 0; base < K; base += NT) {
         const uint32_t s = base + tid;
         const uint32_t L = (s < K) ? s_len[s] : 0u;
         const uint32_t grp = s >> 6;
-        uint64_t todo = __ballot(L != 0);
-        uint32_t rank = 0;
-        while (todo) {
-            const int first = __ffsll((unsigned long long)todo) - 1;
-            const uint32_t Lc = __shfl(L, first, 64);
-            const uint64_t mask = __ballot(L == Lc);
-            if (L == Lc) rank = __popcll(mask & ((1ull << lane) - 1ull));
-            if ((int)lane == first) s_wcnt[grp * 32 + Lc] = __popcll(mask);
-            todo &= ~mask;
+        uint32_t rank = 0, mine = 0;
+#pragma unroll
+        for (uint32_t l = 1; l <= kMaxLen; l++) {
+            const uint64_t mask = __ballot(L == l);
+            if (L == l) rank = __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+            if (lane == l) mine = (uint32_t)__popcll(mask);
         }
+        if (lane < 32 && grp < 16) s_wcnt[grp * 32 + lane] = mine;
         if (s < K) s_rank[s] = (uint16_t)rank;
     }
     __syncthreads();
