@@ -1000,6 +1000,17 @@ __global__ __launch_bounds__(kEncThreads) __attribute__((amdgpu_waves_per_eu(4))
         };
 
         for (uint32_t sb = 0; sb < G.nsub; sb++) {
+            // (a wavefront's issue priority falls as it gets through its group: instruction issue favours the wavefronts
+            // started first, and the workgroups that share a compute unit would otherwise finish one after the other)
+            // the levels get shorter towards the end (1/2, 1/4, 1/8, 1/8 of the group): workgroups draw level at every
+            // boundary and can only drift apart again inside the last, short one
+            {
+                const uint32_t togo = G.nsub - sb;                // sub-blocks left, this one included
+                if (8u * togo > 4u * G.nsub) __builtin_amdgcn_s_setprio(3);
+                else if (8u * togo > 2u * G.nsub) __builtin_amdgcn_s_setprio(2);
+                else if (8u * togo > G.nsub) __builtin_amdgcn_s_setprio(1);
+                else __builtin_amdgcn_s_setprio(0);
+            }
             const uint32_t cnt = (G.gcnt - sb * kEncBlock < kEncBlock) ? (G.gcnt - sb * kEncBlock) : kEncBlock;
             uint64_t pk[kEncIters];               // the thread's 4 symbols of a pass packed LSB-first
             uint32_t ln[kEncIters];               // exclusive bit offset of the thread inside its pass

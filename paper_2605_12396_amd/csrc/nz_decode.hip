@@ -623,10 +623,12 @@ __device__ inline void run_huff(const DecodeArgs& A, const SegCtx& C, HuffReader
         // would finish one after the other and leave it half empty towards the end of the kernel (there is nothing left
         // to start in their place).  A wavefront's priority falls as it gets through its segment, which lets the ones
         // that are behind catch up: the workgroups of a compute unit finish closer together.
-        switch (r0 / (2u * kTile16R)) {
-            case 0: __builtin_amdgcn_s_setprio(3); break;
-            case 1: __builtin_amdgcn_s_setprio(2); break;
-            case 2: __builtin_amdgcn_s_setprio(1); break;
+        // (the levels get shorter towards the end -- phases 0-3, 4-5, 6, 7 -- so that the workgroups draw level at every
+        // boundary and can only drift apart again inside the last phase)
+        switch (r0 / kTile16R) {
+            case 0: case 1: case 2: case 3: __builtin_amdgcn_s_setprio(3); break;
+            case 4: case 5: __builtin_amdgcn_s_setprio(2); break;
+            case 6: __builtin_amdgcn_s_setprio(1); break;
             default: __builtin_amdgcn_s_setprio(0); break;
         }
         ra.install(pend);
