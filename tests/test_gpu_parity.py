@@ -643,6 +643,52 @@ def test_codebook_tie_heavy_histograms(nz, seed):
     check_decompress(nz, ref, x, eb, chunk_elems=chunk, alphabet=K)
 
 
+@pytest.mark.parametrize("shape", ["equal", "near_equal", "fibonacci", "staircase", "spikes", "dyadic", "few_heavy_many_light"])
+@pytest.mark.parametrize("K", [256, 1024])
+def test_codebook_histogram_shapes_in_maximal_frames(nz, shape, K):
+    """Histograms chosen for the code construction's merge, in frames of the maximal size (2^20 symbols, so weights
+    reach 2^20): hundreds of equal counts (long runs of leaf pairs, windows that overflow), near-equal counts, a
+    Fibonacci chain (a node joins a leaf at every step, deepest codes), stairs of equal counts (ties between leaves
+    and nodes of the same weight), a few heavy symbols over a flat tail, dyadic counts.  HUFFMAN pinned, bytes
+    against the oracle, then decompress."""
+    rng = np.random.default_rng(7000 + K + len(shape))
+    nsym = K - 2                                               # symbols z = 0 .. K-3 (no escapes)
+    n = 1 << 20
+    if shape == "equal":
+        c = np.full(nsym, n // nsym)
+    elif shape == "near_equal":
+        c = (n / nsym * (1 + 0.01 * rng.standard_normal(nsym))).astype(np.int64)
+    elif shape == "fibonacci":
+        f = [1, 1]
+        while sum(f) + f[-1] + f[-2] <= n and len(f) < nsym:
+            f.append(f[-1] + f[-2])
+        c = np.array(f)
+    elif shape == "staircase":
+        c = np.repeat(np.arange(1, nsym // 37 + 2) * 13, 37)[:nsym]
+    elif shape == "spikes":
+        c = np.full(nsym, 50); c[:3] = [n // 3, n // 5, n // 9]
+    elif shape == "dyadic":
+        c = np.array([1 << (18 - min(i // 2, 18)) for i in range(min(nsym, 60))])
+    else:
+        c = np.concatenate([np.full(5, n // 8), np.full(nsym - 5, 300)])
+    c = np.maximum(c, 0).astype(np.int64)
+    scale = min(1.0, n / c.sum())
+    if scale < 1.0:
+        c = np.maximum((c * scale).astype(np.int64), 1)
+    z = np.repeat(np.arange(c.size), c)
+    rng.shuffle(z)
+    tail = z[:50000]                                           # a second, ragged frame
+    z = np.concatenate([z, tail])
+    q = np.where(z & 1, -((z + 1) >> 1), z >> 1).astype(np.int64)
+    eb = 1e-3
+    step = oracle.step_constants(eb)[0]
+    x = (q.astype(np.float32) * np.float32(step)).astype(np.float32)
+    assert (oracle.quantize(x, eb)[0] == q).all()
+    ref, ores = check_compress(nz, x, eb, chunk_elems=1 << 20, alphabet=K, force_codec=2)
+    assert ores.n_huff == ores.n_frames
+    check_decompress(nz, ref, x, eb, chunk_elems=1 << 20, alphabet=K)
+
+
 def test_more_than_2_to_31_elements(nz):
     """Index arithmetic past 32 bits: 2^31 + 70001 elements (8.6 GB of fp32).  Too large for the oracle to hold, so
     the check is by properties that hold at any size: frame count, stream header, |x - xhat| <= eb for every element,
