@@ -201,13 +201,22 @@ __device__ inline void open_frame(const uint8_t* s, uint64_t total, uint64_t off
         constexpr uint32_t EPT = (1u << kPrimaryBits) / NT;
         uint32_t LL[EPT], pos[EPT], sym[EPT];
         bool has[EPT];
+        // A thread's entries i = tid + k NT differ in their top bits only, so their prefixes v = reversed(i) share all but
+        // the lowest log2(EPT) bits: the limits of the short lengths are multiples of EPT and compare alike for all of
+        // them (counted once), only the last lengths are compared entry by entry.
+        constexpr uint32_t kLowBits = (EPT == 8) ? 3u : ((EPT == 4) ? 2u : 0u);     // log2(EPT) for the workgroup sizes in use
+        static_assert(EPT == 8 || EPT == 4, "entries per thread");
+        const uint32_t vhigh = __brev(tid) >> (32 - kPrimaryBits);                  // prefix of entry k = 0 (low bits zero)
+        uint32_t Lshared = 1;
+#pragma unroll
+        for (uint32_t l = 1; l + kLowBits <= kPrimaryBits; l++) Lshared += (vhigh >= lim[l]) ? 1u : 0u;   // lim[l] is a multiple of 2^(11-l)
 #pragma unroll
         for (uint32_t k = 0; k < EPT; k++) {
             const uint32_t i = tid + k * NT;
             const uint32_t v = __brev(i) >> (32 - kPrimaryBits);       // stream order: first bit is the code's MSB
-            uint32_t L = 1;
+            uint32_t L = Lshared;
 #pragma unroll
-            for (uint32_t l = 1; l < kPrimaryBits; l++) L += (v >= lim[l]) ? 1u : 0u;
+            for (uint32_t l = kPrimaryBits - kLowBits + 1; l < kPrimaryBits; l++) L += (v >= lim[l]) ? 1u : 0u;
             LL[k] = L; has[k] = v < lim[kPrimaryBits];
             pos[k] = has[k] ? (uint32_t)((int32_t)(v >> (kPrimaryBits - L)) + T->base[L]) : 0u;
         }
