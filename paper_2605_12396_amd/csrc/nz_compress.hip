@@ -207,33 +207,41 @@ __device__ inline void book_build(BookShared& B, uint32_t f, uint32_t K, uint32_
         const uint64_t um = __ballot(used);
         if (lane == 0 && um) { atomicAdd(&B.m, (uint32_t)__popcll(um)); atomicMax(&B.nsym, wave * 64 + 64 - (uint32_t)__clzll(um)); }
     }
-    // (2) sort used symbols ascending by (count, symbol): rank = number of smaller keys, counted by several threads
-    // per symbol over disjoint parts of the key array (the workgroup has more threads than a small alphabet has symbols)
+    // (2) sort used symbols ascending by (count, symbol).  Every wavefront sorts its 64 keys with a bitonic network over
+    // its lanes (unused symbols carry the largest key and end up last); a key's rank is then its place in its own run
+    // plus, found by binary search, the number of smaller keys in every other run (keys are distinct).
     const uint32_t key = used ? ((f << 10) | tid) : 0xFFFFFFFFu;
-    B.key[tid] = key;
-    B.w[tid] = 0;                                             // rank accumulators (the queues are set up later)
-    __syncthreads();
-    const uint32_t m = B.m;
-    {
-        const uint32_t parts = (kBookThreads / K) < 16u ? (kBookThreads / K) : 16u;   // K is a power of two <= kBookThreads
-        const uint32_t sy = tid & (K - 1u), part = tid / K;
-        const uint32_t ks = B.key[sy];
-        if (part < parts && ks != 0xFFFFFFFFu) {
-            const uint32_t nch = K >= 4u ? K / 4u : 1u;       // (keys past K are sentinels)
-            const uint32_t per = (nch + parts - 1u) / parts;
-            const uint32_t j0 = part * per, j1 = (j0 + per < nch) ? j0 + per : nch;
-            const uint4* k4 = reinterpret_cast<const uint4*>(B.key);
-            uint32_t cnt = 0;
-#pragma unroll 8
-            for (uint32_t j = j0; j < j1; j++) {
-                const uint4 t = k4[j];
-                cnt += (t.x < ks) + (t.y < ks) + (t.z < ks) + (t.w < ks);
+    const uint32_t runs = K >= 64u ? K / 64u : 1u;            // K is a power of two; symbols past K do not exist
+    uint32_t v = key;
+    if (wave < runs) {
+#pragma unroll
+        for (uint32_t k = 2; k <= 64; k <<= 1) {
+#pragma unroll
+            for (uint32_t j = k >> 1; j >= 1; j >>= 1) {
+                const bool up = (lane & j) != 0;
+                const uint32_t vp = lane_xor(v, j, up);
+                const bool asc = k == 64u || (lane & k) == 0;      // direction of this lane's block of k
+                v = (up != asc) ? (v < vp ? v : vp) : (v > vp ? v : vp);
             }
-            if (cnt) atomicAdd(&B.w[sy], cnt);
         }
+        B.key[tid] = v;                                       // run `wave`, place `lane`
     }
     __syncthreads();
-    if (used) B.sorted[B.w[tid]] = key;
+    const uint32_t m = B.m;
+    if (wave < runs && v != 0xFFFFFFFFu) {
+        uint32_t rank = lane;
+#pragma unroll 4
+        for (uint32_t r = 0; r < runs; r++) {
+            if (r == wave) continue;                          // (uniform over the wavefront)
+            const uint32_t* run = B.key + r * 64u;
+            uint32_t pos = 0;                                 // number of keys of the run below v
+#pragma unroll
+            for (uint32_t st = 32; st >= 1; st >>= 1) pos += (run[pos + st - 1u] < v) ? st : 0u;
+            pos += (run[pos] < v) ? 1u : 0u;                  // (pos <= 63 before this probe)
+            rank += pos;
+        }
+        B.sorted[rank] = v;
+    }
     __syncthreads();
     // leaves in order, followed by sentinels; the internal-node queue starts out all sentinels
     constexpr uint32_t INF = 0xFFFFFFFFu;
