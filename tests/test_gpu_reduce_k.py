@@ -202,3 +202,38 @@ def test_streams_of_the_stochastic_quantizer(nz):
     assert nz.nz_reduce_k_step(ds, [s.size for s in ss], out, sess.cap, n, step * 2, sess.res, g, sess.ws, sess.ws_bytes) == 0
     assert sess.result()["status"] == nz.ERR_MISMATCH
     assert nz.nz_reduce_k_step(ds, [s.size for s in ss], out, sess.cap, n, float("nan"), sess.res, g, sess.ws, sess.ws_bytes) == nz.ERR_INVALID
+
+
+def test_captured_in_a_hip_graph(nz):
+    """nz_reduce_k reads its host arrays of pointers and sizes during the call only, and only launches kernels: it can be
+    recorded into a HIP graph.  Replays, with eager work in between, must reproduce the oracle's stream every time."""
+    import torch
+    n, eb, chunk, k = 200000, 1e-4, 65536, 5
+    g, o = nz.make_opts(chunk_elems=chunk), oracle.make_opts(chunk_elems=chunk)
+    ss = [oracle.compress(W.gradient_like(n, seed=480 + p), eb, o)[0] for p in range(k)]
+    ref, ores, orc = oracle.reduce_k(ss, n, eb, o)
+    assert orc == 0
+    sess = nz.Session(n, g, "cuda:0", reduce=True)
+    ds = [_dev(np.concatenate([s, np.zeros((-s.size) % 16, np.uint8)])) for s in ss]
+    sizes = [s.size for s in ss]
+    out = sess.new_stream_buffer()
+
+    def work():
+        assert nz.nz_reduce_k(ds, sizes, out, sess.cap, n, eb, sess.res, g, sess.ws, sess.ws_bytes) == 0
+
+    work()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        graph.capture_begin()
+        work()
+        graph.capture_end()
+    for rep in range(3):
+        out.zero_(); sess.res.zero_(); sess.ws.zero_()          # eager work between replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        r = sess.result()
+        assert r["status"] == 0 and r["bytes"] == ores.bytes, rep
+        assert np.array_equal(out[:r["bytes"]].cpu().numpy(), ref), rep
