@@ -237,3 +237,38 @@ def test_captured_in_a_hip_graph(nz):
         r = sess.result()
         assert r["status"] == 0 and r["bytes"] == ores.bytes, rep
         assert np.array_equal(out[:r["bytes"]].cpu().numpy(), ref), rep
+
+
+@pytest.mark.parametrize("predictor", [0, 1], ids=["plain", "delta"])
+def test_garbage_in_an_operand(nz, predictor):
+    """Byte flips anywhere behind the stream header of one operand (HUFFMAN, FIXEDLEN and RAW frames), the damaged
+    operand in any position: never a fault, the oracle's verdict, and -- where the damage cannot be told from valid
+    data -- the oracle's stream."""
+    n = 5 * 16384 + 777
+    eb = 1e-4
+    kw = dict(chunk_elems=16384, predictor=predictor)
+    g, o = nz.make_opts(**kw), oracle.make_opts(**kw)
+    x = np.concatenate([W.gradient_like(2 * 16384, seed=191), W.sweep_payload("uniform", 2 * 16384, 192),
+                        W.gradient_like(16384 + 777, seed=193)])
+    x[3 * 16384 + 5] = np.inf                                           # frame 3 is RAW
+    s = oracle.compress(x, eb, o)[0]
+    others = [oracle.compress(W.gradient_like(n, seed=194 + p), eb, o)[0] for p in range(3)]
+    rng = np.random.default_rng(23 + predictor)
+    base = 64 + 8 * 6
+    n_rejected = n_accepted = 0
+    for trial in range(48):
+        t = s.copy()
+        for _ in range(int(rng.integers(1, 4))):
+            t[int(rng.integers(base, s.size))] ^= int(rng.integers(1, 256))
+        pos = trial % 4
+        ops = list(others); ops.insert(pos, t)
+        ref, ores, orc = oracle.reduce_k(ops, n, eb, o)
+        rc, r, got = gpu_reduce_k(nz, ops, n, eb, g)
+        assert rc == 0 and r["status"] == orc, (trial, pos, r, orc)
+        if orc == 0:
+            assert r["bytes"] == ores.bytes and np.array_equal(got, ref), (trial, pos)
+            n_accepted += 1
+        else:
+            assert r["bytes"] == 0
+            n_rejected += 1
+    assert n_rejected >= 2 and n_accepted >= 2
